@@ -1,0 +1,242 @@
+"""CPU oracle for the SCD local solver (arXiv 1803.06333, Section 3.1) -- TEST INFRASTRUCTURE.
+
+Thin ctypes/numpy access to `snap_oracle.c` (built by `oracle/build.py`) plus a small driver that
+runs epochs the way the paper's solver does (Section 3.1-3.2: a fresh permutation per pass, every
+coordinate once).  Nothing here may be imported by the product package; only `tests/`, the smoke
+check and the benchmark's CPU-baseline leg use it.  It shares no code with the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+from .build import build as build_oracle, LIB_PATH
+
+RIDGE, LOGISTIC, HINGE = 0, 1, 2
+LOSS_ID = {"ridge": RIDGE, "logistic": LOGISTIC, "hinge": HINGE}
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            build_oracle()
+        L = C.CDLL(LIB_PATH)
+        L.oracle_key.restype = C.c_uint32
+        L.oracle_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
+        L.oracle_perm.restype = C.c_int
+        L.oracle_primal_objective.restype = C.c_double
+        L.oracle_hinge_dual_objective.restype = C.c_double
+        L.oracle_primal_gap_fenchel.restype = C.c_double
+        L.oracle_primal_gap_gradient.restype = C.c_double
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def key(seed: int, chunk: int, c: int) -> int:
+    return int(lib().oracle_key(C.c_uint64(seed), C.c_uint32(chunk), C.c_uint32(c)))
+
+
+def permutation(seed: int, m: int, chunk: int = 0, want_keys: bool = False):
+    """perm[k] = the coordinate (relative to the chunk start) visited k-th."""
+    perm = np.empty(m, dtype=np.uint32)
+    keys = np.empty(m, dtype=np.uint32) if want_keys else None
+    rc = lib().oracle_perm(C.c_uint64(seed), C.c_uint32(chunk), C.c_uint32(m), _p(keys), _p(perm))
+    if rc != 0:
+        raise MemoryError("oracle_perm")
+    return (perm, keys) if want_keys else perm
+
+
+@dataclass
+class Matrix:
+    """layout: 'csr' | 'csc' | 'dense_colmajor' of the n x d example matrix X."""
+    layout: str
+    n: int
+    d: int
+    ptr: Optional[np.ndarray]
+    idx: Optional[np.ndarray]
+    val: np.ndarray
+
+    @staticmethod
+    def from_problem(p) -> "Matrix":
+        """From a datagen.Problem (tensors are moved to host numpy)."""
+        g = lambda t: None if t is None else t.detach().cpu().numpy()
+        return Matrix(p.layout, p.n, p.d,
+                      None if p.ptr is None else _i64(g(p.ptr)),
+                      None if p.idx is None else _i32(g(p.idx)), _f32(g(p.val)))
+
+    # products --------------------------------------------------------------------------------
+    def matvec(self, x: np.ndarray) -> np.ndarray:
+        """X x  (length n)."""
+        x = _f64(x)
+        out = np.empty(self.n, dtype=np.float64)
+        if self.layout == "csr":
+            lib().oracle_compressed_matvec(C.c_int64(self.n), C.c_int64(self.n), _p(self.ptr), _p(self.idx),
+                                           _p(self.val), _p(x), C.c_int(0), _p(out))
+        elif self.layout == "csc":
+            lib().oracle_compressed_matvec(C.c_int64(self.d), C.c_int64(self.n), _p(self.ptr), _p(self.idx),
+                                           _p(self.val), _p(x), C.c_int(1), _p(out))
+        else:
+            lib().oracle_dense_matvec(C.c_int64(self.n), C.c_int64(self.d), _p(self.val), _p(x), C.c_int(0), _p(out))
+        return out
+
+    def rmatvec(self, u: np.ndarray) -> np.ndarray:
+        """X^T u  (length d)."""
+        u = _f64(u)
+        out = np.empty(self.d, dtype=np.float64)
+        if self.layout == "csr":
+            lib().oracle_compressed_matvec(C.c_int64(self.n), C.c_int64(self.d), _p(self.ptr), _p(self.idx),
+                                           _p(self.val), _p(u), C.c_int(1), _p(out))
+        elif self.layout == "csc":
+            lib().oracle_compressed_matvec(C.c_int64(self.d), C.c_int64(self.d), _p(self.ptr), _p(self.idx),
+                                           _p(self.val), _p(u), C.c_int(0), _p(out))
+        else:
+            lib().oracle_dense_matvec(C.c_int64(self.n), C.c_int64(self.d), _p(self.val), _p(u), C.c_int(1), _p(out))
+        return out
+
+    def to_dense(self) -> np.ndarray:
+        X = np.zeros((self.n, self.d), dtype=np.float64)
+        if self.layout == "dense_colmajor":
+            return self.val.reshape(self.d, self.n).T.astype(np.float64)
+        major = self.n if self.layout == "csr" else self.d
+        for s in range(major):
+            for k in range(self.ptr[s], self.ptr[s + 1]):
+                if self.layout == "csr":
+                    X[s, self.idx[k]] += self.val[k]
+                else:
+                    X[self.idx[k], s] += self.val[k]
+        return X
+
+
+class Solver:
+    """Sequential SCD on one problem.  form: 'primal' (CSC / dense, ridge or logistic) or 'dual'
+    (CSR, hinge).  State starts at zero (Algorithm 1's starting point)."""
+
+    def __init__(self, A: Matrix, y, loss: str, lam: float, chunk_bounds: Optional[Sequence[int]] = None):
+        self.A, self.y, self.loss, self.lam = A, _f32(y), LOSS_ID[loss], float(lam)
+        if A.layout == "csr":
+            if loss != "hinge":
+                raise ValueError("dual form is implemented for the hinge loss")
+            self.form, self.m, self.vlen = "dual", A.n, A.d
+        else:
+            if loss == "hinge":
+                raise ValueError("hinge loss is solved in the dual form (CSR)")
+            self.form, self.m, self.vlen = "primal", A.d, A.n
+        self.x = np.zeros(self.m, dtype=np.float64)      # w (primal) or alpha (dual)
+        self.v = np.zeros(self.vlen, dtype=np.float64)   # shared vector
+        # streaming: coordinates are visited chunk by chunk, permuted inside each chunk
+        self.bounds = [0, self.m] if chunk_bounds is None else list(chunk_bounds)
+        self.last_perm = None
+
+    def epoch(self, seed: int):
+        L = lib()
+        n = C.c_int64(self.A.n)
+        perms = []
+        for ch in range(len(self.bounds) - 1):
+            c0, c1 = self.bounds[ch], self.bounds[ch + 1]
+            perm = permutation(seed, c1 - c0, chunk=ch)
+            perms.append(perm.astype(np.int64) + c0)
+            args = (C.c_double(self.lam), _p(perm), C.c_int64(c0), C.c_int64(c1 - c0), _p(self.x), _p(self.v))
+            if self.form == "dual":
+                L.oracle_epoch_dual_hinge(n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val), _p(self.y), *args)
+            elif self.A.layout == "csc":
+                L.oracle_epoch_primal_sparse(C.c_int(self.loss), n, _p(self.A.ptr), _p(self.A.idx),
+                                             _p(self.A.val), _p(self.y), *args)
+            else:
+                L.oracle_epoch_primal_dense(C.c_int(self.loss), n, _p(self.A.val), _p(self.y), *args)
+        self.last_perm = np.concatenate(perms)
+
+    # model ----------------------------------------------------------------------------------
+    def weights(self) -> np.ndarray:
+        return self.x.copy() if self.form == "primal" else self.v / (self.lam * self.A.n)
+
+    def shared_from_model(self) -> np.ndarray:
+        """v recomputed from the model by the definition v = A alpha."""
+        if self.form == "primal":
+            return self.A.matvec(self.x)
+        return self.A.rmatvec(self.y.astype(np.float64) * self.x)
+
+    # objectives -----------------------------------------------------------------------------
+    def primal(self) -> float:
+        if self.form == "primal":
+            return primal_objective(self.loss, self.v, self.y, self.x, self.lam)
+        return self.primal_dual()[0]
+
+    def primal_dual(self):
+        assert self.form == "dual"
+        w = self.weights()
+        xw = self.A.matvec(w)
+        P, D = C.c_double(), C.c_double()
+        lib().oracle_hinge_primal_dual(C.c_int64(self.A.n), C.c_int64(self.A.d), _p(self.x), _p(self.v),
+                                       _p(xw), _p(self.y), C.c_double(self.lam), C.byref(P), C.byref(D))
+        return P.value, D.value
+
+    def dual(self) -> float:
+        assert self.form == "dual"
+        return float(lib().oracle_hinge_dual_objective(C.c_int64(self.A.n), C.c_int64(self.A.d), _p(self.x),
+                                                       _p(self.v), C.c_double(self.lam)))
+
+    def gap(self, form: str = "gradient") -> float:
+        if self.form == "dual":
+            P, D = self.primal_dual()
+            return P - D
+        return primal_gap(self.A, self.loss, self.v, self.y, self.x, self.lam, form)
+
+    def predict(self, X: Matrix) -> np.ndarray:
+        return X.matvec(self.weights())
+
+
+def primal_objective(loss: int, z, y, w, lam: float) -> float:
+    z, w, y = _f64(z), _f64(w), _f32(y)
+    return float(lib().oracle_primal_objective(C.c_int(loss), C.c_int64(z.size), C.c_int64(w.size), _p(z), _p(y),
+                                               _p(w), C.c_double(lam)))
+
+
+def primal_gap(A: Matrix, loss: int, v, y, w, lam: float, form: str = "gradient") -> float:
+    v, w, y = _f64(v), _f64(w), _f32(y)
+    u = np.empty(A.n, dtype=np.float64)
+    lib().oracle_primal_dual_candidate(C.c_int(loss), C.c_int64(A.n), _p(v), _p(y), _p(u))
+    xtu = A.rmatvec(u)
+    if form == "gradient":
+        return float(lib().oracle_primal_gap_gradient(C.c_int64(A.d), _p(w), _p(xtu), C.c_double(lam)))
+    return float(lib().oracle_primal_gap_fenchel(C.c_int(loss), C.c_int64(A.n), C.c_int64(A.d), _p(v), _p(y),
+                                                 _p(w), _p(u), _p(xtu), C.c_double(lam)))
+
+
+def solve(A: Matrix, y, loss: str, lam: float, epochs: int, seed0: int = 0, tol: Optional[float] = None,
+          chunk_bounds=None) -> Solver:
+    """Run `epochs` passes with permutation seeds seed0, seed0+1, ...; stop early when the gap
+    falls below tol * max(1, |P|)."""
+    s = Solver(A, y, loss, lam, chunk_bounds)
+    for e in range(epochs):
+        s.epoch(seed0 + e)
+        if tol is not None and (e % 5 == 4 or e == epochs - 1):
+            if s.gap() <= tol * max(1.0, abs(s.primal())):
+                break
+    return s

@@ -1,0 +1,339 @@
+"""Pins for the CPU oracle: every part of it is checked against something other than itself --
+closed forms, brute force, library routines, invariants (Sections 1 eq. (1), 3.1, 3.2)."""
+import math
+
+import numpy as np
+import pytest
+import scipy.optimize
+import scipy.sparse as sp
+
+import oracle
+from oracle import Matrix
+
+pytestmark = pytest.mark.usefixtures("oracle_lib")
+rng = np.random.default_rng(12345)
+
+
+def dense_to_csc(X):
+    S = sp.csc_matrix(X)
+    S.sort_indices()
+    return Matrix("csc", X.shape[0], X.shape[1], S.indptr.astype(np.int64), S.indices.astype(np.int32),
+                  S.data.astype(np.float32))
+
+
+def dense_to_csr(X):
+    S = sp.csr_matrix(X)
+    S.sort_indices()
+    return Matrix("csr", X.shape[0], X.shape[1], S.indptr.astype(np.int64), S.indices.astype(np.int32),
+                  S.data.astype(np.float32))
+
+
+def dense_colmajor(X):
+    return Matrix("dense_colmajor", X.shape[0], X.shape[1], None, None,
+                  np.ascontiguousarray(X.T, dtype=np.float32).reshape(-1))
+
+
+def sparse_random(n, d, density, r):
+    X = r.standard_normal((n, d)) * (r.random((n, d)) < density)
+    return X.astype(np.float32).astype(np.float64)
+
+
+# independent numpy definitions of the objectives (written from eq. (1) with the 1/n scaling)
+def P_ridge(X, y, w, lam):
+    return 0.5 * np.mean((X @ w - y) ** 2) + 0.5 * lam * w @ w
+
+
+def P_logistic(X, y, w, lam):
+    return np.mean(np.logaddexp(0.0, -y * (X @ w))) + 0.5 * lam * w @ w
+
+
+def P_hinge(X, y, w, lam):
+    return np.mean(np.maximum(0.0, 1 - y * (X @ w))) + 0.5 * lam * w @ w
+
+
+def ridge_closed_form(X, y, lam):
+    n, d = X.shape
+    return np.linalg.solve(X.T @ X / n + lam * np.eye(d), X.T @ y / n)
+
+
+# ---------------------------------------------------------------------------------------------
+# ridge
+@pytest.mark.parametrize("layout", ["csc", "dense"])
+def test_ridge_converges_to_normal_equations(layout):
+    n, d, lam = 60, 7, 0.05
+    X = sparse_random(n, d, 0.6, rng)
+    y = rng.standard_normal(n).astype(np.float32)
+    A = dense_to_csc(X) if layout == "csc" else dense_colmajor(X)
+    s = oracle.solve(A, y, "ridge", lam, epochs=400)
+    wstar = ridge_closed_form(X, y.astype(np.float64), lam)
+    np.testing.assert_allclose(s.weights(), wstar, rtol=0, atol=1e-10)
+    assert abs(s.primal() - P_ridge(X, y, wstar, lam)) < 1e-13
+    np.testing.assert_allclose(s.v, X @ s.x, atol=1e-12)
+
+
+def test_ridge_single_feature_one_update_is_exact():
+    a = np.array([[1.5], [-2.0], [0.5], [3.0]], dtype=np.float32)
+    y = np.array([1.0, 0.5, -1.0, 2.0], dtype=np.float32)
+    lam, n = 0.3, 4
+    s = oracle.solve(dense_to_csc(a.astype(np.float64)), y, "ridge", lam, epochs=1)
+    expect = (a[:, 0].astype(np.float64) @ y / n) / (a[:, 0].astype(np.float64) @ a[:, 0] / n + lam)
+    assert s.x[0] == pytest.approx(expect, rel=1e-15)
+
+
+def test_ridge_objective_never_increases_per_update():
+    n, d, lam = 40, 12, 0.01
+    X = sparse_random(n, d, 0.5, rng)
+    y = rng.standard_normal(n).astype(np.float32)
+    A = dense_to_csc(X)
+    s = oracle.Solver(A, y, "ridge", lam)
+    lib = oracle.lib()
+    import ctypes as C
+    prev = P_ridge(X, y, s.x, lam)
+    for e in range(3):
+        perm = oracle.permutation(e, d)
+        for k in range(d):
+            one = perm[k:k + 1].copy()
+            lib.oracle_epoch_primal_sparse(C.c_int(0), C.c_int64(n), oracle._p(A.ptr), oracle._p(A.idx),
+                                           oracle._p(A.val), oracle._p(s.y), C.c_double(lam), oracle._p(one),
+                                           C.c_int64(0), C.c_int64(1), oracle._p(s.x), oracle._p(s.v))
+            cur = P_ridge(X, y, s.x, lam)
+            assert cur <= prev + 1e-15
+            # exact coordinate minimiser: the partial derivative along that coordinate vanishes
+            j = int(one[0])
+            gj = X[:, j] @ (X @ s.x - y) / n + lam * s.x[j]
+            assert abs(gj) < 1e-14
+            prev = cur
+
+
+@pytest.mark.parametrize("seed", [0, 1, 7])
+def test_ridge_orthogonal_columns_converge_in_one_epoch(seed):
+    n, d, lam = 30, 10, 0.2
+    X = np.zeros((n, d))
+    X[np.arange(n), np.arange(n) % d] = rng.standard_normal(n).astype(np.float32)  # one nonzero per row
+    y = rng.standard_normal(n).astype(np.float32)
+    s = oracle.solve(dense_to_csc(X), y, "ridge", lam, epochs=1, seed0=seed)
+    np.testing.assert_allclose(s.x, ridge_closed_form(X, y.astype(np.float64), lam), atol=1e-14)
+
+
+def test_ridge_config2_slice_against_normal_equations():
+    import datagen
+    p = datagen.dense_ridge(n=2000, d=200)
+    A = Matrix.from_problem(p)
+    y = p.y.numpy()
+    s = oracle.solve(A, y, "ridge", p.lam, epochs=3000, tol=1e-14)
+    X = A.to_dense()
+    wstar = ridge_closed_form(X, y.astype(np.float64), p.lam)
+    assert abs(s.primal() - P_ridge(X, y, wstar, p.lam)) <= 1e-9 * P_ridge(X, y, wstar, p.lam)
+    assert np.linalg.norm(s.x - wstar) <= 1e-3 * np.linalg.norm(wstar)
+
+
+# ---------------------------------------------------------------------------------------------
+# logistic
+def test_logistic_single_feature_newton_vs_bisection():
+    a = np.array([0.5, -1.0, 2.0, 1.0, -0.7], dtype=np.float32).astype(np.float64)
+    y = np.array([1, 1, -1, 1, -1], dtype=np.float32)
+    lam, n = 0.1, 5
+    dP = lambda w: np.mean(-y * a / (1 + np.exp(y * a * w))) + lam * w
+    root = scipy.optimize.brentq(dP, -50, 50, xtol=1e-15, rtol=1e-15)
+    A = dense_to_csc(a.reshape(-1, 1))
+    s = oracle.Solver(A, y, "logistic", lam)
+    errs = []
+    for e in range(8):
+        s.epoch(e)
+        errs.append(abs(s.x[0] - root))
+    assert errs[-1] < 1e-14
+    # Newton's quadratic convergence: error_{k+1} <= C error_k^2 once close
+    k = next(i for i, e in enumerate(errs) if e < 1e-2)
+    assert errs[k + 1] < 10 * errs[k] ** 2 + 1e-15
+    # the first step from w = 0 is -g/h with p = 1/2 everywhere
+    s1 = oracle.solve(A, y, "logistic", lam, epochs=1)
+    assert s1.x[0] == pytest.approx(-(np.mean(-y * a * 0.5) / (np.mean(a * a * 0.25) + lam)), rel=1e-14)
+
+
+def test_logistic_two_features_brute_force():
+    n, lam = 25, 0.05
+    X = rng.standard_normal((n, 2)).astype(np.float32).astype(np.float64)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    s = oracle.solve(dense_to_csc(X), y, "logistic", lam, epochs=200)
+    g = np.linspace(-3, 3, 601)
+    W0, W1 = np.meshgrid(g, g, indexing="ij")
+    Z = X[:, 0][:, None, None] * W0 + X[:, 1][:, None, None] * W1
+    Pgrid = np.mean(np.logaddexp(0, -y[:, None, None] * Z), axis=0) + 0.5 * lam * (W0 ** 2 + W1 ** 2)
+    i, j = np.unravel_index(np.argmin(Pgrid), Pgrid.shape)
+    assert abs(s.x[0] - g[i]) <= 0.011 and abs(s.x[1] - g[j]) <= 0.011
+    assert s.primal() <= Pgrid.min() + 1e-12
+    assert s.primal() == pytest.approx(P_logistic(X, y, s.x, lam), rel=1e-13)
+
+
+@pytest.mark.parametrize("layout", ["csc", "dense"])
+def test_logistic_against_quasi_newton(layout):
+    n, d, lam = 200, 15, 0.01
+    X = sparse_random(n, d, 0.4, rng)
+    y = np.where(X @ rng.standard_normal(d) + 0.3 * rng.standard_normal(n) > 0, 1.0, -1.0).astype(np.float32)
+    A = dense_to_csc(X) if layout == "csc" else dense_colmajor(X)
+    s = oracle.solve(A, y, "logistic", lam, epochs=500, tol=1e-15)
+    f = lambda w: P_logistic(X, y, w, lam)
+    gr = lambda w: X.T @ (-y / (1 + np.exp(y * (X @ w)))) / n + lam * w
+    r = scipy.optimize.minimize(f, np.zeros(d), jac=gr, method="L-BFGS-B", options={"ftol": 1e-16, "gtol": 1e-12,
+                                                                                      "maxiter": 5000})
+    assert np.max(np.abs(gr(s.x))) < 1e-8          # gradient computed independently vanishes
+    assert abs(s.primal() - r.fun) < 1e-10
+    np.testing.assert_allclose(s.x, r.x, atol=2e-5)
+    np.testing.assert_allclose(s.v, X @ s.x, atol=1e-11)
+
+
+def test_logistic_extreme_margins_are_finite():
+    X = np.array([[800.0], [-800.0]])
+    y = np.array([1.0, -1.0], dtype=np.float32)
+    s = oracle.Solver(dense_to_csc(X), y, "logistic", 1e-3)
+    s.x[:] = 5.0
+    s.v[:] = X[:, 0] * 5.0
+    assert np.isfinite(s.primal()) and np.isfinite(s.gap()) and np.isfinite(s.gap("fenchel"))
+    s.x[:] = -5.0
+    s.v[:] = X[:, 0] * -5.0
+    assert s.primal() == pytest.approx(4000.0 + 0.5e-3 * 25, rel=1e-12)
+    s.epoch(0)
+    assert np.all(np.isfinite(s.x))
+
+
+# ---------------------------------------------------------------------------------------------
+# hinge (dual)
+def test_hinge_single_example_closed_form():
+    for scale, lam in [(1.0, 0.5), (3.0, 0.5), (0.2, 2.0)]:
+        x = np.array([[0.6 * scale, -0.8 * scale]], dtype=np.float32)
+        s = oracle.solve(dense_to_csr(x.astype(np.float64)), np.array([1.0], dtype=np.float32), "hinge", lam, epochs=1)
+        nrm = float(x.astype(np.float64)[0] @ x.astype(np.float64)[0])
+        assert s.x[0] == pytest.approx(min(1.0, max(0.0, lam * 1 / nrm)), rel=1e-12)
+
+
+def test_hinge_box_monotone_and_weak_duality():
+    n, d, lam = 50, 6, 0.02
+    X = sparse_random(n, d, 0.7, rng)
+    X[3, :] = 0.0   # an empty row
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    A = dense_to_csr(X)
+    s = oracle.Solver(A, y, "hinge", lam)
+    import ctypes as C
+    lib = oracle.lib()
+    prevD = s.dual()
+    assert prevD == 0.0
+    for e in range(4):
+        perm = oracle.permutation(e, n)
+        for k in range(n):
+            one = perm[k:k + 1].copy()
+            lib.oracle_epoch_dual_hinge(C.c_int64(n), oracle._p(A.ptr), oracle._p(A.idx), oracle._p(A.val),
+                                        oracle._p(s.y), C.c_double(lam), oracle._p(one), C.c_int64(0),
+                                        C.c_int64(1), oracle._p(s.x), oracle._p(s.v))
+            assert s.x.min() >= 0.0 and s.x.max() <= 1.0
+            D = s.dual()
+            assert D >= prevD - 1e-15
+            prevD = D
+        P, D = s.primal_dual()
+        w = s.weights()
+        assert P == pytest.approx(P_hinge(X, y, w, lam), rel=1e-13)
+        assert D == pytest.approx(np.mean(s.x) - 0.5 * lam * w @ w, rel=1e-13, abs=1e-15)
+        assert P >= D - 1e-15
+        np.testing.assert_allclose(s.v, X.T @ (y * s.x), atol=1e-12)
+    assert s.x[3] == 1.0
+
+
+def test_hinge_two_features_brute_force():
+    n, lam = 30, 0.1
+    X = rng.standard_normal((n, 2)).astype(np.float32).astype(np.float64)
+    y = np.where(X @ np.array([1.0, -0.5]) + 0.5 * rng.standard_normal(n) > 0, 1.0, -1.0).astype(np.float32)
+    s = oracle.solve(dense_to_csr(X), y, "hinge", lam, epochs=3000, tol=1e-13)
+    g = np.linspace(-4, 4, 801)
+    W0, W1 = np.meshgrid(g, g, indexing="ij")
+    Z = X[:, 0][:, None, None] * W0 + X[:, 1][:, None, None] * W1
+    Pgrid = np.mean(np.maximum(0, 1 - y[:, None, None] * Z), axis=0) + 0.5 * lam * (W0 ** 2 + W1 ** 2)
+    i, j = np.unravel_index(np.argmin(Pgrid), Pgrid.shape)
+    P, D = s.primal_dual()
+    assert P - D < 1e-10
+    assert P <= Pgrid.min() + 1e-12 and P >= Pgrid.min() - 1e-3
+    w = s.weights()
+    assert abs(w[0] - g[i]) <= 0.02 and abs(w[1] - g[j]) <= 0.02
+
+
+# ---------------------------------------------------------------------------------------------
+# duality gap
+@pytest.mark.parametrize("loss", ["ridge", "logistic"])
+def test_gap_forms_agree_closed_form_at_zero_and_bounds(loss):
+    n, d, lam = 80, 9, 0.03
+    X = sparse_random(n, d, 0.5, rng)
+    y = (rng.standard_normal(n) if loss == "ridge" else np.where(rng.random(n) < 0.4, 1.0, -1.0)).astype(np.float32)
+    A = dense_to_csc(X)
+    s = oracle.Solver(A, y, loss, lam)
+    g0 = np.linalg.norm(X.T @ y) ** 2 / (2 * lam * n * n) / (1.0 if loss == "ridge" else 4.0)
+    assert s.gap() == pytest.approx(g0, rel=1e-12)
+    assert s.gap("fenchel") == pytest.approx(g0, rel=1e-10)
+    if loss == "ridge":
+        Pstar = P_ridge(X, y, ridge_closed_form(X, y.astype(np.float64), lam), lam)
+    else:
+        Pstar = oracle.solve(A, y, loss, lam, epochs=2000, tol=1e-15).primal()
+    last = None
+    for e in range(30):
+        s.epoch(e)
+        G, Gf = s.gap(), s.gap("fenchel")
+        assert G >= 0 and abs(G - Gf) <= 1e-9 * max(1.0, G)
+        assert G >= s.primal() - Pstar - 1e-12
+        last = G
+    assert last < 1e-8 * g0
+
+
+def test_gap_hinge_goes_to_zero_and_bounds_suboptimality():
+    n, d, lam = 60, 5, 0.05
+    X = sparse_random(n, d, 0.8, rng)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    A = dense_to_csr(X)
+    ref = oracle.solve(A, y, "hinge", lam, epochs=5000, tol=1e-14)
+    Dstar = ref.dual()
+    s = oracle.Solver(A, y, "hinge", lam)
+    assert s.gap() == pytest.approx(1.0, rel=1e-15)      # alpha = 0: P = 1, D = 0
+    for e in range(200):
+        s.epoch(e)
+        assert s.gap() >= Dstar - s.dual() - 1e-12
+    assert s.gap() < 1e-6
+
+
+# ---------------------------------------------------------------------------------------------
+# products
+@pytest.mark.parametrize("layout", ["csr", "csc", "dense"])
+def test_products_against_dense_and_scipy(layout):
+    n, d = 37, 23
+    X = sparse_random(n, d, 0.3, rng)
+    A = {"csr": dense_to_csr, "csc": dense_to_csc, "dense": dense_colmajor}[layout](X)
+    x, u = rng.standard_normal(d), rng.standard_normal(n)
+    np.testing.assert_allclose(A.matvec(x), X @ x, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(A.rmatvec(u), X.T @ u, rtol=1e-13, atol=1e-13)
+    assert u @ A.matvec(x) == pytest.approx(x @ A.rmatvec(u), rel=1e-12)
+    np.testing.assert_allclose(A.to_dense(), X)
+
+
+def test_products_medium_against_scipy():
+    S = sp.random(3000, 800, density=0.01, format="csr", random_state=3, dtype=np.float32)
+    S.sort_indices()
+    A = Matrix("csr", 3000, 800, S.indptr.astype(np.int64), S.indices.astype(np.int32), S.data)
+    x = rng.standard_normal(800)
+    np.testing.assert_allclose(A.matvec(x), S.astype(np.float64) @ x, rtol=1e-12, atol=1e-12)
+    Sc = S.tocsc()
+    Sc.sort_indices()
+    Ac = Matrix("csc", 3000, 800, Sc.indptr.astype(np.int64), Sc.indices.astype(np.int32), Sc.data)
+    np.testing.assert_allclose(Ac.matvec(x), S.astype(np.float64) @ x, rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
+# streaming order: chunks in sequence, permutation inside each chunk (Section 3.2)
+def test_chunked_epoch_visits_every_coordinate_once_in_chunk_order():
+    n, d, lam = 50, 20, 0.05
+    X = sparse_random(n, d, 0.5, rng)
+    y = rng.standard_normal(n).astype(np.float32)
+    bounds = [0, 7, 12, 20]
+    s = oracle.Solver(dense_to_csc(X), y, "ridge", lam, chunk_bounds=bounds)
+    s.epoch(3)
+    assert sorted(s.last_perm.tolist()) == list(range(d))
+    for ch in range(3):
+        seg = s.last_perm[bounds[ch]:bounds[ch + 1]]
+        assert seg.min() >= bounds[ch] and seg.max() < bounds[ch + 1]
+    for e in range(400):
+        s.epoch(e)
+    np.testing.assert_allclose(s.x, ridge_closed_form(X, y.astype(np.float64), lam), atol=1e-10)
