@@ -1,0 +1,165 @@
+/*
+ * snap.h -- C ABI of the MI355X (gfx950) local solver: asynchronous stochastic coordinate descent
+ * (SCD) for generalized linear models, the GPU-resident solver of Snap ML (arXiv 1803.06333,
+ * Section 3.1), with the double-buffered data streaming of Section 3.2.
+ *
+ * Problem (paper eq. (1)):  min_alpha f(A alpha) + sum_i g_i(alpha_i),  shared vector v = A alpha.
+ * With X the n_rows x n_cols example matrix, labels y and lambda > 0 the library minimises
+ *
+ *      P(w) = (1/n) sum_i loss(y_i, x_i.w) + (lambda/2) ||w||^2
+ *
+ *   primal form (CSC or dense column-major; ridge, logistic): coordinates = columns, model w,
+ *                v = X w (length n_rows);
+ *   dual form   (CSR; hinge): coordinates = rows, model alpha in [0,1]^n, v = X^T (y o alpha)
+ *                (length n_cols), w = v / (lambda n).
+ *
+ * One coordinate update = gather-dot of the coordinate's nonzeros with v, a scalar step (closed
+ * form for ridge and the clipped hinge dual, one Newton step for logistic), and an atomic scatter
+ * of delta * a_j into v; an epoch visits every coordinate once in the order of a seeded
+ * permutation with many coordinates in flight.
+ *
+ * Conventions
+ *  - Every function returns SNAP_OK (0) or a negative SNAP_E* code; snap_last_error() gives a
+ *    thread-local message.  Nothing aborts or throws across this boundary.
+ *  - All pointers in snap_matrix live in ONE memory space, named by `mem`.  In resident mode the
+ *    library copies matrix and labels during snap_create (the caller may free them afterwards).
+ *    In streaming mode (device_budget_bytes > 0 and the matrix larger than the budget) the matrix
+ *    arrays must be SNAP_MEM_HOST_PINNED and are BORROWED until snap_destroy.
+ *  - Index arrays: ptr is int64[major+1] (absolute offsets, ptr[0] == 0), idx is int32[nnz] with
+ *    0 <= idx < minor, val is fp32[nnz].  Dense: val only, n_rows*n_cols fp32, column-major
+ *    (element (i,j) at val[j*n_rows+i]) or row-major (val[i*n_cols+j]); ptr = idx = NULL.
+ *  - Labels y: fp32[n_rows], in the same memory space as the matrix; logistic and hinge need
+ *    y in {-1,+1}.
+ *  - Output buffers of snap_get_* are HOST pointers, caller allocated.  snap_predict writes to a
+ *    buffer in the memory space of its matrix argument.
+ *  - snap_epoch works on the handle's compute stream; the query functions synchronise that
+ *    stream.  One handle must not be used from two threads at once.
+ */
+#ifndef SNAP_H
+#define SNAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct snap_handle snap_handle; /* opaque, owned by the library */
+
+enum { SNAP_CSR = 0, SNAP_CSC = 1, SNAP_DENSE_ROWMAJOR = 2, SNAP_DENSE_COLMAJOR = 3 };
+enum { SNAP_RIDGE = 0, SNAP_LOGISTIC = 1, SNAP_HINGE = 2 };
+enum { SNAP_FORM_AUTO = 0, SNAP_PRIMAL = 1, SNAP_DUAL = 2 }; /* AUTO: CSC/dense -> primal, CSR -> dual */
+enum { SNAP_MEM_HOST = 0, SNAP_MEM_HOST_PINNED = 1, SNAP_MEM_DEVICE = 2 };
+enum {
+    SNAP_OK = 0,
+    SNAP_EINVAL = -1,       /* bad argument (null pointer, negative size, inconsistent ptr array...) */
+    SNAP_EUNSUPPORTED = -2, /* (loss, form, layout) combination that is not implemented */
+    SNAP_ENOMEM = -3,       /* host or device allocation failed */
+    SNAP_EHIP = -4,         /* a HIP runtime call failed */
+    SNAP_ESTATE = -5        /* a kernel reported an internal failure (bounded wait expired) */
+};
+
+typedef struct {
+    int layout;            /* SNAP_CSR ... */
+    int mem;               /* SNAP_MEM_* of ptr, idx, val (and of y / out that accompany it) */
+    int64_t n_rows, n_cols, nnz;
+    const int64_t *ptr;
+    const int32_t *idx;
+    const float *val;
+} snap_matrix;
+
+typedef struct {
+    int form;                    /* SNAP_FORM_AUTO | SNAP_PRIMAL | SNAP_DUAL */
+    size_t device_budget_bytes;  /* 0: keep the matrix resident; else stream it when larger */
+    size_t chunk_bytes;          /* streaming chunk size in bytes of idx+val (0: 4 GiB) */
+    void *compute_stream;        /* hipStream_t to run on (e.g. PyTorch's), or NULL: own stream */
+    void *copy_stream;           /* hipStream_t for chunk copies, or NULL: own stream */
+    int refresh_v_every;         /* recompute v = A x every this many epochs; 0 = never */
+    int profile;                 /* 1: bracket each epoch's SCD kernels with HIP events */
+    int adaptive;                /* 0: default (= on), 1: on, 2: off.  On: after every epoch the
+                                    objective is evaluated; if it got worse the epoch's updates are
+                                    discarded, the number of nonzeros in flight is halved and, once that
+                                    is at its floor, the damping is halved (Section 3.1, "Adaptive
+                                    Damping").  snap_epoch then waits for the epoch to finish. */
+    float damping;               /* initial damping in (0,1]; 0 means 1 (no damping) */
+    int64_t max_inflight_nnz;    /* cap on the nonzeros of coordinates in flight at once; 0 = automatic:
+                                    a quarter of the effective length of v, (sum f)^2 / sum f^2 over the
+                                    access counts f of the entries of v (dense data: no cap) */
+    int reserved[4];             /* must be zero */
+} snap_options;
+
+/* Per-epoch figures gathered when options.profile = 1 (milliseconds of device time). */
+typedef struct {
+    float epoch_ms;        /* whole snap_epoch: permutation + SCD kernels (+ chunk waits) */
+    float scd_ms;          /* the SCD epoch kernels alone (the dominant kernels) */
+    float perm_ms;         /* key generation + radix sort + class partition */
+    float copy_ms;         /* streaming: sum of chunk copy times (0 when resident) */
+    int64_t n_chunks;      /* streaming: chunks per epoch (1 when resident) */
+    int64_t n_small;       /* coordinates handled one-wavefront-per-coordinate */
+    int64_t n_large;       /* coordinates split over several workgroups */
+    int64_t n_items;       /* workgroup work items of the split-coordinate kernel */
+    int64_t inflight_nnz;  /* cap on nonzeros in flight used by the last epoch */
+    float damping;         /* damping used by the last epoch */
+    int rejected;          /* 1 if the adaptive check discarded the last epoch's updates */
+} snap_epoch_stats;
+
+/* Section 1 eq. (1) / Section 3.1.  Builds the solver state for X (A), y, loss and lambda:
+ * copies or registers the data, computes the squared norm of every coordinate, sets the model
+ * and the shared vector to zero (Algorithm 1's starting point).  opt may be NULL (defaults).
+ * On failure *out is NULL. */
+int snap_create(const snap_matrix *A, const float *y, int loss, double lambda,
+                const snap_options *opt, snap_handle **out);
+
+/* Section 3.1 / 3.2.  One pass over all coordinates, each exactly once, in the order given by the
+ * permutation that perm_seed defines: a 32-bit xorshift key per coordinate, coordinates sorted by
+ * (key, index).  Streaming: chunks of consecutive coordinates are visited in order, permuted
+ * inside each chunk, the next chunk being copied while the current one is processed.
+ * Stream-ordered; with options.adaptive off it returns after enqueueing, with it on it also
+ * waits for the epoch and applies the accept / discard decision. */
+int snap_epoch(snap_handle *h, uint64_t perm_seed);
+
+/* P(w) above and, in the dual form, D(alpha) = (1/n) sum alpha_i - (lambda/2)||w||^2.
+ * `dual` may be NULL; in the primal form *dual receives P - gap.  fp32 data, fp64 reductions in a
+ * fixed order (deterministic). */
+int snap_objective(snap_handle *h, double *primal, double *dual);
+
+/* Duality gap of eq. (1) with the dual candidate u = grad f(v): primal form
+ * ||X^T u + lambda w||^2 / (2 lambda); hinge dual form P(w(alpha)) - D(alpha).  Deterministic. */
+int snap_duality_gap(snap_handle *h, double *gap);
+
+/* Decision values out[i] = x_i . w for the rows of X (CSR, dense row-major or dense
+ * column-major; X->n_cols must equal the training n_cols).  out has X->n_rows floats in the memory
+ * space X->mem. */
+int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
+
+/* w (n_cols floats, may be NULL) and the coordinate vector (w in primal form, alpha in dual form;
+ * m floats, may be NULL), to host memory. */
+int snap_get_model(snap_handle *h, float *w_out, float *coord_out);
+
+/* Overwrite the coordinate vector (m host floats) and recompute v = A x from it. */
+int snap_set_model(snap_handle *h, const float *coord_in);
+
+/* The shared vector v as the solver maintains it (host; n_rows floats primal, n_cols dual). */
+int snap_get_shared(snap_handle *h, float *v_out);
+
+/* v <- A x recomputed from the model (removes fp32 drift of the atomically updated v). */
+int snap_recompute_shared(snap_handle *h);
+
+/* The visiting order of the last epoch (m host uint32; streaming: chunk after chunk, absolute
+ * coordinate numbers) and, if keys_out != NULL, the 32-bit key of every coordinate. */
+int snap_get_perm(snap_handle *h, uint32_t *perm_out, uint32_t *keys_out);
+
+/* Timing of the last epoch (valid when options.profile = 1). */
+int snap_get_epoch_stats(snap_handle *h, snap_epoch_stats *out);
+
+/* Number of coordinates m and length of v. */
+int snap_get_dims(snap_handle *h, int64_t *n_coords, int64_t *shared_len);
+
+const char *snap_last_error(void); /* thread-local string */
+void snap_destroy(snap_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SNAP_H */

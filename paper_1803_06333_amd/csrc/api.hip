@@ -1,0 +1,515 @@
+// The C ABI of libsnap (see include/snap.h): argument checking, data placement, the epoch driver.
+#include "common.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <cmath>
+#include <algorithm>
+#include <new>
+#include <vector>
+
+namespace snap {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char* what, const char* file, int line) {
+    set_error("HIP error %d (%s) in %s at %s:%d", (int)e, hipGetErrorString(e), what, file, line);
+    return e == hipErrorOutOfMemory ? SNAP_ENOMEM : SNAP_EHIP;
+}
+
+__global__ void k_check_indices(const int32_t* __restrict__ idx, int64_t count, int64_t minor, uint32_t* flag) {
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < count; k += (int64_t)gridDim.x * blockDim.x)
+        if (idx[k] < 0 || (int64_t)idx[k] >= minor) atomicOr(flag, 1u);
+}
+
+__global__ void k_check_labels(const float* __restrict__ y, int64_t n, uint32_t* flag) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        if (!(y[i] == 1.0f || y[i] == -1.0f)) atomicOr(flag, 2u);
+}
+
+static int check_status(snap_handle* h) {
+    uint32_t st = 0;
+    SNAP_HIP(hipMemcpyAsync(&st, h->status, sizeof(st), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    if (st & 1u) {
+        set_error("a scatter work item gave up waiting for its coordinate's step; the state is invalid");
+        return SNAP_ESTATE;
+    }
+    return SNAP_OK;
+}
+
+static void destroy(snap_handle* h) {
+    if (!h) return;
+    if (h->compute) (void)hipStreamSynchronize(h->compute);
+    if (h->copy) (void)hipStreamSynchronize(h->copy);
+    (void)hipFree(h->ptr);
+    (void)hipFree(h->idx);
+    (void)hipFree(h->val);
+    (void)hipFree(h->y);
+    (void)hipFree(h->x);
+    (void)hipFree(h->v);
+    (void)hipFree(h->norms);
+    (void)hipFree(h->cls);
+    (void)hipFree(h->w_tmp);
+    (void)hipFree(h->gdot);
+    (void)hipFree(h->large_list);
+    (void)hipFree(h->large_seg_off);
+    (void)hipFree(h->seg_partial);
+    (void)hipFree(h->keys);
+    (void)hipFree(h->perm);
+    (void)hipFree(h->order);
+    (void)hipFree(h->lstate);
+    (void)hipFree(h->item_start);
+    (void)hipFree(h->ticket);
+    (void)hipFree(h->status);
+    (void)hipFree(h->x_snap);
+    (void)hipFree(h->v_snap);
+    for (int b = 0; b < 2; ++b) {
+        (void)hipFree(h->buf_idx[b]);
+        (void)hipFree(h->buf_val[b]);
+        if (h->ev_copied[b]) (void)hipEventDestroy(h->ev_copied[b]);
+        if (h->ev_free[b]) (void)hipEventDestroy(h->ev_free[b]);
+    }
+    for (auto& e : h->ev)
+        if (e) (void)hipEventDestroy(e);
+    sorter_free(h->sorter);
+    reducer_free(h->red);
+    delete[] h->chunks;
+    if (h->own_compute && h->compute) (void)hipStreamDestroy(h->compute);
+    if (h->own_copy && h->copy) (void)hipStreamDestroy(h->copy);
+    delete h;
+}
+
+static int64_t n_segments(int64_t len) { return (len + SEG - 1) / SEG; }
+
+static int build(snap_handle* h, const snap_matrix* A, const float* y) {
+    SNAP_HIP(hipGetDevice(&h->device));
+    if (h->opt.compute_stream) {
+        h->compute = (hipStream_t)h->opt.compute_stream;
+    } else {
+        SNAP_HIP(hipStreamCreateWithFlags(&h->compute, hipStreamNonBlocking));
+        h->own_compute = true;
+    }
+    if (h->opt.copy_stream) {
+        h->copy = (hipStream_t)h->opt.copy_stream;
+    } else {
+        SNAP_HIP(hipStreamCreateWithFlags(&h->copy, hipStreamNonBlocking));
+        h->own_copy = true;
+    }
+    for (auto& e : h->ev) SNAP_HIP(hipEventCreate(&e));
+    SNAP_TRY(reducer_alloc(h->red));
+    SNAP_HIP(hipMalloc(&h->status, sizeof(uint32_t)));
+    SNAP_HIP(hipMalloc(&h->ticket, sizeof(uint32_t)));
+    SNAP_TRY(fill_zero(h->status, 4, h->compute));
+    SNAP_TRY(fill_zero(h->ticket, 4, h->compute));
+
+    const int64_t m = h->m;
+    // ---- the matrix: host copy of ptr for planning, device copies of everything -----------------
+    std::vector<int64_t> hptr;
+    if (!h->dense) {
+        hptr.resize((size_t)m + 1);
+        SNAP_HIP(hipMemcpy(hptr.data(), A->ptr, (size_t)(m + 1) * sizeof(int64_t), hipMemcpyDefault));
+        if (hptr[0] != 0 || hptr[(size_t)m] != h->nnz) {
+            set_error("ptr[0] must be 0 and ptr[last] must equal nnz");
+            return SNAP_EINVAL;
+        }
+        for (int64_t c = 0; c < m; ++c)
+            if (hptr[(size_t)c + 1] < hptr[(size_t)c]) {
+                set_error("ptr is not non-decreasing at %lld", (long long)c);
+                return SNAP_EINVAL;
+            }
+        SNAP_HIP(hipMalloc(&h->ptr, (size_t)(m + 1) * sizeof(int64_t)));
+        SNAP_HIP(hipMemcpyAsync(h->ptr, hptr.data(), (size_t)(m + 1) * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
+        SNAP_HIP(hipMalloc(&h->idx, (size_t)(h->nnz ? h->nnz : 1) * sizeof(uint32_t)));
+        SNAP_HIP(hipMalloc(&h->val, (size_t)(h->nnz ? h->nnz : 1) * sizeof(float)));
+        SNAP_HIP(hipMemcpyAsync(h->idx, A->idx, (size_t)h->nnz * sizeof(uint32_t), hipMemcpyDefault, h->compute));
+        SNAP_HIP(hipMemcpyAsync(h->val, A->val, (size_t)h->nnz * sizeof(float), hipMemcpyDefault, h->compute));
+    } else {
+        const size_t count = (size_t)h->n * (size_t)h->d;
+        SNAP_HIP(hipMalloc(&h->val, (count ? count : 1) * sizeof(float)));
+        SNAP_HIP(hipMemcpyAsync(h->val, A->val, count * sizeof(float), hipMemcpyDefault, h->compute));
+    }
+    SNAP_HIP(hipMalloc(&h->y, (size_t)(h->n ? h->n : 1) * sizeof(float)));
+    SNAP_HIP(hipMemcpyAsync(h->y, y, (size_t)h->n * sizeof(float), hipMemcpyDefault, h->compute));
+
+    // ---- validation on the device: indices in range, labels +-1 where the loss needs them ---------
+    {
+        const int64_t minor = h->form == SNAP_PRIMAL ? h->n : h->d;
+        if (!h->dense && h->nnz > 0)
+            hipLaunchKernelGGL(k_check_indices, dim3(4096), dim3(256), 0, h->compute, (const int32_t*)h->idx, h->nnz,
+                               minor, h->status);
+        if (h->loss != SNAP_RIDGE && h->n > 0)
+            hipLaunchKernelGGL(k_check_labels, dim3(1024), dim3(256), 0, h->compute, h->y, h->n, h->status);
+        uint32_t st = 0;
+        SNAP_HIP(hipMemcpyAsync(&st, h->status, 4, hipMemcpyDeviceToHost, h->compute));
+        SNAP_HIP(hipStreamSynchronize(h->compute));
+        SNAP_TRY(fill_zero(h->status, 4, h->compute));
+        if (st & 1u) {
+            set_error("an index in idx is outside [0, %lld)", (long long)minor);
+            return SNAP_EINVAL;
+        }
+        if (st & 2u) {
+            set_error("labels must be +1 or -1 for this loss");
+            return SNAP_EINVAL;
+        }
+    }
+
+    // ---- state ---------------------------------------------------------------------------------
+    SNAP_HIP(hipMalloc(&h->x, (size_t)(m ? m : 1) * sizeof(float)));
+    SNAP_HIP(hipMalloc(&h->v, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
+    SNAP_HIP(hipMalloc(&h->norms, (size_t)(m ? m : 1) * sizeof(float)));
+    SNAP_HIP(hipMalloc(&h->cls, (size_t)(m ? m : 1) + 4));
+    SNAP_HIP(hipMalloc(&h->w_tmp, (size_t)(h->d ? h->d : 1) * sizeof(float)));
+    SNAP_HIP(hipMalloc(&h->gdot, (size_t)(m ? m : 1) * sizeof(double)));
+    SNAP_HIP(hipMalloc(&h->keys, (size_t)(m ? m : 1) * sizeof(uint32_t)));
+    SNAP_HIP(hipMalloc(&h->perm, (size_t)(m ? m : 1) * sizeof(uint32_t)));
+    SNAP_TRY(fill_zero(h->x, (size_t)m * sizeof(float), h->compute));
+    SNAP_TRY(fill_zero(h->v, (size_t)h->vlen * sizeof(float), h->compute));
+    SNAP_TRY(fill_zero(h->perm, (size_t)m * sizeof(uint32_t), h->compute));
+    SNAP_TRY(fill_zero(h->keys, (size_t)m * sizeof(uint32_t), h->compute));
+    SNAP_TRY(compute_norms_and_classes(h));
+    if (h->kind == K_PRIMAL_LOGISTIC && !h->dense) SNAP_TRY(fold_labels(h, h->idx, h->nnz, h->compute));
+
+    // ---- chunks and the static list of large coordinates (host planning) --------------------------
+    h->n_chunks = 1;
+    h->chunks = new (std::nothrow) snap_handle::Chunk[1];
+    if (!h->chunks) return SNAP_ENOMEM;
+    std::vector<int64_t> large, seg_off;
+    seg_off.push_back(0);
+    snap_handle::Chunk& ck = h->chunks[0];
+    ck = {0, m, 0, h->nnz, 0, 0, 0};
+    for (int64_t c = 0; c < m; ++c) {
+        const int64_t len = h->dense ? h->ld : hptr[(size_t)c + 1] - hptr[(size_t)c];
+        if (h->dense || len > SMALL_MAX) {
+            ++ck.n_large;
+            ck.n_items += 2 * n_segments(len);
+            large.push_back(c);
+            seg_off.push_back(seg_off.back() + n_segments(len));
+        } else {
+            ++ck.n_small;
+        }
+    }
+    h->max_chunk_m = m;
+    h->max_large = ck.n_large;
+    h->n_large_total = (int64_t)large.size();
+    h->n_seg_total = seg_off.back();
+    SNAP_TRY(sorter_alloc(h->sorter, m));
+    SNAP_HIP(hipMalloc(&h->order, (size_t)(m ? m : 1) * sizeof(uint32_t)));
+    SNAP_HIP(hipMalloc(&h->lstate, (size_t)(h->max_large + 1) * sizeof(LargeState)));
+    SNAP_HIP(hipMalloc(&h->item_start, (size_t)(h->max_large + 2) * sizeof(int64_t)));
+    SNAP_HIP(hipMalloc(&h->large_list, (large.size() + 1) * sizeof(int64_t)));
+    SNAP_HIP(hipMalloc(&h->large_seg_off, seg_off.size() * sizeof(int64_t)));
+    SNAP_HIP(hipMalloc(&h->seg_partial, (size_t)(h->n_seg_total + 1) * sizeof(double)));
+    SNAP_HIP(hipMemcpyAsync(h->large_list, large.data(), large.size() * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
+    SNAP_HIP(hipMemcpyAsync(h->large_seg_off, seg_off.data(), seg_off.size() * sizeof(int64_t), hipMemcpyHostToDevice,
+                            h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));   // host vectors above go out of scope
+
+    // ---- concurrency control ---------------------------------------------------------------------
+    h->adaptive = h->opt.adaptive != 2;
+    h->damping = h->opt.damping > 0.0f ? h->opt.damping : 1.0f;
+    {
+        int64_t small_nnz = 0;
+        if (!h->dense)
+            for (int64_t c = 0; c < m; ++c) {
+                const int64_t len = hptr[(size_t)c + 1] - hptr[(size_t)c];
+                if (len <= SMALL_MAX) small_nnz += len;
+            }
+        h->avg_small_len = ck.n_small > 0 ? std::max(1.0, (double)small_nnz / (double)ck.n_small) : 1.0;
+    }
+    h->inflight_floor = WAVE;
+    if (h->opt.max_inflight_nnz > 0) {
+        h->inflight_nnz = h->opt.max_inflight_nnz;
+    } else if (h->dense) {
+        h->inflight_nnz = 0;                      // no cap; the adaptive check lowers it if needed
+    } else {
+        double eff = 0.0;
+        SNAP_TRY(effective_shared_length(h, &eff));
+        h->inflight_nnz = std::max<int64_t>(1, (int64_t)(0.25 * eff));
+    }
+    if (h->adaptive) {
+        SNAP_HIP(hipMalloc(&h->x_snap, (size_t)(m ? m : 1) * sizeof(float)));
+        SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
+    }
+    return SNAP_OK;
+}
+
+}  // namespace snap
+
+using namespace snap;
+
+extern "C" {
+
+const char* snap_last_error(void) { return g_error; }
+
+int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, const snap_options* opt,
+                snap_handle** out) {
+    if (out) *out = nullptr;
+    if (!A || !y || !out) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    if (A->n_rows < 0 || A->n_cols < 0 || A->nnz < 0 || !(lambda > 0.0) || A->n_rows > 0x7FFFFFFFll ||
+        A->n_cols > 0x7FFFFFFFll) {
+        set_error("sizes must be non-negative and below 2^31 per dimension, lambda positive");
+        return SNAP_EINVAL;
+    }
+    if (A->layout < SNAP_CSR || A->layout > SNAP_DENSE_COLMAJOR || A->mem < SNAP_MEM_HOST || A->mem > SNAP_MEM_DEVICE ||
+        loss < SNAP_RIDGE || loss > SNAP_HINGE) {
+        set_error("unknown layout, memory space or loss");
+        return SNAP_EINVAL;
+    }
+    const bool dense = A->layout == SNAP_DENSE_ROWMAJOR || A->layout == SNAP_DENSE_COLMAJOR;
+    if (!A->val || (!dense && (!A->ptr || !A->idx))) {
+        set_error("matrix arrays missing");
+        return SNAP_EINVAL;
+    }
+    snap_options o{};
+    if (opt) o = *opt;
+    for (int r : o.reserved)
+        if (r != 0) {
+            set_error("options.reserved must be zero");
+            return SNAP_EINVAL;
+        }
+    int form = o.form;
+    const bool row_coords = A->layout == SNAP_CSR || A->layout == SNAP_DENSE_ROWMAJOR;
+    if (form == SNAP_FORM_AUTO) form = row_coords ? SNAP_DUAL : SNAP_PRIMAL;
+    if (form != SNAP_PRIMAL && form != SNAP_DUAL) {
+        set_error("unknown form");
+        return SNAP_EINVAL;
+    }
+    if ((form == SNAP_PRIMAL) == row_coords) {
+        set_error("the primal form needs column access (CSC / dense column-major), the dual form row access");
+        return SNAP_EUNSUPPORTED;
+    }
+    if ((form == SNAP_PRIMAL && loss == SNAP_HINGE) || (form == SNAP_DUAL && loss != SNAP_HINGE)) {
+        set_error("supported pairs: (ridge, primal), (logistic, primal), (hinge, dual)");
+        return SNAP_EUNSUPPORTED;
+    }
+    if (o.device_budget_bytes != 0) {
+        set_error("streaming is not available in this build");
+        return SNAP_EUNSUPPORTED;
+    }
+    snap_handle* h = new (std::nothrow) snap_handle();
+    if (!h) {
+        set_error("out of host memory");
+        return SNAP_ENOMEM;
+    }
+    h->layout = A->layout;
+    h->loss = loss;
+    h->form = form;
+    h->kind = loss == SNAP_RIDGE ? K_PRIMAL_RIDGE : (loss == SNAP_LOGISTIC ? K_PRIMAL_LOGISTIC : K_DUAL_HINGE);
+    h->dense = dense;
+    h->n = A->n_rows;
+    h->d = A->n_cols;
+    h->nnz = dense ? A->n_rows * A->n_cols : A->nnz;
+    h->m = form == SNAP_PRIMAL ? h->d : h->n;
+    h->vlen = form == SNAP_PRIMAL ? h->n : h->d;
+    h->ld = dense ? h->vlen : 0;
+    h->lambda = lambda;
+    h->opt = o;
+    const int rc = build(h, A, y);
+    if (rc != SNAP_OK) {
+        destroy(h);
+        return rc;
+    }
+    *out = h;
+    return SNAP_OK;
+}
+
+void snap_destroy(snap_handle* h) { destroy(h); }
+
+int snap_epoch(snap_handle* h, uint64_t perm_seed) {
+    if (!h) {
+        set_error("null handle");
+        return SNAP_EINVAL;
+    }
+    if (h->m == 0) return SNAP_OK;
+    const bool prof = h->opt.profile != 0;
+    if (h->adaptive) {
+        // value and state before the epoch, for the accept / discard decision
+        if (!h->monitor_valid) {
+            SNAP_TRY(monitor_value(h, &h->monitor_prev));
+            h->monitor_valid = true;
+        }
+        SNAP_HIP(hipMemcpyAsync(h->x_snap, h->x, (size_t)h->m * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
+        SNAP_HIP(hipMemcpyAsync(h->v_snap, h->v, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
+    }
+    if (prof) SNAP_HIP(hipEventRecord(h->ev[0], h->compute));
+    const snap_handle::Chunk& ck = h->chunks[0];
+    SNAP_TRY(make_permutation(h, perm_seed, 0u, 0, h->m, h->keys, h->perm, h->order));
+    if (prof) SNAP_HIP(hipEventRecord(h->ev[1], h->compute));
+    ChunkView cv{h->ptr, h->idx, h->val, 0, 0, h->m};
+    SNAP_TRY(scd_run_chunk(h, cv, ck, h->order));
+    if (prof) {
+        SNAP_HIP(hipEventRecord(h->ev[2], h->compute));
+        h->stats_pending = true;
+    }
+    h->stats.inflight_nnz = h->inflight_nnz;
+    h->stats.damping = h->damping;
+    h->stats.rejected = 0;
+    ++h->epochs_done;
+    if (h->opt.refresh_v_every > 0 && h->epochs_done % h->opt.refresh_v_every == 0) SNAP_TRY(recompute_shared(h));
+    if (h->adaptive) {
+        double now = 0.0;
+        SNAP_TRY(monitor_value(h, &now));
+        const double slack = 1e-6 * std::max(std::fabs(h->monitor_prev), 1e-30);
+        if (!(now <= h->monitor_prev + slack)) {          // worse (or not a number): discard the epoch
+            SNAP_HIP(hipMemcpyAsync(h->x, h->x_snap, (size_t)h->m * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
+            SNAP_HIP(hipMemcpyAsync(h->v, h->v_snap, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
+            h->stats.rejected = 1;
+            // first fewer nonzeros in flight (down to one wavefront's worth), then smaller steps
+            const int64_t cur = h->inflight_nnz > 0 ? h->inflight_nnz : (int64_t)256 * 8 * SEG;
+            if (cur > h->inflight_floor)
+                h->inflight_nnz = std::max<int64_t>(h->inflight_floor, cur / 2);
+            else
+                h->damping *= 0.5f;
+        } else {
+            h->monitor_prev = now;
+        }
+    }
+    return SNAP_OK;
+}
+
+int snap_objective(snap_handle* h, double* primal, double* dual) {
+    if (!h || !primal) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    SNAP_TRY(check_status(h));
+    return objective(h, primal, dual, nullptr);
+}
+
+int snap_duality_gap(snap_handle* h, double* gap) {
+    if (!h || !gap) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    SNAP_TRY(check_status(h));
+    return objective(h, nullptr, nullptr, gap);
+}
+
+int snap_predict(snap_handle* h, const snap_matrix* X, float* out) {
+    if (!h || !X || !out) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    if (X->layout < SNAP_CSR || X->layout > SNAP_DENSE_COLMAJOR || X->mem < SNAP_MEM_HOST || X->mem > SNAP_MEM_DEVICE) {
+        set_error("unknown layout or memory space");
+        return SNAP_EINVAL;
+    }
+    const bool dense = X->layout >= SNAP_DENSE_ROWMAJOR;
+    if (X->n_cols != h->d || X->n_rows < 0 || X->nnz < 0 || !X->val || (!dense && (!X->ptr || !X->idx))) {
+        set_error("predict: the matrix must have the training number of columns and valid arrays");
+        return SNAP_EINVAL;
+    }
+    SNAP_TRY(check_status(h));
+    return predict(h, X, out);
+}
+
+int snap_get_model(snap_handle* h, float* w_out, float* coord_out) {
+    if (!h) {
+        set_error("null handle");
+        return SNAP_EINVAL;
+    }
+    SNAP_TRY(check_status(h));
+    if (w_out) SNAP_TRY(weights_to_host(h, w_out));
+    if (coord_out) {
+        SNAP_HIP(hipMemcpyAsync(coord_out, h->x, (size_t)h->m * sizeof(float), hipMemcpyDeviceToHost, h->compute));
+        SNAP_HIP(hipStreamSynchronize(h->compute));
+    }
+    return SNAP_OK;
+}
+
+int snap_set_model(snap_handle* h, const float* coord_in) {
+    if (!h || !coord_in) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    SNAP_HIP(hipMemcpyAsync(h->x, coord_in, (size_t)h->m * sizeof(float), hipMemcpyHostToDevice, h->compute));
+    SNAP_TRY(recompute_shared(h));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    h->monitor_valid = false;
+    return SNAP_OK;
+}
+
+int snap_get_shared(snap_handle* h, float* v_out) {
+    if (!h || !v_out) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    SNAP_TRY(check_status(h));
+    SNAP_HIP(hipMemcpyAsync(v_out, h->v, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    return SNAP_OK;
+}
+
+int snap_recompute_shared(snap_handle* h) {
+    if (!h) {
+        set_error("null handle");
+        return SNAP_EINVAL;
+    }
+    return recompute_shared(h);
+}
+
+int snap_get_perm(snap_handle* h, uint32_t* perm_out, uint32_t* keys_out) {
+    if (!h || !perm_out) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    SNAP_HIP(hipMemcpyAsync(perm_out, h->perm, (size_t)h->m * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+    if (keys_out)
+        SNAP_HIP(hipMemcpyAsync(keys_out, h->keys, (size_t)h->m * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    for (int64_t ch = 0; ch < h->n_chunks; ++ch)
+        for (int64_t c = h->chunks[ch].c0; c < h->chunks[ch].c1; ++c) perm_out[c] += (uint32_t)h->chunks[ch].c0;
+    return SNAP_OK;
+}
+
+int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
+    if (!h || !out) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    if (h->stats_pending) {
+        SNAP_HIP(hipEventSynchronize(h->ev[2]));
+        float total = 0, perm = 0, scd = 0;
+        SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
+        SNAP_HIP(hipEventElapsedTime(&perm, h->ev[0], h->ev[1]));
+        SNAP_HIP(hipEventElapsedTime(&scd, h->ev[1], h->ev[2]));
+        h->stats.epoch_ms = total;
+        h->stats.perm_ms = perm;
+        h->stats.scd_ms = scd;
+        h->stats.copy_ms = 0;
+        h->stats_pending = false;
+    }
+    h->stats.n_chunks = h->n_chunks;
+    h->stats.n_small = h->stats.n_large = h->stats.n_items = 0;
+    for (int64_t ch = 0; ch < h->n_chunks; ++ch) {
+        h->stats.n_small += h->chunks[ch].n_small;
+        h->stats.n_large += h->chunks[ch].n_large;
+        h->stats.n_items += h->chunks[ch].n_items;
+    }
+    *out = h->stats;
+    return SNAP_OK;
+}
+
+int snap_get_dims(snap_handle* h, int64_t* n_coords, int64_t* shared_len) {
+    if (!h) {
+        set_error("null handle");
+        return SNAP_EINVAL;
+    }
+    if (n_coords) *n_coords = h->m;
+    if (shared_len) *shared_len = h->vlen;
+    return SNAP_OK;
+}
+
+}  // extern "C"

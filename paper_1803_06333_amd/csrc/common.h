@@ -1,0 +1,178 @@
+// Internal declarations shared by the HIP sources of libsnap (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <cstddef>
+#include "../../include/snap.h"
+
+namespace snap {
+
+// ---- error plumbing --------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what, const char* file, int line);
+
+#define SNAP_HIP(call)                                                         \
+    do {                                                                       \
+        hipError_t e_ = (call);                                                \
+        if (e_ != hipSuccess) return ::snap::hip_fail(e_, #call, __FILE__, __LINE__); \
+    } while (0)
+
+#define SNAP_TRY(call)                 \
+    do {                               \
+        int rc_ = (call);              \
+        if (rc_ != SNAP_OK) return rc_; \
+    } while (0)
+
+// ---- constants -------------------------------------------------------------------------------
+constexpr int WAVE = 64;
+constexpr int TPB = 256;                 // threads per workgroup of the epoch kernels (4 waves)
+constexpr int WAVES_PER_WG = TPB / WAVE;
+// A coordinate with more nonzeros than SMALL_MAX is split into segments of SEG nonzeros, one
+// workgroup each (two phases: partial dots, then scatter).
+constexpr int64_t SEG = 8192;
+constexpr int64_t SMALL_MAX = 4096;
+constexpr uint32_t LABEL_BIT = 0x80000000u;   // primal logistic: sign of y folded into the row index
+constexpr uint32_t SPIN_LIMIT = 1u << 22;     // bounded wait of a scatter item for its coordinate's step
+
+enum Kind { K_PRIMAL_RIDGE = 0, K_PRIMAL_LOGISTIC = 1, K_DUAL_HINGE = 2 };
+
+// Per-epoch state of one split ("large") coordinate, indexed by its position in the epoch order.
+struct LargeState {
+    double g, h;          // accumulated partial sums of the dot phase
+    float delta;          // the step, valid once ready != 0
+    uint32_t done;        // dot items finished
+    uint32_t ready;       // 1 when delta has been published
+    uint32_t pad;
+};
+
+// One chunk of coordinates [c0, c1) whose nonzeros [ptr[c0], ptr[c1]) sit in (idx, val).
+struct ChunkView {
+    const int64_t* ptr;       // device, absolute offsets, indexed by absolute coordinate
+    const uint32_t* idx;      // device, element k of the matrix at idx[k - nnz_base]
+    const float* val;
+    int64_t nnz_base;
+    int64_t c0, c1;
+};
+
+struct Sorter {              // scratch of the radix sort, sized for max_m coordinates
+    uint32_t *keys_a = nullptr, *keys_b = nullptr, *vals_a = nullptr, *vals_b = nullptr;
+    uint32_t* block_hist = nullptr;
+    int64_t max_m = 0;
+    int64_t n_blocks = 0;
+};
+
+struct Reducer {             // scratch for deterministic fp64 reductions
+    double* partial = nullptr;   // [REDUCE_BLOCKS * 4]
+    double* result = nullptr;    // [8] device
+    double* host = nullptr;      // [8] pinned host
+};
+constexpr int REDUCE_BLOCKS = 1024;
+
+}  // namespace snap
+
+struct snap_handle {
+    int layout = 0, loss = 0, form = 0, kind = 0;
+    bool dense = false;
+    int64_t n = 0, d = 0, nnz = 0;
+    int64_t m = 0, vlen = 0;          // coordinates, length of v
+    int64_t ld = 0;                   // dense: elements per coordinate (= n)
+    double lambda = 0;
+    snap_options opt{};
+    int device = 0;
+
+    // resident data (device)
+    int64_t* ptr = nullptr;           // [m+1]
+    uint32_t* idx = nullptr;          // [nnz] (label bit folded for primal logistic)
+    float* val = nullptr;             // [nnz] or dense matrix, coordinate-major
+    float* y = nullptr;               // [n]
+    float* x = nullptr;               // [m]
+    float* v = nullptr;               // [vlen]
+    float* norms = nullptr;           // [m] squared norms of the coordinates
+    uint8_t* cls = nullptr;           // [m] 0 = small, 1 = large
+    float* w_tmp = nullptr;           // [d] scratch: w in dual form
+    double* gdot = nullptr;           // [m] per-coordinate dots with v (objective / gap pass)
+
+    // static list of the large coordinates (ascending) with their segment offsets
+    int64_t* large_list = nullptr;    // [n_large_total]
+    int64_t* large_seg_off = nullptr; // [n_large_total+1]
+    double* seg_partial = nullptr;    // [n_seg_total]
+    int64_t n_large_total = 0, n_seg_total = 0;
+
+    // epoch order
+    snap::Sorter sorter;
+    uint32_t* keys = nullptr;         // [m] keys of the last epoch
+    uint32_t* perm = nullptr;         // [m] visiting order of the last epoch
+    uint32_t* order = nullptr;        // [max chunk m] order partitioned: small first, then large
+    int64_t max_chunk_m = 0;
+
+    // split-coordinate bookkeeping (per chunk, sized for the worst chunk)
+    snap::LargeState* lstate = nullptr;
+    int64_t* item_start = nullptr;    // [n_large+1] prefix sums of items in epoch order
+    uint32_t* ticket = nullptr;       // work-item counter
+    uint32_t* status = nullptr;       // device error flag
+    int64_t max_large = 0;
+
+    // chunks (resident: one chunk covering everything)
+    struct Chunk { int64_t c0, c1, nnz0, nnz1, n_small, n_large, n_items; };
+    Chunk* chunks = nullptr;
+    int64_t n_chunks = 0;
+    bool streaming = false;
+    const int64_t* host_ptr = nullptr;   // streaming: borrowed pinned arrays
+    const int32_t* host_idx = nullptr;
+    const float* host_val = nullptr;
+    uint32_t* buf_idx[2] = {nullptr, nullptr};
+    float* buf_val[2] = {nullptr, nullptr};
+    hipEvent_t ev_copied[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+    bool buf_used[2] = {false, false};
+    int64_t max_chunk_nnz = 0;
+    uint32_t* ybits = nullptr;
+
+    hipStream_t compute = nullptr, copy = nullptr;
+    bool own_compute = false, own_copy = false;
+    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t* ev_copy_pairs = nullptr;
+    // concurrency control and the adaptive safeguard
+    int64_t inflight_nnz = 0;         // current cap on nonzeros in flight (<= 0: no cap)
+    int64_t inflight_floor = 0;       // the cap is never halved below this
+    float damping = 1.0f;
+    bool adaptive = true;
+    float* x_snap = nullptr;          // [m] state before the epoch (adaptive mode)
+    float* v_snap = nullptr;          // [vlen]
+    double monitor_prev = 0.0;        // objective before the epoch (minimised quantity)
+    bool monitor_valid = false;
+    double avg_small_len = 1.0;
+    snap_epoch_stats stats{};
+    bool stats_pending = false;
+    int64_t epochs_done = 0;
+    snap::Reducer red;
+};
+
+namespace snap {
+
+// perm.hip
+int sorter_alloc(Sorter& s, int64_t max_m);
+void sorter_free(Sorter& s);
+// keys_out[c] = key(seed, chunk, c) for c in [0, m); order_out = coordinates sorted by (key, c);
+// part_out = the same order stably partitioned by cls[c0 + c] (class 0 first); either may be null.
+int make_permutation(snap_handle* h, uint64_t seed, uint32_t chunk, int64_t c0, int64_t m,
+                     uint32_t* keys_out, uint32_t* order_out, uint32_t* part_out);
+
+// scd.hip
+int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk& ck, const uint32_t* order);
+
+// linalg.hip
+int compute_norms_and_classes(snap_handle* h);
+int fold_labels(snap_handle* h, uint32_t* idx, int64_t count, hipStream_t s);
+int recompute_shared(snap_handle* h);
+int objective(snap_handle* h, double* primal, double* dual, double* gap);
+// the quantity the solver decreases (P in primal form, -D in dual form), vectors only
+int monitor_value(snap_handle* h, double* value);
+// (sum f)^2 / sum f^2 over the access counts f of the entries of v
+int effective_shared_length(snap_handle* h, double* out);
+int predict(snap_handle* h, const snap_matrix* X, float* out);
+int weights_to_host(snap_handle* h, float* w_out);
+int reducer_alloc(Reducer& r);
+void reducer_free(Reducer& r);
+int fill_zero(void* p, size_t bytes, hipStream_t s);
+
+}  // namespace snap

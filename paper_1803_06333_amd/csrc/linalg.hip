@@ -1,0 +1,632 @@
+// Deterministic helper kernels around the SCD epoch: squared norms of the coordinates, label
+// folding, v = A x (Algorithm 1: the shared vector is A alpha), the objective P(w) (eq. (1) with
+// the 1/n scaling), the duality gap and decision values.  fp32 data, every sum in fp64 and in a
+// fixed order (no atomics on the reduction paths, so repeated calls give identical bits; the
+// only exception is the scatter product for compressed-column data, which uses atomics on v).
+#include "common.h"
+
+namespace snap {
+
+constexpr int LTPB = 256;
+
+__device__ __forceinline__ double wave_sum_d(double x) {
+#pragma unroll
+    for (int off = WAVE / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, WAVE);
+    return x;
+}
+
+// sum over the workgroup, result valid in thread 0 (fixed order)
+__device__ __forceinline__ double block_sum_d(double x, double* scratch /* >= LTPB/WAVE */) {
+    x = wave_sum_d(x);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) scratch[threadIdx.x / WAVE] = x;
+    __syncthreads();
+    double s = 0.0;
+    if (threadIdx.x == 0)
+        for (int w = 0; w < (int)(blockDim.x / WAVE); ++w) s += scratch[w];
+    return s;
+}
+
+__global__ void k_fill_zero(uint32_t* p, size_t words) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+int fill_zero(void* p, size_t bytes, hipStream_t s) {
+    if (bytes == 0) return SNAP_OK;
+    const size_t words = bytes / 4;   // all buffers here are multiples of 4 bytes
+    int grid = (int)((words + 255) / 256 < 8192 ? (words + 255) / 256 : 8192);
+    hipLaunchKernelGGL(k_fill_zero, dim3(grid), dim3(256), 0, s, (uint32_t*)p, words);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+// ---- squared norms and size classes -------------------------------------------------------------
+__global__ void __launch_bounds__(LTPB)
+k_coord_norms(const int64_t* __restrict__ ptr, const float* __restrict__ val, int64_t m, int64_t dense_len,
+              float* __restrict__ norms, uint8_t* __restrict__ cls) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
+    for (int64_t c = wave0; c < m; c += nwaves) {
+        const int64_t s0 = dense_len > 0 ? c * dense_len : ptr[c];
+        const int64_t s1 = dense_len > 0 ? s0 + dense_len : ptr[c + 1];
+        double acc = 0.0;
+        for (int64_t k = s0 + lane; k < s1; k += WAVE) acc += (double)val[k] * (double)val[k];
+        acc = wave_sum_d(acc);
+        if (lane == 0) {
+            norms[c] = (float)acc;
+            cls[c] = (dense_len > 0 || s1 - s0 > SMALL_MAX) ? 1 : 0;
+        }
+    }
+}
+
+int compute_norms_and_classes(snap_handle* h) {
+    // resident data only; a streamed matrix is handled chunk by chunk by the caller
+    const int64_t dense_len = h->dense ? h->ld : 0;
+    int grid = (int)((h->m + 3) / 4 < 16384 ? (h->m + 3) / 4 : 16384);
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(k_coord_norms, dim3(grid), dim3(LTPB), 0, h->compute, h->ptr, h->val, h->m, dense_len,
+                       h->norms, h->cls);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+// Sign of the label folded into bit 31 of the row index (primal logistic regression).
+__global__ void k_fold_labels(uint32_t* __restrict__ idx, int64_t count, const float* __restrict__ y) {
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < count; k += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t r = idx[k] & ~LABEL_BIT;
+        idx[k] = r | (y[r] < 0.0f ? LABEL_BIT : 0u);
+    }
+}
+
+int fold_labels(snap_handle* h, uint32_t* idx, int64_t count, hipStream_t s) {
+    if (count == 0) return SNAP_OK;
+    int grid = (int)((count + 255) / 256 < 16384 ? (count + 255) / 256 : 16384);
+    hipLaunchKernelGGL(k_fold_labels, dim3(grid), dim3(256), 0, s, idx, count, h->y);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+// ---- v = A x -------------------------------------------------------------------------------------
+// compressed data: out[idx[k]] += mult(c) * val[k] for every nonzero k of every coordinate c in
+// [c0, c1); mult(c) = x[c] (primal) or y[c] x[c] (dual).  Each workgroup takes a block of
+// consecutive nonzeros and locates their coordinates by bisection of ptr.
+constexpr int64_t AXPY_BLOCK = 4096;
+
+__global__ void __launch_bounds__(LTPB)
+k_scatter_axpy(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const float* __restrict__ val,
+               int64_t nnz_base, int64_t c0, int64_t c1, int64_t k0, int64_t k1, const float* __restrict__ x,
+               const float* __restrict__ ymul, uint32_t idx_mask, float* out) {
+    const int64_t b0 = k0 + (int64_t)blockIdx.x * AXPY_BLOCK, b1 = min(k1, b0 + AXPY_BLOCK);
+    // coordinate of the block's first nonzero: largest c in [c0, c1) with ptr[c] <= b0
+    int64_t lo = c0, hi = c1;
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr[mid] <= b0) lo = mid; else hi = mid;
+    }
+    const int64_t cstart = lo;
+    for (int64_t k = b0 + threadIdx.x; k < b1; k += LTPB) {
+        int64_t l = cstart, r = c1;                    // largest c >= cstart with ptr[c] <= k
+        // gallop first: most blocks sit inside one or a few coordinates
+        int64_t step = 1;
+        while (l + step < c1 && ptr[l + step] <= k) { l += step; step <<= 1; }
+        r = min(c1, l + step);
+        while (r - l > 1) {
+            const int64_t mid = (l + r) >> 1;
+            if (ptr[mid] <= k) l = mid; else r = mid;
+        }
+        const float mult = ymul ? ymul[l] * x[l] : x[l];
+        if (mult != 0.0f) unsafeAtomicAdd(out + (idx[k - nnz_base] & idx_mask), mult * val[k - nnz_base]);
+    }
+}
+
+// dense, coordinate-major (element e of coordinate c at A[c*len + e]): out[e] = sum_c mult(c) A[c*len+e]
+__global__ void __launch_bounds__(LTPB)
+k_dense_axpy_all(const float* __restrict__ A, int64_t m, int64_t len, const float* __restrict__ x,
+                 const float* __restrict__ ymul, float* __restrict__ out) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= len) return;
+    double acc = 0.0;
+    for (int64_t c = 0; c < m; ++c) {
+        const float mult = ymul ? ymul[c] * x[c] : x[c];
+        acc += (double)mult * (double)A[c * len + e];
+    }
+    out[e] = (float)acc;
+}
+
+int recompute_shared(snap_handle* h) {
+    const float* ymul = h->form == SNAP_DUAL ? h->y : nullptr;
+    if (h->dense) {
+        hipLaunchKernelGGL(k_dense_axpy_all, dim3((unsigned)((h->ld + LTPB - 1) / LTPB)), dim3(LTPB), 0, h->compute,
+                           h->val, h->m, h->ld, h->x, ymul, h->v);
+        SNAP_HIP(hipGetLastError());
+        return SNAP_OK;
+    }
+    if (h->streaming) {
+        set_error("recomputing v is not available for a streamed matrix");
+        return SNAP_EUNSUPPORTED;
+    }
+    SNAP_TRY(fill_zero(h->v, (size_t)h->vlen * sizeof(float), h->compute));
+    if (h->nnz > 0) {
+        const int64_t nb = (h->nnz + AXPY_BLOCK - 1) / AXPY_BLOCK;
+        hipLaunchKernelGGL(k_scatter_axpy, dim3((unsigned)nb), dim3(LTPB), 0, h->compute, h->ptr, h->idx, h->val,
+                           (int64_t)0, (int64_t)0, h->m, (int64_t)0, h->nnz, h->x, ymul, ~LABEL_BIT, h->v);
+        SNAP_HIP(hipGetLastError());
+    }
+    return SNAP_OK;
+}
+
+// ---- per-coordinate dots with v (no update), fp64 ---------------------------------------------------
+// primal: gdot[c] = sum_k a_k loss'(y_r, v_r); dual: gdot[c] = sum_k a_k v_r.
+template <int KIND>
+__device__ __forceinline__ double dot_term(float a, float vv, float yy) {
+    if (KIND == K_PRIMAL_RIDGE) return (double)a * ((double)vv - (double)yy);
+    if (KIND == K_PRIMAL_LOGISTIC) {
+        const double t = (double)yy * (double)vv;            // p = sigmoid(-t), overflow safe
+        const double p = t >= 0 ? exp(-t) / (1.0 + exp(-t)) : 1.0 / (1.0 + exp(t));
+        return -(double)a * (double)yy * p;
+    }
+    return (double)a * (double)vv;
+}
+
+template <int KIND>
+__device__ __forceinline__ double dot_range(const uint32_t* __restrict__ idx, const float* __restrict__ val,
+                                            int64_t s0, int64_t s1, int64_t dense_e0, const float* __restrict__ v,
+                                            const float* __restrict__ y, int first, int stride) {
+    double acc = 0.0;
+    for (int64_t k = s0 + first; k < s1; k += stride) {
+        uint32_t r;
+        float yy = 0.0f;
+        if (idx) {
+            const uint32_t raw = idx[k];
+            if (KIND == K_PRIMAL_LOGISTIC) {
+                r = raw & ~LABEL_BIT;
+                yy = (raw & LABEL_BIT) ? -1.0f : 1.0f;
+            } else {
+                r = raw;
+                if (KIND == K_PRIMAL_RIDGE) yy = y[r];
+            }
+        } else {
+            r = (uint32_t)(dense_e0 + (k - s0));
+            if (KIND != K_DUAL_HINGE) yy = y[r];
+        }
+        acc += dot_term<KIND>(val[k], v[r], yy);
+    }
+    return acc;
+}
+
+// one wavefront per coordinate (all coordinates of class 0 in [c0,c1))
+template <int KIND>
+__global__ void __launch_bounds__(LTPB)
+k_dots_small(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const float* __restrict__ val,
+             int64_t nnz_base, int64_t c0, int64_t c1, const uint8_t* __restrict__ cls, const float* __restrict__ v,
+             const float* __restrict__ y, double* __restrict__ gdot) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
+    for (int64_t c = c0 + wave0; c < c1; c += nwaves) {
+        if (cls[c]) continue;
+        double acc = dot_range<KIND>(idx, val, ptr[c] - nnz_base, ptr[c + 1] - nnz_base, 0, v, y, lane, WAVE);
+        acc = wave_sum_d(acc);
+        if (lane == 0) gdot[c] = acc;
+    }
+}
+
+// class-1 coordinates: one workgroup per segment of SEG elements writes a partial sum; the list
+// (large_list, seg_off) is the static one built at creation
+template <int KIND>
+__global__ void __launch_bounds__(LTPB)
+k_dots_large_partial(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const float* __restrict__ val,
+                     int64_t nnz_base, int64_t dense_len, const int64_t* __restrict__ large_list,
+                     const int64_t* __restrict__ seg_off, int64_t l0, int64_t l1, int64_t seg_base,
+                     const float* __restrict__ v, const float* __restrict__ y, double* __restrict__ partial) {
+    __shared__ double scratch[LTPB / WAVE];
+    const int64_t s = seg_base + blockIdx.x;
+    int64_t lo = l0, hi = l1;
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (seg_off[mid] <= s) lo = mid; else hi = mid;
+    }
+    const int64_t c = large_list[lo];
+    const int64_t seg = s - seg_off[lo];
+    int64_t b0, len;
+    if (dense_len > 0) { b0 = c * dense_len; len = dense_len; }
+    else { b0 = ptr[c] - nnz_base; len = ptr[c + 1] - ptr[c]; }
+    const int64_t e0 = seg * SEG, e1 = min(len, e0 + SEG);
+    double acc = dot_range<KIND>(dense_len > 0 ? nullptr : idx, val, b0 + e0, b0 + e1, e0, v, y, threadIdx.x, LTPB);
+    acc = block_sum_d(acc, scratch);
+    if (threadIdx.x == 0) partial[s] = acc;
+}
+
+__global__ void k_dots_large_finish(const int64_t* __restrict__ large_list, const int64_t* __restrict__ seg_off,
+                                    int64_t l0, int64_t l1, const double* __restrict__ partial,
+                                    double* __restrict__ gdot) {
+    const int64_t l = l0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= l1) return;
+    double acc = 0.0;
+    for (int64_t s = seg_off[l]; s < seg_off[l + 1]; ++s) acc += partial[s];
+    gdot[large_list[l]] = acc;
+}
+
+template <int KIND>
+static int coord_dots_kind(snap_handle* h) {
+    const int64_t dense_len = h->dense ? h->ld : 0;
+    if (!h->dense && h->m > 0) {
+        int grid = (int)((h->m + 3) / 4 < 32768 ? (h->m + 3) / 4 : 32768);
+        hipLaunchKernelGGL((k_dots_small<KIND>), dim3(grid), dim3(LTPB), 0, h->compute, h->ptr, h->idx, h->val,
+                           (int64_t)0, (int64_t)0, h->m, h->cls, h->v, h->y, h->gdot);
+    }
+    if (h->n_large_total > 0) {
+        const int64_t nseg = h->n_seg_total;
+        hipLaunchKernelGGL((k_dots_large_partial<KIND>), dim3((unsigned)nseg), dim3(LTPB), 0, h->compute, h->ptr,
+                           h->idx, h->val, (int64_t)0, dense_len, h->large_list, h->large_seg_off, (int64_t)0,
+                           h->n_large_total, (int64_t)0, h->v, h->y, h->seg_partial);
+        hipLaunchKernelGGL(k_dots_large_finish, dim3((unsigned)((h->n_large_total + 255) / 256)), dim3(256), 0,
+                           h->compute, h->large_list, h->large_seg_off, (int64_t)0, h->n_large_total, h->seg_partial,
+                           h->gdot);
+    }
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+static int coord_dots(snap_handle* h) {
+    if (h->streaming) {
+        set_error("the duality gap is not available for a streamed matrix");
+        return SNAP_EUNSUPPORTED;
+    }
+    switch (h->kind) {
+    case K_PRIMAL_RIDGE: return coord_dots_kind<K_PRIMAL_RIDGE>(h);
+    case K_PRIMAL_LOGISTIC: return coord_dots_kind<K_PRIMAL_LOGISTIC>(h);
+    default: return coord_dots_kind<K_DUAL_HINGE>(h);
+    }
+}
+
+// ---- transform-reduce in fp64, fixed order ----------------------------------------------------------
+enum ReduceMode {
+    R_LOSS_RIDGE = 0,    // a = v, b = y      : 0.5 (v-y)^2
+    R_LOSS_LOGISTIC = 1, // a = v, b = y      : log(1+exp(-y v))
+    R_SQNORM = 2,        // a = x             : x^2
+    R_SUM = 3,           // a = x             : x
+    R_GRADSQ = 4,        // d = gdot, a = x   : (gdot*s0 + s1*x)^2
+    R_HINGE = 5          // d = gdot, b = y   : max(0, 1 - y gdot s0)
+};
+
+struct ReduceArgs {
+    const float* a;
+    const float* b;
+    const double* d;
+    double s0, s1;
+    int64_t count;
+};
+
+template <int MODE>
+__device__ __forceinline__ double reduce_term(const ReduceArgs& r, int64_t i) {
+    if (MODE == R_LOSS_RIDGE) {
+        const double t = (double)r.a[i] - (double)r.b[i];
+        return 0.5 * t * t;
+    }
+    if (MODE == R_LOSS_LOGISTIC) {
+        const double t = -(double)r.b[i] * (double)r.a[i];
+        return t > 0 ? t + log1p(exp(-t)) : log1p(exp(t));
+    }
+    if (MODE == R_SQNORM) return (double)r.a[i] * (double)r.a[i];
+    if (MODE == R_SUM) return (double)r.a[i];
+    if (MODE == R_GRADSQ) {
+        const double t = r.d[i] * r.s0 + r.s1 * (double)r.a[i];
+        return t * t;
+    }
+    const double t = 1.0 - (double)r.b[i] * r.d[i] * r.s0;
+    return t > 0 ? t : 0.0;
+}
+
+template <int MODE>
+__global__ void __launch_bounds__(LTPB) k_reduce_partial(ReduceArgs r, double* __restrict__ partial) {
+    __shared__ double scratch[LTPB / WAVE];
+    // contiguous slice per workgroup, strided inside it: the order of the additions is fixed
+    const int64_t per = (r.count + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = min(r.count, (int64_t)blockIdx.x * per), hi = min(r.count, lo + per);
+    double acc = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += LTPB) acc += reduce_term<MODE>(r, i);
+    acc = block_sum_d(acc, scratch);
+    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+}
+
+__global__ void __launch_bounds__(LTPB) k_reduce_final(const double* __restrict__ partial, int count,
+                                                        double* __restrict__ out) {
+    __shared__ double scratch[LTPB / WAVE];
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < count; i += LTPB) acc += partial[i];
+    acc = block_sum_d(acc, scratch);
+    if (threadIdx.x == 0) *out = acc;
+}
+
+static int reduce_to(snap_handle* h, int mode, const ReduceArgs& r, int slot) {
+    double* partial = h->red.partial;
+    double* out = h->red.result + slot;
+    const dim3 g(REDUCE_BLOCKS), b(LTPB);
+    switch (mode) {
+    case R_LOSS_RIDGE: hipLaunchKernelGGL((k_reduce_partial<R_LOSS_RIDGE>), g, b, 0, h->compute, r, partial); break;
+    case R_LOSS_LOGISTIC: hipLaunchKernelGGL((k_reduce_partial<R_LOSS_LOGISTIC>), g, b, 0, h->compute, r, partial); break;
+    case R_SQNORM: hipLaunchKernelGGL((k_reduce_partial<R_SQNORM>), g, b, 0, h->compute, r, partial); break;
+    case R_SUM: hipLaunchKernelGGL((k_reduce_partial<R_SUM>), g, b, 0, h->compute, r, partial); break;
+    case R_GRADSQ: hipLaunchKernelGGL((k_reduce_partial<R_GRADSQ>), g, b, 0, h->compute, r, partial); break;
+    default: hipLaunchKernelGGL((k_reduce_partial<R_HINGE>), g, b, 0, h->compute, r, partial); break;
+    }
+    hipLaunchKernelGGL(k_reduce_final, dim3(1), b, 0, h->compute, partial, REDUCE_BLOCKS, out);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+int reducer_alloc(Reducer& r) {
+    SNAP_HIP(hipMalloc(&r.partial, 2 * REDUCE_BLOCKS * sizeof(double)));
+    SNAP_HIP(hipMalloc(&r.result, 8 * sizeof(double)));
+    SNAP_HIP(hipHostMalloc(&r.host, 8 * sizeof(double)));
+    return SNAP_OK;
+}
+
+void reducer_free(Reducer& r) {
+    (void)hipFree(r.partial);
+    (void)hipFree(r.result);
+    (void)hipHostFree(r.host);
+    r = Reducer{};
+}
+
+__global__ void k_scale(const float* __restrict__ in, float s, float* __restrict__ out, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = in[i] * s;
+}
+
+// P, D and the gap.  Any of the outputs may be null; the gap (and D in primal form) needs one pass
+// over the matrix, P in primal form only the vectors.
+int objective(snap_handle* h, double* primal, double* dual, double* gap) {
+    const double n = (double)h->n, lam = h->lambda;
+    double* res = h->red.host;
+    if (h->form == SNAP_PRIMAL) {
+        const bool need_gap = gap != nullptr || dual != nullptr;
+        ReduceArgs r{h->v, h->y, nullptr, 0.0, 0.0, h->n};
+        SNAP_TRY(reduce_to(h, h->loss == SNAP_RIDGE ? R_LOSS_RIDGE : R_LOSS_LOGISTIC, r, 0));
+        ReduceArgs rx{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
+        SNAP_TRY(reduce_to(h, R_SQNORM, rx, 1));
+        if (need_gap) {
+            SNAP_TRY(coord_dots(h));
+            ReduceArgs rg{h->x, nullptr, h->gdot, 1.0 / n, lam, h->m};
+            SNAP_TRY(reduce_to(h, R_GRADSQ, rg, 2));
+        }
+        SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
+        SNAP_HIP(hipStreamSynchronize(h->compute));
+        const double P = res[0] / n + 0.5 * lam * res[1];
+        const double G = need_gap ? res[2] / (2.0 * lam) : 0.0;
+        if (primal) *primal = P;
+        if (gap) *gap = G;
+        if (dual) *dual = P - G;
+        return SNAP_OK;
+    }
+    // hinge, dual form: w = v/(lambda n); margins y_i x_i.w from the row dots with v
+    SNAP_TRY(coord_dots(h));
+    ReduceArgs rh{nullptr, h->y, h->gdot, 1.0 / (lam * n), 0.0, h->m};
+    SNAP_TRY(reduce_to(h, R_HINGE, rh, 0));
+    ReduceArgs ra{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
+    SNAP_TRY(reduce_to(h, R_SUM, ra, 1));
+    ReduceArgs rv{h->v, nullptr, nullptr, 0.0, 0.0, h->vlen};
+    SNAP_TRY(reduce_to(h, R_SQNORM, rv, 2));
+    SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    const double ww = res[2] / (lam * n * lam * n);
+    const double P = res[0] / n + 0.5 * lam * ww;
+    const double D = res[1] / n - 0.5 * lam * ww;
+    if (primal) *primal = P;
+    if (dual) *dual = D;
+    if (gap) *gap = P - D;
+    return SNAP_OK;
+}
+
+int monitor_value(snap_handle* h, double* value) {
+    const double n = (double)h->n, lam = h->lambda;
+    double* res = h->red.host;
+    if (h->form == SNAP_PRIMAL) {
+        ReduceArgs r{h->v, h->y, nullptr, 0.0, 0.0, h->n};
+        SNAP_TRY(reduce_to(h, h->loss == SNAP_RIDGE ? R_LOSS_RIDGE : R_LOSS_LOGISTIC, r, 0));
+        ReduceArgs rx{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
+        SNAP_TRY(reduce_to(h, R_SQNORM, rx, 1));
+    } else {
+        ReduceArgs ra{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
+        SNAP_TRY(reduce_to(h, R_SUM, ra, 0));
+        ReduceArgs rv{h->v, nullptr, nullptr, 0.0, 0.0, h->vlen};
+        SNAP_TRY(reduce_to(h, R_SQNORM, rv, 1));
+    }
+    SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    if (h->form == SNAP_PRIMAL) *value = res[0] / n + 0.5 * lam * res[1];
+    else *value = -(res[0] / n - 0.5 * res[1] / (lam * n * n));     // -D(alpha)
+    return SNAP_OK;
+}
+
+// ---- effective length of v ------------------------------------------------------------------------
+__global__ void k_count_accesses(const uint32_t* __restrict__ idx, int64_t count, uint32_t* __restrict__ freq) {
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < count; k += (int64_t)gridDim.x * blockDim.x)
+        atomicAdd(freq + (idx[k] & ~LABEL_BIT), 1u);
+}
+
+__global__ void __launch_bounds__(LTPB)
+k_freq_moments(const uint32_t* __restrict__ freq, int64_t count, double* __restrict__ partial) {
+    __shared__ double scratch[LTPB / WAVE];
+    const int64_t per = (count + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = min(count, (int64_t)blockIdx.x * per), hi = min(count, lo + per);
+    double s1 = 0.0, s2 = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += LTPB) {
+        const double f = (double)freq[i];
+        s1 += f;
+        s2 += f * f;
+    }
+    s1 = block_sum_d(s1, scratch);
+    s2 = block_sum_d(s2, scratch);
+    if (threadIdx.x == 0) {
+        partial[blockIdx.x] = s1;
+        partial[REDUCE_BLOCKS + blockIdx.x] = s2;
+    }
+}
+
+// How many entries of v the accesses are effectively spread over: (sum f)^2 / sum f^2 with f the
+// number of nonzeros that touch each entry.  Uniform access gives the length of v; a few hot
+// entries (popular columns in the dual form) give a much smaller number.
+int effective_shared_length(snap_handle* h, double* out) {
+    if (h->dense || h->nnz == 0 || h->vlen == 0) {
+        *out = (double)h->vlen;
+        return SNAP_OK;
+    }
+    uint32_t* freq = nullptr;
+    SNAP_HIP(hipMalloc(&freq, (size_t)h->vlen * sizeof(uint32_t)));
+    int rc = fill_zero(freq, (size_t)h->vlen * sizeof(uint32_t), h->compute);
+    if (rc == SNAP_OK) {
+        hipLaunchKernelGGL(k_count_accesses, dim3(8192), dim3(256), 0, h->compute, h->idx, h->nnz, freq);
+        hipLaunchKernelGGL(k_freq_moments, dim3(REDUCE_BLOCKS), dim3(LTPB), 0, h->compute, freq, h->vlen, h->red.partial);
+        hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial, REDUCE_BLOCKS, h->red.result);
+        hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial + REDUCE_BLOCKS,
+                           REDUCE_BLOCKS, h->red.result + 1);
+        hipError_t e = hipMemcpyAsync(h->red.host, h->red.result, 2 * sizeof(double), hipMemcpyDeviceToHost, h->compute);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->compute);
+        if (e != hipSuccess) rc = hip_fail(e, "effective_shared_length", __FILE__, __LINE__);
+    }
+    (void)hipFree(freq);
+    if (rc != SNAP_OK) return rc;
+    const double s1 = h->red.host[0], s2 = h->red.host[1];
+    *out = s2 > 0.0 ? s1 * s1 / s2 : (double)h->vlen;
+    return SNAP_OK;
+}
+
+// ---- decision values -------------------------------------------------------------------------------
+__global__ void __launch_bounds__(LTPB)
+k_csr_rowdot(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx, const float* __restrict__ val,
+             int64_t rows, const float* __restrict__ w, float* __restrict__ out) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
+    for (int64_t i = wave0; i < rows; i += nwaves) {
+        double acc = 0.0;
+        for (int64_t k = ptr[i] + lane; k < ptr[i + 1]; k += WAVE) acc += (double)val[k] * (double)w[idx[k]];
+        acc = wave_sum_d(acc);
+        if (lane == 0) out[i] = (float)acc;
+    }
+}
+
+// dense: out[i] = sum_j X(i,j) w[j]; element (i,j) at X[i*rs + j*cs]
+__global__ void __launch_bounds__(LTPB)
+k_dense_rowdot(const float* __restrict__ X, int64_t rows, int64_t cols, int64_t rs, int64_t cs,
+               const float* __restrict__ w, float* __restrict__ out) {
+    if (cs == 1) {      // row-major: one wavefront per row
+        const int lane = threadIdx.x & (WAVE - 1);
+        const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+        const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
+        for (int64_t i = wave0; i < rows; i += nwaves) {
+            double acc = 0.0;
+            for (int64_t j = lane; j < cols; j += WAVE) acc += (double)X[i * rs + j] * (double)w[j];
+            acc = wave_sum_d(acc);
+            if (lane == 0) out[i] = (float)acc;
+        }
+    } else {            // column-major: one thread per row, coalesced over rows
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < rows;
+             i += (int64_t)gridDim.x * blockDim.x) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < cols; ++j) acc += (double)X[i + j * cs] * (double)w[j];
+            out[i] = (float)acc;
+        }
+    }
+}
+
+static int model_weights(snap_handle* h, const float** w) {
+    if (h->form == SNAP_PRIMAL) {
+        *w = h->x;
+        return SNAP_OK;
+    }
+    int grid = (int)((h->d + 255) / 256 < 4096 ? (h->d + 255) / 256 : 4096);
+    hipLaunchKernelGGL(k_scale, dim3(grid), dim3(256), 0, h->compute, h->v, (float)(1.0 / (h->lambda * (double)h->n)),
+                       h->w_tmp, h->d);
+    SNAP_HIP(hipGetLastError());
+    *w = h->w_tmp;
+    return SNAP_OK;
+}
+
+int weights_to_host(snap_handle* h, float* w_out) {
+    const float* w;
+    SNAP_TRY(model_weights(h, &w));
+    SNAP_HIP(hipMemcpyAsync(w_out, w, (size_t)h->d * sizeof(float), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    return SNAP_OK;
+}
+
+int predict(snap_handle* h, const snap_matrix* X, float* out) {
+    const float* w;
+    SNAP_TRY(model_weights(h, &w));
+    const bool on_dev = X->mem == SNAP_MEM_DEVICE;
+    const int64_t rows = X->n_rows, cols = X->n_cols;
+    int64_t* dptr = nullptr;
+    int32_t* didx = nullptr;
+    float* dval = nullptr;
+    float* dout = nullptr;
+    int rc = SNAP_OK;
+    const bool sparse = X->layout == SNAP_CSR || X->layout == SNAP_CSC;
+    const int64_t major = X->layout == SNAP_CSR ? rows : cols;
+    const int64_t count = sparse ? X->nnz : rows * cols;
+    auto cleanup = [&]() {
+        if (!on_dev) {
+            (void)hipFree(dptr);
+            (void)hipFree(didx);
+            (void)hipFree(dval);
+            (void)hipFree(dout);
+        }
+    };
+#define PRED_HIP(call)                                              \
+    do {                                                            \
+        hipError_t e_ = (call);                                     \
+        if (e_ != hipSuccess) {                                     \
+            rc = hip_fail(e_, #call, __FILE__, __LINE__);           \
+            cleanup();                                              \
+            return rc;                                              \
+        }                                                           \
+    } while (0)
+    if (on_dev) {
+        dptr = const_cast<int64_t*>(X->ptr);
+        didx = const_cast<int32_t*>(X->idx);
+        dval = const_cast<float*>(X->val);
+        dout = out;
+    } else {
+        if (sparse) {
+            PRED_HIP(hipMalloc(&dptr, (size_t)(major + 1) * sizeof(int64_t)));
+            PRED_HIP(hipMalloc(&didx, (size_t)(count ? count : 1) * sizeof(int32_t)));
+            PRED_HIP(hipMemcpyAsync(dptr, X->ptr, (size_t)(major + 1) * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
+            PRED_HIP(hipMemcpyAsync(didx, X->idx, (size_t)count * sizeof(int32_t), hipMemcpyHostToDevice, h->compute));
+        }
+        PRED_HIP(hipMalloc(&dval, (size_t)(count ? count : 1) * sizeof(float)));
+        PRED_HIP(hipMemcpyAsync(dval, X->val, (size_t)count * sizeof(float), hipMemcpyHostToDevice, h->compute));
+        PRED_HIP(hipMalloc(&dout, (size_t)(rows ? rows : 1) * sizeof(float)));
+    }
+    if (rows > 0) {
+        int grid = (int)((rows + 3) / 4 < 32768 ? (rows + 3) / 4 : 32768);
+        if (X->layout == SNAP_CSR) {
+            hipLaunchKernelGGL(k_csr_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+        } else if (X->layout == SNAP_CSC) {
+            rc = fill_zero(dout, (size_t)rows * sizeof(float), h->compute);
+            if (rc == SNAP_OK && count > 0) {
+                const int64_t nb = (count + AXPY_BLOCK - 1) / AXPY_BLOCK;
+                hipLaunchKernelGGL(k_scatter_axpy, dim3((unsigned)nb), dim3(LTPB), 0, h->compute, dptr,
+                                   (const uint32_t*)didx, dval, (int64_t)0, (int64_t)0, cols, (int64_t)0, count, w,
+                                   (const float*)nullptr, 0xFFFFFFFFu, dout);
+            }
+        } else if (X->layout == SNAP_DENSE_ROWMAJOR) {
+            hipLaunchKernelGGL(k_dense_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dval, rows, cols, cols, (int64_t)1,
+                               w, dout);
+        } else {
+            hipLaunchKernelGGL(k_dense_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dval, rows, cols, (int64_t)1, rows,
+                               w, dout);
+        }
+        PRED_HIP(hipGetLastError());
+    }
+    if (!on_dev) PRED_HIP(hipMemcpyAsync(out, dout, (size_t)rows * sizeof(float), hipMemcpyDeviceToHost, h->compute));
+    PRED_HIP(hipStreamSynchronize(h->compute));
+    cleanup();
+#undef PRED_HIP
+    return rc;
+}
+
+}  // namespace snap

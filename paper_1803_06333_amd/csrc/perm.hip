@@ -1,0 +1,209 @@
+// Epoch order (Section 3.2, "Streaming Permutation Generation"): one 32-bit xorshift key per
+// coordinate, then a sort of the keys that carries the coordinate indices.  The paper makes the
+// keys on host threads and sorts them with a library radix sort; here the key is a counter-based
+// function of (seed, chunk, coordinate), so it is produced directly on the device, and the sort is
+// a least-significant-digit radix sort written for 64-wide wavefronts.  Equal keys keep the order
+// of their indices (every pass is stable and the input is index-ascending), which makes the result
+// unique and bit-comparable with any other correct sort.
+#include "common.h"
+
+namespace snap {
+
+constexpr int RADIX_BITS = 8;
+constexpr int RADIX = 1 << RADIX_BITS;
+constexpr int SORT_TPB = 256;
+constexpr int SORT_ROUNDS = 8;                                   // 64-element rounds per wavefront
+constexpr int SORT_TILE = SORT_TPB * SORT_ROUNDS;                // 2048 elements per workgroup
+constexpr int SORT_WAVES = SORT_TPB / WAVE;
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// 64-bit integer mix of (seed, chunk, c) folded to a non-zero 32-bit state, then four rounds of
+// the (13,17,5) xorshift.
+__device__ __forceinline__ uint32_t perm_key(uint64_t seed_chunk_mix, uint32_t c) {
+    uint64_t z = mix64(seed_chunk_mix + (uint64_t)c * 0x9E3779B97F4A7C15ull);
+    uint32_t x = (uint32_t)(z ^ (z >> 32));
+    if (x == 0u) x = 0x6C078965u;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        x ^= x << 13;
+        x ^= x >> 17;
+        x ^= x << 5;
+    }
+    return x;
+}
+
+__global__ void k_make_keys(uint64_t seed, uint32_t chunk, uint32_t m, uint32_t* __restrict__ keys,
+                            uint32_t* __restrict__ vals, uint32_t* __restrict__ keys_copy) {
+    const uint64_t base = mix64(seed ^ mix64((uint64_t)chunk + 0x632BE59BD9B4E019ull));
+    for (uint32_t c = blockIdx.x * blockDim.x + threadIdx.x; c < m; c += gridDim.x * blockDim.x) {
+        uint32_t k = perm_key(base, c);
+        keys[c] = k;
+        vals[c] = c;
+        if (keys_copy) keys_copy[c] = k;
+    }
+}
+
+// digit of element i: bits [shift, shift+8) of its key, or (cls != null) the class of its value
+__device__ __forceinline__ uint32_t digit_of(uint32_t key, uint32_t val, int shift, const uint8_t* cls) {
+    return cls ? (uint32_t)cls[val] : ((key >> shift) & (RADIX - 1));
+}
+
+// block_hist[digit * n_blocks + block] = number of elements of that digit in the block's tile
+__global__ void __launch_bounds__(SORT_TPB)
+k_radix_hist(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, uint32_t m, int shift,
+             const uint8_t* __restrict__ cls, uint32_t* __restrict__ block_hist, uint32_t n_blocks) {
+    __shared__ uint32_t hist[RADIX];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t base = blockIdx.x * SORT_TILE;
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        uint32_t i = base + r * SORT_TPB + threadIdx.x;
+        if (i < m) atomicAdd(&hist[digit_of(keys[i], vals[i], shift, cls)], 1u);
+    }
+    __syncthreads();
+    block_hist[(size_t)threadIdx.x * n_blocks + blockIdx.x] = hist[threadIdx.x];
+}
+
+// exclusive prefix sum over `count` entries, in place, one workgroup of 1024 threads
+__global__ void __launch_bounds__(1024) k_exclusive_scan(uint32_t* __restrict__ a, uint32_t count) {
+    __shared__ uint32_t part[1024];
+    const uint32_t per = (count + 1023u) / 1024u;
+    const uint32_t lo = min(count, threadIdx.x * per), hi = min(count, lo + per);
+    uint32_t s = 0;
+    for (uint32_t i = lo; i < hi; ++i) s += a[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        uint32_t t = threadIdx.x >= off ? part[threadIdx.x - off] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += t;
+        __syncthreads();
+    }
+    uint32_t run = part[threadIdx.x] - s;   // exclusive prefix of this thread's range
+    for (uint32_t i = lo; i < hi; ++i) {
+        uint32_t t = a[i];
+        a[i] = run;
+        run += t;
+    }
+}
+
+// Stable scatter of one digit pass.  Wavefront w of the workgroup owns SORT_ROUNDS consecutive
+// groups of 64 elements; inside a group the rank among equal digits comes from ballots, across
+// groups from a per-wavefront running count in LDS, across wavefronts from a small prefix sum.
+__global__ void __launch_bounds__(SORT_TPB)
+k_radix_scatter(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals,
+                uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, uint32_t m, int shift,
+                const uint8_t* __restrict__ cls, const uint32_t* __restrict__ block_off, uint32_t n_blocks) {
+    __shared__ uint32_t cnt[SORT_WAVES][RADIX];
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_TPB) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    const uint32_t base = blockIdx.x * SORT_TILE + w * (SORT_ROUNDS * WAVE);
+    uint32_t key[SORT_ROUNDS], val[SORT_ROUNDS], dig[SORT_ROUNDS], rank[SORT_ROUNDS];
+    const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const uint32_t i = base + r * WAVE + lane;
+        const bool live = i < m;
+        key[r] = live ? keys[i] : 0u;
+        val[r] = live ? vals[i] : 0u;
+        dig[r] = live ? digit_of(key[r], val[r], shift, cls) : 0u;
+        uint64_t peers = __ballot(live);
+#pragma unroll
+        for (int b = 0; b < RADIX_BITS; ++b) {
+            const bool bit = (dig[r] >> b) & 1u;
+            const uint64_t bal = __ballot(bit && live);
+            peers &= bit ? bal : ~bal;
+        }
+        if (!live) peers = 0;
+        const uint32_t before = cnt[w][dig[r]];                 // all lanes read before any lane writes
+        rank[r] = before + (uint32_t)__popcll(peers & lt);
+        if (live && (peers & lt) == 0) cnt[w][dig[r]] = before + (uint32_t)__popcll(peers);
+    }
+    __syncthreads();
+    // exclusive prefix over the wavefronts, per digit; thread t handles digit t
+    {
+        uint32_t run = block_off[(size_t)threadIdx.x * n_blocks + blockIdx.x];
+#pragma unroll
+        for (int ww = 0; ww < SORT_WAVES; ++ww) {
+            uint32_t c = cnt[ww][threadIdx.x];
+            cnt[ww][threadIdx.x] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const uint32_t i = base + r * WAVE + lane;
+        if (i < m) {
+            const uint32_t pos = cnt[w][dig[r]] + rank[r];
+            keys_out[pos] = key[r];
+            vals_out[pos] = val[r];
+        }
+    }
+}
+
+int sorter_alloc(Sorter& s, int64_t max_m) {
+    s.max_m = max_m > 0 ? max_m : 1;
+    s.n_blocks = (s.max_m + SORT_TILE - 1) / SORT_TILE;
+    size_t bytes = (size_t)s.max_m * sizeof(uint32_t);
+    SNAP_HIP(hipMalloc(&s.keys_a, bytes));
+    SNAP_HIP(hipMalloc(&s.keys_b, bytes));
+    SNAP_HIP(hipMalloc(&s.vals_a, bytes));
+    SNAP_HIP(hipMalloc(&s.vals_b, bytes));
+    SNAP_HIP(hipMalloc(&s.block_hist, (size_t)s.n_blocks * RADIX * sizeof(uint32_t)));
+    return SNAP_OK;
+}
+
+void sorter_free(Sorter& s) {
+    (void)hipFree(s.keys_a);
+    (void)hipFree(s.keys_b);
+    (void)hipFree(s.vals_a);
+    (void)hipFree(s.vals_b);
+    (void)hipFree(s.block_hist);
+    s = Sorter{};
+}
+
+static int radix_pass(snap_handle* h, uint32_t*& ka, uint32_t*& va, uint32_t*& kb, uint32_t*& vb, uint32_t m,
+                      int shift, const uint8_t* cls) {
+    Sorter& s = h->sorter;
+    const uint32_t nb = (m + SORT_TILE - 1) / SORT_TILE;
+    hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(SORT_TPB), 0, h->compute, ka, va, m, shift, cls, s.block_hist, nb);
+    hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, h->compute, s.block_hist, nb * RADIX);
+    hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(SORT_TPB), 0, h->compute, ka, va, kb, vb, m, shift, cls,
+                       s.block_hist, nb);
+    uint32_t* t = ka; ka = kb; kb = t;
+    t = va; va = vb; vb = t;
+    return SNAP_OK;
+}
+
+int make_permutation(snap_handle* h, uint64_t seed, uint32_t chunk, int64_t c0, int64_t m, uint32_t* keys_out,
+                     uint32_t* order_out, uint32_t* part_out) {
+    if (m <= 0) return SNAP_OK;
+    Sorter& s = h->sorter;
+    if (m > s.max_m || m > 0xFFFFFFFFll) {
+        set_error("permutation of %lld coordinates exceeds the sorter capacity", (long long)m);
+        return SNAP_EINVAL;
+    }
+    uint32_t *ka = s.keys_a, *va = s.vals_a, *kb = s.keys_b, *vb = s.vals_b;
+    const uint32_t mm = (uint32_t)m;
+    const int grid = (int)((m + 255) / 256 < 4096 ? (m + 255) / 256 : 4096);
+    hipLaunchKernelGGL(k_make_keys, dim3(grid), dim3(256), 0, h->compute, seed, chunk, mm, ka, va, keys_out);
+    for (int shift = 0; shift < 32; shift += RADIX_BITS) SNAP_TRY(radix_pass(h, ka, va, kb, vb, mm, shift, nullptr));
+    if (order_out)
+        SNAP_HIP(hipMemcpyAsync(order_out, va, (size_t)m * sizeof(uint32_t), hipMemcpyDeviceToDevice, h->compute));
+    if (part_out) {
+        SNAP_TRY(radix_pass(h, ka, va, kb, vb, mm, 0, h->cls + c0));
+        SNAP_HIP(hipMemcpyAsync(part_out, va, (size_t)m * sizeof(uint32_t), hipMemcpyDeviceToDevice, h->compute));
+    }
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+}  // namespace snap

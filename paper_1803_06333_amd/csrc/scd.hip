@@ -1,0 +1,347 @@
+// The SCD epoch kernels (Section 3.1): per coordinate a gather-dot of its nonzeros with the shared
+// vector v, a scalar step (closed form for ridge and for the clipped hinge dual, one Newton step
+// for logistic regression), and an atomic scatter of delta * a_j into v.  Many coordinates are in
+// flight at once and see each other's partial updates, as in the paper's asynchronous solver.
+//
+// The paper's solver gives every coordinate one thread block.  On a 256-CU part with click-log
+// data (a few columns holding a fifth of all rows each, a million columns of a few hundred) that
+// leaves the epoch waiting for a handful of blocks, so coordinates are handled in two classes:
+//   small  (<= SMALL_MAX nonzeros): one 64-wide wavefront per coordinate, four per workgroup;
+//   large  (>  SMALL_MAX nonzeros): split into segments of SEG nonzeros.  Every segment is two
+//          work items, "dot" and "scatter".  Workgroups draw items from one atomic ticket counter
+//          in epoch order; the dot items of a coordinate add their partial sums into its state and
+//          the last one to arrive takes the step and publishes delta; a scatter item waits for
+//          that flag.  A waiting workgroup only ever waits for workgroups that drew an earlier
+//          ticket and are therefore already running, so the wait always ends; it is bounded by
+//          SPIN_LIMIT all the same and raises the handle's status word instead of hanging.
+#include "common.h"
+#include <algorithm>
+
+namespace snap {
+
+struct StepParams {
+    double lambda;
+    double inv_n;     // 1/n
+    double lam_n;     // lambda * n
+    double damping;   // in (0,1]: the step is scaled by it (Section 3.1, adaptive damping)
+};
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int off = WAVE / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, WAVE);
+    return x;
+}
+
+__device__ __forceinline__ float load_shared(const float* v, uint32_t r) {
+    // relaxed device-scope load: sees the other compute dies' atomic updates of v
+    return __hip_atomic_load(v + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Contribution of one nonzero (value a, shared entry vv, label yy) to the two sums of the step.
+template <int KIND>
+__device__ __forceinline__ void accumulate(float a, float vv, float yy, float& g, float& h) {
+    if (KIND == K_PRIMAL_RIDGE) {
+        g += a * (vv - yy);                       // loss' = v - y ; loss'' = 1 (h comes from the norm)
+    } else if (KIND == K_PRIMAL_LOGISTIC) {
+        const float e = __expf(yy * vv);          // p = sigmoid(-y v) = 1/(1+e)
+        const float p = 1.0f / (1.0f + e);
+        g -= a * yy * p;                          // loss'  = -y p
+        h += a * a * (p - p * p);                 // loss'' = p (1 - p)
+    } else {
+        g += a * vv;                              // x_i . v
+    }
+}
+
+// The scalar step.  Returns the new value of the coordinate; `mult` receives the multiplier of a_j
+// that is added to v: the change actually applied to the fp32 coordinate (times y_i in the hinge
+// dual), so that v keeps tracking A x as closely as fp32 allows.
+template <int KIND>
+__device__ __forceinline__ float take_step(double g, double h, float xc, float norm, float yc,
+                                           const StepParams& sp, float& mult) {
+    float xn;
+    if (KIND == K_PRIMAL_RIDGE || KIND == K_PRIMAL_LOGISTIC) {
+        const double G = g * sp.inv_n + sp.lambda * (double)xc;
+        const double H = (KIND == K_PRIMAL_RIDGE ? (double)norm : h) * sp.inv_n + sp.lambda;
+        xn = (float)((double)xc - sp.damping * G / H);
+        mult = (float)((double)xn - (double)xc);
+    } else {
+        double anew;
+        if (norm == 0.0f) {
+            anew = 1.0;                                   // empty row: dD/dalpha = 1/n > 0
+        } else {
+            const double m = (double)yc * g / sp.lam_n;   // y_i x_i.w
+            const double q = (double)norm / sp.lam_n;
+            anew = (double)xc + (1.0 - m) / q;
+            anew = anew < 0.0 ? 0.0 : (anew > 1.0 ? 1.0 : anew);
+        }
+        anew = (double)xc + sp.damping * (anew - (double)xc);   // stays inside the box
+        xn = (float)anew;
+        mult = (float)(((double)xn - (double)xc) * (double)yc);
+    }
+    return xn;
+}
+
+template <int KIND>
+__device__ __forceinline__ void decode(uint32_t raw, uint32_t& r, float& yy, const float* __restrict__ y) {
+    if (KIND == K_PRIMAL_LOGISTIC) {
+        r = raw & ~LABEL_BIT;
+        yy = (raw & LABEL_BIT) ? -1.0f : 1.0f;
+    } else if (KIND == K_PRIMAL_RIDGE) {
+        r = raw;
+        yy = y[r];
+    } else {
+        r = raw;
+        yy = 0.0f;
+    }
+}
+
+// ---- small coordinates: one wavefront each ----------------------------------------------------
+template <int KIND>
+__global__ void __launch_bounds__(TPB)
+k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, const float* __restrict__ y,
+            float* __restrict__ x, float* v, const float* __restrict__ norms, StepParams sp, int64_t n_waves) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t wave0 = ((int64_t)blockIdx.x * TPB + threadIdx.x) / WAVE;
+    if (wave0 >= n_waves) return;
+    // n_waves wavefronts walk the epoch order round-robin: at most n_waves coordinates in flight
+    for (int64_t wid = wave0; wid < n_small; wid += n_waves) {
+        const int64_t c = cv.c0 + (int64_t)order[wid];
+        const int64_t s0 = cv.ptr[c] - cv.nnz_base, s1 = cv.ptr[c + 1] - cv.nnz_base;
+        float g = 0.0f, h = 0.0f;
+        // the first nonzero of every lane stays in registers for the scatter pass
+        uint32_t r0 = 0;
+        float a0 = 0.0f;
+        const bool have0 = s0 + lane < s1;
+        if (have0) {
+            float yy;
+            decode<KIND>(cv.idx[s0 + lane], r0, yy, y);
+            a0 = cv.val[s0 + lane];
+            accumulate<KIND>(a0, load_shared(v, r0), yy, g, h);
+        }
+        for (int64_t k = s0 + WAVE + lane; k < s1; k += WAVE) {
+            uint32_t r;
+            float yy;
+            decode<KIND>(cv.idx[k], r, yy, y);
+            accumulate<KIND>(cv.val[k], load_shared(v, r), yy, g, h);
+        }
+        g = wave_sum(g);
+        if (KIND == K_PRIMAL_LOGISTIC) h = wave_sum(h);
+        float mult = 0.0f;
+        if (lane == 0) {
+            const float xc = x[c];
+            const float yc = KIND == K_DUAL_HINGE ? y[c] : 0.0f;
+            x[c] = take_step<KIND>((double)g, (double)h, xc, norms[c], yc, sp, mult);
+        }
+        mult = __shfl(mult, 0, WAVE);
+        if (mult == 0.0f) continue;
+        if (have0) unsafeAtomicAdd(v + r0, mult * a0);
+        for (int64_t k = s0 + WAVE + lane; k < s1; k += WAVE) {
+            const uint32_t r = cv.idx[k] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu);
+            unsafeAtomicAdd(v + r, mult * cv.val[k]);
+        }
+    }
+}
+
+// ---- large coordinates: segments, two phases, ticket order -------------------------------------
+__device__ __forceinline__ int64_t items_of(int64_t len) { return 2 * ((len + SEG - 1) / SEG); }
+
+// One workgroup: prefix sums of the items of the large coordinates in epoch order, zeroed state,
+// ticket counter back to zero.
+__global__ void __launch_bounds__(1024)
+k_large_prepare(const int64_t* __restrict__ ptr, int64_t c0, const uint32_t* __restrict__ order_large,
+                int64_t n_large, int64_t dense_len, int64_t* __restrict__ item_start, LargeState* __restrict__ st,
+                uint32_t* __restrict__ ticket) {
+    __shared__ int64_t part[1024];
+    const int64_t per = (n_large + 1023) / 1024;
+    const int64_t lo = min(n_large, (int64_t)threadIdx.x * per), hi = min(n_large, lo + per);
+    int64_t s = 0;
+    for (int64_t k = lo; k < hi; ++k) {
+        const int64_t c = c0 + (int64_t)order_large[k];
+        s += items_of(dense_len > 0 ? dense_len : ptr[c + 1] - ptr[c]);
+        st[k] = LargeState{0.0, 0.0, 0.0f, 0u, 0u, 0u};
+    }
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        int64_t t = threadIdx.x >= off ? part[threadIdx.x - off] : 0;
+        __syncthreads();
+        part[threadIdx.x] += t;
+        __syncthreads();
+    }
+    int64_t run = part[threadIdx.x] - s;
+    for (int64_t k = lo; k < hi; ++k) {
+        const int64_t c = c0 + (int64_t)order_large[k];
+        item_start[k] = run;
+        run += items_of(dense_len > 0 ? dense_len : ptr[c + 1] - ptr[c]);
+    }
+    if (threadIdx.x == 1023) item_start[n_large] = part[1023];
+    if (threadIdx.x == 0) *ticket = 0u;
+}
+
+template <int KIND, bool DENSE>
+__global__ void __launch_bounds__(TPB)
+k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_large,
+            const int64_t* __restrict__ item_start, int64_t n_items, LargeState* st, uint32_t* ticket,
+            uint32_t* status, const float* __restrict__ y, float* __restrict__ x, float* v,
+            const float* __restrict__ norms, StepParams sp, int64_t dense_len) {
+    __shared__ uint32_t s_ticket;
+    __shared__ float s_mult;
+    __shared__ float s_part[2 * WAVES_PER_WG];
+  // a fixed number of workgroups (the cap on work in flight) keeps drawing tickets
+  for (;;) {
+    __syncthreads();                                   // s_ticket / s_mult / s_part are reused
+    if (threadIdx.x == 0) s_ticket = atomicAdd(ticket, 1u);
+    __syncthreads();
+    const int64_t t = (int64_t)s_ticket;
+    if (t >= n_items) return;
+    int64_t lo = 0, hi = n_large;                      // largest k with item_start[k] <= t
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (item_start[mid] <= t) lo = mid; else hi = mid;
+    }
+    const int64_t k = lo;
+    const int64_t c = cv.c0 + (int64_t)order_large[k];
+    int64_t b0, len;
+    if (DENSE) {
+        b0 = c * dense_len;
+        len = dense_len;
+    } else {
+        b0 = cv.ptr[c] - cv.nnz_base;
+        len = cv.ptr[c + 1] - cv.ptr[c];
+    }
+    const int64_t nseg = (len + SEG - 1) / SEG;
+    const int64_t item = t - item_start[k];
+    const bool dot_phase = item < nseg;
+    const int64_t seg = dot_phase ? item : item - nseg;
+    const int64_t e0 = seg * SEG, e1 = min(len, e0 + SEG);     // element range inside the coordinate
+
+    if (dot_phase) {
+        float g = 0.0f, h = 0.0f;
+        for (int64_t e = e0 + threadIdx.x; e < e1; e += TPB) {
+            uint32_t r;
+            float yy;
+            if (DENSE) {
+                r = (uint32_t)e;
+                yy = KIND == K_DUAL_HINGE ? 0.0f : y[r];
+            } else {
+                decode<KIND>(cv.idx[b0 + e], r, yy, y);
+            }
+            accumulate<KIND>(cv.val[b0 + e], load_shared(v, r), yy, g, h);
+        }
+        g = wave_sum(g);
+        h = wave_sum(h);
+        const int w = threadIdx.x / WAVE;
+        if ((threadIdx.x & (WAVE - 1)) == 0) {
+            s_part[2 * w] = g;
+            s_part[2 * w + 1] = h;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double G = 0.0, H = 0.0;
+#pragma unroll
+            for (int ww = 0; ww < WAVES_PER_WG; ++ww) {
+                G += (double)s_part[2 * ww];
+                H += (double)s_part[2 * ww + 1];
+            }
+            atomicAdd(&st[k].g, G);
+            atomicAdd(&st[k].h, H);
+            __threadfence();
+            const uint32_t arrived = atomicAdd(&st[k].done, 1u);
+            if (arrived == (uint32_t)nseg - 1u) {              // last dot item of this coordinate
+                __threadfence();
+                const double Gt = atomicAdd(&st[k].g, 0.0);
+                const double Ht = atomicAdd(&st[k].h, 0.0);
+                const float xc = x[c];
+                const float yc = KIND == K_DUAL_HINGE ? y[c] : 0.0f;
+                float mult;
+                x[c] = take_step<KIND>(Gt, Ht, xc, norms[c], yc, sp, mult);
+                __hip_atomic_store(&st[k].delta, mult, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&st[k].ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        continue;
+    }
+
+    // scatter phase: wait (bounded) for the step of this coordinate
+    if (threadIdx.x == 0) {
+        uint32_t spins = 0;
+        bool ok = true;
+        while (__hip_atomic_load(&st[k].ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+            __builtin_amdgcn_s_sleep(8);
+            if (++spins > SPIN_LIMIT) {
+                ok = false;
+                break;
+            }
+        }
+        if (ok) {
+            s_mult = __hip_atomic_load(&st[k].delta, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            s_mult = 0.0f;
+            atomicOr(status, 1u);
+        }
+    }
+    __syncthreads();
+    const float mult = s_mult;
+    if (mult == 0.0f) continue;
+    for (int64_t e = e0 + threadIdx.x; e < e1; e += TPB) {
+        uint32_t r;
+        if (DENSE) r = (uint32_t)e;
+        else r = cv.idx[b0 + e] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu);
+        unsafeAtomicAdd(v + r, mult * cv.val[b0 + e]);
+    }
+  }
+}
+
+template <int KIND>
+static int launch_kind(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk& ck, const uint32_t* order,
+                       const StepParams& sp) {
+    const int64_t dense_len = h->dense ? h->ld : 0;
+    if (ck.n_large > 0) {
+        const uint32_t* order_large = order + ck.n_small;
+        hipLaunchKernelGGL(k_large_prepare, dim3(1), dim3(1024), 0, h->compute, cv.ptr, cv.c0, order_large, ck.n_large,
+                           dense_len, h->item_start, h->lstate, h->ticket);
+        int64_t wgs = ck.n_items;
+        if (h->inflight_nnz > 0) wgs = std::min<int64_t>(wgs, std::max<int64_t>(1, h->inflight_nnz / SEG));
+        wgs = std::min<int64_t>(wgs, 256 * 8);          // no more than the device holds at once
+        const dim3 grid((unsigned)wgs);
+        if (h->dense)
+            hipLaunchKernelGGL((k_scd_large<KIND, true>), grid, dim3(TPB), 0, h->compute, cv, order_large, ck.n_large,
+                               h->item_start, ck.n_items, h->lstate, h->ticket, h->status, h->y, h->x, h->v, h->norms,
+                               sp, dense_len);
+        else
+            hipLaunchKernelGGL((k_scd_large<KIND, false>), grid, dim3(TPB), 0, h->compute, cv, order_large, ck.n_large,
+                               h->item_start, ck.n_items, h->lstate, h->ticket, h->status, h->y, h->x, h->v, h->norms,
+                               sp, dense_len);
+    }
+    if (ck.n_small > 0) {
+        int64_t waves = std::min<int64_t>(ck.n_small, 256 * 32);
+        if (h->inflight_nnz > 0)
+            waves = std::min<int64_t>(waves, std::max<int64_t>(1, (int64_t)((double)h->inflight_nnz / h->avg_small_len)));
+        const dim3 grid((unsigned)((waves + WAVES_PER_WG - 1) / WAVES_PER_WG));
+        hipLaunchKernelGGL((k_scd_small<KIND>), grid, dim3(TPB), 0, h->compute, cv, order, ck.n_small, h->y, h->x,
+                           h->v, h->norms, sp, waves);
+    }
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk& ck, const uint32_t* order) {
+    StepParams sp;
+    sp.lambda = h->lambda;
+    sp.inv_n = 1.0 / (double)h->n;
+    sp.lam_n = h->lambda * (double)h->n;
+    sp.damping = (double)h->damping;
+    if (ck.n_items > 0x7FFFFFFFll || ck.n_small / WAVES_PER_WG > 0x7FFFFFFFll) {
+        set_error("chunk too large for one launch");
+        return SNAP_EINVAL;
+    }
+    switch (h->kind) {
+    case K_PRIMAL_RIDGE: return launch_kind<K_PRIMAL_RIDGE>(h, cv, ck, order, sp);
+    case K_PRIMAL_LOGISTIC: return launch_kind<K_PRIMAL_LOGISTIC>(h, cv, ck, order, sp);
+    case K_DUAL_HINGE: return launch_kind<K_DUAL_HINGE>(h, cv, ck, order, sp);
+    }
+    set_error("unknown solver kind");
+    return SNAP_EINVAL;
+}
+
+}  // namespace snap

@@ -1,0 +1,238 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
+inputs.  Tolerances (fp32 GPU path against the fp64 oracle):
+  - permutation and keys: bit-exact;
+  - deterministic kernels (objective, gap, v = A x, decision values): relative error <= 1e-5;
+  - asynchronous solver: final objective within 1e-4 relative of the oracle's converged objective;
+  - v = A x after every epoch: relative error (2-norm) <= 1e-4."""
+import numpy as np
+import pytest
+import torch
+
+import datagen
+import oracle
+import paper_1803_06333_amd as snap
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def rel(a, b):
+    return abs(a - b) / max(abs(b), 1e-300)
+
+
+def relnorm(a, b):
+    return np.linalg.norm(np.asarray(a, dtype=np.float64) - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def gpu_solver(p, **kw):
+    return snap.Solver.from_problem(p.to(DEV), **kw)
+
+
+def small_problems():
+    return {
+        "cfg1_sparse_logistic": datagen.uniform_sparse_logistic(),
+        "cfg2_dense_ridge": datagen.dense_ridge(n=20_000, d=300),
+        "cfg3_zipf_svm": datagen.zipf_sparse_svm(n=40_000, d=5_000, lam=1e-4),
+        "cfg4_onehot_logistic": datagen.onehot_fields(n=200_000, d=5_000, lam=1e-4),
+    }
+
+
+PROBLEMS = None
+
+
+def problem(name):
+    global PROBLEMS
+    if PROBLEMS is None:
+        PROBLEMS = small_problems()
+    return PROBLEMS[name]
+
+
+NAMES = ["cfg1_sparse_logistic", "cfg2_dense_ridge", "cfg3_zipf_svm", "cfg4_onehot_logistic"]
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("m", [1, 2, 63, 64, 65, 2047, 2048, 2049, 5000, 300_001])
+def test_permutation_bit_exact(m):
+    # a matrix with m empty columns is enough to drive the permutation
+    ptr = np.zeros(m + 1, dtype=np.int64)
+    s = snap.Solver("csc", 4, m, ptr, np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.float32),
+                    np.ones(4, dtype=np.float32), "ridge", 0.1)
+    for seed in [0, 1, 2 ** 64 - 1, 180306333]:
+        s.epoch(seed)
+        perm, keys = s.perm(want_keys=True)
+        operm, okeys = oracle.permutation(seed, m, want_keys=True)
+        assert np.array_equal(keys, okeys), "keys differ for m=%d seed=%d" % (m, seed)
+        assert np.array_equal(perm, operm), "perm differs for m=%d seed=%d" % (m, seed)
+    s.close()
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_deterministic_kernels(name):
+    """objective / gap / v = A x / decision values at a fixed model, against the oracle."""
+    p = problem(name)
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    g = gpu_solver(p)
+    o = oracle.Solver(A, y, p.loss, p.lam)
+    rng = np.random.default_rng(7)
+    # state 0: the zero model
+    P0 = g.objective()
+    assert rel(P0, o.primal()) <= 1e-5
+    assert rel(g.duality_gap(), o.gap()) <= 1e-5
+    # a random model (alpha in [0,1] for the dual form)
+    if o.form == "dual":
+        x = rng.random(o.m).astype(np.float32)
+    else:
+        x = (0.05 * rng.standard_normal(o.m)).astype(np.float32)
+    g.set_model(x)
+    o.x[:] = x.astype(np.float64)
+    o.v[:] = o.shared_from_model()
+    assert relnorm(g.shared(), o.v) <= 1e-5
+    if o.form == "dual":
+        P, D = g.objective(want_dual=True)
+        oP, oD = o.primal_dual()
+        assert rel(P, oP) <= 1e-5 and rel(D, oD) <= 1e-5
+    else:
+        assert rel(g.objective(), o.primal()) <= 1e-5
+    assert rel(g.duality_gap(), o.gap()) <= 1e-5
+    # deterministic: same bits on a second call
+    assert g.duality_gap() == g.duality_gap() and g.objective() == g.objective()
+    w, xc = g.model()
+    assert np.array_equal(xc, x)
+    assert relnorm(w, o.weights()) <= 1e-5
+    # decision values on the training matrix in the layouts predict supports
+    want = A.matvec(o.weights())
+    if p.layout == "dense_colmajor":
+        out = g.predict("dense_colmajor", p.n, None, None, p.val.numpy())
+        assert relnorm(out, want) <= 1e-5
+        rm = np.ascontiguousarray(p.val.numpy().reshape(p.d, p.n).T).reshape(-1)
+        out = g.predict("dense_rowmajor", p.n, None, None, torch.from_numpy(rm).to(DEV))
+        assert relnorm(out.cpu().numpy(), want) <= 1e-5
+    else:
+        out = g.predict(p.layout, p.n, p.ptr.numpy(), p.idx.numpy(), p.val.numpy())
+        assert relnorm(out, want) <= 1e-5
+        if "csr" in p.meta:
+            rp, ri, rv = (t.to(DEV) for t in p.meta["csr"])
+            out = g.predict("csr", p.n, rp, ri, rv)
+            assert relnorm(out.cpu().numpy(), want) <= 1e-5
+    g.close()
+
+
+@pytest.mark.parametrize("name,epochs", [("cfg1_sparse_logistic", 10), ("cfg2_dense_ridge", 20),
+                                         ("cfg3_zipf_svm", 30), ("cfg4_onehot_logistic", 40)])
+def test_solver_reaches_oracle_objective(name, epochs):
+    p = problem(name)
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    ref = oracle.solve(A, y, p.loss, p.lam, epochs=500, tol=1e-6)
+    dual = ref.form == "dual"
+    target = ref.dual() if dual else ref.primal()
+    g = gpu_solver(p)
+    best = None
+    for e in range(epochs):
+        g.epoch(e)
+        # invariant: the maintained v equals A x recomputed from the model (oracle product, fp64)
+        _, x = g.model()
+        ref_v = oracle.Solver(A, y, p.loss, p.lam)
+        ref_v.x[:] = x
+        assert relnorm(g.shared(), ref_v.shared_from_model()) <= 1e-4, "v != A x after epoch %d" % e
+        if dual:
+            assert x.min() >= 0.0 and x.max() <= 1.0
+            val = g.objective(want_dual=True)[1]
+        else:
+            val = g.objective()
+        best = val if best is None else (max(best, val) if dual else min(best, val))
+    assert rel(best, target) <= 1e-4, "objective %r vs oracle %r" % (best, target)
+    assert g.duality_gap() >= 0.0
+    g.close()
+
+
+def test_permutation_is_the_oracles_on_a_real_problem():
+    p = problem("cfg4_onehot_logistic")
+    g = gpu_solver(p)
+    g.epoch(42)
+    assert np.array_equal(g.perm(), oracle.permutation(42, p.d))
+    g.close()
+
+
+def test_orthogonal_columns_match_sequential_result():
+    """With mutually orthogonal columns the asynchronous epoch equals the sequential one."""
+    n, d = 50_000, 300
+    rng = np.random.default_rng(3)
+    cols = rng.integers(0, d, size=n)
+    order = np.argsort(cols, kind="stable")
+    ptr = np.zeros(d + 1, dtype=np.int64)
+    ptr[1:] = np.cumsum(np.bincount(cols, minlength=d))
+    idx = order.astype(np.int32)
+    val = rng.standard_normal(n).astype(np.float32)
+    y = rng.standard_normal(n).astype(np.float32)
+    g = snap.Solver("csc", n, d, ptr, idx, val, y, "ridge", 0.01)
+    g.epoch(5)
+    o = oracle.solve(oracle.Matrix("csc", n, d, ptr, idx, val), y, "ridge", 0.01, epochs=1, seed0=5)
+    _, x = g.model()
+    np.testing.assert_allclose(x, o.x, rtol=2e-5, atol=1e-7)
+    assert relnorm(g.shared(), o.v) <= 1e-5
+    g.close()
+
+
+def test_edge_cases_empty_and_ragged():
+    # empty columns, a single huge column spanning several segments, one-element columns
+    n = 40_000
+    lens = [0, 1, 0, 4096, 4097, 8192, 8193, 30_000, 0, 63, 64, 65]
+    d = len(lens)
+    rng = np.random.default_rng(11)
+    ptr = np.zeros(d + 1, dtype=np.int64)
+    ptr[1:] = np.cumsum(lens)
+    idx = np.concatenate([np.sort(rng.choice(n, size=l, replace=False)) for l in lens]).astype(np.int32)
+    val = rng.standard_normal(idx.size).astype(np.float32)
+    for loss in ["ridge", "logistic"]:
+        y = (rng.standard_normal(n) if loss == "ridge" else np.where(rng.random(n) < 0.5, 1.0, -1.0)).astype(np.float32)
+        A = oracle.Matrix("csc", n, d, ptr, idx, val)
+        ref = oracle.solve(A, y, loss, 0.05, epochs=300, tol=1e-12)
+        g = snap.Solver("csc", n, d, ptr, idx, val, y, loss, 0.05)
+        for e in range(60):
+            g.epoch(e)
+        assert rel(g.objective(), ref.primal()) <= 1e-4
+        _, x = g.model()
+        assert x[0] == 0.0 and x[2] == 0.0 and x[8] == 0.0
+        g.close()
+    # dual form with an empty row: alpha = 1
+    rows = 3000
+    rl = rng.integers(1, 40, size=rows)
+    rl[7] = 0
+    rptr = np.zeros(rows + 1, dtype=np.int64)
+    rptr[1:] = np.cumsum(rl)
+    ridx = np.concatenate([np.sort(rng.choice(500, size=l, replace=False)) for l in rl]).astype(np.int32)
+    rval = rng.standard_normal(ridx.size).astype(np.float32)
+    y = np.where(rng.random(rows) < 0.5, 1.0, -1.0).astype(np.float32)
+    g = snap.Solver("csr", rows, 500, rptr, ridx, rval, y, "hinge", 0.01)
+    ref = oracle.solve(oracle.Matrix("csr", rows, 500, rptr, ridx, rval), y, "hinge", 0.01, epochs=2000, tol=1e-9)
+    for e in range(200):
+        g.epoch(e)
+    _, a = g.model()
+    assert a[7] == 1.0 and a.min() >= 0 and a.max() <= 1
+    assert rel(g.objective(want_dual=True)[1], ref.dual()) <= 1e-4
+    g.close()
+
+
+def test_error_paths():
+    ptr = np.array([0, 2, 3], dtype=np.int64)
+    idx = np.array([0, 1, 2], dtype=np.int32)
+    val = np.ones(3, dtype=np.float32)
+    y = np.array([1, -1, 1], dtype=np.float32)
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", 3, 2, ptr, idx, val, y, "hinge", 0.1)
+    assert e.value.code == -2
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", 3, 2, ptr, idx, val, y, "ridge", -1.0)
+    assert e.value.code == -1
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", 2, 2, ptr, idx, val, y[:2], "ridge", 0.1)       # row index 2 out of range
+    assert e.value.code == -1
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", 3, 2, ptr, idx, val, np.array([1, 0.5, 1], dtype=np.float32), "logistic", 0.1)
+    assert e.value.code == -1
+    bad = np.array([0, 3, 2], dtype=np.int64)
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", 3, 2, bad, idx, val, y, "ridge", 0.1)
+    assert e.value.code == -1
