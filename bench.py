@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the SCD local solver on one MI355X (arXiv 1803.06333, Section 3.1 / 4.1).
+
+A step is one whole epoch of the hot path -- permutation, gather-dot / step / atomic scatter over
+every coordinate, the adaptive accept check -- on the click-log-shaped logistic-regression workload
+(45 840 617 x 1 000 000, 39 one-hot fields, seeded synthetic stand-in for the public click logs the
+paper uses), with all inputs resident in HBM before the timed region.
+
+Prints ONE JSON line: coordinate updates per second plus the roofline of the dominant kernel and a
+CPU baseline (the fp64 oracle timed on the host cores on a bounded sample of the same workload).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..4 (default: 4)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the row count (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gap", action="store_true", help="skip the time-to-gap leg")
+    ap.add_argument("--gap-target", type=float, default=1e-3)
+    ap.add_argument("--gap-max-epochs", type=int, default=400)
+    ap.add_argument("--gap-max-seconds", type=float, default=60.0)
+    ap.add_argument("--inflight", type=int, default=0, help="override the cap on nonzeros in flight")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one elementwise pass over 1 GiB (read 1 GiB, write 1 GiB) so that a counter "
+                         "run can scale FETCH_SIZE / WRITE_SIZE against known traffic")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the one-GPU local solver only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import datagen
+    import paper_1803_06333_amd as snap
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    snap.load_library()           # fails loudly when the HIP library is not built
+
+    t0 = time.time()
+    p = datagen.config(args.config, device=dev, scale=args.scale)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    dense = p.layout.startswith("dense")
+    m = p.d if p.layout != "csr" else p.n
+    nnz = p.nnz
+
+    t0 = time.time()
+    g = snap.Solver.from_problem(p, profile=True, max_inflight_nnz=args.inflight)
+    torch.cuda.synchronize()
+    create_s = time.time() - t0
+
+    for e in range(args.warmup):
+        g.epoch(1000 + e)
+    torch.cuda.synchronize()
+    per_kernel = {"large_ms": [], "small_ms": [], "perm_ms": [], "scd_ms": []}
+    rejected = 0
+    t0 = time.perf_counter()
+    for e in range(args.steps):
+        g.epoch(2000 + e)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # per-kernel device times (HIP events recorded by the library on its compute stream) for a few
+    # more epochs, outside the timed region because reading them synchronises
+    for e in range(min(5, max(1, args.steps))):
+        g.epoch(3000 + e)
+        st = g.epoch_stats()
+        for k in per_kernel:
+            per_kernel[k].append(st[k])
+        rejected += st["rejected"]
+    st = g.epoch_stats()
+    ms_per_step = 1e3 * elapsed / args.steps
+    updates_per_s = m * args.steps / elapsed
+
+    # algorithmic bytes: 16 B per nonzero (index, value, read and write of v) sparse, 12 B per
+    # element dense, plus 24 B per coordinate (order entry, offsets, model read+write, norm)
+    per_elem = 12 if dense else 16
+    alg_epoch = per_elem * nnz + 24 * m
+    avg = lambda xs: float(np.mean(xs)) if xs else 0.0
+    large_ms, small_ms = avg(per_kernel["large_ms"]), avg(per_kernel["small_ms"])
+    if large_ms >= small_ms:
+        dom, dom_ms, dom_bytes = "k_scd_large", large_ms, per_elem * st["nnz_large"] + 24 * st["n_large"]
+    else:
+        dom, dom_ms, dom_bytes = "k_scd_small", small_ms, per_elem * st["nnz_small"] + 24 * st["n_small"]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "traffic_config%d.json" % args.config)
+    if os.path.exists(tf) and args.scale == 1.0:
+        try:
+            traffic = json.load(open(tf)).get(dom)
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": 8000.0, "unit": "GB/s",
+                "frac": round(achieved / 8000.0, 5), "traffic": traffic,
+                "kernel_ms": round(dom_ms, 4), "algorithmic_bytes_per_launch": int(dom_bytes),
+                "epoch_algorithmic_GBps": round(alg_epoch / (ms_per_step * 1e-3) / 1e9, 2)}
+
+    out = {
+        "metric": "coordinate updates/s (one SCD epoch = permutation + gather-dot/step/atomic-scatter over all "
+                  "coordinates)",
+        "value": updates_per_s, "unit": "coordinate updates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config%d:%s" % (args.config, p.name), "n_rows": p.n, "n_cols": p.d, "nnz": nnz,
+                   "loss": p.loss, "lambda": p.lam, "layout": p.layout, "scale": args.scale},
+        "roofline": roofline,
+        "epochs_per_s": args.steps / elapsed, "nnz_per_s": nnz * args.steps / elapsed,
+        "kernel_ms": {k: round(avg(v), 4) for k, v in per_kernel.items()},
+        "inflight_nnz": st["inflight_nnz"], "damping": st["damping"], "rejected_epochs_in_sample": rejected,
+        "n_small": st["n_small"], "n_large": st["n_large"], "generate_s": round(gen_s, 2),
+        "create_s": round(create_s, 2),
+    }
+
+    # ---- time to duality gap (fresh solver state) ------------------------------------------------
+    if not args.no_gap:
+        g.set_model(np.zeros(g.n_coords, dtype=np.float32))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        solve_s, reached, ep, gap, trace = 0.0, False, 0, float("nan"), []
+        while ep < args.gap_max_epochs and time.perf_counter() - t0 < args.gap_max_seconds:
+            ts = time.perf_counter()
+            for _ in range(5):
+                g.epoch(5000 + ep)
+                ep += 1
+            torch.cuda.synchronize()
+            solve_s += time.perf_counter() - ts
+            gap = g.duality_gap()
+            trace.append([ep, round(solve_s, 4), gap])
+            if gap <= args.gap_target:
+                reached = True
+                break
+        out["time_to_gap"] = {"target": args.gap_target, "reached": reached, "epochs": ep,
+                              "solve_seconds": round(solve_s, 4),
+                              "wall_seconds_with_gap_evaluations": round(time.perf_counter() - t0, 4),
+                              "final_gap": gap, "final_objective": g.objective(), "trace": trace[-8:]}
+
+    # ---- CPU baseline: the oracle, one thread, on a bounded sample of the same epoch --------------
+    if not args.no_cpu_baseline:
+        import oracle
+        A = oracle.Matrix.from_problem(p)
+        yh = p.y.cpu().numpy()
+        o = oracle.Solver(A, yh, p.loss, p.lam)
+        perm = oracle.permutation(7000, o.m)
+        # visit the first coordinates of one epoch order until about 15 s of CPU time are spent
+        import ctypes as C
+        L = oracle.lib()
+        done, t_cpu, batch, nnz_done = 0, 0.0, max(1, o.m // 200), 0
+        while done < o.m and t_cpu < 15.0:
+            mc = min(batch, o.m - done)
+            sl = np.ascontiguousarray(perm[done:done + mc])
+            ts = time.perf_counter()
+            args_t = (C.c_double(o.lam), oracle._p(sl), C.c_int64(0), C.c_int64(mc), oracle._p(o.x), oracle._p(o.v))
+            if o.form == "dual":
+                L.oracle_epoch_dual_hinge(C.c_int64(A.n), oracle._p(A.ptr), oracle._p(A.idx), oracle._p(A.val),
+                                          oracle._p(o.y), *args_t)
+            elif A.layout == "csc":
+                L.oracle_epoch_primal_sparse(C.c_int(o.loss), C.c_int64(A.n), oracle._p(A.ptr), oracle._p(A.idx),
+                                             oracle._p(A.val), oracle._p(o.y), *args_t)
+            else:
+                L.oracle_epoch_primal_dense(C.c_int(o.loss), C.c_int64(A.n), oracle._p(A.val), oracle._p(o.y), *args_t)
+            t_cpu += time.perf_counter() - ts
+            if A.ptr is not None:
+                nnz_done += int((A.ptr[sl.astype(np.int64) + 1] - A.ptr[sl.astype(np.int64)]).sum())
+            else:
+                nnz_done += mc * A.n
+            done += mc
+        out["cpu_baseline"] = {"value": done / t_cpu, "unit": "coordinate updates/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d of %d coordinates of one epoch order (%d nonzeros, %.1f s), "
+                                         "sequential fp64 oracle" % (done, o.m, nnz_done, t_cpu),
+                               "nnz_per_s": nnz_done / t_cpu, "host_cores_available": os.cpu_count()}
+    g.close()
+    if args.calibrate:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.add(a, 1.0, out=b)
+        torch.cuda.synchronize()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -102,6 +102,10 @@ typedef struct {
     int64_t inflight_nnz;  /* cap on nonzeros in flight used by the last epoch */
     float damping;         /* damping used by the last epoch */
     int rejected;          /* 1 if the adaptive check discarded the last epoch's updates */
+    float large_ms;        /* the split-coordinate kernel (with its prepare step) */
+    float small_ms;        /* the wavefront-per-coordinate kernel */
+    int64_t nnz_large;     /* nonzeros of the split coordinates */
+    int64_t nnz_small;     /* nonzeros of the wavefront-per-coordinate class */
 } snap_epoch_stats;
 
 /* Section 1 eq. (1) / Section 3.1.  Builds the solver state for X (A), y, loss and lambda:

@@ -43,7 +43,8 @@ class SnapOptions(C.Structure):
 class SnapEpochStats(C.Structure):
     _fields_ = [("epoch_ms", C.c_float), ("scd_ms", C.c_float), ("perm_ms", C.c_float), ("copy_ms", C.c_float),
                 ("n_chunks", C.c_int64), ("n_small", C.c_int64), ("n_large", C.c_int64), ("n_items", C.c_int64),
-                ("inflight_nnz", C.c_int64), ("damping", C.c_float), ("rejected", C.c_int)]
+                ("inflight_nnz", C.c_int64), ("damping", C.c_float), ("rejected", C.c_int),
+                ("large_ms", C.c_float), ("small_ms", C.c_float), ("nnz_large", C.c_int64), ("nnz_small", C.c_int64)]
 
 
 class SnapError(RuntimeError):
@@ -125,6 +126,8 @@ class Solver:
                  damping: float = 0.0, max_inflight_nnz: int = 0):
         self._lib = load_library()
         self._h = C.c_void_p()
+        if torch is not None and isinstance(val, torch.Tensor) and val.is_cuda:
+            torch.cuda.synchronize(val.device)       # the library reads the tensors on its own stream
         sm, self._keep = make_matrix(layout, n_rows, n_cols, ptr, idx, val)
         py, my, ky = _describe(y, np.float32, "float32")
         if (my == MEM_DEVICE) != (sm.mem == MEM_DEVICE):

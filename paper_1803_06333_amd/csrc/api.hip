@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <cmath>
 #include <algorithm>
 #include <new>
@@ -88,7 +89,7 @@ static void destroy(snap_handle* h) {
     delete h;
 }
 
-static int64_t n_segments(int64_t len) { return (len + SEG - 1) / SEG; }
+
 
 static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_HIP(hipGetDevice(&h->device));
@@ -112,6 +113,8 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_TRY(fill_zero(h->ticket, 4, h->compute));
 
     const int64_t m = h->m;
+    if (const char* e = getenv("SNAP_SEG")) h->seg = std::max<int64_t>(256, atoll(e));          // tuning knobs
+    if (const char* e = getenv("SNAP_SMALL_MAX")) h->small_max = std::max<int64_t>(0, atoll(e));
     // ---- the matrix: host copy of ptr for planning, device copies of everything -----------------
     std::vector<int64_t> hptr;
     if (!h->dense) {
@@ -188,11 +191,11 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     ck = {0, m, 0, h->nnz, 0, 0, 0};
     for (int64_t c = 0; c < m; ++c) {
         const int64_t len = h->dense ? h->ld : hptr[(size_t)c + 1] - hptr[(size_t)c];
-        if (h->dense || len > SMALL_MAX) {
+        if (h->dense || len > h->small_max) {
             ++ck.n_large;
-            ck.n_items += 2 * n_segments(len);
+            ck.n_items += 2 * ((len + h->seg - 1) / h->seg);
             large.push_back(c);
-            seg_off.push_back(seg_off.back() + n_segments(len));
+            seg_off.push_back(seg_off.back() + ((len + h->seg - 1) / h->seg));
         } else {
             ++ck.n_small;
         }
@@ -221,9 +224,11 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
         if (!h->dense)
             for (int64_t c = 0; c < m; ++c) {
                 const int64_t len = hptr[(size_t)c + 1] - hptr[(size_t)c];
-                if (len <= SMALL_MAX) small_nnz += len;
+                if (len <= h->small_max) small_nnz += len;
             }
         h->avg_small_len = ck.n_small > 0 ? std::max(1.0, (double)small_nnz / (double)ck.n_small) : 1.0;
+        h->nnz_small = small_nnz;
+        h->nnz_large = h->nnz - small_nnz;
     }
     h->inflight_floor = WAVE;
     if (h->opt.max_inflight_nnz > 0) {
@@ -367,7 +372,7 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
             SNAP_HIP(hipMemcpyAsync(h->v, h->v_snap, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
             h->stats.rejected = 1;
             // first fewer nonzeros in flight (down to one wavefront's worth), then smaller steps
-            const int64_t cur = h->inflight_nnz > 0 ? h->inflight_nnz : (int64_t)256 * 8 * SEG;
+            const int64_t cur = h->inflight_nnz > 0 ? h->inflight_nnz : (int64_t)256 * 8 * h->seg;
             if (cur > h->inflight_floor)
                 h->inflight_nnz = std::max<int64_t>(h->inflight_floor, cur / 2);
             else
@@ -481,7 +486,11 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
     }
     if (h->stats_pending) {
         SNAP_HIP(hipEventSynchronize(h->ev[2]));
-        float total = 0, perm = 0, scd = 0;
+        float total = 0, perm = 0, scd = 0, large = 0, small = 0;
+        SNAP_HIP(hipEventElapsedTime(&large, h->ev[1], h->ev[3]));
+        SNAP_HIP(hipEventElapsedTime(&small, h->ev[3], h->ev[2]));
+        h->stats.large_ms = large;
+        h->stats.small_ms = small;
         SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
         SNAP_HIP(hipEventElapsedTime(&perm, h->ev[0], h->ev[1]));
         SNAP_HIP(hipEventElapsedTime(&scd, h->ev[1], h->ev[2]));
@@ -491,6 +500,8 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         h->stats.copy_ms = 0;
         h->stats_pending = false;
     }
+    h->stats.nnz_large = h->nnz_large;
+    h->stats.nnz_small = h->nnz_small;
     h->stats.n_chunks = h->n_chunks;
     h->stats.n_small = h->stats.n_large = h->stats.n_items = 0;
     for (int64_t ch = 0; ch < h->n_chunks; ++ch) {

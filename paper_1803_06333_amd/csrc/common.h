@@ -29,8 +29,8 @@ constexpr int TPB = 256;                 // threads per workgroup of the epoch k
 constexpr int WAVES_PER_WG = TPB / WAVE;
 // A coordinate with more nonzeros than SMALL_MAX is split into segments of SEG nonzeros, one
 // workgroup each (two phases: partial dots, then scatter).
-constexpr int64_t SEG = 8192;
-constexpr int64_t SMALL_MAX = 4096;
+constexpr int64_t SEG_DEFAULT = 8192;
+constexpr int64_t SMALL_MAX_DEFAULT = 4096;
 constexpr uint32_t LABEL_BIT = 0x80000000u;   // primal logistic: sign of y folded into the row index
 constexpr uint32_t SPIN_LIMIT = 1u << 22;     // bounded wait of a scatter item for its coordinate's step
 
@@ -39,9 +39,8 @@ enum Kind { K_PRIMAL_RIDGE = 0, K_PRIMAL_LOGISTIC = 1, K_DUAL_HINGE = 2 };
 // Per-epoch state of one split ("large") coordinate, indexed by its position in the epoch order.
 struct LargeState {
     double g, h;          // accumulated partial sums of the dot phase
-    float delta;          // the step, valid once ready != 0
+    uint64_t published;   // (1 << 32) | bits of the scatter multiplier, written once by one 64-bit store
     uint32_t done;        // dot items finished
-    uint32_t ready;       // 1 when delta has been published
     uint32_t pad;
 };
 
@@ -76,6 +75,8 @@ struct snap_handle {
     int64_t n = 0, d = 0, nnz = 0;
     int64_t m = 0, vlen = 0;          // coordinates, length of v
     int64_t ld = 0;                   // dense: elements per coordinate (= n)
+    int64_t seg = snap::SEG_DEFAULT;  // nonzeros per work item of a split coordinate
+    int64_t small_max = snap::SMALL_MAX_DEFAULT;   // longest coordinate handled by one wavefront
     double lambda = 0;
     snap_options opt{};
     int device = 0;
@@ -141,6 +142,7 @@ struct snap_handle {
     double monitor_prev = 0.0;        // objective before the epoch (minimised quantity)
     bool monitor_valid = false;
     double avg_small_len = 1.0;
+    int64_t nnz_small = 0, nnz_large = 0;
     snap_epoch_stats stats{};
     bool stats_pending = false;
     int64_t epochs_done = 0;

@@ -44,7 +44,7 @@ int fill_zero(void* p, size_t bytes, hipStream_t s) {
 // ---- squared norms and size classes -------------------------------------------------------------
 __global__ void __launch_bounds__(LTPB)
 k_coord_norms(const int64_t* __restrict__ ptr, const float* __restrict__ val, int64_t m, int64_t dense_len,
-              float* __restrict__ norms, uint8_t* __restrict__ cls) {
+              int64_t small_max, float* __restrict__ norms, uint8_t* __restrict__ cls) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
     const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
@@ -56,7 +56,7 @@ k_coord_norms(const int64_t* __restrict__ ptr, const float* __restrict__ val, in
         acc = wave_sum_d(acc);
         if (lane == 0) {
             norms[c] = (float)acc;
-            cls[c] = (dense_len > 0 || s1 - s0 > SMALL_MAX) ? 1 : 0;
+            cls[c] = (dense_len > 0 || s1 - s0 > small_max) ? 1 : 0;
         }
     }
 }
@@ -67,7 +67,7 @@ int compute_norms_and_classes(snap_handle* h) {
     int grid = (int)((h->m + 3) / 4 < 16384 ? (h->m + 3) / 4 : 16384);
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL(k_coord_norms, dim3(grid), dim3(LTPB), 0, h->compute, h->ptr, h->val, h->m, dense_len,
-                       h->norms, h->cls);
+                       h->small_max, h->norms, h->cls);
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
 }
@@ -220,7 +220,7 @@ __global__ void __launch_bounds__(LTPB)
 k_dots_large_partial(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const float* __restrict__ val,
                      int64_t nnz_base, int64_t dense_len, const int64_t* __restrict__ large_list,
                      const int64_t* __restrict__ seg_off, int64_t l0, int64_t l1, int64_t seg_base,
-                     const float* __restrict__ v, const float* __restrict__ y, double* __restrict__ partial) {
+                     int64_t SEG, const float* __restrict__ v, const float* __restrict__ y, double* __restrict__ partial) {
     __shared__ double scratch[LTPB / WAVE];
     const int64_t s = seg_base + blockIdx.x;
     int64_t lo = l0, hi = l1;
@@ -261,7 +261,7 @@ static int coord_dots_kind(snap_handle* h) {
         const int64_t nseg = h->n_seg_total;
         hipLaunchKernelGGL((k_dots_large_partial<KIND>), dim3((unsigned)nseg), dim3(LTPB), 0, h->compute, h->ptr,
                            h->idx, h->val, (int64_t)0, dense_len, h->large_list, h->large_seg_off, (int64_t)0,
-                           h->n_large_total, (int64_t)0, h->v, h->y, h->seg_partial);
+                           h->n_large_total, (int64_t)0, h->seg, h->v, h->y, h->seg_partial);
         hipLaunchKernelGGL(k_dots_large_finish, dim3((unsigned)((h->n_large_total + 255) / 256)), dim3(256), 0,
                            h->compute, h->large_list, h->large_seg_off, (int64_t)0, h->n_large_total, h->seg_partial,
                            h->gdot);

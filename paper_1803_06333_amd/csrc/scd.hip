@@ -143,22 +143,29 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
 }
 
 // ---- large coordinates: segments, two phases, ticket order -------------------------------------
-__device__ __forceinline__ int64_t items_of(int64_t len) { return 2 * ((len + SEG - 1) / SEG); }
+// Everything the workgroups of one coordinate exchange (partial sums, arrival count, the published
+// step) goes through device-scope atomic operations, which are performed at the level of the
+// memory system that all compute dies share.  Ordering between them therefore only needs the
+// earlier operations to have completed (a workgroup-scope release fence = wait for outstanding
+// memory operations); a device-scope fence would also write back and invalidate the L2 of the die
+// on every work item, which costs far more than the item itself.
+__device__ __forceinline__ void wait_memory_ops() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
 
 // One workgroup: prefix sums of the items of the large coordinates in epoch order, zeroed state,
 // ticket counter back to zero.
 __global__ void __launch_bounds__(1024)
 k_large_prepare(const int64_t* __restrict__ ptr, int64_t c0, const uint32_t* __restrict__ order_large,
-                int64_t n_large, int64_t dense_len, int64_t* __restrict__ item_start, LargeState* __restrict__ st,
-                uint32_t* __restrict__ ticket) {
+                int64_t n_large, int64_t dense_len, int64_t seg_len, int64_t* __restrict__ item_start,
+                LargeState* __restrict__ st, uint32_t* __restrict__ ticket) {
     __shared__ int64_t part[1024];
     const int64_t per = (n_large + 1023) / 1024;
     const int64_t lo = min(n_large, (int64_t)threadIdx.x * per), hi = min(n_large, lo + per);
     int64_t s = 0;
     for (int64_t k = lo; k < hi; ++k) {
         const int64_t c = c0 + (int64_t)order_large[k];
-        s += items_of(dense_len > 0 ? dense_len : ptr[c + 1] - ptr[c]);
-        st[k] = LargeState{0.0, 0.0, 0.0f, 0u, 0u, 0u};
+        const int64_t len = dense_len > 0 ? dense_len : ptr[c + 1] - ptr[c];
+        s += 2 * ((len + seg_len - 1) / seg_len);
+        st[k] = LargeState{0.0, 0.0, 0ull, 0u, 0u};
     }
     part[threadIdx.x] = s;
     __syncthreads();
@@ -171,125 +178,158 @@ k_large_prepare(const int64_t* __restrict__ ptr, int64_t c0, const uint32_t* __r
     int64_t run = part[threadIdx.x] - s;
     for (int64_t k = lo; k < hi; ++k) {
         const int64_t c = c0 + (int64_t)order_large[k];
+        const int64_t len = dense_len > 0 ? dense_len : ptr[c + 1] - ptr[c];
         item_start[k] = run;
-        run += items_of(dense_len > 0 ? dense_len : ptr[c + 1] - ptr[c]);
+        run += 2 * ((len + seg_len - 1) / seg_len);
     }
     if (threadIdx.x == 1023) item_start[n_large] = part[1023];
     if (threadIdx.x == 0) *ticket = 0u;
 }
+
+constexpr int UNROLL = 4;
 
 template <int KIND, bool DENSE>
 __global__ void __launch_bounds__(TPB)
 k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_large,
             const int64_t* __restrict__ item_start, int64_t n_items, LargeState* st, uint32_t* ticket,
             uint32_t* status, const float* __restrict__ y, float* __restrict__ x, float* v,
-            const float* __restrict__ norms, StepParams sp, int64_t dense_len) {
+            const float* __restrict__ norms, StepParams sp, int64_t dense_len, int64_t seg_len) {
     __shared__ uint32_t s_ticket;
     __shared__ float s_mult;
     __shared__ float s_part[2 * WAVES_PER_WG];
-  // a fixed number of workgroups (the cap on work in flight) keeps drawing tickets
-  for (;;) {
-    __syncthreads();                                   // s_ticket / s_mult / s_part are reused
-    if (threadIdx.x == 0) s_ticket = atomicAdd(ticket, 1u);
-    __syncthreads();
-    const int64_t t = (int64_t)s_ticket;
-    if (t >= n_items) return;
-    int64_t lo = 0, hi = n_large;                      // largest k with item_start[k] <= t
-    while (hi - lo > 1) {
-        const int64_t mid = (lo + hi) >> 1;
-        if (item_start[mid] <= t) lo = mid; else hi = mid;
-    }
-    const int64_t k = lo;
-    const int64_t c = cv.c0 + (int64_t)order_large[k];
-    int64_t b0, len;
-    if (DENSE) {
-        b0 = c * dense_len;
-        len = dense_len;
-    } else {
-        b0 = cv.ptr[c] - cv.nnz_base;
-        len = cv.ptr[c + 1] - cv.ptr[c];
-    }
-    const int64_t nseg = (len + SEG - 1) / SEG;
-    const int64_t item = t - item_start[k];
-    const bool dot_phase = item < nseg;
-    const int64_t seg = dot_phase ? item : item - nseg;
-    const int64_t e0 = seg * SEG, e1 = min(len, e0 + SEG);     // element range inside the coordinate
-
-    if (dot_phase) {
-        float g = 0.0f, h = 0.0f;
-        for (int64_t e = e0 + threadIdx.x; e < e1; e += TPB) {
-            uint32_t r;
-            float yy;
-            if (DENSE) {
-                r = (uint32_t)e;
-                yy = KIND == K_DUAL_HINGE ? 0.0f : y[r];
-            } else {
-                decode<KIND>(cv.idx[b0 + e], r, yy, y);
-            }
-            accumulate<KIND>(cv.val[b0 + e], load_shared(v, r), yy, g, h);
+    // a fixed number of workgroups (the cap on work in flight) keeps drawing tickets
+    for (;;) {
+        __syncthreads();                                   // s_ticket / s_mult / s_part are reused
+        if (threadIdx.x == 0) s_ticket = atomicAdd(ticket, 1u);
+        __syncthreads();
+        const int64_t t = (int64_t)s_ticket;
+        if (t >= n_items) return;
+        int64_t lo = 0, hi = n_large;                      // largest k with item_start[k] <= t
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (item_start[mid] <= t) lo = mid; else hi = mid;
         }
-        g = wave_sum(g);
-        h = wave_sum(h);
-        const int w = threadIdx.x / WAVE;
-        if ((threadIdx.x & (WAVE - 1)) == 0) {
-            s_part[2 * w] = g;
-            s_part[2 * w + 1] = h;
+        const int64_t k = lo;
+        const int64_t c = cv.c0 + (int64_t)order_large[k];
+        int64_t b0, len;
+        if (DENSE) {
+            b0 = c * dense_len;
+            len = dense_len;
+        } else {
+            b0 = cv.ptr[c] - cv.nnz_base;
+            len = cv.ptr[c + 1] - cv.ptr[c];
+        }
+        const int64_t nseg = (len + seg_len - 1) / seg_len;
+        const int64_t item = t - item_start[k];
+        const bool dot_phase = item < nseg;
+        const int64_t seg = dot_phase ? item : item - nseg;
+        const int64_t e0 = seg * seg_len, e1 = min(len, e0 + seg_len);   // element range of the item
+        const uint32_t* __restrict__ idxp = cv.idx + b0;
+        const float* __restrict__ valp = cv.val + b0;
+
+        if (dot_phase) {
+            float g = 0.0f, h = 0.0f;
+            int64_t e = e0 + threadIdx.x;
+            // UNROLL independent index/value loads, then their gathers, then the arithmetic
+            for (; e + (UNROLL - 1) * TPB < e1; e += UNROLL * TPB) {
+                uint32_t r[UNROLL];
+                float a[UNROLL], yy[UNROLL], vv[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int64_t eu = e + u * TPB;
+                    a[u] = valp[eu];
+                    if (DENSE) {
+                        r[u] = (uint32_t)eu;
+                        yy[u] = KIND == K_DUAL_HINGE ? 0.0f : y[r[u]];
+                    } else {
+                        decode<KIND>(idxp[eu], r[u], yy[u], y);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) vv[u] = load_shared(v, r[u]);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) accumulate<KIND>(a[u], vv[u], yy[u], g, h);
+            }
+            for (; e < e1; e += TPB) {
+                uint32_t r;
+                float yy;
+                if (DENSE) {
+                    r = (uint32_t)e;
+                    yy = KIND == K_DUAL_HINGE ? 0.0f : y[r];
+                } else {
+                    decode<KIND>(idxp[e], r, yy, y);
+                }
+                accumulate<KIND>(valp[e], load_shared(v, r), yy, g, h);
+            }
+            g = wave_sum(g);
+            h = wave_sum(h);
+            const int w = threadIdx.x / WAVE;
+            if ((threadIdx.x & (WAVE - 1)) == 0) {
+                s_part[2 * w] = g;
+                s_part[2 * w + 1] = h;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double G = 0.0, H = 0.0;
+#pragma unroll
+                for (int ww = 0; ww < WAVES_PER_WG; ++ww) {
+                    G += (double)s_part[2 * ww];
+                    H += (double)s_part[2 * ww + 1];
+                }
+                atomicAdd(&st[k].g, G);
+                atomicAdd(&st[k].h, H);
+                wait_memory_ops();                                  // both sums are in before the count
+                const uint32_t arrived = atomicAdd(&st[k].done, 1u);
+                if (arrived == (uint32_t)nseg - 1u) {              // last dot item of this coordinate
+                    const double Gt = atomicAdd(&st[k].g, 0.0);
+                    const double Ht = atomicAdd(&st[k].h, 0.0);
+                    const float xc = x[c];
+                    const float yc = KIND == K_DUAL_HINGE ? y[c] : 0.0f;
+                    float mult;
+                    x[c] = take_step<KIND>(Gt, Ht, xc, norms[c], yc, sp, mult);
+                    const uint64_t word = (1ull << 32) | (uint64_t)__float_as_uint(mult);
+                    __hip_atomic_store(&st[k].published, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            continue;
+        }
+
+        // scatter phase: wait (bounded) for the step of this coordinate
+        if (threadIdx.x == 0) {
+            uint32_t spins = 0;
+            uint64_t word;
+            while (((word = __hip_atomic_load(&st[k].published, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) == 0) {
+                __builtin_amdgcn_s_sleep(16);
+                if (++spins > SPIN_LIMIT) break;
+            }
+            if ((word >> 32) != 0) {
+                s_mult = __uint_as_float((uint32_t)word);
+            } else {
+                s_mult = 0.0f;
+                atomicOr(status, 1u);
+            }
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            double G = 0.0, H = 0.0;
+        const float mult = s_mult;
+        if (mult == 0.0f) continue;
+        int64_t e = e0 + threadIdx.x;
+        for (; e + (UNROLL - 1) * TPB < e1; e += UNROLL * TPB) {
+            uint32_t r[UNROLL];
+            float a[UNROLL];
 #pragma unroll
-            for (int ww = 0; ww < WAVES_PER_WG; ++ww) {
-                G += (double)s_part[2 * ww];
-                H += (double)s_part[2 * ww + 1];
+            for (int u = 0; u < UNROLL; ++u) {
+                const int64_t eu = e + u * TPB;
+                a[u] = valp[eu];
+                r[u] = DENSE ? (uint32_t)eu : (idxp[eu] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu));
             }
-            atomicAdd(&st[k].g, G);
-            atomicAdd(&st[k].h, H);
-            __threadfence();
-            const uint32_t arrived = atomicAdd(&st[k].done, 1u);
-            if (arrived == (uint32_t)nseg - 1u) {              // last dot item of this coordinate
-                __threadfence();
-                const double Gt = atomicAdd(&st[k].g, 0.0);
-                const double Ht = atomicAdd(&st[k].h, 0.0);
-                const float xc = x[c];
-                const float yc = KIND == K_DUAL_HINGE ? y[c] : 0.0f;
-                float mult;
-                x[c] = take_step<KIND>(Gt, Ht, xc, norms[c], yc, sp, mult);
-                __hip_atomic_store(&st[k].delta, mult, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&st[k].ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) unsafeAtomicAdd(v + r[u], mult * a[u]);
         }
-        continue;
-    }
-
-    // scatter phase: wait (bounded) for the step of this coordinate
-    if (threadIdx.x == 0) {
-        uint32_t spins = 0;
-        bool ok = true;
-        while (__hip_atomic_load(&st[k].ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-            __builtin_amdgcn_s_sleep(8);
-            if (++spins > SPIN_LIMIT) {
-                ok = false;
-                break;
-            }
-        }
-        if (ok) {
-            s_mult = __hip_atomic_load(&st[k].delta, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            s_mult = 0.0f;
-            atomicOr(status, 1u);
+        for (; e < e1; e += TPB) {
+            const uint32_t r = DENSE ? (uint32_t)e : (idxp[e] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu));
+            unsafeAtomicAdd(v + r, mult * valp[e]);
         }
     }
-    __syncthreads();
-    const float mult = s_mult;
-    if (mult == 0.0f) continue;
-    for (int64_t e = e0 + threadIdx.x; e < e1; e += TPB) {
-        uint32_t r;
-        if (DENSE) r = (uint32_t)e;
-        else r = cv.idx[b0 + e] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu);
-        unsafeAtomicAdd(v + r, mult * cv.val[b0 + e]);
-    }
-  }
 }
 
 template <int KIND>
@@ -299,20 +339,21 @@ static int launch_kind(snap_handle* h, const ChunkView& cv, const snap_handle::C
     if (ck.n_large > 0) {
         const uint32_t* order_large = order + ck.n_small;
         hipLaunchKernelGGL(k_large_prepare, dim3(1), dim3(1024), 0, h->compute, cv.ptr, cv.c0, order_large, ck.n_large,
-                           dense_len, h->item_start, h->lstate, h->ticket);
+                           dense_len, h->seg, h->item_start, h->lstate, h->ticket);
         int64_t wgs = ck.n_items;
-        if (h->inflight_nnz > 0) wgs = std::min<int64_t>(wgs, std::max<int64_t>(1, h->inflight_nnz / SEG));
+        if (h->inflight_nnz > 0) wgs = std::min<int64_t>(wgs, std::max<int64_t>(1, h->inflight_nnz / h->seg));
         wgs = std::min<int64_t>(wgs, 256 * 8);          // no more than the device holds at once
         const dim3 grid((unsigned)wgs);
         if (h->dense)
             hipLaunchKernelGGL((k_scd_large<KIND, true>), grid, dim3(TPB), 0, h->compute, cv, order_large, ck.n_large,
                                h->item_start, ck.n_items, h->lstate, h->ticket, h->status, h->y, h->x, h->v, h->norms,
-                               sp, dense_len);
+                               sp, dense_len, h->seg);
         else
             hipLaunchKernelGGL((k_scd_large<KIND, false>), grid, dim3(TPB), 0, h->compute, cv, order_large, ck.n_large,
                                h->item_start, ck.n_items, h->lstate, h->ticket, h->status, h->y, h->x, h->v, h->norms,
-                               sp, dense_len);
+                               sp, dense_len, h->seg);
     }
+    if (h->opt.profile) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
     if (ck.n_small > 0) {
         int64_t waves = std::min<int64_t>(ck.n_small, 256 * 32);
         if (h->inflight_nnz > 0)
