@@ -157,6 +157,10 @@ int snap_get_perm(snap_handle *h, uint32_t *perm_out, uint32_t *keys_out);
 /* Timing of the last epoch (valid when options.profile = 1). */
 int snap_get_epoch_stats(snap_handle *h, snap_epoch_stats *out);
 
+/* Streaming layout: *n_chunks receives the number of chunks (1 when resident); bounds_out, if not
+ * NULL, receives n_chunks+1 coordinate boundaries (host int64): chunk k is [bounds[k], bounds[k+1]). */
+int snap_get_chunks(snap_handle *h, int64_t *n_chunks, int64_t *bounds_out);
+
 /* Number of coordinates m and length of v. */
 int snap_get_dims(snap_handle *h, int64_t *n_coords, int64_t *shared_len);
 

@@ -25,7 +25,7 @@ LOSSES = {"ridge": RIDGE, "logistic": LOGISTIC, "hinge": HINGE}
 
 EXPORTS = ["snap_create", "snap_epoch", "snap_objective", "snap_duality_gap", "snap_predict", "snap_get_model",
            "snap_set_model", "snap_get_shared", "snap_recompute_shared", "snap_get_perm", "snap_get_epoch_stats",
-           "snap_get_dims", "snap_last_error", "snap_destroy"]
+           "snap_get_dims", "snap_get_chunks", "snap_last_error", "snap_destroy"]
 
 
 class SnapMatrix(C.Structure):
@@ -80,6 +80,7 @@ def load_library():
         L.snap_get_perm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.snap_get_epoch_stats.argtypes = [C.c_void_p, C.POINTER(SnapEpochStats)]
         L.snap_get_dims.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        L.snap_get_chunks.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]
         _lib = L
     return _lib
 
@@ -210,6 +211,13 @@ class Solver:
         k = np.empty(self.n_coords, dtype=np.uint32) if want_keys else None
         _check(self._lib.snap_get_perm(self._h, p.ctypes.data, k.ctypes.data if want_keys else None))
         return (p, k) if want_keys else p
+
+    def chunk_bounds(self) -> list:
+        n = C.c_int64()
+        _check(self._lib.snap_get_chunks(self._h, C.byref(n), None))
+        b = np.empty(n.value + 1, dtype=np.int64)
+        _check(self._lib.snap_get_chunks(self._h, C.byref(n), b.ctypes.data))
+        return b.tolist()
 
     def epoch_stats(self) -> dict:
         s = SnapEpochStats()

@@ -73,12 +73,7 @@ static void destroy(snap_handle* h) {
     (void)hipFree(h->status);
     (void)hipFree(h->x_snap);
     (void)hipFree(h->v_snap);
-    for (int b = 0; b < 2; ++b) {
-        (void)hipFree(h->buf_idx[b]);
-        (void)hipFree(h->buf_val[b]);
-        if (h->ev_copied[b]) (void)hipEventDestroy(h->ev_copied[b]);
-        if (h->ev_free[b]) (void)hipEventDestroy(h->ev_free[b]);
-    }
+    stream_free(h);
     for (auto& e : h->ev)
         if (e) (void)hipEventDestroy(e);
     sorter_free(h->sorter);
@@ -90,6 +85,24 @@ static void destroy(snap_handle* h) {
 }
 
 
+
+// Creation pass over one chunk: indices in range, squared norms + size classes, access counts.
+struct CreatePass {
+    uint32_t* freq;
+    int64_t minor;
+};
+
+static int create_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void* arg) {
+    CreatePass* cp = (CreatePass*)arg;
+    const snap_handle::Chunk& ck = h->chunks[chunk];
+    const int64_t count = ck.nnz1 - ck.nnz0;
+    if (!h->dense && count > 0)
+        hipLaunchKernelGGL(k_check_indices, dim3(4096), dim3(256), 0, h->compute, (const int32_t*)cv.idx, count,
+                           cp->minor, h->status);
+    SNAP_HIP(hipGetLastError());
+    if (!h->dense && cp->freq) SNAP_TRY(count_accesses_chunk(h, cv, count, cp->freq));
+    return norms_and_classes_chunk(h, cv);
+}
 
 static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_HIP(hipGetDevice(&h->device));
@@ -115,7 +128,8 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     const int64_t m = h->m;
     if (const char* e = getenv("SNAP_SEG")) h->seg = std::max<int64_t>(256, atoll(e));          // tuning knobs
     if (const char* e = getenv("SNAP_SMALL_MAX")) h->small_max = std::max<int64_t>(0, atoll(e));
-    // ---- the matrix: host copy of ptr for planning, device copies of everything -----------------
+
+    // ---- offsets: host copy for planning, device copy for the kernels -------------------------------
     std::vector<int64_t> hptr;
     if (!h->dense) {
         hptr.resize((size_t)m + 1);
@@ -131,6 +145,72 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
             }
         SNAP_HIP(hipMalloc(&h->ptr, (size_t)(m + 1) * sizeof(int64_t)));
         SNAP_HIP(hipMemcpyAsync(h->ptr, hptr.data(), (size_t)(m + 1) * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
+    }
+    auto len_of = [&](int64_t c) { return h->dense ? h->ld : hptr[(size_t)c + 1] - hptr[(size_t)c]; };
+
+    // ---- chunks: one for resident data, else ranges of coordinates of at most chunk_bytes ------------
+    h->streaming = !h->dense && h->opt.device_budget_bytes > 0 &&
+                   (size_t)h->nnz * 8u > h->opt.device_budget_bytes;
+    std::vector<snap_handle::Chunk> chunks;
+    if (!h->streaming) {
+        chunks.push_back({0, m, 0, h->nnz, 0, 0, 0, 0, 0});
+    } else {
+        if (A->mem != SNAP_MEM_HOST_PINNED) {
+            set_error("streaming needs the matrix arrays in pinned host memory (SNAP_MEM_HOST_PINNED)");
+            return SNAP_EINVAL;
+        }
+        const size_t chunk_bytes = h->opt.chunk_bytes ? h->opt.chunk_bytes : ((size_t)4 << 30);
+        const int64_t chunk_nnz = std::max<int64_t>(1, (int64_t)(chunk_bytes / 8));
+        int64_t c0 = 0;
+        while (c0 < m) {
+            int64_t c1 = c0 + 1;                       // at least one coordinate per chunk
+            while (c1 < m && hptr[(size_t)c1 + 1] - hptr[(size_t)c0] <= chunk_nnz) ++c1;
+            chunks.push_back({c0, c1, hptr[(size_t)c0], hptr[(size_t)c1], 0, 0, 0, 0, 0});
+            c0 = c1;
+        }
+        if (chunks.empty()) chunks.push_back({0, 0, 0, 0, 0, 0, 0, 0, 0});
+        h->host_ptr = A->ptr;
+        h->host_idx = A->idx;
+        h->host_val = A->val;
+    }
+    h->n_chunks = (int64_t)chunks.size();
+    std::vector<int64_t> large, seg_off;
+    seg_off.push_back(0);
+    int64_t small_nnz = 0, n_small_total = 0;
+    for (auto& ck : chunks) {
+        ck.l0 = (int64_t)large.size();
+        for (int64_t c = ck.c0; c < ck.c1; ++c) {
+            const int64_t len = len_of(c);
+            if (h->dense || len > h->small_max) {
+                const int64_t ns = (len + h->seg - 1) / h->seg;
+                ++ck.n_large;
+                ck.n_items += 2 * ns;
+                large.push_back(c);
+                seg_off.push_back(seg_off.back() + ns);
+            } else {
+                ++ck.n_small;
+                small_nnz += len;
+            }
+        }
+        ck.l1 = (int64_t)large.size();
+        n_small_total += ck.n_small;
+        h->max_chunk_m = std::max(h->max_chunk_m, ck.c1 - ck.c0);
+        h->max_large = std::max(h->max_large, ck.n_large);
+        h->max_chunk_nnz = std::max(h->max_chunk_nnz, ck.nnz1 - ck.nnz0);
+    }
+    h->chunks = new (std::nothrow) snap_handle::Chunk[chunks.size()];
+    if (!h->chunks) return SNAP_ENOMEM;
+    std::copy(chunks.begin(), chunks.end(), h->chunks);
+    h->n_large_total = (int64_t)large.size();
+    h->n_seg_total = seg_off.back();
+    h->avg_small_len = n_small_total > 0 ? std::max(1.0, (double)small_nnz / (double)n_small_total) : 1.0;
+    h->nnz_small = small_nnz;
+    h->nnz_large = h->nnz - small_nnz;
+
+    // ---- device memory ---------------------------------------------------------------------------
+    if (h->streaming) {
+        SNAP_TRY(stream_alloc(h));
+    } else if (!h->dense) {
         SNAP_HIP(hipMalloc(&h->idx, (size_t)(h->nnz ? h->nnz : 1) * sizeof(uint32_t)));
         SNAP_HIP(hipMalloc(&h->val, (size_t)(h->nnz ? h->nnz : 1) * sizeof(float)));
         SNAP_HIP(hipMemcpyAsync(h->idx, A->idx, (size_t)h->nnz * sizeof(uint32_t), hipMemcpyDefault, h->compute));
@@ -142,30 +222,6 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     }
     SNAP_HIP(hipMalloc(&h->y, (size_t)(h->n ? h->n : 1) * sizeof(float)));
     SNAP_HIP(hipMemcpyAsync(h->y, y, (size_t)h->n * sizeof(float), hipMemcpyDefault, h->compute));
-
-    // ---- validation on the device: indices in range, labels +-1 where the loss needs them ---------
-    {
-        const int64_t minor = h->form == SNAP_PRIMAL ? h->n : h->d;
-        if (!h->dense && h->nnz > 0)
-            hipLaunchKernelGGL(k_check_indices, dim3(4096), dim3(256), 0, h->compute, (const int32_t*)h->idx, h->nnz,
-                               minor, h->status);
-        if (h->loss != SNAP_RIDGE && h->n > 0)
-            hipLaunchKernelGGL(k_check_labels, dim3(1024), dim3(256), 0, h->compute, h->y, h->n, h->status);
-        uint32_t st = 0;
-        SNAP_HIP(hipMemcpyAsync(&st, h->status, 4, hipMemcpyDeviceToHost, h->compute));
-        SNAP_HIP(hipStreamSynchronize(h->compute));
-        SNAP_TRY(fill_zero(h->status, 4, h->compute));
-        if (st & 1u) {
-            set_error("an index in idx is outside [0, %lld)", (long long)minor);
-            return SNAP_EINVAL;
-        }
-        if (st & 2u) {
-            set_error("labels must be +1 or -1 for this loss");
-            return SNAP_EINVAL;
-        }
-    }
-
-    // ---- state ---------------------------------------------------------------------------------
     SNAP_HIP(hipMalloc(&h->x, (size_t)(m ? m : 1) * sizeof(float)));
     SNAP_HIP(hipMalloc(&h->v, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
     SNAP_HIP(hipMalloc(&h->norms, (size_t)(m ? m : 1) * sizeof(float)));
@@ -178,34 +234,8 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_TRY(fill_zero(h->v, (size_t)h->vlen * sizeof(float), h->compute));
     SNAP_TRY(fill_zero(h->perm, (size_t)m * sizeof(uint32_t), h->compute));
     SNAP_TRY(fill_zero(h->keys, (size_t)m * sizeof(uint32_t), h->compute));
-    SNAP_TRY(compute_norms_and_classes(h));
-    if (h->kind == K_PRIMAL_LOGISTIC && !h->dense) SNAP_TRY(fold_labels(h, h->idx, h->nnz, h->compute));
-
-    // ---- chunks and the static list of large coordinates (host planning) --------------------------
-    h->n_chunks = 1;
-    h->chunks = new (std::nothrow) snap_handle::Chunk[1];
-    if (!h->chunks) return SNAP_ENOMEM;
-    std::vector<int64_t> large, seg_off;
-    seg_off.push_back(0);
-    snap_handle::Chunk& ck = h->chunks[0];
-    ck = {0, m, 0, h->nnz, 0, 0, 0};
-    for (int64_t c = 0; c < m; ++c) {
-        const int64_t len = h->dense ? h->ld : hptr[(size_t)c + 1] - hptr[(size_t)c];
-        if (h->dense || len > h->small_max) {
-            ++ck.n_large;
-            ck.n_items += 2 * ((len + h->seg - 1) / h->seg);
-            large.push_back(c);
-            seg_off.push_back(seg_off.back() + ((len + h->seg - 1) / h->seg));
-        } else {
-            ++ck.n_small;
-        }
-    }
-    h->max_chunk_m = m;
-    h->max_large = ck.n_large;
-    h->n_large_total = (int64_t)large.size();
-    h->n_seg_total = seg_off.back();
-    SNAP_TRY(sorter_alloc(h->sorter, m));
-    SNAP_HIP(hipMalloc(&h->order, (size_t)(m ? m : 1) * sizeof(uint32_t)));
+    SNAP_TRY(sorter_alloc(h->sorter, h->max_chunk_m));
+    SNAP_HIP(hipMalloc(&h->order, (size_t)(h->max_chunk_m ? h->max_chunk_m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->lstate, (size_t)(h->max_large + 1) * sizeof(LargeState)));
     SNAP_HIP(hipMalloc(&h->item_start, (size_t)(h->max_large + 2) * sizeof(int64_t)));
     SNAP_HIP(hipMalloc(&h->large_list, (large.size() + 1) * sizeof(int64_t)));
@@ -214,37 +244,68 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_HIP(hipMemcpyAsync(h->large_list, large.data(), large.size() * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
     SNAP_HIP(hipMemcpyAsync(h->large_seg_off, seg_off.data(), seg_off.size() * sizeof(int64_t), hipMemcpyHostToDevice,
                             h->compute));
+
+    // ---- one pass over the data: validation, norms, classes, access counts --------------------------
+    h->adaptive = h->opt.adaptive != 2;
+    h->damping = h->opt.damping > 0.0f ? h->opt.damping : 1.0f;
+    h->inflight_floor = WAVE;
+    const bool auto_cap = h->opt.max_inflight_nnz <= 0 && !h->dense;
+    CreatePass cp{nullptr, h->form == SNAP_PRIMAL ? h->n : h->d};
+    if (auto_cap && h->vlen > 0) {
+        SNAP_HIP(hipMalloc(&cp.freq, (size_t)h->vlen * sizeof(uint32_t)));
+        const int rc = fill_zero(cp.freq, (size_t)h->vlen * sizeof(uint32_t), h->compute);
+        if (rc != SNAP_OK) {
+            (void)hipFree(cp.freq);
+            return rc;
+        }
+    }
+    if (h->loss != SNAP_RIDGE && h->n > 0)
+        hipLaunchKernelGGL(k_check_labels, dim3(1024), dim3(256), 0, h->compute, h->y, h->n, h->status);
+    int rc = for_each_chunk(h, create_chunk, &cp, /*fold=*/false, /*profile=*/false);
+    uint32_t st = 0;
+    if (rc == SNAP_OK) {
+        hipError_t e = hipMemcpyAsync(&st, h->status, 4, hipMemcpyDeviceToHost, h->compute);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->compute);
+        if (e != hipSuccess) rc = hip_fail(e, "creation pass", __FILE__, __LINE__);
+    }
+    double eff = (double)h->vlen;
+    if (rc == SNAP_OK && cp.freq && !(st & 1u)) rc = access_moments(h, cp.freq, &eff);
+    (void)hipStreamSynchronize(h->compute);
+    (void)hipFree(cp.freq);
+    SNAP_TRY(rc);
+    SNAP_TRY(fill_zero(h->status, 4, h->compute));
+    if (st & 1u) {
+        set_error("an index in idx is outside [0, %lld)", (long long)cp.minor);
+        return SNAP_EINVAL;
+    }
+    if (st & 2u) {
+        set_error("labels must be +1 or -1 for this loss");
+        return SNAP_EINVAL;
+    }
+    if (!h->streaming && h->kind == K_PRIMAL_LOGISTIC && !h->dense) SNAP_TRY(fold_labels(h, h->idx, h->nnz, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));   // host vectors above go out of scope
 
     // ---- concurrency control ---------------------------------------------------------------------
-    h->adaptive = h->opt.adaptive != 2;
-    h->damping = h->opt.damping > 0.0f ? h->opt.damping : 1.0f;
-    {
-        int64_t small_nnz = 0;
-        if (!h->dense)
-            for (int64_t c = 0; c < m; ++c) {
-                const int64_t len = hptr[(size_t)c + 1] - hptr[(size_t)c];
-                if (len <= h->small_max) small_nnz += len;
-            }
-        h->avg_small_len = ck.n_small > 0 ? std::max(1.0, (double)small_nnz / (double)ck.n_small) : 1.0;
-        h->nnz_small = small_nnz;
-        h->nnz_large = h->nnz - small_nnz;
-    }
-    h->inflight_floor = WAVE;
-    if (h->opt.max_inflight_nnz > 0) {
-        h->inflight_nnz = h->opt.max_inflight_nnz;
-    } else if (h->dense) {
-        h->inflight_nnz = 0;                      // no cap; the adaptive check lowers it if needed
-    } else {
-        double eff = 0.0;
-        SNAP_TRY(effective_shared_length(h, &eff));
-        h->inflight_nnz = std::max<int64_t>(1, (int64_t)(0.25 * eff));
-    }
+    if (h->opt.max_inflight_nnz > 0) h->inflight_nnz = h->opt.max_inflight_nnz;
+    else if (h->dense) h->inflight_nnz = 0;       // no cap; the adaptive check lowers it if needed
+    else h->inflight_nnz = std::max<int64_t>(1, (int64_t)(0.25 * eff));
     if (h->adaptive) {
         SNAP_HIP(hipMalloc(&h->x_snap, (size_t)(m ? m : 1) * sizeof(float)));
         SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
     }
     return SNAP_OK;
+}
+
+// One chunk of an epoch: its permutation, then the SCD kernels.
+static int epoch_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void* arg) {
+    const uint64_t seed = *(const uint64_t*)arg;
+    const snap_handle::Chunk& ck = h->chunks[chunk];
+    const int64_t mc = ck.c1 - ck.c0;
+    if (mc == 0) return SNAP_OK;
+    const bool prof = h->opt.profile != 0 && !h->streaming;
+    SNAP_TRY(make_permutation(h, seed, (uint32_t)chunk, ck.c0, mc, h->keys + ck.c0, h->perm + ck.c0, h->order));
+    if (prof) SNAP_HIP(hipEventRecord(h->ev[1], h->compute));
+    return scd_run_chunk(h, cv, ck, h->order);
 }
 
 }  // namespace snap
@@ -299,10 +360,6 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
         set_error("supported pairs: (ridge, primal), (logistic, primal), (hinge, dual)");
         return SNAP_EUNSUPPORTED;
     }
-    if (o.device_budget_bytes != 0) {
-        set_error("streaming is not available in this build");
-        return SNAP_EUNSUPPORTED;
-    }
     snap_handle* h = new (std::nothrow) snap_handle();
     if (!h) {
         set_error("out of host memory");
@@ -349,11 +406,7 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         SNAP_HIP(hipMemcpyAsync(h->v_snap, h->v, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
     }
     if (prof) SNAP_HIP(hipEventRecord(h->ev[0], h->compute));
-    const snap_handle::Chunk& ck = h->chunks[0];
-    SNAP_TRY(make_permutation(h, perm_seed, 0u, 0, h->m, h->keys, h->perm, h->order));
-    if (prof) SNAP_HIP(hipEventRecord(h->ev[1], h->compute));
-    ChunkView cv{h->ptr, h->idx, h->val, 0, 0, h->m};
-    SNAP_TRY(scd_run_chunk(h, cv, ck, h->order));
+    SNAP_TRY(for_each_chunk(h, epoch_chunk, &perm_seed, /*fold=*/true, /*profile=*/prof));
     if (prof) {
         SNAP_HIP(hipEventRecord(h->ev[2], h->compute));
         h->stats_pending = true;
@@ -484,6 +537,25 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         set_error("null argument");
         return SNAP_EINVAL;
     }
+    if (h->stats_pending && h->streaming) {
+        SNAP_HIP(hipEventSynchronize(h->ev[2]));
+        SNAP_HIP(hipStreamSynchronize(h->copy));
+        float total = 0, copy = 0, scd = 0;
+        SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
+        if (h->chunk_events_valid)
+            for (int64_t ch = 0; ch < h->n_chunks; ++ch) {
+                float a = 0, b = 0;
+                SNAP_HIP(hipEventElapsedTime(&a, h->ev_chunk[4 * ch + 0], h->ev_chunk[4 * ch + 1]));
+                SNAP_HIP(hipEventElapsedTime(&b, h->ev_chunk[4 * ch + 2], h->ev_chunk[4 * ch + 3]));
+                copy += a;
+                scd += b;
+            }
+        h->stats.epoch_ms = total;
+        h->stats.copy_ms = copy;
+        h->stats.scd_ms = scd;
+        h->stats.perm_ms = h->stats.large_ms = h->stats.small_ms = 0;
+        h->stats_pending = false;
+    }
     if (h->stats_pending) {
         SNAP_HIP(hipEventSynchronize(h->ev[2]));
         float total = 0, perm = 0, scd = 0, large = 0, small = 0;
@@ -510,6 +582,19 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         h->stats.n_items += h->chunks[ch].n_items;
     }
     *out = h->stats;
+    return SNAP_OK;
+}
+
+int snap_get_chunks(snap_handle* h, int64_t* n_chunks, int64_t* bounds_out) {
+    if (!h || !n_chunks) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    *n_chunks = h->n_chunks;
+    if (bounds_out) {
+        for (int64_t ch = 0; ch < h->n_chunks; ++ch) bounds_out[ch] = h->chunks[ch].c0;
+        bounds_out[h->n_chunks] = h->m;
+    }
     return SNAP_OK;
 }
 

@@ -114,7 +114,7 @@ struct snap_handle {
     int64_t max_large = 0;
 
     // chunks (resident: one chunk covering everything)
-    struct Chunk { int64_t c0, c1, nnz0, nnz1, n_small, n_large, n_items; };
+    struct Chunk { int64_t c0, c1, nnz0, nnz1, n_small, n_large, n_items, l0, l1; };   // [l0,l1): its range of large_list
     Chunk* chunks = nullptr;
     int64_t n_chunks = 0;
     bool streaming = false;
@@ -124,14 +124,15 @@ struct snap_handle {
     uint32_t* buf_idx[2] = {nullptr, nullptr};
     float* buf_val[2] = {nullptr, nullptr};
     hipEvent_t ev_copied[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
-    bool buf_used[2] = {false, false};
+    int64_t buf_chunk[2] = {-1, -1};     // chunk held (or being loaded) by each buffer
+    bool buf_folded[2] = {false, false}; // labels already folded into that copy
     int64_t max_chunk_nnz = 0;
-    uint32_t* ybits = nullptr;
+    hipEvent_t* ev_chunk = nullptr;      // profile: 4 events per chunk (copy begin/end, compute begin/end)
+    bool chunk_events_valid = false;
 
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
     hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-    hipEvent_t* ev_copy_pairs = nullptr;
     // concurrency control and the adaptive safeguard
     int64_t inflight_nnz = 0;         // current cap on nonzeros in flight (<= 0: no cap)
     int64_t inflight_floor = 0;       // the cap is never halved below this
@@ -162,15 +163,23 @@ int make_permutation(snap_handle* h, uint64_t seed, uint32_t chunk, int64_t c0, 
 // scd.hip
 int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk& ck, const uint32_t* order);
 
+// stream.hip: run fn on every chunk in order (resident data: one chunk, no copies).  Streaming:
+// double-buffered copies on the copy stream overlap fn's work on the compute stream.
+using ChunkFn = int (*)(snap_handle* h, int64_t chunk, const ChunkView& cv, void* arg);
+int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profile);
+int stream_alloc(snap_handle* h);
+void stream_free(snap_handle* h);
+
 // linalg.hip
-int compute_norms_and_classes(snap_handle* h);
+int norms_and_classes_chunk(snap_handle* h, const ChunkView& cv);
+int count_accesses_chunk(snap_handle* h, const ChunkView& cv, int64_t count, uint32_t* freq);
+int access_moments(snap_handle* h, const uint32_t* freq, double* eff_len);
 int fold_labels(snap_handle* h, uint32_t* idx, int64_t count, hipStream_t s);
 int recompute_shared(snap_handle* h);
 int objective(snap_handle* h, double* primal, double* dual, double* gap);
 // the quantity the solver decreases (P in primal form, -D in dual form), vectors only
 int monitor_value(snap_handle* h, double* value);
-// (sum f)^2 / sum f^2 over the access counts f of the entries of v
-int effective_shared_length(snap_handle* h, double* out);
+
 int predict(snap_handle* h, const snap_matrix* X, float* out);
 int weights_to_host(snap_handle* h, float* w_out);
 int reducer_alloc(Reducer& r);

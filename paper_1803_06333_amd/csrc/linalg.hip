@@ -43,14 +43,15 @@ int fill_zero(void* p, size_t bytes, hipStream_t s) {
 
 // ---- squared norms and size classes -------------------------------------------------------------
 __global__ void __launch_bounds__(LTPB)
-k_coord_norms(const int64_t* __restrict__ ptr, const float* __restrict__ val, int64_t m, int64_t dense_len,
-              int64_t small_max, float* __restrict__ norms, uint8_t* __restrict__ cls) {
+k_coord_norms(const int64_t* __restrict__ ptr, const float* __restrict__ val, int64_t nnz_base, int64_t c0,
+              int64_t c1, int64_t dense_len, int64_t small_max, float* __restrict__ norms,
+              uint8_t* __restrict__ cls) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
     const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
-    for (int64_t c = wave0; c < m; c += nwaves) {
-        const int64_t s0 = dense_len > 0 ? c * dense_len : ptr[c];
-        const int64_t s1 = dense_len > 0 ? s0 + dense_len : ptr[c + 1];
+    for (int64_t c = c0 + wave0; c < c1; c += nwaves) {
+        const int64_t s0 = dense_len > 0 ? c * dense_len : ptr[c] - nnz_base;
+        const int64_t s1 = dense_len > 0 ? s0 + dense_len : ptr[c + 1] - nnz_base;
         double acc = 0.0;
         for (int64_t k = s0 + lane; k < s1; k += WAVE) acc += (double)val[k] * (double)val[k];
         acc = wave_sum_d(acc);
@@ -61,13 +62,13 @@ k_coord_norms(const int64_t* __restrict__ ptr, const float* __restrict__ val, in
     }
 }
 
-int compute_norms_and_classes(snap_handle* h) {
-    // resident data only; a streamed matrix is handled chunk by chunk by the caller
+int norms_and_classes_chunk(snap_handle* h, const ChunkView& cv) {
     const int64_t dense_len = h->dense ? h->ld : 0;
-    int grid = (int)((h->m + 3) / 4 < 16384 ? (h->m + 3) / 4 : 16384);
+    const int64_t mc = cv.c1 - cv.c0;
+    int grid = (int)((mc + 3) / 4 < 16384 ? (mc + 3) / 4 : 16384);
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(k_coord_norms, dim3(grid), dim3(LTPB), 0, h->compute, h->ptr, h->val, h->m, dense_len,
-                       h->small_max, h->norms, h->cls);
+    hipLaunchKernelGGL(k_coord_norms, dim3(grid), dim3(LTPB), 0, h->compute, cv.ptr, cv.val, cv.nnz_base, cv.c0,
+                       cv.c1, dense_len, h->small_max, h->norms, h->cls);
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
 }
@@ -135,6 +136,17 @@ k_dense_axpy_all(const float* __restrict__ A, int64_t m, int64_t len, const floa
     out[e] = (float)acc;
 }
 
+static int axpy_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void*) {
+    const float* ymul = h->form == SNAP_DUAL ? h->y : nullptr;
+    const snap_handle::Chunk& ck = h->chunks[chunk];
+    if (ck.nnz1 == ck.nnz0) return SNAP_OK;
+    const int64_t nb = (ck.nnz1 - ck.nnz0 + AXPY_BLOCK - 1) / AXPY_BLOCK;
+    hipLaunchKernelGGL(k_scatter_axpy, dim3((unsigned)nb), dim3(LTPB), 0, h->compute, cv.ptr, cv.idx, cv.val,
+                       cv.nnz_base, cv.c0, cv.c1, ck.nnz0, ck.nnz1, h->x, ymul, ~LABEL_BIT, h->v);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
 int recompute_shared(snap_handle* h) {
     const float* ymul = h->form == SNAP_DUAL ? h->y : nullptr;
     if (h->dense) {
@@ -143,18 +155,8 @@ int recompute_shared(snap_handle* h) {
         SNAP_HIP(hipGetLastError());
         return SNAP_OK;
     }
-    if (h->streaming) {
-        set_error("recomputing v is not available for a streamed matrix");
-        return SNAP_EUNSUPPORTED;
-    }
     SNAP_TRY(fill_zero(h->v, (size_t)h->vlen * sizeof(float), h->compute));
-    if (h->nnz > 0) {
-        const int64_t nb = (h->nnz + AXPY_BLOCK - 1) / AXPY_BLOCK;
-        hipLaunchKernelGGL(k_scatter_axpy, dim3((unsigned)nb), dim3(LTPB), 0, h->compute, h->ptr, h->idx, h->val,
-                           (int64_t)0, (int64_t)0, h->m, (int64_t)0, h->nnz, h->x, ymul, ~LABEL_BIT, h->v);
-        SNAP_HIP(hipGetLastError());
-    }
-    return SNAP_OK;
+    return for_each_chunk(h, axpy_chunk, nullptr, true, false);
 }
 
 // ---- per-coordinate dots with v (no update), fp64 ---------------------------------------------------
@@ -219,10 +221,10 @@ template <int KIND>
 __global__ void __launch_bounds__(LTPB)
 k_dots_large_partial(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const float* __restrict__ val,
                      int64_t nnz_base, int64_t dense_len, const int64_t* __restrict__ large_list,
-                     const int64_t* __restrict__ seg_off, int64_t l0, int64_t l1, int64_t seg_base,
+                     const int64_t* __restrict__ seg_off, int64_t l0, int64_t l1,
                      int64_t SEG, const float* __restrict__ v, const float* __restrict__ y, double* __restrict__ partial) {
     __shared__ double scratch[LTPB / WAVE];
-    const int64_t s = seg_base + blockIdx.x;
+    const int64_t s = seg_off[l0] + blockIdx.x;       // global segment number
     int64_t lo = l0, hi = l1;
     while (hi - lo > 1) {
         const int64_t mid = (lo + hi) >> 1;
@@ -250,35 +252,32 @@ __global__ void k_dots_large_finish(const int64_t* __restrict__ large_list, cons
 }
 
 template <int KIND>
-static int coord_dots_kind(snap_handle* h) {
+static int coord_dots_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void*) {
     const int64_t dense_len = h->dense ? h->ld : 0;
-    if (!h->dense && h->m > 0) {
-        int grid = (int)((h->m + 3) / 4 < 32768 ? (h->m + 3) / 4 : 32768);
-        hipLaunchKernelGGL((k_dots_small<KIND>), dim3(grid), dim3(LTPB), 0, h->compute, h->ptr, h->idx, h->val,
-                           (int64_t)0, (int64_t)0, h->m, h->cls, h->v, h->y, h->gdot);
+    const snap_handle::Chunk& ck = h->chunks[chunk];
+    const int64_t mc = cv.c1 - cv.c0;
+    if (!h->dense && mc > 0) {
+        int grid = (int)((mc + 3) / 4 < 32768 ? (mc + 3) / 4 : 32768);
+        hipLaunchKernelGGL((k_dots_small<KIND>), dim3(grid), dim3(LTPB), 0, h->compute, cv.ptr, cv.idx, cv.val,
+                           cv.nnz_base, cv.c0, cv.c1, h->cls, h->v, h->y, h->gdot);
     }
-    if (h->n_large_total > 0) {
-        const int64_t nseg = h->n_seg_total;
-        hipLaunchKernelGGL((k_dots_large_partial<KIND>), dim3((unsigned)nseg), dim3(LTPB), 0, h->compute, h->ptr,
-                           h->idx, h->val, (int64_t)0, dense_len, h->large_list, h->large_seg_off, (int64_t)0,
-                           h->n_large_total, (int64_t)0, h->seg, h->v, h->y, h->seg_partial);
-        hipLaunchKernelGGL(k_dots_large_finish, dim3((unsigned)((h->n_large_total + 255) / 256)), dim3(256), 0,
-                           h->compute, h->large_list, h->large_seg_off, (int64_t)0, h->n_large_total, h->seg_partial,
-                           h->gdot);
+    if (ck.l1 > ck.l0) {
+        const int64_t nseg = ck.n_items / 2;
+        hipLaunchKernelGGL((k_dots_large_partial<KIND>), dim3((unsigned)nseg), dim3(LTPB), 0, h->compute, cv.ptr,
+                           cv.idx, cv.val, cv.nnz_base, dense_len, h->large_list, h->large_seg_off, ck.l0, ck.l1,
+                           h->seg, h->v, h->y, h->seg_partial);
+        hipLaunchKernelGGL(k_dots_large_finish, dim3((unsigned)((ck.l1 - ck.l0 + 255) / 256)), dim3(256), 0,
+                           h->compute, h->large_list, h->large_seg_off, ck.l0, ck.l1, h->seg_partial, h->gdot);
     }
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
 }
 
 static int coord_dots(snap_handle* h) {
-    if (h->streaming) {
-        set_error("the duality gap is not available for a streamed matrix");
-        return SNAP_EUNSUPPORTED;
-    }
     switch (h->kind) {
-    case K_PRIMAL_RIDGE: return coord_dots_kind<K_PRIMAL_RIDGE>(h);
-    case K_PRIMAL_LOGISTIC: return coord_dots_kind<K_PRIMAL_LOGISTIC>(h);
-    default: return coord_dots_kind<K_DUAL_HINGE>(h);
+    case K_PRIMAL_RIDGE: return for_each_chunk(h, coord_dots_chunk<K_PRIMAL_RIDGE>, nullptr, true, false);
+    case K_PRIMAL_LOGISTIC: return for_each_chunk(h, coord_dots_chunk<K_PRIMAL_LOGISTIC>, nullptr, true, false);
+    default: return for_each_chunk(h, coord_dots_chunk<K_DUAL_HINGE>, nullptr, true, false);
     }
 }
 
@@ -467,31 +466,24 @@ k_freq_moments(const uint32_t* __restrict__ freq, int64_t count, double* __restr
     }
 }
 
+int count_accesses_chunk(snap_handle* h, const ChunkView& cv, int64_t count, uint32_t* freq) {
+    if (count > 0) hipLaunchKernelGGL(k_count_accesses, dim3(8192), dim3(256), 0, h->compute, cv.idx, count, freq);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
 // How many entries of v the accesses are effectively spread over: (sum f)^2 / sum f^2 with f the
 // number of nonzeros that touch each entry.  Uniform access gives the length of v; a few hot
 // entries (popular columns in the dual form) give a much smaller number.
-int effective_shared_length(snap_handle* h, double* out) {
-    if (h->dense || h->nnz == 0 || h->vlen == 0) {
-        *out = (double)h->vlen;
-        return SNAP_OK;
-    }
-    uint32_t* freq = nullptr;
-    SNAP_HIP(hipMalloc(&freq, (size_t)h->vlen * sizeof(uint32_t)));
-    int rc = fill_zero(freq, (size_t)h->vlen * sizeof(uint32_t), h->compute);
-    if (rc == SNAP_OK) {
-        hipLaunchKernelGGL(k_count_accesses, dim3(8192), dim3(256), 0, h->compute, h->idx, h->nnz, freq);
-        hipLaunchKernelGGL(k_freq_moments, dim3(REDUCE_BLOCKS), dim3(LTPB), 0, h->compute, freq, h->vlen, h->red.partial);
-        hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial, REDUCE_BLOCKS, h->red.result);
-        hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial + REDUCE_BLOCKS,
-                           REDUCE_BLOCKS, h->red.result + 1);
-        hipError_t e = hipMemcpyAsync(h->red.host, h->red.result, 2 * sizeof(double), hipMemcpyDeviceToHost, h->compute);
-        if (e == hipSuccess) e = hipStreamSynchronize(h->compute);
-        if (e != hipSuccess) rc = hip_fail(e, "effective_shared_length", __FILE__, __LINE__);
-    }
-    (void)hipFree(freq);
-    if (rc != SNAP_OK) return rc;
+int access_moments(snap_handle* h, const uint32_t* freq, double* eff_len) {
+    hipLaunchKernelGGL(k_freq_moments, dim3(REDUCE_BLOCKS), dim3(LTPB), 0, h->compute, freq, h->vlen, h->red.partial);
+    hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial, REDUCE_BLOCKS, h->red.result);
+    hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial + REDUCE_BLOCKS,
+                       REDUCE_BLOCKS, h->red.result + 1);
+    SNAP_HIP(hipMemcpyAsync(h->red.host, h->red.result, 2 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
     const double s1 = h->red.host[0], s2 = h->red.host[1];
-    *out = s2 > 0.0 ? s1 * s1 / s2 : (double)h->vlen;
+    *eff_len = s2 > 0.0 ? s1 * s1 / s2 : (double)h->vlen;
     return SNAP_OK;
 }
 

@@ -353,7 +353,7 @@ static int launch_kind(snap_handle* h, const ChunkView& cv, const snap_handle::C
                                h->item_start, ck.n_items, h->lstate, h->ticket, h->status, h->y, h->x, h->v, h->norms,
                                sp, dense_len, h->seg);
     }
-    if (h->opt.profile) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
+    if (h->opt.profile && !h->streaming) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
     if (ck.n_small > 0) {
         int64_t waves = std::min<int64_t>(ck.n_small, 256 * 32);
         if (h->inflight_nnz > 0)

@@ -1,0 +1,102 @@
+// Data streaming (Section 3.2, "Asynchronous Data Streaming"): device memory holds an active and a
+// swap buffer; while the kernels work on the chunk in the active buffer (compute stream) the next
+// chunk is copied from pinned host memory into the swap buffer (copy stream); events hand the
+// buffers over.  A chunk is a range of consecutive coordinates with its slices of idx and val;
+// ptr, y, the model and the shared vector stay resident.
+#include "common.h"
+
+namespace snap {
+
+int stream_alloc(snap_handle* h) {
+    const size_t cap = (size_t)(h->max_chunk_nnz > 0 ? h->max_chunk_nnz : 1);
+    for (int b = 0; b < 2; ++b) {
+        SNAP_HIP(hipMalloc(&h->buf_idx[b], cap * sizeof(uint32_t)));
+        SNAP_HIP(hipMalloc(&h->buf_val[b], cap * sizeof(float)));
+        SNAP_HIP(hipEventCreateWithFlags(&h->ev_copied[b], hipEventDisableTiming));
+        SNAP_HIP(hipEventCreateWithFlags(&h->ev_free[b], hipEventDisableTiming));
+        h->buf_chunk[b] = -1;
+        h->buf_folded[b] = false;
+    }
+    if (h->opt.profile) {
+        h->ev_chunk = new (std::nothrow) hipEvent_t[(size_t)(4 * h->n_chunks)]();
+        if (!h->ev_chunk) return SNAP_ENOMEM;
+        for (int64_t i = 0; i < 4 * h->n_chunks; ++i) SNAP_HIP(hipEventCreate(&h->ev_chunk[i]));
+    }
+    return SNAP_OK;
+}
+
+void stream_free(snap_handle* h) {
+    for (int b = 0; b < 2; ++b) {
+        (void)hipFree(h->buf_idx[b]);
+        (void)hipFree(h->buf_val[b]);
+        if (h->ev_copied[b]) (void)hipEventDestroy(h->ev_copied[b]);
+        if (h->ev_free[b]) (void)hipEventDestroy(h->ev_free[b]);
+        h->buf_idx[b] = nullptr;
+        h->buf_val[b] = nullptr;
+        h->ev_copied[b] = h->ev_free[b] = nullptr;
+    }
+    if (h->ev_chunk) {
+        for (int64_t i = 0; i < 4 * h->n_chunks; ++i)
+            if (h->ev_chunk[i]) (void)hipEventDestroy(h->ev_chunk[i]);
+        delete[] h->ev_chunk;
+        h->ev_chunk = nullptr;
+    }
+}
+
+// Enqueue the copy of chunk ch into buffer b on the copy stream, once the last user of b is done.
+static int enqueue_copy(snap_handle* h, int64_t ch, int b, bool profile) {
+    const snap_handle::Chunk& ck = h->chunks[ch];
+    const size_t count = (size_t)(ck.nnz1 - ck.nnz0);
+    SNAP_HIP(hipStreamWaitEvent(h->copy, h->ev_free[b], 0));
+    if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 0], h->copy));
+    if (count > 0) {
+        SNAP_HIP(hipMemcpyAsync(h->buf_idx[b], h->host_idx + ck.nnz0, count * sizeof(uint32_t), hipMemcpyHostToDevice,
+                                h->copy));
+        SNAP_HIP(hipMemcpyAsync(h->buf_val[b], h->host_val + ck.nnz0, count * sizeof(float), hipMemcpyHostToDevice,
+                                h->copy));
+    }
+    if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 1], h->copy));
+    SNAP_HIP(hipEventRecord(h->ev_copied[b], h->copy));
+    h->buf_chunk[b] = ch;
+    h->buf_folded[b] = false;
+    return SNAP_OK;
+}
+
+int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profile) {
+    if (!h->streaming) {
+        ChunkView cv{h->ptr, h->idx, h->val, 0, 0, h->m};
+        return fn(h, 0, cv, arg);
+    }
+    profile = profile && h->ev_chunk != nullptr;
+    const int64_t C = h->n_chunks;
+    int b = h->buf_chunk[0] == 0 ? 0 : (h->buf_chunk[1] == 0 ? 1 : -1);
+    if (b < 0 || profile) {          // (a profiled pass times its own copy of chunk 0)
+        b = b < 0 ? 0 : b;
+        SNAP_TRY(enqueue_copy(h, 0, b, profile));
+    }
+    for (int64_t ch = 0; ch < C; ++ch) {
+        const int nb = 1 - b;
+        const snap_handle::Chunk& ck = h->chunks[ch];
+        if (C > 1) {
+            // the next chunk (after the last one: chunk 0 again, for the next pass) goes to the other
+            // buffer while this one is processed
+            const int64_t next = ch + 1 < C ? ch + 1 : 0;
+            SNAP_TRY(enqueue_copy(h, next, nb, profile && ch + 1 < C));
+        }
+        SNAP_HIP(hipStreamWaitEvent(h->compute, h->ev_copied[b], 0));
+        if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 2], h->compute));
+        if (fold && h->kind == K_PRIMAL_LOGISTIC && !h->buf_folded[b]) {
+            SNAP_TRY(fold_labels(h, h->buf_idx[b], ck.nnz1 - ck.nnz0, h->compute));
+            h->buf_folded[b] = true;
+        }
+        ChunkView cv{h->ptr, h->buf_idx[b], h->buf_val[b], ck.nnz0, ck.c0, ck.c1};
+        SNAP_TRY(fn(h, ch, cv, arg));
+        if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 3], h->compute));
+        SNAP_HIP(hipEventRecord(h->ev_free[b], h->compute));
+        b = nb;
+    }
+    if (profile) h->chunk_events_valid = true;
+    return SNAP_OK;
+}
+
+}  // namespace snap
