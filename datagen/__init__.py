@@ -260,13 +260,16 @@ def _numeric_bin_pmf(f: int) -> np.ndarray:
     return np.maximum(p, 1e-12)
 
 
-def onehot_categories(n: int, d: int, seed: int, f: int, device, row0: int = 0, nrows: Optional[int] = None):
-    """Category (column offset inside field f) of rows [row0, row0+nrows): int64."""
+def onehot_categories(n: int, d: int, seed: int, f: int, device, row0: int = 0, nrows: Optional[int] = None,
+                      rows: Optional[torch.Tensor] = None):
+    """Category (column offset inside field f) of rows [row0, row0+nrows), or of the given int64
+    row numbers: int64."""
     starts, sizes = field_layout(d)
     nrows = n - row0 if nrows is None else nrows
     pmf = _numeric_bin_pmf(f) if f < N_NUMERIC else zipf_pmf(sizes[f], 1.2)
     table = cdf_table_u32(pmf, device)
-    return sample_table(table, stream_base(seed, 100 + f), _arange(nrows, device) + row0)
+    which = _arange(nrows, device) + row0 if rows is None else rows.to(device=device, dtype=torch.int64)
+    return sample_table(table, stream_base(seed, 100 + f), which)
 
 
 def onehot_fields(n=45_840_617, d=1_000_000, seed=CONFIG_SEED + 4, lam=1e-6, epochs=100,
