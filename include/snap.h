@@ -86,10 +86,20 @@ typedef struct {
     int64_t max_inflight_nnz;    /* cap on the nonzeros of coordinates in flight at once; 0 = automatic:
                                     a quarter of the effective length of v, (sum f)^2 / sum f^2 over the
                                     access counts f of the entries of v (dense data: no cap) */
-    int reserved[4];             /* must be zero */
+    const int64_t *group_bounds; /* optional (host memory, copied): n_groups+1 increasing coordinate
+                                    boundaries, group_bounds[0] = 0, last = number of coordinates, such that
+                                    the coordinates INSIDE a group have pairwise disjoint supports (the
+                                    columns of one one-hot encoded field).  Verified at creation.  Enables
+                                    the exact group-sweep epoch (primal form, sparse, resident): groups are
+                                    visited in order, all coordinates of a group at once -- identical to
+                                    visiting them one by one, since they do not interact -- with plain
+                                    coalesced updates of v instead of atomics. */
+    int64_t n_groups;            /* 0: no groups */
 } snap_options;
 
-/* Per-epoch figures gathered when options.profile = 1 (milliseconds of device time). */
+/* Per-epoch figures gathered when options.profile = 1 (milliseconds of device time).  With group
+ * sweeps "large" stands for the hot ranks handled by the row passes (large_ms = sum of the row-pass
+ * kernels, n_items = number of row passes), "small" for the rest, n_chunks for the groups. */
 typedef struct {
     float epoch_ms;        /* whole snap_epoch: permutation + SCD kernels (+ chunk waits) */
     float scd_ms;          /* the SCD epoch kernels alone (the dominant kernels) */
@@ -158,7 +168,9 @@ int snap_get_perm(snap_handle *h, uint32_t *perm_out, uint32_t *keys_out);
 int snap_get_epoch_stats(snap_handle *h, snap_epoch_stats *out);
 
 /* Streaming layout: *n_chunks receives the number of chunks (1 when resident); bounds_out, if not
- * NULL, receives n_chunks+1 coordinate boundaries (host int64): chunk k is [bounds[k], bounds[k+1]). */
+ * NULL, receives n_chunks+1 coordinate boundaries (host int64): chunk k is [bounds[k], bounds[k+1]).
+ * With group_bounds in force the groups are reported (they play the role of the chunks: visited in
+ * order, permutation inside each, the group index entering the key). */
 int snap_get_chunks(snap_handle *h, int64_t *n_chunks, int64_t *bounds_out);
 
 /* Number of coordinates m and length of v. */

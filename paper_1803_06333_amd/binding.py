@@ -37,7 +37,7 @@ class SnapOptions(C.Structure):
     _fields_ = [("form", C.c_int), ("device_budget_bytes", C.c_size_t), ("chunk_bytes", C.c_size_t),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p), ("refresh_v_every", C.c_int),
                 ("profile", C.c_int), ("adaptive", C.c_int), ("damping", C.c_float),
-                ("max_inflight_nnz", C.c_int64), ("reserved", C.c_int * 4)]
+                ("max_inflight_nnz", C.c_int64), ("group_bounds", C.c_void_p), ("n_groups", C.c_int64)]
 
 
 class SnapEpochStats(C.Structure):
@@ -60,10 +60,11 @@ def load_library():
     """Load the built HIP library; there is no fallback path."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = os.environ.get("SNAP_LIB_PATH", LIB_PATH)      # (override used for tuning builds)
+        if not os.path.exists(path):
             raise ImportError("libsnap.so is not built (%s); run `python -m paper_1803_06333_amd.build` or "
                               "__graft_entry__.build()" % LIB_PATH)
-        L = C.CDLL(LIB_PATH)
+        L = C.CDLL(path)
         L.snap_last_error.restype = C.c_char_p
         L.snap_destroy.restype = None
         L.snap_destroy.argtypes = [C.c_void_p]
@@ -124,7 +125,7 @@ class Solver:
     def __init__(self, layout: str, n_rows: int, n_cols: int, ptr, idx, val, y, loss: str, lam: float,
                  form: int = FORM_AUTO, device_budget_bytes: int = 0, chunk_bytes: int = 0, compute_stream: int = 0,
                  copy_stream: int = 0, refresh_v_every: int = 0, profile: bool = False, adaptive: bool = True,
-                 damping: float = 0.0, max_inflight_nnz: int = 0):
+                 damping: float = 0.0, max_inflight_nnz: int = 0, group_bounds=None):
         self._lib = load_library()
         self._h = C.c_void_p()
         if torch is not None and isinstance(val, torch.Tensor) and val.is_cuda:
@@ -138,6 +139,9 @@ class Solver:
         opt.compute_stream, opt.copy_stream = compute_stream or None, copy_stream or None
         opt.refresh_v_every, opt.profile = refresh_v_every, int(profile)
         opt.adaptive, opt.damping, opt.max_inflight_nnz = (1 if adaptive else 2), damping, max_inflight_nnz
+        if group_bounds is not None:
+            gb = np.ascontiguousarray(group_bounds, dtype=np.int64)
+            opt.group_bounds, opt.n_groups = gb.ctypes.data, gb.size - 1
         self._keep_stream = (self._keep, ky)
         _check(self._lib.snap_create(C.byref(sm), py, LOSSES[loss], lam, C.byref(opt), C.byref(self._h)))
         m, vl = C.c_int64(), C.c_int64()

@@ -74,6 +74,7 @@ static void destroy(snap_handle* h) {
     (void)hipFree(h->x_snap);
     (void)hipFree(h->v_snap);
     stream_free(h);
+    grouped_free(h);
     for (auto& e : h->ev)
         if (e) (void)hipEventDestroy(e);
     sorter_free(h->sorter);
@@ -293,6 +294,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
         SNAP_HIP(hipMalloc(&h->x_snap, (size_t)(m ? m : 1) * sizeof(float)));
         SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
     }
+    if (h->opt.n_groups > 0) SNAP_TRY(grouped_setup(h, hptr.data()));
     return SNAP_OK;
 }
 
@@ -340,11 +342,10 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
     }
     snap_options o{};
     if (opt) o = *opt;
-    for (int r : o.reserved)
-        if (r != 0) {
-            set_error("options.reserved must be zero");
-            return SNAP_EINVAL;
-        }
+    if (o.n_groups < 0 || (o.n_groups > 0 && !o.group_bounds)) {
+        set_error("n_groups must be non-negative and come with group_bounds");
+        return SNAP_EINVAL;
+    }
     int form = o.form;
     const bool row_coords = A->layout == SNAP_CSR || A->layout == SNAP_DENSE_ROWMAJOR;
     if (form == SNAP_FORM_AUTO) form = row_coords ? SNAP_DUAL : SNAP_PRIMAL;
@@ -406,7 +407,17 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         SNAP_HIP(hipMemcpyAsync(h->v_snap, h->v, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
     }
     if (prof) SNAP_HIP(hipEventRecord(h->ev[0], h->compute));
-    SNAP_TRY(for_each_chunk(h, epoch_chunk, &perm_seed, /*fold=*/true, /*profile=*/prof));
+    if (h->grouped) {
+        // exact group sweeps; the visiting order inside a group does not change the result and is
+        // only generated when snap_get_perm asks for it
+        if (prof) SNAP_HIP(hipEventRecord(h->ev[1], h->compute));
+        SNAP_TRY(grouped_epoch(h));
+        if (prof) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
+        h->perm_stale = true;
+        h->last_seed = perm_seed;
+    } else {
+        SNAP_TRY(for_each_chunk(h, epoch_chunk, &perm_seed, /*fold=*/true, /*profile=*/prof));
+    }
     if (prof) {
         SNAP_HIP(hipEventRecord(h->ev[2], h->compute));
         h->stats_pending = true;
@@ -523,10 +534,22 @@ int snap_get_perm(snap_handle* h, uint32_t* perm_out, uint32_t* keys_out) {
         set_error("null argument");
         return SNAP_EINVAL;
     }
+    if (h->grouped && h->perm_stale) {
+        for (int64_t g = 0; g < h->n_groups; ++g) {
+            const int64_t c0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - c0;
+            SNAP_TRY(make_permutation(h, h->last_seed, (uint32_t)g, c0, sz, h->keys + c0, h->perm + c0, nullptr));
+        }
+        h->perm_stale = false;
+    }
     SNAP_HIP(hipMemcpyAsync(perm_out, h->perm, (size_t)h->m * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
     if (keys_out)
         SNAP_HIP(hipMemcpyAsync(keys_out, h->keys, (size_t)h->m * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));
+    if (h->grouped) {
+        for (int64_t g = 0; g < h->n_groups; ++g)
+            for (int64_t c = h->gbounds_host[g]; c < h->gbounds_host[g + 1]; ++c) perm_out[c] += (uint32_t)h->gbounds_host[g];
+        return SNAP_OK;
+    }
     for (int64_t ch = 0; ch < h->n_chunks; ++ch)
         for (int64_t c = h->chunks[ch].c0; c < h->chunks[ch].c1; ++c) perm_out[c] += (uint32_t)h->chunks[ch].c0;
     return SNAP_OK;
@@ -556,6 +579,22 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         h->stats.perm_ms = h->stats.large_ms = h->stats.small_ms = 0;
         h->stats_pending = false;
     }
+    if (h->stats_pending && h->grouped) {
+        SNAP_HIP(hipEventSynchronize(h->ev[2]));
+        float total = 0, rows = 0;
+        SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
+        if (h->ev_group)
+            for (int i = 0; i < h->n_row_passes; ++i) {
+                float t = 0;
+                SNAP_HIP(hipEventElapsedTime(&t, h->ev_group[2 * i], h->ev_group[2 * i + 1]));
+                rows += t;
+            }
+        h->stats.epoch_ms = h->stats.scd_ms = total;
+        h->stats.large_ms = rows;              // the row passes
+        h->stats.small_ms = total - rows;      // column-wise sums of the short coordinates + step kernels
+        h->stats.perm_ms = h->stats.copy_ms = 0;
+        h->stats_pending = false;
+    }
     if (h->stats_pending) {
         SNAP_HIP(hipEventSynchronize(h->ev[2]));
         float total = 0, perm = 0, scd = 0, large = 0, small = 0;
@@ -581,6 +620,14 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         h->stats.n_large += h->chunks[ch].n_large;
         h->stats.n_items += h->chunks[ch].n_items;
     }
+    if (h->grouped) {          // group sweeps: "large" = hot ranks (row passes), "small" = the rest, items = row passes
+        h->stats.n_chunks = h->n_groups;
+        h->stats.n_large = h->g_hot_coords;
+        h->stats.n_small = h->m - h->g_hot_coords;
+        h->stats.nnz_large = h->g_hot_nnz;
+        h->stats.nnz_small = h->nnz - h->g_hot_nnz;
+        h->stats.n_items = h->n_row_passes;
+    }
     *out = h->stats;
     return SNAP_OK;
 }
@@ -589,6 +636,11 @@ int snap_get_chunks(snap_handle* h, int64_t* n_chunks, int64_t* bounds_out) {
     if (!h || !n_chunks) {
         set_error("null argument");
         return SNAP_EINVAL;
+    }
+    if (h->grouped) {
+        *n_chunks = h->n_groups;
+        if (bounds_out) std::copy(h->gbounds_host, h->gbounds_host + h->n_groups + 1, bounds_out);
+        return SNAP_OK;
     }
     *n_chunks = h->n_chunks;
     if (bounds_out) {

@@ -29,7 +29,7 @@ constexpr int TPB = 256;                 // threads per workgroup of the epoch k
 constexpr int WAVES_PER_WG = TPB / WAVE;
 // A coordinate with more nonzeros than SMALL_MAX is split into segments of SEG nonzeros, one
 // workgroup each (two phases: partial dots, then scatter).
-constexpr int64_t SEG_DEFAULT = 8192;
+constexpr int64_t SEG_DEFAULT = 16384;
 constexpr int64_t SMALL_MAX_DEFAULT = 4096;
 constexpr uint32_t LABEL_BIT = 0x80000000u;   // primal logistic: sign of y folded into the row index
 constexpr uint32_t SPIN_LIMIT = 1u << 22;     // bounded wait of a scatter item for its coordinate's step
@@ -130,6 +130,27 @@ struct snap_handle {
     hipEvent_t* ev_chunk = nullptr;      // profile: 4 events per chunk (copy begin/end, compute begin/end)
     bool chunk_events_valid = false;
 
+    // exact group sweeps (coordinates of a group have disjoint supports)
+    bool grouped = false;
+    bool unit_values = false;         // every stored value is 1.0: no per-row value arrays
+    int64_t n_groups = 0, n_pad = 0;  // n_pad: row stride of the per-group row maps (multiple of 4)
+    int64_t* gbounds_host = nullptr;  // [n_groups+1]
+    int* ghot_host = nullptr;         // [n_groups] number of hot (LDS-accumulated) ranks per group
+    uint32_t* rowmap = nullptr;       // [n_groups][n_pad]: (label bit | rank of the row's coordinate in the group)
+    float* rowval = nullptr;          // [n_groups][n_pad] values (null when unit_values)
+    uint32_t* rank_of = nullptr;      // [m] rank of a coordinate inside its group (by decreasing length)
+    uint32_t* coord_of = nullptr;     // [m] coordinate at (group start + rank)
+    float* gdelta = nullptr;          // [m] step of (group start + rank), read by the next row pass
+    float* gacc = nullptr;            // [2][m] sums of the cold ranks (gathered column-wise)
+    void* gpartial = nullptr;         // [row-pass workgroups][2*hot] per-workgroup partial sums (int64 fixed point)
+    int gscale_exp = 0;               // largest |value| <= 2^gscale_exp
+    int64_t gpartial_stride = 0;
+    hipEvent_t* ev_group = nullptr;   // profile: begin/end of every row pass
+    int n_row_passes = 0;
+    int64_t g_hot_coords = 0, g_hot_nnz = 0;
+    bool perm_stale = false;          // grouped mode makes the visiting order only on request
+    uint64_t last_seed = 0;
+
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
     hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
@@ -167,6 +188,11 @@ int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk&
 // double-buffered copies on the copy stream overlap fn's work on the compute stream.
 using ChunkFn = int (*)(snap_handle* h, int64_t chunk, const ChunkView& cv, void* arg);
 int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profile);
+// grouped.hip
+int grouped_setup(snap_handle* h, const int64_t* hptr);
+int grouped_epoch(snap_handle* h);
+void grouped_free(snap_handle* h);
+
 int stream_alloc(snap_handle* h);
 void stream_free(snap_handle* h);
 

@@ -14,86 +14,10 @@
 //          that flag.  A waiting workgroup only ever waits for workgroups that drew an earlier
 //          ticket and are therefore already running, so the wait always ends; it is bounded by
 //          SPIN_LIMIT all the same and raises the handle's status word instead of hanging.
-#include "common.h"
+#include "scd_device.h"
 #include <algorithm>
 
 namespace snap {
-
-struct StepParams {
-    double lambda;
-    double inv_n;     // 1/n
-    double lam_n;     // lambda * n
-    double damping;   // in (0,1]: the step is scaled by it (Section 3.1, adaptive damping)
-};
-
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int off = WAVE / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, WAVE);
-    return x;
-}
-
-__device__ __forceinline__ float load_shared(const float* v, uint32_t r) {
-    // relaxed device-scope load: sees the other compute dies' atomic updates of v
-    return __hip_atomic_load(v + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Contribution of one nonzero (value a, shared entry vv, label yy) to the two sums of the step.
-template <int KIND>
-__device__ __forceinline__ void accumulate(float a, float vv, float yy, float& g, float& h) {
-    if (KIND == K_PRIMAL_RIDGE) {
-        g += a * (vv - yy);                       // loss' = v - y ; loss'' = 1 (h comes from the norm)
-    } else if (KIND == K_PRIMAL_LOGISTIC) {
-        const float e = __expf(yy * vv);          // p = sigmoid(-y v) = 1/(1+e)
-        const float p = 1.0f / (1.0f + e);
-        g -= a * yy * p;                          // loss'  = -y p
-        h += a * a * (p - p * p);                 // loss'' = p (1 - p)
-    } else {
-        g += a * vv;                              // x_i . v
-    }
-}
-
-// The scalar step.  Returns the new value of the coordinate; `mult` receives the multiplier of a_j
-// that is added to v: the change actually applied to the fp32 coordinate (times y_i in the hinge
-// dual), so that v keeps tracking A x as closely as fp32 allows.
-template <int KIND>
-__device__ __forceinline__ float take_step(double g, double h, float xc, float norm, float yc,
-                                           const StepParams& sp, float& mult) {
-    float xn;
-    if (KIND == K_PRIMAL_RIDGE || KIND == K_PRIMAL_LOGISTIC) {
-        const double G = g * sp.inv_n + sp.lambda * (double)xc;
-        const double H = (KIND == K_PRIMAL_RIDGE ? (double)norm : h) * sp.inv_n + sp.lambda;
-        xn = (float)((double)xc - sp.damping * G / H);
-        mult = (float)((double)xn - (double)xc);
-    } else {
-        double anew;
-        if (norm == 0.0f) {
-            anew = 1.0;                                   // empty row: dD/dalpha = 1/n > 0
-        } else {
-            const double m = (double)yc * g / sp.lam_n;   // y_i x_i.w
-            const double q = (double)norm / sp.lam_n;
-            anew = (double)xc + (1.0 - m) / q;
-            anew = anew < 0.0 ? 0.0 : (anew > 1.0 ? 1.0 : anew);
-        }
-        anew = (double)xc + sp.damping * (anew - (double)xc);   // stays inside the box
-        xn = (float)anew;
-        mult = (float)(((double)xn - (double)xc) * (double)yc);
-    }
-    return xn;
-}
-
-template <int KIND>
-__device__ __forceinline__ void decode(uint32_t raw, uint32_t& r, float& yy, const float* __restrict__ y) {
-    if (KIND == K_PRIMAL_LOGISTIC) {
-        r = raw & ~LABEL_BIT;
-        yy = (raw & LABEL_BIT) ? -1.0f : 1.0f;
-    } else if (KIND == K_PRIMAL_RIDGE) {
-        r = raw;
-        yy = y[r];
-    } else {
-        r = raw;
-        yy = 0.0f;
-    }
-}
 
 // ---- small coordinates: one wavefront each ----------------------------------------------------
 template <int KIND>
@@ -186,7 +110,21 @@ k_large_prepare(const int64_t* __restrict__ ptr, int64_t c0, const uint32_t* __r
     if (threadIdx.x == 0) *ticket = 0u;
 }
 
-constexpr int UNROLL = 4;
+#ifndef SNAP_UNROLL
+#define SNAP_UNROLL 4
+#endif
+constexpr int UNROLL = SNAP_UNROLL;
+
+// index / value streams are read once per pass: load them with the non-temporal hint so that they
+// do not push the lines of v out of the caches
+template <typename T>
+__device__ __forceinline__ T stream_load(const T* p) {
+#ifdef SNAP_NO_NT
+    return *p;
+#else
+    return __builtin_nontemporal_load(p);
+#endif
+}
 
 template <int KIND, bool DENSE>
 __global__ void __launch_bounds__(TPB)
@@ -237,12 +175,12 @@ k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_la
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     const int64_t eu = e + u * TPB;
-                    a[u] = valp[eu];
+                    a[u] = stream_load(valp + eu);
                     if (DENSE) {
                         r[u] = (uint32_t)eu;
                         yy[u] = KIND == K_DUAL_HINGE ? 0.0f : y[r[u]];
                     } else {
-                        decode<KIND>(idxp[eu], r[u], yy[u], y);
+                        decode<KIND>(stream_load(idxp + eu), r[u], yy[u], y);
                     }
                 }
 #pragma unroll
@@ -319,8 +257,9 @@ k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_la
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const int64_t eu = e + u * TPB;
-                a[u] = valp[eu];
-                r[u] = DENSE ? (uint32_t)eu : (idxp[eu] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu));
+                a[u] = stream_load(valp + eu);
+                r[u] = DENSE ? (uint32_t)eu
+                             : (stream_load(idxp + eu) & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu));
             }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) unsafeAtomicAdd(v + r[u], mult * a[u]);
@@ -367,11 +306,7 @@ static int launch_kind(snap_handle* h, const ChunkView& cv, const snap_handle::C
 }
 
 int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk& ck, const uint32_t* order) {
-    StepParams sp;
-    sp.lambda = h->lambda;
-    sp.inv_n = 1.0 / (double)h->n;
-    sp.lam_n = h->lambda * (double)h->n;
-    sp.damping = (double)h->damping;
+    const StepParams sp = make_step_params(h);
     if (ck.n_items > 0x7FFFFFFFll || ck.n_small / WAVES_PER_WG > 0x7FFFFFFFll) {
         set_error("chunk too large for one launch");
         return SNAP_EINVAL;

@@ -306,3 +306,65 @@ def test_streaming_needs_pinned_memory():
     with pytest.raises(snap.SnapError) as e:
         snap.Solver.from_problem(p, device_budget_bytes=1 << 10, chunk_bytes=1 << 16)
     assert e.value.code == -1
+
+
+# ---------------------------------------------------------------------------------------------
+# exact group sweeps: the coordinates of one group (the columns of a one-hot field) do not share
+# rows, so a sweep over the groups equals sequential SCD visiting "group 0, group 1, ..." -- the
+# oracle with those groups as chunks -- update for update, not just in the limit
+def _onehot_variant(loss, unit):
+    p = datagen.onehot_fields(n=150_000, d=4_000, lam=1e-4, seed=91)
+    rng = np.random.default_rng(4)
+    if not unit:
+        p.val = torch.from_numpy((0.5 + rng.random(p.nnz)).astype(np.float32))
+    if loss == "ridge":
+        p.loss = "ridge"
+        p.y = torch.from_numpy(rng.standard_normal(p.n).astype(np.float32))
+    return p
+
+
+@pytest.mark.parametrize("loss,unit", [("logistic", True), ("logistic", False), ("ridge", True), ("ridge", False)])
+def test_group_sweeps_equal_sequential_oracle(loss, unit):
+    p = _onehot_variant(loss, unit)
+    groups = p.meta["field_starts"] + [p.d]
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    g = gpu_solver(p, group_bounds=groups)
+    assert g.chunk_bounds() == groups
+    o = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=groups)
+    for e in range(6):
+        g.epoch(e)
+        o.epoch(e)
+        _, x = g.model()
+        # same trajectory as the sequential oracle (fp32 against fp64)
+        assert relnorm(x, o.x) <= 2e-5, "model differs from the sequential oracle after epoch %d" % e
+        assert relnorm(g.shared(), o.v) <= 2e-5
+        assert rel(g.objective(), o.primal()) <= 1e-5
+        assert g.epoch_stats()["rejected"] == 0
+    assert np.array_equal(g.perm().astype(np.int64), o.last_perm)
+    assert rel(g.duality_gap(), o.gap()) <= 1e-3        # squared gradient norm, amplifies fp32 differences
+    # continue to convergence of the gap
+    for e in range(6, 40):
+        g.epoch(e)
+        o.epoch(e)
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    g.close()
+
+
+def test_group_sweeps_reject_overlapping_groups():
+    p = problem("cfg1_sparse_logistic")                  # uniform columns: any two groups of columns overlap
+    with pytest.raises(snap.SnapError) as e:
+        gpu_solver(p, group_bounds=[0, 500, 1000])
+    assert e.value.code == -1
+    with pytest.raises(snap.SnapError) as e:
+        gpu_solver(p, group_bounds=[0, 500, 999])
+    assert e.value.code == -1
+    # one coordinate per group is always valid (and equals the plain sequential order of the groups)
+    q = datagen.uniform_sparse_logistic(n=2000, d=60, k=5, seed=3)
+    g = gpu_solver(q, group_bounds=list(range(61)))
+    o = oracle.Solver(oracle.Matrix.from_problem(q), q.y.numpy(), q.loss, q.lam, chunk_bounds=list(range(61)))
+    for e in range(5):
+        g.epoch(e)
+        o.epoch(e)
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    g.close()
