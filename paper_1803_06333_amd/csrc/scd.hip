@@ -6,8 +6,8 @@
 // The paper's solver gives every coordinate one thread block.  On a 256-CU part with click-log
 // data (a few columns holding a fifth of all rows each, a million columns of a few hundred) that
 // leaves the epoch waiting for a handful of blocks, so coordinates are handled in two classes:
-//   small  (<= SMALL_MAX nonzeros): one 64-wide wavefront per coordinate, four per workgroup;
-//   large  (>  SMALL_MAX nonzeros): split into segments of SEG nonzeros.  Every segment is two
+//   small  (<= small_max = 4096 nonzeros): one 64-wide wavefront per coordinate, four per workgroup;
+//   large  (longer): split into segments of seg = 16384 nonzeros.  Every segment is two
 //          work items, "dot" and "scatter".  Workgroups draw items from one atomic ticket counter
 //          in epoch order; the dot items of a coordinate add their partial sums into its state and
 //          the last one to arrive takes the step and publishes delta; a scatter item waits for
