@@ -77,7 +77,7 @@ typedef struct {
     void *copy_stream;           /* hipStream_t for chunk copies, or NULL: own stream */
     int refresh_v_every;         /* recompute v = A x every this many epochs; 0 = never */
     int profile;                 /* 1: bracket each epoch's SCD kernels with HIP events */
-    int adaptive;                /* 0: default (= on), 1: on, 2: off.  On: after every epoch the
+    int adaptive;                /* 0: default (on; off with group_bounds), 1: on, 2: off.  On: after every epoch the
                                     objective is evaluated; if it got worse the epoch's updates are
                                     discarded, the number of nonzeros in flight is halved and, once that
                                     is at its floor, the damping is halved (Section 3.1, "Adaptive

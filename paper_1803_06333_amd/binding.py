@@ -124,7 +124,7 @@ class Solver:
 
     def __init__(self, layout: str, n_rows: int, n_cols: int, ptr, idx, val, y, loss: str, lam: float,
                  form: int = FORM_AUTO, device_budget_bytes: int = 0, chunk_bytes: int = 0, compute_stream: int = 0,
-                 copy_stream: int = 0, refresh_v_every: int = 0, profile: bool = False, adaptive: bool = True,
+                 copy_stream: int = 0, refresh_v_every: int = 0, profile: bool = False, adaptive=None,
                  damping: float = 0.0, max_inflight_nnz: int = 0, group_bounds=None):
         self._lib = load_library()
         self._h = C.c_void_p()
@@ -138,7 +138,8 @@ class Solver:
         opt.form, opt.device_budget_bytes, opt.chunk_bytes = form, device_budget_bytes, chunk_bytes
         opt.compute_stream, opt.copy_stream = compute_stream or None, copy_stream or None
         opt.refresh_v_every, opt.profile = refresh_v_every, int(profile)
-        opt.adaptive, opt.damping, opt.max_inflight_nnz = (1 if adaptive else 2), damping, max_inflight_nnz
+        opt.adaptive = 0 if adaptive is None else (1 if adaptive else 2)
+        opt.damping, opt.max_inflight_nnz = damping, max_inflight_nnz
         if group_bounds is not None:
             gb = np.ascontiguousarray(group_bounds, dtype=np.int64)
             opt.group_bounds, opt.n_groups = gb.ctypes.data, gb.size - 1

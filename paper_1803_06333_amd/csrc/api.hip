@@ -247,7 +247,8 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
                             h->compute));
 
     // ---- one pass over the data: validation, norms, classes, access counts --------------------------
-    h->adaptive = h->opt.adaptive != 2;
+    // default: on for the asynchronous epoch; off for group sweeps, which are exact (no asynchrony to guard)
+    h->adaptive = h->opt.adaptive == 1 || (h->opt.adaptive == 0 && h->opt.n_groups == 0);
     h->damping = h->opt.damping > 0.0f ? h->opt.damping : 1.0f;
     h->inflight_floor = WAVE;
     const bool auto_cap = h->opt.max_inflight_nnz <= 0 && !h->dense;

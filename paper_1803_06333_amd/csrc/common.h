@@ -141,7 +141,6 @@ struct snap_handle {
     uint32_t* rank_of = nullptr;      // [m] rank of a coordinate inside its group (by decreasing length)
     uint32_t* coord_of = nullptr;     // [m] coordinate at (group start + rank)
     float* gdelta = nullptr;          // [m] step of (group start + rank), read by the next row pass
-    float* gacc = nullptr;            // [2][m] sums of the cold ranks (gathered column-wise)
     void* gpartial = nullptr;         // [row-pass workgroups][2*hot] per-workgroup partial sums (int64 fixed point)
     int gscale_exp = 0;               // largest |value| <= 2^gscale_exp
     int64_t gpartial_stride = 0;

@@ -13,9 +13,9 @@
 //     (v[r] += delta[g-1][rank]), evaluates loss' and loss'' at the new v[r] and adds them into the
 //     sums of group g's coordinate: hot ranks (the longest coordinates) accumulate in LDS, one
 //     partial array per workgroup, summed afterwards in a fixed order;
-//   - the remaining (short) coordinates of the group take their sums column-wise, one wavefront per
-//     coordinate, after the row pass;
-//   - a step kernel turns the sums into steps for the next row pass.
+//   - a second kernel sums the partials of the hot ranks, lets the remaining (short) coordinates of
+//     the group take their sums column-wise, one wavefront per coordinate, and turns all sums into
+//     the steps that the next row pass applies.
 // Traffic per group and row: two map entries, read + write of v = 16 bytes (+ values unless all 1).
 #include "scd_device.h"
 
@@ -36,7 +36,21 @@ constexpr uint32_t RANK_NONE = 0x7FFFFFFFu;      // row not covered by the group
 // accurate than fp32 accumulation.
 constexpr int HOT_MAX = 8192;                    // ranks accumulated in LDS (two int64 each: 128 KB)
 constexpr int ROW_TPB = 1024;
-constexpr int ROW_WGS = 256;                     // one workgroup per compute unit
+constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit
+static int row_wgs() {
+    static const int v = [] {
+        const char* e = getenv("SNAP_ROW_WGS");      // tuning knob
+        return e ? std::max(1, atoi(e)) : ROW_WGS_DEFAULT;
+    }();
+    return v;
+}
+static int hot_max() {
+    static const int v = [] {
+        const char* e = getenv("SNAP_HOT_MAX");      // tuning knob
+        return e ? std::max(4, std::min(HOT_MAX, atoi(e))) : HOT_MAX;
+    }();
+    return v;
+}
 
 // ---- creation --------------------------------------------------------------------------------------
 __global__ void k_fill_u32(uint32_t* p, size_t count, uint32_t value) {
@@ -104,12 +118,11 @@ void grouped_free(snap_handle* h) {
     (void)hipFree(h->rank_of);
     (void)hipFree(h->coord_of);
     (void)hipFree(h->gdelta);
-    (void)hipFree(h->gacc);
     (void)hipFree(h->gpartial);
     h->rowmap = nullptr;
     h->rowval = nullptr;
     h->rank_of = h->coord_of = nullptr;
-    h->gdelta = h->gacc = nullptr;
+    h->gdelta = nullptr;
     h->gpartial = nullptr;
 }
 
@@ -138,7 +151,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
 
     int lds_max = 0;
     SNAP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
-    const int hot_cap = std::max(4, std::min<int>(HOT_MAX, (lds_max - 1024) / 16));
+    const int hot_cap = std::max(4, std::min<int>(hot_max(), (lds_max - 1024) / 16));
     // ranks inside each group: coordinates by decreasing length (ties by index)
     std::vector<uint32_t> rank_of((size_t)m), coord_of((size_t)m);
     int max_hot = 1;
@@ -156,7 +169,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
         // hot ranks: accumulated in LDS by the row pass; a rank is worth a slot while its
         // coordinate is long enough to be hit by most workgroups
         int hot = 0;
-        while (hot < sz && hot < hot_cap && hptr[order[(size_t)hot] + 1] - hptr[order[(size_t)hot]] >= ROW_WGS / 2) ++hot;
+        while (hot < sz && hot < hot_cap && hptr[order[(size_t)hot] + 1] - hptr[order[(size_t)hot]] >= ROW_WGS_DEFAULT / 2) ++hot;
         h->ghot_host[g] = hot;
         max_hot = std::max(max_hot, hot);
     }
@@ -167,8 +180,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
     SNAP_HIP(hipMalloc(&h->rank_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->coord_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->gdelta, (size_t)(m ? m : 1) * sizeof(float)));
-    SNAP_HIP(hipMalloc(&h->gacc, (size_t)(m ? m : 1) * 2 * sizeof(float)));
-    SNAP_HIP(hipMalloc(&h->gpartial, (size_t)ROW_WGS * (size_t)h->gpartial_stride * sizeof(long long)));
+    SNAP_HIP(hipMalloc(&h->gpartial, (size_t)row_wgs() * (size_t)h->gpartial_stride * sizeof(long long)));
     SNAP_HIP(hipMalloc(&h->rowmap, (size_t)G * (size_t)h->n_pad * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->rowval, (size_t)G * (size_t)h->n_pad * sizeof(float)));
     SNAP_HIP(hipMalloc(&d_gb, (size_t)(G + 1) * sizeof(int64_t)));
@@ -364,51 +376,49 @@ k_group_rows(const uint32_t* __restrict__ map_prev, const float* __restrict__ va
     }
 }
 
-// ---- cold ranks: column-wise sums, one wavefront per coordinate --------------------------------------
-template <int KIND>
-__global__ void __launch_bounds__(256)
-k_group_cold(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const float* __restrict__ val,
-             const uint32_t* __restrict__ coord_of, int64_t g0, int64_t first_cold, int64_t group_size,
-             const float* __restrict__ v, const float* __restrict__ y, float* __restrict__ acc_g,
-             float* __restrict__ acc_h) {
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
-    const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
-    for (int64_t rk = first_cold + wave0; rk < group_size; rk += nwaves) {
-        const int64_t c = coord_of[g0 + rk];
-        float g = 0.0f, hh = 0.0f;
-        for (int64_t k = ptr[c] + lane; k < ptr[c + 1]; k += WAVE) {
-            uint32_t r;
-            float yy;
-            decode<KIND>(idx[k], r, yy, y);
-            accumulate<KIND>(val[k], v[r], yy, g, hh);      // v is not written while this kernel runs
-        }
-        g = wave_sum(g);
-        hh = wave_sum(hh);
-        if (lane == 0) {
-            acc_g[g0 + rk] = g;
-            acc_h[g0 + rk] = hh;
-        }
-    }
-}
-
-// ---- steps of one group ------------------------------------------------------------------------------
-// 32 ranks per workgroup, 8 threads per rank: each sums every 8th workgroup partial of a hot rank (in
-// a fixed order: reproducible), the eight parts are combined in LDS, then one thread takes the step.
+// ---- sums of the short coordinates and the steps of one group ------------------------------------------
+// One launch, two kinds of workgroups.  The first n_hot_blocks handle the hot ranks: 32 ranks per
+// workgroup, 8 threads per rank, each summing every 8th per-workgroup partial of the row pass (integer
+// sums: exact and independent of the order), combined in LDS, then one thread takes the step.  The
+// others handle the cold ranks: one wavefront per coordinate gathers its two sums column-wise (v is
+// not written while this kernel runs) and takes the step right away.
 constexpr int STEP_RANKS = 32, STEP_PARTS = 8;
 
 template <int KIND>
 __global__ void __launch_bounds__(STEP_RANKS * STEP_PARTS)
-k_group_step(const long long* __restrict__ partial, int64_t partial_stride, int n_wgs, int hot,
-             double inv_scale_g, double inv_scale_h,
-             const float* __restrict__ acc_g, const float* __restrict__ acc_h, const uint32_t* __restrict__ coord_of,
-             int64_t g0, int64_t group_size, float* __restrict__ x, const float* __restrict__ norms,
-             float* __restrict__ delta, StepParams sp) {
+k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, int n_wgs, int hot, int n_hot_blocks,
+               double inv_scale_g, double inv_scale_h, const int64_t* __restrict__ ptr,
+               const uint32_t* __restrict__ idx, const float* __restrict__ val, const float* __restrict__ v,
+               const float* __restrict__ y, const uint32_t* __restrict__ coord_of, int64_t g0, int64_t group_size,
+               float* __restrict__ x, const float* __restrict__ norms, float* __restrict__ delta, StepParams sp) {
     __shared__ long long sg[STEP_PARTS][STEP_RANKS], sh[STEP_PARTS][STEP_RANKS];
+    if ((int)blockIdx.x >= n_hot_blocks) {
+        const int lane = threadIdx.x & (WAVE - 1);
+        const int64_t wave0 = ((int64_t)(blockIdx.x - n_hot_blocks) * blockDim.x + threadIdx.x) / WAVE;
+        const int64_t nwaves = (int64_t)(gridDim.x - n_hot_blocks) * blockDim.x / WAVE;
+        for (int64_t rk = hot + wave0; rk < group_size; rk += nwaves) {
+            const int64_t c = coord_of[g0 + rk];
+            float g = 0.0f, hh = 0.0f;
+            for (int64_t k = ptr[c] + lane; k < ptr[c + 1]; k += WAVE) {
+                uint32_t r;
+                float yy;
+                decode<KIND>(idx[k], r, yy, y);
+                accumulate<KIND>(val[k], v[r], yy, g, hh);
+            }
+            g = wave_sum(g);
+            hh = wave_sum(hh);
+            if (lane == 0) {
+                float mult;
+                x[c] = take_step<KIND>((double)g, (double)hh, x[c], norms[c], 0.0f, sp, mult);
+                delta[g0 + rk] = mult;
+            }
+        }
+        return;
+    }
     const int lr = threadIdx.x % STEP_RANKS, part = threadIdx.x / STEP_RANKS;
     const int64_t rk = (int64_t)blockIdx.x * STEP_RANKS + lr;
-    long long Gi = 0, Hi = 0;                       // integer sums: exact, independent of the order
-    if (rk < group_size && rk < hot) {
+    long long Gi = 0, Hi = 0;
+    if (rk < hot) {
         for (int w = part; w < n_wgs; w += STEP_PARTS) {
             Gi += partial[(size_t)w * partial_stride + rk];
             if (KIND == K_PRIMAL_LOGISTIC) Hi += partial[(size_t)w * partial_stride + hot + rk];
@@ -417,25 +427,17 @@ k_group_step(const long long* __restrict__ partial, int64_t partial_stride, int 
     sg[part][lr] = Gi;
     sh[part][lr] = Hi;
     __syncthreads();
-    if (part != 0 || rk >= group_size) return;
-    double G, H;
-    if (rk < hot) {
-        Gi = 0;
-        Hi = 0;
+    if (part != 0 || rk >= hot) return;
+    Gi = 0;
+    Hi = 0;
 #pragma unroll
-        for (int p = 0; p < STEP_PARTS; ++p) {
-            Gi += sg[p][lr];
-            Hi += sh[p][lr];
-        }
-        G = (double)Gi * inv_scale_g;
-        H = (double)Hi * inv_scale_h;
-    } else {
-        G = (double)acc_g[g0 + rk];
-        H = (double)acc_h[g0 + rk];
+    for (int p = 0; p < STEP_PARTS; ++p) {
+        Gi += sg[p][lr];
+        Hi += sh[p][lr];
     }
     const int64_t c = coord_of[g0 + rk];
     float mult;
-    x[c] = take_step<KIND>(G, H, x[c], norms[c], 0.0f, sp, mult);
+    x[c] = take_step<KIND>((double)Gi * inv_scale_g, (double)Hi * inv_scale_h, x[c], norms[c], 0.0f, sp, mult);
     delta[g0 + rk] = mult;
 }
 
@@ -443,8 +445,6 @@ template <int KIND, bool UNIT>
 static int grouped_epoch_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
     const int64_t n = h->n, G = h->n_groups;
-    float* acc_g = h->gacc;
-    float* acc_h = h->gacc + h->m;
     long long* gpart = (long long*)h->gpartial;
     // power-of-two scales (exact in fp32): |a loss'| <= 2^e and a^2 loss'' <= 2^(2e) for the logistic loss,
     // at most 2^18 rows per workgroup, so the sums stay below 2^59; ridge terms are unbounded in
@@ -469,31 +469,28 @@ static int grouped_epoch_kind(snap_handle* h) {
         if (n > 0 && (scatter || histo)) {
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass], h->compute));
             if (scatter && histo)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true>), dim3(ROW_WGS), dim3(ROW_TPB), lds, h->compute,
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, n, gpart,
                                    h->gpartial_stride, scale_g, scale_h);
             else if (scatter)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false>), dim3(ROW_WGS), dim3(ROW_TPB), 0, h->compute,
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false>), dim3(row_wgs()), dim3(ROW_TPB), 0, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, 0, h->v, h->y, n, gpart,
                                    h->gpartial_stride, scale_g, scale_h);
             else
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true>), dim3(ROW_WGS), dim3(ROW_TPB), lds, h->compute,
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, n, gpart,
                                    h->gpartial_stride, scale_g, scale_h);
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
             ++n_pass;
         }
         if (last) break;
-        if (hot < sz) {
-            const int64_t cold = sz - hot;
-            int grid = (int)std::min<int64_t>((cold + 3) / 4, 16384);
-            hipLaunchKernelGGL((k_group_cold<KIND>), dim3(grid), dim3(256), 0, h->compute, h->ptr, h->idx, h->val,
-                               h->coord_of, g0, (int64_t)hot, sz, h->v, h->y, acc_g, acc_h);
-        }
-        hipLaunchKernelGGL((k_group_step<KIND>), dim3((unsigned)((sz + STEP_RANKS - 1) / STEP_RANKS)),
-                           dim3(STEP_RANKS * STEP_PARTS), 0, h->compute,
-                           gpart, h->gpartial_stride, ROW_WGS, hot, 1.0 / (double)scale_g, 1.0 / (double)scale_h, acc_g,
-                           acc_h, h->coord_of, g0, sz, h->x, h->norms, h->gdelta, sp);
+        const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
+        const int64_t cold = sz - hot;
+        const int n_cold_blocks = (int)std::min<int64_t>((cold + 3) / 4, 16384);
+        hipLaunchKernelGGL((k_group_finish<KIND>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
+                           dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, row_wgs(), hot,
+                           n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, h->ptr, h->idx, h->val, h->v,
+                           h->y, h->coord_of, g0, sz, h->x, h->norms, h->gdelta, sp);
         prev = g;
     }
     h->n_row_passes = n_pass;

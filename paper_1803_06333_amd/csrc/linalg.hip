@@ -288,7 +288,8 @@ enum ReduceMode {
     R_SQNORM = 2,        // a = x             : x^2
     R_SUM = 3,           // a = x             : x
     R_GRADSQ = 4,        // d = gdot, a = x   : (gdot*s0 + s1*x)^2
-    R_HINGE = 5          // d = gdot, b = y   : max(0, 1 - y gdot s0)
+    R_HINGE = 5,         // d = gdot, b = y   : max(0, 1 - y gdot s0)
+    R_LOSS_LOGISTIC_F32 = 6  // as R_LOSS_LOGISTIC with fp32 transcendentals (accept check of the epoch)
 };
 
 struct ReduceArgs {
@@ -308,6 +309,10 @@ __device__ __forceinline__ double reduce_term(const ReduceArgs& r, int64_t i) {
     if (MODE == R_LOSS_LOGISTIC) {
         const double t = -(double)r.b[i] * (double)r.a[i];
         return t > 0 ? t + log1p(exp(-t)) : log1p(exp(t));
+    }
+    if (MODE == R_LOSS_LOGISTIC_F32) {
+        const float t = -r.b[i] * r.a[i];
+        return (double)(t > 0.0f ? t + log1pf(__expf(-t)) : log1pf(__expf(t)));
     }
     if (MODE == R_SQNORM) return (double)r.a[i] * (double)r.a[i];
     if (MODE == R_SUM) return (double)r.a[i];
@@ -350,6 +355,9 @@ static int reduce_to(snap_handle* h, int mode, const ReduceArgs& r, int slot) {
     case R_SQNORM: hipLaunchKernelGGL((k_reduce_partial<R_SQNORM>), g, b, 0, h->compute, r, partial); break;
     case R_SUM: hipLaunchKernelGGL((k_reduce_partial<R_SUM>), g, b, 0, h->compute, r, partial); break;
     case R_GRADSQ: hipLaunchKernelGGL((k_reduce_partial<R_GRADSQ>), g, b, 0, h->compute, r, partial); break;
+    case R_LOSS_LOGISTIC_F32:
+        hipLaunchKernelGGL((k_reduce_partial<R_LOSS_LOGISTIC_F32>), g, b, 0, h->compute, r, partial);
+        break;
     default: hipLaunchKernelGGL((k_reduce_partial<R_HINGE>), g, b, 0, h->compute, r, partial); break;
     }
     hipLaunchKernelGGL(k_reduce_final, dim3(1), b, 0, h->compute, partial, REDUCE_BLOCKS, out);
@@ -425,7 +433,7 @@ int monitor_value(snap_handle* h, double* value) {
     double* res = h->red.host;
     if (h->form == SNAP_PRIMAL) {
         ReduceArgs r{h->v, h->y, nullptr, 0.0, 0.0, h->n};
-        SNAP_TRY(reduce_to(h, h->loss == SNAP_RIDGE ? R_LOSS_RIDGE : R_LOSS_LOGISTIC, r, 0));
+        SNAP_TRY(reduce_to(h, h->loss == SNAP_RIDGE ? R_LOSS_RIDGE : R_LOSS_LOGISTIC_F32, r, 0));
         ReduceArgs rx{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
         SNAP_TRY(reduce_to(h, R_SQNORM, rx, 1));
     } else {
