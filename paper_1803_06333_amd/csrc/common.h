@@ -133,10 +133,12 @@ struct snap_handle {
     // exact group sweeps (coordinates of a group have disjoint supports)
     bool grouped = false;
     bool unit_values = false;         // every stored value is 1.0: no per-row value arrays
-    int64_t n_groups = 0, n_pad = 0;  // n_pad: row stride of the per-group row maps (multiple of 4)
+    int64_t n_groups = 0, n_pad = 0;  // n_pad: row stride of the per-group row maps (multiple of 8)
     int64_t* gbounds_host = nullptr;  // [n_groups+1]
     int* ghot_host = nullptr;         // [n_groups] number of hot (LDS-accumulated) ranks per group
-    uint32_t* rowmap = nullptr;       // [n_groups][n_pad]: (label bit | rank of the row's coordinate in the group)
+    void* rowmap = nullptr;           // [n_groups][n_pad]: rank of the row's coordinate in the group (uint16 or uint32)
+    bool map16 = true;
+    uint8_t* ybits = nullptr;         // bit r = 1 when y[r] < 0
     float* rowval = nullptr;          // [n_groups][n_pad] values (null when unit_values)
     uint32_t* rank_of = nullptr;      // [m] rank of a coordinate inside its group (by decreasing length)
     uint32_t* coord_of = nullptr;     // [m] coordinate at (group start + rank)

@@ -8,7 +8,8 @@
 // What makes it fast on this part is that both inner loops turn from random 4-byte accesses to the
 // 183 MB vector v into coalesced streams over the rows:
 //   - every group g has a row map: rowmap[g][r] = rank of the coordinate of g that contains row r
-//     (ranks order the group's coordinates by decreasing length; bit 31 carries the label sign);
+//     (ranks order the group's coordinates by decreasing length); 16 bits per entry when no group has
+//     more than 65535 coordinates, else 32; the label signs sit in a bit array of their own;
 //   - one row pass reads v[r] once, applies the step of the previous group
 //     (v[r] += delta[g-1][rank]), evaluates loss' and loss'' at the new v[r] and adds them into the
 //     sums of group g's coordinate: hot ranks (the longest coordinates) accumulate in LDS, one
@@ -16,7 +17,8 @@
 //   - a second kernel sums the partials of the hot ranks, lets the remaining (short) coordinates of
 //     the group take their sums column-wise, one wavefront per coordinate, and turns all sums into
 //     the steps that the next row pass applies.
-// Traffic per group and row: two map entries, read + write of v = 16 bytes (+ values unless all 1).
+// Traffic per group and row: two map entries (2 + 2 bytes), read + write of v (8 bytes), one label bit
+// (+ values unless all 1).
 #include "scd_device.h"
 
 #include <algorithm>
@@ -28,13 +30,15 @@
 
 namespace snap {
 
-constexpr uint32_t RANK_MASK = 0x7FFFFFFFu;
-constexpr uint32_t RANK_NONE = 0x7FFFFFFFu;      // row not covered by the group
+constexpr uint32_t RANK_NONE = 0xFFFFFFFFu;      // row not covered by the group (all ones in either map width)
 // The sums of the hot ranks are kept in LDS as 64-bit fixed-point integers: integer LDS atomics run
-// more than twenty times faster here than ds_add_f32 (measured), the result does not depend on the
-// order of the additions (the epoch is bit-reproducible), and with 40 fractional bits it is more
-// accurate than fp32 accumulation.
+// more than twenty times faster here than ds_add_f32 (measured), and the result does not depend on
+// the order of the additions (the epoch is bit-reproducible).  A term is scaled so that it fits 32
+// bits (one v_cvt; a float-to-int64 conversion costs a dozen instructions and the row pass is
+// bound by instruction issue as much as by bandwidth): 24 fractional bits relative to the largest
+// |value|, the fp32 precision of the term itself; the 64-bit sum cannot overflow.
 constexpr int HOT_MAX = 8192;                    // ranks accumulated in LDS (two int64 each: 128 KB)
+constexpr int DELTA_LDS = 8192;                  // steps of the previous group kept in LDS (32 KB)
 constexpr int ROW_TPB = 1024;
 constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit
 static int row_wgs() {
@@ -56,6 +60,18 @@ static int hot_max() {
 __global__ void k_fill_u32(uint32_t* p, size_t count, uint32_t value) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
         p[i] = value;
+}
+
+// Largest |value| (bit order = value order for non-negative floats) and whether every value is 1.
+__global__ void k_value_stats(const float* __restrict__ val, int64_t nnz, uint32_t* flags) {
+    uint32_t mx = 0, not_one = 0;
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < nnz; k += (int64_t)gridDim.x * blockDim.x) {
+        const float a = val[k];
+        mx = max(mx, __float_as_uint(fabsf(a)));
+        not_one |= a != 1.0f ? 2u : 0u;
+    }
+    if (not_one) atomicOr(flags, 2u);
+    atomicMax(flags + 1, mx);
 }
 
 // For every nonzero: row map entry of its group <- rank of its coordinate.  A second writer of the
@@ -89,16 +105,23 @@ k_build_rowmap(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx
         const uint32_t old = atomicCAS(rowmap + slot, RANK_NONE, rank_of[l]);
         if (old != RANK_NONE) atomicOr(flags, 1u);
         if (rowval) rowval[slot] = val[k];
-        if (val[k] != 1.0f) atomicOr(flags, 2u);
-        atomicMax(flags + 1, __float_as_uint(fabsf(val[k])));      // largest magnitude (bit order = value order)
     }
 }
 
-__global__ void k_rowmap_labels(uint32_t* __restrict__ rowmap, int64_t n_groups, int64_t n, int64_t n_pad,
-                                const float* __restrict__ y) {
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += (int64_t)gridDim.x * blockDim.x) {
-        const uint32_t bit = y[r] < 0.0f ? LABEL_BIT : 0u;
-        for (int64_t g = 0; g < n_groups; ++g) rowmap[(size_t)g * n_pad + r] |= bit;
+__global__ void k_narrow_map(const uint32_t* __restrict__ wide, uint16_t* __restrict__ narrow, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        narrow[i] = (uint16_t)wide[i];            // ranks are below 65535; "none" (all ones) stays all ones
+}
+
+// bit (r & 7) of byte (r >> 3) = 1 when y[r] < 0
+__global__ void k_label_bits(const float* __restrict__ y, int64_t n, uint8_t* __restrict__ bits, int64_t n_bytes) {
+    for (int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; b < n_bytes; b += (int64_t)gridDim.x * blockDim.x) {
+        uint32_t w = 0;
+        for (int j = 0; j < 8; ++j) {
+            const int64_t r = 8 * b + j;
+            if (r < n && y[r] < 0.0f) w |= 1u << j;
+        }
+        bits[b] = (uint8_t)w;
     }
 }
 
@@ -115,6 +138,8 @@ void grouped_free(snap_handle* h) {
     h->ghot_host = nullptr;
     (void)hipFree(h->rowmap);
     (void)hipFree(h->rowval);
+    (void)hipFree(h->ybits);
+    h->ybits = nullptr;
     (void)hipFree(h->rank_of);
     (void)hipFree(h->coord_of);
     (void)hipFree(h->gdelta);
@@ -143,7 +168,6 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
             return SNAP_EINVAL;
         }
     h->n_groups = G;
-    h->n_pad = (n + 3) / 4 * 4;
     h->gbounds_host = new (std::nothrow) int64_t[(size_t)G + 1];
     h->ghot_host = new (std::nothrow) int[(size_t)G];
     if (!h->gbounds_host || !h->ghot_host) return SNAP_ENOMEM;
@@ -151,7 +175,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
 
     int lds_max = 0;
     SNAP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
-    const int hot_cap = std::max(4, std::min<int>(hot_max(), (lds_max - 1024) / 16));
+    const int hot_cap = std::max(4, std::min<int>(hot_max(), (lds_max - 1024 - 4 * DELTA_LDS) / 16));
     // ranks inside each group: coordinates by decreasing length (ties by index)
     std::vector<uint32_t> rank_of((size_t)m), coord_of((size_t)m);
     int max_hot = 1;
@@ -175,19 +199,25 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
     }
     h->gpartial_stride = 2 * (int64_t)max_hot;
 
+    h->map16 = true;
+    for (int64_t g = 0; g < G; ++g)
+        if (gb[g + 1] - gb[g] > 65535) h->map16 = false;
+    h->n_pad = (n + 7) / 8 * 8;
+    const size_t map_count = (size_t)G * (size_t)h->n_pad;
     int64_t* d_gb = nullptr;
     uint32_t* flags = nullptr;
+    uint32_t* wide = nullptr;
     SNAP_HIP(hipMalloc(&h->rank_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->coord_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->gdelta, (size_t)(m ? m : 1) * sizeof(float)));
     SNAP_HIP(hipMalloc(&h->gpartial, (size_t)row_wgs() * (size_t)h->gpartial_stride * sizeof(long long)));
-    SNAP_HIP(hipMalloc(&h->rowmap, (size_t)G * (size_t)h->n_pad * sizeof(uint32_t)));
-    SNAP_HIP(hipMalloc(&h->rowval, (size_t)G * (size_t)h->n_pad * sizeof(float)));
+    SNAP_HIP(hipMalloc(&h->ybits, (size_t)(h->n_pad / 8 + 16)));
     SNAP_HIP(hipMalloc(&d_gb, (size_t)(G + 1) * sizeof(int64_t)));
     SNAP_HIP(hipMalloc(&flags, 2 * sizeof(uint32_t)));
     auto fail = [&](int rc) {
         (void)hipFree(d_gb);
         (void)hipFree(flags);
+        (void)hipFree(wide);
         return rc;
     };
 #define G_HIP(call)                                                                \
@@ -199,20 +229,14 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
     G_HIP(hipMemcpyAsync(h->coord_of, coord_of.data(), (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
     G_HIP(hipMemcpyAsync(d_gb, gb, (size_t)(G + 1) * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
     int rc = fill_zero(flags, 8, h->compute);
-    if (rc == SNAP_OK) rc = fill_zero(h->rowval, (size_t)G * (size_t)h->n_pad * sizeof(float), h->compute);
     if (rc == SNAP_OK) rc = fill_zero(h->gdelta, (size_t)m * sizeof(float), h->compute);
     if (rc != SNAP_OK) return fail(rc);
-    hipLaunchKernelGGL(k_fill_u32, dim3(8192), dim3(256), 0, h->compute, h->rowmap, (size_t)G * (size_t)h->n_pad, RANK_NONE);
-    if (h->nnz > 0)
-        hipLaunchKernelGGL(k_build_rowmap, dim3((unsigned)((h->nnz + 4095) / 4096)), dim3(256), 0, h->compute, h->ptr,
-                           h->idx, h->val, m, h->nnz, d_gb, G, h->rank_of, h->n_pad, h->rowmap, h->rowval, flags);
-    if (h->kind == K_PRIMAL_LOGISTIC && n > 0)
-        hipLaunchKernelGGL(k_rowmap_labels, dim3(4096), dim3(256), 0, h->compute, h->rowmap, G, n, h->n_pad, h->y);
-    G_HIP(hipGetLastError());
+    // values: all ones (no per-row value arrays) or not, and their largest magnitude
     uint32_t fl2[2] = {0, 0};
+    if (h->nnz > 0) hipLaunchKernelGGL(k_value_stats, dim3(4096), dim3(256), 0, h->compute, h->val, h->nnz, flags);
     G_HIP(hipMemcpyAsync(fl2, flags, 8, hipMemcpyDeviceToHost, h->compute));
     G_HIP(hipStreamSynchronize(h->compute));
-    const uint32_t fl = fl2[0];
+    h->unit_values = !(fl2[0] & 2u);
     {
         float amax;
         memcpy(&amax, &fl2[1], 4);
@@ -220,17 +244,33 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
         if (amax > 0.0f) (void)frexpf(amax, &e);     // amax <= 2^e
         h->gscale_exp = e;
     }
+    if (!h->unit_values) {
+        G_HIP(hipMalloc(&h->rowval, map_count * sizeof(float)));
+        rc = fill_zero(h->rowval, map_count * sizeof(float), h->compute);
+        if (rc != SNAP_OK) return fail(rc);
+    }
+    // 32-bit map first (compare-and-swap per nonzero), narrowed to 16 bits afterwards when possible
+    G_HIP(hipMalloc(&wide, map_count * sizeof(uint32_t)));
+    hipLaunchKernelGGL(k_fill_u32, dim3(8192), dim3(256), 0, h->compute, wide, map_count, RANK_NONE);
+    if (h->nnz > 0)
+        hipLaunchKernelGGL(k_build_rowmap, dim3((unsigned)((h->nnz + 4095) / 4096)), dim3(256), 0, h->compute, h->ptr,
+                           h->idx, h->val, m, h->nnz, d_gb, G, h->rank_of, h->n_pad, wide, h->rowval, flags);
+    hipLaunchKernelGGL(k_label_bits, dim3(4096), dim3(256), 0, h->compute, h->y, n, h->ybits, h->n_pad / 8);
+    if (h->map16) {
+        G_HIP(hipMalloc(&h->rowmap, map_count * sizeof(uint16_t)));
+        hipLaunchKernelGGL(k_narrow_map, dim3(8192), dim3(256), 0, h->compute, wide, (uint16_t*)h->rowmap, map_count);
+    }
+    G_HIP(hipGetLastError());
+    G_HIP(hipMemcpyAsync(fl2, flags, 8, hipMemcpyDeviceToHost, h->compute));
+    G_HIP(hipStreamSynchronize(h->compute));
 #undef G_HIP
     (void)hipFree(d_gb);
     (void)hipFree(flags);
-    if (fl & 1u) {
+    if (h->map16) (void)hipFree(wide);
+    else h->rowmap = wide;
+    if (fl2[0] & 1u) {
         set_error("two coordinates of one group share a row: the groups are not disjoint");
         return SNAP_EINVAL;
-    }
-    h->unit_values = !(fl & 2u);
-    if (h->unit_values) {
-        (void)hipFree(h->rowval);
-        h->rowval = nullptr;
     }
     if (h->opt.profile) {
         h->ev_group = new (std::nothrow) hipEvent_t[(size_t)(2 * (G + 1))]();
@@ -252,120 +292,138 @@ int grouped_setup(snap_handle* h, const int64_t* hptr) {
 
 // ---- the row pass ------------------------------------------------------------------------------------
 // SCATTER: v[r] += delta_prev[rank] * a for the previous group.  HIST: sums of the current group's
-// hot ranks.  Four consecutive rows per thread and iteration (128-bit loads and stores).
-template <int KIND, bool UNIT, bool SCATTER, bool HIST>
-__global__ void __launch_bounds__(ROW_TPB)
-k_group_rows(const uint32_t* __restrict__ map_prev, const float* __restrict__ val_prev,
-             const float* __restrict__ delta_prev, const uint32_t* __restrict__ map_cur,
-             const float* __restrict__ val_cur, int hot, float* __restrict__ v, const float* __restrict__ y,
-             int64_t n, long long* __restrict__ partial, int64_t partial_stride, float scale_g, float scale_h) {
-    // fixed point: [0,hot): sum of a loss' * scale_g, [hot,2hot): sum of a^2 loss'' * scale_h
-    extern __shared__ unsigned long long hist[];
-    if (HIST) {
-        for (int i = threadIdx.x; i < 2 * hot; i += ROW_TPB) hist[i] = 0ull;
-        __syncthreads();
+// hot ranks.  Every thread takes one 128-bit load of each map per iteration: 8 consecutive rows with
+// 16-bit maps, 4 with 32-bit maps.
+template <typename MAPT> struct MapTraits;
+template <> struct MapTraits<uint16_t> { static constexpr int R = 8; static constexpr uint32_t NONE = 0xFFFFu; };
+template <> struct MapTraits<uint32_t> { static constexpr int R = 4; static constexpr uint32_t NONE = 0xFFFFFFFFu; };
+
+// Round-to-nearest fixed point.  Logistic terms are bounded, so their scaled magnitude is known to
+// stay below 2^31 and one 32-bit conversion does; ridge terms a (v - y) have no a-priori bound and
+// take the 64-bit conversion.
+template <int KIND>
+__device__ __forceinline__ unsigned long long to_fixed(float x, float scale) {
+    if (KIND == K_PRIMAL_LOGISTIC) return (unsigned long long)(long long)__float2int_rn(x * scale);
+    return (unsigned long long)__float2ll_rn(x * scale);
+}
+
+__device__ __forceinline__ void load_ranks(const uint16_t* p, uint32_t (&out)[8]) {
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    out[0] = u.x & 0xFFFFu; out[1] = u.x >> 16; out[2] = u.y & 0xFFFFu; out[3] = u.y >> 16;
+    out[4] = u.z & 0xFFFFu; out[5] = u.z >> 16; out[6] = u.w & 0xFFFFu; out[7] = u.w >> 16;
+}
+
+__device__ __forceinline__ void load_ranks(const uint32_t* p, uint32_t (&out)[4]) {
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    out[0] = u.x; out[1] = u.y; out[2] = u.z; out[3] = u.w;
+}
+
+template <int R>
+__device__ __forceinline__ void load_floats(const float* p, float (&out)[R]) {
+#pragma unroll
+    for (int q = 0; q < R / 4; ++q) {
+        const float4 t = *reinterpret_cast<const float4*>(p + 4 * q);
+        out[4 * q] = t.x; out[4 * q + 1] = t.y; out[4 * q + 2] = t.z; out[4 * q + 3] = t.w;
     }
-    // the four longest coordinates of a group hold a third of its rows: their sums stay in
+}
+
+template <int KIND, bool UNIT, bool SCATTER, bool HIST, typename MAPT>
+__global__ void __launch_bounds__(ROW_TPB)
+k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_prev,
+             const float* __restrict__ delta_prev, const MAPT* __restrict__ map_cur,
+             const float* __restrict__ val_cur, int hot, float* __restrict__ v, const float* __restrict__ y,
+             const uint8_t* __restrict__ ybits, int64_t n, long long* __restrict__ partial, int64_t partial_stride,
+             float scale_g, float scale_h, int kd) {
+    constexpr int R = MapTraits<MAPT>::R;
+    constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
+    // LDS: fixed-point sums, [0,hot): sum of a loss' * scale_g, [hot,2hot): sum of a^2 loss'' * scale_h,
+    // then the steps of the previous group's first kd ranks (a gather from global memory per row
+    // costs a third of the pass; nearly every row hits one of these)
+    extern __shared__ unsigned long long hist[];
+    float* dl = reinterpret_cast<float*>(hist + 2 * hot);
+    if (HIST)
+        for (int i = threadIdx.x; i < 2 * hot; i += ROW_TPB) hist[i] = 0ull;
+    if (SCATTER)
+        for (int i = threadIdx.x; i < kd; i += ROW_TPB) dl[i] = delta_prev[i];
+    __syncthreads();
+    // the two longest coordinates of a group hold a quarter of its rows: their sums stay in
     // registers (one LDS update per wavefront at the end) instead of colliding in LDS
-    float rg0 = 0.0f, rg1 = 0.0f, rg2 = 0.0f, rg3 = 0.0f, rh0 = 0.0f, rh1 = 0.0f, rh2 = 0.0f, rh3 = 0.0f;
-    const int64_t quads = (n + 3) / 4;
-    const int64_t per = (quads + gridDim.x - 1) / gridDim.x;
-    const int64_t q0 = min(quads, (int64_t)blockIdx.x * per), q1 = min(quads, q0 + per);
+    float rg0 = 0.0f, rg1 = 0.0f, rh0 = 0.0f, rh1 = 0.0f;
+    const int64_t packs = (n + R - 1) / R;
+    const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
+    const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
     for (int64_t q = q0 + threadIdx.x; q < q1; q += ROW_TPB) {
-        const int64_t r = 4 * q;
-        float vv[4];
-        uint32_t mp[4] = {RANK_NONE, RANK_NONE, RANK_NONE, RANK_NONE}, mc[4] = {RANK_NONE, RANK_NONE, RANK_NONE, RANK_NONE};
-        float ap[4] = {1.0f, 1.0f, 1.0f, 1.0f}, ac[4] = {1.0f, 1.0f, 1.0f, 1.0f}, yy[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        const bool full = r + 3 < n;
+        const int64_t r = R * q;
+        float vv[R], ap[R], ac[R], yy[R];
+        uint32_t mp[R], mc[R];
+        const bool full = r + R - 1 < n;           // maps, values and label bits are padded; v and y are not
         if (full) {
-            const float4 t = *reinterpret_cast<const float4*>(v + r);
-            vv[0] = t.x; vv[1] = t.y; vv[2] = t.z; vv[3] = t.w;
-            if (SCATTER) {
-                const uint4 u = *reinterpret_cast<const uint4*>(map_prev + r);
-                mp[0] = u.x; mp[1] = u.y; mp[2] = u.z; mp[3] = u.w;
-                if (!UNIT) {
-                    const float4 a = *reinterpret_cast<const float4*>(val_prev + r);
-                    ap[0] = a.x; ap[1] = a.y; ap[2] = a.z; ap[3] = a.w;
-                }
-            }
-            if (HIST) {
-                const uint4 u = *reinterpret_cast<const uint4*>(map_cur + r);
-                mc[0] = u.x; mc[1] = u.y; mc[2] = u.z; mc[3] = u.w;
-                if (!UNIT) {
-                    const float4 a = *reinterpret_cast<const float4*>(val_cur + r);
-                    ac[0] = a.x; ac[1] = a.y; ac[2] = a.z; ac[3] = a.w;
-                }
-                if (KIND == K_PRIMAL_RIDGE) {
-                    const float4 t2 = *reinterpret_cast<const float4*>(y + r);
-                    yy[0] = t2.x; yy[1] = t2.y; yy[2] = t2.z; yy[3] = t2.w;
-                }
-            }
+            load_floats<R>(v + r, vv);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bool in = r + j < n;          // the maps are padded to a multiple of four rows
-                vv[j] = in ? v[r + j] : 0.0f;
-                if (SCATTER) {
-                    mp[j] = in ? map_prev[r + j] : RANK_NONE;
-                    if (!UNIT) ap[j] = in ? val_prev[r + j] : 0.0f;
-                }
-                if (HIST) {
-                    mc[j] = in ? map_cur[r + j] : RANK_NONE;
-                    if (!UNIT) ac[j] = in ? val_cur[r + j] : 0.0f;
-                    if (KIND == K_PRIMAL_RIDGE) yy[j] = in ? y[r + j] : 0.0f;
-                }
-            }
+            for (int j = 0; j < R; ++j) vv[j] = r + j < n ? v[r + j] : 0.0f;
         }
         if (SCATTER) {
+            load_ranks(map_prev + r, mp);
+            if (!UNIT) load_floats<R>(val_prev + r, ap);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t rk = mp[j] & RANK_MASK;
-                if (rk != RANK_NONE) vv[j] += delta_prev[rk] * ap[j];
-            }
+            for (int j = 0; j < R; ++j)
+                if (mp[j] != NONE)
+                    vv[j] += (mp[j] < (uint32_t)kd ? dl[mp[j]] : delta_prev[mp[j]]) * (UNIT ? 1.0f : ap[j]);
             if (full) {
-                *reinterpret_cast<float4*>(v + r) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+#pragma unroll
+                for (int qq = 0; qq < R / 4; ++qq)
+                    *reinterpret_cast<float4*>(v + r + 4 * qq) =
+                        make_float4(vv[4 * qq], vv[4 * qq + 1], vv[4 * qq + 2], vv[4 * qq + 3]);
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < R; ++j)
                     if (r + j < n) v[r + j] = vv[j];
             }
         }
         if (HIST) {
+            load_ranks(map_cur + r, mc);
+            if (!UNIT) load_floats<R>(val_cur + r, ac);
+            uint32_t lab = 0;
+            if (KIND == K_PRIMAL_LOGISTIC) {
+                lab = (uint32_t)ybits[r >> 3] >> (r & 7);
+            } else if (full) {
+                load_floats<R>(y + r, yy);
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t rk = mc[j] & RANK_MASK;
-                if (rk < (uint32_t)hot) {
-                    if (KIND == K_PRIMAL_LOGISTIC) yy[j] = (mc[j] & LABEL_BIT) ? -1.0f : 1.0f;
+                for (int j = 0; j < R; ++j) yy[j] = r + j < n ? y[r + j] : 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const uint32_t rk = mc[j];
+                if (rk < (uint32_t)hot) {          // (a row past the end has rank "none", which is never hot)
+                    if (KIND == K_PRIMAL_LOGISTIC) yy[j] = ((lab >> j) & 1u) ? -1.0f : 1.0f;
                     float g = 0.0f, hh = 0.0f;
-                    accumulate<KIND>(ac[j], vv[j], yy[j], g, hh);
-                    if (rk < 4u) {
+                    accumulate<KIND>(UNIT ? 1.0f : ac[j], vv[j], yy[j], g, hh);
+                    if (rk < 2u) {
                         rg0 += rk == 0u ? g : 0.0f;
                         rg1 += rk == 1u ? g : 0.0f;
-                        rg2 += rk == 2u ? g : 0.0f;
-                        rg3 += rk == 3u ? g : 0.0f;
                         if (KIND == K_PRIMAL_LOGISTIC) {
                             rh0 += rk == 0u ? hh : 0.0f;
                             rh1 += rk == 1u ? hh : 0.0f;
-                            rh2 += rk == 2u ? hh : 0.0f;
-                            rh3 += rk == 3u ? hh : 0.0f;
                         }
                     } else {
-                        atomicAdd(&hist[rk], (unsigned long long)__float2ll_rn(g * scale_g));
+                        atomicAdd(&hist[rk], to_fixed<KIND>(g, scale_g));
                         if (KIND == K_PRIMAL_LOGISTIC)
-                            atomicAdd(&hist[hot + rk], (unsigned long long)__float2ll_rn(hh * scale_h));
+                            atomicAdd(&hist[hot + rk], to_fixed<KIND>(hh, scale_h));
                     }
                 }
             }
         }
     }
     if (HIST) {
-        rg0 = wave_sum(rg0); rg1 = wave_sum(rg1); rg2 = wave_sum(rg2); rg3 = wave_sum(rg3);
+        rg0 = wave_sum(rg0); rg1 = wave_sum(rg1);
         if (KIND == K_PRIMAL_LOGISTIC) {
-            rh0 = wave_sum(rh0); rh1 = wave_sum(rh1); rh2 = wave_sum(rh2); rh3 = wave_sum(rh3);
+            rh0 = wave_sum(rh0); rh1 = wave_sum(rh1);
         }
         if ((threadIdx.x & (WAVE - 1)) == 0) {
-            const float rg[4] = {rg0, rg1, rg2, rg3}, rh[4] = {rh0, rh1, rh2, rh3};
-            for (int t = 0; t < 4 && t < hot; ++t) {
+            const float rg[2] = {rg0, rg1}, rh[2] = {rh0, rh1};
+            for (int t = 0; t < 2 && t < hot; ++t) {
                 atomicAdd(&hist[t], (unsigned long long)__float2ll_rn(rg[t] * scale_g));
                 if (KIND == K_PRIMAL_LOGISTIC) atomicAdd(&hist[hot + t], (unsigned long long)__float2ll_rn(rh[t] * scale_h));
             }
@@ -441,16 +499,16 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
     delta[g0 + rk] = mult;
 }
 
-template <int KIND, bool UNIT>
+template <int KIND, bool UNIT, typename MAPT>
 static int grouped_epoch_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
     const int64_t n = h->n, G = h->n_groups;
     long long* gpart = (long long*)h->gpartial;
-    // power-of-two scales (exact in fp32): |a loss'| <= 2^e and a^2 loss'' <= 2^(2e) for the logistic loss,
-    // at most 2^18 rows per workgroup, so the sums stay below 2^59; ridge terms are unbounded in
-    // principle, 24 fractional bits leave 2^39 of range
-    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ldexpf(1.0f, 40 - h->gscale_exp) : ldexpf(1.0f, 24);
-    const float scale_h = ldexpf(1.0f, 40 - 2 * h->gscale_exp);
+    // power-of-two scales (exact in fp32).  Logistic: |a loss'| <= 2^e and a^2 loss'' <= 2^(2e-2), so the
+    // scaled terms stay below 2^30 and the per-wavefront register sums (at most 2^18 rows) below 2^48.
+    // Ridge terms a (v - y): 24 fractional bits, 2^39 of range in the 64-bit sum.
+    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ldexpf(1.0f, 30 - h->gscale_exp) : ldexpf(1.0f, 24);
+    const float scale_h = ldexpf(1.0f, 30 - 2 * h->gscale_exp);
     int64_t prev = -1;                              // last non-empty group, whose steps are still to be applied
     const bool prof = h->opt.profile != 0 && h->ev_group != nullptr;
     int n_pass = 0;
@@ -459,27 +517,29 @@ static int grouped_epoch_kind(snap_handle* h) {
         const int64_t g0 = last ? 0 : h->gbounds_host[g], sz = last ? 0 : h->gbounds_host[g + 1] - g0;
         if (!last && sz == 0) continue;
         const int hot = last ? 0 : h->ghot_host[g];
-        const uint32_t* map_prev = prev >= 0 ? h->rowmap + (size_t)prev * h->n_pad : nullptr;
+        const MAPT* maps = (const MAPT*)h->rowmap;
+        const MAPT* map_prev = prev >= 0 ? maps + (size_t)prev * h->n_pad : nullptr;
         const float* val_prev = (prev >= 0 && !UNIT) ? h->rowval + (size_t)prev * h->n_pad : nullptr;
         const float* delta_prev = prev >= 0 ? h->gdelta + h->gbounds_host[prev] : nullptr;
-        const uint32_t* map_cur = last ? nullptr : h->rowmap + (size_t)g * h->n_pad;
+        const MAPT* map_cur = last ? nullptr : maps + (size_t)g * h->n_pad;
         const float* val_cur = (last || UNIT) ? nullptr : h->rowval + (size_t)g * h->n_pad;
-        const size_t lds = (size_t)2 * hot * sizeof(unsigned long long);
+        const int kd = prev >= 0 ? (int)std::min<int64_t>(DELTA_LDS, h->gbounds_host[prev + 1] - h->gbounds_host[prev]) : 0;
+        const size_t lds = (size_t)2 * hot * sizeof(unsigned long long) + (size_t)kd * sizeof(float);
         const bool scatter = prev >= 0, histo = !last && hot > 0;
         if (n > 0 && (scatter || histo)) {
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass], h->compute));
             if (scatter && histo)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h);
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
+                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, h->ybits, n, gpart,
+                                   h->gpartial_stride, scale_g, scale_h, kd);
             else if (scatter)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false>), dim3(row_wgs()), dim3(ROW_TPB), 0, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, 0, h->v, h->y, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h);
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
+                                   map_prev, val_prev, delta_prev, map_cur, val_cur, 0, h->v, h->y, h->ybits, n, gpart,
+                                   h->gpartial_stride, scale_g, scale_h, kd);
             else
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h);
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
+                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, h->ybits, n, gpart,
+                                   h->gpartial_stride, scale_g, scale_h, kd);
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
             ++n_pass;
         }
@@ -498,11 +558,16 @@ static int grouped_epoch_kind(snap_handle* h) {
     return SNAP_OK;
 }
 
+template <int KIND>
+static int grouped_epoch_dispatch(snap_handle* h) {
+    if (h->map16)
+        return h->unit_values ? grouped_epoch_kind<KIND, true, uint16_t>(h) : grouped_epoch_kind<KIND, false, uint16_t>(h);
+    return h->unit_values ? grouped_epoch_kind<KIND, true, uint32_t>(h) : grouped_epoch_kind<KIND, false, uint32_t>(h);
+}
+
 int grouped_epoch(snap_handle* h) {
-    if (h->kind == K_PRIMAL_RIDGE)
-        return h->unit_values ? grouped_epoch_kind<K_PRIMAL_RIDGE, true>(h) : grouped_epoch_kind<K_PRIMAL_RIDGE, false>(h);
-    return h->unit_values ? grouped_epoch_kind<K_PRIMAL_LOGISTIC, true>(h)
-                          : grouped_epoch_kind<K_PRIMAL_LOGISTIC, false>(h);
+    return h->kind == K_PRIMAL_RIDGE ? grouped_epoch_dispatch<K_PRIMAL_RIDGE>(h)
+                                     : grouped_epoch_dispatch<K_PRIMAL_LOGISTIC>(h);
 }
 
 }  // namespace snap

@@ -30,7 +30,7 @@ __device__ __forceinline__ void accumulate(float a, float vv, float yy, float& g
         g += a * (vv - yy);                       // loss' = v - y ; loss'' = 1 (h comes from the norm)
     } else if (KIND == K_PRIMAL_LOGISTIC) {
         const float e = __expf(yy * vv);          // p = sigmoid(-y v) = 1/(1+e)
-        const float p = 1.0f / (1.0f + e);
+        const float p = __builtin_amdgcn_rcpf(1.0f + e);   // hardware reciprocal (1 ulp); e = inf gives p = 0
         g -= a * yy * p;                          // loss'  = -y p
         h += a * a * (p - p * p);                 // loss'' = p (1 - p)
     } else {

@@ -368,3 +368,30 @@ def test_group_sweeps_reject_overlapping_groups():
         o.epoch(e)
     assert rel(g.objective(), o.primal()) <= 1e-5
     g.close()
+
+
+def test_group_sweeps_wide_group_uses_32_bit_maps():
+    """A group with more than 65535 coordinates takes the 32-bit row-map path."""
+    n, d1, d2 = 200_000, 70_000, 50
+    rng = np.random.default_rng(8)
+    c1 = rng.integers(0, d1, size=n)                     # field 1: 70 000 categories
+    c2 = rng.integers(0, d2, size=n)                     # field 2: 50 categories
+    cols = np.concatenate([c1, d1 + c2])
+    rows = np.concatenate([np.arange(n), np.arange(n)])
+    order = np.lexsort((rows, cols))
+    d = d1 + d2
+    ptr = np.zeros(d + 1, dtype=np.int64)
+    ptr[1:] = np.cumsum(np.bincount(cols, minlength=d))
+    idx = rows[order].astype(np.int32)
+    val = np.ones(idx.size, dtype=np.float32)
+    y = np.where(rng.random(n) < 0.3, 1.0, -1.0).astype(np.float32)
+    groups = [0, d1, d]
+    g = snap.Solver("csc", n, d, ptr, idx, val, y, "logistic", 1e-4, group_bounds=groups)
+    o = oracle.Solver(oracle.Matrix("csc", n, d, ptr, idx, val), y, "logistic", 1e-4, chunk_bounds=groups)
+    for e in range(5):
+        g.epoch(e)
+        o.epoch(e)
+        _, x = g.model()
+        assert relnorm(x, o.x) <= 2e-5
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    g.close()
