@@ -84,8 +84,10 @@ typedef struct {
                                     Damping").  snap_epoch then waits for the epoch to finish. */
     float damping;               /* initial damping in (0,1]; 0 means 1 (no damping) */
     int64_t max_inflight_nnz;    /* cap on the nonzeros of coordinates in flight at once; 0 = automatic:
-                                    a quarter of the effective length of v, (sum f)^2 / sum f^2 over the
-                                    access counts f of the entries of v (dense data: no cap) */
+                                    a quarter of the length of v, lowered by the adaptive check when an
+                                    epoch makes the objective worse; with the check off, a quarter of the
+                                    effective length of v, (sum f)^2 / sum f^2 over the access counts f of
+                                    the entries of v (dense data: no cap) */
     const int64_t *group_bounds; /* optional (host memory, copied): n_groups+1 increasing coordinate
                                     boundaries, group_bounds[0] = 0, last = number of coordinates, such that
                                     the coordinates INSIDE a group have pairwise disjoint supports (the

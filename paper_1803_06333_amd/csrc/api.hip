@@ -251,7 +251,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     h->adaptive = h->opt.adaptive == 1 || (h->opt.adaptive == 0 && h->opt.n_groups == 0);
     h->damping = h->opt.damping > 0.0f ? h->opt.damping : 1.0f;
     h->inflight_floor = WAVE;
-    const bool auto_cap = h->opt.max_inflight_nnz <= 0 && !h->dense;
+    const bool auto_cap = h->opt.max_inflight_nnz <= 0 && !h->dense && !h->adaptive;
     CreatePass cp{nullptr, h->form == SNAP_PRIMAL ? h->n : h->d};
     if (auto_cap && h->vlen > 0) {
         SNAP_HIP(hipMalloc(&cp.freq, (size_t)h->vlen * sizeof(uint32_t)));
@@ -290,7 +290,12 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     // ---- concurrency control ---------------------------------------------------------------------
     if (h->opt.max_inflight_nnz > 0) h->inflight_nnz = h->opt.max_inflight_nnz;
     else if (h->dense) h->inflight_nnz = 0;       // no cap; the adaptive check lowers it if needed
-    else h->inflight_nnz = std::max<int64_t>(1, (int64_t)(0.25 * eff));
+    else {
+        // a quarter of the length of v; without the accept check to fall back on, a quarter of its
+        // effective length (much smaller when a few entries of v take most of the accesses)
+        const double len = h->adaptive ? (double)h->vlen : eff;
+        h->inflight_nnz = std::max<int64_t>(WAVE, (int64_t)(0.25 * len));
+    }
     if (h->adaptive) {
         SNAP_HIP(hipMalloc(&h->x_snap, (size_t)(m ? m : 1) * sizeof(float)));
         SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
