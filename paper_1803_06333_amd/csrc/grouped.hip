@@ -436,11 +436,11 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
 
 // ---- sums of the short coordinates and the steps of one group ------------------------------------------
 // One launch, two kinds of workgroups.  The first n_hot_blocks handle the hot ranks: 32 ranks per
-// workgroup, 8 threads per rank, each summing every 8th per-workgroup partial of the row pass (integer
+// workgroup, 32 threads per rank, each summing every 32nd per-workgroup partial of the row pass (integer
 // sums: exact and independent of the order), combined in LDS, then one thread takes the step.  The
 // others handle the cold ranks: one wavefront per coordinate gathers its two sums column-wise (v is
 // not written while this kernel runs) and takes the step right away.
-constexpr int STEP_RANKS = 32, STEP_PARTS = 8;
+constexpr int STEP_RANKS = 32, STEP_PARTS = 32;
 
 template <int KIND>
 __global__ void __launch_bounds__(STEP_RANKS * STEP_PARTS)
@@ -477,6 +477,7 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
     const int64_t rk = (int64_t)blockIdx.x * STEP_RANKS + lr;
     long long Gi = 0, Hi = 0;
     if (rk < hot) {
+#pragma unroll 8
         for (int w = part; w < n_wgs; w += STEP_PARTS) {
             Gi += partial[(size_t)w * partial_stride + rk];
             if (KIND == K_PRIMAL_LOGISTIC) Hi += partial[(size_t)w * partial_stride + hot + rk];
@@ -546,7 +547,8 @@ static int grouped_epoch_kind(snap_handle* h) {
         if (last) break;
         const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
         const int64_t cold = sz - hot;
-        const int n_cold_blocks = (int)std::min<int64_t>((cold + 3) / 4, 16384);
+        const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
+        const int n_cold_blocks = (int)std::min<int64_t>((cold + waves_per_block - 1) / waves_per_block, 8192);
         hipLaunchKernelGGL((k_group_finish<KIND>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
                            dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, row_wgs(), hot,
                            n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, h->ptr, h->idx, h->val, h->v,
