@@ -93,9 +93,10 @@ typedef struct {
                                     the coordinates INSIDE a group have pairwise disjoint supports (the
                                     columns of one one-hot encoded field).  Verified at creation.  Enables
                                     the exact group-sweep epoch (primal form, sparse, resident): groups are
-                                    visited in order, all coordinates of a group at once -- identical to
-                                    visiting them one by one, since they do not interact -- with plain
-                                    coalesced updates of v instead of atomics. */
+                                    visited in a random order drawn from perm_seed (keys of the groups
+                                    under chunk id 0xFFFFFFFF, sorted), all coordinates of a group at
+                                    once -- identical to visiting them one by one, since they do not
+                                    interact -- with plain coalesced updates of v instead of atomics. */
     int64_t n_groups;            /* 0: no groups */
 } snap_options;
 
@@ -171,8 +172,8 @@ int snap_get_epoch_stats(snap_handle *h, snap_epoch_stats *out);
 
 /* Streaming layout: *n_chunks receives the number of chunks (1 when resident); bounds_out, if not
  * NULL, receives n_chunks+1 coordinate boundaries (host int64): chunk k is [bounds[k], bounds[k+1]).
- * With group_bounds in force the groups are reported (they play the role of the chunks: visited in
- * order, permutation inside each, the group index entering the key). */
+ * With group_bounds in force the groups are reported (they play the role of the chunks: permutation
+ * inside each with the group index entering the key; the groups themselves in seeded random order). */
 int snap_get_chunks(snap_handle *h, int64_t *n_chunks, int64_t *bounds_out);
 
 /* Number of coordinates m and length of v. */

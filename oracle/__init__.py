@@ -138,7 +138,10 @@ class Solver:
     """Sequential SCD on one problem.  form: 'primal' (CSC / dense, ridge or logistic) or 'dual'
     (CSR, hinge).  State starts at zero (Algorithm 1's starting point)."""
 
-    def __init__(self, A: Matrix, y, loss: str, lam: float, chunk_bounds: Optional[Sequence[int]] = None):
+    GROUP_ORDER_CHUNK = 0xFFFFFFFF     # chunk id under which the order of the chunks is drawn
+
+    def __init__(self, A: Matrix, y, loss: str, lam: float, chunk_bounds: Optional[Sequence[int]] = None,
+                 shuffle_chunks: bool = False):
         self.A, self.y, self.loss, self.lam = A, _f32(y), LOSS_ID[loss], float(lam)
         if A.layout == "csr":
             if loss != "hinge":
@@ -152,13 +155,19 @@ class Solver:
         self.v = np.zeros(self.vlen, dtype=np.float64)   # shared vector
         # streaming: coordinates are visited chunk by chunk, permuted inside each chunk
         self.bounds = [0, self.m] if chunk_bounds is None else list(chunk_bounds)
+        # shuffle_chunks: the chunks themselves are visited in a seeded random order (their keys under
+        # the reserved chunk id, sorted), not 0, 1, 2, ...
+        self.shuffle_chunks = shuffle_chunks
         self.last_perm = None
 
     def epoch(self, seed: int):
         L = lib()
         n = C.c_int64(self.A.n)
         perms = []
-        for ch in range(len(self.bounds) - 1):
+        nch = len(self.bounds) - 1
+        order = permutation(seed, nch, chunk=self.GROUP_ORDER_CHUNK) if self.shuffle_chunks else range(nch)
+        for ch in order:
+            ch = int(ch)
             c0, c1 = self.bounds[ch], self.bounds[ch + 1]
             perm = permutation(seed, c1 - c0, chunk=ch)
             perms.append(perm.astype(np.int64) + c0)
@@ -230,10 +239,10 @@ def primal_gap(A: Matrix, loss: int, v, y, w, lam: float, form: str = "gradient"
 
 
 def solve(A: Matrix, y, loss: str, lam: float, epochs: int, seed0: int = 0, tol: Optional[float] = None,
-          chunk_bounds=None) -> Solver:
+          chunk_bounds=None, shuffle_chunks: bool = False) -> Solver:
     """Run `epochs` passes with permutation seeds seed0, seed0+1, ...; stop early when the gap
     falls below tol * max(1, |P|)."""
-    s = Solver(A, y, loss, lam, chunk_bounds)
+    s = Solver(A, y, loss, lam, chunk_bounds, shuffle_chunks)
     for e in range(epochs):
         s.epoch(seed0 + e)
         if tol is not None and (e % 5 == 4 or e == epochs - 1):

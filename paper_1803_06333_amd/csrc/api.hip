@@ -417,6 +417,7 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         // exact group sweeps; the visiting order inside a group does not change the result and is
         // only generated when snap_get_perm asks for it
         if (prof) SNAP_HIP(hipEventRecord(h->ev[1], h->compute));
+        h->last_seed = perm_seed;
         SNAP_TRY(grouped_epoch(h));
         if (prof) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
         h->perm_stale = true;
@@ -552,8 +553,15 @@ int snap_get_perm(snap_handle* h, uint32_t* perm_out, uint32_t* keys_out) {
         SNAP_HIP(hipMemcpyAsync(keys_out, h->keys, (size_t)h->m * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));
     if (h->grouped) {
-        for (int64_t g = 0; g < h->n_groups; ++g)
-            for (int64_t c = h->gbounds_host[g]; c < h->gbounds_host[g + 1]; ++c) perm_out[c] += (uint32_t)h->gbounds_host[g];
+        // stored group by group; reported in visiting order: groups in the epoch's order, the
+        // permutation of each group inside
+        std::vector<uint32_t> tmp(perm_out, perm_out + h->m), ktmp;
+        if (keys_out) ktmp.assign(keys_out, keys_out + h->m);
+        int64_t pos = 0;
+        for (int64_t g : group_order(h->last_seed, h->n_groups)) {
+            const int64_t c0 = h->gbounds_host[g], c1 = h->gbounds_host[g + 1];
+            for (int64_t c = c0; c < c1; ++c) perm_out[pos++] = tmp[(size_t)c] + (uint32_t)c0;
+        }
         return SNAP_OK;
     }
     for (int64_t ch = 0; ch < h->n_chunks; ++ch)

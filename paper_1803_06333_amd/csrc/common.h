@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <cstdint>
 #include <cstddef>
+#include <vector>
 #include "../../include/snap.h"
 
 namespace snap {
@@ -192,6 +193,7 @@ int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profil
 // grouped.hip
 int grouped_setup(snap_handle* h, const int64_t* hptr);
 int grouped_epoch(snap_handle* h);
+std::vector<int64_t> group_order(uint64_t seed, int64_t n_groups);   // visiting order of the groups for a seed
 void grouped_free(snap_handle* h);
 
 int stream_alloc(snap_handle* h);

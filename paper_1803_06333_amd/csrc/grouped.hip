@@ -2,8 +2,9 @@
 // supports (the columns of one one-hot encoded field of click-log data, Section 4).  Coordinates of
 // one group do not interact -- no row of v is touched by two of them -- so updating all of them at
 // once IS the sequential coordinate-descent result for that group; groups are visited one after
-// the other.  The epoch therefore equals sequential SCD (Section 3.1) in the order "group 0, group
-// 1, ..." exactly (up to rounding), and needs neither atomics on v nor a cap on the work in flight.
+// the other, in a seeded random order.  The epoch therefore equals sequential SCD (Section 3.1)
+// in that order exactly (up to rounding), and needs neither atomics on v nor a cap on the work
+// in flight.
 //
 // What makes it fast on this part is that both inner loops turn from random 4-byte accesses to the
 // 183 MB vector v into coalesced streams over the rows:
@@ -20,6 +21,7 @@
 // Traffic per group and row: two map entries (2 + 2 bytes), read + write of v (8 bytes), one label bit
 // (+ values unless all 1).
 #include "scd_device.h"
+#include "perm_key.h"
 
 #include <algorithm>
 #include <cmath>
@@ -500,6 +502,16 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
     delta[g0 + rk] = mult;
 }
 
+std::vector<int64_t> group_order(uint64_t seed, int64_t n_groups) {
+    std::vector<uint64_t> comp((size_t)n_groups);
+    const uint64_t base = perm_key_base(seed, GROUP_ORDER_CHUNK);
+    for (int64_t g = 0; g < n_groups; ++g) comp[(size_t)g] = ((uint64_t)perm_key(base, (uint32_t)g) << 32) | (uint64_t)g;
+    std::sort(comp.begin(), comp.end());
+    std::vector<int64_t> order((size_t)n_groups);
+    for (int64_t i = 0; i < n_groups; ++i) order[(size_t)i] = (int64_t)(comp[(size_t)i] & 0xFFFFFFFFull);
+    return order;
+}
+
 template <int KIND, bool UNIT, typename MAPT>
 static int grouped_epoch_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
@@ -513,8 +525,13 @@ static int grouped_epoch_kind(snap_handle* h) {
     int64_t prev = -1;                              // last non-empty group, whose steps are still to be applied
     const bool prof = h->opt.profile != 0 && h->ev_group != nullptr;
     int n_pass = 0;
-    for (int64_t g = 0; g <= G; ++g) {
-        const bool last = g == G;
+    // the groups are visited in a seeded random order (keys of the epoch's seed under a reserved
+    // chunk id, sorted with the group index as tie-break): on the click-log workload a fresh order
+    // every epoch reaches a given duality gap in a fifth of the epochs a fixed order needs
+    const std::vector<int64_t> gorder = group_order(h->last_seed, G);
+    for (int64_t gi = 0; gi <= G; ++gi) {
+        const bool last = gi == G;
+        const int64_t g = last ? G : gorder[(size_t)gi];
         const int64_t g0 = last ? 0 : h->gbounds_host[g], sz = last ? 0 : h->gbounds_host[g + 1] - g0;
         if (!last && sz == 0) continue;
         const int hot = last ? 0 : h->ghot_host[g];

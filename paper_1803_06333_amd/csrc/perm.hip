@@ -6,6 +6,7 @@
 // of their indices (every pass is stable and the input is index-ascending), which makes the result
 // unique and bit-comparable with any other correct sort.
 #include "common.h"
+#include "perm_key.h"
 
 namespace snap {
 
@@ -16,31 +17,9 @@ constexpr int SORT_ROUNDS = 8;                                   // 64-element r
 constexpr int SORT_TILE = SORT_TPB * SORT_ROUNDS;                // 2048 elements per workgroup
 constexpr int SORT_WAVES = SORT_TPB / WAVE;
 
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
-    z += 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
-// 64-bit integer mix of (seed, chunk, c) folded to a non-zero 32-bit state, then four rounds of
-// the (13,17,5) xorshift.
-__device__ __forceinline__ uint32_t perm_key(uint64_t seed_chunk_mix, uint32_t c) {
-    uint64_t z = mix64(seed_chunk_mix + (uint64_t)c * 0x9E3779B97F4A7C15ull);
-    uint32_t x = (uint32_t)(z ^ (z >> 32));
-    if (x == 0u) x = 0x6C078965u;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        x ^= x << 13;
-        x ^= x >> 17;
-        x ^= x << 5;
-    }
-    return x;
-}
-
 __global__ void k_make_keys(uint64_t seed, uint32_t chunk, uint32_t m, uint32_t* __restrict__ keys,
                             uint32_t* __restrict__ vals, uint32_t* __restrict__ keys_copy) {
-    const uint64_t base = mix64(seed ^ mix64((uint64_t)chunk + 0x632BE59BD9B4E019ull));
+    const uint64_t base = perm_key_base(seed, chunk);
     for (uint32_t c = blockIdx.x * blockDim.x + threadIdx.x; c < m; c += gridDim.x * blockDim.x) {
         uint32_t k = perm_key(base, c);
         keys[c] = k;

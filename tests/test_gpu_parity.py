@@ -310,8 +310,9 @@ def test_streaming_needs_pinned_memory():
 
 # ---------------------------------------------------------------------------------------------
 # exact group sweeps: the coordinates of one group (the columns of a one-hot field) do not share
-# rows, so a sweep over the groups equals sequential SCD visiting "group 0, group 1, ..." -- the
-# oracle with those groups as chunks -- update for update, not just in the limit
+# rows, so a sweep over the groups equals sequential SCD visiting the groups in the same (seeded
+# random) order -- the oracle with those groups as shuffled chunks -- update for update, not just in
+# the limit
 def _onehot_variant(loss, unit):
     p = datagen.onehot_fields(n=150_000, d=4_000, lam=1e-4, seed=91)
     rng = np.random.default_rng(4)
@@ -331,7 +332,7 @@ def test_group_sweeps_equal_sequential_oracle(loss, unit):
     y = p.y.numpy()
     g = gpu_solver(p, group_bounds=groups)
     assert g.chunk_bounds() == groups
-    o = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=groups)
+    o = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
     for e in range(6):
         g.epoch(e)
         o.epoch(e)
@@ -362,7 +363,8 @@ def test_group_sweeps_reject_overlapping_groups():
     # one coordinate per group is always valid (and equals the plain sequential order of the groups)
     q = datagen.uniform_sparse_logistic(n=2000, d=60, k=5, seed=3)
     g = gpu_solver(q, group_bounds=list(range(61)))
-    o = oracle.Solver(oracle.Matrix.from_problem(q), q.y.numpy(), q.loss, q.lam, chunk_bounds=list(range(61)))
+    o = oracle.Solver(oracle.Matrix.from_problem(q), q.y.numpy(), q.loss, q.lam, chunk_bounds=list(range(61)),
+                      shuffle_chunks=True)
     for e in range(5):
         g.epoch(e)
         o.epoch(e)
@@ -387,7 +389,8 @@ def test_group_sweeps_wide_group_uses_32_bit_maps():
     y = np.where(rng.random(n) < 0.3, 1.0, -1.0).astype(np.float32)
     groups = [0, d1, d]
     g = snap.Solver("csc", n, d, ptr, idx, val, y, "logistic", 1e-4, group_bounds=groups)
-    o = oracle.Solver(oracle.Matrix("csc", n, d, ptr, idx, val), y, "logistic", 1e-4, chunk_bounds=groups)
+    o = oracle.Solver(oracle.Matrix("csc", n, d, ptr, idx, val), y, "logistic", 1e-4, chunk_bounds=groups,
+                      shuffle_chunks=True)
     for e in range(5):
         g.epoch(e)
         o.epoch(e)

@@ -337,3 +337,25 @@ def test_chunked_epoch_visits_every_coordinate_once_in_chunk_order():
     for e in range(400):
         s.epoch(e)
     np.testing.assert_allclose(s.x, ridge_closed_form(X, y.astype(np.float64), lam), atol=1e-10)
+
+
+def test_shuffled_chunks_visit_every_coordinate_once_and_converge():
+    n, d, lam = 50, 20, 0.05
+    X = sparse_random(n, d, 0.5, rng)
+    y = rng.standard_normal(n).astype(np.float32)
+    bounds = [0, 3, 7, 12, 16, 20]
+    s = oracle.Solver(dense_to_csc(X), y, "ridge", lam, chunk_bounds=bounds, shuffle_chunks=True)
+    orders = set()
+    for e in range(12):
+        s.epoch(e)
+        assert sorted(s.last_perm.tolist()) == list(range(d))
+        # chunks stay contiguous in the visiting order, and their order is the sorted-key order
+        first = [int(np.searchsorted(bounds, c, side="right") - 1) for c in s.last_perm]
+        seq = [k for i, k in enumerate(first) if i == 0 or first[i - 1] != k]
+        assert sorted(seq) == list(range(5))
+        assert seq == oracle.permutation(e, 5, chunk=0xFFFFFFFF).tolist()
+        orders.add(tuple(seq))
+    assert len(orders) > 3
+    for e in range(400):
+        s.epoch(e)
+    np.testing.assert_allclose(s.x, ridge_closed_form(X, y.astype(np.float64), lam), atol=1e-10)
