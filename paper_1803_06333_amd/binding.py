@@ -60,7 +60,7 @@ def load_library():
     """Load the built HIP library; there is no fallback path."""
     global _lib
     if _lib is None:
-        path = os.environ.get("SNAP_LIB_PATH", LIB_PATH)      # (override used for tuning builds)
+        path = LIB_PATH
         if not os.path.exists(path):
             raise ImportError("libsnap.so is not built (%s); run `python -m paper_1803_06333_amd.build` or "
                               "__graft_entry__.build()" % LIB_PATH)

@@ -20,10 +20,10 @@ constexpr int SORT_WAVES = SORT_TPB / WAVE;
 __global__ void k_make_keys(uint64_t seed, uint32_t chunk, uint32_t m, uint32_t* __restrict__ keys,
                             uint32_t* __restrict__ vals, uint32_t* __restrict__ keys_copy) {
     const uint64_t base = perm_key_base(seed, chunk);
-    for (uint32_t c = blockIdx.x * blockDim.x + threadIdx.x; c < m; c += gridDim.x * blockDim.x) {
-        uint32_t k = perm_key(base, c);
+    for (uint64_t c = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; c < m; c += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t k = perm_key(base, (uint32_t)c);
         keys[c] = k;
-        vals[c] = c;
+        vals[c] = (uint32_t)c;
         if (keys_copy) keys_copy[c] = k;
     }
 }
@@ -49,26 +49,39 @@ k_radix_hist(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ val
     block_hist[(size_t)threadIdx.x * n_blocks + blockIdx.x] = hist[threadIdx.x];
 }
 
-// exclusive prefix sum over `count` entries, in place, one workgroup of 1024 threads
+// exclusive prefix sum over `count` entries, in place, one workgroup of 1024 threads: tiles of 4096
+// entries (four consecutive per thread, coalesced), wavefront scans by shuffles, a running carry
 __global__ void __launch_bounds__(1024) k_exclusive_scan(uint32_t* __restrict__ a, uint32_t count) {
-    __shared__ uint32_t part[1024];
-    const uint32_t per = (count + 1023u) / 1024u;
-    const uint32_t lo = min(count, threadIdx.x * per), hi = min(count, lo + per);
-    uint32_t s = 0;
-    for (uint32_t i = lo; i < hi; ++i) s += a[i];
-    part[threadIdx.x] = s;
+    __shared__ uint32_t wave_tot[1024 / WAVE];
+    __shared__ uint32_t carry_s;
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-        uint32_t t = threadIdx.x >= off ? part[threadIdx.x - off] : 0u;
+    for (uint32_t base = 0; base < count; base += 4096u) {
+        const uint32_t i0 = base + 4u * threadIdx.x;
+        uint32_t x[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = i0 + j < count ? a[i0 + j] : 0u;
+        const uint32_t mine = x[0] + x[1] + x[2] + x[3];
+        uint32_t inc = mine;                               // inclusive scan across the wavefront
+#pragma unroll
+        for (int off = 1; off < WAVE; off <<= 1) {
+            const uint32_t t = __shfl_up(inc, off, WAVE);
+            if (lane >= off) inc += t;
+        }
+        if (lane == WAVE - 1) wave_tot[w] = inc;
         __syncthreads();
-        part[threadIdx.x] += t;
+        uint32_t before = carry_s;
+        for (int ww = 0; ww < w; ++ww) before += wave_tot[ww];
+        uint32_t run = before + inc - mine;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i0 + j < count) a[i0 + j] = run;
+            run += x[j];
+        }
         __syncthreads();
-    }
-    uint32_t run = part[threadIdx.x] - s;   // exclusive prefix of this thread's range
-    for (uint32_t i = lo; i < hi; ++i) {
-        uint32_t t = a[i];
-        a[i] = run;
-        run += t;
+        if (threadIdx.x == 1023) carry_s = run;            // total so far
+        __syncthreads();
     }
 }
 

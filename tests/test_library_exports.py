@@ -25,3 +25,27 @@ def test_struct_sizes_match_header_layout():
     assert C.sizeof(snap.binding.SnapMatrix) == 4 + 4 + 3 * 8 + 3 * 8
     assert C.sizeof(snap.binding.SnapOptions) == 8 + 8 + 8 + 8 + 8 + 4 + 4 + 4 + 4 + 8 + 8 + 8
     assert C.sizeof(snap.binding.SnapEpochStats) == 16 + 32 + 8 + 4 + 4 + 4 + 4 + 8 + 8
+
+
+def test_create_without_a_gpu_reports_an_error_instead_of_crashing():
+    """Host logic: argument checks come first; with no device the HIP failure is a return code."""
+    import numpy as np
+    import pytest
+    import torch
+    ptr = np.array([0, 1, 2], dtype=np.int64)
+    idx = np.array([0, 1], dtype=np.int32)
+    val = np.ones(2, dtype=np.float32)
+    y = np.array([1.0, -1.0], dtype=np.float32)
+    with pytest.raises(snap.SnapError) as e:                       # checked before any device call
+        snap.Solver("csc", 2, 2, ptr, idx, val, y, "hinge", 0.1)
+    assert e.value.code == -2
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", 2, 2, ptr, idx, val, y, "ridge", 0.0)
+    assert e.value.code == -1
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csr", 2, 2, ptr, idx, val, y, "ridge", 0.1)   # ridge needs the primal form, CSR gives the dual
+    assert e.value.code == -2
+    if not torch.cuda.is_available():
+        with pytest.raises(snap.SnapError) as e:
+            snap.Solver("csc", 2, 2, ptr, idx, val, y, "ridge", 0.1)
+        assert e.value.code in (-4, -3)
