@@ -398,3 +398,52 @@ def test_group_sweeps_wide_group_uses_32_bit_maps():
         assert relnorm(x, o.x) <= 2e-5
     assert rel(g.objective(), o.primal()) <= 1e-5
     g.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# the accept check (Section 3.1, "Adaptive Damping"): too much work in flight makes an epoch worse;
+# the epoch is discarded, the cap on work in flight halved, and the solver still converges
+def test_accept_check_discards_bad_epochs_and_recovers():
+    p = problem("cfg4_onehot_logistic")
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    target = oracle.solve(A, y, p.loss, p.lam, epochs=500, tol=1e-6).primal()
+    g = gpu_solver(p, max_inflight_nnz=1 << 30, profile=True)      # everything in flight: Jacobi on one-hot data
+    rejected, caps, prev = 0, [], g.objective()
+    for e in range(80):
+        g.epoch(e)
+        st = g.epoch_stats()
+        cur = g.objective()
+        if st["rejected"]:
+            rejected += 1
+            assert cur == pytest.approx(prev, rel=1e-12), "a discarded epoch must leave the state untouched"
+        else:
+            assert cur <= prev * (1 + 2e-6)
+        caps.append(st["inflight_nnz"])
+        prev = cur
+    assert rejected >= 1 and caps[-1] < caps[0]
+    assert rel(prev, target) <= 1e-4
+    # without the check the same setting does not get there
+    u = gpu_solver(p, max_inflight_nnz=1 << 30, adaptive=False)
+    for e in range(20):
+        u.epoch(e)
+    assert not (rel(u.objective(), target) <= 1e-4)
+    g.close()
+    u.close()
+
+
+def test_options_damping_and_refresh():
+    p = problem("cfg1_sparse_logistic")
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    target = oracle.solve(A, y, p.loss, p.lam, epochs=200, tol=1e-9).primal()
+    g = gpu_solver(p, damping=0.5, refresh_v_every=3, profile=True)
+    for e in range(60):
+        g.epoch(e)
+    assert g.epoch_stats()["damping"] == pytest.approx(0.5)
+    assert rel(g.objective(), target) <= 1e-4              # half steps still converge, more slowly
+    _, x = g.model()
+    chk = oracle.Solver(A, y, p.loss, p.lam)
+    chk.x[:] = x
+    assert relnorm(g.shared(), chk.shared_from_model()) <= 1e-5
+    g.close()
