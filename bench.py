@@ -251,15 +251,17 @@ def main():
             mc = min(batch, o.m - done)
             sl = np.ascontiguousarray(perm[done:done + mc])
             ts = time.perf_counter()
-            args_t = (C.c_double(o.lam), oracle._p(sl), C.c_int64(0), C.c_int64(mc), oracle._p(o.x), oracle._p(o.v))
+            args_t = (oracle._p(sl), C.c_int64(0), C.c_int64(mc), oracle._p(o.x), oracle._p(o.v))
+            lam_t = (C.c_double(o.lam), C.c_double(0.0))
             if o.form == "dual":
                 L.oracle_epoch_dual_hinge(C.c_int64(A.n), oracle._p(A.ptr), oracle._p(A.idx), oracle._p(A.val),
-                                          oracle._p(o.y), *args_t)
+                                          oracle._p(o.y), lam_t[0], *args_t)
             elif A.layout == "csc":
                 L.oracle_epoch_primal_sparse(C.c_int(o.loss), C.c_int64(A.n), oracle._p(A.ptr), oracle._p(A.idx),
-                                             oracle._p(A.val), oracle._p(o.y), *args_t)
+                                             oracle._p(A.val), oracle._p(o.y), *lam_t, *args_t)
             else:
-                L.oracle_epoch_primal_dense(C.c_int(o.loss), C.c_int64(A.n), oracle._p(A.val), oracle._p(o.y), *args_t)
+                L.oracle_epoch_primal_dense(C.c_int(o.loss), C.c_int64(A.n), oracle._p(A.val), oracle._p(o.y), *lam_t,
+                                            *args_t)
             t_cpu += time.perf_counter() - ts
             if A.ptr is not None:
                 nnz_done += int((A.ptr[sl.astype(np.int64) + 1] - A.ptr[sl.astype(np.int64)]).sum())

@@ -141,8 +141,10 @@ class Solver:
     GROUP_ORDER_CHUNK = 0xFFFFFFFF     # chunk id under which the order of the chunks is drawn
 
     def __init__(self, A: Matrix, y, loss: str, lam: float, chunk_bounds: Optional[Sequence[int]] = None,
-                 shuffle_chunks: bool = False):
-        self.A, self.y, self.loss, self.lam = A, _f32(y), LOSS_ID[loss], float(lam)
+                 shuffle_chunks: bool = False, lam1: float = 0.0):
+        self.A, self.y, self.loss, self.lam, self.lam1 = A, _f32(y), LOSS_ID[loss], float(lam), float(lam1)
+        if lam1 != 0.0 and A.layout == "csr":
+            raise ValueError("the l1 term belongs to the primal forms")
         if A.layout == "csr":
             if loss != "hinge":
                 raise ValueError("dual form is implemented for the hinge loss")
@@ -171,14 +173,16 @@ class Solver:
             c0, c1 = self.bounds[ch], self.bounds[ch + 1]
             perm = permutation(seed, c1 - c0, chunk=ch)
             perms.append(perm.astype(np.int64) + c0)
-            args = (C.c_double(self.lam), _p(perm), C.c_int64(c0), C.c_int64(c1 - c0), _p(self.x), _p(self.v))
+            tail = (_p(perm), C.c_int64(c0), C.c_int64(c1 - c0), _p(self.x), _p(self.v))
             if self.form == "dual":
-                L.oracle_epoch_dual_hinge(n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val), _p(self.y), *args)
+                L.oracle_epoch_dual_hinge(n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val), _p(self.y),
+                                          C.c_double(self.lam), *tail)
             elif self.A.layout == "csc":
-                L.oracle_epoch_primal_sparse(C.c_int(self.loss), n, _p(self.A.ptr), _p(self.A.idx),
-                                             _p(self.A.val), _p(self.y), *args)
+                L.oracle_epoch_primal_sparse(C.c_int(self.loss), n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val),
+                                             _p(self.y), C.c_double(self.lam), C.c_double(self.lam1), *tail)
             else:
-                L.oracle_epoch_primal_dense(C.c_int(self.loss), n, _p(self.A.val), _p(self.y), *args)
+                L.oracle_epoch_primal_dense(C.c_int(self.loss), n, _p(self.A.val), _p(self.y), C.c_double(self.lam),
+                                            C.c_double(self.lam1), *tail)
         self.last_perm = np.concatenate(perms)
 
     # model ----------------------------------------------------------------------------------
@@ -194,7 +198,7 @@ class Solver:
     # objectives -----------------------------------------------------------------------------
     def primal(self) -> float:
         if self.form == "primal":
-            return primal_objective(self.loss, self.v, self.y, self.x, self.lam)
+            return primal_objective(self.loss, self.v, self.y, self.x, self.lam, self.lam1)
         return self.primal_dual()[0]
 
     def primal_dual(self):
@@ -215,19 +219,21 @@ class Solver:
         if self.form == "dual":
             P, D = self.primal_dual()
             return P - D
-        return primal_gap(self.A, self.loss, self.v, self.y, self.x, self.lam, form)
+        if self.lam1 != 0.0:
+            form = "fenchel"              # the gradient form needs a differentiable regulariser
+        return primal_gap(self.A, self.loss, self.v, self.y, self.x, self.lam, form, self.lam1)
 
     def predict(self, X: Matrix) -> np.ndarray:
         return X.matvec(self.weights())
 
 
-def primal_objective(loss: int, z, y, w, lam: float) -> float:
+def primal_objective(loss: int, z, y, w, lam: float, lam1: float = 0.0) -> float:
     z, w, y = _f64(z), _f64(w), _f32(y)
     return float(lib().oracle_primal_objective(C.c_int(loss), C.c_int64(z.size), C.c_int64(w.size), _p(z), _p(y),
-                                               _p(w), C.c_double(lam)))
+                                               _p(w), C.c_double(lam), C.c_double(lam1)))
 
 
-def primal_gap(A: Matrix, loss: int, v, y, w, lam: float, form: str = "gradient") -> float:
+def primal_gap(A: Matrix, loss: int, v, y, w, lam: float, form: str = "gradient", lam1: float = 0.0) -> float:
     v, w, y = _f64(v), _f64(w), _f32(y)
     u = np.empty(A.n, dtype=np.float64)
     lib().oracle_primal_dual_candidate(C.c_int(loss), C.c_int64(A.n), _p(v), _p(y), _p(u))
@@ -235,14 +241,14 @@ def primal_gap(A: Matrix, loss: int, v, y, w, lam: float, form: str = "gradient"
     if form == "gradient":
         return float(lib().oracle_primal_gap_gradient(C.c_int64(A.d), _p(w), _p(xtu), C.c_double(lam)))
     return float(lib().oracle_primal_gap_fenchel(C.c_int(loss), C.c_int64(A.n), C.c_int64(A.d), _p(v), _p(y),
-                                                 _p(w), _p(u), _p(xtu), C.c_double(lam)))
+                                                 _p(w), _p(u), _p(xtu), C.c_double(lam), C.c_double(lam1)))
 
 
 def solve(A: Matrix, y, loss: str, lam: float, epochs: int, seed0: int = 0, tol: Optional[float] = None,
-          chunk_bounds=None, shuffle_chunks: bool = False) -> Solver:
+          chunk_bounds=None, shuffle_chunks: bool = False, lam1: float = 0.0) -> Solver:
     """Run `epochs` passes with permutation seeds seed0, seed0+1, ...; stop early when the gap
     falls below tol * max(1, |P|)."""
-    s = Solver(A, y, loss, lam, chunk_bounds, shuffle_chunks)
+    s = Solver(A, y, loss, lam, chunk_bounds, shuffle_chunks, lam1)
     for e in range(epochs):
         s.epoch(seed0 + e)
         if tol is not None and (e % 5 == 4 or e == epochs - 1):

@@ -22,6 +22,9 @@
  *               v = X^T (y o alpha) (length d), w = v/(lambda n);
  *               f(v) = ||v||^2/(2 lambda n^2),  g_i(a) = -a/n + indicator[0,1](a).
  *
+ * An optional l1 term (eq. (1) covers "sparse models such as lasso and elastic-net") turns the
+ * primal regulariser into g_j(w) = (lambda/2) w^2 + lambda1 |w|.
+ *
  * The paper leaves the objective scaling, the update formulas, the random-key generator and the
  * duality gap unstated; the readings taken are written next to each function.
  *
@@ -136,10 +139,29 @@ static double loss_d2(int loss, double y, double z)
 /*     g = (1/n) sum_i a_ij loss'(y_i, v_i) + lambda w_j                                         */
 /*     h = (1/n) sum_i a_ij^2 loss''(y_i, v_i) + lambda          ( >= lambda > 0 )               */
 /*     delta = -g/h ;  w_j += delta ;  v_i += delta a_ij on the column's support.                */
+/* With an l1 term the same quadratic model of the loss along w_j,                               */
+/*     gf delta + (hf/2) delta^2,  gf = (1/n) sum a loss',  hf = (1/n) sum a^2 loss'',            */
+/* plus (lambda/2)(w+delta)^2 + lambda1 |w+delta| is minimised exactly by soft-thresholding:      */
+/*     w_new = S(hf w - gf, lambda1) / (hf + lambda),   S(t, k) = sign(t) max(|t| - k, 0)         */
+/* (lambda1 = 0 gives the step above; for ridge loss it is the exact coordinate minimiser).       */
 /* ------------------------------------------------------------------------------------------- */
+static double soft_threshold(double t, double k)
+{
+    if (t > k) return t - k;
+    if (t < -k) return t + k;
+    return 0.0;
+}
+
+static double primal_step(double gsum, double hsum, double n, double lambda, double lambda1, double wj)
+{
+    double gf = gsum / n, hf = hsum / n;
+    if (lambda1 == 0.0) return -(gf + lambda * wj) / (hf + lambda);
+    return soft_threshold(hf * wj - gf, lambda1) / (hf + lambda) - wj;
+}
+
 static void primal_update_sparse(int loss, int64_t n, const int64_t *colptr, const int32_t *row,
-                                 const float *val, const float *y, double lambda, int64_t j,
-                                 double *w, double *v)
+                                 const float *val, const float *y, double lambda, double lambda1,
+                                 int64_t j, double *w, double *v)
 {
     double g = 0.0, h = 0.0;
     for (int64_t k = colptr[j]; k < colptr[j + 1]; ++k) {
@@ -148,25 +170,24 @@ static void primal_update_sparse(int loss, int64_t n, const int64_t *colptr, con
         g += a * loss_d1(loss, y[i], v[i]);
         h += a * a * loss_d2(loss, y[i], v[i]);
     }
-    g = g / (double)n + lambda * w[j];
-    h = h / (double)n + lambda;
-    double delta = -g / h;
+    double delta = primal_step(g, h, (double)n, lambda, lambda1, w[j]);
     w[j] += delta;
     for (int64_t k = colptr[j]; k < colptr[j + 1]; ++k) v[row[k]] += delta * (double)val[k];
 }
 
 /* Coordinates c0 + perm[0..mc) are visited in that order (c0 = first coordinate of the chunk). */
 void oracle_epoch_primal_sparse(int loss, int64_t n, const int64_t *colptr, const int32_t *row,
-                                const float *val, const float *y, double lambda,
+                                const float *val, const float *y, double lambda, double lambda1,
                                 const uint32_t *perm, int64_t c0, int64_t mc, double *w, double *v)
 {
     for (int64_t k = 0; k < mc; ++k)
-        primal_update_sparse(loss, n, colptr, row, val, y, lambda, c0 + perm[k], w, v);
+        primal_update_sparse(loss, n, colptr, row, val, y, lambda, lambda1, c0 + perm[k], w, v);
 }
 
 /* Dense column-major matrix: element (i, j) at A[j*n + i]. */
 void oracle_epoch_primal_dense(int loss, int64_t n, const float *A, const float *y, double lambda,
-                               const uint32_t *perm, int64_t c0, int64_t mc, double *w, double *v)
+                               double lambda1, const uint32_t *perm, int64_t c0, int64_t mc, double *w,
+                               double *v)
 {
     for (int64_t k = 0; k < mc; ++k) {
         int64_t j = c0 + perm[k];
@@ -176,9 +197,7 @@ void oracle_epoch_primal_dense(int loss, int64_t n, const float *A, const float 
             g += (double)a[i] * loss_d1(loss, y[i], v[i]);
             h += (double)a[i] * (double)a[i] * loss_d2(loss, y[i], v[i]);
         }
-        g = g / (double)n + lambda * w[j];
-        h = h / (double)n + lambda;
-        double delta = -g / h;
+        double delta = primal_step(g, h, (double)n, lambda, lambda1, w[j]);
         w[j] += delta;
         for (int64_t i = 0; i < n; ++i) v[i] += delta * (double)a[i];
     }
@@ -269,13 +288,16 @@ void oracle_dense_matvec(int64_t n, int64_t d, const float *A, const double *x, 
 /*     P(w) = (1/n) sum_i loss(y_i, z_i) + (lambda/2) ||w||^2,   z = X w.                         */
 /* ------------------------------------------------------------------------------------------- */
 double oracle_primal_objective(int loss, int64_t n, int64_t d, const double *z, const float *y,
-                               const double *w, double lambda)
+                               const double *w, double lambda, double lambda1)
 {
-    double s = 0.0, r = 0.0;
+    double s = 0.0, r = 0.0, a = 0.0;
 #pragma omp parallel for reduction(+ : s)
     for (int64_t i = 0; i < n; ++i) s += loss_value(loss, y[i], z[i]);
-    for (int64_t j = 0; j < d; ++j) r += w[j] * w[j];
-    return s / (double)n + 0.5 * lambda * r;
+    for (int64_t j = 0; j < d; ++j) {
+        r += w[j] * w[j];
+        a += fabs(w[j]);
+    }
+    return s / (double)n + 0.5 * lambda * r + lambda1 * a;
 }
 
 /* Hinge dual value D(alpha) from alpha and v = X^T (y o alpha). */
@@ -297,7 +319,7 @@ double oracle_hinge_dual_objective(int64_t n, int64_t d, const double *alpha, co
 /*        ridge:    u = (v - y)/n,        f*(u) = u.y + (n/2)||u||^2                              */
 /*        logistic: u_i = -y_i p_i/n, p_i = sigmoid(-y_i v_i),                                    */
 /*                  f*(u) = (1/n) sum_i [p_i ln p_i + (1-p_i) ln(1-p_i)]     (0 ln 0 := 0)         */
-/*        g_j*(t) = t^2/(2 lambda)                                                                */
+/*        g_j*(t) = t^2/(2 lambda);  with an l1 term  g_j*(t) = max(|t| - lambda1, 0)^2/(2 lambda) */
 /*  (b) gradient form   G = ||X^T u + lambda w||^2 / (2 lambda) = ||grad P(w)||^2/(2 lambda).     */
 /* ------------------------------------------------------------------------------------------- */
 static double xlogx(double p) { return p > 0.0 ? p * log(p) : 0.0; }
@@ -310,9 +332,10 @@ void oracle_primal_dual_candidate(int loss, int64_t n, const double *v, const fl
 }
 
 double oracle_primal_gap_fenchel(int loss, int64_t n, int64_t d, const double *v, const float *y,
-                                 const double *w, const double *u, const double *xtu, double lambda)
+                                 const double *w, const double *u, const double *xtu, double lambda,
+                                 double lambda1)
 {
-    double P = oracle_primal_objective(loss, n, d, v, y, w, lambda);
+    double P = oracle_primal_objective(loss, n, d, v, y, w, lambda, lambda1);
     double fstar = 0.0;
     if (loss == LOSS_RIDGE) {
         for (int64_t i = 0; i < n; ++i) fstar += u[i] * (double)y[i] + 0.5 * (double)n * u[i] * u[i];
@@ -324,7 +347,10 @@ double oracle_primal_gap_fenchel(int loss, int64_t n, int64_t d, const double *v
         fstar /= (double)n;
     }
     double gstar = 0.0;
-    for (int64_t j = 0; j < d; ++j) gstar += xtu[j] * xtu[j];
+    for (int64_t j = 0; j < d; ++j) {
+        double t = fabs(xtu[j]) - lambda1;
+        if (t > 0.0) gstar += t * t;
+    }
     gstar /= 2.0 * lambda;
     double D = -fstar - gstar;
     return P - D;

@@ -94,7 +94,8 @@ def test_ridge_objective_never_increases_per_update():
         for k in range(d):
             one = perm[k:k + 1].copy()
             lib.oracle_epoch_primal_sparse(C.c_int(0), C.c_int64(n), oracle._p(A.ptr), oracle._p(A.idx),
-                                           oracle._p(A.val), oracle._p(s.y), C.c_double(lam), oracle._p(one),
+                                           oracle._p(A.val), oracle._p(s.y), C.c_double(lam), C.c_double(0.0),
+                                           oracle._p(one),
                                            C.c_int64(0), C.c_int64(1), oracle._p(s.x), oracle._p(s.v))
             cur = P_ridge(X, y, s.x, lam)
             assert cur <= prev + 1e-15
@@ -359,3 +360,118 @@ def test_shuffled_chunks_visit_every_coordinate_once_and_converge():
     for e in range(400):
         s.epoch(e)
     np.testing.assert_allclose(s.x, ridge_closed_form(X, y.astype(np.float64), lam), atol=1e-10)
+
+
+# ---------------------------------------------------------------------------------------------
+# l1 / elastic-net term of the primal forms:  P(w) = (1/n) sum loss + (lam/2)||w||^2 + lam1 ||w||_1
+def kkt_violation(gf, w, lam, lam1):
+    """Distance of 0 from the subdifferential of P at w; gf = gradient of the loss term."""
+    r = gf + lam * w
+    nz = w != 0
+    out = np.zeros_like(w)
+    out[nz] = np.abs(r[nz] + lam1 * np.sign(w[nz]))
+    out[~nz] = np.maximum(np.abs(r[~nz]) - lam1, 0.0)
+    return float(out.max())
+
+
+@pytest.mark.parametrize("layout", ["csc", "dense"])
+def test_elastic_net_ridge_loss_against_sklearn(layout):
+    from sklearn.linear_model import ElasticNet
+    n, d, lam, lam1 = 120, 15, 0.02, 0.05
+    X = sparse_random(n, d, 0.5, rng)
+    wtrue = rng.standard_normal(d) * (rng.random(d) < 0.4)
+    y = (X @ wtrue + 0.1 * rng.standard_normal(n)).astype(np.float32)
+    A = dense_to_csc(X) if layout == "csc" else dense_colmajor(X)
+    s = oracle.solve(A, y, "ridge", lam, epochs=600, lam1=lam1)
+    # sklearn: 1/(2n)||y - Xw||^2 + alpha*l1_ratio*||w||_1 + alpha*(1-l1_ratio)/2*||w||^2
+    alpha = lam + lam1
+    ref = ElasticNet(alpha=alpha, l1_ratio=lam1 / alpha, fit_intercept=False, tol=1e-14, max_iter=100000)
+    ref.fit(X, y.astype(np.float64))
+    np.testing.assert_allclose(s.weights(), ref.coef_, atol=1e-9)
+    assert np.sum(s.weights() == 0.0) == np.sum(ref.coef_ == 0.0) > 0        # exact zeros, same support
+    P = P_ridge(X, y, s.weights(), lam) + lam1 * np.abs(s.weights()).sum()
+    assert s.primal() == pytest.approx(P, rel=1e-13)
+
+
+def test_elastic_net_one_update_minimises_the_coordinate_problem():
+    # ridge loss: the step is the exact minimiser along the coordinate -- check against a fine scan
+    n, d, lam, lam1 = 30, 4, 0.1, 0.08
+    X = sparse_random(n, d, 0.9, rng)
+    y = rng.standard_normal(n).astype(np.float32)
+    s = oracle.Solver(dense_to_csc(X), y, "ridge", lam, lam1=lam1)
+    s.x[:] = rng.standard_normal(d)
+    s.v[:] = X @ s.x
+    w0 = s.x.copy()
+    s.epoch(3)
+    j0 = int(s.last_perm[0])
+
+    def P(w):
+        return P_ridge(X, y, w, lam) + lam1 * np.abs(w).sum()
+    # replay the epoch coordinate by coordinate with a golden-section search on the 1-D problem
+    w = w0.copy()
+    for j in s.last_perm:
+        f = lambda t: P(np.concatenate([w[:j], [t], w[j + 1:]]))
+        t = scipy.optimize.minimize_scalar(f, bracket=(-3, 3), tol=1e-14).x
+        cand = [t, 0.0]                                     # the kink at 0 may be the minimiser
+        w[j] = min(cand, key=f)
+    np.testing.assert_allclose(s.x, w, atol=2e-7)
+    assert j0 in range(d)
+
+
+def test_l1_large_enough_gives_the_zero_model():
+    n, d, lam = 50, 6, 0.01
+    X = sparse_random(n, d, 0.7, rng)
+    y = rng.standard_normal(n).astype(np.float32)
+    lam1 = 1.0001 * np.abs(X.T @ y).max() / n               # ridge loss: gradient at 0 is -X^T y / n
+    s = oracle.solve(dense_to_csc(X), y, "ridge", lam, epochs=3, lam1=lam1)
+    assert np.all(s.weights() == 0.0) and np.all(s.v == 0.0)
+    yl = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    lam1 = 1.0001 * np.abs(X.T @ yl).max() / (2 * n)         # logistic: gradient at 0 is -X^T y / (2n)
+    s = oracle.solve(dense_to_csc(X), yl, "logistic", lam, epochs=3, lam1=lam1)
+    assert np.all(s.weights() == 0.0)
+    s = oracle.solve(dense_to_csc(X), yl, "logistic", lam, epochs=3, lam1=0.5 * lam1)
+    assert np.any(s.weights() != 0.0)
+
+
+@pytest.mark.parametrize("loss", ["ridge", "logistic"])
+def test_elastic_net_kkt_and_gap(loss):
+    n, d, lam, lam1 = 90, 12, 0.02, 0.03
+    X = sparse_random(n, d, 0.5, rng)
+    y = (rng.standard_normal(n) if loss == "ridge" else np.where(rng.random(n) < 0.45, 1.0, -1.0)).astype(np.float32)
+    A = dense_to_csc(X)
+    s = oracle.Solver(A, y, loss, lam, lam1=lam1)
+    # gap at w = 0: u = grad f(0), P + f*(u) = 0 for both losses, so the gap is sum_j g*(x_j.u)
+    gf0 = -X.T @ y / n / (1.0 if loss == "ridge" else 2.0)
+    g0 = np.sum(np.maximum(np.abs(gf0) - lam1, 0.0) ** 2) / (2 * lam)
+    assert s.gap() == pytest.approx(g0, rel=1e-10)
+    ref = oracle.solve(A, y, loss, lam, epochs=3000, tol=1e-16, lam1=lam1)
+    w = ref.weights()
+    z = X @ w
+    gf = X.T @ ((z - y) if loss == "ridge" else (-y / (1 + np.exp(y * z)))) / n
+    assert kkt_violation(gf, w, lam, lam1) < 1e-9          # entries of gf are ~3e-2
+    assert 0 < np.sum(w == 0.0) < d
+    Pfun = P_ridge if loss == "ridge" else P_logistic
+    Pstar = Pfun(X, y, w, lam) + lam1 * np.abs(w).sum()
+    assert ref.primal() == pytest.approx(Pstar, rel=1e-13)
+    # a perturbed model has a larger objective (w is the minimiser, not just a stationary point)
+    for _ in range(20):
+        wp = w + 1e-3 * rng.standard_normal(d)
+        assert Pfun(X, y, wp, lam) + lam1 * np.abs(wp).sum() > Pstar
+    last = None
+    for e in range(40):
+        s.epoch(e)
+        G = s.gap()
+        assert G >= s.primal() - Pstar - 1e-12
+        last = G
+    assert -1e-14 <= last < 1e-8 * g0                      # P + D* cancels to rounding at the optimum
+
+
+def test_l1_zero_reproduces_the_plain_step_and_dual_form_rejects_it():
+    n, d, lam = 40, 5, 0.05
+    X = sparse_random(n, d, 0.6, rng)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    a = oracle.solve(dense_to_csc(X), y, "logistic", lam, epochs=5)
+    b = oracle.solve(dense_to_csc(X), y, "logistic", lam, epochs=5, lam1=1e-300)   # takes the thresholded branch
+    np.testing.assert_allclose(a.x, b.x, rtol=0, atol=1e-15)
+    with pytest.raises(ValueError):
+        oracle.Solver(dense_to_csr(X), y, "hinge", lam, lam1=0.1)
