@@ -98,6 +98,12 @@ typedef struct {
                                     once -- identical to visiting them one by one, since they do not
                                     interact -- with plain coalesced updates of v instead of atomics. */
     int64_t n_groups;            /* 0: no groups */
+    double lambda1;              /* >= 0: weight of an l1 term in the primal forms (eq. (1): lasso / elastic-net
+                                    regularisers), P(w) = (1/n) sum loss + (lambda/2)||w||^2 + lambda1 ||w||_1.
+                                    The step soft-thresholds the minimiser of the quadratic model of the
+                                    coordinate problem; exact zeros are kept.  The duality gap is then the
+                                    Fenchel form P(w) + f*(u) + sum_j g*(-a_j.u), u = grad f(v),
+                                    g*(t) = max(|t| - lambda1, 0)^2 / (2 lambda).  Dual form: must be 0. */
 } snap_options;
 
 /* Per-epoch figures gathered when options.profile = 1 (milliseconds of device time).  With group

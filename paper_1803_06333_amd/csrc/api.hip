@@ -352,6 +352,10 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
         set_error("n_groups must be non-negative and come with group_bounds");
         return SNAP_EINVAL;
     }
+    if (!(o.lambda1 >= 0.0)) {
+        set_error("lambda1 must be non-negative");
+        return SNAP_EINVAL;
+    }
     int form = o.form;
     const bool row_coords = A->layout == SNAP_CSR || A->layout == SNAP_DENSE_ROWMAJOR;
     if (form == SNAP_FORM_AUTO) form = row_coords ? SNAP_DUAL : SNAP_PRIMAL;
@@ -365,6 +369,10 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
     }
     if ((form == SNAP_PRIMAL && loss == SNAP_HINGE) || (form == SNAP_DUAL && loss != SNAP_HINGE)) {
         set_error("supported pairs: (ridge, primal), (logistic, primal), (hinge, dual)");
+        return SNAP_EUNSUPPORTED;
+    }
+    if (form == SNAP_DUAL && o.lambda1 > 0.0) {
+        set_error("the l1 term belongs to the primal forms");
         return SNAP_EUNSUPPORTED;
     }
     snap_handle* h = new (std::nothrow) snap_handle();
@@ -384,6 +392,7 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
     h->vlen = form == SNAP_PRIMAL ? h->n : h->d;
     h->ld = dense ? h->vlen : 0;
     h->lambda = lambda;
+    h->lambda1 = o.lambda1;
     h->opt = o;
     const int rc = build(h, A, y);
     if (rc != SNAP_OK) {

@@ -78,7 +78,7 @@ struct snap_handle {
     int64_t ld = 0;                   // dense: elements per coordinate (= n)
     int64_t seg = snap::SEG_DEFAULT;  // nonzeros per work item of a split coordinate
     int64_t small_max = snap::SMALL_MAX_DEFAULT;   // longest coordinate handled by one wavefront
-    double lambda = 0;
+    double lambda = 0, lambda1 = 0;
     snap_options opt{};
     int device = 0;
 

@@ -289,7 +289,11 @@ enum ReduceMode {
     R_SUM = 3,           // a = x             : x
     R_GRADSQ = 4,        // d = gdot, a = x   : (gdot*s0 + s1*x)^2
     R_HINGE = 5,         // d = gdot, b = y   : max(0, 1 - y gdot s0)
-    R_LOSS_LOGISTIC_F32 = 6  // as R_LOSS_LOGISTIC with fp32 transcendentals (accept check of the epoch)
+    R_LOSS_LOGISTIC_F32 = 6, // as R_LOSS_LOGISTIC with fp32 transcendentals (accept check of the epoch)
+    R_ABSSUM = 7,        // a = x             : |x|
+    R_CONJ_RIDGE = 8,    // a = v, b = y      : n f*(u) at u = (v-y)/n        = (v-y) y + (v-y)^2/2
+    R_CONJ_LOGISTIC = 9, // a = v, b = y      : n f*(u) at u = -y p/n         = p ln p + (1-p) ln(1-p), p = sigmoid(-y v)
+    R_CONJ_REG = 10      // d = gdot          : max(|gdot s0| - s1, 0)^2      (2 lambda g*(a_j.u))
 };
 
 struct ReduceArgs {
@@ -316,6 +320,23 @@ __device__ __forceinline__ double reduce_term(const ReduceArgs& r, int64_t i) {
     }
     if (MODE == R_SQNORM) return (double)r.a[i] * (double)r.a[i];
     if (MODE == R_SUM) return (double)r.a[i];
+    if (MODE == R_ABSSUM) return fabs((double)r.a[i]);
+    if (MODE == R_CONJ_RIDGE) {
+        const double t = (double)r.a[i] - (double)r.b[i];
+        return t * (double)r.b[i] + 0.5 * t * t;
+    }
+    if (MODE == R_CONJ_LOGISTIC) {
+        // ln p = -log(1+exp(t)), ln(1-p) = -log(1+exp(-t)), t = y v
+        const double t = (double)r.b[i] * (double)r.a[i];
+        const double lp = t > 0 ? t + log1p(exp(-t)) : log1p(exp(t));
+        const double lq = t > 0 ? log1p(exp(-t)) : -t + log1p(exp(t));
+        const double p = exp(-lp);
+        return -(p * lp + (1.0 - p) * lq);
+    }
+    if (MODE == R_CONJ_REG) {
+        const double t = fabs(r.d[i] * r.s0) - r.s1;
+        return t > 0 ? t * t : 0.0;
+    }
     if (MODE == R_GRADSQ) {
         const double t = r.d[i] * r.s0 + r.s1 * (double)r.a[i];
         return t * t;
@@ -358,6 +379,12 @@ static int reduce_to(snap_handle* h, int mode, const ReduceArgs& r, int slot) {
     case R_LOSS_LOGISTIC_F32:
         hipLaunchKernelGGL((k_reduce_partial<R_LOSS_LOGISTIC_F32>), g, b, 0, h->compute, r, partial);
         break;
+    case R_ABSSUM: hipLaunchKernelGGL((k_reduce_partial<R_ABSSUM>), g, b, 0, h->compute, r, partial); break;
+    case R_CONJ_RIDGE: hipLaunchKernelGGL((k_reduce_partial<R_CONJ_RIDGE>), g, b, 0, h->compute, r, partial); break;
+    case R_CONJ_LOGISTIC:
+        hipLaunchKernelGGL((k_reduce_partial<R_CONJ_LOGISTIC>), g, b, 0, h->compute, r, partial);
+        break;
+    case R_CONJ_REG: hipLaunchKernelGGL((k_reduce_partial<R_CONJ_REG>), g, b, 0, h->compute, r, partial); break;
     default: hipLaunchKernelGGL((k_reduce_partial<R_HINGE>), g, b, 0, h->compute, r, partial); break;
     }
     hipLaunchKernelGGL(k_reduce_final, dim3(1), b, 0, h->compute, partial, REDUCE_BLOCKS, out);
@@ -387,7 +414,7 @@ __global__ void k_scale(const float* __restrict__ in, float s, float* __restrict
 // P, D and the gap.  Any of the outputs may be null; the gap (and D in primal form) needs one pass
 // over the matrix, P in primal form only the vectors.
 int objective(snap_handle* h, double* primal, double* dual, double* gap) {
-    const double n = (double)h->n, lam = h->lambda;
+    const double n = (double)h->n, lam = h->lambda, lam1 = h->lambda1;
     double* res = h->red.host;
     if (h->form == SNAP_PRIMAL) {
         const bool need_gap = gap != nullptr || dual != nullptr;
@@ -395,15 +422,24 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
         SNAP_TRY(reduce_to(h, h->loss == SNAP_RIDGE ? R_LOSS_RIDGE : R_LOSS_LOGISTIC, r, 0));
         ReduceArgs rx{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
         SNAP_TRY(reduce_to(h, R_SQNORM, rx, 1));
+        if (lam1 > 0.0) SNAP_TRY(reduce_to(h, R_ABSSUM, rx, 3));
         if (need_gap) {
             SNAP_TRY(coord_dots(h));
-            ReduceArgs rg{h->x, nullptr, h->gdot, 1.0 / n, lam, h->m};
-            SNAP_TRY(reduce_to(h, R_GRADSQ, rg, 2));
+            if (lam1 > 0.0) {
+                // Fenchel form: P + f*(u) + sum_j g*(a_j.u), u = grad f(v); a_j.u = gdot_j / n
+                ReduceArgs rg{nullptr, nullptr, h->gdot, 1.0 / n, lam1, h->m};
+                SNAP_TRY(reduce_to(h, R_CONJ_REG, rg, 2));
+                SNAP_TRY(reduce_to(h, h->loss == SNAP_RIDGE ? R_CONJ_RIDGE : R_CONJ_LOGISTIC, r, 4));
+            } else {
+                ReduceArgs rg{h->x, nullptr, h->gdot, 1.0 / n, lam, h->m};
+                SNAP_TRY(reduce_to(h, R_GRADSQ, rg, 2));
+            }
         }
         SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
         SNAP_HIP(hipStreamSynchronize(h->compute));
-        const double P = res[0] / n + 0.5 * lam * res[1];
-        const double G = need_gap ? res[2] / (2.0 * lam) : 0.0;
+        const double P = res[0] / n + 0.5 * lam * res[1] + (lam1 > 0.0 ? lam1 * res[3] : 0.0);
+        double G = 0.0;
+        if (need_gap) G = lam1 > 0.0 ? P + res[4] / n + res[2] / (2.0 * lam) : res[2] / (2.0 * lam);
         if (primal) *primal = P;
         if (gap) *gap = G;
         if (dual) *dual = P - G;
@@ -436,6 +472,7 @@ int monitor_value(snap_handle* h, double* value) {
         SNAP_TRY(reduce_to(h, h->loss == SNAP_RIDGE ? R_LOSS_RIDGE : R_LOSS_LOGISTIC_F32, r, 0));
         ReduceArgs rx{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
         SNAP_TRY(reduce_to(h, R_SQNORM, rx, 1));
+        if (h->lambda1 > 0.0) SNAP_TRY(reduce_to(h, R_ABSSUM, rx, 2));
     } else {
         ReduceArgs ra{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
         SNAP_TRY(reduce_to(h, R_SUM, ra, 0));
@@ -444,7 +481,7 @@ int monitor_value(snap_handle* h, double* value) {
     }
     SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));
-    if (h->form == SNAP_PRIMAL) *value = res[0] / n + 0.5 * lam * res[1];
+    if (h->form == SNAP_PRIMAL) *value = res[0] / n + 0.5 * lam * res[1] + (h->lambda1 > 0.0 ? h->lambda1 * res[2] : 0.0);
     else *value = -(res[0] / n - 0.5 * res[1] / (lam * n * n));     // -D(alpha)
     return SNAP_OK;
 }

@@ -7,6 +7,7 @@ namespace snap {
 
 struct StepParams {
     double lambda;
+    double lambda1;   // weight of the l1 term (primal forms)
     double inv_n;     // 1/n
     double lam_n;     // lambda * n
     double damping;   // in (0,1]: the step is scaled by it (Section 3.1, adaptive damping)
@@ -46,9 +47,18 @@ __device__ __forceinline__ float take_step(double g, double h, float xc, float n
                                            const StepParams& sp, float& mult) {
     float xn;
     if (KIND == K_PRIMAL_RIDGE || KIND == K_PRIMAL_LOGISTIC) {
-        const double G = g * sp.inv_n + sp.lambda * (double)xc;
-        const double H = (KIND == K_PRIMAL_RIDGE ? (double)norm : h) * sp.inv_n + sp.lambda;
-        xn = (float)((double)xc - sp.damping * G / H);
+        const double Gf = g * sp.inv_n;                                       // loss part of the gradient
+        const double Hf = (KIND == K_PRIMAL_RIDGE ? (double)norm : h) * sp.inv_n;
+        double step;
+        if (sp.lambda1 == 0.0) {
+            step = -(Gf + sp.lambda * (double)xc) / (Hf + sp.lambda);
+        } else {
+            // minimiser of Gf d + (Hf/2) d^2 + (lambda/2)(x+d)^2 + lambda1 |x+d|: soft threshold
+            const double t = Hf * (double)xc - Gf;
+            const double s = t > sp.lambda1 ? t - sp.lambda1 : (t < -sp.lambda1 ? t + sp.lambda1 : 0.0);
+            step = s / (Hf + sp.lambda) - (double)xc;
+        }
+        xn = (float)((double)xc + sp.damping * step);
         mult = (float)((double)xn - (double)xc);
     } else {
         double anew;
@@ -85,6 +95,7 @@ __device__ __forceinline__ void decode(uint32_t raw, uint32_t& r, float& yy, con
 inline StepParams make_step_params(const snap_handle* h) {
     StepParams sp;
     sp.lambda = h->lambda;
+    sp.lambda1 = h->lambda1;
     sp.inv_n = 1.0 / (double)h->n;
     sp.lam_n = h->lambda * (double)h->n;
     sp.damping = (double)h->damping;
