@@ -57,10 +57,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4,
                     help="benchmark configuration 1..5 (default: 4; 5 = streamed from pinned host memory)")
-    ap.add_argument("--mode", choices=["auto", "async", "groups"], default="auto",
-                    help="groups: exact sweeps over the one-hot fields (config 4); async: permutation-ordered "
-                         "asynchronous epoch with atomic write-back (any data); auto: groups for config 4 with "
-                         "the async path measured beside it, async otherwise")
+    ap.add_argument("--mode", choices=["auto", "async", "groups", "tiles"], default="auto",
+                    help="groups: exact sweeps over the one-hot fields (config 4); tiles: exact tile sweeps (dense "
+                         "ridge, config 2); async: permutation-ordered asynchronous epoch with atomic write-back "
+                         "(any data); auto: groups for config 4 with the async path measured beside it, tiles for "
+                         "config 2, async otherwise")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the row count (debugging only)")
     ap.add_argument("--budget-gib", type=float, default=16.0, help="config 5: device budget for the matrix")
     ap.add_argument("--chunk-gib", type=float, default=4.0, help="config 5: chunk size")
@@ -91,9 +92,9 @@ def main():
     snap.load_library()           # fails loudly when the HIP library is not built
     mode = args.mode
     if mode == "auto":
-        mode = "groups" if args.config == 4 else "async"
-    if mode == "groups" and args.config != 4:
-        print("bench.py: --mode groups needs the one-hot config 4", file=sys.stderr)
+        mode = {4: "groups", 2: "tiles"}.get(args.config, "async")
+    if (mode == "groups" and args.config != 4) or (mode == "tiles" and args.config != 2):
+        print("bench.py: --mode groups needs the one-hot config 4, --mode tiles the dense config 2", file=sys.stderr)
         sys.exit(2)
 
     t0 = time.time()
@@ -120,6 +121,8 @@ def main():
         gen_s += time.time() - t1
     if mode == "groups":
         kw["group_bounds"] = p.meta["field_starts"] + [p.d]
+    if dense:
+        kw["dense_tiles"] = mode == "tiles"
     t0 = time.time()
     g = snap.Solver.from_problem(p, profile=True, max_inflight_nnz=args.inflight, damping=args.damping, **kw)
     torch.cuda.synchronize()
@@ -139,6 +142,11 @@ def main():
         # words, read and write of v per row)
         passes = max(1, st["n_items"])
         dom, dom_ms, dom_bytes = "k_group_rows", kms["large_ms"] / passes, 16 * p.n
+    elif mode == "tiles":
+        # one pass reads the columns of two tiles (write-back of one, inner products of the next) and
+        # reads v, y and writes v once: 2 x 4 B per element per epoch plus 12 B per row per pass
+        passes = max(1, st["n_items"])
+        dom, dom_ms, dom_bytes = "k_tile_pass", kms["large_ms"] / passes, (8 * nnz + 12 * p.n * passes) / passes
     elif args.config == 5:
         dom, dom_ms, dom_bytes = "scd kernels of all chunks", kms["scd_ms"], alg_epoch
     elif kms["large_ms"] >= kms["small_ms"]:
@@ -173,7 +181,9 @@ def main():
         "damping": st["damping"], "rejected_epochs_in_sample": rejected,
         "generate_s": round(gen_s, 2), "create_s": round(create_s, 2),
     }
-    if mode == "groups":
+    if mode == "tiles":
+        out["tiles"] = {"n_tiles": st["n_chunks"], "row_passes_per_epoch": st["n_items"]}
+    elif mode == "groups":
         out["groups"] = {"n_groups": st["n_chunks"], "row_passes_per_epoch": st["n_items"],
                          "hot_coordinates": st["n_large"], "hot_nnz": st["nnz_large"],
                          "cold_coordinates": st["n_small"], "cold_nnz": st["nnz_small"]}

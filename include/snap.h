@@ -104,6 +104,16 @@ typedef struct {
                                     coordinate problem; exact zeros are kept.  The duality gap is then the
                                     Fenchel form P(w) + f*(u) + sum_j g*(-a_j.u), u = grad f(v),
                                     g*(t) = max(|t| - lambda1, 0)^2 / (2 lambda).  Dual form: must be 0. */
+    int dense_tiles;             /* exact tile sweeps for dense column-major ridge regression, resident data
+                                    (Section 3.1, dense data): tiles of 128 consecutive columns, visited in a
+                                    random order drawn from perm_seed (keys of the tiles under chunk id
+                                    0xFFFFFFFF), the columns of a tile in the order of their keys under the
+                                    tile's index as chunk id; the steps of a tile are taken one after the
+                                    other from inner products corrected with the tile's Gram block, so the
+                                    result is the sequential one and v is updated with plain stores.
+                                    0: automatic (used whenever it applies), 1: required (error when it does
+                                    not apply), 2: off (asynchronous epoch with atomic updates of v).
+                                    snap_get_chunks reports the tiles. */
 } snap_options;
 
 /* Per-epoch figures gathered when options.profile = 1 (milliseconds of device time).  With group

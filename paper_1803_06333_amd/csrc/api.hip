@@ -74,6 +74,7 @@ static void destroy(snap_handle* h) {
     (void)hipFree(h->x_snap);
     (void)hipFree(h->v_snap);
     stream_free(h);
+    dense_tiles_free(h);
     grouped_free(h);
     for (auto& e : h->ev)
         if (e) (void)hipEventDestroy(e);
@@ -248,7 +249,12 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
 
     // ---- one pass over the data: validation, norms, classes, access counts --------------------------
     // default: on for the asynchronous epoch; off for group sweeps, which are exact (no asynchrony to guard)
-    h->adaptive = h->opt.adaptive == 1 || (h->opt.adaptive == 0 && h->opt.n_groups == 0);
+    const bool use_tiles = h->opt.dense_tiles != 2 && h->opt.n_groups == 0 && dense_tiles_applicable(h);
+    if (h->opt.dense_tiles == 1 && !use_tiles) {
+        set_error("tile sweeps need dense column-major data, ridge loss, resident data and no groups");
+        return SNAP_EUNSUPPORTED;
+    }
+    h->adaptive = h->opt.adaptive == 1 || (h->opt.adaptive == 0 && h->opt.n_groups == 0 && !use_tiles);
     h->damping = h->opt.damping > 0.0f ? h->opt.damping : 1.0f;
     h->inflight_floor = WAVE;
     const bool auto_cap = h->opt.max_inflight_nnz <= 0 && !h->dense && !h->adaptive;
@@ -301,6 +307,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
         SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
     }
     if (h->opt.n_groups > 0) SNAP_TRY(grouped_setup(h, hptr.data()));
+    if (use_tiles) SNAP_TRY(dense_tiles_setup(h));
     return SNAP_OK;
 }
 
@@ -350,6 +357,10 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
     if (opt) o = *opt;
     if (o.n_groups < 0 || (o.n_groups > 0 && !o.group_bounds)) {
         set_error("n_groups must be non-negative and come with group_bounds");
+        return SNAP_EINVAL;
+    }
+    if (o.dense_tiles < 0 || o.dense_tiles > 2) {
+        set_error("dense_tiles must be 0, 1 or 2");
         return SNAP_EINVAL;
     }
     if (!(o.lambda1 >= 0.0)) {
@@ -430,7 +441,12 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         SNAP_TRY(grouped_epoch(h));
         if (prof) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
         h->perm_stale = true;
+    } else if (h->tiled) {
+        if (prof) SNAP_HIP(hipEventRecord(h->ev[1], h->compute));
         h->last_seed = perm_seed;
+        SNAP_TRY(dense_tiles_epoch(h));
+        if (prof) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
+        h->perm_stale = true;
     } else {
         SNAP_TRY(for_each_chunk(h, epoch_chunk, &perm_seed, /*fold=*/true, /*profile=*/prof));
     }
@@ -550,7 +566,8 @@ int snap_get_perm(snap_handle* h, uint32_t* perm_out, uint32_t* keys_out) {
         set_error("null argument");
         return SNAP_EINVAL;
     }
-    if (h->grouped && h->perm_stale) {
+    const bool blocks = h->grouped || h->tiled;      // coordinates visited block by block (groups / tiles)
+    if (blocks && h->perm_stale) {
         for (int64_t g = 0; g < h->n_groups; ++g) {
             const int64_t c0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - c0;
             SNAP_TRY(make_permutation(h, h->last_seed, (uint32_t)g, c0, sz, h->keys + c0, h->perm + c0, nullptr));
@@ -561,7 +578,7 @@ int snap_get_perm(snap_handle* h, uint32_t* perm_out, uint32_t* keys_out) {
     if (keys_out)
         SNAP_HIP(hipMemcpyAsync(keys_out, h->keys, (size_t)h->m * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));
-    if (h->grouped) {
+    if (blocks) {
         // stored group by group; reported in visiting order: groups in the epoch's order, the
         // permutation of each group inside
         std::vector<uint32_t> tmp(perm_out, perm_out + h->m), ktmp;
@@ -602,7 +619,7 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         h->stats.perm_ms = h->stats.large_ms = h->stats.small_ms = 0;
         h->stats_pending = false;
     }
-    if (h->stats_pending && h->grouped) {
+    if (h->stats_pending && (h->grouped || h->tiled)) {
         SNAP_HIP(hipEventSynchronize(h->ev[2]));
         float total = 0, rows = 0;
         SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
@@ -643,7 +660,7 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         h->stats.n_large += h->chunks[ch].n_large;
         h->stats.n_items += h->chunks[ch].n_items;
     }
-    if (h->grouped) {          // group sweeps: "large" = hot ranks (row passes), "small" = the rest, items = row passes
+    if (h->grouped || h->tiled) {   // group sweeps: "large" = hot ranks (row passes), "small" = the rest, items = row passes
         h->stats.n_chunks = h->n_groups;
         h->stats.n_large = h->g_hot_coords;
         h->stats.n_small = h->m - h->g_hot_coords;
@@ -660,7 +677,7 @@ int snap_get_chunks(snap_handle* h, int64_t* n_chunks, int64_t* bounds_out) {
         set_error("null argument");
         return SNAP_EINVAL;
     }
-    if (h->grouped) {
+    if (h->grouped || h->tiled) {
         *n_chunks = h->n_groups;
         if (bounds_out) std::copy(h->gbounds_host, h->gbounds_host + h->n_groups + 1, bounds_out);
         return SNAP_OK;

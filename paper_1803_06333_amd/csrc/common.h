@@ -153,6 +153,14 @@ struct snap_handle {
     bool perm_stale = false;          // grouped mode makes the visiting order only on request
     uint64_t last_seed = 0;
 
+    // exact tile sweeps (dense ridge): tiles of consecutive columns listed in gbounds_host / n_groups
+    bool tiled = false;
+    float* tgram = nullptr;           // [tiles][128][128] Gram blocks of the tiles
+    float* tpartial = nullptr;        // [tile_wgs][128] per-workgroup partial inner products of the current tile
+    float* tmult = nullptr;           // [2][128] steps of the previous / current tile
+    int64_t tile_wgs = 0;
+    int tile_vec = 4;                 // consecutive rows per thread of the row pass
+
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
     hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
@@ -195,6 +203,12 @@ int grouped_setup(snap_handle* h, const int64_t* hptr);
 int grouped_epoch(snap_handle* h);
 std::vector<int64_t> group_order(uint64_t seed, int64_t n_groups);   // visiting order of the groups for a seed
 void grouped_free(snap_handle* h);
+
+// dense_tiles.hip
+bool dense_tiles_applicable(const snap_handle* h);
+int dense_tiles_setup(snap_handle* h);
+int dense_tiles_epoch(snap_handle* h);
+void dense_tiles_free(snap_handle* h);
 
 int stream_alloc(snap_handle* h);
 void stream_free(snap_handle* h);

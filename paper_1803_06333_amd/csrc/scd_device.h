@@ -19,6 +19,26 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
+// The same sum through the data-parallel-primitive lane moves of the vector ALU (no LDS traffic):
+// all-reduce inside each row of 16 lanes (swap neighbours, swap pairs, rotate by 4, rotate by 8),
+// then the four row sums are read as scalars.  The result is uniform over the wavefront.
+__device__ __forceinline__ float wave_sum_dpp(float x) {
+    constexpr int QUAD_SWAP_1 = 0xB1;    // quad_perm [1,0,3,2]
+    constexpr int QUAD_SWAP_2 = 0x4E;    // quad_perm [2,3,0,1]
+    constexpr int ROW_ROR_4 = 0x124, ROW_ROR_8 = 0x128;
+    int xi = __float_as_int(x);
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, xi, QUAD_SWAP_1, 0xF, 0xF, false));
+    xi = __float_as_int(x);
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, xi, QUAD_SWAP_2, 0xF, 0xF, false));
+    xi = __float_as_int(x);
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, xi, ROW_ROR_4, 0xF, 0xF, false));
+    xi = __float_as_int(x);
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, xi, ROW_ROR_8, 0xF, 0xF, false));
+    xi = __float_as_int(x);
+    return __int_as_float(__builtin_amdgcn_readlane(xi, 0)) + __int_as_float(__builtin_amdgcn_readlane(xi, 16)) +
+           __int_as_float(__builtin_amdgcn_readlane(xi, 32)) + __int_as_float(__builtin_amdgcn_readlane(xi, 48));
+}
+
 __device__ __forceinline__ float load_shared(const float* v, uint32_t r) {
     // relaxed device-scope load: sees the other compute dies' atomic updates of v
     return __hip_atomic_load(v + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -39,6 +59,24 @@ __device__ __forceinline__ void accumulate(float a, float vv, float yy, float& g
     }
 }
 
+// Step of a primal coordinate from the loss part of the gradient Gf = (1/n) sum a loss', the curvature
+// Hf = (1/n) sum a^2 loss'' and rinv = 1/(Hf + lambda) (constant per coordinate for the ridge loss).
+__device__ __forceinline__ float primal_step(double Gf, double Hf, double rinv, float xc, const StepParams& sp,
+                                             float& mult) {
+    double step;
+    if (sp.lambda1 == 0.0) {
+        step = -(Gf + sp.lambda * (double)xc) * rinv;
+    } else {
+        // minimiser of Gf d + (Hf/2) d^2 + (lambda/2)(x+d)^2 + lambda1 |x+d|: soft threshold
+        const double t = Hf * (double)xc - Gf;
+        const double s = t - fmax(-sp.lambda1, fmin(t, sp.lambda1));       // t minus its clamp to [-lambda1, lambda1]
+        step = s * rinv - (double)xc;
+    }
+    const float xn = (float)((double)xc + sp.damping * step);
+    mult = (float)((double)xn - (double)xc);
+    return xn;
+}
+
 // The scalar step.  Returns the new value of the coordinate; `mult` receives the multiplier of a_j
 // that is added to v: the change actually applied to the fp32 coordinate (times y_i in the hinge
 // dual), so that v keeps tracking A x as closely as fp32 allows.
@@ -47,19 +85,8 @@ __device__ __forceinline__ float take_step(double g, double h, float xc, float n
                                            const StepParams& sp, float& mult) {
     float xn;
     if (KIND == K_PRIMAL_RIDGE || KIND == K_PRIMAL_LOGISTIC) {
-        const double Gf = g * sp.inv_n;                                       // loss part of the gradient
         const double Hf = (KIND == K_PRIMAL_RIDGE ? (double)norm : h) * sp.inv_n;
-        double step;
-        if (sp.lambda1 == 0.0) {
-            step = -(Gf + sp.lambda * (double)xc) / (Hf + sp.lambda);
-        } else {
-            // minimiser of Gf d + (Hf/2) d^2 + (lambda/2)(x+d)^2 + lambda1 |x+d|: soft threshold
-            const double t = Hf * (double)xc - Gf;
-            const double s = t > sp.lambda1 ? t - sp.lambda1 : (t < -sp.lambda1 ? t + sp.lambda1 : 0.0);
-            step = s / (Hf + sp.lambda) - (double)xc;
-        }
-        xn = (float)((double)xc + sp.damping * step);
-        mult = (float)((double)xn - (double)xc);
+        xn = primal_step(g * sp.inv_n, Hf, 1.0 / (Hf + sp.lambda), xc, sp, mult);
     } else {
         double anew;
         if (norm == 0.0f) {

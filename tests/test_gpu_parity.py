@@ -540,3 +540,79 @@ def test_elastic_net_error_paths():
     with pytest.raises(snap.SnapError) as e:
         gpu_solver(q, lam1=-1.0)
     assert e.value.code == -1
+
+
+# ---------------------------------------------------------------------------------------------
+# dense data: exact tile sweeps (ridge) and the asynchronous dense path (any loss)
+def _tile_bounds(d, b=128):
+    return list(range(0, d, b)) + [d]
+
+
+@pytest.mark.parametrize("n,d,lam1", [(20_000, 300, 0.0), (20_001, 70, 0.0), (5_003, 64, 0.0), (20_000, 300, 1e-4),
+                                      (900, 130, 0.0)])
+def test_dense_tile_sweeps_equal_sequential_oracle(n, d, lam1):
+    p = datagen.dense_ridge(n=n, d=d, seed=5)
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    bounds = _tile_bounds(d)
+    g = gpu_solver(p, lam1=lam1, dense_tiles=True)
+    assert g.chunk_bounds() == bounds
+    o = oracle.Solver(A, y, "ridge", p.lam, chunk_bounds=bounds, shuffle_chunks=True, lam1=lam1)
+    for e in range(6):
+        g.epoch(e)
+        o.epoch(e)
+        _, x = g.model()
+        assert relnorm(x, o.x) <= 2e-5, "model differs from the sequential oracle after epoch %d" % e
+        assert relnorm(g.shared(), o.v) <= 2e-5
+        assert rel(g.objective(), o.primal()) <= 1e-5
+        assert g.epoch_stats()["rejected"] == 0
+    assert np.array_equal(g.perm().astype(np.int64), o.last_perm)
+    # the maintained v is A x recomputed from the model
+    chk = oracle.Solver(A, y, "ridge", p.lam)
+    chk.x[:] = g.model()[1]
+    assert relnorm(g.shared(), chk.shared_from_model()) <= 1e-5
+    g.close()
+
+
+def test_dense_tile_sweeps_are_the_default_and_can_be_switched_off():
+    p = problem("cfg2_dense_ridge")
+    A = oracle.Matrix.from_problem(p)
+    ref = oracle.solve(A, p.y.numpy(), "ridge", p.lam, epochs=500, tol=1e-6)
+    g = gpu_solver(p)
+    assert g.chunk_bounds() == _tile_bounds(p.d)            # tiles in use
+    a = gpu_solver(p, dense_tiles=False)
+    assert a.chunk_bounds() == [0, p.d]                      # one chunk: asynchronous epoch
+    for e in range(20):
+        g.epoch(e)
+        a.epoch(e)
+    assert rel(g.objective(), ref.primal()) <= 1e-4
+    assert rel(a.objective(), ref.primal()) <= 1e-4
+    g.close()
+    a.close()
+    with pytest.raises(snap.SnapError) as e:
+        gpu_solver(problem("cfg1_sparse_logistic"), dense_tiles=True)
+    assert e.value.code == -2
+
+
+def test_dense_logistic_asynchronous_path():
+    p = datagen.dense_ridge(n=20_000, d=300, seed=8)
+    rng = np.random.default_rng(8)
+    X = p.val.numpy().reshape(p.d, p.n).T.astype(np.float64)
+    wstar = rng.standard_normal(p.d)
+    p.y = torch.from_numpy(np.where(X @ wstar + 0.1 * rng.standard_normal(p.n) > 0, 1.0, -1.0).astype(np.float32))
+    p.loss, p.lam = "logistic", 1e-3
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    ref = oracle.solve(A, y, "logistic", p.lam, epochs=500, tol=1e-6)
+    g = gpu_solver(p)
+    assert g.chunk_bounds() == [0, p.d]
+    best = None
+    for e in range(25):
+        g.epoch(e)
+        chk = oracle.Solver(A, y, "logistic", p.lam)
+        chk.x[:] = g.model()[1]
+        assert relnorm(g.shared(), chk.shared_from_model()) <= 1e-4
+        val = g.objective()
+        best = val if best is None else min(best, val)
+    assert rel(best, ref.primal()) <= 1e-4
+    g.close()
