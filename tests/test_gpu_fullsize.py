@@ -58,6 +58,65 @@ def test_config4_click_log_logistic_full_size():
     g.close()
 
 
+def test_config4_group_sweeps_full_size():
+    """The launch configuration bench.py times for config 4 (exact sweeps over the 39 one-hot fields).  The
+    sweeps are deterministic, so the oracle can replay the first two fields of the first epoch in closed
+    form, vectorised over the rows: the model of their columns is final for that epoch."""
+    seed = datagen.CONFIG_SEED + 4
+    p = datagen.config(4, device=DEV)
+    starts, n, lam = p.meta["field_starts"], p.n, p.lam
+    bounds = starts + [p.d]
+    g = snap.Solver.from_problem(p, group_bounds=bounds)
+    assert g.chunk_bounds() == bounds
+    g.epoch(0)
+    P1 = g.objective()
+    _, x = g.model()
+    x = x.astype(np.float64)
+    y = p.y.cpu().numpy().astype(np.float64)
+    order = oracle.permutation(0, 39, chunk=oracle.Solver.GROUP_ORDER_CHUNK)   # fields in visiting order
+    f0, f1 = int(order[0]), int(order[1])
+    # first field: every column from the zero model, loss' = -y/2, loss'' = 1/4
+    c0 = datagen.onehot_categories(n, p.d, seed, f0, "cpu").numpy()
+    size0 = bounds[f0 + 1] - bounds[f0]
+    gsum = np.bincount(c0, weights=-0.5 * y, minlength=size0)
+    hsum = 0.25 * np.bincount(c0, minlength=size0)
+    w0 = -(gsum / n) / (hsum / n + lam)
+    got0 = x[bounds[f0]:bounds[f0 + 1]]
+    assert np.linalg.norm(got0 - w0) <= 1e-5 * np.linalg.norm(w0)
+    # second field: one Newton step per column at v = (first field's model of the row's column)
+    v = w0[c0]
+    c1 = datagen.onehot_categories(n, p.d, seed, f1, "cpu").numpy()
+    size1 = bounds[f1 + 1] - bounds[f1]
+    prob = 1.0 / (1.0 + np.exp(y * v))                                      # sigmoid(-y v)
+    gsum = np.bincount(c1, weights=-y * prob, minlength=size1)
+    hsum = np.bincount(c1, weights=prob * (1.0 - prob), minlength=size1)
+    w1 = -(gsum / n) / (hsum / n + lam)
+    got1 = x[bounds[f1]:bounds[f1 + 1]]
+    assert np.linalg.norm(got1 - w1) <= 2e-5 * np.linalg.norm(w1)
+    assert np.max(np.abs(got1 - w1)) <= 1e-4 * np.max(np.abs(w1))
+    del c0, c1, prob, v
+    # later epochs: monotone objective, sampled rows of v, objective and gap by the oracle at the GPU's state
+    P = [P1]
+    for e in range(1, 4):
+        g.epoch(e)
+        P.append(g.objective())
+    assert P[3] < P[2] < P[1] < P[0] < np.log(2.0)
+    _, x = g.model()
+    v = g.shared()
+    rows = torch.from_numpy(np.unique(np.random.default_rng(6).integers(0, n, size=20000)))
+    want = np.zeros(rows.numel())
+    for f in range(39):
+        cat = datagen.onehot_categories(n, p.d, seed, f, "cpu", rows=rows).numpy()
+        want += x.astype(np.float64)[starts[f] + cat]
+    got = v[rows.numpy()].astype(np.float64)
+    assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want)
+    yf = p.y.cpu().numpy()
+    assert rel(P[3], oracle.primal_objective(oracle.LOGISTIC, v, yf, x, lam)) <= 1e-5
+    A = oracle.Matrix.from_problem(p)
+    assert rel(g.duality_gap(), oracle.primal_gap(A, oracle.LOGISTIC, v, yf, x, lam)) <= 1e-5
+    g.close()
+
+
 def test_config2_dense_ridge_full_size():
     """Exact tile sweeps (the configuration bench.py times) follow the sequential oracle at full size; the
     asynchronous dense kernel on the same data is judged by its objective."""
@@ -115,4 +174,47 @@ def test_config3_zipf_svm_full_size():
     vo = A.rmatvec(y.astype(np.float64) * a)
     assert np.linalg.norm(g.shared() - vo) <= 1e-4 * np.linalg.norm(vo)
     assert np.array_equal(g.perm(), oracle.permutation(5, p.n))
+    g.close()
+
+
+def test_config5_streamed_full_size():
+    """200 M rows held in pinned host memory and streamed in 4 GiB chunks (the configuration
+    bench.py --config 5 times): chunking, sampled rows of v against the generator's definition, the
+    objective by the oracle at the GPU's state."""
+    seed = datagen.CONFIG_SEED + 5
+    p = datagen.config(5, device=DEV)
+    assert p.n == 200_000_000 and p.d == 1_000_000 and p.nnz == 39 * p.n
+    for name in ("ptr", "idx", "val", "y"):
+        src = getattr(p, name)
+        dst = torch.empty(src.shape, dtype=src.dtype, pin_memory=True)
+        dst.copy_(src)
+        setattr(p, name, dst)
+        del src
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30, profile=True)
+    bounds = g.chunk_bounds()
+    ptr = p.ptr.numpy()
+    assert len(bounds) - 1 >= 15 and bounds[0] == 0 and bounds[-1] == p.d
+    assert all(8 * (ptr[b] - ptr[a]) <= (4 << 30) for a, b in zip(bounds, bounds[1:]))
+    P = [g.objective()]
+    assert rel(P[0], np.log(2.0)) <= 1e-6
+    for e in range(2):
+        g.epoch(e)
+        P.append(g.objective())
+    assert P[2] < P[1] < P[0]
+    st = g.epoch_stats()
+    assert st["n_chunks"] == len(bounds) - 1
+    assert st["copy_ms"] > 0 and st["scd_ms"] > 0 and st["epoch_ms"] < st["copy_ms"] + st["scd_ms"]   # overlapped
+    _, x = g.model()
+    v = g.shared()
+    rows = torch.from_numpy(np.unique(np.random.default_rng(7).integers(0, p.n, size=20000)))
+    starts = p.meta["field_starts"]
+    want = np.zeros(rows.numel())
+    for f in range(39):
+        cat = datagen.onehot_categories(p.n, p.d, seed, f, "cpu", rows=rows).numpy()
+        want += x.astype(np.float64)[starts[f] + cat]
+    got = v[rows.numpy()].astype(np.float64)
+    assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want)
+    assert rel(P[2], oracle.primal_objective(oracle.LOGISTIC, v, p.y.numpy(), x, p.lam)) <= 1e-5
     g.close()
