@@ -33,6 +33,7 @@ def lib():
         L.oracle_perm.restype = C.c_int
         L.oracle_primal_objective.restype = C.c_double
         L.oracle_hinge_dual_objective.restype = C.c_double
+        L.oracle_logistic_dual_objective.restype = C.c_double
         L.oracle_primal_gap_fenchel.restype = C.c_double
         L.oracle_primal_gap_gradient.restype = C.c_double
         _lib = L
@@ -136,7 +137,8 @@ class Matrix:
 
 class Solver:
     """Sequential SCD on one problem.  form: 'primal' (CSC / dense, ridge or logistic) or 'dual'
-    (CSR, hinge).  State starts at zero (Algorithm 1's starting point)."""
+    (CSR, hinge or logistic).  State starts at zero (Algorithm 1's starting point); the logistic dual
+    at alpha = 1/2."""
 
     GROUP_ORDER_CHUNK = 0xFFFFFFFF     # chunk id under which the order of the chunks is drawn
 
@@ -146,8 +148,8 @@ class Solver:
         if lam1 != 0.0 and A.layout == "csr":
             raise ValueError("the l1 term belongs to the primal forms")
         if A.layout == "csr":
-            if loss != "hinge":
-                raise ValueError("dual form is implemented for the hinge loss")
+            if loss == "ridge":
+                raise ValueError("dual form is implemented for the hinge and logistic losses")
             self.form, self.m, self.vlen = "dual", A.n, A.d
         else:
             if loss == "hinge":
@@ -155,6 +157,10 @@ class Solver:
             self.form, self.m, self.vlen = "primal", A.d, A.n
         self.x = np.zeros(self.m, dtype=np.float64)      # w (primal) or alpha (dual)
         self.v = np.zeros(self.vlen, dtype=np.float64)   # shared vector
+        if self.form == "dual" and loss == "logistic":
+            # the entropy term needs alpha inside (0,1): start at 1/2, v = X^T (y o alpha)
+            self.x[:] = 0.5
+            self.v = A.rmatvec(self.y.astype(np.float64) * self.x)
         # streaming: coordinates are visited chunk by chunk, permuted inside each chunk
         self.bounds = [0, self.m] if chunk_bounds is None else list(chunk_bounds)
         # shuffle_chunks: the chunks themselves are visited in a seeded random order (their keys under
@@ -175,8 +181,8 @@ class Solver:
             perms.append(perm.astype(np.int64) + c0)
             tail = (_p(perm), C.c_int64(c0), C.c_int64(c1 - c0), _p(self.x), _p(self.v))
             if self.form == "dual":
-                L.oracle_epoch_dual_hinge(n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val), _p(self.y),
-                                          C.c_double(self.lam), *tail)
+                fn = L.oracle_epoch_dual_hinge if self.loss == HINGE else L.oracle_epoch_dual_logistic
+                fn(n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val), _p(self.y), C.c_double(self.lam), *tail)
             elif self.A.layout == "csc":
                 L.oracle_epoch_primal_sparse(C.c_int(self.loss), n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val),
                                              _p(self.y), C.c_double(self.lam), C.c_double(self.lam1), *tail)
@@ -206,14 +212,15 @@ class Solver:
         w = self.weights()
         xw = self.A.matvec(w)
         P, D = C.c_double(), C.c_double()
-        lib().oracle_hinge_primal_dual(C.c_int64(self.A.n), C.c_int64(self.A.d), _p(self.x), _p(self.v),
-                                       _p(xw), _p(self.y), C.c_double(self.lam), C.byref(P), C.byref(D))
+        fn = lib().oracle_hinge_primal_dual if self.loss == HINGE else lib().oracle_logistic_primal_dual
+        fn(C.c_int64(self.A.n), C.c_int64(self.A.d), _p(self.x), _p(self.v), _p(xw), _p(self.y),
+           C.c_double(self.lam), C.byref(P), C.byref(D))
         return P.value, D.value
 
     def dual(self) -> float:
         assert self.form == "dual"
-        return float(lib().oracle_hinge_dual_objective(C.c_int64(self.A.n), C.c_int64(self.A.d), _p(self.x),
-                                                       _p(self.v), C.c_double(self.lam)))
+        fn = lib().oracle_hinge_dual_objective if self.loss == HINGE else lib().oracle_logistic_dual_objective
+        return float(fn(C.c_int64(self.A.n), C.c_int64(self.A.d), _p(self.x), _p(self.v), C.c_double(self.lam)))
 
     def gap(self, form: str = "gradient") -> float:
         if self.form == "dual":

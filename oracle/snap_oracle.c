@@ -18,9 +18,10 @@
  *
  *  primal form: coordinates are features, alpha = w, A = X, v = X w (length n);
  *               f(v) = (1/n) sum_i loss(y_i, v_i),  g_j(w_j) = (lambda/2) w_j^2.
- *  dual form (hinge): coordinates are examples, alpha in [0,1]^n, A = X^T diag(y),
- *               v = X^T (y o alpha) (length d), w = v/(lambda n);
- *               f(v) = ||v||^2/(2 lambda n^2),  g_i(a) = -a/n + indicator[0,1](a).
+ *  dual form: coordinates are examples, alpha in [0,1]^n, A = X^T diag(y),
+ *               v = X^T (y o alpha) (length d), w = v/(lambda n); f(v) = ||v||^2/(2 lambda n^2);
+ *               hinge:    g_i(a) = -a/n + indicator[0,1](a);
+ *               logistic: g_i(a) = (a ln a + (1-a) ln(1-a))/n on (0,1).
  *
  * An optional l1 term (eq. (1) covers "sparse models such as lasso and elastic-net") turns the
  * primal regulariser into g_j(w) = (lambda/2) w^2 + lambda1 |w|.
@@ -31,7 +32,8 @@
  * Pinned (tests/test_oracle_*.py): ridge against the normal equations, logistic against brute
  * force and an independent quasi-Newton solve, hinge against brute-force primal minimisation and
  * the box/monotonicity invariants, the gap against its closed forms and P - P*, the sparse
- * products against dense matmul.  Parity unpinned: nothing in this file.
+ * products against dense matmul, the logistic dual against the primal logistic solution (strong
+ * duality, alpha* = sigmoid(-y x.w*)) and brute force.  Parity unpinned: nothing in this file.
  */
 #include <math.h>
 #include <stdint.h>
@@ -284,6 +286,47 @@ void oracle_dense_matvec(int64_t n, int64_t d, const float *A, const double *x, 
 }
 
 /* ------------------------------------------------------------------------------------------- */
+/* One dual coordinate update for the logistic loss (Section 3.1: no closed form, a single       */
+/* Newton step from the previous value).  With the conjugate of the logistic loss the dual is    */
+/*     D(alpha) = -(1/n) sum_i [alpha_i ln alpha_i + (1-alpha_i) ln(1-alpha_i)]                   */
+/*                - (lambda/2) ||w(alpha)||^2,     alpha in (0,1)^n,  w = v/(lambda n),           */
+/* and along alpha_i, with m = y_i x_i.w and q = ||x_i||^2/(lambda n),                            */
+/*     -n dD/dalpha_i = ln(alpha_i/(1-alpha_i)) + m,     -n d2D/dalpha_i^2 = 1/(alpha_i(1-alpha_i)) + q. */
+/* Readings taken where the paper is silent: the start is alpha_i = 1/2 (the entropy is not       */
+/* defined at Algorithm 1's alpha = 0; 1/2 is the dual optimum of w = 0), and the Newton iterate   */
+/* is clipped to [2^-20, 1 - 2^-20], both exactly representable in fp32.                          */
+/* ------------------------------------------------------------------------------------------- */
+#define ORACLE_ALPHA_EPS (1.0 / 1048576.0)
+
+void oracle_epoch_dual_logistic(int64_t n, const int64_t *rowptr, const int32_t *col, const float *val,
+                                const float *y, double lambda, const uint32_t *perm, int64_t c0,
+                                int64_t mc, double *alpha, double *v)
+{
+    const double ln = lambda * (double)n;
+    for (int64_t k = 0; k < mc; ++k) {
+        int64_t i = c0 + perm[k];
+        double dot = 0.0, nrm = 0.0;
+        for (int64_t t = rowptr[i]; t < rowptr[i + 1]; ++t) {
+            dot += (double)val[t] * v[col[t]];
+            nrm += (double)val[t] * (double)val[t];
+        }
+        double a = alpha[i];
+        double m = (double)y[i] * dot / ln;
+        double q = nrm / ln;
+        double g = log(a) - log1p(-a) + m;
+        double h = 1.0 / (a * (1.0 - a)) + q;
+        double anew = a - g / h;
+        if (anew < ORACLE_ALPHA_EPS) anew = ORACLE_ALPHA_EPS;
+        if (anew > 1.0 - ORACLE_ALPHA_EPS) anew = 1.0 - ORACLE_ALPHA_EPS;
+        double delta = anew - a;
+        alpha[i] = anew;
+        if (delta != 0.0)
+            for (int64_t t = rowptr[i]; t < rowptr[i + 1]; ++t)
+                v[col[t]] += delta * (double)y[i] * (double)val[t];
+    }
+}
+
+/* ------------------------------------------------------------------------------------------- */
 /* Objectives.  Reading taken for the scaling that eq. (1) leaves open:                          */
 /*     P(w) = (1/n) sum_i loss(y_i, z_i) + (lambda/2) ||w||^2,   z = X w.                         */
 /* ------------------------------------------------------------------------------------------- */
@@ -308,6 +351,19 @@ double oracle_hinge_dual_objective(int64_t n, int64_t d, const double *alpha, co
     for (int64_t j = 0; j < d; ++j) vv += v[j] * v[j];
     double ln = lambda * (double)n;
     return sa / (double)n - 0.5 * lambda * vv / (ln * ln);
+}
+
+/* Logistic dual value D(alpha) from alpha and v = X^T (y o alpha)  (0 ln 0 := 0). */
+double oracle_logistic_dual_objective(int64_t n, int64_t d, const double *alpha, const double *v, double lambda)
+{
+    double ent = 0.0, vv = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double a = alpha[i], b = 1.0 - alpha[i];
+        ent += (a > 0.0 ? a * log(a) : 0.0) + (b > 0.0 ? b * log(b) : 0.0);
+    }
+    for (int64_t j = 0; j < d; ++j) vv += v[j] * v[j];
+    double ln = lambda * (double)n;
+    return -ent / (double)n - 0.5 * lambda * vv / (ln * ln);
 }
 
 /* ------------------------------------------------------------------------------------------- */
@@ -381,4 +437,16 @@ void oracle_hinge_primal_dual(int64_t n, int64_t d, const double *alpha, const d
     }
     *P = hs / (double)n + 0.5 * lambda * ww;
     *D = sa / (double)n - 0.5 * lambda * ww;
+}
+
+/* Logistic, dual form: w = v/(lambda n), xw = X w supplied;
+ *   P = (1/n) sum log(1 + exp(-y_i x_i.w)) + (lambda/2)||w||^2,  D as above,  G = P - D. */
+void oracle_logistic_primal_dual(int64_t n, int64_t d, const double *alpha, const double *v,
+                                 const double *xw, const float *y, double lambda, double *P, double *D)
+{
+    double ln = lambda * (double)n, ww = 0.0, ls = 0.0;
+    for (int64_t j = 0; j < d; ++j) ww += (v[j] / ln) * (v[j] / ln);
+    for (int64_t i = 0; i < n; ++i) ls += log1pexp(-(double)y[i] * xw[i]);
+    *P = ls / (double)n + 0.5 * lambda * ww;
+    *D = oracle_logistic_dual_objective(n, d, alpha, v, lambda);
 }

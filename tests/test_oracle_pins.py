@@ -475,3 +475,93 @@ def test_l1_zero_reproduces_the_plain_step_and_dual_form_rejects_it():
     np.testing.assert_allclose(a.x, b.x, rtol=0, atol=1e-15)
     with pytest.raises(ValueError):
         oracle.Solver(dense_to_csr(X), y, "hinge", lam, lam1=0.1)
+
+
+# ---------------------------------------------------------------------------------------------
+# logistic regression in the dual form (examples as coordinates)
+def D_logistic(X, y, alpha, lam):
+    """Independent numpy definition of the logistic dual (conjugate of log(1+exp(-z)) is the entropy)."""
+    n = X.shape[0]
+    w = X.T @ (y * alpha) / (lam * n)
+    ent = np.sum(alpha * np.log(alpha) + (1 - alpha) * np.log1p(-alpha))
+    return -ent / n - 0.5 * lam * w @ w
+
+
+def test_dual_logistic_start_and_one_newton_step():
+    n, d, lam = 12, 4, 0.1
+    X = sparse_random(n, d, 0.8, rng)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    s = oracle.Solver(dense_to_csr(X), y, "logistic", lam)
+    assert s.form == "dual" and np.all(s.x == 0.5)
+    np.testing.assert_allclose(s.v, X.T @ (0.5 * y), atol=1e-14)
+    assert s.dual() == pytest.approx(D_logistic(X, y, s.x, lam), rel=1e-13)
+    a0 = s.x.copy()
+    s.epoch(0)
+    # replay with derivatives of D taken numerically (central differences), coordinate by coordinate
+    a = a0.copy()
+    for i in s.last_perm:
+        f = lambda t: -n * D_logistic(X, y, np.concatenate([a[:i], [t], a[i + 1:]]), lam)
+        e = 1e-5
+        g = (f(a[i] + e) - f(a[i] - e)) / (2 * e)
+        h = (f(a[i] + e) - 2 * f(a[i]) + f(a[i] - e)) / (e * e)
+        a[i] = min(max(a[i] - g / h, 2.0 ** -20), 1 - 2.0 ** -20)
+    np.testing.assert_allclose(s.x, a, atol=2e-5)
+    np.testing.assert_allclose(s.v, X.T @ (y * s.x), atol=1e-12)
+
+
+def test_dual_logistic_reaches_the_primal_solution():
+    n, d, lam = 80, 6, 0.05
+    X = sparse_random(n, d, 0.7, rng)
+    wtrue = rng.standard_normal(d)
+    y = np.where(X @ wtrue + 0.5 * rng.standard_normal(n) > 0, 1.0, -1.0).astype(np.float32)
+    # independent primal solution (quasi-Newton on the numpy objective)
+    res = scipy.optimize.minimize(lambda w: P_logistic(X, y, w, lam), np.zeros(d), method="L-BFGS-B",
+                                  jac=lambda w: X.T @ (-y / (1 + np.exp(y * (X @ w)))) / n + lam * w,
+                                  options={"ftol": 1e-16, "gtol": 1e-12, "maxiter": 5000})
+    wstar, Pstar = res.x, res.fun
+    s = oracle.Solver(dense_to_csr(X), y, "logistic", lam)
+    prev_gap = None
+    for e in range(300):
+        s.epoch(e)
+        P, D = s.primal_dual()
+        assert P >= D - 1e-13                                            # weak duality at every iterate
+        assert D <= Pstar + 1e-12 and P >= Pstar - 1e-12
+        assert s.x.min() >= 2.0 ** -20 and s.x.max() <= 1 - 2.0 ** -20    # stays inside the box
+        prev_gap = P - D
+    assert prev_gap < 1e-10
+    np.testing.assert_allclose(s.weights(), wstar, atol=1e-6)
+    assert s.dual() == pytest.approx(Pstar, abs=1e-10)                    # strong duality
+    np.testing.assert_allclose(s.x, 1 / (1 + np.exp(y * (X @ wstar))), atol=1e-6)   # alpha* = sigmoid(-y x.w*)
+    assert s.dual() == pytest.approx(D_logistic(X, y, s.x, lam), rel=1e-12)
+    assert s.primal() == pytest.approx(P_logistic(X, y, s.weights(), lam), rel=1e-12)
+
+
+def test_dual_logistic_two_examples_brute_force():
+    X = np.array([[1.0, 0.5], [-0.75, 1.25]], dtype=np.float32).astype(np.float64)
+    y = np.array([1.0, -1.0], dtype=np.float32)
+    lam = 0.3
+    s = oracle.solve(dense_to_csr(X), y, "logistic", lam, epochs=200)
+    g = np.linspace(0.001, 0.999, 999)
+    A1, A2 = np.meshgrid(g, g, indexing="ij")
+    W = (np.outer(A1.ravel() * y[0], X[0]) + np.outer(A2.ravel() * y[1], X[1])) / (lam * 2)
+    ent = A1 * np.log(A1) + (1 - A1) * np.log(1 - A1) + A2 * np.log(A2) + (1 - A2) * np.log(1 - A2)
+    Dg = -ent.ravel() / 2 - 0.5 * lam * np.sum(W * W, axis=1)
+    k = int(np.argmax(Dg))
+    assert abs(s.x[0] - A1.ravel()[k]) <= 0.002 and abs(s.x[1] - A2.ravel()[k]) <= 0.002
+    assert s.dual() >= Dg[k] - 1e-12
+
+
+def test_dual_logistic_well_separated_examples_leave_the_boundary():
+    # margins large enough that the first Newton step from 1/2 overshoots and is clipped; the iterates
+    # then have to grow back from the clip value to alpha* = sigmoid(-margin)
+    n, d, lam = 6, 2, 0.02
+    X = np.array([[3.0, 0.0], [2.5, 0.5], [-3.0, 0.2], [0.1, 2.0], [-0.2, -2.5], [2.0, 2.0]])
+    y = np.sign(X @ np.array([1.0, 1.0])).astype(np.float32)
+    s = oracle.Solver(dense_to_csr(X), y, "logistic", lam)
+    s.epoch(0)
+    assert np.any(s.x == 2.0 ** -20)
+    for e in range(1, 400):
+        s.epoch(e)
+    w = s.weights()
+    np.testing.assert_allclose(s.x, 1 / (1 + np.exp(y * (X @ w))), rtol=1e-6)
+    assert s.gap() < 1e-10
