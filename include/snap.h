@@ -10,8 +10,12 @@
  *
  *   primal form (CSC or dense column-major; ridge, logistic): coordinates = columns, model w,
  *                v = X w (length n_rows);
- *   dual form   (CSR; hinge): coordinates = rows, model alpha in [0,1]^n, v = X^T (y o alpha)
- *                (length n_cols), w = v / (lambda n).
+ *   dual form   (CSR; hinge, logistic): coordinates = rows, model alpha in [0,1]^n,
+ *                v = X^T (y o alpha) (length n_cols), w = v / (lambda n).  Hinge: closed-form step
+ *                clipped to [0,1], start alpha = 0.  Logistic (Section 3.1: a single Newton step
+ *                from the previous value): D(alpha) = -(1/n) sum [alpha ln alpha + (1-alpha)
+ *                ln(1-alpha)] - (lambda/2)||w||^2, start alpha = 1/2, iterates kept in
+ *                [2^-20, 1 - 2^-20] (snap_set_model clips to that range).
  *
  * One coordinate update = gather-dot of the coordinate's nonzeros with v, a scalar step (closed
  * form for ridge and the clipped hinge dual, one Newton step for logistic), and an atomic scatter
@@ -152,13 +156,14 @@ int snap_create(const snap_matrix *A, const float *y, int loss, double lambda,
  * waits for the epoch and applies the accept / discard decision. */
 int snap_epoch(snap_handle *h, uint64_t perm_seed);
 
-/* P(w) above and, in the dual form, D(alpha) = (1/n) sum alpha_i - (lambda/2)||w||^2.
+/* P(w) above and, in the dual form, D(alpha) = (1/n) sum alpha_i - (lambda/2)||w||^2 (hinge; the
+ * logistic dual is given with the forms above).
  * `dual` may be NULL; in the primal form *dual receives P - gap.  fp32 data, fp64 reductions in a
  * fixed order (deterministic). */
 int snap_objective(snap_handle *h, double *primal, double *dual);
 
 /* Duality gap of eq. (1) with the dual candidate u = grad f(v): primal form
- * ||X^T u + lambda w||^2 / (2 lambda); hinge dual form P(w(alpha)) - D(alpha).  Deterministic. */
+ * ||X^T u + lambda w||^2 / (2 lambda); dual form P(w(alpha)) - D(alpha).  Deterministic. */
 int snap_duality_gap(snap_handle *h, double *gap);
 
 /* Decision values out[i] = x_i . w for the rows of X (CSR, dense row-major or dense

@@ -308,6 +308,11 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     }
     if (h->opt.n_groups > 0) SNAP_TRY(grouped_setup(h, hptr.data()));
     if (use_tiles) SNAP_TRY(dense_tiles_setup(h));
+    if (h->form == SNAP_DUAL && h->loss == SNAP_LOGISTIC && m > 0) {
+        // the entropy term of the logistic dual needs alpha inside (0,1): start at 1/2, v = A alpha
+        SNAP_TRY(fill_value(h->x, 0.5f, m, h->compute));
+        SNAP_TRY(recompute_shared(h));
+    }
     return SNAP_OK;
 }
 
@@ -378,8 +383,8 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
         set_error("the primal form needs column access (CSC / dense column-major), the dual form row access");
         return SNAP_EUNSUPPORTED;
     }
-    if ((form == SNAP_PRIMAL && loss == SNAP_HINGE) || (form == SNAP_DUAL && loss != SNAP_HINGE)) {
-        set_error("supported pairs: (ridge, primal), (logistic, primal), (hinge, dual)");
+    if ((form == SNAP_PRIMAL && loss == SNAP_HINGE) || (form == SNAP_DUAL && loss == SNAP_RIDGE)) {
+        set_error("supported pairs: (ridge, primal), (logistic, primal), (logistic, dual), (hinge, dual)");
         return SNAP_EUNSUPPORTED;
     }
     if (form == SNAP_DUAL && o.lambda1 > 0.0) {
@@ -394,7 +399,7 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
     h->layout = A->layout;
     h->loss = loss;
     h->form = form;
-    h->kind = loss == SNAP_RIDGE ? K_PRIMAL_RIDGE : (loss == SNAP_LOGISTIC ? K_PRIMAL_LOGISTIC : K_DUAL_HINGE);
+    h->kind = form == SNAP_DUAL ? K_DUAL : (loss == SNAP_RIDGE ? K_PRIMAL_RIDGE : K_PRIMAL_LOGISTIC);
     h->dense = dense;
     h->n = A->n_rows;
     h->d = A->n_cols;
@@ -536,6 +541,8 @@ int snap_set_model(snap_handle* h, const float* coord_in) {
         return SNAP_EINVAL;
     }
     SNAP_HIP(hipMemcpyAsync(h->x, coord_in, (size_t)h->m * sizeof(float), hipMemcpyHostToDevice, h->compute));
+    if (h->form == SNAP_DUAL && h->loss == SNAP_LOGISTIC)       // the entropy term lives on (0,1)
+        SNAP_TRY(clamp_range(h->x, (float)ALPHA_EPS, (float)(1.0 - ALPHA_EPS), h->m, h->compute));
     SNAP_TRY(recompute_shared(h));
     SNAP_HIP(hipStreamSynchronize(h->compute));
     h->monitor_valid = false;

@@ -35,7 +35,9 @@ constexpr int64_t SMALL_MAX_DEFAULT = 4096;
 constexpr uint32_t LABEL_BIT = 0x80000000u;   // primal logistic: sign of y folded into the row index
 constexpr uint32_t SPIN_LIMIT = 1u << 22;     // bounded wait of a scatter item for its coordinate's step
 
-enum Kind { K_PRIMAL_RIDGE = 0, K_PRIMAL_LOGISTIC = 1, K_DUAL_HINGE = 2 };
+// K_DUAL: examples as coordinates (hinge or logistic loss: the kernels differ only in the scalar step)
+enum Kind { K_PRIMAL_RIDGE = 0, K_PRIMAL_LOGISTIC = 1, K_DUAL = 2 };
+constexpr double ALPHA_EPS = 1.0 / 1048576.0;   // logistic dual: the iterates stay in [2^-20, 1 - 2^-20]
 
 // Per-epoch state of one split ("large") coordinate, indexed by its position in the epoch order.
 struct LargeState {
@@ -219,6 +221,8 @@ int count_accesses_chunk(snap_handle* h, const ChunkView& cv, int64_t count, uin
 int access_moments(snap_handle* h, const uint32_t* freq, double* eff_len);
 int fold_labels(snap_handle* h, uint32_t* idx, int64_t count, hipStream_t s);
 int recompute_shared(snap_handle* h);
+int fill_value(float* p, float value, int64_t count, hipStream_t s);
+int clamp_range(float* p, float lo, float hi, int64_t count, hipStream_t s);
 int objective(snap_handle* h, double* primal, double* dual, double* gap);
 // the quantity the solver decreases (P in primal form, -D in dual form), vectors only
 int monitor_value(snap_handle* h, double* value);

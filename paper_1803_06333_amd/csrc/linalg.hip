@@ -32,6 +32,32 @@ __global__ void k_fill_zero(uint32_t* p, size_t words) {
         p[i] = 0u;
 }
 
+__global__ void k_fill_value(float* p, float value, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = value;
+}
+
+int fill_value(float* p, float value, int64_t count, hipStream_t s) {
+    if (count <= 0) return SNAP_OK;
+    const int grid = (int)((count + 255) / 256 < 4096 ? (count + 255) / 256 : 4096);
+    hipLaunchKernelGGL(k_fill_value, dim3(grid), dim3(256), 0, s, p, value, count);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+__global__ void k_clamp(float* p, float lo, float hi, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = fminf(fmaxf(p[i], lo), hi);
+}
+
+int clamp_range(float* p, float lo, float hi, int64_t count, hipStream_t s) {
+    if (count <= 0) return SNAP_OK;
+    const int grid = (int)((count + 255) / 256 < 4096 ? (count + 255) / 256 : 4096);
+    hipLaunchKernelGGL(k_clamp, dim3(grid), dim3(256), 0, s, p, lo, hi, count);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
 int fill_zero(void* p, size_t bytes, hipStream_t s) {
     if (bytes == 0) return SNAP_OK;
     const size_t words = bytes / 4;   // all buffers here are multiples of 4 bytes
@@ -191,7 +217,7 @@ __device__ __forceinline__ double dot_range(const uint32_t* __restrict__ idx, co
             }
         } else {
             r = (uint32_t)(dense_e0 + (k - s0));
-            if (KIND != K_DUAL_HINGE) yy = y[r];
+            if (KIND != K_DUAL) yy = y[r];
         }
         acc += dot_term<KIND>(val[k], v[r], yy);
     }
@@ -277,7 +303,7 @@ static int coord_dots(snap_handle* h) {
     switch (h->kind) {
     case K_PRIMAL_RIDGE: return for_each_chunk(h, coord_dots_chunk<K_PRIMAL_RIDGE>, nullptr, true, false);
     case K_PRIMAL_LOGISTIC: return for_each_chunk(h, coord_dots_chunk<K_PRIMAL_LOGISTIC>, nullptr, true, false);
-    default: return for_each_chunk(h, coord_dots_chunk<K_DUAL_HINGE>, nullptr, true, false);
+    default: return for_each_chunk(h, coord_dots_chunk<K_DUAL>, nullptr, true, false);
     }
 }
 
@@ -293,7 +319,9 @@ enum ReduceMode {
     R_ABSSUM = 7,        // a = x             : |x|
     R_CONJ_RIDGE = 8,    // a = v, b = y      : n f*(u) at u = (v-y)/n        = (v-y) y + (v-y)^2/2
     R_CONJ_LOGISTIC = 9, // a = v, b = y      : n f*(u) at u = -y p/n         = p ln p + (1-p) ln(1-p), p = sigmoid(-y v)
-    R_CONJ_REG = 10      // d = gdot          : max(|gdot s0| - s1, 0)^2      (2 lambda g*(a_j.u))
+    R_CONJ_REG = 10,     // d = gdot          : max(|gdot s0| - s1, 0)^2      (2 lambda g*(a_j.u))
+    R_LOGISTIC_MARGIN = 11, // d = gdot, b = y   : log(1 + exp(-y gdot s0))      (dual form: margins from the row dots)
+    R_ENTROPY = 12       // a = alpha         : a ln a + (1-a) ln(1-a)        (0 ln 0 := 0)
 };
 
 struct ReduceArgs {
@@ -332,6 +360,14 @@ __device__ __forceinline__ double reduce_term(const ReduceArgs& r, int64_t i) {
         const double lq = t > 0 ? log1p(exp(-t)) : -t + log1p(exp(t));
         const double p = exp(-lp);
         return -(p * lp + (1.0 - p) * lq);
+    }
+    if (MODE == R_LOGISTIC_MARGIN) {
+        const double t = -(double)r.b[i] * r.d[i] * r.s0;
+        return t > 0 ? t + log1p(exp(-t)) : log1p(exp(t));
+    }
+    if (MODE == R_ENTROPY) {
+        const double a = (double)r.a[i], b = 1.0 - a;
+        return (a > 0.0 ? a * log(a) : 0.0) + (b > 0.0 ? b * log(b) : 0.0);
     }
     if (MODE == R_CONJ_REG) {
         const double t = fabs(r.d[i] * r.s0) - r.s1;
@@ -385,6 +421,10 @@ static int reduce_to(snap_handle* h, int mode, const ReduceArgs& r, int slot) {
         hipLaunchKernelGGL((k_reduce_partial<R_CONJ_LOGISTIC>), g, b, 0, h->compute, r, partial);
         break;
     case R_CONJ_REG: hipLaunchKernelGGL((k_reduce_partial<R_CONJ_REG>), g, b, 0, h->compute, r, partial); break;
+    case R_LOGISTIC_MARGIN:
+        hipLaunchKernelGGL((k_reduce_partial<R_LOGISTIC_MARGIN>), g, b, 0, h->compute, r, partial);
+        break;
+    case R_ENTROPY: hipLaunchKernelGGL((k_reduce_partial<R_ENTROPY>), g, b, 0, h->compute, r, partial); break;
     default: hipLaunchKernelGGL((k_reduce_partial<R_HINGE>), g, b, 0, h->compute, r, partial); break;
     }
     hipLaunchKernelGGL(k_reduce_final, dim3(1), b, 0, h->compute, partial, REDUCE_BLOCKS, out);
@@ -445,19 +485,21 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
         if (dual) *dual = P - G;
         return SNAP_OK;
     }
-    // hinge, dual form: w = v/(lambda n); margins y_i x_i.w from the row dots with v
+    // dual form: w = v/(lambda n); margins y_i x_i.w from the row dots with v;
+    // D = (1/n) sum alpha - (lambda/2)||w||^2 (hinge), -(1/n) sum entropy terms - (lambda/2)||w||^2 (logistic)
+    const bool logistic = h->loss == SNAP_LOGISTIC;
     SNAP_TRY(coord_dots(h));
     ReduceArgs rh{nullptr, h->y, h->gdot, 1.0 / (lam * n), 0.0, h->m};
-    SNAP_TRY(reduce_to(h, R_HINGE, rh, 0));
+    SNAP_TRY(reduce_to(h, logistic ? R_LOGISTIC_MARGIN : R_HINGE, rh, 0));
     ReduceArgs ra{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
-    SNAP_TRY(reduce_to(h, R_SUM, ra, 1));
+    SNAP_TRY(reduce_to(h, logistic ? R_ENTROPY : R_SUM, ra, 1));
     ReduceArgs rv{h->v, nullptr, nullptr, 0.0, 0.0, h->vlen};
     SNAP_TRY(reduce_to(h, R_SQNORM, rv, 2));
     SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));
     const double ww = res[2] / (lam * n * lam * n);
     const double P = res[0] / n + 0.5 * lam * ww;
-    const double D = res[1] / n - 0.5 * lam * ww;
+    const double D = (logistic ? -res[1] : res[1]) / n - 0.5 * lam * ww;
     if (primal) *primal = P;
     if (dual) *dual = D;
     if (gap) *gap = P - D;
@@ -475,14 +517,14 @@ int monitor_value(snap_handle* h, double* value) {
         if (h->lambda1 > 0.0) SNAP_TRY(reduce_to(h, R_ABSSUM, rx, 2));
     } else {
         ReduceArgs ra{h->x, nullptr, nullptr, 0.0, 0.0, h->m};
-        SNAP_TRY(reduce_to(h, R_SUM, ra, 0));
+        SNAP_TRY(reduce_to(h, h->loss == SNAP_LOGISTIC ? R_ENTROPY : R_SUM, ra, 0));
         ReduceArgs rv{h->v, nullptr, nullptr, 0.0, 0.0, h->vlen};
         SNAP_TRY(reduce_to(h, R_SQNORM, rv, 1));
     }
     SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));
     if (h->form == SNAP_PRIMAL) *value = res[0] / n + 0.5 * lam * res[1] + (h->lambda1 > 0.0 ? h->lambda1 * res[2] : 0.0);
-    else *value = -(res[0] / n - 0.5 * res[1] / (lam * n * n));     // -D(alpha)
+    else *value = -((h->loss == SNAP_LOGISTIC ? -res[0] : res[0]) / n - 0.5 * res[1] / (lam * n * n));   // -D(alpha)
     return SNAP_OK;
 }
 

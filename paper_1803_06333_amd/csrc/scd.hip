@@ -53,7 +53,7 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
         float mult = 0.0f;
         if (lane == 0) {
             const float xc = x[c];
-            const float yc = KIND == K_DUAL_HINGE ? y[c] : 0.0f;
+            const float yc = KIND == K_DUAL ? y[c] : 0.0f;
             x[c] = take_step<KIND>((double)g, (double)h, xc, norms[c], yc, sp, mult);
         }
         mult = __shfl(mult, 0, WAVE);
@@ -178,7 +178,7 @@ k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_la
                     a[u] = stream_load(valp + eu);
                     if (DENSE) {
                         r[u] = (uint32_t)eu;
-                        yy[u] = KIND == K_DUAL_HINGE ? 0.0f : y[r[u]];
+                        yy[u] = KIND == K_DUAL ? 0.0f : y[r[u]];
                     } else {
                         decode<KIND>(stream_load(idxp + eu), r[u], yy[u], y);
                     }
@@ -193,7 +193,7 @@ k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_la
                 float yy;
                 if (DENSE) {
                     r = (uint32_t)e;
-                    yy = KIND == K_DUAL_HINGE ? 0.0f : y[r];
+                    yy = KIND == K_DUAL ? 0.0f : y[r];
                 } else {
                     decode<KIND>(idxp[e], r, yy, y);
                 }
@@ -222,7 +222,7 @@ k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_la
                     const double Gt = atomicAdd(&st[k].g, 0.0);
                     const double Ht = atomicAdd(&st[k].h, 0.0);
                     const float xc = x[c];
-                    const float yc = KIND == K_DUAL_HINGE ? y[c] : 0.0f;
+                    const float yc = KIND == K_DUAL ? y[c] : 0.0f;
                     float mult;
                     x[c] = take_step<KIND>(Gt, Ht, xc, norms[c], yc, sp, mult);
                     const uint64_t word = (1ull << 32) | (uint64_t)__float_as_uint(mult);
@@ -314,7 +314,7 @@ int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk&
     switch (h->kind) {
     case K_PRIMAL_RIDGE: return launch_kind<K_PRIMAL_RIDGE>(h, cv, ck, order, sp);
     case K_PRIMAL_LOGISTIC: return launch_kind<K_PRIMAL_LOGISTIC>(h, cv, ck, order, sp);
-    case K_DUAL_HINGE: return launch_kind<K_DUAL_HINGE>(h, cv, ck, order, sp);
+    case K_DUAL: return launch_kind<K_DUAL>(h, cv, ck, order, sp);
     }
     set_error("unknown solver kind");
     return SNAP_EINVAL;

@@ -8,6 +8,7 @@ namespace snap {
 struct StepParams {
     double lambda;
     double lambda1;   // weight of the l1 term (primal forms)
+    int dual_logistic; // dual form: 1 = logistic loss (Newton step on the entropy), 0 = hinge
     double inv_n;     // 1/n
     double lam_n;     // lambda * n
     double damping;   // in (0,1]: the step is scaled by it (Section 3.1, adaptive damping)
@@ -89,7 +90,13 @@ __device__ __forceinline__ float take_step(double g, double h, float xc, float n
         xn = primal_step(g * sp.inv_n, Hf, 1.0 / (Hf + sp.lambda), xc, sp, mult);
     } else {
         double anew;
-        if (norm == 0.0f) {
+        if (sp.dual_logistic) {
+            // -n dD/da = ln(a/(1-a)) + m,  -n d2D/da2 = 1/(a(1-a)) + q: one Newton step, kept inside (0,1)
+            const double a = (double)xc;
+            const double m = (double)yc * g / sp.lam_n, q = (double)norm / sp.lam_n;
+            anew = a - (log(a) - log1p(-a) + m) / (1.0 / (a * (1.0 - a)) + q);
+            anew = anew < ALPHA_EPS ? ALPHA_EPS : (anew > 1.0 - ALPHA_EPS ? 1.0 - ALPHA_EPS : anew);
+        } else if (norm == 0.0f) {
             anew = 1.0;                                   // empty row: dD/dalpha = 1/n > 0
         } else {
             const double m = (double)yc * g / sp.lam_n;   // y_i x_i.w
@@ -123,6 +130,7 @@ inline StepParams make_step_params(const snap_handle* h) {
     StepParams sp;
     sp.lambda = h->lambda;
     sp.lambda1 = h->lambda1;
+    sp.dual_logistic = (h->form == SNAP_DUAL && h->loss == SNAP_LOGISTIC) ? 1 : 0;
     sp.inv_n = 1.0 / (double)h->n;
     sp.lam_n = h->lambda * (double)h->n;
     sp.damping = (double)h->damping;
