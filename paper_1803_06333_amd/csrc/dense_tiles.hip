@@ -161,7 +161,7 @@ k_tile_pass(const float* __restrict__ A, int64_t ld, int64_t n, int64_t prev_c0,
                 for (int k = 0; k < PASS_VEC; ++k) s += a[k] * r[q][k];
             }
         }
-        s = wave_sum_dpp(s);
+        s = wave_sum(s);
         if (lane == 0) partial[(size_t)blockIdx.x * TILE_B + j] = s;
     }
 }

@@ -309,8 +309,9 @@ __device__ __forceinline__ unsigned long long to_fixed(float x, float scale) {
     return (unsigned long long)__float2ll_rn(x * scale);
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void load_ranks(const uint16_t* p, uint32_t (&out)[8]) {
-    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    const u32x4 u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     out[0] = u.x & 0xFFFFu; out[1] = u.x >> 16; out[2] = u.y & 0xFFFFu; out[3] = u.y >> 16;
     out[4] = u.z & 0xFFFFu; out[5] = u.z >> 16; out[6] = u.w & 0xFFFFu; out[7] = u.w >> 16;
 }

@@ -14,16 +14,11 @@ struct StepParams {
     double damping;   // in (0,1]: the step is scaled by it (Section 3.1, adaptive damping)
 };
 
+// Sum over the wavefront through the data-parallel-primitive lane moves of the vector ALU (no LDS
+// traffic, unlike shuffles): all-reduce inside each row of 16 lanes (swap neighbours, swap pairs,
+// rotate by 4, rotate by 8), then the four row sums are read as scalars.  The result is uniform over
+// the wavefront; lanes that are switched off contribute 0.
 __device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int off = WAVE / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, WAVE);
-    return x;
-}
-
-// The same sum through the data-parallel-primitive lane moves of the vector ALU (no LDS traffic):
-// all-reduce inside each row of 16 lanes (swap neighbours, swap pairs, rotate by 4, rotate by 8),
-// then the four row sums are read as scalars.  The result is uniform over the wavefront.
-__device__ __forceinline__ float wave_sum_dpp(float x) {
     constexpr int QUAD_SWAP_1 = 0xB1;    // quad_perm [1,0,3,2]
     constexpr int QUAD_SWAP_2 = 0x4E;    // quad_perm [2,3,0,1]
     constexpr int ROW_ROR_4 = 0x124, ROW_ROR_8 = 0x128;
