@@ -121,6 +121,8 @@ def main():
         gen_s += time.time() - t1
     if mode == "groups":
         kw["group_bounds"] = p.meta["field_starts"] + [p.d]
+    elif not dense and p.layout == "csc":
+        kw["auto_groups"] = False                 # async: the structure-free epoch, no search for groups
     if dense:
         kw["dense_tiles"] = mode == "tiles"
     t0 = time.time()
@@ -228,7 +230,8 @@ def main():
 
     # ---- the structure-free asynchronous path on the same data (config 4, auto) --------------------
     if args.mode == "auto" and args.config == 4:
-        ga = snap.Solver.from_problem(p, profile=True, max_inflight_nnz=args.inflight, damping=args.damping)
+        ga = snap.Solver.from_problem(p, profile=True, max_inflight_nnz=args.inflight, damping=args.damping,
+                                      auto_groups=False)
         steps_a = max(3, min(args.steps, 8))
         el, kma, sta, rej = timed_epochs(ga, torch, steps_a, 1, 9000)
         big = kma["large_ms"] >= kma["small_ms"]

@@ -118,6 +118,14 @@ typedef struct {
                                     0: automatic (used whenever it applies), 1: required (error when it does
                                     not apply), 2: off (asynchronous epoch with atomic updates of v).
                                     snap_get_chunks reports the tiles. */
+    int auto_groups;             /* without group_bounds (primal form, sparse, resident): look for a partition of
+                                    the coordinates into few ranges of consecutive coordinates with pairwise
+                                    disjoint supports (the fields of one-hot encoded data) and, when one is
+                                    found, use the group sweeps described at group_bounds.  The search costs
+                                    about two passes over the nonzeros and gives up as soon as the ranges
+                                    turn out short (more than 8 + 10 nnz_covered / n_rows of them).
+                                    0: automatic, 1: required (error when nothing is found), 2: off.
+                                    snap_get_chunks reports what was found. */
 } snap_options;
 
 /* Per-epoch figures gathered when options.profile = 1 (milliseconds of device time).  With group

@@ -293,6 +293,16 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     if (!h->streaming && h->kind == K_PRIMAL_LOGISTIC && !h->dense) SNAP_TRY(fold_labels(h, h->idx, h->nnz, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));   // host vectors above go out of scope
 
+    // ---- groups of coordinates with disjoint supports: given by the caller, or looked for ------------
+    std::vector<int64_t> gbounds;
+    if (h->opt.n_groups > 0) gbounds.assign(h->opt.group_bounds, h->opt.group_bounds + h->opt.n_groups + 1);
+    else if (h->opt.auto_groups != 2) SNAP_TRY(detect_groups(h, hptr.data(), gbounds));
+    if (h->opt.auto_groups == 1 && gbounds.empty()) {
+        set_error("no partition of the coordinates into few ranges with disjoint supports was found");
+        return SNAP_EUNSUPPORTED;
+    }
+    if (!gbounds.empty() && h->opt.adaptive == 0) h->adaptive = false;   // group sweeps are exact: nothing to guard
+
     // ---- concurrency control ---------------------------------------------------------------------
     if (h->opt.max_inflight_nnz > 0) h->inflight_nnz = h->opt.max_inflight_nnz;
     else if (h->dense) h->inflight_nnz = 0;       // no cap; the adaptive check lowers it if needed
@@ -306,7 +316,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
         SNAP_HIP(hipMalloc(&h->x_snap, (size_t)(m ? m : 1) * sizeof(float)));
         SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
     }
-    if (h->opt.n_groups > 0) SNAP_TRY(grouped_setup(h, hptr.data()));
+    if (!gbounds.empty()) SNAP_TRY(grouped_setup(h, hptr.data(), gbounds.data(), (int64_t)gbounds.size() - 1));
     if (use_tiles) SNAP_TRY(dense_tiles_setup(h));
     if (h->form == SNAP_DUAL && h->loss == SNAP_LOGISTIC && m > 0) {
         // the entropy term of the logistic dual needs alpha inside (0,1): start at 1/2, v = A alpha
@@ -362,6 +372,10 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
     if (opt) o = *opt;
     if (o.n_groups < 0 || (o.n_groups > 0 && !o.group_bounds)) {
         set_error("n_groups must be non-negative and come with group_bounds");
+        return SNAP_EINVAL;
+    }
+    if (o.auto_groups < 0 || o.auto_groups > 2) {
+        set_error("auto_groups must be 0, 1 or 2");
         return SNAP_EINVAL;
     }
     if (o.dense_tiles < 0 || o.dense_tiles > 2) {

@@ -201,7 +201,8 @@ int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk&
 using ChunkFn = int (*)(snap_handle* h, int64_t chunk, const ChunkView& cv, void* arg);
 int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profile);
 // grouped.hip
-int grouped_setup(snap_handle* h, const int64_t* hptr);
+int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* bounds, int64_t n_groups);
+int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bounds);   // empty: nothing found
 int grouped_epoch(snap_handle* h);
 std::vector<int64_t> group_order(uint64_t seed, int64_t n_groups);   // visiting order of the groups for a seed
 void grouped_free(snap_handle* h);

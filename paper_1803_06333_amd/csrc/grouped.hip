@@ -153,9 +153,117 @@ void grouped_free(snap_handle* h) {
     h->gpartial = nullptr;
 }
 
-int grouped_setup(snap_handle* h, const int64_t* hptr) {
-    const int64_t m = h->m, G = h->opt.n_groups, n = h->n;
-    const int64_t* gb = h->opt.group_bounds;
+// ---- finding the groups ---------------------------------------------------------------------------------
+// Greedy cut of the coordinates into the fewest ranges of consecutive coordinates whose members share
+// no row (for one-hot encoded data: the fields).  A range is grown by galloping: a candidate block of
+// further coordinates is accepted when marking its rows with a fresh tag meets no row already
+// marked by the range or by the block itself; after the first refusal the block size is halved
+// until the exact end of the range is known.  Tags of refused blocks stay behind and are ignored
+// (ok[] says which tags of the current range were accepted), so nothing is ever cleared and every
+// nonzero is visited about twice.
+__global__ void k_mark_rows(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, int64_t c0, int64_t c1,
+                            uint32_t tag, uint32_t tag_lo, const uint8_t* __restrict__ ok, uint32_t* __restrict__ tags,
+                            uint32_t* __restrict__ conflict) {
+    const int64_t k0 = ptr[c0], k1 = ptr[c1];
+    bool bad = false;
+    for (int64_t k = k0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < k1; k += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t r = idx[k] & ~LABEL_BIT;
+        const uint32_t seen = tags[r];
+        if (seen >= tag_lo && seen < tag && ok[seen - tag_lo]) {
+            bad = true;                                   // the row belongs to the range already
+        } else if (atomicExch(tags + r, tag) == tag) {
+            bad = true;                                   // two coordinates of the block share the row
+        }
+    }
+    if (bad) atomicOr(conflict, 1u);
+}
+
+// bounds: empty when the data have no such structure worth using (see the give-up rule below).
+int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bounds) {
+    bounds.clear();
+    const int64_t m = h->m, n = h->n;
+    if (h->form != SNAP_PRIMAL || h->dense || h->streaming || m < 2 || n < 1 || h->nnz < 1) return SNAP_OK;
+    constexpr int MAX_TESTS = 128;                        // per range: 2 log2(range length) is needed
+    uint32_t* tags = nullptr;
+    uint32_t* conflict = nullptr;
+    uint8_t* ok = nullptr;
+    uint32_t* host_flag = nullptr;
+    SNAP_HIP(hipMalloc(&tags, (size_t)n * sizeof(uint32_t)));
+    auto done = [&](int rc) {
+        (void)hipFree(tags);
+        (void)hipFree(conflict);
+        (void)hipFree(ok);
+        (void)hipHostFree(host_flag);
+        return rc;
+    };
+#define D_HIP(call)                                                                \
+    do {                                                                           \
+        hipError_t e_ = (call);                                                    \
+        if (e_ != hipSuccess) return done(hip_fail(e_, #call, __FILE__, __LINE__)); \
+    } while (0)
+    D_HIP(hipMalloc(&conflict, sizeof(uint32_t)));
+    D_HIP(hipMalloc(&ok, MAX_TESTS));
+    D_HIP(hipHostMalloc(&host_flag, sizeof(uint32_t)));
+    int rc = fill_zero(tags, (size_t)n * sizeof(uint32_t), h->compute);
+    if (rc != SNAP_OK) return done(rc);
+    uint8_t ok_host[MAX_TESTS];
+    uint32_t tag = 1;                                     // 0: never marked
+    std::vector<int64_t> gb{0};
+    int64_t start = 0;
+    while (start < m) {
+        // one range [start, end)
+        const uint32_t tag_lo = tag;
+        int tests = 0;
+        memset(ok_host, 0, sizeof(ok_host));
+        D_HIP(hipMemsetAsync(ok, 0, MAX_TESTS, h->compute));
+        int64_t end = start, step = 1;
+        bool refused = false;
+        while (end < m && step > 0 && tests < MAX_TESTS) {
+            const int64_t to = std::min(m, end + step);
+            bool good = true;
+            if (hptr[to] > hptr[end]) {
+                const int64_t cnt = hptr[to] - hptr[end];
+                const int grid = (int)std::min<int64_t>((cnt + 255) / 256, 16384);
+                D_HIP(hipMemsetAsync(conflict, 0, sizeof(uint32_t), h->compute));
+                hipLaunchKernelGGL(k_mark_rows, dim3(grid), dim3(256), 0, h->compute, h->ptr, h->idx, end, to, tag, tag_lo,
+                                   ok, tags, conflict);
+                D_HIP(hipMemcpyAsync(host_flag, conflict, sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+                D_HIP(hipStreamSynchronize(h->compute));
+                good = *host_flag == 0;
+                if (good) {
+                    ok_host[tag - tag_lo] = 1;
+                    D_HIP(hipMemcpyAsync(ok + (tag - tag_lo), ok_host + (tag - tag_lo), 1, hipMemcpyHostToDevice, h->compute));
+                }
+                ++tag;
+                ++tests;
+            }
+            if (good) {
+                end = to;
+                step = refused ? step / 2 : step * 2;
+            } else {
+                refused = true;
+                step /= 2;
+            }
+        }
+        if (end == start) return done(SNAP_OK);           // a coordinate with a repeated row: no structure to use
+        gb.push_back(end);
+        start = end;
+        // give up early on data without such structure: a range pays one pass over all rows, which is
+        // only worth it when the range holds a good fraction of a nonzero per row
+        const double covered = (double)hptr[end] / (double)n;
+        if ((double)(gb.size() - 1) > 8.0 + 10.0 * covered) return done(SNAP_OK);
+    }
+    size_t free_b = 0, total_b = 0;
+    D_HIP(hipMemGetInfo(&free_b, &total_b));
+    const size_t n_pad = (size_t)((n + 7) / 8 * 8);
+    if ((gb.size() - 1) * n_pad * 6 > free_b / 2) return done(SNAP_OK);      // the row maps would not fit comfortably
+#undef D_HIP
+    bounds = gb;
+    return done(SNAP_OK);
+}
+
+int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_t G) {
+    const int64_t m = h->m, n = h->n;
     if (h->form != SNAP_PRIMAL || h->dense || h->streaming) {
         set_error("group sweeps need the primal form on resident sparse data");
         return SNAP_EUNSUPPORTED;

@@ -25,6 +25,8 @@ def relnorm(a, b):
 
 
 def gpu_solver(p, **kw):
+    # the tests choose the epoch engine themselves: no search for groups unless a test asks for it
+    kw.setdefault("auto_groups", False)
     return snap.Solver.from_problem(p.to(DEV), **kw)
 
 
@@ -712,3 +714,73 @@ def test_dual_logistic_streamed_row_chunks():
     chk.x[:] = g.model()[1]
     assert relnorm(g.shared(), chk.shared_from_model()) <= 1e-4
     g.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# automatic search for ranges of coordinates with disjoint supports
+@pytest.mark.parametrize("loss,unit", [("logistic", True), ("ridge", False)])
+def test_auto_groups_finds_the_fields_of_one_hot_data(loss, unit):
+    p = _onehot_variant(loss, unit)
+    fields = p.meta["field_starts"] + [p.d]
+    g = gpu_solver(p, auto_groups=None)                  # default: look for groups
+    assert g.chunk_bounds() == fields
+    A = oracle.Matrix.from_problem(p)
+    o = oracle.Solver(A, p.y.numpy(), p.loss, p.lam, chunk_bounds=fields, shuffle_chunks=True)
+    for e in range(4):
+        g.epoch(e)
+        o.epoch(e)
+        assert relnorm(g.model()[1], o.x) <= 2e-5
+        assert g.epoch_stats()["rejected"] == 0
+    g.close()
+    # required and found: the same
+    g = gpu_solver(p, auto_groups=True)
+    assert g.chunk_bounds() == fields
+    g.close()
+
+
+def test_auto_groups_merges_what_can_be_merged_and_handles_empty_columns():
+    # three "fields" over disjoint row sets can share one range; empty columns belong anywhere
+    n, d = 3000, 40
+    rng = np.random.default_rng(9)
+    cols = np.empty(n, dtype=np.int64)
+    cols[:1000] = rng.integers(0, 10, 1000)              # rows 0..999 use columns 0..9
+    cols[1000:2000] = rng.integers(12, 20, 1000)         # columns 10, 11 stay empty
+    cols[2000:] = rng.integers(20, 30, 1000)
+    second = rng.integers(30, 40, n)                     # every row also has a column in 30..39
+    ptr = np.zeros(d + 1, dtype=np.int64)
+    rows = []
+    for c in range(d):
+        r = np.nonzero((cols == c) | (second == c))[0]
+        rows.append(r)
+        ptr[c + 1] = ptr[c] + r.size
+    idx = np.concatenate(rows).astype(np.int32)
+    val = np.ones(idx.size, dtype=np.float32)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    g = snap.Solver("csc", n, d, ptr, idx, val, y, "logistic", 1e-3, auto_groups=True)
+    assert g.chunk_bounds() == [0, 30, 40]
+    A = oracle.Matrix("csc", n, d, ptr, idx, val)
+    o = oracle.Solver(A, y, "logistic", 1e-3, chunk_bounds=[0, 30, 40], shuffle_chunks=True)
+    for e in range(5):
+        g.epoch(e)
+        o.epoch(e)
+    assert relnorm(g.model()[1], o.x) <= 2e-5
+    g.close()
+
+
+def test_auto_groups_gives_up_on_unstructured_data():
+    p = problem("cfg1_sparse_logistic")
+    g = gpu_solver(p, auto_groups=None)
+    assert g.chunk_bounds() == [0, p.d]                  # asynchronous epoch
+    g.epoch(0)
+    assert np.array_equal(g.perm(), oracle.permutation(0, p.d))
+    g.close()
+    with pytest.raises(snap.SnapError) as e:
+        gpu_solver(p, auto_groups=True)
+    assert e.value.code == -2
+    # a column that repeats a row cannot be in any group
+    ptr = np.array([0, 2, 3], dtype=np.int64)
+    idx = np.array([1, 1, 0], dtype=np.int32)
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", 3, 2, ptr, idx, np.ones(3, dtype=np.float32), np.ones(3, dtype=np.float32), "ridge", 0.1,
+                    auto_groups=True)
+    assert e.value.code == -2
