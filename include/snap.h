@@ -160,8 +160,9 @@ int snap_create(const snap_matrix *A, const float *y, int loss, double lambda,
  * permutation that perm_seed defines: a 32-bit xorshift key per coordinate, coordinates sorted by
  * (key, index).  Streaming: chunks of consecutive coordinates are visited in order, permuted
  * inside each chunk, the next chunk being copied while the current one is processed.
- * Stream-ordered; with options.adaptive off it returns after enqueueing, with it on it also
- * waits for the epoch and applies the accept / discard decision. */
+ * Stream-ordered; with options.adaptive off it returns after enqueueing (streamed data: once the
+ * last chunk copy of the pass has ended), with it on it also waits for the epoch and applies the
+ * accept / discard decision. */
 int snap_epoch(snap_handle *h, uint64_t perm_seed);
 
 /* P(w) above and, in the dual form, D(alpha) = (1/n) sum alpha_i - (lambda/2)||w||^2 (hinge; the
@@ -204,6 +205,11 @@ int snap_get_epoch_stats(snap_handle *h, snap_epoch_stats *out);
  * With group_bounds in force the groups are reported (they play the role of the chunks: permutation
  * inside each with the group index entering the key; the groups themselves in seeded random order). */
 int snap_get_chunks(snap_handle *h, int64_t *n_chunks, int64_t *bounds_out);
+
+/* Bytes that one pass over the data copies from host memory (0 when the matrix is resident).  When
+ * every stored value is 1.0 (found at creation) only the indices are streamed: 4 bytes per nonzero
+ * instead of 8. */
+int snap_get_stream_bytes(snap_handle *h, int64_t *bytes_per_pass);
 
 /* Number of coordinates m and length of v. */
 int snap_get_dims(snap_handle *h, int64_t *n_coords, int64_t *shared_len);

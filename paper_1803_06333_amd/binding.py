@@ -25,7 +25,7 @@ LOSSES = {"ridge": RIDGE, "logistic": LOGISTIC, "hinge": HINGE}
 
 EXPORTS = ["snap_create", "snap_epoch", "snap_objective", "snap_duality_gap", "snap_predict", "snap_get_model",
            "snap_set_model", "snap_get_shared", "snap_recompute_shared", "snap_get_perm", "snap_get_epoch_stats",
-           "snap_get_dims", "snap_get_chunks", "snap_last_error", "snap_destroy"]
+           "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_last_error", "snap_destroy"]
 
 
 class SnapMatrix(C.Structure):
@@ -227,6 +227,12 @@ class Solver:
         b = np.empty(n.value + 1, dtype=np.int64)
         _check(self._lib.snap_get_chunks(self._h, C.byref(n), b.ctypes.data))
         return b.tolist()
+
+    def stream_bytes(self) -> int:
+        """Bytes copied from host memory by one pass over the data (0: resident)."""
+        b = C.c_int64()
+        _check(self._lib.snap_get_stream_bytes(self._h, C.byref(b)))
+        return b.value
 
     def epoch_stats(self) -> dict:
         s = SnapEpochStats()

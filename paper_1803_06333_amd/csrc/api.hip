@@ -36,10 +36,25 @@ __global__ void k_check_labels(const float* __restrict__ y, int64_t n, uint32_t*
         if (!(y[i] == 1.0f || y[i] == -1.0f)) atomicOr(flag, 2u);
 }
 
+// streaming: are all stored values 1.0 (pattern-only data, e.g. one-hot encodings)?  flag bit 2 says no
+__global__ void k_check_unit_values(const float* __restrict__ val, int64_t count, uint32_t* flag) {
+    bool other = false;
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < count; k += (int64_t)gridDim.x * blockDim.x)
+        other |= val[k] != 1.0f;
+    if (other) atomicOr(flag, 4u);
+}
+
+// the status word reaches the host through mapped pinned memory (a copy command could wait behind
+// the chunk copies of a streamed pass)
+__global__ void k_publish_status(const uint32_t* __restrict__ status, double* __restrict__ host_mapped) {
+    if (threadIdx.x == 0) reinterpret_cast<uint32_t*>(host_mapped)[0] = *status;
+}
+
 static int check_status(snap_handle* h) {
-    uint32_t st = 0;
-    SNAP_HIP(hipMemcpyAsync(&st, h->status, sizeof(st), hipMemcpyDeviceToHost, h->compute));
+    hipLaunchKernelGGL(k_publish_status, dim3(1), dim3(WAVE), 0, h->compute, h->status, h->red.host_mapped + 7);
+    SNAP_HIP(hipGetLastError());
     SNAP_HIP(hipStreamSynchronize(h->compute));
+    const uint32_t st = reinterpret_cast<const uint32_t*>(h->red.host + 7)[0];
     if (st & 1u) {
         set_error("a scatter work item gave up waiting for its coordinate's step; the state is invalid");
         return SNAP_ESTATE;
@@ -101,6 +116,8 @@ static int create_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void
     if (!h->dense && count > 0)
         hipLaunchKernelGGL(k_check_indices, dim3(4096), dim3(256), 0, h->compute, (const int32_t*)cv.idx, count,
                            cp->minor, h->status);
+    if (h->streaming && count > 0)
+        hipLaunchKernelGGL(k_check_unit_values, dim3(4096), dim3(256), 0, h->compute, cv.val, count, h->status);
     SNAP_HIP(hipGetLastError());
     if (!h->dense && cp->freq) SNAP_TRY(count_accesses_chunk(h, cv, count, cp->freq));
     return norms_and_classes_chunk(h, cv);
@@ -289,6 +306,13 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     if (st & 2u) {
         set_error("labels must be +1 or -1 for this loss");
         return SNAP_EINVAL;
+    }
+    if (h->streaming && !(st & 4u) && h->nnz > 0) {
+        // every stored value is 1.0: the value array never has to cross the host link again.  Both
+        // value buffers are filled with ones once (after the prefetch that may still be writing one).
+        SNAP_HIP(hipStreamSynchronize(h->copy));
+        for (int b = 0; b < 2; ++b) SNAP_TRY(fill_value(h->buf_val[b], 1.0f, h->max_chunk_nnz, h->compute));
+        h->stream_unit = true;
     }
     if (!h->streaming && h->kind == K_PRIMAL_LOGISTIC && !h->dense) SNAP_TRY(fold_labels(h, h->idx, h->nnz, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));   // host vectors above go out of scope
@@ -708,6 +732,15 @@ int snap_get_chunks(snap_handle* h, int64_t* n_chunks, int64_t* bounds_out) {
         for (int64_t ch = 0; ch < h->n_chunks; ++ch) bounds_out[ch] = h->chunks[ch].c0;
         bounds_out[h->n_chunks] = h->m;
     }
+    return SNAP_OK;
+}
+
+int snap_get_stream_bytes(snap_handle* h, int64_t* bytes_per_pass) {
+    if (!h || !bytes_per_pass) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    *bytes_per_pass = h->streaming ? h->nnz * (int64_t)(h->stream_unit ? sizeof(uint32_t) : sizeof(uint32_t) + sizeof(float)) : 0;
     return SNAP_OK;
 }
 

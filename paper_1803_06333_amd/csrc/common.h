@@ -66,7 +66,8 @@ struct Sorter {              // scratch of the radix sort, sized for max_m coord
 struct Reducer {             // scratch for deterministic fp64 reductions
     double* partial = nullptr;   // [REDUCE_BLOCKS * 4]
     double* result = nullptr;    // [8] device
-    double* host = nullptr;      // [8] pinned host
+    double* host = nullptr;      // [8] pinned host, mapped into the device's address space
+    double* host_mapped = nullptr;   // the device's pointer to the same memory
 };
 constexpr int REDUCE_BLOCKS = 1024;
 
@@ -121,6 +122,7 @@ struct snap_handle {
     Chunk* chunks = nullptr;
     int64_t n_chunks = 0;
     bool streaming = false;
+    bool stream_unit = false;            // streaming: all values are 1.0, only the indices are copied
     const int64_t* host_ptr = nullptr;   // streaming: borrowed pinned arrays
     const int32_t* host_idx = nullptr;
     const float* host_val = nullptr;

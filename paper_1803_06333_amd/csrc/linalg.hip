@@ -432,10 +432,24 @@ static int reduce_to(snap_handle* h, int mode, const ReduceArgs& r, int slot) {
     return SNAP_OK;
 }
 
+// The eight result slots go to the host through mapped pinned memory, written by a kernel: a copy
+// command, however small, can queue behind gigabytes of chunk copies on the copy engines.
+__global__ void k_publish(const double* __restrict__ result, double* __restrict__ host_mapped, int count) {
+    if ((int)threadIdx.x < count) host_mapped[threadIdx.x] = result[threadIdx.x];
+}
+
+static int fetch_results(snap_handle* h, int count) {
+    hipLaunchKernelGGL(k_publish, dim3(1), dim3(WAVE), 0, h->compute, h->red.result, h->red.host_mapped, count);
+    SNAP_HIP(hipGetLastError());
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    return SNAP_OK;
+}
+
 int reducer_alloc(Reducer& r) {
     SNAP_HIP(hipMalloc(&r.partial, 2 * REDUCE_BLOCKS * sizeof(double)));
     SNAP_HIP(hipMalloc(&r.result, 8 * sizeof(double)));
-    SNAP_HIP(hipHostMalloc(&r.host, 8 * sizeof(double)));
+    SNAP_HIP(hipHostMalloc(&r.host, 8 * sizeof(double), hipHostMallocMapped));
+    SNAP_HIP(hipHostGetDevicePointer((void**)&r.host_mapped, r.host, 0));
     return SNAP_OK;
 }
 
@@ -475,8 +489,7 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
                 SNAP_TRY(reduce_to(h, R_GRADSQ, rg, 2));
             }
         }
-        SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
-        SNAP_HIP(hipStreamSynchronize(h->compute));
+        SNAP_TRY(fetch_results(h, 8));
         const double P = res[0] / n + 0.5 * lam * res[1] + (lam1 > 0.0 ? lam1 * res[3] : 0.0);
         double G = 0.0;
         if (need_gap) G = lam1 > 0.0 ? P + res[4] / n + res[2] / (2.0 * lam) : res[2] / (2.0 * lam);
@@ -495,8 +508,7 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
     SNAP_TRY(reduce_to(h, logistic ? R_ENTROPY : R_SUM, ra, 1));
     ReduceArgs rv{h->v, nullptr, nullptr, 0.0, 0.0, h->vlen};
     SNAP_TRY(reduce_to(h, R_SQNORM, rv, 2));
-    SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
-    SNAP_HIP(hipStreamSynchronize(h->compute));
+    SNAP_TRY(fetch_results(h, 8));
     const double ww = res[2] / (lam * n * lam * n);
     const double P = res[0] / n + 0.5 * lam * ww;
     const double D = (logistic ? -res[1] : res[1]) / n - 0.5 * lam * ww;
@@ -521,8 +533,7 @@ int monitor_value(snap_handle* h, double* value) {
         ReduceArgs rv{h->v, nullptr, nullptr, 0.0, 0.0, h->vlen};
         SNAP_TRY(reduce_to(h, R_SQNORM, rv, 1));
     }
-    SNAP_HIP(hipMemcpyAsync(res, h->red.result, 8 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
-    SNAP_HIP(hipStreamSynchronize(h->compute));
+    SNAP_TRY(fetch_results(h, 8));
     if (h->form == SNAP_PRIMAL) *value = res[0] / n + 0.5 * lam * res[1] + (h->lambda1 > 0.0 ? h->lambda1 * res[2] : 0.0);
     else *value = -((h->loss == SNAP_LOGISTIC ? -res[0] : res[0]) / n - 0.5 * res[1] / (lam * n * n));   // -D(alpha)
     return SNAP_OK;
@@ -567,8 +578,7 @@ int access_moments(snap_handle* h, const uint32_t* freq, double* eff_len) {
     hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial, REDUCE_BLOCKS, h->red.result);
     hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(LTPB), 0, h->compute, h->red.partial + REDUCE_BLOCKS,
                        REDUCE_BLOCKS, h->red.result + 1);
-    SNAP_HIP(hipMemcpyAsync(h->red.host, h->red.result, 2 * sizeof(double), hipMemcpyDeviceToHost, h->compute));
-    SNAP_HIP(hipStreamSynchronize(h->compute));
+    SNAP_TRY(fetch_results(h, 2));
     const double s1 = h->red.host[0], s2 = h->red.host[1];
     *eff_len = s2 > 0.0 ? s1 * s1 / s2 : (double)h->vlen;
     return SNAP_OK;

@@ -52,8 +52,9 @@ static int enqueue_copy(snap_handle* h, int64_t ch, int b, bool profile) {
     if (count > 0) {
         SNAP_HIP(hipMemcpyAsync(h->buf_idx[b], h->host_idx + ck.nnz0, count * sizeof(uint32_t), hipMemcpyHostToDevice,
                                 h->copy));
-        SNAP_HIP(hipMemcpyAsync(h->buf_val[b], h->host_val + ck.nnz0, count * sizeof(float), hipMemcpyHostToDevice,
-                                h->copy));
+        if (!h->stream_unit)       // (pattern-only data: the value buffers hold ones for good)
+            SNAP_HIP(hipMemcpyAsync(h->buf_val[b], h->host_val + ck.nnz0, count * sizeof(float), hipMemcpyHostToDevice,
+                                    h->copy));
     }
     if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 1], h->copy));
     SNAP_HIP(hipEventRecord(h->ev_copied[b], h->copy));
@@ -96,6 +97,11 @@ int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profil
         b = nb;
     }
     if (profile) h->chunk_events_valid = true;
+    // The pass ends with the host waiting for the copy stream (by then only the fetch of chunk 0 for
+    // the next pass is outstanding).  Measured: when the host instead runs a whole pass ahead of the
+    // copy stream, the copy commands and the kernels stop overlapping (68 ms per chunk instead of 40
+    // on the 200 M-row workload: each kernel then starts only when the next chunk's copy has ended).
+    SNAP_HIP(hipStreamSynchronize(h->copy));
     return SNAP_OK;
 }
 

@@ -205,6 +205,7 @@ def test_config5_streamed_full_size():
     assert P[2] < P[1] < P[0]
     st = g.epoch_stats()
     assert st["n_chunks"] == len(bounds) - 1
+    assert g.stream_bytes() == 4 * p.nnz                  # the all-ones values stay on the device
     assert st["copy_ms"] > 0 and st["scd_ms"] > 0 and st["epoch_ms"] < st["copy_ms"] + st["scd_ms"]   # overlapped
     _, x = g.model()
     v = g.shared()

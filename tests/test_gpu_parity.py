@@ -252,22 +252,28 @@ def _pinned(p):
     return q
 
 
-@pytest.mark.parametrize("name,chunk_bytes,budget", [("stream_uniform_logistic", 1 << 20, 2 << 20),
-                                                     ("stream_onehot_logistic", 5 << 20, 4 << 20)])
-def test_streamed_epochs_match_oracle_and_resident(name, chunk_bytes, budget):
+@pytest.mark.parametrize("name,chunk_bytes,budget,unit", [("stream_uniform_logistic", 1 << 20, 2 << 20, True),
+                                                          ("stream_uniform_logistic", 1 << 20, 2 << 20, False),
+                                                          ("stream_onehot_logistic", 5 << 20, 4 << 20, True)])
+def test_streamed_epochs_match_oracle_and_resident(name, chunk_bytes, budget, unit):
     p = problem(name)
+    if not unit:                                         # general values: the value array is streamed too
+        p = p.to("cpu")
+        p.val = torch.from_numpy((0.5 + np.random.default_rng(2).random(p.nnz)).astype(np.float32))
     q = _pinned(p)
     A = oracle.Matrix.from_problem(p)
     y = p.y.numpy()
     g = snap.Solver.from_problem(q, device_budget_bytes=budget, chunk_bytes=chunk_bytes, profile=True)
     bounds = g.chunk_bounds()
     assert len(bounds) - 1 >= 6 and bounds[0] == 0 and bounds[-1] == p.d
+    assert g.stream_bytes() == (4 if unit else 8) * p.nnz      # all-ones values are not copied again
     ptr = p.ptr.numpy()
     for k in range(len(bounds) - 1):                     # chunk sizes respect chunk_bytes (or one coordinate)
         nnzk = ptr[bounds[k + 1]] - ptr[bounds[k]]
         assert nnzk * 8 <= chunk_bytes or bounds[k + 1] - bounds[k] == 1
     o = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=bounds)
     r = gpu_solver(p)                                    # resident twin for the deterministic kernels
+    assert r.stream_bytes() == 0
     assert rel(g.duality_gap(), r.duality_gap()) <= 1e-12
     epochs = 30
     for e in range(epochs):
