@@ -77,8 +77,10 @@ typedef struct {
     int form;                    /* SNAP_FORM_AUTO | SNAP_PRIMAL | SNAP_DUAL */
     size_t device_budget_bytes;  /* 0: keep the matrix resident; else stream it when larger */
     size_t chunk_bytes;          /* streaming chunk size in bytes of idx+val (0: 4 GiB) */
-    void *compute_stream;        /* hipStream_t to run on (e.g. PyTorch's), or NULL: own stream */
-    void *copy_stream;           /* hipStream_t for chunk copies, or NULL: own stream */
+    void *compute_stream;        /* hipStream_t to run on (e.g. PyTorch's), or NULL: the library's compute stream of
+                                    the current device (one per device, shared by all handles created this way:
+                                    their work is ordered among them) */
+    void *copy_stream;           /* hipStream_t for chunk copies, or NULL: the library's copy stream of the device */
     int refresh_v_every;         /* recompute v = A x every this many epochs; 0 = never */
     int profile;                 /* 1: bracket each epoch's SCD kernels with HIP events */
     int adaptive;                /* 0: default (on; off with group_bounds), 1: on, 2: off.  On: after every epoch the

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdlib>
+#include <mutex>
 #include <cmath>
 #include <algorithm>
 #include <new>
@@ -96,8 +97,6 @@ static void destroy(snap_handle* h) {
     sorter_free(h->sorter);
     reducer_free(h->red);
     delete[] h->chunks;
-    if (h->own_compute && h->compute) (void)hipStreamDestroy(h->compute);
-    if (h->own_copy && h->copy) (void)hipStreamDestroy(h->copy);
     delete h;
 }
 
@@ -123,20 +122,31 @@ static int create_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void
     return norms_and_classes_chunk(h, cv);
 }
 
+// The library's own streams: one compute and one copy stream per device, created on first use and
+// kept for the life of the process.  Handles come and go (a test suite makes hundreds of them) and
+// all share these two: a stream may cost the runtime a hardware queue with its pinned host memory,
+// and stream creation is not something to have fail in the middle of snap_create when pinned memory
+// is short.
+static int library_stream(int device, int which, hipStream_t* out) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex lock;
+    static hipStream_t streams[MAX_DEVICES][2] = {};
+    if (device < 0 || device >= MAX_DEVICES) {
+        set_error("device index %d out of range", device);
+        return SNAP_EINVAL;
+    }
+    std::lock_guard<std::mutex> guard(lock);
+    if (!streams[device][which]) SNAP_HIP(hipStreamCreateWithFlags(&streams[device][which], hipStreamNonBlocking));
+    *out = streams[device][which];
+    return SNAP_OK;
+}
+
 static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_HIP(hipGetDevice(&h->device));
-    if (h->opt.compute_stream) {
-        h->compute = (hipStream_t)h->opt.compute_stream;
-    } else {
-        SNAP_HIP(hipStreamCreateWithFlags(&h->compute, hipStreamNonBlocking));
-        h->own_compute = true;
-    }
-    if (h->opt.copy_stream) {
-        h->copy = (hipStream_t)h->opt.copy_stream;
-    } else {
-        SNAP_HIP(hipStreamCreateWithFlags(&h->copy, hipStreamNonBlocking));
-        h->own_copy = true;
-    }
+    if (h->opt.compute_stream) h->compute = (hipStream_t)h->opt.compute_stream;
+    else SNAP_TRY(library_stream(h->device, 0, &h->compute));
+    if (h->opt.copy_stream) h->copy = (hipStream_t)h->opt.copy_stream;
+    else SNAP_TRY(library_stream(h->device, 1, &h->copy));
     for (auto& e : h->ev) SNAP_HIP(hipEventCreate(&e));
     SNAP_TRY(reducer_alloc(h->red));
     SNAP_HIP(hipMalloc(&h->status, sizeof(uint32_t)));
@@ -365,6 +375,7 @@ static int epoch_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void*
 }  // namespace snap
 
 using namespace snap;
+
 
 extern "C" {
 

@@ -166,7 +166,6 @@ struct snap_handle {
     int tile_vec = 4;                 // consecutive rows per thread of the row pass
 
     hipStream_t compute = nullptr, copy = nullptr;
-    bool own_compute = false, own_copy = false;
     hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     // concurrency control and the adaptive safeguard
     int64_t inflight_nnz = 0;         // current cap on nonzeros in flight (<= 0: no cap)

@@ -219,3 +219,9 @@ def test_config5_streamed_full_size():
     assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want)
     assert rel(P[2], oracle.primal_objective(oracle.LOGISTIC, v, p.y.numpy(), x, p.lam)) <= 1e-5
     g.close()
+    # give the 62 GB of pinned host memory back: PyTorch's host allocator would keep them cached, and
+    # later pinned allocations of this process (the runtime's own included) would fail
+    del p, g
+    import gc
+    gc.collect()
+    torch._C._host_emptyCache()
