@@ -150,7 +150,8 @@ k_tile_pass(const float* __restrict__ A, int64_t ld, int64_t n, int64_t prev_c0,
     }
     const float* col = A + cur_c0 * ld;
 #pragma unroll 4
-    for (int j = w; j < TILE_B; j += NQ) {
+    for (int jj = 0; jj < TILE_B / NQ; ++jj) {
+        const int j = w + jj * NQ;
         float s = 0.0f;
         if (j < n_cur) {
 #pragma unroll
