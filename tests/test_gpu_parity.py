@@ -557,7 +557,7 @@ def _tile_bounds(d, b=128):
 
 
 @pytest.mark.parametrize("n,d,lam1", [(20_000, 300, 0.0), (20_001, 70, 0.0), (5_003, 64, 0.0), (20_000, 300, 1e-4),
-                                      (900, 130, 0.0)])
+                                      (900, 130, 0.0), (5, 1, 0.0), (3, 200, 0.0), (1, 129, 0.0), (1026, 257, 1e-5)])
 def test_dense_tile_sweeps_equal_sequential_oracle(n, d, lam1):
     p = datagen.dense_ridge(n=n, d=d, seed=5)
     A = oracle.Matrix.from_problem(p)
