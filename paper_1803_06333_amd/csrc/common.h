@@ -205,6 +205,7 @@ int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profil
 int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* bounds, int64_t n_groups);
 int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bounds);   // empty: nothing found
 int grouped_epoch(snap_handle* h);
+int grouped_dots(snap_handle* h);    // gdot[c] = inner product of coordinate c with loss'(v), by row passes
 std::vector<int64_t> group_order(uint64_t seed, int64_t n_groups);   // visiting order of the groups for a seed
 void grouped_free(snap_handle* h);
 

@@ -553,13 +553,15 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
 // not written while this kernel runs) and takes the step right away.
 constexpr int STEP_RANKS = 32, STEP_PARTS = 32;
 
-template <int KIND>
+// DOTS: no step is taken; the first sum (the coordinate's inner product with loss'(v)) goes to gdot.
+template <int KIND, bool DOTS>
 __global__ void __launch_bounds__(STEP_RANKS * STEP_PARTS)
 k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, int n_wgs, int hot, int n_hot_blocks,
                double inv_scale_g, double inv_scale_h, const int64_t* __restrict__ ptr,
                const uint32_t* __restrict__ idx, const float* __restrict__ val, const float* __restrict__ v,
                const float* __restrict__ y, const uint32_t* __restrict__ coord_of, int64_t g0, int64_t group_size,
-               float* __restrict__ x, const float* __restrict__ norms, float* __restrict__ delta, StepParams sp) {
+               float* __restrict__ x, const float* __restrict__ norms, float* __restrict__ delta, StepParams sp,
+               double* __restrict__ gdot) {
     __shared__ long long sg[STEP_PARTS][STEP_RANKS], sh[STEP_PARTS][STEP_RANKS];
     if ((int)blockIdx.x >= n_hot_blocks) {
         const int lane = threadIdx.x & (WAVE - 1);
@@ -577,9 +579,13 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
             g = wave_sum(g);
             hh = wave_sum(hh);
             if (lane == 0) {
-                float mult;
-                x[c] = take_step<KIND>((double)g, (double)hh, x[c], norms[c], 0.0f, sp, mult);
-                delta[g0 + rk] = mult;
+                if (DOTS) {
+                    gdot[c] = (double)g;
+                } else {
+                    float mult;
+                    x[c] = take_step<KIND>((double)g, (double)hh, x[c], norms[c], 0.0f, sp, mult);
+                    delta[g0 + rk] = mult;
+                }
             }
         }
         return;
@@ -606,6 +612,10 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
         Hi += sh[p][lr];
     }
     const int64_t c = coord_of[g0 + rk];
+    if (DOTS) {
+        gdot[c] = (double)Gi * inv_scale_g;
+        return;
+    }
     float mult;
     x[c] = take_step<KIND>((double)Gi * inv_scale_g, (double)Hi * inv_scale_h, x[c], norms[c], 0.0f, sp, mult);
     delta[g0 + rk] = mult;
@@ -675,15 +685,62 @@ static int grouped_epoch_kind(snap_handle* h) {
         const int64_t cold = sz - hot;
         const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
         const int n_cold_blocks = (int)std::min<int64_t>((cold + waves_per_block - 1) / waves_per_block, 8192);
-        hipLaunchKernelGGL((k_group_finish<KIND>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
+        hipLaunchKernelGGL((k_group_finish<KIND, false>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
                            dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, row_wgs(), hot,
                            n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, h->ptr, h->idx, h->val, h->v,
-                           h->y, h->coord_of, g0, sz, h->x, h->norms, h->gdelta, sp);
+                           h->y, h->coord_of, g0, sz, h->x, h->norms, h->gdelta, sp, nullptr);
         prev = g;
     }
     h->n_row_passes = n_pass;
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
+}
+
+// Inner products of every coordinate with loss'(v) (the gradient of the loss term times n), for the
+// objective / duality-gap pass: the same row passes as an epoch, sums only, nothing is stepped.
+template <int KIND, bool UNIT, typename MAPT>
+static int grouped_dots_kind(snap_handle* h) {
+    const StepParams sp = make_step_params(h);
+    const int64_t n = h->n, G = h->n_groups;
+    long long* gpart = (long long*)h->gpartial;
+    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ldexpf(1.0f, 30 - h->gscale_exp) : ldexpf(1.0f, 24);
+    const float scale_h = ldexpf(1.0f, 30 - 2 * h->gscale_exp);
+    const MAPT* maps = (const MAPT*)h->rowmap;
+    for (int64_t g = 0; g < G; ++g) {
+        const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
+        if (sz == 0) continue;
+        const int hot = h->ghot_host[g];
+        if (n > 0 && hot > 0) {
+            const size_t lds = (size_t)2 * hot * sizeof(unsigned long long);
+            hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
+                               (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr, maps + (size_t)g * h->n_pad,
+                               UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot, h->v, h->y, h->ybits, n,
+                               gpart, h->gpartial_stride, scale_g, scale_h, 0);
+        }
+        const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
+        const int64_t cold = sz - hot;
+        const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
+        const int n_cold_blocks = (int)std::min<int64_t>((cold + waves_per_block - 1) / waves_per_block, 8192);
+        if (n_hot_blocks + n_cold_blocks > 0)
+            hipLaunchKernelGGL((k_group_finish<KIND, true>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
+                               dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, row_wgs(), hot,
+                               n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, h->ptr, h->idx, h->val, h->v,
+                               h->y, h->coord_of, g0, sz, h->x, h->norms, h->gdelta, sp, h->gdot);
+    }
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
+template <int KIND>
+static int grouped_dots_dispatch(snap_handle* h) {
+    if (h->map16)
+        return h->unit_values ? grouped_dots_kind<KIND, true, uint16_t>(h) : grouped_dots_kind<KIND, false, uint16_t>(h);
+    return h->unit_values ? grouped_dots_kind<KIND, true, uint32_t>(h) : grouped_dots_kind<KIND, false, uint32_t>(h);
+}
+
+int grouped_dots(snap_handle* h) {
+    return h->kind == K_PRIMAL_RIDGE ? grouped_dots_dispatch<K_PRIMAL_RIDGE>(h)
+                                     : grouped_dots_dispatch<K_PRIMAL_LOGISTIC>(h);
 }
 
 template <int KIND>

@@ -478,7 +478,7 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
         SNAP_TRY(reduce_to(h, R_SQNORM, rx, 1));
         if (lam1 > 0.0) SNAP_TRY(reduce_to(h, R_ABSSUM, rx, 3));
         if (need_gap) {
-            SNAP_TRY(coord_dots(h));
+            SNAP_TRY(h->grouped ? grouped_dots(h) : coord_dots(h));
             if (lam1 > 0.0) {
                 // Fenchel form: P + f*(u) + sum_j g*(a_j.u), u = grad f(v); a_j.u = gdot_j / n
                 ReduceArgs rg{nullptr, nullptr, h->gdot, 1.0 / n, lam1, h->m};

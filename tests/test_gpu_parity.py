@@ -790,3 +790,35 @@ def test_auto_groups_gives_up_on_unstructured_data():
         snap.Solver("csc", 3, 2, ptr, idx, np.ones(3, dtype=np.float32), np.ones(3, dtype=np.float32), "ridge", 0.1,
                     auto_groups=True)
     assert e.value.code == -2
+
+
+@pytest.mark.parametrize("loss,unit,lam1", [("logistic", True, 0.0), ("logistic", False, 2e-4), ("ridge", True, 0.0),
+                                            ("ridge", False, 1e-3)])
+def test_group_sweeps_objective_and_gap_at_a_given_model(loss, unit, lam1):
+    # with groups the gradient pass behind the duality gap runs as row passes, not column gathers
+    p = _onehot_variant(loss, unit)
+    groups = p.meta["field_starts"] + [p.d]
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    rng = np.random.default_rng(21)
+    w = (0.2 * rng.standard_normal(p.d) * (rng.random(p.d) < 0.5)).astype(np.float32)
+    o = oracle.Solver(A, y, p.loss, p.lam, lam1=lam1)
+    o.x[:] = w
+    o.v[:] = o.shared_from_model()
+    g = gpu_solver(p, group_bounds=groups, lam1=lam1)
+    a = gpu_solver(p, lam1=lam1)                           # column-wise gradient pass on the same model
+    for s in (g, a):
+        s.set_model(w)
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    assert rel(g.duality_gap(), o.gap()) <= 1e-5
+    assert rel(g.duality_gap(), a.duality_gap()) <= 1e-5
+    P, D = g.objective(want_dual=True)
+    assert abs((P - D) - g.duality_gap()) <= 1e-12 * max(1.0, abs(P))
+    # at the zero model too (closed form: every loss' is -y/2 resp. -y)
+    z = np.zeros(p.d, dtype=np.float32)
+    g.set_model(z)
+    o.x[:] = 0
+    o.v[:] = 0
+    assert rel(g.duality_gap(), o.gap()) <= 1e-5
+    g.close()
+    a.close()
