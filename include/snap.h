@@ -208,6 +208,13 @@ int snap_get_epoch_stats(snap_handle *h, snap_epoch_stats *out);
  * inside each with the group index entering the key; the groups themselves in seeded random order). */
 int snap_get_chunks(snap_handle *h, int64_t *n_chunks, int64_t *bounds_out);
 
+/* Host-side pieces of the epoch order (Section 3.2), usable without a device: the 32-bit key of
+ * coordinate c of a chunk (group, tile) under perm_seed -- the order inside the chunk is the
+ * coordinates sorted by (key, index) -- and the visiting order of n_blocks groups or tiles (their
+ * keys under the reserved chunk id 0xFFFFFFFF, sorted the same way; order_out: n_blocks entries). */
+uint32_t snap_perm_key(uint64_t perm_seed, uint32_t chunk, uint32_t c);
+int snap_block_order(uint64_t perm_seed, int64_t n_blocks, int64_t *order_out);
+
 /* Bytes that one pass over the data copies from host memory (0 when the matrix is resident).  When
  * every stored value is 1.0 (found at creation) only the indices are streamed: 4 bytes per nonzero
  * instead of 8. */

@@ -25,7 +25,7 @@ LOSSES = {"ridge": RIDGE, "logistic": LOGISTIC, "hinge": HINGE}
 
 EXPORTS = ["snap_create", "snap_epoch", "snap_objective", "snap_duality_gap", "snap_predict", "snap_get_model",
            "snap_set_model", "snap_get_shared", "snap_recompute_shared", "snap_get_perm", "snap_get_epoch_stats",
-           "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_last_error", "snap_destroy"]
+           "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_perm_key", "snap_block_order", "snap_last_error", "snap_destroy"]
 
 
 class SnapMatrix(C.Structure):
@@ -83,6 +83,9 @@ def load_library():
         L.snap_get_epoch_stats.argtypes = [C.c_void_p, C.POINTER(SnapEpochStats)]
         L.snap_get_dims.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.snap_get_chunks.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]
+        L.snap_perm_key.restype = C.c_uint32
+        L.snap_perm_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
+        L.snap_block_order.argtypes = [C.c_uint64, C.c_int64, C.c_void_p]
         _lib = L
     return _lib
 
@@ -118,6 +121,18 @@ def make_matrix(layout: str, n_rows: int, n_cols: int, ptr, idx, val):
     nnz = int(k3.numel() if hasattr(k3, "numel") else k3.size)
     sm = SnapMatrix(LAYOUTS[layout], mem, n_rows, n_cols, nnz, pp, pi, pv)
     return sm, (k1, k2, k3)
+
+
+def perm_key(seed: int, chunk: int, c: int) -> int:
+    """Key of coordinate c of a chunk under the seed (host function of the library)."""
+    return int(load_library().snap_perm_key(seed, chunk, c))
+
+
+def block_order(seed: int, n_blocks: int) -> list:
+    """Visiting order of the groups / tiles of an epoch with this seed (host function of the library)."""
+    out = np.empty(max(n_blocks, 1), dtype=np.int64)
+    _check(load_library().snap_block_order(seed, n_blocks, out.ctypes.data))
+    return out[:n_blocks].tolist()
 
 
 class Solver:

@@ -1,5 +1,6 @@
 // The C ABI of libsnap (see include/snap.h): argument checking, data placement, the epoch driver.
 #include "common.h"
+#include "perm_key.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -743,6 +744,20 @@ int snap_get_chunks(snap_handle* h, int64_t* n_chunks, int64_t* bounds_out) {
         for (int64_t ch = 0; ch < h->n_chunks; ++ch) bounds_out[ch] = h->chunks[ch].c0;
         bounds_out[h->n_chunks] = h->m;
     }
+    return SNAP_OK;
+}
+
+uint32_t snap_perm_key(uint64_t perm_seed, uint32_t chunk, uint32_t c) {
+    return perm_key(perm_key_base(perm_seed, chunk), c);
+}
+
+int snap_block_order(uint64_t perm_seed, int64_t n_blocks, int64_t* order_out) {
+    if (n_blocks < 0 || n_blocks > 0xFFFFFFFFll || (n_blocks > 0 && !order_out)) {
+        set_error("snap_block_order: need 0 <= n_blocks < 2^32 and an output array");
+        return SNAP_EINVAL;
+    }
+    const std::vector<int64_t> order = group_order(perm_seed, n_blocks);
+    std::copy(order.begin(), order.end(), order_out);
     return SNAP_OK;
 }
 

@@ -49,3 +49,28 @@ def test_create_without_a_gpu_reports_an_error_instead_of_crashing():
         with pytest.raises(snap.SnapError) as e:
             snap.Solver("csc", 2, 2, ptr, idx, val, y, "ridge", 0.1)
         assert e.value.code in (-4, -3)
+
+
+def test_host_side_epoch_order_matches_the_known_answers_and_the_oracle():
+    """The library's own key generator and block order, called on the host (no device), against the
+    fixture written from the oracle and against the oracle directly: the two implement the same
+    counter-based generator separately."""
+    import numpy as np
+    import oracle
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "perm_known_answers.txt")) if l[0] != "#"]
+    n_checked = 0
+    for kind, seed, chunk, m, *vals in rows:
+        if kind != "keys":
+            continue
+        got = [snap.perm_key(int(seed), int(chunk), c) for c in range(16)]
+        assert got == [int(v) for v in vals]
+        n_checked += 1
+    assert n_checked >= 4
+    rng = np.random.default_rng(0)
+    for seed, chunk in [(0, 0), (7, 3), (2 ** 64 - 1, 2 ** 32 - 1), (180306333, 12345)]:
+        for c in [0, 1, 63, 64, 4095, 2 ** 31, 2 ** 32 - 1] + rng.integers(0, 2 ** 32, 20).tolist():
+            assert snap.perm_key(seed, chunk, int(c)) == oracle.lib().oracle_key(seed, chunk, int(c))
+    for seed, nb in [(0, 1), (5, 2), (42, 39), (9, 1000), (2 ** 63, 4097)]:
+        want = oracle.permutation(seed, nb, chunk=oracle.Solver.GROUP_ORDER_CHUNK)
+        assert snap.block_order(seed, nb) == want.tolist()
+    assert snap.block_order(3, 0) == []
