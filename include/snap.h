@@ -208,6 +208,13 @@ int snap_get_epoch_stats(snap_handle *h, snap_epoch_stats *out);
  * inside each with the group index entering the key; the groups themselves in seeded random order). */
 int snap_get_chunks(snap_handle *h, int64_t *n_chunks, int64_t *bounds_out);
 
+/* Epochs until the duality gap is small: runs snap_epoch with seeds seed0, seed0 + 1, ... and
+ * evaluates the gap after every check_every-th epoch (>= 1), stopping when gap <= gap_tol or after
+ * max_epochs.  *epochs_out (may be NULL) receives the number of epochs run, *gap_out (may be NULL)
+ * the last gap evaluated (evaluated once at the end if no check fell on the last epoch). */
+int snap_solve(snap_handle *h, uint64_t seed0, int64_t max_epochs, double gap_tol, int64_t check_every,
+               int64_t *epochs_out, double *gap_out);
+
 /* Host-side pieces of the epoch order (Section 3.2), usable without a device: the 32-bit key of
  * coordinate c of a chunk (group, tile) under perm_seed -- the order inside the chunk is the
  * coordinates sorted by (key, index) -- and the visiting order of n_blocks groups or tiles (their

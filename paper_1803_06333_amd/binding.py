@@ -25,7 +25,7 @@ LOSSES = {"ridge": RIDGE, "logistic": LOGISTIC, "hinge": HINGE}
 
 EXPORTS = ["snap_create", "snap_epoch", "snap_objective", "snap_duality_gap", "snap_predict", "snap_get_model",
            "snap_set_model", "snap_get_shared", "snap_recompute_shared", "snap_get_perm", "snap_get_epoch_stats",
-           "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_perm_key", "snap_block_order", "snap_last_error", "snap_destroy"]
+           "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_solve", "snap_perm_key", "snap_block_order", "snap_last_error", "snap_destroy"]
 
 
 class SnapMatrix(C.Structure):
@@ -83,6 +83,8 @@ def load_library():
         L.snap_get_epoch_stats.argtypes = [C.c_void_p, C.POINTER(SnapEpochStats)]
         L.snap_get_dims.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.snap_get_chunks.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]
+        L.snap_solve.argtypes = [C.c_void_p, C.c_uint64, C.c_int64, C.c_double, C.c_int64, C.POINTER(C.c_int64),
+                                 C.POINTER(C.c_double)]
         L.snap_perm_key.restype = C.c_uint32
         L.snap_perm_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
         L.snap_block_order.argtypes = [C.c_uint64, C.c_int64, C.c_void_p]
@@ -242,6 +244,12 @@ class Solver:
         b = np.empty(n.value + 1, dtype=np.int64)
         _check(self._lib.snap_get_chunks(self._h, C.byref(n), b.ctypes.data))
         return b.tolist()
+
+    def solve(self, seed0: int, max_epochs: int, gap_tol: float, check_every: int = 5):
+        """Epochs with seeds seed0, seed0 + 1, ... until the duality gap is at most gap_tol: (epochs run, gap)."""
+        e, g = C.c_int64(), C.c_double()
+        _check(self._lib.snap_solve(self._h, seed0, max_epochs, gap_tol, check_every, C.byref(e), C.byref(g)))
+        return e.value, g.value
 
     def stream_bytes(self) -> int:
         """Bytes copied from host memory by one pass over the data (0: resident)."""

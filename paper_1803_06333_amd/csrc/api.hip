@@ -747,6 +747,33 @@ int snap_get_chunks(snap_handle* h, int64_t* n_chunks, int64_t* bounds_out) {
     return SNAP_OK;
 }
 
+int snap_solve(snap_handle* h, uint64_t seed0, int64_t max_epochs, double gap_tol, int64_t check_every,
+               int64_t* epochs_out, double* gap_out) {
+    if (!h || max_epochs < 0 || check_every < 1 || !(gap_tol >= 0.0)) {
+        set_error("snap_solve: need a handle, max_epochs >= 0, check_every >= 1, gap_tol >= 0");
+        return SNAP_EINVAL;
+    }
+    int64_t e = 0;
+    double gap = 0.0;
+    bool fresh = false;
+    for (; e < max_epochs; ++e) {
+        SNAP_TRY(snap_epoch(h, seed0 + (uint64_t)e));
+        fresh = false;
+        if ((e + 1) % check_every == 0) {
+            SNAP_TRY(snap_duality_gap(h, &gap));
+            fresh = true;
+            if (gap <= gap_tol) {
+                ++e;
+                break;
+            }
+        }
+    }
+    if (!fresh) SNAP_TRY(snap_duality_gap(h, &gap));
+    if (epochs_out) *epochs_out = e;
+    if (gap_out) *gap_out = gap;
+    return SNAP_OK;
+}
+
 uint32_t snap_perm_key(uint64_t perm_seed, uint32_t chunk, uint32_t c) {
     return perm_key(perm_key_base(perm_seed, chunk), c);
 }

@@ -822,3 +822,34 @@ def test_group_sweeps_objective_and_gap_at_a_given_model(loss, unit, lam1):
     assert rel(g.duality_gap(), o.gap()) <= 1e-5
     g.close()
     a.close()
+
+
+def test_solve_runs_epochs_until_the_gap_target():
+    p = _onehot_variant("logistic", True)
+    groups = p.meta["field_starts"] + [p.d]
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    g = gpu_solver(p, group_bounds=groups)
+    epochs, gap = g.solve(100, 200, 1e-4, check_every=4)
+    assert 0 < epochs < 200 and epochs % 4 == 0 and gap <= 1e-4
+    assert rel(gap, g.duality_gap()) <= 1e-12
+    # the same epochs by hand (same seeds) reach the same model: group sweeps are deterministic
+    r = gpu_solver(p, group_bounds=groups)
+    for e in range(epochs):
+        r.epoch(100 + e)
+    assert np.array_equal(r.model()[1], g.model()[1])
+    # the oracle taking the same epochs agrees on where that is
+    o = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    for e in range(epochs):
+        o.epoch(100 + e)
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    assert o.gap() <= 1.1e-4
+    # budget exhausted: reports the gap it stopped at; zero epochs: just the gap
+    e2, gap2 = r.solve(0, 3, 0.0, check_every=5)
+    assert e2 == 3 and gap2 > 0.0
+    e3, gap3 = r.solve(0, 0, 1.0)
+    assert e3 == 0 and rel(gap3, r.duality_gap()) <= 1e-12
+    with pytest.raises(snap.SnapError):
+        r.solve(0, 5, 1e-3, check_every=0)
+    g.close()
+    r.close()
