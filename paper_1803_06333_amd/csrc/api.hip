@@ -57,8 +57,13 @@ static int check_status(snap_handle* h) {
     SNAP_HIP(hipGetLastError());
     SNAP_HIP(hipStreamSynchronize(h->compute));
     const uint32_t st = reinterpret_cast<const uint32_t*>(h->red.host + 7)[0];
-    if (st & 1u) {
+    if (st & STATUS_SPIN) {
         set_error("a scatter work item gave up waiting for its coordinate's step; the state is invalid");
+        return SNAP_ESTATE;
+    }
+    if (st & STATUS_RANGE) {
+        set_error("group sweeps: a term a (v - y) reached 2^14, beyond the range of the fixed-point sums; the state "
+                  "is invalid (scale the data, or create the handle with auto_groups off and without group_bounds)");
         return SNAP_ESTATE;
     }
     return SNAP_OK;

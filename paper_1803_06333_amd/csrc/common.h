@@ -33,6 +33,8 @@ constexpr int WAVES_PER_WG = TPB / WAVE;
 constexpr int64_t SEG_DEFAULT = 16384;
 constexpr int64_t SMALL_MAX_DEFAULT = 4096;
 constexpr uint32_t LABEL_BIT = 0x80000000u;   // primal logistic: sign of y folded into the row index
+constexpr uint32_t STATUS_SPIN = 1u;          // status word: a scatter item gave up waiting for its coordinate's step
+constexpr uint32_t STATUS_RANGE = 8u;         // status word: a term too large for the fixed-point sums of a group sweep
 constexpr uint32_t SPIN_LIMIT = 1u << 22;     // bounded wait of a scatter item for its coordinate's step
 
 // K_DUAL: examples as coordinates (hinge or logistic loss: the kernels differ only in the scalar step)

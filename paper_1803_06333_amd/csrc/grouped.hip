@@ -410,7 +410,10 @@ template <> struct MapTraits<uint32_t> { static constexpr int R = 4; static cons
 
 // Round-to-nearest fixed point.  Logistic terms are bounded, so their scaled magnitude is known to
 // stay below 2^31 and one 32-bit conversion does; ridge terms a (v - y) have no a-priori bound and
-// take the 64-bit conversion.
+// take the 64-bit conversion.  With 24 fractional bits the 64-bit sum of a ridge coordinate has 2^39 of
+// range: every term a (v - y) must stay below 2^14 for up to 2^25 rows; larger terms raise the handle's
+// status word instead of overflowing silently.
+constexpr float RIDGE_TERM_LIMIT = 16384.0f;
 template <int KIND>
 __device__ __forceinline__ unsigned long long to_fixed(float x, float scale) {
     if (KIND == K_PRIMAL_LOGISTIC) return (unsigned long long)(long long)__float2int_rn(x * scale);
@@ -444,7 +447,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
              const float* __restrict__ delta_prev, const MAPT* __restrict__ map_cur,
              const float* __restrict__ val_cur, int hot, float* __restrict__ v, const float* __restrict__ y,
              const uint8_t* __restrict__ ybits, int64_t n, long long* __restrict__ partial, int64_t partial_stride,
-             float scale_g, float scale_h, int kd) {
+             float scale_g, float scale_h, int kd, uint32_t* __restrict__ status) {
     constexpr int R = MapTraits<MAPT>::R;
     constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
     // LDS: fixed-point sums, [0,hot): sum of a loss' * scale_g, [hot,2hot): sum of a^2 loss'' * scale_h,
@@ -460,6 +463,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
     // the two longest coordinates of a group hold a quarter of its rows: their sums stay in
     // registers (one LDS update per wavefront at the end) instead of colliding in LDS
     float rg0 = 0.0f, rg1 = 0.0f, rh0 = 0.0f, rh1 = 0.0f;
+    bool too_large = false;                    // ridge: a term outside the range the 64-bit sums are laid out for
     const int64_t packs = (n + R - 1) / R;
     const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
     const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
@@ -511,6 +515,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                     if (KIND == K_PRIMAL_LOGISTIC) yy[j] = ((lab >> j) & 1u) ? -1.0f : 1.0f;
                     float g = 0.0f, hh = 0.0f;
                     accumulate<KIND>(UNIT ? 1.0f : ac[j], vv[j], yy[j], g, hh);
+                    if (KIND == K_PRIMAL_RIDGE) too_large |= !(fabsf(g) < RIDGE_TERM_LIMIT);
                     if (rk < 2u) {
                         rg0 += rk == 0u ? g : 0.0f;
                         rg1 += rk == 1u ? g : 0.0f;
@@ -528,6 +533,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         }
     }
     if (HIST) {
+        if (KIND == K_PRIMAL_RIDGE && too_large) atomicOr(status, STATUS_RANGE);
         rg0 = wave_sum(rg0); rg1 = wave_sum(rg1);
         if (KIND == K_PRIMAL_LOGISTIC) {
             rh0 = wave_sum(rh0); rh1 = wave_sum(rh1);
@@ -668,15 +674,15 @@ static int grouped_epoch_kind(snap_handle* h) {
             if (scatter && histo)
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, kd);
+                                   h->gpartial_stride, scale_g, scale_h, kd, h->status);
             else if (scatter)
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, 0, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, kd);
+                                   h->gpartial_stride, scale_g, scale_h, kd, h->status);
             else
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, kd);
+                                   h->gpartial_stride, scale_g, scale_h, kd, h->status);
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
             ++n_pass;
         }
@@ -715,7 +721,7 @@ static int grouped_dots_kind(snap_handle* h) {
             hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
                                (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr, maps + (size_t)g * h->n_pad,
                                UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot, h->v, h->y, h->ybits, n,
-                               gpart, h->gpartial_stride, scale_g, scale_h, 0);
+                               gpart, h->gpartial_stride, scale_g, scale_h, 0, h->status);
         }
         const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
         const int64_t cold = sz - hot;

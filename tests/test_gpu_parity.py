@@ -853,3 +853,19 @@ def test_solve_runs_epochs_until_the_gap_target():
         r.solve(0, 5, 1e-3, check_every=0)
     g.close()
     r.close()
+
+
+def test_group_sweeps_report_terms_beyond_the_fixed_point_range():
+    p = _onehot_variant("ridge", False)
+    groups = p.meta["field_starts"] + [p.d]
+    p.y = p.y * 1e6                                        # residuals of 1e6: a (v - y) far beyond 2^14
+    g = gpu_solver(p, group_bounds=groups)
+    g.epoch(0)
+    with pytest.raises(snap.SnapError) as e:
+        g.objective()
+    assert e.value.code == -5 and "range" in str(e.value)
+    g.close()
+    a = gpu_solver(p)                                      # the asynchronous epoch has no such limit
+    a.epoch(0)
+    assert np.isfinite(a.objective())
+    a.close()
