@@ -143,6 +143,9 @@ struct snap_handle {
     int64_t n_groups = 0, n_pad = 0;  // n_pad: row stride of the per-group row maps (multiple of 8)
     int64_t* gbounds_host = nullptr;  // [n_groups+1]
     int* ghot_host = nullptr;         // [n_groups] number of hot (LDS-accumulated) ranks per group
+    int* gk64_host = nullptr;         // [n_groups] of those, the leading ranks that keep two 64-bit sums (the rest: one packed word)
+    bool gpack = false;               // packed ranks in use (logistic loss)
+    int g_row_wgs = 0, g_kd_max = 0;  // workgroups of a row pass; steps of the previous group kept in LDS
     void* rowmap = nullptr;           // [n_groups][n_pad]: rank of the row's coordinate in the group (uint16 or uint32)
     bool map16 = true;
     uint8_t* ybits = nullptr;         // bit r = 1 when y[r] < 0

@@ -39,14 +39,32 @@ constexpr uint32_t RANK_NONE = 0xFFFFFFFFu;      // row not covered by the group
 // bits (one v_cvt; a float-to-int64 conversion costs a dozen instructions and the row pass is
 // bound by instruction issue as much as by bandwidth): 24 fractional bits relative to the largest
 // |value|, the fp32 precision of the term itself; the 64-bit sum cannot overflow.
-constexpr int HOT_MAX = 8192;                    // ranks accumulated in LDS (two int64 each: 128 KB)
-constexpr int DELTA_LDS = 8192;                  // steps of the previous group kept in LDS (32 KB)
+//
+// Packed ranks (logistic loss).  With two 8-byte sums per rank and 32 KB of steps the LDS of a compute
+// unit holds one workgroup, 16 wavefronts, and the row pass is short of wavefronts to hide its
+// latencies (measured: two resident workgroups run the same pass 20 % faster).  Both sums of a rank
+// whose coordinate has at most PACK_COUNT_MAX rows fit ONE 64-bit word -- 34 bits for the signed sum
+// of a loss' (21 fractional bits relative to the largest |value|), 30 bits for the sum of a^2 loss''
+// (20 fractional bits); the rounding of the terms averages out over the rows (relative error of a sum
+// about 1e-6 / sqrt(rows)) -- so only the few hundred longest coordinates keep two words.
+// That halves the LDS per rank (and the LDS atomics per row) for the rest, and two workgroups fit.
+constexpr int HOT_MAX = 8192;                    // ranks accumulated in LDS
+constexpr int DELTA_LDS = 8192;                  // steps of the previous group kept in LDS (32 KB; 16 KB when packing)
 constexpr int ROW_TPB = 1024;
-constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit
-static int row_wgs() {
+constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit (two when packing)
+constexpr int PACK_COUNT_MAX = 4095;             // rows of a coordinate whose two sums share one word
+constexpr int PACK_H_BITS = 30;
+static int row_wgs_knob() {
     static const int v = [] {
         const char* e = getenv("SNAP_ROW_WGS");      // tuning knob
-        return e ? std::max(1, atoi(e)) : ROW_WGS_DEFAULT;
+        return e ? std::max(1, atoi(e)) : 0;
+    }();
+    return v;
+}
+static bool pack_knob() {
+    static const bool v = [] {
+        const char* e = getenv("SNAP_PACK");         // tuning knob: 0 switches the packed ranks off
+        return !(e && e[0] == '0');
     }();
     return v;
 }
@@ -136,8 +154,10 @@ void grouped_free(snap_handle* h) {
     }
     delete[] h->gbounds_host;
     delete[] h->ghot_host;
+    delete[] h->gk64_host;
     h->gbounds_host = nullptr;
     h->ghot_host = nullptr;
+    h->gk64_host = nullptr;
     (void)hipFree(h->rowmap);
     (void)hipFree(h->rowval);
     (void)hipFree(h->ybits);
@@ -280,15 +300,20 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     h->n_groups = G;
     h->gbounds_host = new (std::nothrow) int64_t[(size_t)G + 1];
     h->ghot_host = new (std::nothrow) int[(size_t)G];
-    if (!h->gbounds_host || !h->ghot_host) return SNAP_ENOMEM;
+    h->gk64_host = new (std::nothrow) int[(size_t)G];
+    if (!h->gbounds_host || !h->ghot_host || !h->gk64_host) return SNAP_ENOMEM;
     std::copy(gb, gb + G + 1, h->gbounds_host);
 
     int lds_max = 0;
     SNAP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
-    const int hot_cap = std::max(4, std::min<int>(hot_max(), (lds_max - 1024 - 4 * DELTA_LDS) / 16));
+    // packed ranks: two workgroups per compute unit, each with half of the LDS
+    h->gpack = h->kind == K_PRIMAL_LOGISTIC && pack_knob();
+    h->g_kd_max = h->gpack ? DELTA_LDS / 2 : DELTA_LDS;
+    h->g_row_wgs = row_wgs_knob() > 0 ? row_wgs_knob() : (h->gpack ? 2 * ROW_WGS_DEFAULT : ROW_WGS_DEFAULT);
+    const int lds_budget = (h->gpack ? lds_max / 2 : lds_max) - 1024 - 4 * h->g_kd_max;   // bytes for the sums
     // ranks inside each group: coordinates by decreasing length (ties by index)
     std::vector<uint32_t> rank_of((size_t)m), coord_of((size_t)m);
-    int max_hot = 1;
+    int max_words = 2;
     for (int64_t g = 0; g < G; ++g) {
         const int64_t c0 = gb[g], sz = gb[g + 1] - gb[g];
         std::vector<int64_t> order((size_t)sz);
@@ -302,12 +327,21 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         }
         // hot ranks: accumulated in LDS by the row pass; a rank is worth a slot while its
         // coordinate is long enough to be hit by most workgroups
-        int hot = 0;
-        while (hot < sz && hot < hot_cap && hptr[order[(size_t)hot] + 1] - hptr[order[(size_t)hot]] >= ROW_WGS_DEFAULT / 2) ++hot;
+        // ... and of those, the first k64 keep two 64-bit words (too many rows for a packed word; ranks 0
+        // and 1, which the row pass sums in registers, always do), the others one
+        auto rows_of = [&](int r) { return hptr[order[(size_t)r] + 1] - hptr[order[(size_t)r]]; };
+        int hot = 0, k64 = 0;
+        while (hot < sz && hot < hot_max() && rows_of(hot) >= ROW_WGS_DEFAULT / 2) {
+            const bool two_words = !h->gpack || hot < 2 || rows_of(hot) > PACK_COUNT_MAX;
+            if (8 * (hot + 1 + k64 + (two_words ? 1 : 0)) > lds_budget) break;
+            k64 += two_words ? 1 : 0;
+            ++hot;
+        }
         h->ghot_host[g] = hot;
-        max_hot = std::max(max_hot, hot);
+        h->gk64_host[g] = k64;
+        max_words = std::max(max_words, hot + k64);
     }
-    h->gpartial_stride = 2 * (int64_t)max_hot;
+    h->gpartial_stride = (int64_t)max_words;
 
     h->map16 = true;
     for (int64_t g = 0; g < G; ++g)
@@ -320,7 +354,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     SNAP_HIP(hipMalloc(&h->rank_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->coord_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->gdelta, (size_t)(m ? m : 1) * sizeof(float)));
-    SNAP_HIP(hipMalloc(&h->gpartial, (size_t)row_wgs() * (size_t)h->gpartial_stride * sizeof(long long)));
+    SNAP_HIP(hipMalloc(&h->gpartial, (size_t)h->g_row_wgs * (size_t)h->gpartial_stride * sizeof(long long)));
     SNAP_HIP(hipMalloc(&h->ybits, (size_t)(h->n_pad / 8 + 16)));
     SNAP_HIP(hipMalloc(&d_gb, (size_t)(G + 1) * sizeof(int64_t)));
     SNAP_HIP(hipMalloc(&flags, 2 * sizeof(uint32_t)));
@@ -441,22 +475,29 @@ __device__ __forceinline__ void load_floats(const float* p, float (&out)[R]) {
     }
 }
 
+// Scales of a packed word: a loss' <= 2^e in magnitude gets 21 - e fractional bits (times at most 4095
+// rows: below 2^33), a^2 loss'' <= 2^(2e-2) gets 20 - 2e (below 2^30 in total).
+struct PackScales {
+    float g, h;
+};
+
 template <int KIND, bool UNIT, bool SCATTER, bool HIST, typename MAPT>
 __global__ void __launch_bounds__(ROW_TPB)
 k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_prev,
              const float* __restrict__ delta_prev, const MAPT* __restrict__ map_cur,
-             const float* __restrict__ val_cur, int hot, float* __restrict__ v, const float* __restrict__ y,
+             const float* __restrict__ val_cur, int hot, int k64, float* __restrict__ v, const float* __restrict__ y,
              const uint8_t* __restrict__ ybits, int64_t n, long long* __restrict__ partial, int64_t partial_stride,
-             float scale_g, float scale_h, int kd, uint32_t* __restrict__ status) {
+             float scale_g, float scale_h, PackScales ps, int kd, uint32_t* __restrict__ status) {
     constexpr int R = MapTraits<MAPT>::R;
     constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
-    // LDS: fixed-point sums, [0,hot): sum of a loss' * scale_g, [hot,2hot): sum of a^2 loss'' * scale_h,
-    // then the steps of the previous group's first kd ranks (a gather from global memory per row
-    // costs a third of the pass; nearly every row hits one of these)
+    // LDS: fixed-point sums.  Ranks below k64: [rank] sum of a loss' * scale_g, [k64 + rank] sum of
+    // a^2 loss'' * scale_h.  Ranks k64 .. hot-1: one packed word at [k64 + rank] (k64 = hot: none).
+    // Then the steps of the previous group's first kd ranks (a gather from global memory per row
+    // costs a third of the pass; nearly every row hits one of these).
     extern __shared__ unsigned long long hist[];
-    float* dl = reinterpret_cast<float*>(hist + 2 * hot);
+    float* dl = reinterpret_cast<float*>(hist + hot + k64);
     if (HIST)
-        for (int i = threadIdx.x; i < 2 * hot; i += ROW_TPB) hist[i] = 0ull;
+        for (int i = threadIdx.x; i < hot + k64; i += ROW_TPB) hist[i] = 0ull;
     if (SCATTER)
         for (int i = threadIdx.x; i < kd; i += ROW_TPB) dl[i] = delta_prev[i];
     __syncthreads();
@@ -523,10 +564,14 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                             rh0 += rk == 0u ? hh : 0.0f;
                             rh1 += rk == 1u ? hh : 0.0f;
                         }
-                    } else {
+                    } else if (rk < (uint32_t)k64) {
                         atomicAdd(&hist[rk], to_fixed<KIND>(g, scale_g));
                         if (KIND == K_PRIMAL_LOGISTIC)
-                            atomicAdd(&hist[hot + rk], to_fixed<KIND>(hh, scale_h));
+                            atomicAdd(&hist[k64 + rk], to_fixed<KIND>(hh, scale_h));
+                    } else {
+                        const long long word = ((long long)__float2int_rn(g * ps.g) << PACK_H_BITS) +
+                                               (long long)__float2int_rn(hh * ps.h);
+                        atomicAdd(&hist[k64 + rk], (unsigned long long)word);
                     }
                 }
             }
@@ -542,12 +587,12 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             const float rg[2] = {rg0, rg1}, rh[2] = {rh0, rh1};
             for (int t = 0; t < 2 && t < hot; ++t) {
                 atomicAdd(&hist[t], (unsigned long long)__float2ll_rn(rg[t] * scale_g));
-                if (KIND == K_PRIMAL_LOGISTIC) atomicAdd(&hist[hot + t], (unsigned long long)__float2ll_rn(rh[t] * scale_h));
+                if (KIND == K_PRIMAL_LOGISTIC) atomicAdd(&hist[k64 + t], (unsigned long long)__float2ll_rn(rh[t] * scale_h));
             }
         }
         __syncthreads();
         long long* out = partial + (size_t)blockIdx.x * (size_t)partial_stride;
-        for (int i = threadIdx.x; i < 2 * hot; i += ROW_TPB) out[i] = (long long)hist[i];
+        for (int i = threadIdx.x; i < hot + k64; i += ROW_TPB) out[i] = (long long)hist[i];
     }
 }
 
@@ -562,8 +607,8 @@ constexpr int STEP_RANKS = 32, STEP_PARTS = 32;
 // DOTS: no step is taken; the first sum (the coordinate's inner product with loss'(v)) goes to gdot.
 template <int KIND, bool DOTS>
 __global__ void __launch_bounds__(STEP_RANKS * STEP_PARTS)
-k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, int n_wgs, int hot, int n_hot_blocks,
-               double inv_scale_g, double inv_scale_h, const int64_t* __restrict__ ptr,
+k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, int n_wgs, int hot, int k64, int n_hot_blocks,
+               double inv_scale_g, double inv_scale_h, double inv_pack_g, double inv_pack_h, const int64_t* __restrict__ ptr,
                const uint32_t* __restrict__ idx, const float* __restrict__ val, const float* __restrict__ v,
                const float* __restrict__ y, const uint32_t* __restrict__ coord_of, int64_t g0, int64_t group_size,
                float* __restrict__ x, const float* __restrict__ norms, float* __restrict__ delta, StepParams sp,
@@ -599,11 +644,22 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
     const int lr = threadIdx.x % STEP_RANKS, part = threadIdx.x / STEP_RANKS;
     const int64_t rk = (int64_t)blockIdx.x * STEP_RANKS + lr;
     long long Gi = 0, Hi = 0;
+    const bool packed = rk >= k64;              // one word per workgroup holding both sums
     if (rk < hot) {
+        if (!packed) {
 #pragma unroll 8
-        for (int w = part; w < n_wgs; w += STEP_PARTS) {
-            Gi += partial[(size_t)w * partial_stride + rk];
-            if (KIND == K_PRIMAL_LOGISTIC) Hi += partial[(size_t)w * partial_stride + hot + rk];
+            for (int w = part; w < n_wgs; w += STEP_PARTS) {
+                Gi += partial[(size_t)w * partial_stride + rk];
+                if (KIND == K_PRIMAL_LOGISTIC) Hi += partial[(size_t)w * partial_stride + k64 + rk];
+            }
+        } else {
+#pragma unroll 8
+            for (int w = part; w < n_wgs; w += STEP_PARTS) {
+                const long long word = partial[(size_t)w * partial_stride + k64 + rk];
+                const long long hw = word & ((1ll << PACK_H_BITS) - 1);      // the low field is never negative
+                Hi += hw;
+                Gi += (word - hw) >> PACK_H_BITS;
+            }
         }
     }
     sg[part][lr] = Gi;
@@ -618,12 +674,14 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
         Hi += sh[p][lr];
     }
     const int64_t c = coord_of[g0 + rk];
+    const double gsum = (double)Gi * (packed ? inv_pack_g : inv_scale_g);
+    const double hsum = (double)Hi * (packed ? inv_pack_h : inv_scale_h);
     if (DOTS) {
-        gdot[c] = (double)Gi * inv_scale_g;
+        gdot[c] = gsum;
         return;
     }
     float mult;
-    x[c] = take_step<KIND>((double)Gi * inv_scale_g, (double)Hi * inv_scale_h, x[c], norms[c], 0.0f, sp, mult);
+    x[c] = take_step<KIND>(gsum, hsum, x[c], norms[c], 0.0f, sp, mult);
     delta[g0 + rk] = mult;
 }
 
@@ -647,6 +705,7 @@ static int grouped_epoch_kind(snap_handle* h) {
     // Ridge terms a (v - y): 24 fractional bits, 2^39 of range in the 64-bit sum.
     const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ldexpf(1.0f, 30 - h->gscale_exp) : ldexpf(1.0f, 24);
     const float scale_h = ldexpf(1.0f, 30 - 2 * h->gscale_exp);
+    const PackScales ps{ldexpf(1.0f, 21 - h->gscale_exp), ldexpf(1.0f, 20 - 2 * h->gscale_exp)};
     int64_t prev = -1;                              // last non-empty group, whose steps are still to be applied
     const bool prof = h->opt.profile != 0 && h->ev_group != nullptr;
     int n_pass = 0;
@@ -659,30 +718,31 @@ static int grouped_epoch_kind(snap_handle* h) {
         const int64_t g = last ? G : gorder[(size_t)gi];
         const int64_t g0 = last ? 0 : h->gbounds_host[g], sz = last ? 0 : h->gbounds_host[g + 1] - g0;
         if (!last && sz == 0) continue;
-        const int hot = last ? 0 : h->ghot_host[g];
+        const int hot = last ? 0 : h->ghot_host[g], k64 = last ? 0 : h->gk64_host[g];
         const MAPT* maps = (const MAPT*)h->rowmap;
         const MAPT* map_prev = prev >= 0 ? maps + (size_t)prev * h->n_pad : nullptr;
         const float* val_prev = (prev >= 0 && !UNIT) ? h->rowval + (size_t)prev * h->n_pad : nullptr;
         const float* delta_prev = prev >= 0 ? h->gdelta + h->gbounds_host[prev] : nullptr;
         const MAPT* map_cur = last ? nullptr : maps + (size_t)g * h->n_pad;
         const float* val_cur = (last || UNIT) ? nullptr : h->rowval + (size_t)g * h->n_pad;
-        const int kd = prev >= 0 ? (int)std::min<int64_t>(DELTA_LDS, h->gbounds_host[prev + 1] - h->gbounds_host[prev]) : 0;
-        const size_t lds = (size_t)2 * hot * sizeof(unsigned long long) + (size_t)kd * sizeof(float);
+        const int kd = prev >= 0 ? (int)std::min<int64_t>(h->g_kd_max, h->gbounds_host[prev + 1] - h->gbounds_host[prev]) : 0;
+        const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + (size_t)kd * sizeof(float);
+        const dim3 row_grid((unsigned)h->g_row_wgs);
         const bool scatter = prev >= 0, histo = !last && hot > 0;
         if (n > 0 && (scatter || histo)) {
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass], h->compute));
             if (scatter && histo)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, kd, h->status);
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
+                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status);
             else if (scatter)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, 0, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, kd, h->status);
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                   map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, h->v, h->y, h->ybits, n, gpart,
+                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status);
             else
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, kd, h->status);
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
+                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status);
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
             ++n_pass;
         }
@@ -692,9 +752,10 @@ static int grouped_epoch_kind(snap_handle* h) {
         const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
         const int n_cold_blocks = (int)std::min<int64_t>((cold + waves_per_block - 1) / waves_per_block, 8192);
         hipLaunchKernelGGL((k_group_finish<KIND, false>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
-                           dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, row_wgs(), hot,
-                           n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, h->ptr, h->idx, h->val, h->v,
-                           h->y, h->coord_of, g0, sz, h->x, h->norms, h->gdelta, sp, nullptr);
+                           dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
+                           n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, 1.0 / (double)ps.g,
+                           1.0 / (double)ps.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
+                           h->gdelta, sp, nullptr);
         prev = g;
     }
     h->n_row_passes = n_pass;
@@ -711,17 +772,18 @@ static int grouped_dots_kind(snap_handle* h) {
     long long* gpart = (long long*)h->gpartial;
     const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ldexpf(1.0f, 30 - h->gscale_exp) : ldexpf(1.0f, 24);
     const float scale_h = ldexpf(1.0f, 30 - 2 * h->gscale_exp);
+    const PackScales ps{ldexpf(1.0f, 21 - h->gscale_exp), ldexpf(1.0f, 20 - 2 * h->gscale_exp)};
     const MAPT* maps = (const MAPT*)h->rowmap;
     for (int64_t g = 0; g < G; ++g) {
         const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
         if (sz == 0) continue;
-        const int hot = h->ghot_host[g];
+        const int hot = h->ghot_host[g], k64 = h->gk64_host[g];
         if (n > 0 && hot > 0) {
-            const size_t lds = (size_t)2 * hot * sizeof(unsigned long long);
-            hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3(row_wgs()), dim3(ROW_TPB), lds, h->compute,
-                               (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr, maps + (size_t)g * h->n_pad,
-                               UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot, h->v, h->y, h->ybits, n,
-                               gpart, h->gpartial_stride, scale_g, scale_h, 0, h->status);
+            const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long);
+            hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), lds,
+                               h->compute, (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr,
+                               maps + (size_t)g * h->n_pad, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
+                               k64, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale_g, scale_h, ps, 0, h->status);
         }
         const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
         const int64_t cold = sz - hot;
@@ -729,9 +791,10 @@ static int grouped_dots_kind(snap_handle* h) {
         const int n_cold_blocks = (int)std::min<int64_t>((cold + waves_per_block - 1) / waves_per_block, 8192);
         if (n_hot_blocks + n_cold_blocks > 0)
             hipLaunchKernelGGL((k_group_finish<KIND, true>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
-                               dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, row_wgs(), hot,
-                               n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, h->ptr, h->idx, h->val, h->v,
-                               h->y, h->coord_of, g0, sz, h->x, h->norms, h->gdelta, sp, h->gdot);
+                               dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
+                               n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, 1.0 / (double)ps.g,
+                               1.0 / (double)ps.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
+                               h->gdelta, sp, h->gdot);
     }
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
