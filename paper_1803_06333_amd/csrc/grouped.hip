@@ -309,6 +309,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     // packed ranks: two workgroups per compute unit, each with half of the LDS
     h->gpack = h->kind == K_PRIMAL_LOGISTIC && pack_knob();
     h->g_kd_max = h->gpack ? DELTA_LDS / 2 : DELTA_LDS;
+    if (const char* e = getenv("SNAP_DELTA_LDS")) h->g_kd_max = std::max(0, std::min(DELTA_LDS, atoi(e)));   // tuning knob
     h->g_row_wgs = row_wgs_knob() > 0 ? row_wgs_knob() : (h->gpack ? 2 * ROW_WGS_DEFAULT : ROW_WGS_DEFAULT);
     const int lds_budget = (h->gpack ? lds_max / 2 : lds_max) - 1024 - 4 * h->g_kd_max;   // bytes for the sums
     // ranks inside each group: coordinates by decreasing length (ties by index)
