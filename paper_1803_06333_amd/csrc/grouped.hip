@@ -307,7 +307,8 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     int lds_max = 0;
     SNAP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
     // packed ranks: two workgroups per compute unit, each with half of the LDS
-    h->gpack = h->kind == K_PRIMAL_LOGISTIC && pack_knob();
+    // (the ridge loss has one sum per rank to begin with: 8 bytes each, nothing to pack)
+    h->gpack = pack_knob();
     h->g_kd_max = h->gpack ? DELTA_LDS / 2 : DELTA_LDS;
     if (const char* e = getenv("SNAP_DELTA_LDS")) h->g_kd_max = std::max(0, std::min(DELTA_LDS, atoi(e)));   // tuning knob
     h->g_row_wgs = row_wgs_knob() > 0 ? row_wgs_knob() : (h->gpack ? 2 * ROW_WGS_DEFAULT : ROW_WGS_DEFAULT);
@@ -333,7 +334,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         auto rows_of = [&](int r) { return hptr[order[(size_t)r] + 1] - hptr[order[(size_t)r]]; };
         int hot = 0, k64 = 0;
         while (hot < sz && hot < hot_max() && rows_of(hot) >= ROW_WGS_DEFAULT / 2) {
-            const bool two_words = !h->gpack || hot < 2 || rows_of(hot) > PACK_COUNT_MAX;
+            const bool two_words = h->kind == K_PRIMAL_LOGISTIC && (!h->gpack || hot < 2 || rows_of(hot) > PACK_COUNT_MAX);
             if (8 * (hot + 1 + k64 + (two_words ? 1 : 0)) > lds_budget) break;
             k64 += two_words ? 1 : 0;
             ++hot;
@@ -491,8 +492,9 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
              float scale_g, float scale_h, PackScales ps, int kd, uint32_t* __restrict__ status) {
     constexpr int R = MapTraits<MAPT>::R;
     constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
-    // LDS: fixed-point sums.  Ranks below k64: [rank] sum of a loss' * scale_g, [k64 + rank] sum of
-    // a^2 loss'' * scale_h.  Ranks k64 .. hot-1: one packed word at [k64 + rank] (k64 = hot: none).
+    // LDS: fixed-point sums.  Logistic: ranks below k64: [rank] sum of a loss' * scale_g, [k64 + rank]
+    // sum of a^2 loss'' * scale_h; ranks k64 .. hot-1: one packed word at [k64 + rank] (k64 = hot: none).
+    // Ridge: [rank] sum of a loss' * scale_g, k64 = 0.
     // Then the steps of the previous group's first kd ranks (a gather from global memory per row
     // costs a third of the pass; nearly every row hits one of these).
     extern __shared__ unsigned long long hist[];
@@ -565,7 +567,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                             rh0 += rk == 0u ? hh : 0.0f;
                             rh1 += rk == 1u ? hh : 0.0f;
                         }
-                    } else if (rk < (uint32_t)k64) {
+                    } else if (KIND != K_PRIMAL_LOGISTIC || rk < (uint32_t)k64) {
                         atomicAdd(&hist[rk], to_fixed<KIND>(g, scale_g));
                         if (KIND == K_PRIMAL_LOGISTIC)
                             atomicAdd(&hist[k64 + rk], to_fixed<KIND>(hh, scale_h));
@@ -645,7 +647,7 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
     const int lr = threadIdx.x % STEP_RANKS, part = threadIdx.x / STEP_RANKS;
     const int64_t rk = (int64_t)blockIdx.x * STEP_RANKS + lr;
     long long Gi = 0, Hi = 0;
-    const bool packed = rk >= k64;              // one word per workgroup holding both sums
+    const bool packed = KIND == K_PRIMAL_LOGISTIC && rk >= k64;      // one word per workgroup holding both sums
     if (rk < hot) {
         if (!packed) {
 #pragma unroll 8
