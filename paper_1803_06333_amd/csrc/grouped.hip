@@ -310,7 +310,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     // (the ridge loss has one sum per rank to begin with: 8 bytes each, nothing to pack)
     h->gpack = pack_knob();
     h->g_kd_max = h->gpack ? DELTA_LDS / 2 : DELTA_LDS;
-    if (const char* e = getenv("SNAP_DELTA_LDS")) h->g_kd_max = std::max(0, std::min(DELTA_LDS, atoi(e)));   // tuning knob
+    if (const char* e = getenv("SNAP_DELTA_LDS")) h->g_kd_max = std::max(1, std::min(DELTA_LDS, atoi(e)));   // tuning knob
     h->g_row_wgs = row_wgs_knob() > 0 ? row_wgs_knob() : (h->gpack ? 2 * ROW_WGS_DEFAULT : ROW_WGS_DEFAULT);
     const int lds_budget = (h->gpack ? lds_max / 2 : lds_max) - 1024 - 4 * h->g_kd_max;   // bytes for the sums
     // ranks inside each group: coordinates by decreasing length (ties by index)
@@ -525,10 +525,16 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         if (SCATTER) {
             load_ranks(map_prev + r, mp);
             if (!UNIT) load_floats<R>(val_prev + r, ap);
+            // straight-line per row (a wavefront's rows take every path anyway, and each divergent
+            // region costs its exec-mask bookkeeping): the step comes from LDS with a clamped index;
+            // only the rare rank beyond the LDS copy enters a region of its own
 #pragma unroll
-            for (int j = 0; j < R; ++j)
-                if (mp[j] != NONE)
-                    vv[j] += (mp[j] < (uint32_t)kd ? dl[mp[j]] : delta_prev[mp[j]]) * (UNIT ? 1.0f : ap[j]);
+            for (int j = 0; j < R; ++j) {
+                const uint32_t mr = mp[j];
+                float dv = dl[min(mr, (uint32_t)(kd - 1))];
+                if (mr >= (uint32_t)kd && mr != NONE) dv = delta_prev[mr];
+                vv[j] += mr != NONE ? dv * (UNIT ? 1.0f : ap[j]) : 0.0f;
+            }
             if (full) {
 #pragma unroll
                 for (int qq = 0; qq < R / 4; ++qq)
@@ -554,28 +560,31 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             }
 #pragma unroll
             for (int j = 0; j < R; ++j) {
+                // the terms are computed for every row (a row past the end has rank "none", which is
+                // never hot, and v = 0); one region holds the LDS updates
                 const uint32_t rk = mc[j];
-                if (rk < (uint32_t)hot) {          // (a row past the end has rank "none", which is never hot)
-                    if (KIND == K_PRIMAL_LOGISTIC) yy[j] = ((lab >> j) & 1u) ? -1.0f : 1.0f;
-                    float g = 0.0f, hh = 0.0f;
-                    accumulate<KIND>(UNIT ? 1.0f : ac[j], vv[j], yy[j], g, hh);
-                    if (KIND == K_PRIMAL_RIDGE) too_large |= !(fabsf(g) < RIDGE_TERM_LIMIT);
-                    if (rk < 2u) {
-                        rg0 += rk == 0u ? g : 0.0f;
-                        rg1 += rk == 1u ? g : 0.0f;
-                        if (KIND == K_PRIMAL_LOGISTIC) {
-                            rh0 += rk == 0u ? hh : 0.0f;
-                            rh1 += rk == 1u ? hh : 0.0f;
-                        }
-                    } else if (KIND != K_PRIMAL_LOGISTIC || rk < (uint32_t)k64) {
-                        atomicAdd(&hist[rk], to_fixed<KIND>(g, scale_g));
-                        if (KIND == K_PRIMAL_LOGISTIC)
-                            atomicAdd(&hist[k64 + rk], to_fixed<KIND>(hh, scale_h));
-                    } else {
-                        const long long word = ((long long)__float2int_rn(g * ps.g) << PACK_H_BITS) +
-                                               (long long)__float2int_rn(hh * ps.h);
+                if (KIND == K_PRIMAL_LOGISTIC) yy[j] = ((lab >> j) & 1u) ? -1.0f : 1.0f;
+                float g = 0.0f, hh = 0.0f;
+                accumulate<KIND>(UNIT ? 1.0f : ac[j], vv[j], yy[j], g, hh);
+                const bool in = rk < (uint32_t)hot;
+                if (KIND == K_PRIMAL_RIDGE) too_large |= in && !(fabsf(g) < RIDGE_TERM_LIMIT);
+                rg0 += rk == 0u ? g : 0.0f;                    // (hot >= 1 whenever this kernel sums)
+                rg1 += (rk == 1u && in) ? g : 0.0f;
+                if (KIND == K_PRIMAL_LOGISTIC) {
+                    rh0 += rk == 0u ? hh : 0.0f;
+                    rh1 += (rk == 1u && in) ? hh : 0.0f;
+                    // ranks below k64: sum of a^2 loss'' at [k64 + rank] and sum of a loss' at [rank];
+                    // the others: both in one word at [k64 + rank]
+                    const bool two = rk < (uint32_t)k64;
+                    const int gi = __float2int_rn(g * (two ? scale_g : ps.g));
+                    const int hi = __float2int_rn(hh * (two ? scale_h : ps.h));
+                    if (in && rk >= 2u) {
+                        const long long word = (long long)hi + ((long long)(two ? 0 : gi) << PACK_H_BITS);
                         atomicAdd(&hist[k64 + rk], (unsigned long long)word);
+                        if (two) atomicAdd(&hist[rk], (unsigned long long)(long long)gi);
                     }
+                } else if (in && rk >= 2u) {
+                    atomicAdd(&hist[rk], to_fixed<KIND>(g, scale_g));
                 }
             }
         }
