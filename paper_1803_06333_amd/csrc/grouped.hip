@@ -43,17 +43,19 @@ constexpr uint32_t RANK_NONE = 0xFFFFFFFFu;      // row not covered by the group
 // Packed ranks (logistic loss).  With two 8-byte sums per rank and 32 KB of steps the LDS of a compute
 // unit holds one workgroup, 16 wavefronts, and the row pass is short of wavefronts to hide its
 // latencies (measured: two resident workgroups run the same pass 20 % faster).  Both sums of a rank
-// whose coordinate has at most PACK_COUNT_MAX rows fit ONE 64-bit word -- 34 bits for the signed sum
-// of a loss' (21 fractional bits relative to the largest |value|), 30 bits for the sum of a^2 loss''
-// (20 fractional bits); the rounding of the terms averages out over the rows (relative error of a sum
-// about 1e-6 / sqrt(rows)) -- so only the few hundred longest coordinates keep two words.
+// whose coordinate has at most PACK_COUNT_MAX rows fit ONE 64-bit word -- the high half for the signed
+// sum of a loss' (19 fractional bits relative to the largest |value|), the low half for the sum of
+// a^2 loss'' (22 fractional bits), so that a word is put together from two 32-bit conversions without
+// 64-bit arithmetic; the rounding of the terms averages out over the rows (relative error of a sum
+// about 2e-6 / sqrt(rows)) -- so only the few hundred longest coordinates keep two words.  All ranks
+// use these scales (the pass is bound by instruction issue; one set of scales saves selects).
 // That halves the LDS per rank (and the LDS atomics per row) for the rest, and two workgroups fit.
 constexpr int HOT_MAX = 8192;                    // ranks accumulated in LDS
 constexpr int DELTA_LDS = 8192;                  // steps of the previous group kept in LDS (32 KB; 16 KB when packing)
 constexpr int ROW_TPB = 1024;
 constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit (two when packing)
 constexpr int PACK_COUNT_MAX = 4095;             // rows of a coordinate whose two sums share one word
-constexpr int PACK_H_BITS = 30;
+constexpr int PACK_H_BITS = 32;                  // a packed word: sum of a^2 loss'' in the low half, of a loss' in the high half
 static int row_wgs_knob() {
     static const int v = [] {
         const char* e = getenv("SNAP_ROW_WGS");      // tuning knob
@@ -477,8 +479,8 @@ __device__ __forceinline__ void load_floats(const float* p, float (&out)[R]) {
     }
 }
 
-// Scales of a packed word: a loss' <= 2^e in magnitude gets 21 - e fractional bits (times at most 4095
-// rows: below 2^33), a^2 loss'' <= 2^(2e-2) gets 20 - 2e (below 2^30 in total).
+// Scales of the logistic sums: a loss' <= 2^e in magnitude gets 19 - e fractional bits (times at most
+// 4095 rows: below 2^31), a^2 loss'' <= 2^(2e-2) gets 22 - 2e (below 2^32 in total).
 struct PackScales {
     float g, h;
 };
@@ -576,11 +578,12 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                     // ranks below k64: sum of a^2 loss'' at [k64 + rank] and sum of a loss' at [rank];
                     // the others: both in one word at [k64 + rank]
                     const bool two = rk < (uint32_t)k64;
-                    const int gi = __float2int_rn(g * (two ? scale_g : ps.g));
-                    const int hi = __float2int_rn(hh * (two ? scale_h : ps.h));
+                    const int gi = __float2int_rn(g * ps.g);
+                    const int hi = __float2int_rn(hh * ps.h);
                     if (in && rk >= 2u) {
-                        const long long word = (long long)hi + ((long long)(two ? 0 : gi) << PACK_H_BITS);
-                        atomicAdd(&hist[k64 + rk], (unsigned long long)word);
+                        const unsigned long long word =
+                            (unsigned long long)(uint32_t)hi | ((unsigned long long)(uint32_t)(two ? 0 : gi) << PACK_H_BITS);
+                        atomicAdd(&hist[k64 + rk], word);
                         if (two) atomicAdd(&hist[rk], (unsigned long long)(long long)gi);
                     }
                 } else if (in && rk >= 2u) {
@@ -712,12 +715,12 @@ static int grouped_epoch_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
     const int64_t n = h->n, G = h->n_groups;
     long long* gpart = (long long*)h->gpartial;
-    // power-of-two scales (exact in fp32).  Logistic: |a loss'| <= 2^e and a^2 loss'' <= 2^(2e-2), so the
-    // scaled terms stay below 2^30 and the per-wavefront register sums (at most 2^18 rows) below 2^48.
-    // Ridge terms a (v - y): 24 fractional bits, 2^39 of range in the 64-bit sum.
-    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ldexpf(1.0f, 30 - h->gscale_exp) : ldexpf(1.0f, 24);
-    const float scale_h = ldexpf(1.0f, 30 - 2 * h->gscale_exp);
-    const PackScales ps{ldexpf(1.0f, 21 - h->gscale_exp), ldexpf(1.0f, 20 - 2 * h->gscale_exp)};
+    // power-of-two scales (exact in fp32).  Logistic: |a loss'| <= 2^e and a^2 loss'' <= 2^(2e-2), scaled
+    // to 19 resp. 20 bits (see PackScales).  Ridge terms a (v - y): 24 fractional bits, 2^39 of range in
+    // the 64-bit sum.
+    const PackScales ps{ldexpf(1.0f, 19 - h->gscale_exp), ldexpf(1.0f, 22 - 2 * h->gscale_exp)};
+    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ps.g : ldexpf(1.0f, 24);
+    const float scale_h = ps.h;
     int64_t prev = -1;                              // last non-empty group, whose steps are still to be applied
     const bool prof = h->opt.profile != 0 && h->ev_group != nullptr;
     int n_pass = 0;
@@ -782,9 +785,9 @@ static int grouped_dots_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
     const int64_t n = h->n, G = h->n_groups;
     long long* gpart = (long long*)h->gpartial;
-    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ldexpf(1.0f, 30 - h->gscale_exp) : ldexpf(1.0f, 24);
-    const float scale_h = ldexpf(1.0f, 30 - 2 * h->gscale_exp);
-    const PackScales ps{ldexpf(1.0f, 21 - h->gscale_exp), ldexpf(1.0f, 20 - 2 * h->gscale_exp)};
+    const PackScales ps{ldexpf(1.0f, 19 - h->gscale_exp), ldexpf(1.0f, 22 - 2 * h->gscale_exp)};
+    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ps.g : ldexpf(1.0f, 24);
+    const float scale_h = ps.h;
     const MAPT* maps = (const MAPT*)h->rowmap;
     for (int64_t g = 0; g < G; ++g) {
         const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
