@@ -484,6 +484,8 @@ __device__ __forceinline__ void load_floats(const float* p, float (&out)[R]) {
 struct PackScales {
     float g, h;
 };
+constexpr float FIX_MAGIC = 12582912.0f;         // 1.5 * 2^23
+constexpr unsigned long long FIX_BIAS = 0x4B400000ull;   // its bit pattern
 
 template <int KIND, bool UNIT, bool SCATTER, bool HIST, typename MAPT>
 __global__ void __launch_bounds__(ROW_TPB)
@@ -504,7 +506,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
     if (HIST)
         for (int i = threadIdx.x; i < hot + k64; i += ROW_TPB) hist[i] = 0ull;
     if (SCATTER)
-        for (int i = threadIdx.x; i < kd; i += ROW_TPB) dl[i] = delta_prev[i];
+        for (int i = threadIdx.x; i <= kd; i += ROW_TPB) dl[i] = i < kd ? delta_prev[i] : 0.0f;   // [kd]: a zero for the rows without a step
     __syncthreads();
     // the two longest coordinates of a group hold a quarter of its rows: their sums stay in
     // registers (one LDS update per wavefront at the end) instead of colliding in LDS
@@ -528,15 +530,19 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             load_ranks(map_prev + r, mp);
             if (!UNIT) load_floats<R>(val_prev + r, ap);
             // straight-line per row (a wavefront's rows take every path anyway, and each divergent
-            // region costs its exec-mask bookkeeping): the step comes from LDS with a clamped index;
-            // only the rare rank beyond the LDS copy enters a region of its own
+            // region costs its exec-mask bookkeeping): the step comes from LDS with the index clamped
+            // to kd, where a zero sits for the rows that the previous group does not cover; only the
+            // rare rank beyond the LDS copy enters a region of its own
+            float dv[R];
 #pragma unroll
-            for (int j = 0; j < R; ++j) {
-                const uint32_t mr = mp[j];
-                float dv = dl[min(mr, (uint32_t)(kd - 1))];
-                if (mr >= (uint32_t)kd && mr != NONE) dv = delta_prev[mr];
-                vv[j] += mr != NONE ? dv * (UNIT ? 1.0f : ap[j]) : 0.0f;
-            }
+            for (int j = 0; j < R; ++j) dv[j] = dl[min(mp[j], (uint32_t)kd)];
+#pragma unroll
+            for (int j = 0; j < R; ++j) asm("" : "+v"(dv[j]));   // (keeps these LDS reads: merged with the global ones they turn into flat loads)
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+                if (mp[j] >= (uint32_t)kd && mp[j] != NONE) dv[j] = delta_prev[mp[j]];
+#pragma unroll
+            for (int j = 0; j < R; ++j) vv[j] += dv[j] * (UNIT ? 1.0f : ap[j]);
             if (full) {
 #pragma unroll
                 for (int qq = 0; qq < R / 4; ++qq)
@@ -565,26 +571,42 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                 // the terms are computed for every row (a row past the end has rank "none", which is
                 // never hot, and v = 0); one region holds the LDS updates
                 const uint32_t rk = mc[j];
-                if (KIND == K_PRIMAL_LOGISTIC) yy[j] = ((lab >> j) & 1u) ? -1.0f : 1.0f;
-                float g = 0.0f, hh = 0.0f;
-                accumulate<KIND>(UNIT ? 1.0f : ac[j], vv[j], yy[j], g, hh);
+                float g, hh = 0.0f;
+                if (KIND == K_PRIMAL_LOGISTIC) {
+                    // the label as a sign bit: y v by an xor, and the term is summed as y p = -loss'
+                    // (p = sigmoid(-y v) >= 0 takes the sign by an or; the scale below is negative)
+                    const uint32_t sgn = (lab << (31 - j)) & 0x80000000u;
+                    const float p = __builtin_amdgcn_rcpf(1.0f + __expf(__uint_as_float(__float_as_uint(vv[j]) ^ sgn)));
+                    g = __uint_as_float(__float_as_uint(p) | sgn);
+                    hh = p - p * p;                                // loss'' = p (1 - p)
+                    if (!UNIT) {
+                        g *= ac[j];
+                        hh *= ac[j] * ac[j];
+                    }
+                } else {
+                    g = (UNIT ? 1.0f : ac[j]) * (vv[j] - yy[j]);
+                }
                 const bool in = rk < (uint32_t)hot;
                 if (KIND == K_PRIMAL_RIDGE) too_large |= in && !(fabsf(g) < RIDGE_TERM_LIMIT);
-                rg0 += rk == 0u ? g : 0.0f;                    // (hot >= 1 whenever this kernel sums)
-                rg1 += (rk == 1u && in) ? g : 0.0f;
+                // register ranks: indicator times term (two selects and an fma per sum instead of
+                // a select and an add each; rank 1 is summed even when it is not hot, and then unused)
+                const float m0 = rk == 0u ? 1.0f : 0.0f, m1 = rk == 1u ? 1.0f : 0.0f;
+                rg0 = fmaf(m0, g, rg0);
+                rg1 = fmaf(m1, g, rg1);
                 if (KIND == K_PRIMAL_LOGISTIC) {
-                    rh0 += rk == 0u ? hh : 0.0f;
-                    rh1 += (rk == 1u && in) ? hh : 0.0f;
-                    // ranks below k64: sum of a^2 loss'' at [k64 + rank] and sum of a loss' at [rank];
-                    // the others: both in one word at [k64 + rank]
-                    const bool two = rk < (uint32_t)k64;
-                    const int gi = __float2int_rn(g * ps.g);
-                    const int hi = __float2int_rn(hh * ps.h);
+                    rh0 = fmaf(m0, hh, rh0);
+                    rh1 = fmaf(m1, hh, rh1);
                     if (in && rk >= 2u) {
-                        const unsigned long long word =
-                            (unsigned long long)(uint32_t)hi | ((unsigned long long)(uint32_t)(two ? 0 : gi) << PACK_H_BITS);
-                        atomicAdd(&hist[k64 + rk], word);
-                        if (two) atomicAdd(&hist[rk], (unsigned long long)(long long)gi);
+                        // fixed point by the rounding of an addition: the low mantissa bits of
+                        // x + 1.5 * 2^23 hold round(x) for |x| < 2^22; the constant's bit pattern stays
+                        // in every term and is taken out per coordinate, times its row count, by the
+                        // finishing kernel.  Ranks below k64: sum of a^2 loss'' at [k64 + rank] and sum
+                        // of a loss' at [rank]; the others: both in one word at [k64 + rank].
+                        const uint32_t gb = __float_as_uint(fmaf(g, -ps.g, FIX_MAGIC));
+                        const uint32_t hb = __float_as_uint(fmaf(hh, ps.h, FIX_MAGIC));
+                        const bool two = rk < (uint32_t)k64;
+                        atomicAdd(&hist[k64 + rk], (unsigned long long)hb | ((unsigned long long)(two ? 0u : gb) << PACK_H_BITS));
+                        if (two) atomicAdd(&hist[rk], (unsigned long long)gb);
                     }
                 } else if (in && rk >= 2u) {
                     atomicAdd(&hist[rk], to_fixed<KIND>(g, scale_g));
@@ -601,7 +623,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         if ((threadIdx.x & (WAVE - 1)) == 0) {
             const float rg[2] = {rg0, rg1}, rh[2] = {rh0, rh1};
             for (int t = 0; t < 2 && t < hot; ++t) {
-                atomicAdd(&hist[t], (unsigned long long)__float2ll_rn(rg[t] * scale_g));
+                atomicAdd(&hist[t], (unsigned long long)__float2ll_rn(rg[t] * (KIND == K_PRIMAL_LOGISTIC ? -scale_g : scale_g)));
                 if (KIND == K_PRIMAL_LOGISTIC) atomicAdd(&hist[k64 + t], (unsigned long long)__float2ll_rn(rh[t] * scale_h));
             }
         }
@@ -669,12 +691,7 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
             }
         } else {
 #pragma unroll 8
-            for (int w = part; w < n_wgs; w += STEP_PARTS) {
-                const long long word = partial[(size_t)w * partial_stride + k64 + rk];
-                const long long hw = word & ((1ll << PACK_H_BITS) - 1);      // the low field is never negative
-                Hi += hw;
-                Gi += (word - hw) >> PACK_H_BITS;
-            }
+            for (int w = part; w < n_wgs; w += STEP_PARTS) Gi += partial[(size_t)w * partial_stride + k64 + rk];   // whole words, modulo 2^64
         }
     }
     sg[part][lr] = Gi;
@@ -689,6 +706,19 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
         Hi += sh[p][lr];
     }
     const int64_t c = coord_of[g0 + rk];
+    if (KIND == K_PRIMAL_LOGISTIC && rk >= 2) {
+        // every term of these ranks carries the bit pattern of the rounding constant (the ranks 0 and 1
+        // are summed in registers by the row pass and converted without it)
+        const unsigned long long bias = (unsigned long long)(ptr[c + 1] - ptr[c]) * FIX_BIAS;
+        if (packed) {
+            const unsigned long long word = (unsigned long long)Gi - bias - (bias << PACK_H_BITS);
+            Hi = (long long)(word & 0xFFFFFFFFull);                           // the low field is never negative
+            Gi = (long long)(word - (unsigned long long)Hi) >> PACK_H_BITS;
+        } else {
+            Gi = (long long)((unsigned long long)Gi - bias);
+            Hi = (long long)((unsigned long long)Hi - bias);
+        }
+    }
     const double gsum = (double)Gi * (packed ? inv_pack_g : inv_scale_g);
     const double hsum = (double)Hi * (packed ? inv_pack_h : inv_scale_h);
     if (DOTS) {
@@ -741,7 +771,7 @@ static int grouped_epoch_kind(snap_handle* h) {
         const MAPT* map_cur = last ? nullptr : maps + (size_t)g * h->n_pad;
         const float* val_cur = (last || UNIT) ? nullptr : h->rowval + (size_t)g * h->n_pad;
         const int kd = prev >= 0 ? (int)std::min<int64_t>(h->g_kd_max, h->gbounds_host[prev + 1] - h->gbounds_host[prev]) : 0;
-        const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + (size_t)kd * sizeof(float);
+        const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + (size_t)(kd + 1) * sizeof(float);
         const dim3 row_grid((unsigned)h->g_row_wgs);
         const bool scatter = prev >= 0, histo = !last && hot > 0;
         if (n > 0 && (scatter || histo)) {
