@@ -458,15 +458,15 @@ __device__ __forceinline__ unsigned long long to_fixed(float x, float scale) {
     return (unsigned long long)__float2ll_rn(x * scale);
 }
 
+// One 128-bit load of map entries (non-temporal: the maps are read once per pass and should not push the
+// shared vector out of the last-level cache), and its unpacking into ranks.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void load_ranks(const uint16_t* p, uint32_t (&out)[8]) {
-    const u32x4 u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+__device__ __forceinline__ u32x4 load_map(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+__device__ __forceinline__ void unpack_ranks(const uint16_t*, u32x4 u, uint32_t (&out)[8]) {
     out[0] = u.x & 0xFFFFu; out[1] = u.x >> 16; out[2] = u.y & 0xFFFFu; out[3] = u.y >> 16;
     out[4] = u.z & 0xFFFFu; out[5] = u.z >> 16; out[6] = u.w & 0xFFFFu; out[7] = u.w >> 16;
 }
-
-__device__ __forceinline__ void load_ranks(const uint32_t* p, uint32_t (&out)[4]) {
-    const uint4 u = *reinterpret_cast<const uint4*>(p);
+__device__ __forceinline__ void unpack_ranks(const uint32_t*, u32x4 u, uint32_t (&out)[4]) {
     out[0] = u.x; out[1] = u.y; out[2] = u.z; out[3] = u.w;
 }
 
@@ -526,9 +526,21 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
 #pragma unroll
             for (int j = 0; j < R; ++j) vv[j] = r + j < n ? v[r + j] : 0.0f;
         }
+        // every load of the iteration is issued here, ahead of the first wait (the pass is bound by its
+        // chains of dependent loads; left behind the branches below, the current group's map would be
+        // fetched only after the store of the shared vector)
+        u32x4 raw_prev = {0u, 0u, 0u, 0u}, raw_cur = {0u, 0u, 0u, 0u};
+        uint32_t lab = 0;
         if (SCATTER) {
-            load_ranks(map_prev + r, mp);
+            raw_prev = load_map(map_prev + r);
             if (!UNIT) load_floats<R>(val_prev + r, ap);
+        }
+        if (HIST) {
+            raw_cur = load_map(map_cur + r);
+            if (KIND == K_PRIMAL_LOGISTIC) lab = (uint32_t)ybits[r >> 3] >> (r & 7);
+        }
+        if (SCATTER) {
+            unpack_ranks(map_prev, raw_prev, mp);
             // straight-line per row (a wavefront's rows take every path anyway, and each divergent
             // region costs its exec-mask bookkeeping): the step comes from LDS with the index clamped
             // to kd, where a zero sits for the rows that the previous group does not cover; only the
@@ -555,16 +567,15 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             }
         }
         if (HIST) {
-            load_ranks(map_cur + r, mc);
+            unpack_ranks(map_cur, raw_cur, mc);
             if (!UNIT) load_floats<R>(val_cur + r, ac);
-            uint32_t lab = 0;
-            if (KIND == K_PRIMAL_LOGISTIC) {
-                lab = (uint32_t)ybits[r >> 3] >> (r & 7);
-            } else if (full) {
-                load_floats<R>(y + r, yy);
-            } else {
+            if (KIND != K_PRIMAL_LOGISTIC) {
+                if (full) {
+                    load_floats<R>(y + r, yy);
+                } else {
 #pragma unroll
-                for (int j = 0; j < R; ++j) yy[j] = r + j < n ? y[r + j] : 0.0f;
+                    for (int j = 0; j < R; ++j) yy[j] = r + j < n ? y[r + j] : 0.0f;
+                }
             }
 #pragma unroll
             for (int j = 0; j < R; ++j) {
