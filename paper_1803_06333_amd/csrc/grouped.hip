@@ -539,6 +539,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             raw_cur = load_map(map_cur + r);
             if (KIND == K_PRIMAL_LOGISTIC) lab = (uint32_t)ybits[r >> 3] >> (r & 7);
         }
+        __builtin_amdgcn_sched_barrier(0);         // (nothing moves across: the loads above stay ahead of the first wait)
         if (SCATTER) {
             unpack_ranks(map_prev, raw_prev, mp);
             // straight-line per row (a wavefront's rows take every path anyway, and each divergent
