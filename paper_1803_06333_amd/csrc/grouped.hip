@@ -40,20 +40,30 @@ constexpr uint32_t RANK_NONE = 0xFFFFFFFFu;      // row not covered by the group
 // bound by instruction issue as much as by bandwidth): 24 fractional bits relative to the largest
 // |value|, the fp32 precision of the term itself; the 64-bit sum cannot overflow.
 //
-// Packed ranks (logistic loss).  With two 8-byte sums per rank and 32 KB of steps the LDS of a compute
-// unit holds one workgroup, 16 wavefronts, and the row pass is short of wavefronts to hide its
-// latencies (measured: two resident workgroups run the same pass 20 % faster).  Both sums of a rank
+// Packed ranks (logistic loss).  LDS capacity decides how many coordinates of a group are hot, and a
+// row of a coordinate that is not costs ten times a row of one that is (a whole cache line fetched for
+// its entry of the shared vector in the finishing kernel, a gather of its step in the next row pass).
+// Both sums of a rank
 // whose coordinate has at most PACK_COUNT_MAX rows fit ONE 64-bit word -- the high half for the signed
 // sum of a loss' (19 fractional bits relative to the largest |value|), the low half for the sum of
 // a^2 loss'' (22 fractional bits), so that a word is put together from two 32-bit conversions without
 // 64-bit arithmetic; the rounding of the terms averages out over the rows (relative error of a sum
 // about 2e-6 / sqrt(rows)) -- so only the few hundred longest coordinates keep two words.  All ranks
-// use these scales (the pass is bound by instruction issue; one set of scales saves selects).
-// That halves the LDS per rank (and the LDS atomics per row) for the rest, and two workgroups fit.
-constexpr int HOT_MAX = 8192;                    // ranks accumulated in LDS
-constexpr int DELTA_LDS = 8192;                  // steps of the previous group kept in LDS (32 KB; 16 KB when packing)
+// use these scales (one set of scales saves selects).  That halves the LDS per rank (and the LDS atomics
+// per row) for the rest.
+//
+// One workgroup of 1024 threads per compute unit with all of its LDS: 14336 hot ranks (packed) and 8192
+// steps of the previous group.  Two workgroups per unit with half the tables each used to run the pass
+// 20 % faster while it was bound by instruction issue; since it no longer is, the pass runs as fast
+// with 16 wavefronts per unit, and the larger tables take a tenth off the epoch (click-log workload:
+// 5.84 -> 5.19 ms; 16384 ranks + 4096 steps: 5.33, 12288 + 12288: 5.20).
+constexpr int HOT_MAX = 16384;                   // most ranks accumulated in LDS (tuning knob's ceiling)
+constexpr int HOT_DEFAULT = 14336;
+constexpr int HOT_MIN_ROWS = 32;                 // a rank is worth an LDS slot while its coordinate has that many rows
+constexpr int DELTA_LDS = 16384;                 // most steps of the previous group kept in LDS (tuning knob's ceiling)
+constexpr int DELTA_DEFAULT = 8192;
 constexpr int ROW_TPB = 1024;
-constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit (two when packing)
+constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit
 constexpr int PACK_COUNT_MAX = 4095;             // rows of a coordinate whose two sums share one word
 constexpr int PACK_H_BITS = 32;                  // a packed word: sum of a^2 loss'' in the low half, of a loss' in the high half
 static int row_wgs_knob() {
@@ -73,7 +83,21 @@ static bool pack_knob() {
 static int hot_max() {
     static const int v = [] {
         const char* e = getenv("SNAP_HOT_MAX");      // tuning knob
-        return e ? std::max(4, std::min(HOT_MAX, atoi(e))) : HOT_MAX;
+        return e ? std::max(4, std::min(HOT_MAX, atoi(e))) : HOT_DEFAULT;
+    }();
+    return v;
+}
+static int hot_min_rows() {
+    static const int v = [] {
+        const char* e = getenv("SNAP_HOT_ROWS");     // tuning knob
+        return e ? std::max(1, atoi(e)) : HOT_MIN_ROWS;
+    }();
+    return v;
+}
+static int wgs_per_cu() {
+    static const int v = [] {
+        const char* e = getenv("SNAP_WGS_PER_CU");   // tuning knob: 2 = two workgroups per compute unit, half the LDS each
+        return (e && e[0] == '2') ? 2 : 1;
     }();
     return v;
 }
@@ -308,13 +332,12 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
 
     int lds_max = 0;
     SNAP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device));
-    // packed ranks: two workgroups per compute unit, each with half of the LDS
     // (the ridge loss has one sum per rank to begin with: 8 bytes each, nothing to pack)
     h->gpack = pack_knob();
-    h->g_kd_max = h->gpack ? DELTA_LDS / 2 : DELTA_LDS;
+    h->g_kd_max = DELTA_DEFAULT / wgs_per_cu();
     if (const char* e = getenv("SNAP_DELTA_LDS")) h->g_kd_max = std::max(1, std::min(DELTA_LDS, atoi(e)));   // tuning knob
-    h->g_row_wgs = row_wgs_knob() > 0 ? row_wgs_knob() : (h->gpack ? 2 * ROW_WGS_DEFAULT : ROW_WGS_DEFAULT);
-    const int lds_budget = (h->gpack ? lds_max / 2 : lds_max) - 1024 - 4 * h->g_kd_max;   // bytes for the sums
+    h->g_row_wgs = row_wgs_knob() > 0 ? row_wgs_knob() : wgs_per_cu() * ROW_WGS_DEFAULT;
+    const int lds_budget = lds_max / wgs_per_cu() - 1024 - 4 * h->g_kd_max;   // bytes for the sums
     // ranks inside each group: coordinates by decreasing length (ties by index)
     std::vector<uint32_t> rank_of((size_t)m), coord_of((size_t)m);
     int max_words = 2;
@@ -329,13 +352,13 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
             rank_of[(size_t)order[(size_t)r]] = (uint32_t)r;
             coord_of[(size_t)(c0 + r)] = (uint32_t)order[(size_t)r];
         }
-        // hot ranks: accumulated in LDS by the row pass; a rank is worth a slot while its
-        // coordinate is long enough to be hit by most workgroups
+        // hot ranks: accumulated in LDS by the row pass; a rank is worth a slot (and its share of
+        // every workgroup's partial array) while its coordinate has a few dozen rows
         // ... and of those, the first k64 keep two 64-bit words (too many rows for a packed word; ranks 0
         // and 1, which the row pass sums in registers, always do), the others one
         auto rows_of = [&](int r) { return hptr[order[(size_t)r] + 1] - hptr[order[(size_t)r]]; };
         int hot = 0, k64 = 0;
-        while (hot < sz && hot < hot_max() && rows_of(hot) >= ROW_WGS_DEFAULT / 2) {
+        while (hot < sz && hot < hot_max() && rows_of(hot) >= hot_min_rows()) {
             const bool two_words = h->kind == K_PRIMAL_LOGISTIC && (!h->gpack || hot < 2 || rows_of(hot) > PACK_COUNT_MAX);
             if (8 * (hot + 1 + k64 + (two_words ? 1 : 0)) > lds_budget) break;
             k64 += two_words ? 1 : 0;
