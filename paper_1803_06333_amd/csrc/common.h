@@ -154,6 +154,13 @@ struct snap_handle {
     uint32_t* coord_of = nullptr;     // [m] coordinate at (group start + rank)
     float* gdelta = nullptr;          // [m] step of (group start + rank), read by the next row pass
     void* gpartial = nullptr;         // [row-pass workgroups][2*hot] per-workgroup partial sums (int64 fixed point)
+    // short coordinates of a group: the row pass writes the shared-vector entries of their rows, densely,
+    // in the order in which it visits them; the finishing kernel gathers from that small buffer
+    uint8_t* gcompact_host = nullptr; // [n_groups] 1 when the group's short coordinates are handled that way
+    uint32_t* gwbase = nullptr;       // [n_groups][row-pass wavefronts] first buffer position of the wavefront
+    uint32_t* gcidx = nullptr;        // per nonzero of a short coordinate: buffer position of its row (| label bit)
+    int64_t* gcptr = nullptr;         // [m+1] start in gcidx of (group start + rank); empty for the other ranks
+    float* gcbuf = nullptr;           // [largest count over the groups] entries of the shared vector (ridge: minus label)
     int gscale_exp = 0;               // largest |value| <= 2^gscale_exp
     int64_t gpartial_stride = 0;
     hipEvent_t* ev_group = nullptr;   // profile: begin/end of every row pass

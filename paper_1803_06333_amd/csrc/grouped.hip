@@ -63,43 +63,34 @@ constexpr int HOT_MIN_ROWS = 32;                 // a rank is worth an LDS slot 
 constexpr int DELTA_LDS = 16384;                 // most steps of the previous group kept in LDS (tuning knob's ceiling)
 constexpr int DELTA_DEFAULT = 8192;
 constexpr int ROW_TPB = 1024;
+constexpr int COLD_RING = 128;                   // entries per wavefront staged in LDS on their way to the short coordinates' buffer
 constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit
 constexpr int PACK_COUNT_MAX = 4095;             // rows of a coordinate whose two sums share one word
 constexpr int PACK_H_BITS = 32;                  // a packed word: sum of a^2 loss'' in the low half, of a loss' in the high half
+// Tuning knobs (environment variables), read when a handle is created.
 static int row_wgs_knob() {
-    static const int v = [] {
-        const char* e = getenv("SNAP_ROW_WGS");      // tuning knob
-        return e ? std::max(1, atoi(e)) : 0;
-    }();
-    return v;
+    const char* e = getenv("SNAP_ROW_WGS");
+    return e ? std::max(1, atoi(e)) : 0;
 }
 static bool pack_knob() {
-    static const bool v = [] {
-        const char* e = getenv("SNAP_PACK");         // tuning knob: 0 switches the packed ranks off
-        return !(e && e[0] == '0');
-    }();
-    return v;
+    const char* e = getenv("SNAP_PACK");             // 0 switches the packed ranks off
+    return !(e && e[0] == '0');
+}
+static bool compact_knob() {
+    const char* e = getenv("SNAP_COMPACT");          // 0 switches the dense buffer of the short coordinates off
+    return !(e && e[0] == '0');
 }
 static int hot_max() {
-    static const int v = [] {
-        const char* e = getenv("SNAP_HOT_MAX");      // tuning knob
-        return e ? std::max(4, std::min(HOT_MAX, atoi(e))) : HOT_DEFAULT;
-    }();
-    return v;
+    const char* e = getenv("SNAP_HOT_MAX");
+    return e ? std::max(4, std::min(HOT_MAX, atoi(e))) : HOT_DEFAULT;
 }
 static int hot_min_rows() {
-    static const int v = [] {
-        const char* e = getenv("SNAP_HOT_ROWS");     // tuning knob
-        return e ? std::max(1, atoi(e)) : HOT_MIN_ROWS;
-    }();
-    return v;
+    const char* e = getenv("SNAP_HOT_ROWS");
+    return e ? std::max(1, atoi(e)) : HOT_MIN_ROWS;
 }
 static int wgs_per_cu() {
-    static const int v = [] {
-        const char* e = getenv("SNAP_WGS_PER_CU");   // tuning knob: 2 = two workgroups per compute unit, half the LDS each
-        return (e && e[0] == '2') ? 2 : 1;
-    }();
-    return v;
+    const char* e = getenv("SNAP_WGS_PER_CU");       // 2 = two workgroups per compute unit, half the LDS each
+    return (e && e[0] == '2') ? 2 : 1;
 }
 
 // ---- creation --------------------------------------------------------------------------------------
@@ -181,6 +172,15 @@ void grouped_free(snap_handle* h) {
     delete[] h->gbounds_host;
     delete[] h->ghot_host;
     delete[] h->gk64_host;
+    delete[] h->gcompact_host;
+    h->gcompact_host = nullptr;
+    (void)hipFree(h->gwbase);
+    (void)hipFree(h->gcidx);
+    (void)hipFree(h->gcptr);
+    (void)hipFree(h->gcbuf);
+    h->gwbase = h->gcidx = nullptr;
+    h->gcptr = nullptr;
+    h->gcbuf = nullptr;
     h->gbounds_host = nullptr;
     h->ghot_host = nullptr;
     h->gk64_host = nullptr;
@@ -308,6 +308,8 @@ int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bou
     return done(SNAP_OK);
 }
 
+static int cold_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>& coord_of);
+
 int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_t G) {
     const int64_t m = h->m, n = h->n;
     if (h->form != SNAP_PRIMAL || h->dense || h->streaming) {
@@ -337,7 +339,9 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     h->g_kd_max = DELTA_DEFAULT / wgs_per_cu();
     if (const char* e = getenv("SNAP_DELTA_LDS")) h->g_kd_max = std::max(1, std::min(DELTA_LDS, atoi(e)));   // tuning knob
     h->g_row_wgs = row_wgs_knob() > 0 ? row_wgs_knob() : wgs_per_cu() * ROW_WGS_DEFAULT;
-    const int lds_budget = lds_max / wgs_per_cu() - 1024 - 4 * h->g_kd_max;   // bytes for the sums
+    const int hot_cap = hot_max(), min_rows = hot_min_rows();
+    const int ring_bytes = compact_knob() ? (ROW_TPB / WAVE) * COLD_RING * (int)sizeof(float) : 0;
+    const int lds_budget = lds_max / wgs_per_cu() - 1024 - 4 * h->g_kd_max - ring_bytes;   // bytes for the sums
     // ranks inside each group: coordinates by decreasing length (ties by index)
     std::vector<uint32_t> rank_of((size_t)m), coord_of((size_t)m);
     int max_words = 2;
@@ -358,7 +362,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         // and 1, which the row pass sums in registers, always do), the others one
         auto rows_of = [&](int r) { return hptr[order[(size_t)r] + 1] - hptr[order[(size_t)r]]; };
         int hot = 0, k64 = 0;
-        while (hot < sz && hot < hot_max() && rows_of(hot) >= hot_min_rows()) {
+        while (hot < sz && hot < hot_cap && rows_of(hot) >= min_rows) {
             const bool two_words = h->kind == K_PRIMAL_LOGISTIC && (!h->gpack || hot < 2 || rows_of(hot) > PACK_COUNT_MAX);
             if (8 * (hot + 1 + k64 + (two_words ? 1 : 0)) > lds_budget) break;
             k64 += two_words ? 1 : 0;
@@ -457,6 +461,8 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
             h->g_hot_nnz += hptr[c + 1] - hptr[c];
         }
     }
+    rc = cold_setup(h, hptr, coord_of);
+    if (rc != SNAP_OK) return rc;
     h->grouped = true;
     return SNAP_OK;
 }
@@ -502,6 +508,166 @@ __device__ __forceinline__ void load_floats(const float* p, float (&out)[R]) {
     }
 }
 
+// ---- short coordinates: a dense buffer of their rows' shared-vector entries ------------------------------
+// A coordinate too short for an LDS slot takes its sums column-wise in the finishing kernel.  Gathering
+// its rows' entries straight from the shared vector fetches a whole cache line per nonzero (the rows of
+// all short coordinates of a group are a few percent of the rows, about one per line).  Instead the row
+// pass, which streams the shared vector anyway, writes the entries of these rows densely into a small
+// buffer, in the order in which it visits them -- workgroup, wavefront, iteration, row of the thread's
+// pack, lane -- and the finishing kernel gathers from that buffer (a few MB, served by the L2).  The
+// order is fixed by the launch shape, so the buffer position of every row is found once, at creation, by
+// two passes that mirror the row pass: one counts per wavefront, one (after a prefix sum on the host)
+// numbers the rows.
+__device__ __forceinline__ uint32_t cold_slot(bool cold, uint32_t& run) {
+    const unsigned long long mask = __builtin_amdgcn_ballot_w64(cold);
+    const uint32_t pos = run + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+    run += (uint32_t)__popcll(mask);
+    return pos;
+}
+
+// WRITE = false: slots[wavefront] <- number of rows with a rank >= hot; WRITE = true: slots holds the
+// first position of every wavefront and rowpos[row] <- position, for those rows.
+template <typename MAPT, bool WRITE>
+__global__ void __launch_bounds__(ROW_TPB)
+k_cold_rows(const MAPT* __restrict__ map, int hot, int64_t n, uint32_t* __restrict__ slots, uint32_t* __restrict__ rowpos) {
+    constexpr int R = MapTraits<MAPT>::R;
+    constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
+    const int wave = (int)blockIdx.x * (ROW_TPB / WAVE) + (int)threadIdx.x / WAVE;
+    uint32_t run = WRITE ? slots[wave] : 0u;
+    const int64_t packs = (n + R - 1) / R;                     // (the same split of the rows as in the row pass)
+    const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
+    const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
+    for (int64_t q = q0 + threadIdx.x; q < q1; q += ROW_TPB) {
+        uint32_t mc[R];
+        unpack_ranks(map, load_map(map + R * q), mc);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const bool cold = mc[j] >= (uint32_t)hot && mc[j] != NONE;
+            const uint32_t pos = cold_slot(cold, run);
+            if (WRITE && cold) rowpos[R * q + j] = pos;
+        }
+    }
+    // (the first lane holds the wavefront's lowest pack: no lane runs more iterations)
+    if (!WRITE && (threadIdx.x & (WAVE - 1)) == 0) slots[wave] = run;
+}
+
+// cidx[start of the rank + i] <- buffer position of the row of the coordinate's i-th nonzero (the label
+// bit of the row index, when there is one, is carried along); one wavefront per coordinate.
+__global__ void __launch_bounds__(256)
+k_cold_index(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const uint32_t* __restrict__ coord_of,
+             const int64_t* __restrict__ cptr, int64_t g0, int hot, int64_t group_size, uint32_t label_mask,
+             const uint32_t* __restrict__ rowpos, uint32_t* __restrict__ cidx) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
+    for (int64_t rk = hot + wave0; rk < group_size; rk += nwaves) {
+        const int64_t c = coord_of[g0 + rk], p0 = ptr[c], len = ptr[c + 1] - p0, k0 = cptr[g0 + rk];
+        for (int64_t i = lane; i < len; i += WAVE) {
+            const uint32_t e = idx[p0 + i];
+            cidx[k0 + i] = rowpos[e & ~label_mask] | (e & label_mask);
+        }
+    }
+}
+
+template <typename MAPT>
+static int cold_setup_maps(snap_handle* h, const std::vector<int64_t>& cold_rows, const std::vector<int64_t>& cptr, int64_t total) {
+    const int64_t G = h->n_groups, m = h->m, n = h->n;
+    const int nwaves = h->g_row_wgs * (ROW_TPB / WAVE);
+    const MAPT* maps = (const MAPT*)h->rowmap;
+    const int64_t most = *std::max_element(cold_rows.begin(), cold_rows.end());
+    uint32_t* rowpos = nullptr;
+    auto fail = [&](int rc) {
+        (void)hipFree(rowpos);
+        return rc;
+    };
+#define C_HIP(call)                                                                \
+    do {                                                                           \
+        hipError_t e_ = (call);                                                    \
+        if (e_ != hipSuccess) return fail(hip_fail(e_, #call, __FILE__, __LINE__)); \
+    } while (0)
+    C_HIP(hipMalloc(&h->gwbase, (size_t)G * (size_t)nwaves * sizeof(uint32_t)));
+    C_HIP(hipMalloc(&h->gcptr, (size_t)(m + 1) * sizeof(int64_t)));
+    C_HIP(hipMalloc(&h->gcidx, (size_t)total * sizeof(uint32_t)));
+    C_HIP(hipMalloc(&h->gcbuf, (size_t)most * sizeof(float)));
+    C_HIP(hipMalloc(&rowpos, (size_t)h->n_pad * sizeof(uint32_t)));
+    C_HIP(hipMemcpyAsync(h->gcptr, cptr.data(), (size_t)(m + 1) * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
+    int rc = fill_zero(h->gwbase, (size_t)G * (size_t)nwaves * sizeof(uint32_t), h->compute);
+    if (rc == SNAP_OK) rc = fill_zero(rowpos, (size_t)h->n_pad * sizeof(uint32_t), h->compute);   // (every entry a valid position)
+    if (rc != SNAP_OK) return fail(rc);
+    for (int64_t g = 0; g < G; ++g)
+        if (h->gcompact_host[g])
+            hipLaunchKernelGGL((k_cold_rows<MAPT, false>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), 0, h->compute,
+                               maps + (size_t)g * h->n_pad, h->ghot_host[g], n, h->gwbase + (size_t)g * nwaves, (uint32_t*)nullptr);
+    C_HIP(hipGetLastError());
+    std::vector<uint32_t> slots((size_t)G * (size_t)nwaves);
+    C_HIP(hipMemcpyAsync(slots.data(), h->gwbase, slots.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+    C_HIP(hipStreamSynchronize(h->compute));
+    for (int64_t g = 0; g < G; ++g) {
+        if (!h->gcompact_host[g]) continue;
+        uint64_t sum = 0;
+        for (int w = 0; w < nwaves; ++w) {
+            uint32_t& sl = slots[(size_t)g * nwaves + w];
+            const uint32_t count = sl;
+            sl = (uint32_t)sum;
+            sum += count;
+        }
+        if ((int64_t)sum != cold_rows[(size_t)g]) {          // the row maps and the column lengths disagree
+            set_error("internal error: the rows of the short coordinates do not add up");
+            return fail(SNAP_ESTATE);
+        }
+    }
+    C_HIP(hipMemcpyAsync(h->gwbase, slots.data(), slots.size() * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
+    const uint32_t label_mask = h->kind == K_PRIMAL_LOGISTIC ? LABEL_BIT : 0u;
+    for (int64_t g = 0; g < G; ++g) {
+        if (!h->gcompact_host[g]) continue;
+        const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
+        const int hot = h->ghot_host[g];
+        hipLaunchKernelGGL((k_cold_rows<MAPT, true>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), 0, h->compute,
+                           maps + (size_t)g * h->n_pad, hot, n, h->gwbase + (size_t)g * nwaves, rowpos);
+        const int blocks = (int)std::min<int64_t>((sz - hot + 3) / 4, 16384);
+        hipLaunchKernelGGL(k_cold_index, dim3((unsigned)blocks), dim3(256), 0, h->compute, h->ptr, h->idx, h->coord_of, h->gcptr, g0,
+                           hot, sz, label_mask, rowpos, h->gcidx);
+    }
+    C_HIP(hipGetLastError());
+    C_HIP(hipStreamSynchronize(h->compute));
+#undef C_HIP
+    (void)hipFree(rowpos);
+    return SNAP_OK;
+}
+
+static int cold_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>& coord_of) {
+    const int64_t G = h->n_groups, m = h->m;
+    h->gcompact_host = new (std::nothrow) uint8_t[(size_t)G]();
+    if (!h->gcompact_host) return SNAP_ENOMEM;
+    if (!compact_knob() || h->n == 0) return SNAP_OK;
+    // start in the index array of every (group start + rank); only the ranks behind the hot ones of a
+    // group that has hot ranks (whose row pass computes sums at all) own a stretch of it
+    std::vector<int64_t> cptr((size_t)m + 1, 0), cold_rows((size_t)G, 0);
+    int64_t total = 0;
+    for (int64_t g = 0; g < G; ++g) {
+        const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
+        const int hot = h->ghot_host[g];
+        for (int64_t r = 0; r < sz; ++r) {
+            cptr[(size_t)(g0 + r)] = total;
+            if (hot > 0 && r >= hot) {
+                const int64_t c = coord_of[(size_t)(g0 + r)];
+                total += hptr[c + 1] - hptr[c];
+                cold_rows[(size_t)g] += hptr[c + 1] - hptr[c];
+            }
+        }
+        h->gcompact_host[g] = cold_rows[(size_t)g] > 0;
+    }
+    cptr[(size_t)m] = total;
+    if (total == 0) return SNAP_OK;
+    size_t free_b = 0, total_b = 0;
+    SNAP_HIP(hipMemGetInfo(&free_b, &total_b));
+    if (((size_t)total + (size_t)h->n_pad) * 4 + (size_t)(m + 1) * 8 > free_b / 2) {      // not worth the squeeze
+        std::fill(h->gcompact_host, h->gcompact_host + G, (uint8_t)0);
+        return SNAP_OK;
+    }
+    return h->map16 ? cold_setup_maps<uint16_t>(h, cold_rows, cptr, total) : cold_setup_maps<uint32_t>(h, cold_rows, cptr, total);
+}
+
 // Scales of the logistic sums: a loss' <= 2^e in magnitude gets 19 - e fractional bits (times at most
 // 4095 rows: below 2^31), a^2 loss'' <= 2^(2e-2) gets 22 - 2e (below 2^32 in total).
 struct PackScales {
@@ -516,7 +682,8 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
              const float* __restrict__ delta_prev, const MAPT* __restrict__ map_cur,
              const float* __restrict__ val_cur, int hot, int k64, float* __restrict__ v, const float* __restrict__ y,
              const uint8_t* __restrict__ ybits, int64_t n, long long* __restrict__ partial, int64_t partial_stride,
-             float scale_g, float scale_h, PackScales ps, int kd, uint32_t* __restrict__ status) {
+             float scale_g, float scale_h, PackScales ps, int kd, uint32_t* __restrict__ status,
+             float* __restrict__ cbuf, const uint32_t* __restrict__ wbase) {
     constexpr int R = MapTraits<MAPT>::R;
     constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
     // LDS: fixed-point sums.  Logistic: ranks below k64: [rank] sum of a loss' * scale_g, [k64 + rank]
@@ -534,6 +701,12 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
     // the two longest coordinates of a group hold a quarter of its rows: their sums stay in
     // registers (one LDS update per wavefront at the end) instead of colliding in LDS
     float rg0 = 0.0f, rg1 = 0.0f, rh0 = 0.0f, rh1 = 0.0f;
+    // dense buffer of the short coordinates' rows (null: none): next position of this wavefront.  The
+    // entries pass through a ring of 128 per wavefront in LDS and leave it 64 at a time, in one store
+    // (written row by row they cost eight nearly empty stores per iteration).
+    uint32_t crun = (HIST && cbuf) ? __builtin_amdgcn_readfirstlane(wbase[blockIdx.x * (ROW_TPB / WAVE) + threadIdx.x / WAVE]) : 0u;
+    uint32_t cflushed = crun;
+    float* stage = dl + kd + 1 + (threadIdx.x / WAVE) * COLD_RING;
     bool too_large = false;                    // ridge: a term outside the range the 64-bit sums are laid out for
     const int64_t packs = (n + R - 1) / R;
     const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
@@ -622,6 +795,20 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                     g = (UNIT ? 1.0f : ac[j]) * (vv[j] - yy[j]);
                 }
                 const bool in = rk < (uint32_t)hot;
+                if (cbuf) {
+                    // a row of a short coordinate: its entry goes to the buffer (ridge: minus the label,
+                    // which the finishing kernel then need not gather either)
+                    const bool cold = !in && rk != NONE;
+                    const uint32_t pos = cold_slot(cold, crun);
+                    if (cold) stage[pos & (COLD_RING - 1)] = KIND == K_PRIMAL_LOGISTIC ? vv[j] : vv[j] - yy[j];
+                    if (crun - cflushed >= (uint32_t)WAVE) {      // (uniform; at most 64 entries arrive per row step)
+                        // (the lanes still in the loop are the first ones of the wavefront)
+                        const uint32_t lanes_on = (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(true));
+                        for (uint32_t i = threadIdx.x & (WAVE - 1); i < (uint32_t)WAVE; i += lanes_on)
+                            cbuf[cflushed + i] = stage[(cflushed + i) & (COLD_RING - 1)];
+                        cflushed += WAVE;
+                    }
+                }
                 if (KIND == K_PRIMAL_RIDGE) too_large |= in && !(fabsf(g) < RIDGE_TERM_LIMIT);
                 // register ranks: indicator times term (two selects and an fma per sum instead of
                 // a select and an add each; rank 1 is summed even when it is not hot, and then unused)
@@ -650,6 +837,14 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         }
     }
     if (HIST) {
+        if (cbuf) {
+            // what is left in the ring; the counters are taken from the first lane, which holds the
+            // wavefront's lowest pack and ran every iteration (a lane that left the loop earlier may
+            // hold older ones)
+            crun = __builtin_amdgcn_readfirstlane(crun);
+            cflushed = __builtin_amdgcn_readfirstlane(cflushed);
+            for (uint32_t i = cflushed + (threadIdx.x & (WAVE - 1)); i < crun; i += WAVE) cbuf[i] = stage[i & (COLD_RING - 1)];
+        }
         if (KIND == K_PRIMAL_RIDGE && too_large) atomicOr(status, STATUS_RANGE);
         rg0 = wave_sum(rg0); rg1 = wave_sum(rg1);
         if (KIND == K_PRIMAL_LOGISTIC) {
@@ -684,8 +879,53 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
                const uint32_t* __restrict__ idx, const float* __restrict__ val, const float* __restrict__ v,
                const float* __restrict__ y, const uint32_t* __restrict__ coord_of, int64_t g0, int64_t group_size,
                float* __restrict__ x, const float* __restrict__ norms, float* __restrict__ delta, StepParams sp,
-               double* __restrict__ gdot) {
+               double* __restrict__ gdot, const float* __restrict__ cbuf, const uint32_t* __restrict__ cidx,
+               const int64_t* __restrict__ cptr, int unit) {
     __shared__ long long sg[STEP_PARTS][STEP_RANKS], sh[STEP_PARTS][STEP_RANKS];
+    if ((int)blockIdx.x >= n_hot_blocks && cbuf) {
+        // short coordinates, entries of their rows in the dense buffer: 16 lanes per coordinate (most have
+        // a few dozen rows; four dependent chains per wavefront instead of one), index and value streams
+        // contiguous per coordinate, four loads in flight per lane
+        constexpr int SUB = 16, UNROLL = 4;
+        const int sl = threadIdx.x & (SUB - 1);
+        const int64_t sub0 = ((int64_t)(blockIdx.x - n_hot_blocks) * blockDim.x + threadIdx.x) / SUB;
+        const int64_t nsubs = (int64_t)(gridDim.x - n_hot_blocks) * blockDim.x / SUB;
+        for (int64_t rk = hot + sub0; rk < group_size; rk += nsubs) {
+            const int64_t k0 = cptr[g0 + rk], k1 = cptr[g0 + rk + 1];
+            const int64_t c = coord_of[g0 + rk];
+            const float* vals = unit ? nullptr : val + ptr[c] - k0;      // value of the nonzero at index position k
+            float g = 0.0f, hh = 0.0f;
+            for (int64_t k = k0 + sl; k < k1; k += SUB * UNROLL) {
+                uint32_t e[UNROLL];
+                float a[UNROLL], vv[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const bool on = k + u * SUB < k1;
+                    e[u] = on ? cidx[k + u * SUB] : 0u;
+                    a[u] = !on ? 0.0f : unit ? 1.0f : vals[k + u * SUB];
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) vv[u] = cbuf[KIND == K_PRIMAL_LOGISTIC ? e[u] & ~LABEL_BIT : e[u]];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const float yy = KIND == K_PRIMAL_LOGISTIC ? ((e[u] & LABEL_BIT) ? -1.0f : 1.0f) : 0.0f;
+                    accumulate<KIND>(a[u], vv[u], yy, g, hh);          // (a = 0 past the end: no contribution)
+                }
+            }
+            g = row_sum(g);
+            hh = row_sum(hh);
+            if (sl == 0) {
+                if (DOTS) {
+                    gdot[c] = (double)g;
+                } else {
+                    float mult;
+                    x[c] = take_step<KIND>((double)g, (double)hh, x[c], norms[c], 0.0f, sp, mult);
+                    delta[g0 + rk] = mult;
+                }
+            }
+        }
+        return;
+    }
     if ((int)blockIdx.x >= n_hot_blocks) {
         const int lane = threadIdx.x & (WAVE - 1);
         const int64_t wave0 = ((int64_t)(blockIdx.x - n_hot_blocks) * blockDim.x + threadIdx.x) / WAVE;
@@ -806,23 +1046,29 @@ static int grouped_epoch_kind(snap_handle* h) {
         const MAPT* map_cur = last ? nullptr : maps + (size_t)g * h->n_pad;
         const float* val_cur = (last || UNIT) ? nullptr : h->rowval + (size_t)g * h->n_pad;
         const int kd = prev >= 0 ? (int)std::min<int64_t>(h->g_kd_max, h->gbounds_host[prev + 1] - h->gbounds_host[prev]) : 0;
-        const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + (size_t)(kd + 1) * sizeof(float);
+        // short coordinates through the dense buffer (only with a row pass that computes sums)
+        const bool compact = !last && h->gcompact_host[g] && n > 0;
+        const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + (size_t)(kd + 1) * sizeof(float) +
+                           (compact ? (size_t)(ROW_TPB / WAVE) * COLD_RING * sizeof(float) : 0);
         const dim3 row_grid((unsigned)h->g_row_wgs);
         const bool scatter = prev >= 0, histo = !last && hot > 0;
+        float* cbuf = compact ? h->gcbuf : nullptr;
+        const uint32_t* wbase = compact ? h->gwbase + (size_t)g * (size_t)(h->g_row_wgs * (ROW_TPB / WAVE)) : nullptr;
         if (n > 0 && (scatter || histo)) {
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass], h->compute));
             if (scatter && histo)
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status);
+                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status, cbuf, wbase);
             else if (scatter)
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status);
+                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status, (float*)nullptr,
+                                   (const uint32_t*)nullptr);
             else
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status);
+                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status, cbuf, wbase);
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
             ++n_pass;
         }
@@ -830,12 +1076,13 @@ static int grouped_epoch_kind(snap_handle* h) {
         const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
         const int64_t cold = sz - hot;
         const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
-        const int n_cold_blocks = (int)std::min<int64_t>((cold + waves_per_block - 1) / waves_per_block, 8192);
+        const int per_block = compact ? STEP_RANKS * STEP_PARTS / 16 : waves_per_block;   // coordinates per pass of a workgroup
+        const int n_cold_blocks = (int)std::min<int64_t>((cold + per_block - 1) / per_block, 8192);
         hipLaunchKernelGGL((k_group_finish<KIND, false>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
                            dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
                            n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, 1.0 / (double)ps.g,
                            1.0 / (double)ps.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
-                           h->gdelta, sp, nullptr);
+                           h->gdelta, sp, nullptr, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
         prev = g;
     }
     h->n_row_passes = n_pass;
@@ -858,23 +1105,29 @@ static int grouped_dots_kind(snap_handle* h) {
         const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
         if (sz == 0) continue;
         const int hot = h->ghot_host[g], k64 = h->gk64_host[g];
+        const bool compact = h->gcompact_host[g] && n > 0;
+        float* cbuf = compact ? h->gcbuf : nullptr;
+        const uint32_t* wbase = compact ? h->gwbase + (size_t)g * (size_t)(h->g_row_wgs * (ROW_TPB / WAVE)) : nullptr;
         if (n > 0 && hot > 0) {
-            const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long);
+            const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + sizeof(float) +
+                               (compact ? (size_t)(ROW_TPB / WAVE) * COLD_RING * sizeof(float) : 0);
             hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), lds,
                                h->compute, (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr,
                                maps + (size_t)g * h->n_pad, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
-                               k64, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale_g, scale_h, ps, 0, h->status);
+                               k64, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale_g, scale_h, ps, 0, h->status, cbuf,
+                               wbase);
         }
         const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
         const int64_t cold = sz - hot;
         const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
-        const int n_cold_blocks = (int)std::min<int64_t>((cold + waves_per_block - 1) / waves_per_block, 8192);
+        const int per_block = compact ? STEP_RANKS * STEP_PARTS / 16 : waves_per_block;
+        const int n_cold_blocks = (int)std::min<int64_t>((cold + per_block - 1) / per_block, 8192);
         if (n_hot_blocks + n_cold_blocks > 0)
             hipLaunchKernelGGL((k_group_finish<KIND, true>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
                                dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
                                n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, 1.0 / (double)ps.g,
                                1.0 / (double)ps.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
-                               h->gdelta, sp, h->gdot);
+                               h->gdelta, sp, h->gdot, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
     }
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;

@@ -18,7 +18,15 @@ struct StepParams {
 // traffic, unlike shuffles): all-reduce inside each row of 16 lanes (swap neighbours, swap pairs,
 // rotate by 4, rotate by 8), then the four row sums are read as scalars.  The result is uniform over
 // the wavefront; lanes that are switched off contribute 0.
+__device__ __forceinline__ float row_sum(float x);
 __device__ __forceinline__ float wave_sum(float x) {
+    const int xi = __float_as_int(row_sum(x));
+    return __int_as_float(__builtin_amdgcn_readlane(xi, 0)) + __int_as_float(__builtin_amdgcn_readlane(xi, 16)) +
+           __int_as_float(__builtin_amdgcn_readlane(xi, 32)) + __int_as_float(__builtin_amdgcn_readlane(xi, 48));
+}
+
+// The first part alone: every lane gets the sum over its row of 16 lanes.
+__device__ __forceinline__ float row_sum(float x) {
     constexpr int QUAD_SWAP_1 = 0xB1;    // quad_perm [1,0,3,2]
     constexpr int QUAD_SWAP_2 = 0x4E;    // quad_perm [2,3,0,1]
     constexpr int ROW_ROR_4 = 0x124, ROW_ROR_8 = 0x128;
@@ -30,9 +38,7 @@ __device__ __forceinline__ float wave_sum(float x) {
     x += __int_as_float(__builtin_amdgcn_update_dpp(0, xi, ROW_ROR_4, 0xF, 0xF, false));
     xi = __float_as_int(x);
     x += __int_as_float(__builtin_amdgcn_update_dpp(0, xi, ROW_ROR_8, 0xF, 0xF, false));
-    xi = __float_as_int(x);
-    return __int_as_float(__builtin_amdgcn_readlane(xi, 0)) + __int_as_float(__builtin_amdgcn_readlane(xi, 16)) +
-           __int_as_float(__builtin_amdgcn_readlane(xi, 32)) + __int_as_float(__builtin_amdgcn_readlane(xi, 48));
+    return x;
 }
 
 __device__ __forceinline__ float load_shared(const float* v, uint32_t r) {

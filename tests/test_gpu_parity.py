@@ -360,6 +360,39 @@ def test_group_sweeps_equal_sequential_oracle(loss, unit):
     g.close()
 
 
+# The default launch shape (256 workgroups of 1024 threads, 8 rows per thread and iteration) gives every
+# thread at most one iteration on the small problems above, and their few short coordinates never fill
+# a wavefront's staging ring.  The tuning knobs (read at creation) shrink the launch and the LDS tables,
+# so that the same comparison also covers threads with several iterations, wavefronts cut short in their
+# last iteration, rings flushed inside the loop, steps gathered from beyond the LDS table, and the
+# alternative layouts (two workgroups per compute unit, two-word sums, no dense buffer).
+@pytest.mark.parametrize("knobs", [
+    {"SNAP_ROW_WGS": "16", "SNAP_HOT_MAX": "8"},
+    {"SNAP_ROW_WGS": "3", "SNAP_HOT_MAX": "40", "SNAP_DELTA_LDS": "16"},
+    {"SNAP_ROW_WGS": "16", "SNAP_HOT_MAX": "8", "SNAP_COMPACT": "0"},
+    {"SNAP_WGS_PER_CU": "2", "SNAP_HOT_ROWS": "128"},
+    {"SNAP_PACK": "0", "SNAP_ROW_WGS": "24"},
+], ids=lambda k: ",".join("%s=%s" % (n[5:].lower(), v) for n, v in k.items()))
+@pytest.mark.parametrize("loss,unit", [("logistic", True), ("logistic", False), ("ridge", True)])
+def test_group_sweeps_other_launch_shapes(monkeypatch, knobs, loss, unit):
+    for name, value in knobs.items():
+        monkeypatch.setenv(name, value)
+    p = _onehot_variant(loss, unit)
+    groups = p.meta["field_starts"] + [p.d]
+    A = oracle.Matrix.from_problem(p)
+    g = gpu_solver(p, group_bounds=groups)
+    o = oracle.Solver(A, p.y.numpy(), p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    for e in range(4):
+        g.epoch(e)
+        o.epoch(e)
+        _, x = g.model()
+        assert relnorm(x, o.x) <= 2e-5, "model differs from the sequential oracle after epoch %d" % e
+        assert relnorm(g.shared(), o.v) <= 2e-5
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    assert rel(g.duality_gap(), o.gap()) <= 1e-3
+    g.close()
+
+
 def test_group_sweeps_reject_overlapping_groups():
     p = problem("cfg1_sparse_logistic")                  # uniform columns: any two groups of columns overlap
     with pytest.raises(snap.SnapError) as e:
