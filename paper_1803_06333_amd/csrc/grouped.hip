@@ -16,8 +16,8 @@
 //     sums of group g's coordinate: hot ranks (the longest coordinates) accumulate in LDS, one
 //     partial array per workgroup, summed afterwards in a fixed order;
 //   - a second kernel sums the partials of the hot ranks, lets the remaining (short) coordinates of
-//     the group take their sums column-wise, one wavefront per coordinate, and turns all sums into
-//     the steps that the next row pass applies.
+//     the group take their sums column-wise (from a dense buffer of their rows' entries of v that the
+//     row pass fills on its way), and turns all sums into the steps that the next row pass applies.
 // Traffic per group and row: two map entries (2 + 2 bytes), read + write of v (8 bytes), one label bit
 // (+ values unless all 1).
 #include "scd_device.h"
@@ -867,8 +867,9 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
 // One launch, two kinds of workgroups.  The first n_hot_blocks handle the hot ranks: 32 ranks per
 // workgroup, 32 threads per rank, each summing every 32nd per-workgroup partial of the row pass (integer
 // sums: exact and independent of the order), combined in LDS, then one thread takes the step.  The
-// others handle the cold ranks: one wavefront per coordinate gathers its two sums column-wise (v is
-// not written while this kernel runs) and takes the step right away.
+// others handle the cold ranks: 16 lanes per coordinate gather its two sums column-wise from the dense
+// buffer of the row pass (or, where a group has none, one wavefront per coordinate from v itself, which is
+// not written while this kernel runs) and take the step right away.
 constexpr int STEP_RANKS = 32, STEP_PARTS = 32;
 
 // DOTS: no step is taken; the first sum (the coordinate's inner product with loss'(v)) goes to gdot.
