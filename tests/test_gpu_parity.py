@@ -413,11 +413,18 @@ def test_group_sweeps_reject_overlapping_groups():
     g.close()
 
 
-def test_group_sweeps_wide_group_uses_32_bit_maps():
-    """A group with more than 65535 coordinates takes the 32-bit row-map path."""
+@pytest.mark.parametrize("skewed", [False, True], ids=["uniform", "skewed"])
+def test_group_sweeps_wide_group_uses_32_bit_maps(monkeypatch, skewed):
+    """A group with more than 65535 coordinates takes the 32-bit row-map path.  Uniform categories:
+    every coordinate of the wide group is short (no LDS sums at all for it); skewed: a hundred long
+    coordinates beside the short ones (LDS sums, and the dense buffer for the short coordinates' rows, with
+    four rows per thread and iteration), on a launch small enough for several iterations per thread."""
     n, d1, d2 = 200_000, 70_000, 50
     rng = np.random.default_rng(8)
     c1 = rng.integers(0, d1, size=n)                     # field 1: 70 000 categories
+    if skewed:
+        monkeypatch.setenv("SNAP_ROW_WGS", "16")
+        c1 = np.where(rng.random(n) < 0.5, rng.integers(0, 100, size=n), c1)
     c2 = rng.integers(0, d2, size=n)                     # field 2: 50 categories
     cols = np.concatenate([c1, d1 + c2])
     rows = np.concatenate([np.arange(n), np.arange(n)])
