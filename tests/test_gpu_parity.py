@@ -393,6 +393,24 @@ def test_group_sweeps_other_launch_shapes(monkeypatch, knobs, loss, unit):
     g.close()
 
 
+@pytest.mark.parametrize("loss", ["logistic", "ridge"])
+def test_group_sweeps_are_bit_reproducible(loss):
+    """No floating-point atomics and no order left to chance (integer sums in LDS, fixed orders
+    elsewhere): two runs from the same seeds end in the same bits."""
+    p = _onehot_variant(loss, True)
+    groups = p.meta["field_starts"] + [p.d]
+    models, shared = [], []
+    for _ in range(2):
+        g = gpu_solver(p, group_bounds=groups)
+        for e in range(3):
+            g.epoch(100 + e)
+        models.append(g.model()[1].copy())
+        shared.append(np.array(g.shared(), copy=True))
+        g.close()
+    assert np.array_equal(models[0], models[1])
+    assert np.array_equal(shared[0], shared[1])
+
+
 def test_group_sweeps_reject_overlapping_groups():
     p = problem("cfg1_sparse_logistic")                  # uniform columns: any two groups of columns overlap
     with pytest.raises(snap.SnapError) as e:
