@@ -693,6 +693,41 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
     // costs a third of the pass; nearly every row hits one of these).
     extern __shared__ unsigned long long hist[];
     float* dl = reinterpret_cast<float*>(hist + hot + k64);
+    const int64_t packs = (n + R - 1) / R;
+    const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
+    const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
+    // All loads of an iteration are issued together, ahead of its first wait, and those of the first
+    // iteration ahead of the set-up of the LDS tables (the loop below asks for the next pack's at its end).
+    float vv[R], ap[R], ac[R], yy[R];
+    u32x4 raw_prev = {0u, 0u, 0u, 0u}, raw_cur = {0u, 0u, 0u, 0u};
+    uint32_t lab_byte = 0;
+    auto request = [&](int64_t q) {
+        const int64_t r = R * q;
+        const bool full = r + R - 1 < n;           // maps, values and label bits are padded; v and y are not
+        if (full) {
+            load_floats<R>(v + r, vv);
+        } else {
+#pragma unroll
+            for (int j = 0; j < R; ++j) vv[j] = r + j < n ? v[r + j] : 0.0f;
+        }
+        if (SCATTER) {
+            raw_prev = load_map(map_prev + r);
+            if (!UNIT) load_floats<R>(val_prev + r, ap);
+        }
+        if (HIST) {
+            raw_cur = load_map(map_cur + r);
+            if (!UNIT) load_floats<R>(val_cur + r, ac);
+            if (KIND == K_PRIMAL_LOGISTIC) {
+                lab_byte = ybits[r >> 3];
+            } else if (full) {
+                load_floats<R>(y + r, yy);
+            } else {
+#pragma unroll
+                for (int j = 0; j < R; ++j) yy[j] = r + j < n ? y[r + j] : 0.0f;
+            }
+        }
+    };
+    if (q0 + threadIdx.x < q1) request(q0 + threadIdx.x);
     if (HIST)
         for (int i = threadIdx.x; i < hot + k64; i += ROW_TPB) hist[i] = 0ull;
     if (SCATTER)
@@ -708,34 +743,14 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
     uint32_t cflushed = crun;
     float* stage = dl + kd + 1 + (threadIdx.x / WAVE) * COLD_RING;
     bool too_large = false;                    // ridge: a term outside the range the 64-bit sums are laid out for
-    const int64_t packs = (n + R - 1) / R;
-    const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
-    const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
-    for (int64_t q = q0 + threadIdx.x; q < q1; q += ROW_TPB) {
+    for (int64_t q = q0 + threadIdx.x; q < q1;) {
         const int64_t r = R * q;
-        float vv[R], ap[R], ac[R], yy[R];
         uint32_t mp[R], mc[R];
-        const bool full = r + R - 1 < n;           // maps, values and label bits are padded; v and y are not
-        if (full) {
-            load_floats<R>(v + r, vv);
-        } else {
-#pragma unroll
-            for (int j = 0; j < R; ++j) vv[j] = r + j < n ? v[r + j] : 0.0f;
-        }
-        // every load of the iteration is issued here, ahead of the first wait (the pass is bound by its
-        // chains of dependent loads; left behind the branches below, the current group's map would be
-        // fetched only after the store of the shared vector)
-        u32x4 raw_prev = {0u, 0u, 0u, 0u}, raw_cur = {0u, 0u, 0u, 0u};
-        uint32_t lab = 0;
-        if (SCATTER) {
-            raw_prev = load_map(map_prev + r);
-            if (!UNIT) load_floats<R>(val_prev + r, ap);
-        }
-        if (HIST) {
-            raw_cur = load_map(map_cur + r);
-            if (KIND == K_PRIMAL_LOGISTIC) lab = (uint32_t)ybits[r >> 3] >> (r & 7);
-        }
-        __builtin_amdgcn_sched_barrier(0);         // (nothing moves across: the loads above stay ahead of the first wait)
+        const bool full = r + R - 1 < n;
+        const uint32_t lab = lab_byte >> (r & 7);
+        __builtin_amdgcn_sched_barrier(0);         // (nothing moves across: the requests stay ahead of the first wait;
+                                                   // left to the compiler, the current group's map was fetched only
+                                                   // after the store of the shared vector)
         if (SCATTER) {
             unpack_ranks(map_prev, raw_prev, mp);
             // straight-line per row (a wavefront's rows take every path anyway, and each divergent
@@ -765,15 +780,6 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         }
         if (HIST) {
             unpack_ranks(map_cur, raw_cur, mc);
-            if (!UNIT) load_floats<R>(val_cur + r, ac);
-            if (KIND != K_PRIMAL_LOGISTIC) {
-                if (full) {
-                    load_floats<R>(y + r, yy);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < R; ++j) yy[j] = r + j < n ? y[r + j] : 0.0f;
-                }
-            }
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 // the terms are computed for every row (a row past the end has rank "none", which is
@@ -835,6 +841,8 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                 }
             }
         }
+        q += ROW_TPB;
+        if (q < q1) request(q);
     }
     if (HIST) {
         if (cbuf) {
