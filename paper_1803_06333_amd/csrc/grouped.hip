@@ -903,6 +903,7 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
             const int64_t k0 = cptr[g0 + rk], k1 = cptr[g0 + rk + 1];
             const int64_t c = coord_of[g0 + rk];
             const float* vals = unit ? nullptr : val + ptr[c] - k0;      // value of the nonzero at index position k
+            const float xc = DOTS ? 0.0f : x[c], nc = DOTS ? 0.0f : norms[c];   // (asked for early: off the chain of dependent loads)
             float g = 0.0f, hh = 0.0f;
             for (int64_t k = k0 + sl; k < k1; k += SUB * UNROLL) {
                 uint32_t e[UNROLL];
@@ -928,7 +929,7 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
                     gdot[c] = (double)g;
                 } else {
                     float mult;
-                    x[c] = take_step<KIND>((double)g, (double)hh, x[c], norms[c], 0.0f, sp, mult);
+                    x[c] = take_step<KIND>((double)g, (double)hh, xc, nc, 0.0f, sp, mult);
                     delta[g0 + rk] = mult;
                 }
             }
@@ -966,6 +967,17 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
     const int64_t rk = (int64_t)blockIdx.x * STEP_RANKS + lr;
     long long Gi = 0, Hi = 0;
     const bool packed = KIND == K_PRIMAL_LOGISTIC && rk >= k64;      // one word per workgroup holding both sums
+    // what the thread that takes the step needs besides the sums is asked for first
+    int64_t c = 0, rows = 0;
+    float xc = 0.0f, nc = 0.0f;
+    if (part == 0 && rk < hot) {
+        c = coord_of[g0 + rk];
+        rows = ptr[c + 1] - ptr[c];
+        if (!DOTS) {
+            xc = x[c];
+            nc = norms[c];
+        }
+    }
     if (rk < hot) {
         if (!packed) {
 #pragma unroll 8
@@ -989,11 +1001,10 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
         Gi += sg[p][lr];
         Hi += sh[p][lr];
     }
-    const int64_t c = coord_of[g0 + rk];
     if (KIND == K_PRIMAL_LOGISTIC && rk >= 2) {
         // every term of these ranks carries the bit pattern of the rounding constant (the ranks 0 and 1
         // are summed in registers by the row pass and converted without it)
-        const unsigned long long bias = (unsigned long long)(ptr[c + 1] - ptr[c]) * FIX_BIAS;
+        const unsigned long long bias = (unsigned long long)rows * FIX_BIAS;
         if (packed) {
             const unsigned long long word = (unsigned long long)Gi - bias - (bias << PACK_H_BITS);
             Hi = (long long)(word & 0xFFFFFFFFull);                           // the low field is never negative
@@ -1010,7 +1021,7 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
         return;
     }
     float mult;
-    x[c] = take_step<KIND>(gsum, hsum, x[c], norms[c], 0.0f, sp, mult);
+    x[c] = take_step<KIND>(gsum, hsum, xc, nc, 0.0f, sp, mult);
     delta[g0 + rk] = mult;
 }
 
