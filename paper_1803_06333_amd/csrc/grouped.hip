@@ -52,16 +52,17 @@ constexpr uint32_t RANK_NONE = 0xFFFFFFFFu;      // row not covered by the group
 // use these scales (one set of scales saves selects).  That halves the LDS per rank (and the LDS atomics
 // per row) for the rest.
 //
-// One workgroup of 1024 threads per compute unit with all of its LDS: 14336 hot ranks (packed) and 8192
+// One workgroup of 1024 threads per compute unit with all of its LDS: 12288 hot ranks (packed) and 12288
 // steps of the previous group.  Two workgroups per unit with half the tables each used to run the pass
 // 20 % faster while it was bound by instruction issue; since it no longer is, the pass runs as fast
 // with 16 wavefronts per unit, and the larger tables take a tenth off the epoch (click-log workload:
-// 5.84 -> 5.19 ms; 16384 ranks + 4096 steps: 5.33, 12288 + 12288: 5.20).
+// 5.84 -> 5.19 ms with 14336 ranks + 8192 steps; with the dense buffer for the short coordinates, which
+// makes their rows cheaper, 12288 + 12288 is the better split: 4.92 against 4.95 ms).
 constexpr int HOT_MAX = 16384;                   // most ranks accumulated in LDS (tuning knob's ceiling)
-constexpr int HOT_DEFAULT = 14336;
+constexpr int HOT_DEFAULT = 12288;
 constexpr int HOT_MIN_ROWS = 32;                 // a rank is worth an LDS slot while its coordinate has that many rows
 constexpr int DELTA_LDS = 16384;                 // most steps of the previous group kept in LDS (tuning knob's ceiling)
-constexpr int DELTA_DEFAULT = 8192;
+constexpr int DELTA_DEFAULT = 12288;
 constexpr int ROW_TPB = 1024;
 constexpr int COLD_RING = 128;                   // entries per wavefront staged in LDS on their way to the short coordinates' buffer
 constexpr int ROW_WGS_DEFAULT = 256;             // one workgroup per compute unit
