@@ -373,7 +373,7 @@ def test_group_sweeps_equal_sequential_oracle(loss, unit):
     {"SNAP_WGS_PER_CU": "2", "SNAP_HOT_ROWS": "128"},
     {"SNAP_PACK": "0", "SNAP_ROW_WGS": "24"},
 ], ids=lambda k: ",".join("%s=%s" % (n[5:].lower(), v) for n, v in k.items()))
-@pytest.mark.parametrize("loss,unit", [("logistic", True), ("logistic", False), ("ridge", True)])
+@pytest.mark.parametrize("loss,unit", [("logistic", True), ("logistic", False), ("ridge", True), ("ridge", False)])
 def test_group_sweeps_other_launch_shapes(monkeypatch, knobs, loss, unit):
     for name, value in knobs.items():
         monkeypatch.setenv(name, value)
