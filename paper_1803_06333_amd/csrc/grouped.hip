@@ -476,17 +476,10 @@ template <typename MAPT> struct MapTraits;
 template <> struct MapTraits<uint16_t> { static constexpr int R = 8; static constexpr uint32_t NONE = 0xFFFFu; };
 template <> struct MapTraits<uint32_t> { static constexpr int R = 4; static constexpr uint32_t NONE = 0xFFFFFFFFu; };
 
-// Round-to-nearest fixed point.  Logistic terms are bounded, so their scaled magnitude is known to
-// stay below 2^31 and one 32-bit conversion does; ridge terms a (v - y) have no a-priori bound and
-// take the 64-bit conversion.  With 24 fractional bits the 64-bit sum of a ridge coordinate has 2^39 of
-// range: every term a (v - y) must stay below 2^14 for up to 2^25 rows; larger terms raise the handle's
-// status word instead of overflowing silently.
+// Ridge terms a (v - y) have no a-priori bound and take the 64-bit conversion to fixed point.  With 24
+// fractional bits the 64-bit sum of a ridge coordinate has 2^39 of range: every term must stay below 2^14
+// for up to 2^25 rows; larger terms raise the handle's status word instead of overflowing silently.
 constexpr float RIDGE_TERM_LIMIT = 16384.0f;
-template <int KIND>
-__device__ __forceinline__ unsigned long long to_fixed(float x, float scale) {
-    if (KIND == K_PRIMAL_LOGISTIC) return (unsigned long long)(long long)__float2int_rn(x * scale);
-    return (unsigned long long)__float2ll_rn(x * scale);
-}
 
 // One 128-bit load of map entries (non-temporal: the maps are read once per pass and should not push the
 // shared vector out of the last-level cache), and its unpacking into ranks.
@@ -669,11 +662,16 @@ static int cold_setup(snap_handle* h, const int64_t* hptr, const std::vector<uin
     return h->map16 ? cold_setup_maps<uint16_t>(h, cold_rows, cptr, total) : cold_setup_maps<uint32_t>(h, cold_rows, cptr, total);
 }
 
-// Scales of the logistic sums: a loss' <= 2^e in magnitude gets 19 - e fractional bits (times at most
-// 4095 rows: below 2^31), a^2 loss'' <= 2^(2e-2) gets 22 - 2e (below 2^32 in total).
-struct PackScales {
+// Scales of the sums (powers of two, exact in fp32).  Logistic: a loss' <= 2^e in magnitude gets 19 - e
+// fractional bits (times at most 4095 rows: below 2^31), a^2 loss'' <= 2^(2e-2) gets 22 - 2e (below 2^32
+// in total).  Ridge: 24 fractional bits for a (v - y); no second sum.
+struct SumScales {
     float g, h;
 };
+static SumScales sum_scales(const snap_handle* h) {
+    if (h->kind == K_PRIMAL_LOGISTIC) return SumScales{ldexpf(1.0f, 19 - h->gscale_exp), ldexpf(1.0f, 22 - 2 * h->gscale_exp)};
+    return SumScales{ldexpf(1.0f, 24), 1.0f};
+}
 constexpr float FIX_MAGIC = 12582912.0f;         // 1.5 * 2^23
 constexpr unsigned long long FIX_BIAS = 0x4B400000ull;   // its bit pattern
 
@@ -683,13 +681,13 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
              const float* __restrict__ delta_prev, const MAPT* __restrict__ map_cur,
              const float* __restrict__ val_cur, int hot, int k64, float* __restrict__ v, const float* __restrict__ y,
              const uint8_t* __restrict__ ybits, int64_t n, long long* __restrict__ partial, int64_t partial_stride,
-             float scale_g, float scale_h, PackScales ps, int kd, uint32_t* __restrict__ status,
+             SumScales scale, int kd, uint32_t* __restrict__ status,
              float* __restrict__ cbuf, const uint32_t* __restrict__ wbase) {
     constexpr int R = MapTraits<MAPT>::R;
     constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
-    // LDS: fixed-point sums.  Logistic: ranks below k64: [rank] sum of a loss' * scale_g, [k64 + rank]
-    // sum of a^2 loss'' * scale_h; ranks k64 .. hot-1: one packed word at [k64 + rank] (k64 = hot: none).
-    // Ridge: [rank] sum of a loss' * scale_g, k64 = 0.
+    // LDS: fixed-point sums.  Logistic: ranks below k64: [rank] sum of a loss' * scale.g, [k64 + rank]
+    // sum of a^2 loss'' * scale.h; ranks k64 .. hot-1: one packed word at [k64 + rank] (k64 = hot: none).
+    // Ridge: [rank] sum of a loss' * scale.g, k64 = 0.
     // Then the steps of the previous group's first kd ranks (a gather from global memory per row
     // costs a third of the pass; nearly every row hits one of these).
     extern __shared__ unsigned long long hist[];
@@ -831,14 +829,14 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                         // in every term and is taken out per coordinate, times its row count, by the
                         // finishing kernel.  Ranks below k64: sum of a^2 loss'' at [k64 + rank] and sum
                         // of a loss' at [rank]; the others: both in one word at [k64 + rank].
-                        const uint32_t gb = __float_as_uint(fmaf(g, -ps.g, FIX_MAGIC));
-                        const uint32_t hb = __float_as_uint(fmaf(hh, ps.h, FIX_MAGIC));
+                        const uint32_t gb = __float_as_uint(fmaf(g, -scale.g, FIX_MAGIC));
+                        const uint32_t hb = __float_as_uint(fmaf(hh, scale.h, FIX_MAGIC));
                         const bool two = rk < (uint32_t)k64;
                         atomicAdd(&hist[k64 + rk], (unsigned long long)hb | ((unsigned long long)(two ? 0u : gb) << PACK_H_BITS));
                         if (two) atomicAdd(&hist[rk], (unsigned long long)gb);
                     }
                 } else if (in && rk >= 2u) {
-                    atomicAdd(&hist[rk], to_fixed<KIND>(g, scale_g));
+                    atomicAdd(&hist[rk], (unsigned long long)__float2ll_rn(g * scale.g));
                 }
             }
         }
@@ -862,8 +860,8 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         if ((threadIdx.x & (WAVE - 1)) == 0) {
             const float rg[2] = {rg0, rg1}, rh[2] = {rh0, rh1};
             for (int t = 0; t < 2 && t < hot; ++t) {
-                atomicAdd(&hist[t], (unsigned long long)__float2ll_rn(rg[t] * (KIND == K_PRIMAL_LOGISTIC ? -scale_g : scale_g)));
-                if (KIND == K_PRIMAL_LOGISTIC) atomicAdd(&hist[k64 + t], (unsigned long long)__float2ll_rn(rh[t] * scale_h));
+                atomicAdd(&hist[t], (unsigned long long)__float2ll_rn(rg[t] * (KIND == K_PRIMAL_LOGISTIC ? -scale.g : scale.g)));
+                if (KIND == K_PRIMAL_LOGISTIC) atomicAdd(&hist[k64 + t], (unsigned long long)__float2ll_rn(rh[t] * scale.h));
             }
         }
         __syncthreads();
@@ -885,7 +883,7 @@ constexpr int STEP_RANKS = 32, STEP_PARTS = 32;
 template <int KIND, bool DOTS>
 __global__ void __launch_bounds__(STEP_RANKS * STEP_PARTS)
 k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, int n_wgs, int hot, int k64, int n_hot_blocks,
-               double inv_scale_g, double inv_scale_h, double inv_pack_g, double inv_pack_h, const int64_t* __restrict__ ptr,
+               double inv_scale_g, double inv_scale_h, const int64_t* __restrict__ ptr,
                const uint32_t* __restrict__ idx, const float* __restrict__ val, const float* __restrict__ v,
                const float* __restrict__ y, const uint32_t* __restrict__ coord_of, int64_t g0, int64_t group_size,
                float* __restrict__ x, const float* __restrict__ norms, float* __restrict__ delta, StepParams sp,
@@ -1015,8 +1013,8 @@ k_group_finish(const long long* __restrict__ partial, int64_t partial_stride, in
             Hi = (long long)((unsigned long long)Hi - bias);
         }
     }
-    const double gsum = (double)Gi * (packed ? inv_pack_g : inv_scale_g);
-    const double hsum = (double)Hi * (packed ? inv_pack_h : inv_scale_h);
+    const double gsum = (double)Gi * inv_scale_g;
+    const double hsum = (double)Hi * inv_scale_h;
     if (DOTS) {
         gdot[c] = gsum;
         return;
@@ -1041,12 +1039,7 @@ static int grouped_epoch_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
     const int64_t n = h->n, G = h->n_groups;
     long long* gpart = (long long*)h->gpartial;
-    // power-of-two scales (exact in fp32).  Logistic: |a loss'| <= 2^e and a^2 loss'' <= 2^(2e-2), scaled
-    // to 19 resp. 20 bits (see PackScales).  Ridge terms a (v - y): 24 fractional bits, 2^39 of range in
-    // the 64-bit sum.
-    const PackScales ps{ldexpf(1.0f, 19 - h->gscale_exp), ldexpf(1.0f, 22 - 2 * h->gscale_exp)};
-    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ps.g : ldexpf(1.0f, 24);
-    const float scale_h = ps.h;
+    const SumScales scale = sum_scales(h);
     int64_t prev = -1;                              // last non-empty group, whose steps are still to be applied
     const bool prof = h->opt.profile != 0 && h->ev_group != nullptr;
     int n_pass = 0;
@@ -1080,16 +1073,16 @@ static int grouped_epoch_kind(snap_handle* h) {
             if (scatter && histo)
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status, cbuf, wbase);
+                                   h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
             else if (scatter)
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status, (float*)nullptr,
+                                   h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
                                    (const uint32_t*)nullptr);
             else
                 hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
                                    map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale_g, scale_h, ps, kd, h->status, cbuf, wbase);
+                                   h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
             if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
             ++n_pass;
         }
@@ -1101,8 +1094,7 @@ static int grouped_epoch_kind(snap_handle* h) {
         const int n_cold_blocks = (int)std::min<int64_t>((cold + per_block - 1) / per_block, 8192);
         hipLaunchKernelGGL((k_group_finish<KIND, false>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
                            dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
-                           n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, 1.0 / (double)ps.g,
-                           1.0 / (double)ps.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
+                           n_hot_blocks, 1.0 / (double)scale.g, 1.0 / (double)scale.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
                            h->gdelta, sp, nullptr, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
         prev = g;
     }
@@ -1118,9 +1110,7 @@ static int grouped_dots_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
     const int64_t n = h->n, G = h->n_groups;
     long long* gpart = (long long*)h->gpartial;
-    const PackScales ps{ldexpf(1.0f, 19 - h->gscale_exp), ldexpf(1.0f, 22 - 2 * h->gscale_exp)};
-    const float scale_g = KIND == K_PRIMAL_LOGISTIC ? ps.g : ldexpf(1.0f, 24);
-    const float scale_h = ps.h;
+    const SumScales scale = sum_scales(h);
     const MAPT* maps = (const MAPT*)h->rowmap;
     for (int64_t g = 0; g < G; ++g) {
         const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
@@ -1135,7 +1125,7 @@ static int grouped_dots_kind(snap_handle* h) {
             hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), lds,
                                h->compute, (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr,
                                maps + (size_t)g * h->n_pad, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
-                               k64, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale_g, scale_h, ps, 0, h->status, cbuf,
+                               k64, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale, 0, h->status, cbuf,
                                wbase);
         }
         const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
@@ -1146,8 +1136,7 @@ static int grouped_dots_kind(snap_handle* h) {
         if (n_hot_blocks + n_cold_blocks > 0)
             hipLaunchKernelGGL((k_group_finish<KIND, true>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
                                dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
-                               n_hot_blocks, 1.0 / (double)scale_g, 1.0 / (double)scale_h, 1.0 / (double)ps.g,
-                               1.0 / (double)ps.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
+                               n_hot_blocks, 1.0 / (double)scale.g, 1.0 / (double)scale.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
                                h->gdelta, sp, h->gdot, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
     }
     SNAP_HIP(hipGetLastError());
