@@ -35,15 +35,15 @@ namespace snap {
 constexpr uint32_t RANK_NONE = 0xFFFFFFFFu;      // row not covered by the group (all ones in either map width)
 // The sums of the hot ranks are kept in LDS as 64-bit fixed-point integers: integer LDS atomics run
 // more than twenty times faster here than ds_add_f32 (measured), and the result does not depend on
-// the order of the additions (the epoch is bit-reproducible).  A term is scaled so that it fits 32
-// bits (one v_cvt; a float-to-int64 conversion costs a dozen instructions and the row pass is
-// bound by instruction issue as much as by bandwidth): 24 fractional bits relative to the largest
-// |value|, the fp32 precision of the term itself; the 64-bit sum cannot overflow.
+// the order of the additions (the epoch is bit-reproducible).  The terms of the logistic loss are
+// bounded, so they are scaled to about 20 bits and turned into integers by the rounding of one
+// floating-point addition (a float-to-int64 conversion costs a dozen instructions); the terms of the
+// ridge loss are not and take that conversion, with 24 fractional bits.
 //
 // Packed ranks (logistic loss).  LDS capacity decides how many coordinates of a group are hot, and a
-// row of a coordinate that is not costs ten times a row of one that is (a whole cache line fetched for
-// its entry of the shared vector in the finishing kernel, a gather of its step in the next row pass).
-// Both sums of a rank
+// row of a coordinate that is not costs several times a row of one that is (its entry of the shared
+// vector takes a detour through a buffer to the finishing kernel, its step a gather in the next row
+// pass).  Both sums of a rank
 // whose coordinate has at most PACK_COUNT_MAX rows fit ONE 64-bit word -- the high half for the signed
 // sum of a loss' (19 fractional bits relative to the largest |value|), the low half for the sum of
 // a^2 loss'' (22 fractional bits), so that a word is put together from two 32-bit conversions without
