@@ -168,12 +168,17 @@ class Solver:
         self.shuffle_chunks = shuffle_chunks
         self.last_perm = None
 
-    def epoch(self, seed: int):
+    def epoch(self, seed: int, chunks: Optional[Sequence[int]] = None):
+        """One pass over all chunks, or (Section 3.2, processing only part of the data in a round) over
+        the given chunks only, in the given order."""
         L = lib()
         n = C.c_int64(self.A.n)
         perms = []
         nch = len(self.bounds) - 1
         order = permutation(seed, nch, chunk=self.GROUP_ORDER_CHUNK) if self.shuffle_chunks else range(nch)
+        if chunks is not None:
+            order = list(chunks)
+            assert len(set(order)) == len(order) and all(0 <= int(c) < nch for c in order)
         for ch in order:
             ch = int(ch)
             c0, c1 = self.bounds[ch], self.bounds[ch + 1]
@@ -189,7 +194,7 @@ class Solver:
             else:
                 L.oracle_epoch_primal_dense(C.c_int(self.loss), n, _p(self.A.val), _p(self.y), C.c_double(self.lam),
                                             C.c_double(self.lam1), *tail)
-        self.last_perm = np.concatenate(perms)
+        self.last_perm = np.concatenate(perms) if perms else np.zeros(0, dtype=np.int64)
 
     # model ----------------------------------------------------------------------------------
     def weights(self) -> np.ndarray:
@@ -230,6 +235,13 @@ class Solver:
             form = "fenchel"              # the gradient form needs a differentiable regulariser
         return primal_gap(self.A, self.loss, self.v, self.y, self.x, self.lam, form, self.lam1)
 
+    def chunk_gaps(self) -> np.ndarray:
+        """Share of every chunk in the duality gap at the current state (primal forms): the sum of
+        its coordinates' shares (primal_gap_shares)."""
+        assert self.form == "primal"
+        share = primal_gap_shares(self.A, self.loss, self.v, self.y, self.x, self.lam, self.lam1)
+        return np.array([share[self.bounds[c]:self.bounds[c + 1]].sum() for c in range(len(self.bounds) - 1)])
+
     def predict(self, X: Matrix) -> np.ndarray:
         return X.matvec(self.weights())
 
@@ -249,6 +261,49 @@ def primal_gap(A: Matrix, loss: int, v, y, w, lam: float, form: str = "gradient"
         return float(lib().oracle_primal_gap_gradient(C.c_int64(A.d), _p(w), _p(xtu), C.c_double(lam)))
     return float(lib().oracle_primal_gap_fenchel(C.c_int(loss), C.c_int64(A.n), C.c_int64(A.d), _p(v), _p(y),
                                                  _p(w), _p(u), _p(xtu), C.c_double(lam), C.c_double(lam1)))
+
+
+def primal_gap_shares(A: Matrix, loss: int, v, y, w, lam: float, lam1: float = 0.0) -> np.ndarray:
+    """The duality gap of eq. (1) coordinate by coordinate (the importance measure of the scheme that
+    Section 3.2 cites for choosing what to process).  With the dual candidate u = grad f(v) the loss part
+    of the Fenchel gap vanishes (f(v) + f*(u) = <u, v>) and what is left is a sum over the coordinates,
+        share_j = g_j(w_j) + g_j*(-z_j) + w_j z_j,   z_j = a_j . u,
+    each term non-negative by the Fenchel-Young inequality and zero exactly when w_j minimises the
+    objective along coordinate j's direction for this u.  Here g_j(w) = (lam/2) w^2 + lam1 |w| and
+    g_j*(t) = max(|t| - lam1, 0)^2 / (2 lam)."""
+    v, w, y = _f64(v), _f64(w), _f32(y)
+    u = np.empty(A.n, dtype=np.float64)
+    lib().oracle_primal_dual_candidate(C.c_int(loss), C.c_int64(A.n), _p(v), _p(y), _p(u))
+    z = A.rmatvec(u)
+    gstar = np.maximum(np.abs(z) - lam1, 0.0) ** 2 / (2.0 * lam)
+    return 0.5 * lam * w * w + lam1 * np.abs(w) + gstar + w * z
+
+
+def select_chunks(shares, keep: int):
+    """The `keep` chunks with the largest shares, largest first; equal shares in index order."""
+    order = sorted(range(len(shares)), key=lambda c: (-float(shares[c]), c))
+    return order[:keep]
+
+
+def solve_selected(s: "Solver", seed0: int, max_passes: int, gap_tol: float, refresh_every: int, keep: int):
+    """Gap-based selection of the chunks to process (Section 3.2): every `refresh_every`-th pass visits
+    all chunks and is followed by an evaluation of the chunks' gap shares (their sum is the gap: the
+    stopping test); the passes in between visit only the `keep` chunks whose shares were largest.
+    Returns (passes done, chunk visits, last gap)."""
+    visits, gap, p = 0, float("inf"), 0
+    chosen = list(range(len(s.bounds) - 1))
+    while p < max_passes:
+        full = p % refresh_every == 0
+        s.epoch(seed0 + p, None if full else chosen)
+        visits += (len(s.bounds) - 1) if full else len(chosen)
+        p += 1
+        if full:
+            shares = s.chunk_gaps()
+            gap = float(shares.sum())
+            if gap <= gap_tol:
+                break
+            chosen = select_chunks(shares, keep)
+    return p, visits, gap
 
 
 def solve(A: Matrix, y, loss: str, lam: float, epochs: int, seed0: int = 0, tol: Optional[float] = None,

@@ -565,3 +565,86 @@ def test_dual_logistic_well_separated_examples_leave_the_boundary():
     w = s.weights()
     np.testing.assert_allclose(s.x, 1 / (1 + np.exp(y * (X @ w))), rtol=1e-6)
     assert s.gap() < 1e-10
+
+
+# ---------------------------------------------------------------------------------------------
+# gap shares of the coordinates / chunks and passes over part of the chunks (Section 3.2: choosing
+# the data to process by its share in the duality gap)
+@pytest.mark.parametrize("loss,lam1", [("ridge", 0.0), ("logistic", 0.0), ("ridge", 3e-3), ("logistic", 2e-3)])
+def test_gap_shares_add_up_to_the_gap_and_are_nonnegative(loss, lam1):
+    r = np.random.default_rng(77)
+    X = sparse_random(300, 40, 0.3, r)
+    y = (np.sign(r.standard_normal(300)) if loss == "logistic" else r.standard_normal(300)).astype(np.float32)
+    s = oracle.Solver(dense_to_csc(X), y, loss, 1e-2, chunk_bounds=[0, 7, 19, 40], lam1=lam1)
+    for e in range(3):
+        s.epoch(e)
+        share = oracle.primal_gap_shares(s.A, s.loss, s.v, s.y, s.x, s.lam, s.lam1)
+        assert share.min() >= -1e-15
+        assert abs(share.sum() - s.gap("fenchel")) <= 1e-12 * max(1.0, abs(s.primal()))
+        if lam1 == 0.0:
+            assert abs(share.sum() - s.gap("gradient")) <= 1e-12
+            # written out for the l2 regulariser alone: (z_j + lam w_j)^2 / (2 lam) with z = X^T grad f
+            u = np.array([(v - yy) if loss == "ridge" else -yy / (1.0 + math.exp(yy * v))
+                          for v, yy in zip(s.v.tolist(), y.astype(np.float64).tolist())]) / 300
+            z = X.T @ u
+            np.testing.assert_allclose(share, (z + 1e-2 * s.x) ** 2 / (2 * 1e-2), rtol=1e-9, atol=1e-18)
+        cg = s.chunk_gaps()
+        assert cg.shape == (3,)
+        np.testing.assert_allclose(cg, [share[0:7].sum(), share[7:19].sum(), share[19:40].sum()], rtol=1e-13)
+
+
+@pytest.mark.parametrize("lam1", [0.0, 5e-3])
+def test_gap_share_of_a_coordinate_is_zero_right_after_its_exact_update(lam1):
+    """For the ridge loss the update is the exact minimiser along the coordinate, so with the dual
+    candidate of the state right after it the coordinate's own share vanishes; the others' do not."""
+    r = np.random.default_rng(5)
+    X = sparse_random(200, 12, 0.5, r)
+    y = r.standard_normal(200).astype(np.float32)
+    A = dense_to_csc(X)
+    s = oracle.Solver(A, y, "ridge", 1e-2, chunk_bounds=list(range(13)), lam1=lam1)   # one coordinate per chunk
+    s.epoch(0)
+    for j in (3, 0, 11):
+        s.epoch(1, chunks=[j])
+        share = oracle.primal_gap_shares(A, s.loss, s.v, s.y, s.x, s.lam, s.lam1)
+        assert abs(share[j]) <= 1e-16 + 1e-12 * share.max()
+        assert share.max() > 1e-8
+
+
+def test_pass_over_selected_chunks_touches_only_them_and_all_chunks_is_an_epoch():
+    r = np.random.default_rng(6)
+    X = sparse_random(150, 30, 0.4, r)
+    y = np.sign(r.standard_normal(150)).astype(np.float32)
+    A = dense_to_csc(X)
+    bounds = [0, 10, 18, 30]
+    a = oracle.Solver(A, y, "logistic", 1e-2, chunk_bounds=bounds)
+    b = oracle.Solver(A, y, "logistic", 1e-2, chunk_bounds=bounds)
+    a.epoch(4)
+    b.epoch(4, chunks=[0, 1, 2])
+    assert np.array_equal(a.x, b.x) and np.array_equal(a.v, b.v)
+    before = b.x.copy()
+    b.epoch(5, chunks=[2, 0])
+    assert np.array_equal(b.x[10:18], before[10:18])                   # chunk 1 untouched
+    assert not np.array_equal(b.x[0:10], before[0:10]) and not np.array_equal(b.x[18:30], before[18:30])
+    assert sorted(b.last_perm.tolist()) == list(range(0, 10)) + list(range(18, 30))
+    assert b.last_perm[0] >= 18                                        # chunk 2 first, as asked
+    np.testing.assert_allclose(b.v, A.matvec(b.x), rtol=0, atol=1e-12)
+
+
+def test_selection_picks_the_largest_shares_and_the_selected_solve_reaches_the_optimum():
+    assert oracle.select_chunks([0.1, 0.5, 0.5, 0.0, 0.7], 3) == [4, 1, 2]
+    assert oracle.select_chunks([0.0, 0.0], 5) == [0, 1]
+    r = np.random.default_rng(8)
+    # block structure: the columns of the last chunk carry ten times the signal of the others
+    X = sparse_random(400, 24, 0.3, r)
+    w = r.standard_normal(24)
+    w[18:] *= 10.0
+    y = (X @ w + 0.01 * r.standard_normal(400)).astype(np.float32)
+    A = dense_to_csc(X)
+    bounds = [0, 6, 12, 18, 24]
+    ref = oracle.solve(A, y, "ridge", 1e-3, 400, tol=1e-10)
+    s = oracle.Solver(A, y, "ridge", 1e-3, chunk_bounds=bounds)
+    assert oracle.select_chunks(s.chunk_gaps(), 1) == [3]              # at the zero model the strong block has the largest share
+    passes, visits, gap = oracle.solve_selected(s, 0, 2000, 1e-10, refresh_every=3, keep=2)
+    assert gap <= 1e-10
+    assert visits < passes * 4                                          # part of the passes visited part of the chunks
+    assert abs(s.primal() - ref.primal()) <= 1e-9 * abs(ref.primal())
