@@ -227,6 +227,36 @@ int snap_block_order(uint64_t perm_seed, int64_t n_blocks, int64_t *order_out);
  * instead of 8. */
 int snap_get_stream_bytes(snap_handle *h, int64_t *bytes_per_pass);
 
+/* Processing part of the data in a round, chosen by its share in the duality gap (Section 3.2 names
+ * this as an alternative to sweeping all batches in turn; the measure is the duality gap of eq. (1)
+ * taken coordinate by coordinate).  Chunks are the units snap_get_chunks reports: the streamed batches,
+ * the groups of the group sweeps, or the one chunk of resident data.
+ *
+ * snap_epoch_chunks: one pass over the `count` listed chunks only (host int64 array, distinct numbers
+ * in [0, n_chunks)), in the order given; the permutation inside a chunk is the one snap_epoch would
+ * use with the same seed.  A streamed chunk that still sits in one of the two device buffers is not
+ * copied again.  Not supported by the dense tile sweeps (SNAP_EUNSUPPORTED).  After such a pass
+ * the stretches of snap_get_perm's output that belong to chunks not visited keep their earlier content.
+ *
+ * snap_chunk_gaps: shares_out (host, n_chunks doubles) receives every chunk's share of the duality
+ * gap at the current state, the sum over its coordinates j of g(w_j) + g*(-z_j) + w_j z_j with
+ * z_j = a_j . grad f(v), g(w) = (lambda/2) w^2 + lambda1 |w|; the shares are non-negative and add up to
+ * the gap (*gap_out, may be NULL).  Primal forms only (SNAP_EUNSUPPORTED otherwise); costs one pass
+ * over the matrix, as snap_duality_gap; synchronises.
+ *
+ * snap_solve_selected: passes with seeds seed0, seed0 + 1, ...; every refresh_every-th pass (>= 1; the
+ * first one included) visits all chunks and is followed by snap_chunk_gaps -- their sum is the
+ * stopping test against gap_tol -- and the passes in between visit only the `keep` chunks whose shares
+ * were largest at that evaluation, largest first (equal shares: lower number first).  *passes_out,
+ * *visits_out (chunk visits in total), *gap_out (last gap evaluated; infinity if none) may be NULL.
+ *
+ * snap_get_bytes_copied: bytes of chunk copies from host memory enqueued since creation. */
+int snap_epoch_chunks(snap_handle *h, uint64_t perm_seed, const int64_t *chunks, int64_t count);
+int snap_chunk_gaps(snap_handle *h, double *shares_out, double *gap_out);
+int snap_solve_selected(snap_handle *h, uint64_t seed0, int64_t max_passes, double gap_tol, int64_t refresh_every,
+                        int64_t keep, int64_t *passes_out, int64_t *visits_out, double *gap_out);
+int snap_get_bytes_copied(snap_handle *h, int64_t *total);
+
 /* Number of coordinates m and length of v. */
 int snap_get_dims(snap_handle *h, int64_t *n_coords, int64_t *shared_len);
 

@@ -25,7 +25,9 @@ LOSSES = {"ridge": RIDGE, "logistic": LOGISTIC, "hinge": HINGE}
 
 EXPORTS = ["snap_create", "snap_epoch", "snap_objective", "snap_duality_gap", "snap_predict", "snap_get_model",
            "snap_set_model", "snap_get_shared", "snap_recompute_shared", "snap_get_perm", "snap_get_epoch_stats",
-           "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_solve", "snap_perm_key", "snap_block_order", "snap_last_error", "snap_destroy"]
+           "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_solve", "snap_perm_key", "snap_block_order",
+           "snap_epoch_chunks", "snap_chunk_gaps", "snap_solve_selected", "snap_get_bytes_copied", "snap_last_error",
+           "snap_destroy"]
 
 
 class SnapMatrix(C.Structure):
@@ -85,6 +87,11 @@ def load_library():
         L.snap_get_chunks.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]
         L.snap_solve.argtypes = [C.c_void_p, C.c_uint64, C.c_int64, C.c_double, C.c_int64, C.POINTER(C.c_int64),
                                  C.POINTER(C.c_double)]
+        L.snap_epoch_chunks.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int64]
+        L.snap_chunk_gaps.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+        L.snap_solve_selected.argtypes = [C.c_void_p, C.c_uint64, C.c_int64, C.c_double, C.c_int64, C.c_int64,
+                                          C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        L.snap_get_bytes_copied.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.snap_perm_key.restype = C.c_uint32
         L.snap_perm_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
         L.snap_block_order.argtypes = [C.c_uint64, C.c_int64, C.c_void_p]
@@ -250,6 +257,31 @@ class Solver:
         e, g = C.c_int64(), C.c_double()
         _check(self._lib.snap_solve(self._h, seed0, max_epochs, gap_tol, check_every, C.byref(e), C.byref(g)))
         return e.value, g.value
+
+    def epoch_chunks(self, perm_seed: int, chunks) -> None:
+        """One pass over the listed chunks only, in that order."""
+        c = np.ascontiguousarray(chunks, dtype=np.int64)
+        _check(self._lib.snap_epoch_chunks(self._h, perm_seed, c.ctypes.data, c.size))
+
+    def chunk_gaps(self) -> np.ndarray:
+        """Share of every chunk in the duality gap at the current state (primal forms)."""
+        out = np.empty(len(self.chunk_bounds()) - 1, dtype=np.float64)
+        _check(self._lib.snap_chunk_gaps(self._h, out.ctypes.data, None))
+        return out
+
+    def solve_selected(self, seed0: int, max_passes: int, gap_tol: float, refresh_every: int, keep: int):
+        """Passes that visit all chunks every refresh_every-th time and otherwise the `keep` chunks with
+        the largest gap shares: (passes, chunk visits, last gap)."""
+        p, v, g = C.c_int64(), C.c_int64(), C.c_double()
+        _check(self._lib.snap_solve_selected(self._h, seed0, max_passes, gap_tol, refresh_every, keep, C.byref(p),
+                                             C.byref(v), C.byref(g)))
+        return p.value, v.value, g.value
+
+    def bytes_copied(self) -> int:
+        """Bytes of chunk copies from host memory enqueued since creation."""
+        b = C.c_int64()
+        _check(self._lib.snap_get_bytes_copied(self._h, C.byref(b)))
+        return b.value
 
     def stream_bytes(self) -> int:
         """Bytes copied from host memory by one pass over the data (0: resident)."""

@@ -95,6 +95,8 @@ static void destroy(snap_handle* h) {
     (void)hipFree(h->status);
     (void)hipFree(h->x_snap);
     (void)hipFree(h->v_snap);
+    (void)hipFree(h->share_bounds);
+    (void)hipFree(h->share_out);
     stream_free(h);
     dense_tiles_free(h);
     grouped_free(h);
@@ -502,6 +504,10 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         if (prof) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
         h->perm_stale = true;
     } else if (h->tiled) {
+        if (h->pass_list) {
+            set_error("a pass over part of the tiles is not supported by the dense tile sweeps");
+            return SNAP_EUNSUPPORTED;
+        }
         if (prof) SNAP_HIP(hipEventRecord(h->ev[1], h->compute));
         h->last_seed = perm_seed;
         SNAP_TRY(dense_tiles_epoch(h));
@@ -537,6 +543,93 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
             h->monitor_prev = now;
         }
     }
+    return SNAP_OK;
+}
+
+static int64_t chunk_count(const snap_handle* h) { return (h->grouped || h->tiled) ? h->n_groups : h->n_chunks; }
+
+int snap_epoch_chunks(snap_handle* h, uint64_t perm_seed, const int64_t* chunks, int64_t count) {
+    if (!h || count < 0 || (count > 0 && !chunks)) {
+        set_error("snap_epoch_chunks: need a handle and a list of chunks");
+        return SNAP_EINVAL;
+    }
+    const int64_t C = chunk_count(h);
+    std::vector<char> seen((size_t)C, 0);
+    for (int64_t i = 0; i < count; ++i) {
+        if (chunks[i] < 0 || chunks[i] >= C || seen[(size_t)chunks[i]]) {
+            set_error("snap_epoch_chunks: chunk numbers must lie in [0, n_chunks) and be distinct");
+            return SNAP_EINVAL;
+        }
+        seen[(size_t)chunks[i]] = 1;
+    }
+    if (count == 0) return SNAP_OK;
+    h->pass_list = chunks;
+    h->pass_count = count;
+    const int rc = snap_epoch(h, perm_seed);
+    h->pass_list = nullptr;
+    h->pass_count = 0;
+    return rc;
+}
+
+int snap_chunk_gaps(snap_handle* h, double* shares_out, double* gap_out) {
+    if (!h || !shares_out) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    SNAP_TRY(chunk_gap_shares(h, shares_out));
+    if (gap_out) {
+        double g = 0.0;
+        for (int64_t c = 0; c < chunk_count(h); ++c) g += shares_out[c];
+        *gap_out = g;
+    }
+    return SNAP_OK;
+}
+
+int snap_solve_selected(snap_handle* h, uint64_t seed0, int64_t max_passes, double gap_tol, int64_t refresh_every,
+                        int64_t keep, int64_t* passes_out, int64_t* visits_out, double* gap_out) {
+    if (!h || max_passes < 0 || refresh_every < 1 || keep < 0 || !(gap_tol >= 0.0)) {
+        set_error("snap_solve_selected: need a handle, max_passes >= 0, refresh_every >= 1, keep >= 0, gap_tol >= 0");
+        return SNAP_EINVAL;
+    }
+    const int64_t C = chunk_count(h);
+    std::vector<double> shares((size_t)C, 0.0);
+    std::vector<int64_t> chosen((size_t)C);
+    for (int64_t c = 0; c < C; ++c) chosen[(size_t)c] = c;
+    int64_t p = 0, visits = 0;
+    double gap = INFINITY;
+    while (p < max_passes) {
+        const bool full = p % refresh_every == 0;
+        if (full) {
+            SNAP_TRY(snap_epoch(h, seed0 + (uint64_t)p));
+            visits += C;
+        } else {
+            SNAP_TRY(snap_epoch_chunks(h, seed0 + (uint64_t)p, chosen.data(), (int64_t)chosen.size()));
+            visits += (int64_t)chosen.size();
+        }
+        ++p;
+        if (full) {
+            SNAP_TRY(snap_chunk_gaps(h, shares.data(), &gap));
+            if (gap <= gap_tol) break;
+            // the `keep` chunks with the largest shares, largest first; equal shares in index order
+            chosen.resize((size_t)C);
+            for (int64_t c = 0; c < C; ++c) chosen[(size_t)c] = c;
+            std::stable_sort(chosen.begin(), chosen.end(),
+                             [&](int64_t a, int64_t b) { return shares[(size_t)a] > shares[(size_t)b]; });
+            chosen.resize((size_t)std::min<int64_t>(keep, C));
+        }
+    }
+    if (passes_out) *passes_out = p;
+    if (visits_out) *visits_out = visits;
+    if (gap_out) *gap_out = gap;
+    return SNAP_OK;
+}
+
+int snap_get_bytes_copied(snap_handle* h, int64_t* total) {
+    if (!h || !total) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    *total = h->bytes_copied;
     return SNAP_OK;
 }
 

@@ -134,6 +134,12 @@ struct snap_handle {
     int64_t buf_chunk[2] = {-1, -1};     // chunk held (or being loaded) by each buffer
     bool buf_folded[2] = {false, false}; // labels already folded into that copy
     int64_t max_chunk_nnz = 0;
+    // a pass over part of the chunks (or groups): the list to visit, in order; null = all of them
+    const int64_t* pass_list = nullptr;
+    int64_t pass_count = 0;
+    int64_t bytes_copied = 0;            // streaming: bytes of chunk copies enqueued since creation
+    int64_t* share_bounds = nullptr;     // device [chunks + 1]: coordinate ranges for the gap shares
+    double* share_out = nullptr;         // device [chunks]
     hipEvent_t* ev_chunk = nullptr;      // profile: 4 events per chunk (copy begin/end, compute begin/end)
     bool chunk_events_valid = false;
 
@@ -241,6 +247,7 @@ int clamp_range(float* p, float lo, float hi, int64_t count, hipStream_t s);
 int objective(snap_handle* h, double* primal, double* dual, double* gap);
 // the quantity the solver decreases (P in primal form, -D in dual form), vectors only
 int monitor_value(snap_handle* h, double* value);
+int chunk_gap_shares(snap_handle* h, double* shares_out);   // host array, one entry per chunk (or group)
 
 int predict(snap_handle* h, const snap_matrix* X, float* out);
 int weights_to_host(snap_handle* h, float* w_out);

@@ -1046,9 +1046,12 @@ static int grouped_epoch_kind(snap_handle* h) {
     // the groups are visited in a seeded random order (keys of the epoch's seed under a reserved
     // chunk id, sorted with the group index as tie-break): on the click-log workload a fresh order
     // every epoch reaches a given duality gap in a fifth of the epochs a fixed order needs
-    const std::vector<int64_t> gorder = group_order(h->last_seed, G);
-    for (int64_t gi = 0; gi <= G; ++gi) {
-        const bool last = gi == G;
+    // ... or, for a pass over part of the groups, the caller's list
+    const std::vector<int64_t> gorder =
+        h->pass_list ? std::vector<int64_t>(h->pass_list, h->pass_list + h->pass_count) : group_order(h->last_seed, G);
+    const int64_t n_visit = (int64_t)gorder.size();
+    for (int64_t gi = 0; gi <= n_visit; ++gi) {
+        const bool last = gi == n_visit;
         const int64_t g = last ? G : gorder[(size_t)gi];
         const int64_t g0 = last ? 0 : h->gbounds_host[g], sz = last ? 0 : h->gbounds_host[g + 1] - g0;
         if (!last && sz == 0) continue;

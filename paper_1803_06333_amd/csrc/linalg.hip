@@ -518,6 +518,56 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
     return SNAP_OK;
 }
 
+// Share of every chunk (or group) of coordinates in the duality gap, primal forms (Section 3.2: the
+// importance measure for choosing what to process).  With u = grad f(v) the loss part of the Fenchel
+// gap vanishes and the rest is a sum over the coordinates of
+//     g(w_j) + g*(-z_j) + w_j z_j,   z_j = a_j . u,   g(w) = (lambda/2) w^2 + lambda1 |w|,
+// which for lambda1 = 0 is (z_j + lambda w_j)^2 / (2 lambda).  One workgroup per chunk, fixed order.
+__global__ void __launch_bounds__(LTPB)
+k_chunk_shares(const double* __restrict__ gdot, const float* __restrict__ x, const int64_t* __restrict__ bounds,
+               double inv_n, double lam, double lam1, double* __restrict__ out) {
+    __shared__ double scratch[LTPB / WAVE];
+    const int64_t c0 = bounds[blockIdx.x], c1 = bounds[blockIdx.x + 1];
+    double acc = 0.0;
+    for (int64_t j = c0 + threadIdx.x; j < c1; j += LTPB) {
+        const double z = gdot[j] * inv_n, w = (double)x[j];
+        if (lam1 == 0.0) {
+            const double t = z + lam * w;
+            acc += t * t / (2.0 * lam);
+        } else {
+            const double t = fmax(fabs(z) - lam1, 0.0);
+            acc += 0.5 * lam * w * w + lam1 * fabs(w) + t * t / (2.0 * lam) + w * z;
+        }
+    }
+    acc = block_sum_d(acc, scratch);
+    if (threadIdx.x == 0) out[blockIdx.x] = acc;
+}
+
+int chunk_gap_shares(snap_handle* h, double* shares_out) {
+    if (h->form != SNAP_PRIMAL) {
+        set_error("gap shares of the chunks are defined for the primal forms");
+        return SNAP_EUNSUPPORTED;
+    }
+    const bool by_group = h->grouped || h->tiled;
+    const int64_t C = by_group ? h->n_groups : h->n_chunks;
+    if (C <= 0) return SNAP_OK;
+    if (!h->share_bounds) {
+        std::vector<int64_t> b((size_t)C + 1);
+        for (int64_t c = 0; c < C; ++c) b[(size_t)c] = by_group ? h->gbounds_host[c] : h->chunks[c].c0;
+        b[(size_t)C] = h->m;
+        SNAP_HIP(hipMalloc(&h->share_bounds, ((size_t)C + 1) * sizeof(int64_t)));
+        SNAP_HIP(hipMalloc(&h->share_out, (size_t)C * sizeof(double)));
+        SNAP_HIP(hipMemcpy(h->share_bounds, b.data(), ((size_t)C + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    }
+    SNAP_TRY(h->grouped ? grouped_dots(h) : coord_dots(h));
+    hipLaunchKernelGGL(k_chunk_shares, dim3((unsigned)C), dim3(LTPB), 0, h->compute, h->gdot, h->x, h->share_bounds,
+                       1.0 / (double)h->n, h->lambda, h->lambda1, h->share_out);
+    SNAP_HIP(hipGetLastError());
+    SNAP_HIP(hipMemcpyAsync(shares_out, h->share_out, (size_t)C * sizeof(double), hipMemcpyDeviceToHost, h->compute));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    return SNAP_OK;
+}
+
 int monitor_value(snap_handle* h, double* value) {
     const double n = (double)h->n, lam = h->lambda;
     double* res = h->red.host;

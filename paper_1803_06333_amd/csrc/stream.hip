@@ -50,6 +50,7 @@ static int enqueue_copy(snap_handle* h, int64_t ch, int b, bool profile) {
     SNAP_HIP(hipStreamWaitEvent(h->copy, h->ev_free[b], 0));
     if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 0], h->copy));
     if (count > 0) {
+        h->bytes_copied += (int64_t)(count * (h->stream_unit ? sizeof(uint32_t) : sizeof(uint32_t) + sizeof(float)));
         SNAP_HIP(hipMemcpyAsync(h->buf_idx[b], h->host_idx + ck.nnz0, count * sizeof(uint32_t), hipMemcpyHostToDevice,
                                 h->copy));
         if (!h->stream_unit)       // (pattern-only data: the value buffers hold ones for good)
@@ -64,26 +65,32 @@ static int enqueue_copy(snap_handle* h, int64_t ch, int b, bool profile) {
 }
 
 int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profile) {
+    // the chunks to visit: all of them in order, or the caller's list (Section 3.2: a round may process
+    // part of the data)
+    const int64_t C = h->pass_list ? h->pass_count : h->n_chunks;
+    if (C == 0) return SNAP_OK;
     if (!h->streaming) {
         ChunkView cv{h->ptr, h->idx, h->val, 0, 0, h->m};
         return fn(h, 0, cv, arg);
     }
-    profile = profile && h->ev_chunk != nullptr;
-    const int64_t C = h->n_chunks;
-    int b = h->buf_chunk[0] == 0 ? 0 : (h->buf_chunk[1] == 0 ? 1 : -1);
-    if (b < 0 || profile) {          // (a profiled pass times its own copy of chunk 0)
+    auto chunk_at = [&](int64_t i) { return h->pass_list ? h->pass_list[i] : i; };
+    profile = profile && h->ev_chunk != nullptr && !h->pass_list;
+    const int64_t first = chunk_at(0);
+    int b = h->buf_chunk[0] == first ? 0 : (h->buf_chunk[1] == first ? 1 : -1);
+    if (b < 0 || profile) {          // (a profiled pass times its own copy of the first chunk)
         b = b < 0 ? 0 : b;
-        SNAP_TRY(enqueue_copy(h, 0, b, profile));
+        SNAP_TRY(enqueue_copy(h, first, b, profile));
     }
-    for (int64_t ch = 0; ch < C; ++ch) {
+    for (int64_t i = 0; i < C; ++i) {
+        const int64_t ch = chunk_at(i);
         const int nb = 1 - b;
         const snap_handle::Chunk& ck = h->chunks[ch];
-        if (C > 1) {
-            // the next chunk (after the last one: chunk 0 again, for the next pass) goes to the other
-            // buffer while this one is processed
-            const int64_t next = ch + 1 < C ? ch + 1 : 0;
-            SNAP_TRY(enqueue_copy(h, next, nb, profile && ch + 1 < C));
-        }
+        // the next chunk (after the last one: the first again, for the next pass) goes to the other buffer
+        // while this one is processed -- unless it still sits there from an earlier pass (a working
+        // set of two chunks is copied once)
+        const int64_t next = i + 1 < C ? chunk_at(i + 1) : first;
+        if (next != ch && (h->buf_chunk[nb] != next || profile))
+            SNAP_TRY(enqueue_copy(h, next, nb, profile && i + 1 < C));
         SNAP_HIP(hipStreamWaitEvent(h->compute, h->ev_copied[b], 0));
         if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 2], h->compute));
         if (fold && h->kind == K_PRIMAL_LOGISTIC && !h->buf_folded[b]) {
@@ -97,6 +104,7 @@ int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profil
         b = nb;
     }
     if (profile) h->chunk_events_valid = true;
+    else if (h->pass_list) h->chunk_events_valid = false;
     // The pass ends with the host waiting for the copy stream (by then only the fetch of chunk 0 for
     // the next pass is outstanding).  Measured: when the host instead runs a whole pass ahead of the
     // copy stream, the copy commands and the kernels stop overlapping (68 ms per chunk instead of 40

@@ -309,6 +309,123 @@ def test_streamed_epochs_match_oracle_and_resident(name, chunk_bytes, budget, un
     r.close()
 
 
+# ---------------------------------------------------------------------------------------------
+# passes over part of the chunks, chosen by their share in the duality gap (Section 3.2)
+def test_chunk_gap_shares_match_the_oracle_streamed_and_grouped():
+    # streamed chunks, at a model a few epochs in
+    p = problem("stream_uniform_logistic")
+    q = _pinned(p)
+    A = oracle.Matrix.from_problem(p)
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20)
+    bounds = g.chunk_bounds()
+    o = oracle.Solver(A, p.y.numpy(), p.loss, p.lam, chunk_bounds=bounds)
+    for e in range(3):
+        o.epoch(e)
+    g.set_model(o.x.astype(np.float32))
+    chk = oracle.Solver(A, p.y.numpy(), p.loss, p.lam, chunk_bounds=bounds)
+    chk.x[:] = o.x.astype(np.float32)
+    chk.v[:] = chk.shared_from_model()
+    want = chk.chunk_gaps()
+    got = g.chunk_gaps()
+    assert got.shape == want.shape and got.min() >= 0.0
+    np.testing.assert_allclose(got, want, rtol=1e-3, atol=1e-3 * want.max())
+    assert rel(got.sum(), g.duality_gap()) <= 1e-9          # the shares add up to the gap the library reports
+    g.close()
+    # groups of the exact sweeps, with an l1 term (Fenchel form of the shares)
+    p = _onehot_variant("logistic", True)
+    groups = p.meta["field_starts"] + [p.d]
+    g = gpu_solver(p, group_bounds=groups, lam1=2e-4)
+    o = oracle.Solver(oracle.Matrix.from_problem(p), p.y.numpy(), p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True,
+                      lam1=2e-4)
+    for e in range(2):
+        g.epoch(e)
+        o.epoch(e)
+    got, want = g.chunk_gaps(), o.chunk_gaps()
+    np.testing.assert_allclose(got, want, rtol=2e-3, atol=1e-3 * want.max())
+    assert rel(got.sum(), g.duality_gap()) <= 1e-6
+    g.close()
+    # dual form: not defined
+    p = problem("cfg3_zipf_svm")
+    g = gpu_solver(p)
+    with pytest.raises(snap.SnapError) as e:
+        g.chunk_gaps()
+    assert e.value.code == -2
+    g.close()
+
+
+def test_pass_over_selected_groups_equals_the_oracle():
+    p = _onehot_variant("logistic", True)
+    groups = p.meta["field_starts"] + [p.d]
+    g = gpu_solver(p, group_bounds=groups)
+    o = oracle.Solver(oracle.Matrix.from_problem(p), p.y.numpy(), p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    g.epoch(0)
+    o.epoch(0)
+    for e, chunks in enumerate([[5, 0, 17], [38], [20, 21, 22, 1], list(range(39))]):
+        before = g.model()[1].copy()
+        g.epoch_chunks(10 + e, chunks)
+        o.epoch(10 + e, chunks=chunks)
+        _, x = g.model()
+        assert relnorm(x, o.x) <= 2e-5
+        assert relnorm(g.shared(), o.v) <= 2e-5
+        untouched = np.ones(p.d, dtype=bool)
+        for c in chunks:
+            untouched[groups[c]:groups[c + 1]] = False
+        assert np.array_equal(x[untouched], before[untouched])
+    g.epoch_chunks(99, [])                                   # a pass over nothing
+    assert np.array_equal(g.model()[1], x)
+    for bad in ([39], [-1], [3, 3]):
+        with pytest.raises(snap.SnapError) as e:
+            g.epoch_chunks(0, bad)
+        assert e.value.code == -1
+    g.close()
+
+
+def test_streamed_pass_over_selected_chunks_and_the_selected_solve():
+    p = problem("stream_uniform_logistic")
+    q = _pinned(p)
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20)
+    bounds = g.chunk_bounds()
+    C = len(bounds) - 1
+    chunk_nnz = np.diff(p.ptr.numpy()[bounds])
+    o = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=bounds)
+    g.epoch(0)
+    o.epoch(0)
+    assert g.bytes_copied() >= 4 * p.nnz
+    # a working set of two chunks is copied at most once, however often it is swept
+    base = g.bytes_copied()
+    for e in range(4):
+        g.epoch_chunks(20 + e, [C - 1, 2])
+        o.epoch(20 + e, chunks=[C - 1, 2])
+        gp = g.perm().astype(np.int64)                    # chunk by chunk; the visited ones hold the new order
+        n_last = bounds[C] - bounds[C - 1]
+        assert np.array_equal(gp[bounds[C - 1]:bounds[C]], o.last_perm[:n_last])
+        assert np.array_equal(gp[bounds[2]:bounds[3]], o.last_perm[n_last:])
+    assert g.bytes_copied() - base <= 4 * (chunk_nnz[C - 1] + chunk_nnz[2])
+    _, x = g.model()
+    chk = oracle.Solver(A, y, p.loss, p.lam)
+    chk.x[:] = x
+    assert relnorm(g.shared(), chk.shared_from_model()) <= 1e-4
+    assert rel(g.objective(), o.primal()) <= 1e-3            # asynchronous against sequential, five passes in
+    # three chunks rotate through the two buffers
+    base = g.bytes_copied()
+    g.epoch_chunks(30, [1, 3, 0])
+    assert 0 < g.bytes_copied() - base <= 4 * (chunk_nnz[1] + chunk_nnz[3] + chunk_nnz[0] + chunk_nnz[1])
+    g.close()
+    # the selected solve ends at the same optimum as plain epochs, with fewer chunk visits per pass
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20)
+    target = oracle.solve(A, y, p.loss, p.lam, epochs=500, tol=1e-6, chunk_bounds=bounds).primal()
+    passes, visits, gap = g.solve_selected(0, 400, 1e-5, 4, max(2, C // 2))
+    assert gap <= 1e-5 and passes < 400
+    assert visits < passes * C
+    assert rel(g.objective(), target) <= 1e-4
+    o2 = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=bounds)
+    po, vo, go = oracle.solve_selected(o2, 0, 400, 1e-5, 4, max(2, C // 2))
+    assert go <= 1e-5 and abs(po - passes) <= max(4, passes // 4)          # the sequential oracle needs about as many
+    g.close()
+
+
 def test_streaming_needs_pinned_memory():
     p = problem("cfg1_sparse_logistic")
     with pytest.raises(snap.SnapError) as e:
