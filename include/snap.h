@@ -128,6 +128,12 @@ typedef struct {
                                     turn out short (more than 8 + 10 nnz_covered / n_rows of them).
                                     0: automatic, 1: required (error when nothing is found), 2: off.
                                     snap_get_chunks reports what was found. */
+    int host_keys;               /* 1: the 32-bit keys of the epoch order are generated by host threads into
+                                    pinned memory and copied to the device on a stream of their own, the third
+                                    pipeline stage of Section 3.2 (the host works on the keys of a chunk while
+                                    the device sweeps the one before and the copy engine moves the next); the
+                                    device only sorts.  0 (default): generated on the device, which is faster
+                                    here.  Same generator, same order either way. */
 } snap_options;
 
 /* Per-epoch figures gathered when options.profile = 1 (milliseconds of device time).  With group

@@ -40,7 +40,7 @@ class SnapOptions(C.Structure):
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p), ("refresh_v_every", C.c_int),
                 ("profile", C.c_int), ("adaptive", C.c_int), ("damping", C.c_float),
                 ("max_inflight_nnz", C.c_int64), ("group_bounds", C.c_void_p), ("n_groups", C.c_int64),
-                ("lambda1", C.c_double), ("dense_tiles", C.c_int), ("auto_groups", C.c_int)]
+                ("lambda1", C.c_double), ("dense_tiles", C.c_int), ("auto_groups", C.c_int), ("host_keys", C.c_int)]
 
 
 class SnapEpochStats(C.Structure):
@@ -151,7 +151,7 @@ class Solver:
                  form: int = FORM_AUTO, device_budget_bytes: int = 0, chunk_bytes: int = 0, compute_stream: int = 0,
                  copy_stream: int = 0, refresh_v_every: int = 0, profile: bool = False, adaptive=None,
                  damping: float = 0.0, max_inflight_nnz: int = 0, group_bounds=None, lam1: float = 0.0,
-                 dense_tiles=None, auto_groups=None):
+                 dense_tiles=None, auto_groups=None, host_keys: bool = False):
         self._lib = load_library()
         self._h = C.c_void_p()
         if torch is not None and isinstance(val, torch.Tensor) and val.is_cuda:
@@ -168,6 +168,7 @@ class Solver:
         opt.damping, opt.max_inflight_nnz, opt.lambda1 = damping, max_inflight_nnz, lam1
         opt.dense_tiles = 0 if dense_tiles is None else (1 if dense_tiles else 2)
         opt.auto_groups = 0 if auto_groups is None else (1 if auto_groups else 2)
+        opt.host_keys = int(bool(host_keys))
         if group_bounds is not None:
             gb = np.ascontiguousarray(group_bounds, dtype=np.int64)
             opt.group_bounds, opt.n_groups = gb.ctypes.data, gb.size - 1

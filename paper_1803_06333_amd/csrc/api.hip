@@ -103,6 +103,7 @@ static void destroy(snap_handle* h) {
     for (auto& e : h->ev)
         if (e) (void)hipEventDestroy(e);
     sorter_free(h->sorter);
+    host_keys_free(h);
     reducer_free(h->red);
     delete[] h->chunks;
     delete h;
@@ -138,7 +139,7 @@ static int create_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void
 static int library_stream(int device, int which, hipStream_t* out) {
     constexpr int MAX_DEVICES = 64;
     static std::mutex lock;
-    static hipStream_t streams[MAX_DEVICES][2] = {};
+    static hipStream_t streams[MAX_DEVICES][3] = {};
     if (device < 0 || device >= MAX_DEVICES) {
         set_error("device index %d out of range", device);
         return SNAP_EINVAL;
@@ -155,6 +156,9 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     else SNAP_TRY(library_stream(h->device, 0, &h->compute));
     if (h->opt.copy_stream) h->copy = (hipStream_t)h->opt.copy_stream;
     else SNAP_TRY(library_stream(h->device, 1, &h->copy));
+    // host-made keys travel on a stream of their own: behind the copy of a whole chunk they would
+    // hold up the sweep of the chunk they belong to
+    if (h->opt.host_keys) SNAP_TRY(library_stream(h->device, 2, &h->hk_stream));
     for (auto& e : h->ev) SNAP_HIP(hipEventCreate(&e));
     SNAP_TRY(reducer_alloc(h->red));
     SNAP_HIP(hipMalloc(&h->status, sizeof(uint32_t)));
@@ -272,6 +276,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_TRY(fill_zero(h->perm, (size_t)m * sizeof(uint32_t), h->compute));
     SNAP_TRY(fill_zero(h->keys, (size_t)m * sizeof(uint32_t), h->compute));
     SNAP_TRY(sorter_alloc(h->sorter, h->max_chunk_m));
+    if (h->opt.host_keys) SNAP_TRY(host_keys_alloc(h, h->max_chunk_m));
     SNAP_HIP(hipMalloc(&h->order, (size_t)(h->max_chunk_m ? h->max_chunk_m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->lstate, (size_t)(h->max_large + 1) * sizeof(LargeState)));
     SNAP_HIP(hipMalloc(&h->item_start, (size_t)(h->max_large + 2) * sizeof(int64_t)));

@@ -134,6 +134,13 @@ struct snap_handle {
     int64_t buf_chunk[2] = {-1, -1};     // chunk held (or being loaded) by each buffer
     bool buf_folded[2] = {false, false}; // labels already folded into that copy
     int64_t max_chunk_nnz = 0;
+    // keys of the epoch order made on the host (options.host_keys): two pinned host buffers and their
+    // device twins, used in turn
+    uint32_t* hk_host[2] = {nullptr, nullptr};
+    uint32_t* hk_dev[2] = {nullptr, nullptr};
+    hipEvent_t hk_copied[2] = {nullptr, nullptr}, hk_taken[2] = {nullptr, nullptr};
+    int hk_slot = 0;
+    hipStream_t hk_stream = nullptr;
     // a pass over part of the chunks (or groups): the list to visit, in order; null = all of them
     const int64_t* pass_list = nullptr;
     int64_t pass_count = 0;
@@ -209,6 +216,8 @@ int sorter_alloc(Sorter& s, int64_t max_m);
 void sorter_free(Sorter& s);
 // keys_out[c] = key(seed, chunk, c) for c in [0, m); order_out = coordinates sorted by (key, c);
 // part_out = the same order stably partitioned by cls[c0 + c] (class 0 first); either may be null.
+int host_keys_alloc(snap_handle* h, int64_t max_m);   // options.host_keys: pinned key buffers for make_permutation
+void host_keys_free(snap_handle* h);
 int make_permutation(snap_handle* h, uint64_t seed, uint32_t chunk, int64_t c0, int64_t m,
                      uint32_t* keys_out, uint32_t* order_out, uint32_t* part_out);
 

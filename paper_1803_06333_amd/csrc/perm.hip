@@ -8,6 +8,10 @@
 #include "common.h"
 #include "perm_key.h"
 
+#include <algorithm>
+#include <thread>
+#include <vector>
+
 namespace snap {
 
 constexpr int RADIX_BITS = 8;
@@ -175,6 +179,63 @@ static int radix_pass(snap_handle* h, uint32_t*& ka, uint32_t*& va, uint32_t*& k
     return SNAP_OK;
 }
 
+// ---- keys made on the host (options.host_keys): the third pipeline stage of Section 3.2 --------------
+// Host threads fill a pinned buffer with the chunk's keys (the same counter-based generator as the
+// device's, so the thread count does not matter), a stream of its own takes it to the device, and a small
+// kernel hands the keys to the sorter.  Two buffers are used in turn: the host may prepare the keys of a
+// chunk while the copy of the previous chunk's keys is still under way; since the calls that enqueue a
+// chunk's work return long before the device gets to it, this overlaps with the device's sweep of the
+// chunk before and with the copy engine's transfer of the one after.
+__global__ void k_take_keys(const uint32_t* __restrict__ in, uint32_t m, uint32_t* __restrict__ keys,
+                            uint32_t* __restrict__ vals, uint32_t* __restrict__ keys_copy) {
+    for (uint64_t c = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; c < m; c += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t k = in[c];
+        keys[c] = k;
+        vals[c] = (uint32_t)c;
+        if (keys_copy) keys_copy[c] = k;
+    }
+}
+
+int host_keys_alloc(snap_handle* h, int64_t max_m) {
+    const size_t bytes = (size_t)(max_m > 0 ? max_m : 1) * sizeof(uint32_t);
+    for (int i = 0; i < 2; ++i) {
+        SNAP_HIP(hipHostMalloc(&h->hk_host[i], bytes, hipHostMallocDefault));
+        SNAP_HIP(hipMalloc(&h->hk_dev[i], bytes));
+        SNAP_HIP(hipEventCreateWithFlags(&h->hk_copied[i], hipEventDisableTiming));
+        SNAP_HIP(hipEventCreateWithFlags(&h->hk_taken[i], hipEventDisableTiming));
+    }
+    return SNAP_OK;
+}
+
+void host_keys_free(snap_handle* h) {
+    for (int i = 0; i < 2; ++i) {
+        if (h->hk_host[i]) (void)hipHostFree(h->hk_host[i]);
+        (void)hipFree(h->hk_dev[i]);
+        if (h->hk_copied[i]) (void)hipEventDestroy(h->hk_copied[i]);
+        if (h->hk_taken[i]) (void)hipEventDestroy(h->hk_taken[i]);
+        h->hk_host[i] = h->hk_dev[i] = nullptr;
+        h->hk_copied[i] = h->hk_taken[i] = nullptr;
+    }
+}
+
+static void host_fill_keys(uint32_t* out, uint64_t seed, uint32_t chunk, uint32_t m) {
+    const uint64_t base = perm_key_base(seed, chunk);
+    auto fill = [=](uint32_t lo, uint32_t hi) {
+        for (uint32_t c = lo; c < hi; ++c) out[c] = perm_key(base, c);
+    };
+    const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
+    const unsigned threads = (unsigned)std::min<uint64_t>(std::min(16u, hw), std::max<uint64_t>(1, (uint64_t)m / 65536));
+    if (threads <= 1) {
+        fill(0, m);
+        return;
+    }
+    std::vector<std::thread> pool;
+    const uint32_t per = (m + threads - 1) / threads;
+    for (unsigned t = 1; t < threads; ++t) pool.emplace_back(fill, std::min(m, t * per), std::min(m, (t + 1) * per));
+    fill(0, std::min(m, per));
+    for (auto& th : pool) th.join();
+}
+
 int make_permutation(snap_handle* h, uint64_t seed, uint32_t chunk, int64_t c0, int64_t m, uint32_t* keys_out,
                      uint32_t* order_out, uint32_t* part_out) {
     if (m <= 0) return SNAP_OK;
@@ -186,7 +247,21 @@ int make_permutation(snap_handle* h, uint64_t seed, uint32_t chunk, int64_t c0, 
     uint32_t *ka = s.keys_a, *va = s.vals_a, *kb = s.keys_b, *vb = s.vals_b;
     const uint32_t mm = (uint32_t)m;
     const int grid = (int)((m + 255) / 256 < 4096 ? (m + 255) / 256 : 4096);
-    hipLaunchKernelGGL(k_make_keys, dim3(grid), dim3(256), 0, h->compute, seed, chunk, mm, ka, va, keys_out);
+    if (h->hk_host[0]) {
+        const int sl = h->hk_slot;
+        h->hk_slot ^= 1;
+        SNAP_HIP(hipEventSynchronize(h->hk_copied[sl]));             // the last copy out of this host buffer is done
+        host_fill_keys(h->hk_host[sl], seed, chunk, mm);
+        SNAP_HIP(hipStreamWaitEvent(h->hk_stream, h->hk_taken[sl], 0));  // ... and the sorter has taken the device twin's last content
+        SNAP_HIP(hipMemcpyAsync(h->hk_dev[sl], h->hk_host[sl], (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice,
+                                h->hk_stream));
+        SNAP_HIP(hipEventRecord(h->hk_copied[sl], h->hk_stream));
+        SNAP_HIP(hipStreamWaitEvent(h->compute, h->hk_copied[sl], 0));
+        hipLaunchKernelGGL(k_take_keys, dim3(grid), dim3(256), 0, h->compute, h->hk_dev[sl], mm, ka, va, keys_out);
+        SNAP_HIP(hipEventRecord(h->hk_taken[sl], h->compute));
+    } else {
+        hipLaunchKernelGGL(k_make_keys, dim3(grid), dim3(256), 0, h->compute, seed, chunk, mm, ka, va, keys_out);
+    }
     for (int shift = 0; shift < 32; shift += RADIX_BITS) SNAP_TRY(radix_pass(h, ka, va, kb, vb, mm, shift, nullptr));
     if (order_out)
         SNAP_HIP(hipMemcpyAsync(order_out, va, (size_t)m * sizeof(uint32_t), hipMemcpyDeviceToDevice, h->compute));

@@ -426,6 +426,38 @@ def test_streamed_pass_over_selected_chunks_and_the_selected_solve():
     g.close()
 
 
+def test_keys_made_on_the_host_give_the_same_epoch_order():
+    """options.host_keys: the keys come from host threads through pinned memory and the copy stream
+    (third pipeline stage of Section 3.2); generator and order are the same as with device-made keys."""
+    # resident, a permutation long enough for several host threads, and many epochs through the two buffers
+    p = datagen.uniform_sparse_logistic(n=3_000, d=300_000, k=2, seed=31)
+    g = gpu_solver(p, host_keys=True)
+    r = gpu_solver(p)
+    for e in (0, 1, 2, 7):
+        g.epoch(e)
+        r.epoch(e)
+        pg, kg = g.perm(want_keys=True)
+        pr, kr = r.perm(want_keys=True)
+        assert np.array_equal(kg, kr) and np.array_equal(pg, pr)
+    assert np.array_equal(pg.astype(np.int64), oracle.permutation(7, p.d))
+    g.close()
+    r.close()
+    # streamed: chunk by chunk, against the chunked oracle, and the solver still converges
+    p = problem("stream_uniform_logistic")
+    q = _pinned(p)
+    A = oracle.Matrix.from_problem(p)
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, host_keys=True)
+    bounds = g.chunk_bounds()
+    o = oracle.Solver(A, p.y.numpy(), p.loss, p.lam, chunk_bounds=bounds)
+    for e in range(30):
+        g.epoch(e)
+        o.epoch(e)
+        assert np.array_equal(g.perm().astype(np.int64), o.last_perm)
+    target = oracle.solve(A, p.y.numpy(), p.loss, p.lam, epochs=500, tol=1e-6, chunk_bounds=bounds).primal()
+    assert rel(g.objective(), target) <= 1e-4
+    g.close()
+
+
 def test_streaming_needs_pinned_memory():
     p = problem("cfg1_sparse_logistic")
     with pytest.raises(snap.SnapError) as e:
