@@ -247,8 +247,9 @@ int snap_get_stream_bytes(snap_handle *h, int64_t *bytes_per_pass);
  * snap_chunk_gaps: shares_out (host, n_chunks doubles) receives every chunk's share of the duality
  * gap at the current state, the sum over its coordinates j of g(w_j) + g*(-z_j) + w_j z_j with
  * z_j = a_j . grad f(v), g(w) = (lambda/2) w^2 + lambda1 |w|; the shares are non-negative and add up to
- * the gap (*gap_out, may be NULL).  Primal forms only (SNAP_EUNSUPPORTED otherwise); costs one pass
- * over the matrix, as snap_duality_gap; synchronises.
+ * the gap (*gap_out, may be NULL).  Dual forms: the sum over the chunk's examples i of
+ * (1/n) [ l(m_i) + l*(-alpha_i) + alpha_i m_i ] with the margin m_i = y_i x_i . v / (lambda n) -- the
+ * same properties.  Costs one pass over the matrix, as snap_duality_gap; synchronises.
  *
  * snap_solve_selected: passes with seeds seed0, seed0 + 1, ...; every refresh_every-th pass (>= 1; the
  * first one included) visits all chunks and is followed by snap_chunk_gaps -- their sum is the

@@ -236,10 +236,12 @@ class Solver:
         return primal_gap(self.A, self.loss, self.v, self.y, self.x, self.lam, form, self.lam1)
 
     def chunk_gaps(self) -> np.ndarray:
-        """Share of every chunk in the duality gap at the current state (primal forms): the sum of
-        its coordinates' shares (primal_gap_shares)."""
-        assert self.form == "primal"
-        share = primal_gap_shares(self.A, self.loss, self.v, self.y, self.x, self.lam, self.lam1)
+        """Share of every chunk in the duality gap at the current state: the sum of its coordinates'
+        shares (primal_gap_shares, dual_gap_shares)."""
+        if self.form == "primal":
+            share = primal_gap_shares(self.A, self.loss, self.v, self.y, self.x, self.lam, self.lam1)
+        else:
+            share = dual_gap_shares(self.A, self.loss, self.x, self.v, self.y, self.lam)
         return np.array([share[self.bounds[c]:self.bounds[c + 1]].sum() for c in range(len(self.bounds) - 1)])
 
     def predict(self, X: Matrix) -> np.ndarray:
@@ -277,6 +279,24 @@ def primal_gap_shares(A: Matrix, loss: int, v, y, w, lam: float, lam1: float = 0
     z = A.rmatvec(u)
     gstar = np.maximum(np.abs(z) - lam1, 0.0) ** 2 / (2.0 * lam)
     return 0.5 * lam * w * w + lam1 * np.abs(w) + gstar + w * z
+
+
+def dual_gap_shares(A: Matrix, loss: int, alpha, v, y, lam: float) -> np.ndarray:
+    """The gap P(w(alpha)) - D(alpha) of the dual forms example by example.  With w = v / (lam n) the
+    regulariser's part is lam ||w||^2 = (1/n) sum_i alpha_i m_i, m_i = y_i x_i . w, so
+        P - D = (1/n) sum_i [ l(m_i) + l*(-alpha_i) + alpha_i m_i ],
+    each bracket non-negative by the Fenchel-Young inequality.  Hinge: l(m) = max(0, 1 - m),
+    l*(-a) = -a on [0, 1]; logistic: l(m) = log(1 + exp(-m)), l*(-a) = a ln a + (1 - a) ln(1 - a)."""
+    alpha, v, y = _f64(alpha), _f64(v), _f32(y).astype(np.float64)
+    n = A.n
+    m = y * A.matvec(v / (lam * n))
+    if loss == HINGE:
+        term = np.maximum(0.0, 1.0 - m) - alpha
+    else:
+        with np.errstate(divide="ignore", invalid="ignore"):
+            ent = np.where(alpha > 0, alpha * np.log(alpha), 0.0) + np.where(alpha < 1, (1 - alpha) * np.log1p(-alpha), 0.0)
+        term = np.logaddexp(0.0, -m) + ent
+    return (term + alpha * m) / n
 
 
 def select_chunks(shares, keep: int):

@@ -265,7 +265,7 @@ class Solver:
         _check(self._lib.snap_epoch_chunks(self._h, perm_seed, c.ctypes.data, c.size))
 
     def chunk_gaps(self) -> np.ndarray:
-        """Share of every chunk in the duality gap at the current state (primal forms)."""
+        """Share of every chunk in the duality gap at the current state."""
         out = np.empty(len(self.chunk_bounds()) - 1, dtype=np.float64)
         _check(self._lib.snap_chunk_gaps(self._h, out.ctypes.data, None))
         return out

@@ -119,12 +119,17 @@ int fold_labels(snap_handle* h, uint32_t* idx, int64_t count, hipStream_t s) {
 // compressed data: out[idx[k]] += mult(c) * val[k] for every nonzero k of every coordinate c in
 // [c0, c1); mult(c) = x[c] (primal) or y[c] x[c] (dual).  Each workgroup takes a block of
 // consecutive nonzeros and locates their coordinates by bisection of ptr.
+// OUT = double: the sums are taken in fp64 (hardware atomics) and rounded to fp32 once at the end, so
+// the result does not depend on the order of the additions beyond the last bit -- with fp32 sums a
+// coordinate-by-coordinate order can lose four digits where large terms cancel (a trained dual
+// model: partial sums of a frequent feature a few thousand times its final value).
 constexpr int64_t AXPY_BLOCK = 4096;
 
+template <typename OUT>
 __global__ void __launch_bounds__(LTPB)
 k_scatter_axpy(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const float* __restrict__ val,
                int64_t nnz_base, int64_t c0, int64_t c1, int64_t k0, int64_t k1, const float* __restrict__ x,
-               const float* __restrict__ ymul, uint32_t idx_mask, float* out) {
+               const float* __restrict__ ymul, uint32_t idx_mask, OUT* out) {
     const int64_t b0 = k0 + (int64_t)blockIdx.x * AXPY_BLOCK, b1 = min(k1, b0 + AXPY_BLOCK);
     // coordinate of the block's first nonzero: largest c in [c0, c1) with ptr[c] <= b0
     int64_t lo = c0, hi = c1;
@@ -144,8 +149,13 @@ k_scatter_axpy(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx
             if (ptr[mid] <= k) l = mid; else r = mid;
         }
         const float mult = ymul ? ymul[l] * x[l] : x[l];
-        if (mult != 0.0f) unsafeAtomicAdd(out + (idx[k - nnz_base] & idx_mask), mult * val[k - nnz_base]);
+        if (mult != 0.0f) unsafeAtomicAdd(out + (idx[k - nnz_base] & idx_mask), (OUT)mult * (OUT)val[k - nnz_base]);
     }
+}
+
+__global__ void k_round_to_float(const double* __restrict__ in, float* __restrict__ out, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = (float)in[i];
 }
 
 // dense, coordinate-major (element e of coordinate c at A[c*len + e]): out[e] = sum_c mult(c) A[c*len+e]
@@ -162,13 +172,18 @@ k_dense_axpy_all(const float* __restrict__ A, int64_t m, int64_t len, const floa
     out[e] = (float)acc;
 }
 
-static int axpy_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void*) {
+// user: fp64 accumulator of vlen entries, or null for sums straight into v
+static int axpy_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void* user) {
     const float* ymul = h->form == SNAP_DUAL ? h->y : nullptr;
     const snap_handle::Chunk& ck = h->chunks[chunk];
     if (ck.nnz1 == ck.nnz0) return SNAP_OK;
     const int64_t nb = (ck.nnz1 - ck.nnz0 + AXPY_BLOCK - 1) / AXPY_BLOCK;
-    hipLaunchKernelGGL(k_scatter_axpy, dim3((unsigned)nb), dim3(LTPB), 0, h->compute, cv.ptr, cv.idx, cv.val,
-                       cv.nnz_base, cv.c0, cv.c1, ck.nnz0, ck.nnz1, h->x, ymul, ~LABEL_BIT, h->v);
+    if (user)
+        hipLaunchKernelGGL((k_scatter_axpy<double>), dim3((unsigned)nb), dim3(LTPB), 0, h->compute, cv.ptr, cv.idx,
+                           cv.val, cv.nnz_base, cv.c0, cv.c1, ck.nnz0, ck.nnz1, h->x, ymul, ~LABEL_BIT, (double*)user);
+    else
+        hipLaunchKernelGGL((k_scatter_axpy<float>), dim3((unsigned)nb), dim3(LTPB), 0, h->compute, cv.ptr, cv.idx,
+                           cv.val, cv.nnz_base, cv.c0, cv.c1, ck.nnz0, ck.nnz1, h->x, ymul, ~LABEL_BIT, h->v);
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
 }
@@ -181,8 +196,26 @@ int recompute_shared(snap_handle* h) {
         SNAP_HIP(hipGetLastError());
         return SNAP_OK;
     }
-    SNAP_TRY(fill_zero(h->v, (size_t)h->vlen * sizeof(float), h->compute));
-    return for_each_chunk(h, axpy_chunk, nullptr, true, false);
+    // fp64 sums in a buffer held for this call only; if the device has no room for it, fp32 sums in v
+    double* acc = nullptr;
+    const size_t acc_bytes = (size_t)h->vlen * sizeof(double);
+    if (h->vlen > 0 && hipMalloc(&acc, acc_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        acc = nullptr;
+    }
+    int rc = acc ? fill_zero(acc, acc_bytes, h->compute) : fill_zero(h->v, (size_t)h->vlen * sizeof(float), h->compute);
+    if (rc == SNAP_OK) rc = for_each_chunk(h, axpy_chunk, acc, true, false);
+    if (rc == SNAP_OK && acc) {
+        const int64_t blocks = (h->vlen + 255) / 256;
+        hipLaunchKernelGGL(k_round_to_float, dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, h->compute,
+                           acc, h->v, h->vlen);
+        if (hipGetLastError() != hipSuccess) rc = SNAP_EHIP;
+    }
+    if (acc) {
+        (void)hipStreamSynchronize(h->compute);
+        (void)hipFree(acc);
+    }
+    return rc;
 }
 
 // ---- per-coordinate dots with v (no update), fp64 ---------------------------------------------------
@@ -522,16 +555,30 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
 // importance measure for choosing what to process).  With u = grad f(v) the loss part of the Fenchel
 // gap vanishes and the rest is a sum over the coordinates of
 //     g(w_j) + g*(-z_j) + w_j z_j,   z_j = a_j . u,   g(w) = (lambda/2) w^2 + lambda1 |w|,
-// which for lambda1 = 0 is (z_j + lambda w_j)^2 / (2 lambda).  One workgroup per chunk, fixed order.
+// which for lambda1 = 0 is (z_j + lambda w_j)^2 / (2 lambda).  Dual forms (MODE 1 hinge, 2 logistic):
+// with w = v / (lambda n) the regulariser's part lambda ||w||^2 is (1/n) sum_i alpha_i m_i,
+// m_i = y_i x_i . w, and the gap is the sum over the examples of
+//     (1/n) [ l(m_i) + l*(-alpha_i) + alpha_i m_i ],
+// l*(-a) = -a (hinge), a ln a + (1 - a) ln(1 - a) (logistic); inv_n then carries 1 / (lambda n).
+// One workgroup per chunk, fixed order.
+template <int MODE>
 __global__ void __launch_bounds__(LTPB)
-k_chunk_shares(const double* __restrict__ gdot, const float* __restrict__ x, const int64_t* __restrict__ bounds,
-               double inv_n, double lam, double lam1, double* __restrict__ out) {
+k_chunk_shares(const double* __restrict__ gdot, const float* __restrict__ x, const float* __restrict__ y,
+               const int64_t* __restrict__ bounds, double inv_n, double lam, double lam1, double* __restrict__ out) {
     __shared__ double scratch[LTPB / WAVE];
     const int64_t c0 = bounds[blockIdx.x], c1 = bounds[blockIdx.x + 1];
     double acc = 0.0;
     for (int64_t j = c0 + threadIdx.x; j < c1; j += LTPB) {
         const double z = gdot[j] * inv_n, w = (double)x[j];
-        if (lam1 == 0.0) {
+        if (MODE != 0) {
+            const double mi = (double)y[j] * z;   // margin; w holds alpha_i
+            double t;
+            if (MODE == 1) t = fmax(0.0, 1.0 - mi) - w;
+            else
+                t = fmax(-mi, 0.0) + log1p(exp(-fabs(mi))) + (w > 0.0 ? w * log(w) : 0.0) +
+                    (w < 1.0 ? (1.0 - w) * log1p(-w) : 0.0);
+            acc += t + w * mi;
+        } else if (lam1 == 0.0) {
             const double t = z + lam * w;
             acc += t * t / (2.0 * lam);
         } else {
@@ -540,14 +587,11 @@ k_chunk_shares(const double* __restrict__ gdot, const float* __restrict__ x, con
         }
     }
     acc = block_sum_d(acc, scratch);
+    if (MODE != 0) acc *= lam * inv_n;   // = 1/n
     if (threadIdx.x == 0) out[blockIdx.x] = acc;
 }
 
 int chunk_gap_shares(snap_handle* h, double* shares_out) {
-    if (h->form != SNAP_PRIMAL) {
-        set_error("gap shares of the chunks are defined for the primal forms");
-        return SNAP_EUNSUPPORTED;
-    }
     const bool by_group = h->grouped || h->tiled;
     const int64_t C = by_group ? h->n_groups : h->n_chunks;
     if (C <= 0) return SNAP_OK;
@@ -560,8 +604,17 @@ int chunk_gap_shares(snap_handle* h, double* shares_out) {
         SNAP_HIP(hipMemcpy(h->share_bounds, b.data(), ((size_t)C + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     }
     SNAP_TRY(h->grouped ? grouped_dots(h) : coord_dots(h));
-    hipLaunchKernelGGL(k_chunk_shares, dim3((unsigned)C), dim3(LTPB), 0, h->compute, h->gdot, h->x, h->share_bounds,
-                       1.0 / (double)h->n, h->lambda, h->lambda1, h->share_out);
+    const dim3 grid((unsigned)C), block(LTPB);
+    const double n = (double)h->n;
+    if (h->form == SNAP_PRIMAL)
+        hipLaunchKernelGGL((k_chunk_shares<0>), grid, block, 0, h->compute, h->gdot, h->x, h->y, h->share_bounds,
+                           1.0 / n, h->lambda, h->lambda1, h->share_out);
+    else if (h->loss == SNAP_LOGISTIC)
+        hipLaunchKernelGGL((k_chunk_shares<2>), grid, block, 0, h->compute, h->gdot, h->x, h->y, h->share_bounds,
+                           1.0 / (h->lambda * n), h->lambda, 0.0, h->share_out);
+    else
+        hipLaunchKernelGGL((k_chunk_shares<1>), grid, block, 0, h->compute, h->gdot, h->x, h->y, h->share_bounds,
+                           1.0 / (h->lambda * n), h->lambda, 0.0, h->share_out);
     SNAP_HIP(hipGetLastError());
     SNAP_HIP(hipMemcpyAsync(shares_out, h->share_out, (size_t)C * sizeof(double), hipMemcpyDeviceToHost, h->compute));
     SNAP_HIP(hipStreamSynchronize(h->compute));

@@ -344,12 +344,34 @@ def test_chunk_gap_shares_match_the_oracle_streamed_and_grouped():
     np.testing.assert_allclose(got, want, rtol=2e-3, atol=1e-3 * want.max())
     assert rel(got.sum(), g.duality_gap()) <= 1e-6
     g.close()
-    # dual form: not defined
-    p = problem("cfg3_zipf_svm")
-    g = gpu_solver(p)
-    with pytest.raises(snap.SnapError) as e:
-        g.chunk_gaps()
-    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("loss", ["hinge", "logistic"])
+def test_chunk_gap_shares_dual_forms_streamed(loss):
+    """Shares of streamed batches of examples in P - D, dual forms, against the oracle at the same alpha."""
+    p = problem("cfg3_zipf_svm") if loss == "hinge" else _dual_logistic_problem()
+    A = oracle.Matrix.from_problem(p)
+    g = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, chunk_bytes=1 << 19)
+    bounds = g.chunk_bounds()
+    assert len(bounds) > 4
+    o = oracle.Solver(A, p.y.numpy(), loss, p.lam, chunk_bounds=bounds)
+    for e in range(2):
+        o.epoch(e)
+    g.set_model(o.x.astype(np.float32))
+    chk = oracle.Solver(A, p.y.numpy(), loss, p.lam, chunk_bounds=bounds)
+    chk.x[:] = o.x.astype(np.float32)
+    chk.v[:] = chk.shared_from_model()
+    # v = X^T (y alpha) of a trained model is what is left of large terms that cancel (partial sums of
+    # the frequent features: thousands of times the result); the library sums it in fp64
+    assert relnorm(g.shared(), chk.v) <= 1e-6
+    want, got = chk.chunk_gaps(), g.chunk_gaps()
+    assert got.shape == want.shape and got.min() >= 0.0
+    np.testing.assert_allclose(got, want, rtol=1e-5, atol=1e-6 * want.max())
+    assert rel(got.sum(), g.duality_gap()) <= 1e-6
+    # the selected solve runs on them as well and ends below the tolerance
+    tol = 0.2 * got.sum()
+    passes, visits, gap = g.solve_selected(10, 60, tol, 2, max(1, (len(bounds) - 1) // 2))
+    assert gap <= tol and passes < 60
     g.close()
 
 

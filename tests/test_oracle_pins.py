@@ -648,3 +648,25 @@ def test_selection_picks_the_largest_shares_and_the_selected_solve_reaches_the_o
     assert gap <= 1e-10
     assert visits < passes * 4                                          # part of the passes visited part of the chunks
     assert abs(s.primal() - ref.primal()) <= 1e-9 * abs(ref.primal())
+
+
+@pytest.mark.parametrize("loss", ["hinge", "logistic"])
+def test_dual_gap_shares_add_up_to_the_gap_and_are_nonnegative(loss):
+    r = np.random.default_rng(21)
+    X = sparse_random(120, 30, 0.4, r)
+    y = np.sign(r.standard_normal(120)).astype(np.float32)
+    s = oracle.Solver(dense_to_csr(X), y, loss, 5e-2, chunk_bounds=[0, 50, 120])
+    for e in range(4):
+        share = oracle.dual_gap_shares(s.A, s.loss, s.x, s.v, s.y, s.lam)
+        assert share.min() >= -1e-15
+        assert abs(share.sum() - s.gap()) <= 1e-12 * max(1.0, abs(s.primal()))
+        np.testing.assert_allclose(s.chunk_gaps(), [share[:50].sum(), share[50:].sum()], rtol=1e-13)
+        s.epoch(e)
+    # hinge: right after the exact update of example i (alone in its chunk) its own share vanishes
+    if loss == "hinge":
+        t = oracle.Solver(dense_to_csr(X), y, loss, 5e-2, chunk_bounds=list(range(121)))
+        t.epoch(0)
+        for i in (7, 0, 119):
+            t.epoch(1, chunks=[i])
+            share = oracle.dual_gap_shares(t.A, t.loss, t.x, t.v, t.y, t.lam)
+            assert abs(share[i]) <= 1e-15 and share.max() > 1e-6
