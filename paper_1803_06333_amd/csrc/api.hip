@@ -231,6 +231,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
             } else {
                 ++ck.n_small;
                 small_nnz += len;
+                h->max_small_len = std::max(h->max_small_len, len);
             }
         }
         ck.l1 = (int64_t)large.size();
@@ -496,8 +497,7 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
             SNAP_TRY(monitor_value(h, &h->monitor_prev));
             h->monitor_valid = true;
         }
-        SNAP_HIP(hipMemcpyAsync(h->x_snap, h->x, (size_t)h->m * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
-        SNAP_HIP(hipMemcpyAsync(h->v_snap, h->v, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
+        SNAP_TRY(copy_pair(h->x_snap, h->x, h->m, h->v_snap, h->v, h->vlen, h->compute));
     }
     if (prof) SNAP_HIP(hipEventRecord(h->ev[0], h->compute));
     if (h->grouped) {
@@ -535,8 +535,7 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         SNAP_TRY(monitor_value(h, &now));
         const double slack = 1e-6 * std::max(std::fabs(h->monitor_prev), 1e-30);
         if (!(now <= h->monitor_prev + slack)) {          // worse (or not a number): discard the epoch
-            SNAP_HIP(hipMemcpyAsync(h->x, h->x_snap, (size_t)h->m * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
-            SNAP_HIP(hipMemcpyAsync(h->v, h->v_snap, (size_t)h->vlen * sizeof(float), hipMemcpyDeviceToDevice, h->compute));
+            SNAP_TRY(copy_pair(h->x, h->x_snap, h->m, h->v, h->v_snap, h->vlen, h->compute));
             h->stats.rejected = 1;
             // first fewer nonzeros in flight (down to one wavefront's worth), then smaller steps
             const int64_t cur = h->inflight_nnz > 0 ? h->inflight_nnz : (int64_t)256 * 8 * h->seg;

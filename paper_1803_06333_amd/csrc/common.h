@@ -202,6 +202,7 @@ struct snap_handle {
     double monitor_prev = 0.0;        // objective before the epoch (minimised quantity)
     bool monitor_valid = false;
     double avg_small_len = 1.0;
+    int64_t max_small_len = 0;   // longest coordinate handled by one wavefront
     int64_t nnz_small = 0, nnz_large = 0;
     snap_epoch_stats stats{};
     bool stats_pending = false;
@@ -263,5 +264,7 @@ int weights_to_host(snap_handle* h, float* w_out);
 int reducer_alloc(Reducer& r);
 void reducer_free(Reducer& r);
 int fill_zero(void* p, size_t bytes, hipStream_t s);
+// d0[0..n0) = s0, d1[0..n1) = s1 in one launch (arrays from hipMalloc)
+int copy_pair(float* d0, const float* s0, int64_t n0, float* d1, const float* s1, int64_t n1, hipStream_t s);
 
 }  // namespace snap

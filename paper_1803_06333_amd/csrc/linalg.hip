@@ -67,6 +67,28 @@ int fill_zero(void* p, size_t bytes, hipStream_t s) {
     return SNAP_OK;
 }
 
+// Two copies in one launch (the state saved before an epoch that may be discarded): a copy command
+// costs some tens of microseconds of queueing each, more than a short epoch's permutation.
+__global__ void __launch_bounds__(256)
+k_copy_pair(float* __restrict__ d0, const float* __restrict__ s0, int64_t n0, float* __restrict__ d1,
+            const float* __restrict__ s1, int64_t n1) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    // hipMalloc'd arrays: 16-byte aligned, so whole float4s first, then the tail
+    const int64_t q0 = n0 / 4, q1 = n1 / 4;
+    for (int64_t i = first; i < q0; i += stride) ((float4*)d0)[i] = ((const float4*)s0)[i];
+    for (int64_t i = 4 * q0 + first; i < n0; i += stride) d0[i] = s0[i];
+    for (int64_t i = first; i < q1; i += stride) ((float4*)d1)[i] = ((const float4*)s1)[i];
+    for (int64_t i = 4 * q1 + first; i < n1; i += stride) d1[i] = s1[i];
+}
+
+int copy_pair(float* d0, const float* s0, int64_t n0, float* d1, const float* s1, int64_t n1, hipStream_t s) {
+    const int64_t quads = (n0 > n1 ? n0 : n1) / 4 + 1;
+    const int grid = (int)((quads + 255) / 256 < 4096 ? (quads + 255) / 256 : 4096);
+    hipLaunchKernelGGL(k_copy_pair, dim3(grid), dim3(256), 0, s, d0, s0, n0, d1, s1, n1);
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
 // ---- squared norms and size classes -------------------------------------------------------------
 __global__ void __launch_bounds__(LTPB)
 k_coord_norms(const int64_t* __restrict__ ptr, const float* __restrict__ val, int64_t nnz_base, int64_t c0,

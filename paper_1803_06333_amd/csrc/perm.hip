@@ -53,19 +53,23 @@ k_radix_hist(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ val
     block_hist[(size_t)threadIdx.x * n_blocks + blockIdx.x] = hist[threadIdx.x];
 }
 
-// exclusive prefix sum over `count` entries, in place, one workgroup of 1024 threads: tiles of 4096
-// entries (four consecutive per thread, coalesced), wavefront scans by shuffles, a running carry
-__global__ void __launch_bounds__(1024) k_exclusive_scan(uint32_t* __restrict__ a, uint32_t count) {
-    __shared__ uint32_t wave_tot[1024 / WAVE];
+// Offsets of the scatter in two levels.  Workgroup d turns the counts of digit d, one per block
+// (block_hist[d * n_blocks ..]), into their exclusive prefix sums in place and writes the digit's
+// total; the scatter kernel adds the prefix sum over the 256 totals itself.  (One workgroup
+// scanning all 256 * n_blocks counts took four times as long as the rest of a pass.)
+__global__ void __launch_bounds__(SORT_TPB)
+k_digit_scan(uint32_t* __restrict__ block_hist, uint32_t n_blocks, uint32_t* __restrict__ totals) {
+    __shared__ uint32_t wave_tot[SORT_WAVES];
     __shared__ uint32_t carry_s;
+    uint32_t* a = block_hist + (size_t)blockIdx.x * n_blocks;
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
-    for (uint32_t base = 0; base < count; base += 4096u) {
+    for (uint32_t base = 0; base < n_blocks; base += 4u * SORT_TPB) {
         const uint32_t i0 = base + 4u * threadIdx.x;
         uint32_t x[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = i0 + j < count ? a[i0 + j] : 0u;
+        for (int j = 0; j < 4; ++j) x[j] = i0 + j < n_blocks ? a[i0 + j] : 0u;
         const uint32_t mine = x[0] + x[1] + x[2] + x[3];
         uint32_t inc = mine;                               // inclusive scan across the wavefront
 #pragma unroll
@@ -80,13 +84,14 @@ __global__ void __launch_bounds__(1024) k_exclusive_scan(uint32_t* __restrict__ 
         uint32_t run = before + inc - mine;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (i0 + j < count) a[i0 + j] = run;
+            if (i0 + j < n_blocks) a[i0 + j] = run;
             run += x[j];
         }
         __syncthreads();
-        if (threadIdx.x == 1023) carry_s = run;            // total so far
+        if (threadIdx.x == SORT_TPB - 1) carry_s = run;    // total so far
         __syncthreads();
     }
+    if (threadIdx.x == 0) totals[blockIdx.x] = carry_s;
 }
 
 // Stable scatter of one digit pass.  Wavefront w of the workgroup owns SORT_ROUNDS consecutive
@@ -95,9 +100,21 @@ __global__ void __launch_bounds__(1024) k_exclusive_scan(uint32_t* __restrict__ 
 __global__ void __launch_bounds__(SORT_TPB)
 k_radix_scatter(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals,
                 uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, uint32_t m, int shift,
-                const uint8_t* __restrict__ cls, const uint32_t* __restrict__ block_off, uint32_t n_blocks) {
+                const uint8_t* __restrict__ cls, const uint32_t* __restrict__ block_off, uint32_t n_blocks,
+                const uint32_t* __restrict__ totals) {
     __shared__ uint32_t cnt[SORT_WAVES][RADIX];
+    __shared__ uint32_t digit_wave_tot[SORT_WAVES];
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    // first position of digit t = number of elements with a smaller digit: thread t holds digit t
+    const uint32_t my_total = totals[threadIdx.x];
+    uint32_t digit_base = my_total;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        const uint32_t t = __shfl_up(digit_base, off, WAVE);
+        if (lane >= off) digit_base += t;
+    }
+    if (lane == WAVE - 1) digit_wave_tot[w] = digit_base;
+    digit_base -= my_total;                                    // exclusive, within the wavefront
     for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_TPB) (&cnt[0][0])[i] = 0;
     __syncthreads();
     const uint32_t base = blockIdx.x * SORT_TILE + w * (SORT_ROUNDS * WAVE);
@@ -125,7 +142,8 @@ k_radix_scatter(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ 
     __syncthreads();
     // exclusive prefix over the wavefronts, per digit; thread t handles digit t
     {
-        uint32_t run = block_off[(size_t)threadIdx.x * n_blocks + blockIdx.x];
+        for (int ww = 0; ww < w; ++ww) digit_base += digit_wave_tot[ww];
+        uint32_t run = digit_base + block_off[(size_t)threadIdx.x * n_blocks + blockIdx.x];
 #pragma unroll
         for (int ww = 0; ww < SORT_WAVES; ++ww) {
             uint32_t c = cnt[ww][threadIdx.x];
@@ -153,7 +171,8 @@ int sorter_alloc(Sorter& s, int64_t max_m) {
     SNAP_HIP(hipMalloc(&s.keys_b, bytes));
     SNAP_HIP(hipMalloc(&s.vals_a, bytes));
     SNAP_HIP(hipMalloc(&s.vals_b, bytes));
-    SNAP_HIP(hipMalloc(&s.block_hist, (size_t)s.n_blocks * RADIX * sizeof(uint32_t)));
+    // the counts per (digit, block), then the 256 totals per digit
+    SNAP_HIP(hipMalloc(&s.block_hist, ((size_t)s.n_blocks + 1) * RADIX * sizeof(uint32_t)));
     return SNAP_OK;
 }
 
@@ -171,9 +190,10 @@ static int radix_pass(snap_handle* h, uint32_t*& ka, uint32_t*& va, uint32_t*& k
     Sorter& s = h->sorter;
     const uint32_t nb = (m + SORT_TILE - 1) / SORT_TILE;
     hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(SORT_TPB), 0, h->compute, ka, va, m, shift, cls, s.block_hist, nb);
-    hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, h->compute, s.block_hist, nb * RADIX);
+    uint32_t* totals = s.block_hist + (size_t)s.n_blocks * RADIX;
+    hipLaunchKernelGGL(k_digit_scan, dim3(RADIX), dim3(SORT_TPB), 0, h->compute, s.block_hist, nb, totals);
     hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(SORT_TPB), 0, h->compute, ka, va, kb, vb, m, shift, cls,
-                       s.block_hist, nb);
+                       s.block_hist, nb, totals);
     uint32_t* t = ka; ka = kb; kb = t;
     t = va; va = vb; vb = t;
     return SNAP_OK;

@@ -20,7 +20,26 @@
 namespace snap {
 
 // ---- small coordinates: one wavefront each ----------------------------------------------------
-template <int KIND>
+// A wavefront walks its share of the epoch order, and what a coordinate needs is a chain of dependent
+// loads: its place in the order, its two ptr entries, its indices and values, the entries of v they
+// name, its own x / norm / label.  With few coordinates in flight (the cap that keeps the asynchronous
+// solver convergent: some hundred rows for the hinge dual on data with popular features) that chain,
+// not bandwidth, sets the pace.  So the chain is taken apart over three visits: while the gather of
+// coordinate i is under way, the nonzeros and scalars of i+1, the ptr entries of i+2 and the order
+// entry of i+3 are requested too, all independent of each other; only the reads of v, which must be
+// as late as possible, stay in the visit they belong to.  (x[c], the norms and the labels are not
+// written by other coordinates' updates.)  Up to SMALL_ROUNDS nonzeros per lane travel this way and
+// are scattered from registers; longer coordinates take the rest in plain loops.
+// SMALL_ROUNDS is 1 when no small coordinate of the data is longer than a wavefront, else 4.
+template <int SMALL_ROUNDS>
+struct SmallCoord {
+    int64_t c, s0, s1;            // coordinate, its range in the chunk's arrays
+    uint32_t raw[SMALL_ROUNDS];   // index words of this lane: nonzeros s0 + j * 64 + lane
+    float a[SMALL_ROUNDS];
+    float xc, nc, yc;
+};
+
+template <int KIND, int SMALL_ROUNDS>
 __global__ void __launch_bounds__(TPB)
 k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, const float* __restrict__ y,
             float* __restrict__ x, float* v, const float* __restrict__ norms, StepParams sp, int64_t n_waves) {
@@ -28,41 +47,98 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
     const int64_t wave0 = ((int64_t)blockIdx.x * TPB + threadIdx.x) / WAVE;
     if (wave0 >= n_waves) return;
     // n_waves wavefronts walk the epoch order round-robin: at most n_waves coordinates in flight
-    for (int64_t wid = wave0; wid < n_small; wid += n_waves) {
-        const int64_t c = cv.c0 + (int64_t)order[wid];
-        const int64_t s0 = cv.ptr[c] - cv.nnz_base, s1 = cv.ptr[c + 1] - cv.nnz_base;
-        float g = 0.0f, h = 0.0f;
-        // the first nonzero of every lane stays in registers for the scatter pass
-        uint32_t r0 = 0;
-        float a0 = 0.0f;
-        const bool have0 = s0 + lane < s1;
-        if (have0) {
-            float yy;
-            decode<KIND>(cv.idx[s0 + lane], r0, yy, y);
-            a0 = cv.val[s0 + lane];
-            accumulate<KIND>(a0, load_shared(v, r0), yy, g, h);
+    auto coord_of = [&](int64_t wid) -> int64_t { return wid < n_small ? cv.c0 + (int64_t)order[wid] : -1; };
+    auto range_of = [&](int64_t c, int64_t& s0, int64_t& s1) {
+        s0 = s1 = 0;
+        if (c >= 0) {
+            s0 = cv.ptr[c] - cv.nnz_base;
+            s1 = cv.ptr[c + 1] - cv.nnz_base;
         }
-        for (int64_t k = s0 + WAVE + lane; k < s1; k += WAVE) {
-            uint32_t r;
-            float yy;
-            decode<KIND>(cv.idx[k], r, yy, y);
-            accumulate<KIND>(cv.val[k], load_shared(v, r), yy, g, h);
+    };
+    auto fetch = [&](int64_t c, int64_t s0, int64_t s1) -> SmallCoord<SMALL_ROUNDS> {
+        SmallCoord<SMALL_ROUNDS> q;
+        q.c = c, q.s0 = s0, q.s1 = s1;
+        q.xc = q.nc = q.yc = 0.0f;
+#pragma unroll
+        for (int j = 0; j < SMALL_ROUNDS; ++j) {
+            const int64_t k = s0 + j * WAVE + lane;
+            q.raw[j] = 0u;
+            q.a[j] = 0.0f;
+            if (k < s1) {
+                q.raw[j] = cv.idx[k];
+                q.a[j] = cv.val[k];
+            }
+        }
+        if (c >= 0) {   // the same address in every lane: one request
+            q.xc = x[c];
+            q.nc = norms[c];
+            if (KIND == K_DUAL) q.yc = y[c];
+        }
+        return q;
+    };
+    // fill the pipeline: three coordinates' order entries, two ranges, one record
+    int64_t cB = coord_of(wave0 + n_waves), cA = coord_of(wave0 + 2 * n_waves);
+    int64_t s0B, s1B;
+    SmallCoord<SMALL_ROUNDS> cur;
+    {
+        const int64_t c = coord_of(wave0);
+        int64_t s0, s1;
+        range_of(c, s0, s1);
+        range_of(cB, s0B, s1B);
+        cur = fetch(c, s0, s1);
+    }
+    for (int64_t wid = wave0; wid < n_small; wid += n_waves) {
+        // this visit's requests
+        const int64_t c = cur.c, s0 = cur.s0, s1 = cur.s1;
+        uint32_t r[SMALL_ROUNDS];
+        float vv[SMALL_ROUNDS], yy[SMALL_ROUNDS];
+        bool have[SMALL_ROUNDS];
+#pragma unroll
+        for (int j = 0; j < SMALL_ROUNDS; ++j) {
+            have[j] = s0 + j * WAVE + lane < s1;
+            r[j] = cur.raw[j] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu);
+            vv[j] = yy[j] = 0.0f;
+            if (have[j]) {
+                vv[j] = load_shared(v, r[j]);
+                if (KIND == K_PRIMAL_RIDGE) yy[j] = y[r[j]];
+                if (KIND == K_PRIMAL_LOGISTIC) yy[j] = (cur.raw[j] & LABEL_BIT) ? -1.0f : 1.0f;
+            }
+        }
+        const SmallCoord<SMALL_ROUNDS> nxt = fetch(cB, s0B, s1B);
+        int64_t s0A, s1A;
+        range_of(cA, s0A, s1A);
+        const int64_t c3 = coord_of(wid + 3 * n_waves);
+
+        float g = 0.0f, h = 0.0f;
+        // (these nonzeros stay in registers for the scatter pass)
+#pragma unroll
+        for (int j = 0; j < SMALL_ROUNDS; ++j)
+            if (have[j]) accumulate<KIND>(cur.a[j], vv[j], yy[j], g, h);
+        for (int64_t k = s0 + SMALL_ROUNDS * WAVE + lane; k < s1; k += WAVE) {
+            uint32_t rr;
+            float yk;
+            decode<KIND>(cv.idx[k], rr, yk, y);
+            accumulate<KIND>(cv.val[k], load_shared(v, rr), yk, g, h);
         }
         g = wave_sum(g);
         if (KIND == K_PRIMAL_LOGISTIC) h = wave_sum(h);
         float mult = 0.0f;
-        if (lane == 0) {
-            const float xc = x[c];
-            const float yc = KIND == K_DUAL ? y[c] : 0.0f;
-            x[c] = take_step<KIND>((double)g, (double)h, xc, norms[c], yc, sp, mult);
-        }
+        if (lane == 0) x[c] = take_step<KIND>((double)g, (double)h, cur.xc, cur.nc, cur.yc, sp, mult);
         mult = __shfl(mult, 0, WAVE);
-        if (mult == 0.0f) continue;
-        if (have0) unsafeAtomicAdd(v + r0, mult * a0);
-        for (int64_t k = s0 + WAVE + lane; k < s1; k += WAVE) {
-            const uint32_t r = cv.idx[k] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu);
-            unsafeAtomicAdd(v + r, mult * cv.val[k]);
+        if (mult != 0.0f) {
+#pragma unroll
+            for (int j = 0; j < SMALL_ROUNDS; ++j)
+                if (have[j]) unsafeAtomicAdd(v + r[j], mult * cur.a[j]);
+            for (int64_t k = s0 + SMALL_ROUNDS * WAVE + lane; k < s1; k += WAVE) {
+                const uint32_t rr = cv.idx[k] & (KIND == K_PRIMAL_LOGISTIC ? ~LABEL_BIT : 0xFFFFFFFFu);
+                unsafeAtomicAdd(v + rr, mult * cv.val[k]);
+            }
         }
+        cur = nxt;
+        cB = cA;
+        s0B = s0A;
+        s1B = s1A;
+        cA = c3;
     }
 }
 
@@ -298,8 +374,12 @@ static int launch_kind(snap_handle* h, const ChunkView& cv, const snap_handle::C
         if (h->inflight_nnz > 0)
             waves = std::min<int64_t>(waves, std::max<int64_t>(1, (int64_t)((double)h->inflight_nnz / h->avg_small_len)));
         const dim3 grid((unsigned)((waves + WAVES_PER_WG - 1) / WAVES_PER_WG));
-        hipLaunchKernelGGL((k_scd_small<KIND>), grid, dim3(TPB), 0, h->compute, cv, order, ck.n_small, h->y, h->x,
-                           h->v, h->norms, sp, waves);
+        if (h->max_small_len <= WAVE)
+            hipLaunchKernelGGL((k_scd_small<KIND, 1>), grid, dim3(TPB), 0, h->compute, cv, order, ck.n_small, h->y, h->x,
+                               h->v, h->norms, sp, waves);
+        else
+            hipLaunchKernelGGL((k_scd_small<KIND, 4>), grid, dim3(TPB), 0, h->compute, cv, order, ck.n_small, h->y, h->x,
+                               h->v, h->norms, sp, waves);
     }
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
