@@ -37,7 +37,9 @@
  *  - Output buffers of snap_get_* are HOST pointers, caller allocated.  snap_predict writes to a
  *    buffer in the memory space of its matrix argument.
  *  - snap_epoch works on the handle's compute stream; the query functions synchronise that
- *    stream.  One handle must not be used from two threads at once.
+ *    stream.  One handle must not be used from two threads at once.  Device arrays handed to
+ *    snap_create or snap_predict are read on that stream: work of the caller's own streams that
+ *    writes them must be complete before the call.
  */
 #ifndef SNAP_H
 #define SNAP_H
@@ -183,9 +185,10 @@ int snap_objective(snap_handle *h, double *primal, double *dual);
  * ||X^T u + lambda w||^2 / (2 lambda); dual form P(w(alpha)) - D(alpha).  Deterministic. */
 int snap_duality_gap(snap_handle *h, double *gap);
 
-/* Decision values out[i] = x_i . w for the rows of X (CSR, dense row-major or dense
+/* Decision values out[i] = x_i . w for the rows of X (CSR, CSC, dense row-major or dense
  * column-major; X->n_cols must equal the training n_cols).  out has X->n_rows floats in the memory
- * space X->mem. */
+ * space X->mem.  Compressed X is checked first (ptr from 0 to nnz without decreasing, every index in
+ * range; SNAP_EINVAL otherwise, nothing written): one more pass over ptr and idx.  Synchronises. */
 int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
 
 /* w (n_cols floats, may be NULL) and the coordinate vector (w in primal form, alpha in dual form;

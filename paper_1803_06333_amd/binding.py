@@ -212,6 +212,7 @@ class Solver:
     def predict(self, layout: str, n_rows: int, ptr, idx, val):
         sm, keep = make_matrix(layout, n_rows, self.n_cols, ptr, idx, val)
         if sm.mem == MEM_DEVICE:
+            torch.cuda.synchronize(keep[2].device)   # the library reads the tensors on its own stream
             out = torch.empty(n_rows, dtype=torch.float32, device=keep[2].device)
             _check(self._lib.snap_predict(self._h, C.byref(sm), out.data_ptr()))
             return out

@@ -710,17 +710,22 @@ int access_moments(snap_handle* h, const uint32_t* freq, double* eff_len) {
 }
 
 // ---- decision values -------------------------------------------------------------------------------
+// L lanes per row (8 ... 64, chosen from the average row length): with the 39 entries of a click-log
+// row a whole wavefront per row leaves a third of the lanes idle for one round of loads per row.
+template <int L>
 __global__ void __launch_bounds__(LTPB)
 k_csr_rowdot(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx, const float* __restrict__ val,
              int64_t rows, const float* __restrict__ w, float* __restrict__ out) {
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
-    const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
-    for (int64_t i = wave0; i < rows; i += nwaves) {
+    const int sub = threadIdx.x & (L - 1);
+    const int64_t g0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / L;
+    const int64_t groups = (int64_t)gridDim.x * blockDim.x / L;
+    for (int64_t i = g0; i < rows; i += groups) {
         double acc = 0.0;
-        for (int64_t k = ptr[i] + lane; k < ptr[i + 1]; k += WAVE) acc += (double)val[k] * (double)w[idx[k]];
-        acc = wave_sum_d(acc);
-        if (lane == 0) out[i] = (float)acc;
+        const int64_t s1 = ptr[i + 1];
+        for (int64_t k = ptr[i] + sub; k < s1; k += L) acc += (double)val[k] * (double)w[idx[k]];
+#pragma unroll
+        for (int off = L / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, L);   // the row's L lanes are all here
+        if (sub == 0) out[i] = (float)acc;
     }
 }
 
@@ -769,6 +774,21 @@ int weights_to_host(snap_handle* h, float* w_out) {
     return SNAP_OK;
 }
 
+// Compressed input of snap_predict: ptr[0] = 0, ptr non-decreasing, ptr[major] = nnz, 0 <= idx < minor.
+// The row kernels follow ptr and idx without further checks, so a violation is reported here.
+__global__ void k_check_compressed(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx, int64_t major,
+                                   int64_t minor, int64_t nnz, uint32_t* flag) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool bad = false;
+    for (int64_t i = first; i <= major; i += stride) {
+        const int64_t a = ptr[i];
+        if (a < 0 || a > nnz || (i == 0 && a != 0) || (i == major && a != nnz) || (i < major && ptr[i + 1] < a)) bad = true;
+    }
+    for (int64_t k = first; k < nnz; k += stride)
+        if (idx[k] < 0 || (int64_t)idx[k] >= minor) bad = true;
+    if (bad) atomicOr(flag, 1u);
+}
+
 int predict(snap_handle* h, const snap_matrix* X, float* out) {
     const float* w;
     SNAP_TRY(model_weights(h, &w));
@@ -778,11 +798,13 @@ int predict(snap_handle* h, const snap_matrix* X, float* out) {
     int32_t* didx = nullptr;
     float* dval = nullptr;
     float* dout = nullptr;
+    uint32_t* flag = nullptr;
     int rc = SNAP_OK;
     const bool sparse = X->layout == SNAP_CSR || X->layout == SNAP_CSC;
     const int64_t major = X->layout == SNAP_CSR ? rows : cols;
     const int64_t count = sparse ? X->nnz : rows * cols;
     auto cleanup = [&]() {
+        (void)hipFree(flag);
         if (!on_dev) {
             (void)hipFree(dptr);
             (void)hipFree(didx);
@@ -815,10 +837,34 @@ int predict(snap_handle* h, const snap_matrix* X, float* out) {
         PRED_HIP(hipMemcpyAsync(dval, X->val, (size_t)count * sizeof(float), hipMemcpyHostToDevice, h->compute));
         PRED_HIP(hipMalloc(&dout, (size_t)(rows ? rows : 1) * sizeof(float)));
     }
+    if (sparse) {
+        const int64_t minor = X->layout == SNAP_CSR ? cols : rows;
+        const int64_t work = std::max<int64_t>(major + 1, count);
+        PRED_HIP(hipMalloc(&flag, sizeof(uint32_t)));
+        PRED_HIP(hipMemsetAsync(flag, 0, sizeof(uint32_t), h->compute));
+        hipLaunchKernelGGL(k_check_compressed, dim3((unsigned)std::min<int64_t>((work + 255) / 256, 16384)), dim3(256), 0,
+                           h->compute, dptr, didx, major, minor, count, flag);
+        uint32_t st = 0;
+        PRED_HIP(hipMemcpyAsync(&st, flag, sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+        PRED_HIP(hipStreamSynchronize(h->compute));
+        if (st != 0) {
+            set_error("snap_predict: ptr must start at 0, not decrease and end at nnz; idx must lie in [0, %lld)",
+                      (long long)minor);
+            cleanup();
+            return SNAP_EINVAL;
+        }
+    }
     if (rows > 0) {
         int grid = (int)((rows + 3) / 4 < 32768 ? (rows + 3) / 4 : 32768);
         if (X->layout == SNAP_CSR) {
-            hipLaunchKernelGGL(k_csr_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+            const int64_t avg = count / rows;
+            const int L = avg > 128 ? 64 : (avg > 64 ? 32 : (avg > 32 ? 16 : 8));   // about four to eight rounds per row
+            const int64_t wgs = (rows + LTPB / L - 1) / (LTPB / L);
+            const dim3 g((unsigned)std::min<int64_t>(wgs, 65536));
+            if (L == 64) hipLaunchKernelGGL((k_csr_rowdot<64>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+            else if (L == 32) hipLaunchKernelGGL((k_csr_rowdot<32>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+            else if (L == 16) hipLaunchKernelGGL((k_csr_rowdot<16>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+            else hipLaunchKernelGGL((k_csr_rowdot<8>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
         } else if (X->layout == SNAP_CSC) {
             rc = fill_zero(dout, (size_t)rows * sizeof(float), h->compute);
             if (rc == SNAP_OK && count > 0) {

@@ -242,6 +242,36 @@ def test_error_paths():
     assert e.value.code == -1
 
 
+def test_predict_checks_compressed_input():
+    """ptr and idx of the matrix handed to predict are checked before any kernel follows them."""
+    ptr = np.array([0, 2, 3], dtype=np.int64)
+    idx = np.array([0, 1, 2], dtype=np.int32)
+    val = np.array([1.0, 2.0, 3.0], dtype=np.float32)
+    y = np.array([1, -1, 1], dtype=np.float32)
+    g = snap.Solver("csc", 3, 2, ptr, idx, val, y, "ridge", 0.1)
+    g.set_model(np.array([0.5, -2.0], dtype=np.float32))
+    np.testing.assert_allclose(g.predict("csc", 3, ptr, idx, val), [0.5, 1.0, -6.0], rtol=1e-6)
+    rptr = np.array([0, 1, 2, 3], dtype=np.int64)
+    ridx = np.array([0, 0, 1], dtype=np.int32)
+    np.testing.assert_allclose(g.predict("csr", 3, rptr, ridx, val), [0.5, 1.0, -6.0], rtol=1e-6)
+    cases = [("csr", np.array([0, 1, 2, 3], dtype=np.int64), np.array([0, 2, 1], dtype=np.int32)),    # column 2 of 2
+             ("csr", np.array([0, 1, 2, 3], dtype=np.int64), np.array([0, -1, 1], dtype=np.int32)),
+             ("csr", np.array([0, 2, 1, 3], dtype=np.int64), ridx),                                   # decreasing
+             ("csr", np.array([0, 1, 2, 4], dtype=np.int64), ridx),                                   # past nnz
+             ("csr", np.array([1, 1, 2, 3], dtype=np.int64), ridx),                                   # not from 0
+             ("csc", np.array([0, 2, 3], dtype=np.int64), np.array([0, 3, 2], dtype=np.int32))]       # row 3 of 3
+    for layout, p_, i_ in cases:
+        with pytest.raises(snap.SnapError) as e:
+            g.predict(layout, 3, p_, i_, val)
+        assert e.value.code == -1
+        if torch.cuda.is_available():                    # the same on device arrays
+            with pytest.raises(snap.SnapError) as e:
+                g.predict(layout, 3, torch.from_numpy(p_).to(DEV), torch.from_numpy(i_).to(DEV), torch.from_numpy(val).to(DEV))
+            assert e.value.code == -1
+    np.testing.assert_allclose(g.predict("csr", 3, rptr, ridx, val), [0.5, 1.0, -6.0], rtol=1e-6)   # still usable
+    g.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # streaming (Section 3.2): chunks of coordinates copied from pinned host memory while the previous
 # chunk is processed; chunk order fixed, permutation inside each chunk
