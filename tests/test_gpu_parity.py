@@ -242,6 +242,43 @@ def test_error_paths():
     assert e.value.code == -1
 
 
+def _ragged_matrix(lengths, minor, seed):
+    """Compressed arrays whose major slices have the given lengths: distinct minor indices, N(0,1) values."""
+    r = np.random.default_rng(seed)
+    ptr = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    idx = np.concatenate([np.sort(r.choice(minor, size=k, replace=False)) for k in lengths] or [np.zeros(0)]).astype(np.int32)
+    val = (r.standard_normal(ptr[-1]) / np.sqrt(max(1.0, np.mean(lengths)))).astype(np.float32)
+    return ptr, idx, val
+
+
+@pytest.mark.parametrize("loss,layout", [("ridge", "csc"), ("logistic", "csc"), ("hinge", "csr"), ("logistic", "csr")])
+def test_one_coordinate_in_flight_is_the_sequential_method(loss, layout):
+    """With a cap of one wavefront the asynchronous kernel visits the coordinates one after the other in
+    the epoch order, each seeing all earlier updates: the oracle's sequential pass, step by step, for
+    coordinates of every length around the kernel's register rounds (64 and 256 nonzeros) and its loops."""
+    lengths = np.array([0, 1, 2, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 1000, 4096] * 3)
+    np.random.default_rng(5).shuffle(lengths)
+    minor = 5000
+    ptr, idx, val = _ragged_matrix(lengths, minor, 6)
+    m = len(lengths)
+    r = np.random.default_rng(7)
+    n, d = (minor, m) if layout == "csc" else (m, minor)
+    y = r.standard_normal(n).astype(np.float32) if loss == "ridge" else np.sign(r.standard_normal(n)).astype(np.float32)
+    lam = 1e-2
+    g = snap.Solver(layout, n, d, ptr, idx, val, y, loss, lam, max_inflight_nnz=1, adaptive=False, auto_groups=False)
+    assert g.epoch_stats()["n_large"] == 0
+    o = oracle.Solver(oracle.Matrix(layout, n, d, ptr, idx, val), y, loss, lam)
+    for e in range(3):
+        g.epoch(e)
+        o.epoch(e)
+        assert np.array_equal(g.perm(), o.last_perm)
+        _, x = g.model()
+        assert relnorm(x, o.x) <= 2e-5, (e, relnorm(x, o.x))
+        assert relnorm(g.shared(), o.v) <= 2e-5
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    g.close()
+
+
 def test_predict_checks_compressed_input():
     """ptr and idx of the matrix handed to predict are checked before any kernel follows them."""
     ptr = np.array([0, 2, 3], dtype=np.int64)
