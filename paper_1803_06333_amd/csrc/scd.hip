@@ -46,13 +46,16 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
     const int lane = threadIdx.x & (WAVE - 1);
     const int64_t wave0 = ((int64_t)blockIdx.x * TPB + threadIdx.x) / WAVE;
     if (wave0 >= n_waves) return;
-    // n_waves wavefronts walk the epoch order round-robin: at most n_waves coordinates in flight
-    auto coord_of = [&](int64_t wid) -> int64_t { return wid < n_small ? cv.c0 + (int64_t)order[wid] : -1; };
-    auto range_of = [&](int64_t c, int64_t& s0, int64_t& s1) {
-        s0 = s1 = 0;
+    // n_waves wavefronts walk the epoch order round-robin: at most n_waves coordinates in flight.
+    // What a visit requests for later coordinates is only touched in the next visit, arithmetic on
+    // it included (the wait for a value sits before its first use: an addition right after the load
+    // would put the wait there, and the requests would again be served one after the other).
+    auto order_entry = [&](int64_t wid) -> uint32_t { return wid < n_small ? order[wid] : 0u; };
+    auto ptr_pair = [&](int64_t c, int64_t& p0, int64_t& p1) {
+        p0 = p1 = 0;
         if (c >= 0) {
-            s0 = cv.ptr[c] - cv.nnz_base;
-            s1 = cv.ptr[c + 1] - cv.nnz_base;
+            p0 = cv.ptr[c];
+            p1 = cv.ptr[c + 1];
         }
     };
     auto fetch = [&](int64_t c, int64_t s0, int64_t s1) -> SmallCoord<SMALL_ROUNDS> {
@@ -76,16 +79,18 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
         }
         return q;
     };
-    // fill the pipeline: three coordinates' order entries, two ranges, one record
-    int64_t cB = coord_of(wave0 + n_waves), cA = coord_of(wave0 + 2 * n_waves);
-    int64_t s0B, s1B;
+    // fill the pipeline: three coordinates' order entries, two ptr pairs, one record
+    auto coord_at = [&](int64_t wid, uint32_t entry) -> int64_t { return wid < n_small ? cv.c0 + (int64_t)entry : -1; };
+    int64_t cB = coord_at(wave0 + n_waves, order_entry(wave0 + n_waves));   // its nonzeros are requested next
+    uint32_t entryA = order_entry(wave0 + 2 * n_waves);                     // its ptr pair is read next
+    int64_t p0B, p1B;
     SmallCoord<SMALL_ROUNDS> cur;
     {
-        const int64_t c = coord_of(wave0);
-        int64_t s0, s1;
-        range_of(c, s0, s1);
-        range_of(cB, s0B, s1B);
-        cur = fetch(c, s0, s1);
+        const int64_t c = coord_at(wave0, order_entry(wave0));
+        int64_t p0, p1;
+        ptr_pair(c, p0, p1);
+        ptr_pair(cB, p0B, p1B);
+        cur = fetch(c, p0 - cv.nnz_base, p1 - cv.nnz_base);
     }
     for (int64_t wid = wave0; wid < n_small; wid += n_waves) {
         // this visit's requests
@@ -104,10 +109,11 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
                 if (KIND == K_PRIMAL_LOGISTIC) yy[j] = (cur.raw[j] & LABEL_BIT) ? -1.0f : 1.0f;
             }
         }
-        const SmallCoord<SMALL_ROUNDS> nxt = fetch(cB, s0B, s1B);
-        int64_t s0A, s1A;
-        range_of(cA, s0A, s1A);
-        const int64_t c3 = coord_of(wid + 3 * n_waves);
+        const SmallCoord<SMALL_ROUNDS> nxt = fetch(cB, p0B - cv.nnz_base, p1B - cv.nnz_base);
+        const int64_t cA = coord_at(wid + 2 * n_waves, entryA);
+        int64_t p0A, p1A;
+        ptr_pair(cA, p0A, p1A);
+        const uint32_t entry3 = order_entry(wid + 3 * n_waves);
 
         float g = 0.0f, h = 0.0f;
         // (these nonzeros stay in registers for the scatter pass)
@@ -124,7 +130,7 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
         if (KIND == K_PRIMAL_LOGISTIC) h = wave_sum(h);
         float mult = 0.0f;
         if (lane == 0) x[c] = take_step<KIND>((double)g, (double)h, cur.xc, cur.nc, cur.yc, sp, mult);
-        mult = __shfl(mult, 0, WAVE);
+        mult = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mult), 0));   // lane 0's, without an LDS round trip
         if (mult != 0.0f) {
 #pragma unroll
             for (int j = 0; j < SMALL_ROUNDS; ++j)
@@ -136,9 +142,9 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
         }
         cur = nxt;
         cB = cA;
-        s0B = s0A;
-        s1B = s1A;
-        cA = c3;
+        p0B = p0A;
+        p1B = p1A;
+        entryA = entry3;
     }
 }
 

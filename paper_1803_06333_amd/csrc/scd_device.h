@@ -11,6 +11,7 @@ struct StepParams {
     int dual_logistic; // dual form: 1 = logistic loss (Newton step on the entropy), 0 = hinge
     double inv_n;     // 1/n
     double lam_n;     // lambda * n
+    double inv_lam_n; // 1 / (lambda * n)
     double damping;   // in (0,1]: the step is scaled by it (Section 3.1, adaptive damping)
 };
 
@@ -94,15 +95,16 @@ __device__ __forceinline__ float take_step(double g, double h, float xc, float n
         if (sp.dual_logistic) {
             // -n dD/da = ln(a/(1-a)) + m,  -n d2D/da2 = 1/(a(1-a)) + q: one Newton step, kept inside (0,1)
             const double a = (double)xc;
-            const double m = (double)yc * g / sp.lam_n, q = (double)norm / sp.lam_n;
+            const double m = (double)yc * g * sp.inv_lam_n, q = (double)norm * sp.inv_lam_n;
             anew = a - (log(a) - log1p(-a) + m) / (1.0 / (a * (1.0 - a)) + q);
             anew = anew < ALPHA_EPS ? ALPHA_EPS : (anew > 1.0 - ALPHA_EPS ? 1.0 - ALPHA_EPS : anew);
         } else if (norm == 0.0f) {
             anew = 1.0;                                   // empty row: dD/dalpha = 1/n > 0
         } else {
-            const double m = (double)yc * g / sp.lam_n;   // y_i x_i.w
-            const double q = (double)norm / sp.lam_n;
-            anew = (double)xc + (1.0 - m) / q;
+            // (fp64 divisions are long instruction sequences on the one lane that takes the step, and
+            // with few rows in flight the step is on the critical path: one is left)
+            const double m = (double)yc * g * sp.inv_lam_n;   // y_i x_i.w
+            anew = (double)xc + (1.0 - m) * sp.lam_n / (double)norm;
             anew = anew < 0.0 ? 0.0 : (anew > 1.0 ? 1.0 : anew);
         }
         anew = (double)xc + sp.damping * (anew - (double)xc);   // stays inside the box
@@ -134,6 +136,7 @@ inline StepParams make_step_params(const snap_handle* h) {
     sp.dual_logistic = (h->form == SNAP_DUAL && h->loss == SNAP_LOGISTIC) ? 1 : 0;
     sp.inv_n = 1.0 / (double)h->n;
     sp.lam_n = h->lambda * (double)h->n;
+    sp.inv_lam_n = 1.0 / sp.lam_n;
     sp.damping = (double)h->damping;
     return sp;
 }
