@@ -279,6 +279,37 @@ def test_one_coordinate_in_flight_is_the_sequential_method(loss, layout):
     g.close()
 
 
+@pytest.mark.parametrize("mean_len", [3, 20, 50, 100, 400])
+def test_predict_csr_rows_of_every_length(mean_len):
+    """Decision values for CSR rows from empty to long: every lanes-per-row variant of the row kernel
+    (chosen from the mean row length) against the oracle's x_i . w."""
+    r = np.random.default_rng(100 + mean_len)
+    d = 3000
+    lengths = np.clip(r.poisson(mean_len, size=700), 0, d)
+    lengths[:12] = [0, 1, 7, 8, 9, 15, 16, 17, 63, 64, 65, min(d, 4 * mean_len)]
+    lengths[-1] = 0                                                       # a ragged tail that ends empty
+    ptr, idx, val = _ragged_matrix(lengths, d, 200 + mean_len)
+    n = len(lengths)
+    # any trained model will do: a few epochs of ridge on a small CSC problem with the same d
+    cl = r.integers(1, 40, size=d)
+    cptr, cidx, cval = _ragged_matrix(cl, 500, 300 + mean_len)
+    y = r.standard_normal(500).astype(np.float32)
+    g = snap.Solver("csc", 500, d, cptr, cidx, cval, y, "ridge", 1e-2, auto_groups=False)
+    o = oracle.Solver(oracle.Matrix("csc", 500, d, cptr, cidx, cval), y, "ridge", 1e-2)
+    for e in range(2):
+        o.epoch(e)
+    g.set_model(o.x.astype(np.float32))
+    o.x[:] = o.x.astype(np.float32)
+    want = o.predict(oracle.Matrix("csr", n, d, ptr, idx, val))
+    got = g.predict("csr", n, ptr, idx, val)
+    scale = np.abs(want).max()
+    assert np.abs(got - want).max() <= 1e-6 * scale
+    assert got[0] == 0.0 and got[-1] == 0.0
+    got_dev = g.predict("csr", n, torch.from_numpy(ptr).to(DEV), torch.from_numpy(idx).to(DEV), torch.from_numpy(val).to(DEV))
+    assert np.array_equal(got_dev.cpu().numpy(), got)                     # fixed summation order
+    g.close()
+
+
 def test_predict_checks_compressed_input():
     """ptr and idx of the matrix handed to predict are checked before any kernel follows them."""
     ptr = np.array([0, 2, 3], dtype=np.int64)
