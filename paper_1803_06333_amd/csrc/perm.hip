@@ -163,6 +163,99 @@ k_radix_scatter(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ 
     }
 }
 
+// Up to SORT_TILE coordinates: the keys, the four digit passes and the class partition in one launch
+// of one workgroup (a problem that small is bound by the sixteen launches of the general path, not by
+// their work).  The passes go through the sorter's global buffers; the workgroup's barriers order them.
+// Same keys, same stable passes: the same permutation.
+__device__ __forceinline__ void one_block_pass(const uint32_t* keys, const uint32_t* vals, uint32_t* keys_out,
+                                               uint32_t* vals_out, uint32_t m, int shift, const uint8_t* cls,
+                                               uint32_t (*cnt)[RADIX], uint32_t* wave_tot) {
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_TPB) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    const uint32_t base = w * (SORT_ROUNDS * WAVE);
+    uint32_t key[SORT_ROUNDS], val[SORT_ROUNDS], dig[SORT_ROUNDS], rank[SORT_ROUNDS];
+    const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const uint32_t i = base + r * WAVE + lane;
+        const bool live = i < m;
+        key[r] = live ? keys[i] : 0u;
+        val[r] = live ? vals[i] : 0u;
+        dig[r] = live ? digit_of(key[r], val[r], shift, cls) : 0u;
+        uint64_t peers = __ballot(live);
+#pragma unroll
+        for (int b = 0; b < RADIX_BITS; ++b) {
+            const bool bit = (dig[r] >> b) & 1u;
+            const uint64_t bal = __ballot(bit && live);
+            peers &= bit ? bal : ~bal;
+        }
+        if (!live) peers = 0;
+        const uint32_t before = cnt[w][dig[r]];                 // all lanes read before any lane writes
+        rank[r] = before + (uint32_t)__popcll(peers & lt);
+        if (live && (peers & lt) == 0) cnt[w][dig[r]] = before + (uint32_t)__popcll(peers);
+    }
+    __syncthreads();
+    // thread t holds digit t: elements with a smaller digit, then the wavefronts before this one
+    uint32_t total = 0;
+#pragma unroll
+    for (int ww = 0; ww < SORT_WAVES; ++ww) total += cnt[ww][threadIdx.x];
+    uint32_t run = total;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        const uint32_t t = __shfl_up(run, off, WAVE);
+        if (lane >= off) run += t;
+    }
+    if (lane == WAVE - 1) wave_tot[w] = run;
+    run -= total;
+    __syncthreads();
+    for (int ww = 0; ww < w; ++ww) run += wave_tot[ww];
+#pragma unroll
+    for (int ww = 0; ww < SORT_WAVES; ++ww) {
+        const uint32_t c = cnt[ww][threadIdx.x];
+        cnt[ww][threadIdx.x] = run;
+        run += c;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const uint32_t i = base + r * WAVE + lane;
+        if (i < m) {
+            const uint32_t pos = cnt[w][dig[r]] + rank[r];
+            keys_out[pos] = key[r];
+            vals_out[pos] = val[r];
+        }
+    }
+    __syncthreads();   // the next pass reads what this one wrote, and reuses cnt
+}
+
+__global__ void __launch_bounds__(SORT_TPB)
+k_sort_one_block(uint64_t seed, uint32_t chunk, uint32_t m, const uint8_t* __restrict__ cls, uint32_t* ka, uint32_t* va,
+                 uint32_t* kb, uint32_t* vb, uint32_t* __restrict__ keys_out, uint32_t* __restrict__ order_out,
+                 uint32_t* __restrict__ part_out) {
+    __shared__ uint32_t cnt[SORT_WAVES][RADIX];
+    __shared__ uint32_t wave_tot[SORT_WAVES];
+    const uint64_t base = perm_key_base(seed, chunk);
+    for (uint32_t c = threadIdx.x; c < m; c += SORT_TPB) {
+        const uint32_t k = perm_key(base, c);
+        ka[c] = k;
+        va[c] = c;
+        if (keys_out) keys_out[c] = k;
+    }
+    __syncthreads();
+    for (int shift = 0; shift < 32; shift += RADIX_BITS) {
+        one_block_pass(ka, va, kb, vb, m, shift, nullptr, cnt, wave_tot);
+        uint32_t* t = ka; ka = kb; kb = t;
+        t = va; va = vb; vb = t;
+    }
+    if (order_out)
+        for (uint32_t c = threadIdx.x; c < m; c += SORT_TPB) order_out[c] = va[c];
+    if (part_out) {
+        one_block_pass(ka, va, kb, vb, m, 0, cls, cnt, wave_tot);
+        for (uint32_t c = threadIdx.x; c < m; c += SORT_TPB) part_out[c] = vb[c];
+    }
+}
+
 int sorter_alloc(Sorter& s, int64_t max_m) {
     s.max_m = max_m > 0 ? max_m : 1;
     s.n_blocks = (s.max_m + SORT_TILE - 1) / SORT_TILE;
@@ -267,6 +360,12 @@ int make_permutation(snap_handle* h, uint64_t seed, uint32_t chunk, int64_t c0, 
     uint32_t *ka = s.keys_a, *va = s.vals_a, *kb = s.keys_b, *vb = s.vals_b;
     const uint32_t mm = (uint32_t)m;
     const int grid = (int)((m + 255) / 256 < 4096 ? (m + 255) / 256 : 4096);
+    if (!h->hk_host[0] && m <= SORT_TILE) {
+        hipLaunchKernelGGL(k_sort_one_block, dim3(1), dim3(SORT_TPB), 0, h->compute, seed, chunk, mm,
+                           part_out ? h->cls + c0 : nullptr, ka, va, kb, vb, keys_out, order_out, part_out);
+        SNAP_HIP(hipGetLastError());
+        return SNAP_OK;
+    }
     if (h->hk_host[0]) {
         const int sl = h->hk_slot;
         h->hk_slot ^= 1;
