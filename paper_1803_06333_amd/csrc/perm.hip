@@ -94,6 +94,53 @@ k_digit_scan(uint32_t* __restrict__ block_hist, uint32_t n_blocks, uint32_t* __r
     if (threadIdx.x == 0) totals[blockIdx.x] = carry_s;
 }
 
+// The SORT_ROUNDS groups of 64 elements that one wavefront owns in a digit pass: the elements, their
+// digits, and their ranks among the wavefront's elements of the same digit (inside a group from
+// ballots, across groups from the wavefront's running counts cnt_w[digit]).
+struct SortRounds {
+    uint32_t key[SORT_ROUNDS], val[SORT_ROUNDS], dig[SORT_ROUNDS], rank[SORT_ROUNDS];
+};
+
+__device__ __forceinline__ void rank_rounds(const uint32_t* keys, const uint32_t* vals, uint32_t base, uint32_t m,
+                                            int shift, const uint8_t* cls, uint32_t* cnt_w, SortRounds& q) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const uint32_t i = base + r * WAVE + lane;
+        const bool live = i < m;
+        q.key[r] = live ? keys[i] : 0u;
+        q.val[r] = live ? vals[i] : 0u;
+        q.dig[r] = live ? digit_of(q.key[r], q.val[r], shift, cls) : 0u;
+        uint64_t peers = __ballot(live);
+#pragma unroll
+        for (int b = 0; b < RADIX_BITS; ++b) {
+            const bool bit = (q.dig[r] >> b) & 1u;
+            const uint64_t bal = __ballot(bit && live);
+            peers &= bit ? bal : ~bal;
+        }
+        if (!live) peers = 0;
+        const uint32_t before = cnt_w[q.dig[r]];                 // all lanes read before any lane writes
+        q.rank[r] = before + (uint32_t)__popcll(peers & lt);
+        if (live && (peers & lt) == 0) cnt_w[q.dig[r]] = before + (uint32_t)__popcll(peers);
+    }
+}
+
+// ... and their stable scatter once cnt_w[digit] holds the first position of the wavefront's elements
+__device__ __forceinline__ void scatter_rounds(const SortRounds& q, uint32_t base, uint32_t m, const uint32_t* cnt_w,
+                                               uint32_t* keys_out, uint32_t* vals_out) {
+    const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const uint32_t i = base + r * WAVE + lane;
+        if (i < m) {
+            const uint32_t pos = cnt_w[q.dig[r]] + q.rank[r];
+            keys_out[pos] = q.key[r];
+            vals_out[pos] = q.val[r];
+        }
+    }
+}
+
 // Stable scatter of one digit pass.  Wavefront w of the workgroup owns SORT_ROUNDS consecutive
 // groups of 64 elements; inside a group the rank among equal digits comes from ballots, across
 // groups from a per-wavefront running count in LDS, across wavefronts from a small prefix sum.
@@ -118,27 +165,8 @@ k_radix_scatter(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ 
     for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_TPB) (&cnt[0][0])[i] = 0;
     __syncthreads();
     const uint32_t base = blockIdx.x * SORT_TILE + w * (SORT_ROUNDS * WAVE);
-    uint32_t key[SORT_ROUNDS], val[SORT_ROUNDS], dig[SORT_ROUNDS], rank[SORT_ROUNDS];
-    const uint64_t lt = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int r = 0; r < SORT_ROUNDS; ++r) {
-        const uint32_t i = base + r * WAVE + lane;
-        const bool live = i < m;
-        key[r] = live ? keys[i] : 0u;
-        val[r] = live ? vals[i] : 0u;
-        dig[r] = live ? digit_of(key[r], val[r], shift, cls) : 0u;
-        uint64_t peers = __ballot(live);
-#pragma unroll
-        for (int b = 0; b < RADIX_BITS; ++b) {
-            const bool bit = (dig[r] >> b) & 1u;
-            const uint64_t bal = __ballot(bit && live);
-            peers &= bit ? bal : ~bal;
-        }
-        if (!live) peers = 0;
-        const uint32_t before = cnt[w][dig[r]];                 // all lanes read before any lane writes
-        rank[r] = before + (uint32_t)__popcll(peers & lt);
-        if (live && (peers & lt) == 0) cnt[w][dig[r]] = before + (uint32_t)__popcll(peers);
-    }
+    SortRounds q;
+    rank_rounds(keys, vals, base, m, shift, cls, cnt[w], q);
     __syncthreads();
     // exclusive prefix over the wavefronts, per digit; thread t handles digit t
     {
@@ -152,15 +180,7 @@ k_radix_scatter(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ 
         }
     }
     __syncthreads();
-#pragma unroll
-    for (int r = 0; r < SORT_ROUNDS; ++r) {
-        const uint32_t i = base + r * WAVE + lane;
-        if (i < m) {
-            const uint32_t pos = cnt[w][dig[r]] + rank[r];
-            keys_out[pos] = key[r];
-            vals_out[pos] = val[r];
-        }
-    }
+    scatter_rounds(q, base, m, cnt[w], keys_out, vals_out);
 }
 
 // Up to SORT_TILE coordinates: the keys, the four digit passes and the class partition in one launch
@@ -174,27 +194,8 @@ __device__ __forceinline__ void one_block_pass(const uint32_t* keys, const uint3
     for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_TPB) (&cnt[0][0])[i] = 0;
     __syncthreads();
     const uint32_t base = w * (SORT_ROUNDS * WAVE);
-    uint32_t key[SORT_ROUNDS], val[SORT_ROUNDS], dig[SORT_ROUNDS], rank[SORT_ROUNDS];
-    const uint64_t lt = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int r = 0; r < SORT_ROUNDS; ++r) {
-        const uint32_t i = base + r * WAVE + lane;
-        const bool live = i < m;
-        key[r] = live ? keys[i] : 0u;
-        val[r] = live ? vals[i] : 0u;
-        dig[r] = live ? digit_of(key[r], val[r], shift, cls) : 0u;
-        uint64_t peers = __ballot(live);
-#pragma unroll
-        for (int b = 0; b < RADIX_BITS; ++b) {
-            const bool bit = (dig[r] >> b) & 1u;
-            const uint64_t bal = __ballot(bit && live);
-            peers &= bit ? bal : ~bal;
-        }
-        if (!live) peers = 0;
-        const uint32_t before = cnt[w][dig[r]];                 // all lanes read before any lane writes
-        rank[r] = before + (uint32_t)__popcll(peers & lt);
-        if (live && (peers & lt) == 0) cnt[w][dig[r]] = before + (uint32_t)__popcll(peers);
-    }
+    SortRounds q;
+    rank_rounds(keys, vals, base, m, shift, cls, cnt[w], q);
     __syncthreads();
     // thread t holds digit t: elements with a smaller digit, then the wavefronts before this one
     uint32_t total = 0;
@@ -217,15 +218,7 @@ __device__ __forceinline__ void one_block_pass(const uint32_t* keys, const uint3
         run += c;
     }
     __syncthreads();
-#pragma unroll
-    for (int r = 0; r < SORT_ROUNDS; ++r) {
-        const uint32_t i = base + r * WAVE + lane;
-        if (i < m) {
-            const uint32_t pos = cnt[w][dig[r]] + rank[r];
-            keys_out[pos] = key[r];
-            vals_out[pos] = val[r];
-        }
-    }
+    scatter_rounds(q, base, m, cnt[w], keys_out, vals_out);
     __syncthreads();   // the next pass reads what this one wrote, and reuses cnt
 }
 
