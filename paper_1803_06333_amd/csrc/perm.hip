@@ -20,6 +20,7 @@ constexpr int SORT_TPB = 256;
 constexpr int SORT_ROUNDS = 8;                                   // 64-element rounds per wavefront
 constexpr int SORT_TILE = SORT_TPB * SORT_ROUNDS;                // 2048 elements per workgroup
 constexpr int SORT_WAVES = SORT_TPB / WAVE;
+static_assert(SORT_TPB == RADIX, "thread t of a sort workgroup owns digit t");
 
 __global__ void k_make_keys(uint64_t seed, uint32_t chunk, uint32_t m, uint32_t* __restrict__ keys,
                             uint32_t* __restrict__ vals, uint32_t* __restrict__ keys_copy) {
