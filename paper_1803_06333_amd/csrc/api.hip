@@ -767,7 +767,8 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         if (h->chunk_events_valid)
             for (int64_t ch = 0; ch < h->n_chunks; ++ch) {
                 float a = 0, b = 0;
-                SNAP_HIP(hipEventElapsedTime(&a, h->ev_chunk[4 * ch + 0], h->ev_chunk[4 * ch + 1]));
+                if (h->chunk_copy_timed[(size_t)ch])     // (a chunk that stayed in its buffer was not copied)
+                    SNAP_HIP(hipEventElapsedTime(&a, h->ev_chunk[4 * ch + 0], h->ev_chunk[4 * ch + 1]));
                 SNAP_HIP(hipEventElapsedTime(&b, h->ev_chunk[4 * ch + 2], h->ev_chunk[4 * ch + 3]));
                 copy += a;
                 scd += b;

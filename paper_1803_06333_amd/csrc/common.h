@@ -149,6 +149,7 @@ struct snap_handle {
     double* share_out = nullptr;         // device [chunks]
     hipEvent_t* ev_chunk = nullptr;      // profile: 4 events per chunk (copy begin/end, compute begin/end)
     bool chunk_events_valid = false;
+    std::vector<char> chunk_copy_timed;  // profile: the chunk's copy events were recorded during the last pass
 
     // exact group sweeps (coordinates of a group have disjoint supports)
     bool grouped = false;

@@ -48,7 +48,10 @@ static int enqueue_copy(snap_handle* h, int64_t ch, int b, bool profile) {
     const snap_handle::Chunk& ck = h->chunks[ch];
     const size_t count = (size_t)(ck.nnz1 - ck.nnz0);
     SNAP_HIP(hipStreamWaitEvent(h->copy, h->ev_free[b], 0));
-    if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 0], h->copy));
+    if (profile) {
+        SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 0], h->copy));
+        h->chunk_copy_timed[(size_t)ch] = 1;
+    }
     if (count > 0) {
         h->bytes_copied += (int64_t)(count * (h->stream_unit ? sizeof(uint32_t) : sizeof(uint32_t) + sizeof(float)));
         SNAP_HIP(hipMemcpyAsync(h->buf_idx[b], h->host_idx + ck.nnz0, count * sizeof(uint32_t), hipMemcpyHostToDevice,
@@ -76,9 +79,12 @@ int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profil
     auto chunk_at = [&](int64_t i) { return h->pass_list ? h->pass_list[i] : i; };
     profile = profile && h->ev_chunk != nullptr && !h->pass_list;
     const int64_t first = chunk_at(0);
+    // A profiled pass times the copies it enqueues, whichever pass they serve: the fetch of the first
+    // chunk normally happens at the end of the pass before and is counted there.
+    if (profile) h->chunk_copy_timed.assign((size_t)h->n_chunks, 0);
     int b = h->buf_chunk[0] == first ? 0 : (h->buf_chunk[1] == first ? 1 : -1);
-    if (b < 0 || profile) {          // (a profiled pass times its own copy of the first chunk)
-        b = b < 0 ? 0 : b;
+    if (b < 0) {
+        b = 0;
         SNAP_TRY(enqueue_copy(h, first, b, profile));
     }
     for (int64_t i = 0; i < C; ++i) {
@@ -89,8 +95,7 @@ int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profil
         // while this one is processed -- unless it still sits there from an earlier pass (a working
         // set of two chunks is copied once)
         const int64_t next = i + 1 < C ? chunk_at(i + 1) : first;
-        if (next != ch && (h->buf_chunk[nb] != next || profile))
-            SNAP_TRY(enqueue_copy(h, next, nb, profile && i + 1 < C));
+        if (next != ch && h->buf_chunk[nb] != next) SNAP_TRY(enqueue_copy(h, next, nb, profile));
         SNAP_HIP(hipStreamWaitEvent(h->compute, h->ev_copied[b], 0));
         if (profile) SNAP_HIP(hipEventRecord(h->ev_chunk[4 * ch + 2], h->compute));
         if (fold && h->kind == K_PRIMAL_LOGISTIC && !h->buf_folded[b]) {
