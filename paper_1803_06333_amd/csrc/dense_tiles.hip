@@ -10,6 +10,7 @@
 // with a one-workgroup kernel between two passes that finishes the sums and takes the TILE_B steps
 // in the seeded order.  Tiles are visited in a seeded random order, the coordinates of a tile in the
 // order of their keys under the tile's chunk id (the chunked permutation of Section 3.2).
+#include <hip/hip_ext.h>
 #include "common.h"
 #include "perm_key.h"
 #include "scd_device.h"
@@ -415,15 +416,16 @@ int dense_tiles_epoch(snap_handle* h) {
         float* mult_prev = h->tmult + (size_t)((ti + 1) & 1) * TILE_B;
         float* mult_cur = h->tmult + (size_t)(ti & 1) * TILE_B;
         if (np == 0 && nb == 0) continue;
-        if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass], h->compute));
-#define SNAP_TILE_PASS(AL, VEC)                                                                                  \
-    hipLaunchKernelGGL((k_tile_pass<AL, VEC>), dim3((unsigned)h->tile_wgs), dim3(PASS_TPB), 0, h->compute, h->val, \
-                       h->ld, n, p0, np, mult_prev, c0, nb, h->v, h->y, h->tpartial)
+        // (profile: the two events take the kernel's own start and end times; events recorded between the
+        // launches instead cost the chain of dependent kernels 3 us each)
+        hipEvent_t ev_a = prof ? h->ev_group[2 * n_pass] : nullptr, ev_b = prof ? h->ev_group[2 * n_pass + 1] : nullptr;
+#define SNAP_TILE_PASS(AL, VEC)                                                                                    \
+    hipExtLaunchKernelGGL((k_tile_pass<AL, VEC>), dim3((unsigned)h->tile_wgs), dim3(PASS_TPB), 0, h->compute, ev_a, \
+                          ev_b, 0, h->val, h->ld, n, p0, np, mult_prev, c0, nb, h->v, h->y, h->tpartial)
         if (h->tile_vec == 1) SNAP_TILE_PASS(false, 1);
         else if (h->tile_vec == 2) SNAP_TILE_PASS(true, 2);
         else SNAP_TILE_PASS(true, 4);
 #undef SNAP_TILE_PASS
-        if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
         ++n_pass;
         if (!last) {
             hipLaunchKernelGGL(k_tile_solve, dim3(1), dim3(SOLVE_TPB), 0, h->compute, h->tpartial, (int)h->tile_wgs, c0, nb,

@@ -21,6 +21,7 @@
 // Traffic per group and row: two map entries (2 + 2 bytes), read + write of v (8 bytes), one label bit
 // (+ values unless all 1).
 #include "scd_device.h"
+#include <hip/hip_ext.h>
 #include "perm_key.h"
 
 #include <algorithm>
@@ -1072,21 +1073,22 @@ static int grouped_epoch_kind(snap_handle* h) {
         float* cbuf = compact ? h->gcbuf : nullptr;
         const uint32_t* wbase = compact ? h->gwbase + (size_t)g * (size_t)(h->g_row_wgs * (ROW_TPB / WAVE)) : nullptr;
         if (n > 0 && (scatter || histo)) {
-            if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass], h->compute));
+            // (profile: the two events take the kernel's own start and end times; events recorded between
+            // the launches instead cost the chain of dependent kernels 3 us each)
+            hipEvent_t ev_a = prof ? h->ev_group[2 * n_pass] : nullptr, ev_b = prof ? h->ev_group[2 * n_pass + 1] : nullptr;
             if (scatter && histo)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
+                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y,
+                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
             else if (scatter)
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
-                                   (const uint32_t*)nullptr);
+                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, h->v, h->y,
+                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
+                                      (const uint32_t*)nullptr);
             else
-                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                   map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y, h->ybits, n, gpart,
-                                   h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
-            if (prof) SNAP_HIP(hipEventRecord(h->ev_group[2 * n_pass + 1], h->compute));
+                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y,
+                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
             ++n_pass;
         }
         if (last) break;
