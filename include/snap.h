@@ -84,7 +84,9 @@ typedef struct {
                                     their work is ordered among them) */
     void *copy_stream;           /* hipStream_t for chunk copies, or NULL: the library's copy stream of the device */
     int refresh_v_every;         /* recompute v = A x every this many epochs; 0 = never */
-    int profile;                 /* 1: bracket each epoch's SCD kernels with HIP events */
+    int profile;                 /* 1: time each epoch's SCD kernels with HIP events; 2: the same, but the group
+                                    sweeps time only every fourth row pass, a different one each epoch, and
+                                    report the sum scaled up (timing a pass delays the chain of kernels a little) */
     int adaptive;                /* 0: default (on; off with group_bounds), 1: on, 2: off.  On: after every epoch the
                                     objective is evaluated; if it got worse the epoch's updates are
                                     discarded, the number of nonzeros in flight is halved and, once that

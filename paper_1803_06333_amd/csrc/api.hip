@@ -783,12 +783,18 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         SNAP_HIP(hipEventSynchronize(h->ev[2]));
         float total = 0, rows = 0;
         SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
-        if (h->ev_group)
+        if (h->ev_group) {
+            int timed = 0;
             for (int i = 0; i < h->n_row_passes; ++i) {
+                if (!h->pass_timed[(size_t)i]) continue;
                 float t = 0;
                 SNAP_HIP(hipEventElapsedTime(&t, h->ev_group[2 * i], h->ev_group[2 * i + 1]));
                 rows += t;
+                ++timed;
             }
+            // (profile = 2: the passes that were timed stand for the others)
+            rows = timed > 0 ? rows * (float)h->n_row_passes / (float)timed : 0.0f;
+        }
         h->stats.epoch_ms = h->stats.scd_ms = total;
         h->stats.large_ms = rows;              // the row passes
         h->stats.small_ms = total - rows;      // column-wise sums of the short coordinates + step kernels

@@ -179,6 +179,7 @@ struct snap_handle {
     int64_t gpartial_stride = 0;
     hipEvent_t* ev_group = nullptr;   // profile: begin/end of every row pass
     int n_row_passes = 0;
+    std::vector<char> pass_timed;        // profile: which row passes of the last epoch carry their two events
     int64_t g_hot_coords = 0, g_hot_nnz = 0;
     bool perm_stale = false;          // grouped mode makes the visiting order only on request
     uint64_t last_seed = 0;

@@ -392,6 +392,7 @@ int dense_tiles_setup(snap_handle* h) {
         h->ev_group = new (std::nothrow) hipEvent_t[(size_t)(2 * (T + 1))]();
         if (!h->ev_group) return SNAP_ENOMEM;
         for (int64_t i = 0; i < 2 * (T + 1); ++i) SNAP_HIP(hipEventCreate(&h->ev_group[i]));
+        h->pass_timed.assign((size_t)(T + 1), 1);
     }
     h->g_hot_coords = h->m;             // statistics: every coordinate is handled by the row passes
     h->g_hot_nnz = h->nnz;

@@ -453,6 +453,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         h->ev_group = new (std::nothrow) hipEvent_t[(size_t)(2 * (G + 1))]();
         if (!h->ev_group) return SNAP_ENOMEM;
         for (int64_t i = 0; i < 2 * (G + 1); ++i) SNAP_HIP(hipEventCreate(&h->ev_group[i]));
+        h->pass_timed.assign((size_t)(G + 1), 0);
     }
     // bookkeeping for the statistics: nonzeros and coordinates of the hot ranks
     h->g_hot_coords = h->g_hot_nnz = 0;
@@ -1075,7 +1076,11 @@ static int grouped_epoch_kind(snap_handle* h) {
         if (n > 0 && (scatter || histo)) {
             // (profile: the two events take the kernel's own start and end times; events recorded between
             // the launches instead cost the chain of dependent kernels 3 us each)
-            hipEvent_t ev_a = prof ? h->ev_group[2 * n_pass] : nullptr, ev_b = prof ? h->ev_group[2 * n_pass + 1] : nullptr;
+            // profile = 2 times one pass in four, a different one every epoch: even the attached events
+            // hold the chain up a little (4.67 / 4.72 / 4.87 ms per epoch with none / a quarter / all timed)
+            const bool timed = prof && (h->opt.profile != 2 || ((n_pass + h->epochs_done) & 3) == 0);
+            if (prof) h->pass_timed[(size_t)n_pass] = timed ? 1 : 0;   // (sized with the events, at set-up)
+            hipEvent_t ev_a = timed ? h->ev_group[2 * n_pass] : nullptr, ev_b = timed ? h->ev_group[2 * n_pass + 1] : nullptr;
             if (scatter && histo)
                 hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
                                       ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y,
