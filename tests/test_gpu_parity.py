@@ -669,15 +669,19 @@ def test_group_sweeps_are_bit_reproducible(loss):
     p = _onehot_variant(loss, True)
     groups = p.meta["field_starts"] + [p.d]
     models, shared = [], []
-    for _ in range(2):
-        g = gpu_solver(p, group_bounds=groups)
+    for profile in (0, 0, 1, 2):                           # timing the row passes (all, or one in four) changes nothing
+        g = gpu_solver(p, group_bounds=groups, profile=profile)
         for e in range(3):
             g.epoch(100 + e)
         models.append(g.model()[1].copy())
         shared.append(np.array(g.shared(), copy=True))
+        if profile:
+            st = g.epoch_stats()
+            assert st["n_items"] == len(groups) and 0.0 < st["large_ms"] < st["epoch_ms"]
         g.close()
-    assert np.array_equal(models[0], models[1])
-    assert np.array_equal(shared[0], shared[1])
+    for k in range(1, 4):
+        assert np.array_equal(models[0], models[k])
+        assert np.array_equal(shared[0], shared[k])
 
 
 def test_group_sweeps_reject_overlapping_groups():
