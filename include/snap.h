@@ -203,7 +203,9 @@ int snap_set_model(snap_handle *h, const float *coord_in);
 /* The shared vector v as the solver maintains it (host; n_rows floats primal, n_cols dual). */
 int snap_get_shared(snap_handle *h, float *v_out);
 
-/* v <- A x recomputed from the model (removes fp32 drift of the atomically updated v). */
+/* v <- A x recomputed from the model (removes fp32 drift of the atomically updated v).  The sums are
+ * taken in fp64 and rounded once, in a device buffer of 8 bytes per entry of v that is allocated for the
+ * call (fp32 sums if that allocation fails); synchronises.  snap_set_model does the same. */
 int snap_recompute_shared(snap_handle *h);
 
 /* The visiting order of the last epoch (m host uint32; streaming: chunk after chunk, absolute
