@@ -407,6 +407,33 @@ def test_streamed_epochs_match_oracle_and_resident(name, chunk_bytes, budget, un
     r.close()
 
 
+def test_profiling_a_streamed_epoch_copies_nothing_extra():
+    """options.profile times the chunk copies that an epoch makes anyway: the same bytes cross the host
+    link as without it, one matrix per epoch (the first chunk of an epoch is fetched during the epoch
+    before), and the copy and kernel times it reports are those of all chunks."""
+    p = problem("stream_uniform_logistic")
+    q = _pinned(p)
+    copied = []
+    for profile in (False, True):
+        g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, profile=profile)
+        C = len(g.chunk_bounds()) - 1
+        assert C > 2
+        g.epoch(0)
+        base = g.bytes_copied()
+        for e in range(1, 4):
+            g.epoch(e)
+        copied.append(g.bytes_copied() - base)
+        if profile:
+            st = g.epoch_stats()
+            assert st["n_chunks"] == C and st["copy_ms"] > 0.0 and st["scd_ms"] > 0.0
+        g.close()
+    assert copied[0] == copied[1] == 3 * g_stream_bytes(p)
+
+
+def g_stream_bytes(p):
+    return 4 * p.nnz          # unit values: the indices alone are streamed
+
+
 # ---------------------------------------------------------------------------------------------
 # passes over part of the chunks, chosen by their share in the duality gap (Section 3.2)
 def test_chunk_gap_shares_match_the_oracle_streamed_and_grouped():
