@@ -190,7 +190,9 @@ int snap_duality_gap(snap_handle *h, double *gap);
 /* Decision values out[i] = x_i . w for the rows of X (CSR, CSC, dense row-major or dense
  * column-major; X->n_cols must equal the training n_cols).  out has X->n_rows floats in the memory
  * space X->mem.  Compressed X is checked first (ptr from 0 to nnz without decreasing, every index in
- * range; SNAP_EINVAL otherwise, nothing written): one more pass over ptr and idx.  Synchronises. */
+ * range; SNAP_EINVAL otherwise, nothing written): one more pass over ptr and idx.  Every value is an
+ * fp64 sum rounded once to fp32 (CSC: summed with fp64 atomics in a buffer of 8 bytes per row held for the
+ * call), so the layouts agree to the last bit or two.  Synchronises. */
 int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
 
 /* w (n_cols floats, may be NULL) and the coordinate vector (w in primal form, alpha in dual form;

@@ -799,12 +799,14 @@ int predict(snap_handle* h, const snap_matrix* X, float* out) {
     float* dval = nullptr;
     float* dout = nullptr;
     uint32_t* flag = nullptr;
+    double* acc = nullptr;
     int rc = SNAP_OK;
     const bool sparse = X->layout == SNAP_CSR || X->layout == SNAP_CSC;
     const int64_t major = X->layout == SNAP_CSR ? rows : cols;
     const int64_t count = sparse ? X->nnz : rows * cols;
     auto cleanup = [&]() {
         (void)hipFree(flag);
+        (void)hipFree(acc);
         if (!on_dev) {
             (void)hipFree(dptr);
             (void)hipFree(didx);
@@ -866,12 +868,20 @@ int predict(snap_handle* h, const snap_matrix* X, float* out) {
             else if (L == 16) hipLaunchKernelGGL((k_csr_rowdot<16>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
             else hipLaunchKernelGGL((k_csr_rowdot<8>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
         } else if (X->layout == SNAP_CSC) {
-            rc = fill_zero(dout, (size_t)rows * sizeof(float), h->compute);
+            // column by column into fp64 sums (atomics), rounded once: the result does not depend on the
+            // order of the additions beyond the last bit of the fp64 sum
+            PRED_HIP(hipMalloc(&acc, (size_t)rows * sizeof(double)));
+            rc = fill_zero(acc, (size_t)rows * sizeof(double), h->compute);
             if (rc == SNAP_OK && count > 0) {
                 const int64_t nb = (count + AXPY_BLOCK - 1) / AXPY_BLOCK;
-                hipLaunchKernelGGL(k_scatter_axpy, dim3((unsigned)nb), dim3(LTPB), 0, h->compute, dptr,
+                hipLaunchKernelGGL((k_scatter_axpy<double>), dim3((unsigned)nb), dim3(LTPB), 0, h->compute, dptr,
                                    (const uint32_t*)didx, dval, (int64_t)0, (int64_t)0, cols, (int64_t)0, count, w,
-                                   (const float*)nullptr, 0xFFFFFFFFu, dout);
+                                   (const float*)nullptr, 0xFFFFFFFFu, acc);
+            }
+            if (rc == SNAP_OK) {
+                const int64_t blocks = (rows + 255) / 256;
+                hipLaunchKernelGGL(k_round_to_float, dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0,
+                                   h->compute, acc, dout, rows);
             }
         } else if (X->layout == SNAP_DENSE_ROWMAJOR) {
             hipLaunchKernelGGL(k_dense_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dval, rows, cols, cols, (int64_t)1,
