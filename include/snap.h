@@ -172,12 +172,17 @@ int snap_create(const snap_matrix *A, const float *y, int loss, double lambda,
  * permutation that perm_seed defines: a 32-bit xorshift key per coordinate, coordinates sorted by
  * (key, index).  Streaming: chunks of consecutive coordinates are visited in order, permuted
  * inside each chunk, the next chunk being copied while the current one is processed.
+ * The asynchronous engine handles two classes of coordinates with two kernels: inside a chunk the
+ * coordinates that are split over several workgroups (more than 4096 nonzeros; every coordinate of
+ * dense data) come first, the others after them, each class in the order of the permutation.
+ * snap_get_perm reports that order.
  * Stream-ordered; with options.adaptive off it returns after enqueueing (streamed data: once the
  * last chunk copy of the pass has ended), with it on it also waits for the epoch and applies the
  * accept / discard decision. */
 int snap_epoch(snap_handle *h, uint64_t perm_seed);
 
-/* P(w) above and, in the dual form, D(alpha) = (1/n) sum alpha_i - (lambda/2)||w||^2 (hinge; the
+/* Eq. (1) with the scaling given at the top of this file (Section 3.1: the objective the solver
+ * monitors): P(w) and, in the dual form, D(alpha) = (1/n) sum alpha_i - (lambda/2)||w||^2 (hinge; the
  * logistic dual is given with the forms above).
  * `dual` may be NULL; in the primal form *dual receives P - gap.  fp32 data, fp64 reductions in a
  * fixed order (deterministic). */
@@ -187,7 +192,8 @@ int snap_objective(snap_handle *h, double *primal, double *dual);
  * ||X^T u + lambda w||^2 / (2 lambda); dual form P(w(alpha)) - D(alpha).  Deterministic. */
 int snap_duality_gap(snap_handle *h, double *gap);
 
-/* Decision values out[i] = x_i . w for the rows of X (CSR, CSC, dense row-major or dense
+/* Section 3.4 (the local API follows the scikit-learn estimator interface, fit and predict): decision
+ * values out[i] = x_i . w for the rows of X (CSR, CSC, dense row-major or dense
  * column-major; X->n_cols must equal the training n_cols).  out has X->n_rows floats in the memory
  * space X->mem.  Compressed X is checked first (ptr from 0 to nnz without decreasing, every index in
  * range; SNAP_EINVAL otherwise, nothing written): one more pass over ptr and idx.  Every value is an
@@ -195,14 +201,16 @@ int snap_duality_gap(snap_handle *h, double *gap);
  * call), so the layouts agree to the last bit or two.  Synchronises. */
 int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
 
-/* w (n_cols floats, may be NULL) and the coordinate vector (w in primal form, alpha in dual form;
- * m floats, may be NULL), to host memory. */
+/* The model of eq. (1) / Algorithm 1: w (n_cols floats, may be NULL; in the dual form w = v / (lambda n))
+ * and the coordinate vector alpha of eq. (1) (w in primal form, alpha in dual form; m floats, may be
+ * NULL), to host memory. */
 int snap_get_model(snap_handle *h, float *w_out, float *coord_out);
 
 /* Overwrite the coordinate vector (m host floats) and recompute v = A x from it. */
 int snap_set_model(snap_handle *h, const float *coord_in);
 
-/* The shared vector v as the solver maintains it (host; n_rows floats primal, n_cols dual). */
+/* Algorithm 1's shared vector v = A alpha as the solver maintains it (host; n_rows floats primal,
+ * n_cols dual). */
 int snap_get_shared(snap_handle *h, float *v_out);
 
 /* v <- A x recomputed from the model (removes fp32 drift of the atomically updated v).  The sums are
@@ -210,8 +218,11 @@ int snap_get_shared(snap_handle *h, float *v_out);
  * call (fp32 sums if that allocation fails); synchronises.  snap_set_model does the same. */
 int snap_recompute_shared(snap_handle *h);
 
-/* The visiting order of the last epoch (m host uint32; streaming: chunk after chunk, absolute
- * coordinate numbers) and, if keys_out != NULL, the 32-bit key of every coordinate. */
+/* Section 3.2 (a random permutation of the coordinates of the active buffer from 32-bit xorshift
+ * keys): the order in which the last epoch visited the coordinates (m host uint32; streaming: chunk
+ * after chunk, absolute coordinate numbers; asynchronous engine: inside a chunk the split coordinates
+ * first, see snap_epoch -- without split coordinates this is the coordinates sorted by (key, index))
+ * and, if keys_out != NULL, the 32-bit key of every coordinate (indexed by coordinate). */
 int snap_get_perm(snap_handle *h, uint32_t *perm_out, uint32_t *keys_out);
 
 /* Timing of the last epoch (valid when options.profile = 1). */

@@ -196,6 +196,24 @@ class Solver:
                                             C.c_double(self.lam1), *tail)
         self.last_perm = np.concatenate(perms) if perms else np.zeros(0, dtype=np.int64)
 
+    def visit(self, order):
+        """Sequential updates of the listed coordinates (absolute numbers), one after the other in the
+        order given -- a pass in an order that the caller fixes instead of a seeded permutation."""
+        L = lib()
+        n = C.c_int64(self.A.n)
+        perm = np.ascontiguousarray(order, dtype=np.uint32)
+        tail = (_p(perm), C.c_int64(0), C.c_int64(perm.size), _p(self.x), _p(self.v))
+        if self.form == "dual":
+            fn = L.oracle_epoch_dual_hinge if self.loss == HINGE else L.oracle_epoch_dual_logistic
+            fn(n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val), _p(self.y), C.c_double(self.lam), *tail)
+        elif self.A.layout == "csc":
+            L.oracle_epoch_primal_sparse(C.c_int(self.loss), n, _p(self.A.ptr), _p(self.A.idx), _p(self.A.val),
+                                         _p(self.y), C.c_double(self.lam), C.c_double(self.lam1), *tail)
+        else:
+            L.oracle_epoch_primal_dense(C.c_int(self.loss), n, _p(self.A.val), _p(self.y), C.c_double(self.lam),
+                                        C.c_double(self.lam1), *tail)
+        self.last_perm = perm.astype(np.int64)
+
     # model ----------------------------------------------------------------------------------
     def weights(self) -> np.ndarray:
         return self.x.copy() if self.form == "primal" else self.v / (self.lam * self.A.n)

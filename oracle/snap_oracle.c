@@ -23,8 +23,8 @@
  *               hinge:    g_i(a) = -a/n + indicator[0,1](a);
  *               logistic: g_i(a) = (a ln a + (1-a) ln(1-a))/n on (0,1).
  *
- * An optional l1 term (eq. (1) covers "sparse models such as lasso and elastic-net") turns the
- * primal regulariser into g_j(w) = (lambda/2) w^2 + lambda1 |w|.
+ * An optional l1 term (eq. (1) admits lasso and elastic-net regularisers) turns the primal
+ * regulariser into g_j(w) = (lambda/2) w^2 + lambda1 |w|.
  *
  * The paper leaves the objective scaling, the update formulas, the random-key generator and the
  * duality gap unstated; the readings taken are written next to each function.

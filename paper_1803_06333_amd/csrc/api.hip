@@ -740,8 +740,7 @@ int snap_get_perm(snap_handle* h, uint32_t* perm_out, uint32_t* keys_out) {
     if (blocks) {
         // stored group by group; reported in visiting order: groups in the epoch's order, the
         // permutation of each group inside
-        std::vector<uint32_t> tmp(perm_out, perm_out + h->m), ktmp;
-        if (keys_out) ktmp.assign(keys_out, keys_out + h->m);
+        std::vector<uint32_t> tmp(perm_out, perm_out + h->m);
         int64_t pos = 0;
         for (int64_t g : group_order(h->last_seed, h->n_groups)) {
             const int64_t c0 = h->gbounds_host[g], c1 = h->gbounds_host[g + 1];
@@ -749,8 +748,27 @@ int snap_get_perm(snap_handle* h, uint32_t* perm_out, uint32_t* keys_out) {
         }
         return SNAP_OK;
     }
-    for (int64_t ch = 0; ch < h->n_chunks; ++ch)
-        for (int64_t c = h->chunks[ch].c0; c < h->chunks[ch].c1; ++c) perm_out[c] += (uint32_t)h->chunks[ch].c0;
+    // The asynchronous epoch runs the split coordinates of a chunk first and the others after them,
+    // each class in the order of the keys: that is the order reported.
+    std::vector<uint8_t> cls((size_t)h->m);
+    if (h->n_large_total > 0) {
+        SNAP_HIP(hipMemcpyAsync(cls.data(), h->cls, (size_t)h->m, hipMemcpyDeviceToHost, h->compute));
+        SNAP_HIP(hipStreamSynchronize(h->compute));
+    }
+    std::vector<uint32_t> rest;
+    for (int64_t ch = 0; ch < h->n_chunks; ++ch) {
+        const int64_t c0 = h->chunks[ch].c0, c1 = h->chunks[ch].c1;
+        for (int64_t k = c0; k < c1; ++k) perm_out[k] += (uint32_t)c0;
+        if (h->chunks[ch].n_large == 0) continue;
+        rest.clear();
+        int64_t pos = c0;
+        for (int64_t k = c0; k < c1; ++k) {
+            const uint32_t c = perm_out[k];
+            if (cls[c]) perm_out[pos++] = c;
+            else rest.push_back(c);
+        }
+        std::copy(rest.begin(), rest.end(), perm_out + pos);
+    }
     return SNAP_OK;
 }
 

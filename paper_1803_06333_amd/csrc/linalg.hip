@@ -789,6 +789,66 @@ __global__ void k_check_compressed(const int64_t* __restrict__ ptr, const int32_
     if (bad) atomicOr(flag, 1u);
 }
 
+// the flag of k_check_compressed reaches the host through mapped pinned memory, like the status word
+__global__ void k_publish_flag(const uint32_t* __restrict__ flag, double* __restrict__ host_mapped) {
+    if (threadIdx.x == 0) reinterpret_cast<uint32_t*>(host_mapped)[0] = *flag;
+}
+
+// Checks ptr / idx of a compressed matrix in device memory; `flag` is one device word (cleared here).
+static int check_compressed(snap_handle* h, int layout, const int64_t* dptr, const int32_t* didx, int64_t rows,
+                            int64_t cols, int64_t count, uint32_t* flag) {
+    const int64_t major = layout == SNAP_CSR ? rows : cols, minor = layout == SNAP_CSR ? cols : rows;
+    const int64_t work = std::max<int64_t>(major + 1, count);
+    SNAP_TRY(fill_zero(flag, sizeof(uint32_t), h->compute));
+    hipLaunchKernelGGL(k_check_compressed, dim3((unsigned)std::min<int64_t>((work + 255) / 256, 16384)), dim3(256), 0,
+                       h->compute, dptr, didx, major, minor, count, flag);
+    hipLaunchKernelGGL(k_publish_flag, dim3(1), dim3(WAVE), 0, h->compute, flag, h->red.host_mapped + 6);
+    SNAP_HIP(hipGetLastError());
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    if (reinterpret_cast<const uint32_t*>(h->red.host + 6)[0] != 0) {
+        set_error("snap_predict: ptr must start at 0, not decrease and end at nnz; idx must lie in [0, %lld)",
+                  (long long)minor);
+        return SNAP_EINVAL;
+    }
+    return SNAP_OK;
+}
+
+// The row kernels for a matrix in device memory; acc: rows fp64 sums (CSC only, cleared here).
+static int launch_rowdots(snap_handle* h, int layout, const int64_t* dptr, const int32_t* didx, const float* dval,
+                          int64_t rows, int64_t cols, int64_t count, const float* w, float* dout, double* acc) {
+    if (rows <= 0) return SNAP_OK;
+    const int grid = (int)((rows + 3) / 4 < 32768 ? (rows + 3) / 4 : 32768);
+    if (layout == SNAP_CSR) {
+        const int64_t avg = count / rows;
+        const int L = avg > 128 ? 64 : (avg > 64 ? 32 : (avg > 32 ? 16 : 8));   // about four to eight rounds per row
+        const int64_t wgs = (rows + LTPB / L - 1) / (LTPB / L);
+        const dim3 g((unsigned)std::min<int64_t>(wgs, 65536));
+        if (L == 64) hipLaunchKernelGGL((k_csr_rowdot<64>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+        else if (L == 32) hipLaunchKernelGGL((k_csr_rowdot<32>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+        else if (L == 16) hipLaunchKernelGGL((k_csr_rowdot<16>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+        else hipLaunchKernelGGL((k_csr_rowdot<8>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
+    } else if (layout == SNAP_CSC) {
+        // column by column into fp64 sums (atomics), rounded once: the result does not depend on the
+        // order of the additions beyond the last bit of the fp64 sum
+        SNAP_TRY(fill_zero(acc, (size_t)rows * sizeof(double), h->compute));
+        if (count > 0) {
+            const int64_t nb = (count + AXPY_BLOCK - 1) / AXPY_BLOCK;
+            hipLaunchKernelGGL((k_scatter_axpy<double>), dim3((unsigned)nb), dim3(LTPB), 0, h->compute, dptr,
+                               (const uint32_t*)didx, dval, (int64_t)0, (int64_t)0, cols, (int64_t)0, count, w,
+                               (const float*)nullptr, 0xFFFFFFFFu, acc);
+        }
+        const int64_t blocks = (rows + 255) / 256;
+        hipLaunchKernelGGL(k_round_to_float, dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, h->compute,
+                           acc, dout, rows);
+    } else if (layout == SNAP_DENSE_ROWMAJOR) {
+        hipLaunchKernelGGL(k_dense_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dval, rows, cols, cols, (int64_t)1, w, dout);
+    } else {
+        hipLaunchKernelGGL(k_dense_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dval, rows, cols, (int64_t)1, rows, w, dout);
+    }
+    SNAP_HIP(hipGetLastError());
+    return SNAP_OK;
+}
+
 int predict(snap_handle* h, const snap_matrix* X, float* out) {
     const float* w;
     SNAP_TRY(model_weights(h, &w));
@@ -840,57 +900,18 @@ int predict(snap_handle* h, const snap_matrix* X, float* out) {
         PRED_HIP(hipMalloc(&dout, (size_t)(rows ? rows : 1) * sizeof(float)));
     }
     if (sparse) {
-        const int64_t minor = X->layout == SNAP_CSR ? cols : rows;
-        const int64_t work = std::max<int64_t>(major + 1, count);
         PRED_HIP(hipMalloc(&flag, sizeof(uint32_t)));
-        PRED_HIP(hipMemsetAsync(flag, 0, sizeof(uint32_t), h->compute));
-        hipLaunchKernelGGL(k_check_compressed, dim3((unsigned)std::min<int64_t>((work + 255) / 256, 16384)), dim3(256), 0,
-                           h->compute, dptr, didx, major, minor, count, flag);
-        uint32_t st = 0;
-        PRED_HIP(hipMemcpyAsync(&st, flag, sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
-        PRED_HIP(hipStreamSynchronize(h->compute));
-        if (st != 0) {
-            set_error("snap_predict: ptr must start at 0, not decrease and end at nnz; idx must lie in [0, %lld)",
-                      (long long)minor);
+        rc = check_compressed(h, X->layout, dptr, didx, rows, cols, count, flag);
+        if (rc != SNAP_OK) {
             cleanup();
-            return SNAP_EINVAL;
+            return rc;
         }
     }
-    if (rows > 0) {
-        int grid = (int)((rows + 3) / 4 < 32768 ? (rows + 3) / 4 : 32768);
-        if (X->layout == SNAP_CSR) {
-            const int64_t avg = count / rows;
-            const int L = avg > 128 ? 64 : (avg > 64 ? 32 : (avg > 32 ? 16 : 8));   // about four to eight rounds per row
-            const int64_t wgs = (rows + LTPB / L - 1) / (LTPB / L);
-            const dim3 g((unsigned)std::min<int64_t>(wgs, 65536));
-            if (L == 64) hipLaunchKernelGGL((k_csr_rowdot<64>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
-            else if (L == 32) hipLaunchKernelGGL((k_csr_rowdot<32>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
-            else if (L == 16) hipLaunchKernelGGL((k_csr_rowdot<16>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
-            else hipLaunchKernelGGL((k_csr_rowdot<8>), g, dim3(LTPB), 0, h->compute, dptr, didx, dval, rows, w, dout);
-        } else if (X->layout == SNAP_CSC) {
-            // column by column into fp64 sums (atomics), rounded once: the result does not depend on the
-            // order of the additions beyond the last bit of the fp64 sum
-            PRED_HIP(hipMalloc(&acc, (size_t)rows * sizeof(double)));
-            rc = fill_zero(acc, (size_t)rows * sizeof(double), h->compute);
-            if (rc == SNAP_OK && count > 0) {
-                const int64_t nb = (count + AXPY_BLOCK - 1) / AXPY_BLOCK;
-                hipLaunchKernelGGL((k_scatter_axpy<double>), dim3((unsigned)nb), dim3(LTPB), 0, h->compute, dptr,
-                                   (const uint32_t*)didx, dval, (int64_t)0, (int64_t)0, cols, (int64_t)0, count, w,
-                                   (const float*)nullptr, 0xFFFFFFFFu, acc);
-            }
-            if (rc == SNAP_OK) {
-                const int64_t blocks = (rows + 255) / 256;
-                hipLaunchKernelGGL(k_round_to_float, dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0,
-                                   h->compute, acc, dout, rows);
-            }
-        } else if (X->layout == SNAP_DENSE_ROWMAJOR) {
-            hipLaunchKernelGGL(k_dense_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dval, rows, cols, cols, (int64_t)1,
-                               w, dout);
-        } else {
-            hipLaunchKernelGGL(k_dense_rowdot, dim3(grid), dim3(LTPB), 0, h->compute, dval, rows, cols, (int64_t)1, rows,
-                               w, dout);
-        }
-        PRED_HIP(hipGetLastError());
+    if (X->layout == SNAP_CSC && rows > 0) PRED_HIP(hipMalloc(&acc, (size_t)rows * sizeof(double)));
+    rc = launch_rowdots(h, X->layout, dptr, didx, dval, rows, cols, count, w, dout, acc);
+    if (rc != SNAP_OK) {
+        cleanup();
+        return rc;
     }
     if (!on_dev) PRED_HIP(hipMemcpyAsync(out, dout, (size_t)rows * sizeof(float), hipMemcpyDeviceToHost, h->compute));
     PRED_HIP(hipStreamSynchronize(h->compute));

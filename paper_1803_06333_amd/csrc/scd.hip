@@ -152,10 +152,10 @@ k_scd_small(ChunkView cv, const uint32_t* __restrict__ order, int64_t n_small, c
 // Everything the workgroups of one coordinate exchange (partial sums, arrival count, the published
 // step) goes through device-scope atomic operations, which are performed at the level of the
 // memory system that all compute dies share.  Ordering between them therefore only needs the
-// earlier operations to have completed (a workgroup-scope release fence = wait for outstanding
-// memory operations); a device-scope fence would also write back and invalidate the L2 of the die
-// on every work item, which costs far more than the item itself.
-__device__ __forceinline__ void wait_memory_ops() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+// earlier operations to have completed, which a data dependence on their returned values gives; a
+// device-scope fence would also write back and invalidate the L2 of the die on every work item,
+// which costs far more than the item itself.
+static_assert(sizeof(LargeState) == 32, "one coordinate's state is one 32-byte block (hipMalloc aligns the array)");
 
 // One workgroup: prefix sums of the items of the large coordinates in epoch order, zeroed state,
 // ticket counter back to zero.
@@ -296,10 +296,15 @@ k_scd_large(ChunkView cv, const uint32_t* __restrict__ order_large, int64_t n_la
                     G += (double)s_part[2 * ww];
                     H += (double)s_part[2 * ww + 1];
                 }
-                atomicAdd(&st[k].g, G);
-                atomicAdd(&st[k].h, H);
-                wait_memory_ops();                                  // both sums are in before the count
-                const uint32_t arrived = atomicAdd(&st[k].done, 1u);
+                // Both sums must have been performed before the count goes up.  The two additions return
+                // the old values, and the increment is made to depend on them: a returning atomic
+                // answers only once it has been performed where all compute dies see it, so no
+                // fence (and no assumption about how one is lowered) is needed.
+                const double g_seen = atomicAdd(&st[k].g, G);
+                const double h_seen = atomicAdd(&st[k].h, H);
+                uint32_t one = 1u;
+                asm volatile("" : "+v"(one) : "v"(g_seen), "v"(h_seen));
+                const uint32_t arrived = atomicAdd(&st[k].done, one);
                 if (arrived == (uint32_t)nseg - 1u) {              // last dot item of this coordinate
                     const double Gt = atomicAdd(&st[k].g, 0.0);
                     const double Ht = atomicAdd(&st[k].h, 0.0);

@@ -24,6 +24,21 @@ def relnorm(a, b):
     return np.linalg.norm(np.asarray(a, dtype=np.float64) - b) / max(np.linalg.norm(b), 1e-300)
 
 
+def executed_order(perm, lengths, small_max=4096, bounds=None):
+    """The order the asynchronous engine runs and reports: inside every chunk the split coordinates
+    (longer than small_max) of the permutation first, the others after them, each class in the
+    permutation's order.  perm: absolute coordinate numbers, chunk after chunk."""
+    perm = np.asarray(perm, dtype=np.int64)
+    lengths = np.asarray(lengths)
+    bounds = [0, perm.size] if bounds is None else bounds
+    out = []
+    for a, b in zip(bounds, bounds[1:]):
+        seg = perm[a:b]
+        big = lengths[seg] > small_max
+        out += [seg[big], seg[~big]]
+    return np.concatenate(out) if out else perm
+
+
 def gpu_solver(p, **kw):
     # the tests choose the epoch engine themselves: no search for groups unless a test asks for it
     kw.setdefault("auto_groups", False)
@@ -155,7 +170,10 @@ def test_permutation_is_the_oracles_on_a_real_problem():
     p = problem("cfg4_onehot_logistic")
     g = gpu_solver(p)
     g.epoch(42)
-    assert np.array_equal(g.perm(), oracle.permutation(42, p.d))
+    lengths = np.diff(p.ptr.numpy())
+    assert (lengths > 4096).any()                        # the data has coordinates of both classes
+    assert np.array_equal(g.perm(), executed_order(oracle.permutation(42, p.d), lengths))
+    assert np.array_equal(g.perm(want_keys=True)[1], oracle.permutation(42, p.d, want_keys=True)[1])
     g.close()
 
 
@@ -279,6 +297,39 @@ def test_one_coordinate_in_flight_is_the_sequential_method(loss, layout):
     g.close()
 
 
+@pytest.mark.parametrize("loss,layout", [("ridge", "csc"), ("logistic", "csc"), ("hinge", "csr"), ("logistic", "csr")])
+def test_one_workgroup_in_flight_with_split_coordinates_follows_the_reported_order(monkeypatch, loss, layout):
+    """Coordinates longer than the one-wavefront limit are split into segments and run before the
+    others.  With one workgroup and one wavefront in flight the epoch is sequential in exactly the
+    order that snap_get_perm reports, and equals the oracle visiting the coordinates in that order."""
+    monkeypatch.setenv("SNAP_SMALL_MAX", "100")          # limit of the one-wavefront class
+    monkeypatch.setenv("SNAP_SEG", "256")                # nonzeros per work item of a split coordinate
+    lengths = np.array([0, 1, 64, 100, 101, 255, 256, 257, 511, 512, 513, 1000, 3000] * 3)
+    np.random.default_rng(15).shuffle(lengths)
+    minor = 4000
+    ptr, idx, val = _ragged_matrix(lengths, minor, 16)
+    m = len(lengths)
+    r = np.random.default_rng(17)
+    n, d = (minor, m) if layout == "csc" else (m, minor)
+    y = r.standard_normal(n).astype(np.float32) if loss == "ridge" else np.sign(r.standard_normal(n)).astype(np.float32)
+    lam = 1e-2
+    g = snap.Solver(layout, n, d, ptr, idx, val, y, loss, lam, max_inflight_nnz=1, adaptive=False, auto_groups=False)
+    assert g.epoch_stats()["n_large"] == int(np.sum(lengths > 100))
+    o = oracle.Solver(oracle.Matrix(layout, n, d, ptr, idx, val), y, loss, lam)
+    for e in range(3):
+        g.epoch(e)
+        want_order = executed_order(oracle.permutation(e, m), lengths, 100)
+        got_order, keys = g.perm(want_keys=True)
+        assert np.array_equal(got_order.astype(np.int64), want_order)
+        assert np.array_equal(keys, oracle.permutation(e, m, want_keys=True)[1])
+        o.visit(want_order)
+        _, x = g.model()
+        np.testing.assert_allclose(x, o.x, rtol=2e-5, atol=2e-6 * np.abs(o.x).max())
+        np.testing.assert_allclose(g.shared(), o.v, rtol=2e-5, atol=2e-6 * np.abs(o.v).max())
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    g.close()
+
+
 @pytest.mark.parametrize("mean_len", [3, 20, 50, 100, 400])
 def test_predict_csr_rows_of_every_length(mean_len):
     """Decision values for CSR rows from empty to long: every lanes-per-row variant of the row kernel
@@ -377,7 +428,8 @@ def test_streamed_epochs_match_oracle_and_resident(name, chunk_bytes, budget, un
     for e in range(epochs):
         g.epoch(e)
         o.epoch(e)
-        assert np.array_equal(g.perm().astype(np.int64), o.last_perm), "chunked permutation differs"
+        assert np.array_equal(g.perm().astype(np.int64), executed_order(o.last_perm, np.diff(ptr), bounds=bounds)), \
+            "chunked permutation differs"
         if e % 8 == 0:
             _, x = g.model()
             chk = oracle.Solver(A, y, p.loss, p.lam)

@@ -340,6 +340,28 @@ def test_chunked_epoch_visits_every_coordinate_once_in_chunk_order():
     np.testing.assert_allclose(s.x, ridge_closed_form(X, y.astype(np.float64), lam), atol=1e-10)
 
 
+def test_pass_in_a_given_order_is_the_epoch_of_that_order():
+    """Solver.visit takes the order from the caller: with the seeded permutation it is Solver.epoch bit
+    for bit (every form), and with one coordinate it is that coordinate's exact ridge update."""
+    n, d = 60, 25
+    X = sparse_random(n, d, 0.4, rng)
+    y = np.sign(rng.standard_normal(n)).astype(np.float32)
+    for A, loss in [(dense_to_csc(X), "ridge"), (dense_to_csc(X), "logistic"), (dense_colmajor(X), "ridge"),
+                    (dense_to_csr(X), "hinge"), (dense_to_csr(X), "logistic")]:
+        a, b = oracle.Solver(A, y, loss, 0.1), oracle.Solver(A, y, loss, 0.1)
+        for e in range(3):
+            a.epoch(e)
+            b.visit(oracle.permutation(e, a.m))
+            assert np.array_equal(a.x, b.x) and np.array_equal(a.v, b.v)
+            assert np.array_equal(a.last_perm, b.last_perm)
+    s = oracle.Solver(dense_to_csc(X), y, "ridge", 0.1)
+    s.visit([7])
+    a7 = X[:, 7]
+    want = (a7 @ y.astype(np.float64) / n) / (a7 @ a7 / n + 0.1)
+    assert abs(s.x[7] - want) <= 1e-14 and np.count_nonzero(s.x) == 1
+    np.testing.assert_allclose(s.v, a7 * want, atol=1e-15)
+
+
 def test_shuffled_chunks_visit_every_coordinate_once_and_converge():
     n, d, lam = 50, 20, 0.05
     X = sparse_random(n, d, 0.5, rng)
