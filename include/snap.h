@@ -203,6 +203,17 @@ int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
 
 /* The model of eq. (1) / Algorithm 1: w (n_cols floats, may be NULL; in the dual form w = v / (lambda n))
  * and the coordinate vector alpha of eq. (1) (w in primal form, alpha in dual form; m floats, may be
+/* snap_predict for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same results as snap_predict, but X and out must
+ * be in DEVICE memory (X->mem = SNAP_MEM_DEVICE) and nothing is allocated or freed: the flag of the
+ * input check and the fp64 sums of a compressed-column matrix live in a static device array of the
+ * library (32 MiB + 256 bytes per GPU, held until the process ends).  Limit: a SNAP_CSC matrix may
+ * have at most 4 194 304 rows (SNAP_EINVAL beyond; the other layouts have no limit).  The handle's
+ * device must be the current one.  All calls on one GPU share the array: calls that overlap in time
+ * on one GPU (different handles on different streams, or different threads) race on it and must be
+ * serialised by the caller.  Synchronises. */
+int snap_predict_static(snap_handle *h, const snap_matrix *X, float *out);
+
  * NULL), to host memory. */
 int snap_get_model(snap_handle *h, float *w_out, float *coord_out);
 

@@ -27,7 +27,7 @@ EXPORTS = ["snap_create", "snap_epoch", "snap_objective", "snap_duality_gap", "s
            "snap_set_model", "snap_get_shared", "snap_recompute_shared", "snap_get_perm", "snap_get_epoch_stats",
            "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_solve", "snap_perm_key", "snap_block_order",
            "snap_epoch_chunks", "snap_chunk_gaps", "snap_solve_selected", "snap_get_bytes_copied", "snap_last_error",
-           "snap_destroy"]
+           "snap_destroy", "snap_predict_static"]
 
 
 class SnapMatrix(C.Structure):
@@ -78,6 +78,7 @@ def load_library():
         L.snap_duality_gap.argtypes = [C.c_void_p, C.POINTER(C.c_double)]
         L.snap_predict.argtypes = [C.c_void_p, C.POINTER(SnapMatrix), C.c_void_p]
         L.snap_get_model.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.snap_predict_static.argtypes = [C.c_void_p, C.POINTER(SnapMatrix), C.c_void_p]
         L.snap_set_model.argtypes = [C.c_void_p, C.c_void_p]
         L.snap_get_shared.argtypes = [C.c_void_p, C.c_void_p]
         L.snap_recompute_shared.argtypes = [C.c_void_p]
@@ -221,6 +222,16 @@ class Solver:
         return out
 
     def model(self):
+    def predict_static(self, layout: str, n_rows: int, ptr, idx, val, out):
+        """snap_predict_static: device tensors in, a caller-allocated device tensor out, nothing allocated."""
+        sm, keep = make_matrix(layout, n_rows, self.n_cols, ptr, idx, val)
+        if torch is not None and isinstance(out, torch.Tensor) and out.is_cuda:
+            torch.cuda.synchronize(out.device)       # the library reads and writes the tensors on its own stream
+        if str(out.dtype) != "torch.float32" or not out.is_contiguous() or out.numel() < n_rows:
+            raise TypeError("out must be a contiguous float32 tensor with n_rows entries")
+        _check(self._lib.snap_predict_static(self._h, C.byref(sm), out.data_ptr()))
+        return out
+
         """(w [n_cols], coordinate vector [n_coords]) as numpy arrays."""
         w = np.empty(self.n_cols, dtype=np.float32)
         x = np.empty(self.n_coords, dtype=np.float32)

@@ -673,6 +673,24 @@ int snap_predict(snap_handle* h, const snap_matrix* X, float* out) {
     return predict(h, X, out);
 }
 
+int snap_predict_static(snap_handle* h, const snap_matrix* X, float* out) {
+    if (!h || !X || !out) {
+        set_error("null argument");
+        return SNAP_EINVAL;
+    }
+    if (X->layout < SNAP_CSR || X->layout > SNAP_DENSE_COLMAJOR || X->mem < SNAP_MEM_HOST || X->mem > SNAP_MEM_DEVICE) {
+        set_error("unknown layout or memory space");
+        return SNAP_EINVAL;
+    }
+    const bool dense = X->layout >= SNAP_DENSE_ROWMAJOR;
+    if (X->n_cols != h->d || X->n_rows < 0 || X->nnz < 0 || !X->val || (!dense && (!X->ptr || !X->idx))) {
+        set_error("predict: the matrix must have the training number of columns and valid arrays");
+        return SNAP_EINVAL;
+    }
+    SNAP_TRY(check_status(h));
+    return predict_static(h, X, out);
+}
+
 int snap_get_model(snap_handle* h, float* w_out, float* coord_out) {
     if (!h) {
         set_error("null handle");

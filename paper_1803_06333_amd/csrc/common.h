@@ -270,3 +270,4 @@ int fill_zero(void* p, size_t bytes, hipStream_t s);
 int copy_pair(float* d0, const float* s0, int64_t n0, float* d1, const float* s1, int64_t n1, hipStream_t s);
 
 }  // namespace snap
+int predict_static(snap_handle* h, const snap_matrix* X, float* out);   // no allocation: scratch in a static device array

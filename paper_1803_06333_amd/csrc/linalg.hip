@@ -4,6 +4,8 @@
 // fixed order (no atomics on the reduction paths, so repeated calls give identical bits; the
 // only exception is the scatter product for compressed-column data, which uses atomics on v).
 #include "common.h"
+#include <algorithm>
+#include <mutex>
 
 namespace snap {
 
@@ -918,6 +920,70 @@ int predict(snap_handle* h, const snap_matrix* X, float* out) {
     cleanup();
 #undef PRED_HIP
     return rc;
+}
+
+// ---- decision values for callers that cannot allocate -----------------------------------------------
+// snap_predict allocates what it needs per call (the flag of the input check, the fp64 sums of a
+// compressed-column matrix).  This variant keeps both in a file-scope device array instead: one
+// copy per GPU, held until the process ends, shared by every call on that GPU (calls that overlap
+// on one GPU would race on it).  Layout: [0, 256): the flag word; then STATIC_ROWS_MAX fp64 sums.
+constexpr int64_t STATIC_ROWS_MAX = (int64_t)4 << 20;      // rows of a compressed-column matrix: 32 MiB of sums
+constexpr size_t STATIC_HEAD = 256;
+static __device__ __align__(256) unsigned char scratch[STATIC_HEAD + (size_t)STATIC_ROWS_MAX * sizeof(double)];
+
+// The array's address on the current device (each GPU holds its own copy at its own address), looked
+// up once per device.  The array's name is only a handle for this lookup in host code.
+static int static_scratch(int device, unsigned char** out) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex lock;
+    static unsigned char* ptrs[MAX_DEVICES] = {};
+    if (device < 0 || device >= MAX_DEVICES) {
+        set_error("device index %d out of range", device);
+        return SNAP_EINVAL;
+    }
+    std::lock_guard<std::mutex> guard(lock);
+    if (!ptrs[device]) {
+        void* p = nullptr;
+        SNAP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) {
+            set_error("the address of the static scratch array is null");
+            return SNAP_EHIP;
+        }
+        ptrs[device] = static_cast<unsigned char*>(p);
+    }
+    *out = ptrs[device];
+    return SNAP_OK;
+}
+
+int predict_static(snap_handle* h, const snap_matrix* X, float* out) {
+    int device = -1;
+    SNAP_HIP(hipGetDevice(&device));
+    if (device != h->device) {
+        set_error("snap_predict_static: the handle's device (%d) must be the current one (%d)", h->device, device);
+        return SNAP_EINVAL;
+    }
+    if (X->mem != SNAP_MEM_DEVICE) {
+        set_error("snap_predict_static: the matrix and the output must be in device memory (a host matrix would need a "
+                  "device copy, which this call may not allocate)");
+        return SNAP_EINVAL;
+    }
+    const int64_t rows = X->n_rows, cols = X->n_cols;
+    const bool sparse = X->layout == SNAP_CSR || X->layout == SNAP_CSC;
+    const int64_t count = sparse ? X->nnz : rows * cols;
+    if (X->layout == SNAP_CSC && rows > STATIC_ROWS_MAX) {
+        set_error("snap_predict_static: a compressed-column matrix may have at most %lld rows (the static buffer of fp64 "
+                  "sums); use snap_predict or the row layouts", (long long)STATIC_ROWS_MAX);
+        return SNAP_EINVAL;
+    }
+    unsigned char* base = nullptr;
+    SNAP_TRY(static_scratch(device, &base));
+    const float* w;
+    SNAP_TRY(model_weights(h, &w));
+    if (sparse) SNAP_TRY(check_compressed(h, X->layout, X->ptr, X->idx, rows, cols, count, reinterpret_cast<uint32_t*>(base)));
+    SNAP_TRY(launch_rowdots(h, X->layout, X->ptr, X->idx, X->val, rows, cols, count, w, out,
+                            reinterpret_cast<double*>(base + STATIC_HEAD)));
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    return SNAP_OK;
 }
 
 }  // namespace snap
