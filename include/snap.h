@@ -159,6 +159,8 @@ typedef struct {
     float small_ms;        /* the wavefront-per-coordinate kernel */
     int64_t nnz_large;     /* nonzeros of the split coordinates */
     int64_t nnz_small;     /* nonzeros of the wavefront-per-coordinate class */
+    int row_map_bytes;     /* group sweeps: bytes per entry of a row map (1, 2 or 4); 0 without groups */
+    int unit_values;       /* group sweeps / streaming: 1 when every stored value is 1.0 (no value arrays are read) */
 } snap_epoch_stats;
 
 /* Section 1 eq. (1) / Section 3.1.  Builds the solver state for X (A), y, loss and lambda:
@@ -201,8 +203,6 @@ int snap_duality_gap(snap_handle *h, double *gap);
  * call), so the layouts agree to the last bit or two.  Synchronises. */
 int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
 
-/* The model of eq. (1) / Algorithm 1: w (n_cols floats, may be NULL; in the dual form w = v / (lambda n))
- * and the coordinate vector alpha of eq. (1) (w in primal form, alpha in dual form; m floats, may be
 /* snap_predict for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid allocation.  Same results as snap_predict, but X and out must
  * be in DEVICE memory (X->mem = SNAP_MEM_DEVICE) and nothing is allocated or freed: the flag of the
@@ -214,6 +214,8 @@ int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
  * serialised by the caller.  Synchronises. */
 int snap_predict_static(snap_handle *h, const snap_matrix *X, float *out);
 
+/* The model of eq. (1) / Algorithm 1: w (n_cols floats, may be NULL; in the dual form w = v / (lambda n))
+ * and the coordinate vector alpha of eq. (1) (w in primal form, alpha in dual form; m floats, may be
  * NULL), to host memory. */
 int snap_get_model(snap_handle *h, float *w_out, float *coord_out);
 

@@ -47,7 +47,8 @@ class SnapEpochStats(C.Structure):
     _fields_ = [("epoch_ms", C.c_float), ("scd_ms", C.c_float), ("perm_ms", C.c_float), ("copy_ms", C.c_float),
                 ("n_chunks", C.c_int64), ("n_small", C.c_int64), ("n_large", C.c_int64), ("n_items", C.c_int64),
                 ("inflight_nnz", C.c_int64), ("damping", C.c_float), ("rejected", C.c_int),
-                ("large_ms", C.c_float), ("small_ms", C.c_float), ("nnz_large", C.c_int64), ("nnz_small", C.c_int64)]
+                ("large_ms", C.c_float), ("small_ms", C.c_float), ("nnz_large", C.c_int64), ("nnz_small", C.c_int64),
+                ("row_map_bytes", C.c_int), ("unit_values", C.c_int)]
 
 
 class SnapError(RuntimeError):
@@ -77,8 +78,8 @@ def load_library():
         L.snap_objective.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.snap_duality_gap.argtypes = [C.c_void_p, C.POINTER(C.c_double)]
         L.snap_predict.argtypes = [C.c_void_p, C.POINTER(SnapMatrix), C.c_void_p]
-        L.snap_get_model.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.snap_predict_static.argtypes = [C.c_void_p, C.POINTER(SnapMatrix), C.c_void_p]
+        L.snap_get_model.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.snap_set_model.argtypes = [C.c_void_p, C.c_void_p]
         L.snap_get_shared.argtypes = [C.c_void_p, C.c_void_p]
         L.snap_recompute_shared.argtypes = [C.c_void_p]
@@ -221,7 +222,6 @@ class Solver:
         _check(self._lib.snap_predict(self._h, C.byref(sm), out.ctypes.data))
         return out
 
-    def model(self):
     def predict_static(self, layout: str, n_rows: int, ptr, idx, val, out):
         """snap_predict_static: device tensors in, a caller-allocated device tensor out, nothing allocated."""
         sm, keep = make_matrix(layout, n_rows, self.n_cols, ptr, idx, val)
@@ -232,6 +232,7 @@ class Solver:
         _check(self._lib.snap_predict_static(self._h, C.byref(sm), out.data_ptr()))
         return out
 
+    def model(self):
         """(w [n_cols], coordinate vector [n_coords]) as numpy arrays."""
         w = np.empty(self.n_cols, dtype=np.float32)
         x = np.empty(self.n_coords, dtype=np.float32)
