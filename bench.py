@@ -181,12 +181,14 @@ def time_to_gap(solver, np, torch, ms_epoch, target, max_epochs, max_seconds, ze
 
 def make_problem(cfg, args, torch, datagen, dev):
     t0 = time.time()
-    p = datagen.config(cfg, device=dev, scale=args.scale)
+    # config 5 is pattern-only data (no value array: every stored value is 1), which halves what has to sit
+    # in pinned host memory; the boxes here allow about 64 GiB of it
+    p = datagen.config(cfg, device=dev, scale=args.scale, **({"pattern_only": True} if cfg == 5 else {}))
     torch.cuda.synchronize()
     kw = {}
     if cfg == 5:
         # the matrix lives in pinned host memory and is streamed in chunks (Section 3.2)
-        for name in ("ptr", "idx", "val", "y"):
+        for name in ("ptr", "idx", "y"):
             src = getattr(p, name)
             dst = torch.empty(src.shape, dtype=src.dtype, pin_memory=True)
             dst.copy_(src)

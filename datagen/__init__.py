@@ -129,7 +129,8 @@ class Problem:
 
     @property
     def nnz(self) -> int:
-        return int(self.val.numel())
+        # (val = None: pattern-only data, every stored value is 1)
+        return int(self.val.numel()) if self.val is not None else int(self.idx.numel())
 
     def to(self, device) -> "Problem":
         mv = lambda t: None if t is None else t.to(device)
@@ -273,7 +274,7 @@ def onehot_categories(n: int, d: int, seed: int, f: int, device, row0: int = 0, 
 
 
 def onehot_fields(n=45_840_617, d=1_000_000, seed=CONFIG_SEED + 4, lam=1e-6, epochs=100,
-                  pos_rate=0.256, device="cpu", want_csr=False, name="onehot_fields") -> Problem:
+                  pos_rate=0.256, device="cpu", want_csr=False, name="onehot_fields", pattern_only=False) -> Problem:
     """Configs 4/5: exactly 39 nonzeros (1.0) per row, one per field; categorical fields are
     Zipf(1.2) over disjoint column ranges, numeric fields fall into 64 log-spaced bins.
     w*_j ~ N(0, 1/39); y ~ Bernoulli(sigmoid(x.w* + b)) mapped to +-1 with b set by bisection so
@@ -307,7 +308,8 @@ def onehot_fields(n=45_840_617, d=1_000_000, seed=CONFIG_SEED + 4, lam=1e-6, epo
     b = 0.5 * (lo + hi)
     u = uniform01(stream_base(seed, 21), _arange(n, device))
     y = torch.where(u < torch.sigmoid(margin + b), 1.0, -1.0).to(torch.float32)
-    val = torch.ones(n * nf, dtype=torch.float32, device=device)
+    # pattern_only: no value array at all (val = None stands for "every stored value is 1")
+    val = None if pattern_only else torch.ones(n * nf, dtype=torch.float32, device=device)
     meta = {"wstar": wstar, "bias": b, "field_starts": starts, "field_sizes": sizes}
     if want_csr:
         meta["csr"] = (_arange(n + 1, device) * nf, csr_cols.reshape(-1),

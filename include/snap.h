@@ -30,7 +30,9 @@
  *    In streaming mode (device_budget_bytes > 0 and the matrix larger than the budget) the matrix
  *    arrays must be SNAP_MEM_HOST_PINNED and are BORROWED until snap_destroy.
  *  - Index arrays: ptr is int64[major+1] (absolute offsets, ptr[0] == 0), idx is int32[nnz] with
- *    0 <= idx < minor, val is fp32[nnz].  Dense: val only, n_rows*n_cols fp32, column-major
+ *    0 <= idx < minor, val is fp32[nnz].  For snap_create, val = NULL with a compressed layout means
+ *    pattern-only data: every stored value is 1 (one-hot encodings; no value array has to be kept
+ *    in pinned memory or copied).  Dense: val only, n_rows*n_cols fp32, column-major
  *    (element (i,j) at val[j*n_rows+i]) or row-major (val[i*n_cols+j]); ptr = idx = NULL.
  *  - Labels y: fp32[n_rows], in the same memory space as the matrix; logistic and hinge need
  *    y in {-1,+1}.

@@ -88,9 +88,11 @@ class Matrix:
     def from_problem(p) -> "Matrix":
         """From a datagen.Problem (tensors are moved to host numpy)."""
         g = lambda t: None if t is None else t.detach().cpu().numpy()
+        # (a problem without a value array is pattern-only data: every stored value is 1)
+        val = _f32(g(p.val)) if p.val is not None else np.ones(int(p.idx.numel()), dtype=np.float32)
         return Matrix(p.layout, p.n, p.d,
                       None if p.ptr is None else _i64(g(p.ptr)),
-                      None if p.idx is None else _i32(g(p.idx)), _f32(g(p.val)))
+                      None if p.idx is None else _i32(g(p.idx)), val)
 
     # products --------------------------------------------------------------------------------
     def matvec(self, x: np.ndarray) -> np.ndarray:

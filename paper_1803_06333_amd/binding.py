@@ -129,7 +129,8 @@ def make_matrix(layout: str, n_rows: int, n_cols: int, ptr, idx, val):
     if MEM_DEVICE in mems and len(mems) > 1:
         raise ValueError("matrix arrays must live in one memory space")
     mem = MEM_DEVICE if MEM_DEVICE in mems else (MEM_HOST_PINNED if mems == {MEM_HOST_PINNED} else MEM_HOST)
-    nnz = int(k3.numel() if hasattr(k3, "numel") else k3.size)
+    count_of = lambda k: int(k.numel() if hasattr(k, "numel") else k.size)
+    nnz = count_of(k3) if k3 is not None else count_of(k2)       # (val = None: pattern-only data, snap_create only)
     sm = SnapMatrix(LAYOUTS[layout], mem, n_rows, n_cols, nnz, pp, pi, pv)
     return sm, (k1, k2, k3)
 

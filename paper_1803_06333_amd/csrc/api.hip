@@ -124,7 +124,7 @@ static int create_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void
     if (!h->dense && count > 0)
         hipLaunchKernelGGL(k_check_indices, dim3(4096), dim3(256), 0, h->compute, (const int32_t*)cv.idx, count,
                            cp->minor, h->status);
-    if (h->streaming && count > 0)
+    if (h->streaming && !h->stream_unit && count > 0)
         hipLaunchKernelGGL(k_check_unit_values, dim3(4096), dim3(256), 0, h->compute, cv.val, count, h->status);
     SNAP_HIP(hipGetLastError());
     if (!h->dense && cp->freq) SNAP_TRY(count_accesses_chunk(h, cv, count, cp->freq));
@@ -252,11 +252,17 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     // ---- device memory ---------------------------------------------------------------------------
     if (h->streaming) {
         SNAP_TRY(stream_alloc(h));
+        if (!A->val) {
+            // pattern-only data: the value buffers hold ones from the start and nothing but indices is copied
+            for (int b = 0; b < 2; ++b) SNAP_TRY(fill_value(h->buf_val[b], 1.0f, h->max_chunk_nnz, h->compute));
+            h->stream_unit = true;
+        }
     } else if (!h->dense) {
         SNAP_HIP(hipMalloc(&h->idx, (size_t)(h->nnz ? h->nnz : 1) * sizeof(uint32_t)));
         SNAP_HIP(hipMalloc(&h->val, (size_t)(h->nnz ? h->nnz : 1) * sizeof(float)));
         SNAP_HIP(hipMemcpyAsync(h->idx, A->idx, (size_t)h->nnz * sizeof(uint32_t), hipMemcpyDefault, h->compute));
-        SNAP_HIP(hipMemcpyAsync(h->val, A->val, (size_t)h->nnz * sizeof(float), hipMemcpyDefault, h->compute));
+        if (A->val) SNAP_HIP(hipMemcpyAsync(h->val, A->val, (size_t)h->nnz * sizeof(float), hipMemcpyDefault, h->compute));
+        else SNAP_TRY(fill_value(h->val, 1.0f, h->nnz, h->compute));
     } else {
         const size_t count = (size_t)h->n * (size_t)h->d;
         SNAP_HIP(hipMalloc(&h->val, (count ? count : 1) * sizeof(float)));
@@ -331,7 +337,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
         set_error("labels must be +1 or -1 for this loss");
         return SNAP_EINVAL;
     }
-    if (h->streaming && !(st & 4u) && h->nnz > 0) {
+    if (h->streaming && !h->stream_unit && !(st & 4u) && h->nnz > 0) {
         // every stored value is 1.0: the value array never has to cross the host link again.  Both
         // value buffers are filled with ones once (after the prefetch that may still be writing one).
         SNAP_HIP(hipStreamSynchronize(h->copy));
@@ -413,7 +419,7 @@ int snap_create(const snap_matrix* A, const float* y, int loss, double lambda, c
         return SNAP_EINVAL;
     }
     const bool dense = A->layout == SNAP_DENSE_ROWMAJOR || A->layout == SNAP_DENSE_COLMAJOR;
-    if (!A->val || (!dense && (!A->ptr || !A->idx))) {
+    if ((dense && !A->val) || (!dense && (!A->ptr || !A->idx))) {      // (val = NULL: pattern-only data)
         set_error("matrix arrays missing");
         return SNAP_EINVAL;
     }
@@ -795,6 +801,28 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         set_error("null argument");
         return SNAP_EINVAL;
     }
+    if (h->stats_pending && h->gstream) {
+        // group sweeps over streamed row maps: copies per visit on the copy stream, kernels per visit
+        // (row pass + step kernel, measured from the moment the visit's map is there) on the compute stream
+        SNAP_HIP(hipEventSynchronize(h->ev[2]));
+        SNAP_HIP(hipStreamSynchronize(h->copy));
+        float total = 0, copy = 0, scd = 0;
+        SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
+        if (h->gev_prof && !h->gcopy_timed.empty())
+            for (int64_t i = 0; i <= h->g_visits; ++i) {
+                float a = 0, b = 0;
+                if (i < h->g_visits && h->gcopy_timed[(size_t)i])
+                    SNAP_HIP(hipEventElapsedTime(&a, h->gev_prof[4 * i + 0], h->gev_prof[4 * i + 1]));
+                SNAP_HIP(hipEventElapsedTime(&b, h->gev_prof[4 * i + 2], h->gev_prof[4 * i + 3]));
+                copy += a;
+                scd += b;
+            }
+        h->stats.epoch_ms = total;
+        h->stats.copy_ms = copy;
+        h->stats.scd_ms = scd;
+        h->stats.large_ms = h->stats.small_ms = h->stats.perm_ms = 0;
+        h->stats_pending = false;
+    }
     if (h->stats_pending && h->streaming) {
         SNAP_HIP(hipEventSynchronize(h->ev[2]));
         SNAP_HIP(hipStreamSynchronize(h->copy));
@@ -940,7 +968,8 @@ int snap_get_stream_bytes(snap_handle* h, int64_t* bytes_per_pass) {
         set_error("null argument");
         return SNAP_EINVAL;
     }
-    *bytes_per_pass = h->streaming ? h->nnz * (int64_t)(h->stream_unit ? sizeof(uint32_t) : sizeof(uint32_t) + sizeof(float)) : 0;
+    if (h->gstream) *bytes_per_pass = h->gmap_bytes_per_pass;       // the row maps of the non-empty groups
+    else *bytes_per_pass = h->streaming ? h->nnz * (int64_t)(h->stream_unit ? sizeof(uint32_t) : sizeof(uint32_t) + sizeof(float)) : 0;
     return SNAP_OK;
 }
 

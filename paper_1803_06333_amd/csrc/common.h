@@ -183,6 +183,23 @@ struct snap_handle {
     int64_t g_hot_coords = 0, g_hot_nnz = 0;
     bool perm_stale = false;          // grouped mode makes the visiting order only on request
     uint64_t last_seed = 0;
+    // group sweeps over streamed data: the row maps live in pinned host memory of the library's own and
+    // pass through a ring of three device buffers (previous group, current group, the one being copied)
+    bool gstream = false;
+    void* gmaps_host = nullptr;       // [n_groups][n_pad] row maps (uint16 or uint32), pinned
+    void* gring[3] = {nullptr, nullptr, nullptr};                // device, [n_pad] map entries each
+    int64_t gring_group[3] = {-1, -1, -1};                       // group whose map a slot holds or is being loaded with
+    // a group of at most 255 coordinates crosses the host link as one byte per row and is widened to
+    // the two-byte entries of the row pass on the device
+    uint8_t* gmap8_host = nullptr;    // [n_groups] 1: stored as bytes
+    int64_t* gmap_off_host = nullptr; // [n_groups + 1] byte offset of every group's map in gmaps_host
+    uint8_t* gring8[3] = {nullptr, nullptr, nullptr};            // device, [n_pad] bytes each: landing place of a byte map
+    bool gring_widened[3] = {false, false, false};               // the slot's byte map has been widened into gring
+    hipEvent_t gev_copied[3] = {nullptr, nullptr, nullptr}, gev_free[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t* gev_prof = nullptr;   // profile: per visit copy begin / end (copy stream), kernels begin / end (compute stream)
+    int64_t g_visits = 0;             // visits of the last pass (for the statistics)
+    std::vector<char> gcopy_timed;    // profile: the visit's map was copied (not found in the ring) in the last pass
+    int64_t gmap_bytes_per_pass = 0;  // bytes of row maps that a pass over all groups copies
 
     // exact tile sweeps (dense ridge): tiles of consecutive columns listed in gbounds_host / n_groups
     bool tiled = false;
@@ -262,6 +279,7 @@ int monitor_value(snap_handle* h, double* value);
 int chunk_gap_shares(snap_handle* h, double* shares_out);   // host array, one entry per chunk (or group)
 
 int predict(snap_handle* h, const snap_matrix* X, float* out);
+int predict_static(snap_handle* h, const snap_matrix* X, float* out);   // no allocation: scratch in a static device array
 int weights_to_host(snap_handle* h, float* w_out);
 int reducer_alloc(Reducer& r);
 void reducer_free(Reducer& r);
@@ -270,4 +288,3 @@ int fill_zero(void* p, size_t bytes, hipStream_t s);
 int copy_pair(float* d0, const float* s0, int64_t n0, float* d1, const float* s1, int64_t n1, hipStream_t s);
 
 }  // namespace snap
-int predict_static(snap_handle* h, const snap_matrix* X, float* out);   // no allocation: scratch in a static device array

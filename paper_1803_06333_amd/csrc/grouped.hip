@@ -78,6 +78,10 @@ static bool pack_knob() {
     const char* e = getenv("SNAP_PACK");             // 0 switches the packed ranks off
     return !(e && e[0] == '0');
 }
+static bool map8_knob() {
+    const char* e = getenv("SNAP_MAP8");             // 0: streamed row maps never travel as bytes
+    return !(e && e[0] == '0');
+}
 static bool compact_knob() {
     const char* e = getenv("SNAP_COMPACT");          // 0 switches the dense buffer of the short coordinates off
     return !(e && e[0] == '0');
@@ -152,6 +156,25 @@ __global__ void k_narrow_map(const uint32_t* __restrict__ wide, uint16_t* __rest
         narrow[i] = (uint16_t)wide[i];            // ranks are below 65535; "none" (all ones) stays all ones
 }
 
+// Row maps of groups with at most 255 coordinates as bytes ("none" = 0xFF) for the trip over the host
+// link, and back to the 16-bit entries that the row pass reads; four entries per thread and step.
+__global__ void k_map16_to_8(const uint16_t* __restrict__ in, uint8_t* __restrict__ out, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count / 4; i += (size_t)gridDim.x * blockDim.x) {
+        const uint2 u = reinterpret_cast<const uint2*>(in)[i];
+        reinterpret_cast<uint32_t*>(out)[i] = (u.x & 0xFFu) | ((u.x >> 16 & 0xFFu) << 8) | ((u.y & 0xFFu) << 16) | ((u.y >> 16 & 0xFFu) << 24);
+    }
+}
+__global__ void k_map8_to_16(const uint8_t* __restrict__ in, uint16_t* __restrict__ out, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count / 4; i += (size_t)gridDim.x * blockDim.x) {
+        const uint32_t u = reinterpret_cast<const uint32_t*>(in)[i];
+        auto wide = [](uint32_t b) { return b == 0xFFu ? 0xFFFFu : b; };
+        uint2 o;
+        o.x = wide(u & 0xFFu) | (wide(u >> 8 & 0xFFu) << 16);
+        o.y = wide(u >> 16 & 0xFFu) | (wide(u >> 24) << 16);
+        reinterpret_cast<uint2*>(out)[i] = o;
+    }
+}
+
 // bit (r & 7) of byte (r >> 3) = 1 when y[r] < 0
 __global__ void k_label_bits(const float* __restrict__ y, int64_t n, uint8_t* __restrict__ bits, int64_t n_bytes) {
     for (int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; b < n_bytes; b += (int64_t)gridDim.x * blockDim.x) {
@@ -171,6 +194,27 @@ void grouped_free(snap_handle* h) {
         delete[] h->ev_group;
         h->ev_group = nullptr;
     }
+    if (h->gev_prof) {
+        for (int64_t i = 0; i < 4 * (h->n_groups + 1); ++i)
+            if (h->gev_prof[i]) (void)hipEventDestroy(h->gev_prof[i]);
+        delete[] h->gev_prof;
+        h->gev_prof = nullptr;
+    }
+    for (int b = 0; b < 3; ++b) {
+        (void)hipFree(h->gring[b]);
+        (void)hipFree(h->gring8[b]);
+        h->gring[b] = nullptr;
+        h->gring8[b] = nullptr;
+        if (h->gev_copied[b]) (void)hipEventDestroy(h->gev_copied[b]);
+        if (h->gev_free[b]) (void)hipEventDestroy(h->gev_free[b]);
+        h->gev_copied[b] = h->gev_free[b] = nullptr;
+    }
+    if (h->gmaps_host) (void)hipHostFree(h->gmaps_host);
+    h->gmaps_host = nullptr;
+    delete[] h->gmap8_host;
+    delete[] h->gmap_off_host;
+    h->gmap8_host = nullptr;
+    h->gmap_off_host = nullptr;
     delete[] h->gbounds_host;
     delete[] h->ghot_host;
     delete[] h->gk64_host;
@@ -311,11 +355,16 @@ int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bou
 }
 
 static int cold_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>& coord_of);
+static int streamed_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>& coord_of);
 
 int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_t G) {
     const int64_t m = h->m, n = h->n;
-    if (h->form != SNAP_PRIMAL || h->dense || h->streaming) {
-        set_error("group sweeps need the primal form on resident sparse data");
+    if (h->form != SNAP_PRIMAL || h->dense) {
+        set_error("group sweeps need the primal form on sparse data");
+        return SNAP_EUNSUPPORTED;
+    }
+    if (h->streaming && !h->stream_unit) {
+        set_error("group sweeps on streamed data need all stored values to be 1 (pattern-only data)");
         return SNAP_EUNSUPPORTED;
     }
     if (!gb || G < 1 || gb[0] != 0 || gb[G] != m) {
@@ -380,15 +429,42 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     for (int64_t g = 0; g < G; ++g)
         if (gb[g + 1] - gb[g] > 65535) h->map16 = false;
     h->n_pad = (n + 7) / 8 * 8;
-    const size_t map_count = (size_t)G * (size_t)h->n_pad;
-    int64_t* d_gb = nullptr;
-    uint32_t* flags = nullptr;
-    uint32_t* wide = nullptr;
     SNAP_HIP(hipMalloc(&h->rank_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->coord_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->gdelta, (size_t)(m ? m : 1) * sizeof(float)));
     SNAP_HIP(hipMalloc(&h->gpartial, (size_t)h->g_row_wgs * (size_t)h->gpartial_stride * sizeof(long long)));
     SNAP_HIP(hipMalloc(&h->ybits, (size_t)(h->n_pad / 8 + 16)));
+    SNAP_HIP(hipMemcpyAsync(h->rank_of, rank_of.data(), (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
+    SNAP_HIP(hipMemcpyAsync(h->coord_of, coord_of.data(), (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
+    SNAP_TRY(fill_zero(h->gdelta, (size_t)m * sizeof(float), h->compute));
+    hipLaunchKernelGGL(k_label_bits, dim3(4096), dim3(256), 0, h->compute, h->y, n, h->ybits, h->n_pad / 8);
+    SNAP_HIP(hipGetLastError());
+    SNAP_HIP(hipStreamSynchronize(h->compute));     // (the host tables above are read by the copies)
+    if (h->opt.profile) {
+        h->ev_group = new (std::nothrow) hipEvent_t[(size_t)(2 * (G + 1))]();
+        if (!h->ev_group) return SNAP_ENOMEM;
+        for (int64_t i = 0; i < 2 * (G + 1); ++i) SNAP_HIP(hipEventCreate(&h->ev_group[i]));
+        h->pass_timed.assign((size_t)(G + 1), 0);
+    }
+    // bookkeeping for the statistics: nonzeros and coordinates of the hot ranks
+    h->g_hot_coords = h->g_hot_nnz = 0;
+    for (int64_t g = 0; g < G; ++g) {
+        h->g_hot_coords += h->ghot_host[g];
+        for (int r = 0; r < h->ghot_host[g]; ++r) {
+            const int64_t c = coord_of[(size_t)(gb[g] + r)];
+            h->g_hot_nnz += hptr[c + 1] - hptr[c];
+        }
+    }
+    if (h->streaming) {
+        SNAP_TRY(streamed_setup(h, hptr, coord_of));
+        h->grouped = true;
+        return SNAP_OK;
+    }
+
+    const size_t map_count = (size_t)G * (size_t)h->n_pad;
+    int64_t* d_gb = nullptr;
+    uint32_t* flags = nullptr;
+    uint32_t* wide = nullptr;
     SNAP_HIP(hipMalloc(&d_gb, (size_t)(G + 1) * sizeof(int64_t)));
     SNAP_HIP(hipMalloc(&flags, 2 * sizeof(uint32_t)));
     auto fail = [&](int rc) {
@@ -402,11 +478,8 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         hipError_t e_ = (call);                                                    \
         if (e_ != hipSuccess) return fail(hip_fail(e_, #call, __FILE__, __LINE__)); \
     } while (0)
-    G_HIP(hipMemcpyAsync(h->rank_of, rank_of.data(), (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
-    G_HIP(hipMemcpyAsync(h->coord_of, coord_of.data(), (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
     G_HIP(hipMemcpyAsync(d_gb, gb, (size_t)(G + 1) * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
     int rc = fill_zero(flags, 8, h->compute);
-    if (rc == SNAP_OK) rc = fill_zero(h->gdelta, (size_t)m * sizeof(float), h->compute);
     if (rc != SNAP_OK) return fail(rc);
     // values: all ones (no per-row value arrays) or not, and their largest magnitude
     uint32_t fl2[2] = {0, 0};
@@ -432,7 +505,6 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     if (h->nnz > 0)
         hipLaunchKernelGGL(k_build_rowmap, dim3((unsigned)((h->nnz + 4095) / 4096)), dim3(256), 0, h->compute, h->ptr,
                            h->idx, h->val, m, h->nnz, d_gb, G, h->rank_of, h->n_pad, wide, h->rowval, flags);
-    hipLaunchKernelGGL(k_label_bits, dim3(4096), dim3(256), 0, h->compute, h->y, n, h->ybits, h->n_pad / 8);
     if (h->map16) {
         G_HIP(hipMalloc(&h->rowmap, map_count * sizeof(uint16_t)));
         hipLaunchKernelGGL(k_narrow_map, dim3(8192), dim3(256), 0, h->compute, wide, (uint16_t*)h->rowmap, map_count);
@@ -448,21 +520,6 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     if (fl2[0] & 1u) {
         set_error("two coordinates of one group share a row: the groups are not disjoint");
         return SNAP_EINVAL;
-    }
-    if (h->opt.profile) {
-        h->ev_group = new (std::nothrow) hipEvent_t[(size_t)(2 * (G + 1))]();
-        if (!h->ev_group) return SNAP_ENOMEM;
-        for (int64_t i = 0; i < 2 * (G + 1); ++i) SNAP_HIP(hipEventCreate(&h->ev_group[i]));
-        h->pass_timed.assign((size_t)(G + 1), 0);
-    }
-    // bookkeeping for the statistics: nonzeros and coordinates of the hot ranks
-    h->g_hot_coords = h->g_hot_nnz = 0;
-    for (int64_t g = 0; g < G; ++g) {
-        h->g_hot_coords += h->ghot_host[g];
-        for (int r = 0; r < h->ghot_host[g]; ++r) {
-            const int64_t c = coord_of[(size_t)(gb[g] + r)];
-            h->g_hot_nnz += hptr[c + 1] - hptr[c];
-        }
     }
     rc = cold_setup(h, hptr, coord_of);
     if (rc != SNAP_OK) return rc;
@@ -550,16 +607,16 @@ k_cold_rows(const MAPT* __restrict__ map, int hot, int64_t n, uint32_t* __restri
 // cidx[start of the rank + i] <- buffer position of the row of the coordinate's i-th nonzero (the label
 // bit of the row index, when there is one, is carried along); one wavefront per coordinate.
 __global__ void __launch_bounds__(256)
-k_cold_index(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, const uint32_t* __restrict__ coord_of,
-             const int64_t* __restrict__ cptr, int64_t g0, int hot, int64_t group_size, uint32_t label_mask,
-             const uint32_t* __restrict__ rowpos, uint32_t* __restrict__ cidx) {
+k_cold_index(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, int64_t nnz_base,
+             const uint32_t* __restrict__ coord_of, const int64_t* __restrict__ cptr, int64_t g0, int hot,
+             int64_t group_size, uint32_t label_mask, const uint32_t* __restrict__ rowpos, uint32_t* __restrict__ cidx) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
     const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / WAVE;
     for (int64_t rk = hot + wave0; rk < group_size; rk += nwaves) {
         const int64_t c = coord_of[g0 + rk], p0 = ptr[c], len = ptr[c + 1] - p0, k0 = cptr[g0 + rk];
         for (int64_t i = lane; i < len; i += WAVE) {
-            const uint32_t e = idx[p0 + i];
+            const uint32_t e = idx[p0 + i - nnz_base];       // (idx holds the nonzeros from nnz_base on)
             cidx[k0 + i] = rowpos[e & ~label_mask] | (e & label_mask);
         }
     }
@@ -621,8 +678,8 @@ static int cold_setup_maps(snap_handle* h, const std::vector<int64_t>& cold_rows
         hipLaunchKernelGGL((k_cold_rows<MAPT, true>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), 0, h->compute,
                            maps + (size_t)g * h->n_pad, hot, n, h->gwbase + (size_t)g * nwaves, rowpos);
         const int blocks = (int)std::min<int64_t>((sz - hot + 3) / 4, 16384);
-        hipLaunchKernelGGL(k_cold_index, dim3((unsigned)blocks), dim3(256), 0, h->compute, h->ptr, h->idx, h->coord_of, h->gcptr, g0,
-                           hot, sz, label_mask, rowpos, h->gcidx);
+        hipLaunchKernelGGL(k_cold_index, dim3((unsigned)blocks), dim3(256), 0, h->compute, h->ptr, h->idx, (int64_t)0, h->coord_of,
+                           h->gcptr, g0, hot, sz, label_mask, rowpos, h->gcidx);
     }
     C_HIP(hipGetLastError());
     C_HIP(hipStreamSynchronize(h->compute));
@@ -662,6 +719,201 @@ static int cold_setup(snap_handle* h, const int64_t* hptr, const std::vector<uin
         return SNAP_OK;
     }
     return h->map16 ? cold_setup_maps<uint16_t>(h, cold_rows, cptr, total) : cold_setup_maps<uint32_t>(h, cold_rows, cptr, total);
+}
+
+// ---- streamed data: the row maps are built group by group into pinned host memory ------------------------
+// The matrix stays in the caller's pinned host memory (Section 3.2).  What an epoch of group sweeps
+// reads per nonzero is not its 4-byte row index but the 1-2-byte row-map entry, so the library keeps
+// the maps -- in pinned host memory of its own, built once at creation -- and streams those: a group's
+// nonzeros are copied to a staging buffer, turned into the group's row map on the device, and the map
+// is copied back to the host.  The index lists of the short coordinates (a few percent of the
+// nonzeros) stay on the device.
+__global__ void __launch_bounds__(256)
+k_build_rowmap_group(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, int64_t k_lo, int64_t k_hi,
+                     int64_t c_lo, int64_t c_hi, const uint32_t* __restrict__ rank_of, uint32_t* __restrict__ wide,
+                     uint32_t* __restrict__ flags) {
+    // idx holds the nonzeros [k_lo, k_hi) of the coordinates [c_lo, c_hi); one block per 4096 of them
+    const int64_t b0 = k_lo + (int64_t)blockIdx.x * 4096, b1 = min(k_hi, b0 + 4096);
+    int64_t lo = c_lo, hi = c_hi;                 // coordinate of the block's first nonzero
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr[mid] <= b0) lo = mid; else hi = mid;
+    }
+    const int64_t cstart = lo;
+    for (int64_t k = b0 + threadIdx.x; k < b1; k += 256) {
+        int64_t l = cstart, step = 1;
+        while (l + step < c_hi && ptr[l + step] <= k) { l += step; step <<= 1; }
+        int64_t r = min(c_hi, l + step);
+        while (r - l > 1) {
+            const int64_t mid = (l + r) >> 1;
+            if (ptr[mid] <= k) l = mid; else r = mid;
+        }
+        const uint32_t row = idx[k - k_lo] & ~LABEL_BIT;
+        if (atomicCAS(wide + row, RANK_NONE, rank_of[l]) != RANK_NONE) atomicOr(flags, 1u);
+    }
+}
+
+template <typename MAPT>
+static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
+    const int64_t G = h->n_groups, m = h->m, n = h->n;
+    const int nwaves = h->g_row_wgs * (ROW_TPB / WAVE);
+    // host-side plan of the short coordinates' index lists (as for resident data)
+    h->gcompact_host = new (std::nothrow) uint8_t[(size_t)G]();
+    if (!h->gcompact_host) return SNAP_ENOMEM;
+    std::vector<int64_t> cptr((size_t)m + 1, 0), cold_rows((size_t)G, 0);
+    std::vector<uint32_t> coord_of((size_t)m);
+    SNAP_HIP(hipMemcpy(coord_of.data(), h->coord_of, (size_t)m * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    int64_t total = 0, most = 0, max_group_nnz = 0;
+    for (int64_t g = 0; g < G; ++g) {
+        const int64_t g0 = h->gbounds_host[g], g1 = h->gbounds_host[g + 1];
+        const int hot = h->ghot_host[g];
+        for (int64_t r = 0; r < g1 - g0; ++r) {
+            cptr[(size_t)(g0 + r)] = total;
+            if (r >= hot) {           // (also in a group without hot ranks: the column indices are not on the device)
+                const int64_t c = coord_of[(size_t)(g0 + r)];
+                total += hptr[c + 1] - hptr[c];
+                cold_rows[(size_t)g] += hptr[c + 1] - hptr[c];
+            }
+        }
+        h->gcompact_host[g] = cold_rows[(size_t)g] > 0;
+        most = std::max(most, cold_rows[(size_t)g]);
+        max_group_nnz = std::max(max_group_nnz, hptr[g1] - hptr[g0]);
+    }
+    cptr[(size_t)m] = total;
+    if (max_group_nnz > h->n_pad) {               // more nonzeros than rows: some row is in two coordinates
+        set_error("two coordinates of one group share a row: the groups are not disjoint");
+        return SNAP_EINVAL;
+    }
+    if (total > 0 && !compact_knob()) {
+        set_error("group sweeps on streamed data need the dense buffer of the short coordinates (SNAP_COMPACT=0 is set)");
+        return SNAP_EUNSUPPORTED;
+    }
+    const size_t map_bytes = (size_t)h->n_pad * sizeof(MAPT);
+    h->gmap8_host = new (std::nothrow) uint8_t[(size_t)G]();
+    h->gmap_off_host = new (std::nothrow) int64_t[(size_t)G + 1]();
+    if (!h->gmap8_host || !h->gmap_off_host) return SNAP_ENOMEM;
+    bool any8 = false;
+    for (int64_t g = 0; g < G; ++g) {
+        const int64_t sz = h->gbounds_host[g + 1] - h->gbounds_host[g];
+        h->gmap8_host[g] = sizeof(MAPT) == 2 && sz <= 255 && map8_knob();      // ranks 0 .. 254, 255 = none
+        any8 = any8 || h->gmap8_host[g];
+        h->gmap_off_host[g + 1] = h->gmap_off_host[g] + (sz == 0 ? 0 : h->gmap8_host[g] ? (int64_t)h->n_pad : (int64_t)map_bytes);
+    }
+    h->gmap_bytes_per_pass = h->gmap_off_host[G];
+    SNAP_HIP(hipHostMalloc(&h->gmaps_host, (size_t)std::max<int64_t>(h->gmap_off_host[G], 8), hipHostMallocDefault));
+    for (int b = 0; b < 3; ++b) {
+        SNAP_HIP(hipMalloc(&h->gring[b], map_bytes));
+        if (any8) SNAP_HIP(hipMalloc(&h->gring8[b], (size_t)h->n_pad));
+        SNAP_HIP(hipEventCreateWithFlags(&h->gev_copied[b], hipEventDisableTiming));
+        SNAP_HIP(hipEventCreateWithFlags(&h->gev_free[b], hipEventDisableTiming));
+        h->gring_group[b] = -1;
+    }
+    SNAP_HIP(hipMalloc(&h->gwbase, (size_t)G * (size_t)nwaves * sizeof(uint32_t)));
+    SNAP_HIP(hipMalloc(&h->gcptr, (size_t)(m + 1) * sizeof(int64_t)));
+    SNAP_HIP(hipMalloc(&h->gcidx, (size_t)(total ? total : 1) * sizeof(uint32_t)));
+    SNAP_HIP(hipMalloc(&h->gcbuf, (size_t)(most ? most : 1) * sizeof(float)));
+    SNAP_HIP(hipMemcpyAsync(h->gcptr, cptr.data(), (size_t)(m + 1) * sizeof(int64_t), hipMemcpyHostToDevice, h->compute));
+    SNAP_TRY(fill_zero(h->gwbase, (size_t)G * (size_t)nwaves * sizeof(uint32_t), h->compute));
+    uint32_t *stage = nullptr, *wide = nullptr, *rowpos = nullptr, *flags = nullptr;
+    auto fail = [&](int rc) {
+        (void)hipStreamSynchronize(h->compute);
+        (void)hipFree(stage);
+        (void)hipFree(wide);
+        (void)hipFree(rowpos);
+        (void)hipFree(flags);
+        return rc;
+    };
+#define S_HIP(call)                                                                \
+    do {                                                                           \
+        hipError_t e_ = (call);                                                    \
+        if (e_ != hipSuccess) return fail(hip_fail(e_, #call, __FILE__, __LINE__)); \
+    } while (0)
+#define S_TRY(call)                          \
+    do {                                     \
+        int rc_ = (call);                    \
+        if (rc_ != SNAP_OK) return fail(rc_); \
+    } while (0)
+    S_HIP(hipMalloc(&stage, (size_t)(max_group_nnz ? max_group_nnz : 1) * sizeof(uint32_t)));
+    S_HIP(hipMalloc(&wide, (size_t)h->n_pad * sizeof(uint32_t)));
+    S_HIP(hipMalloc(&rowpos, (size_t)h->n_pad * sizeof(uint32_t)));
+    S_HIP(hipMalloc(&flags, sizeof(uint32_t)));
+    S_TRY(fill_zero(flags, sizeof(uint32_t), h->compute));
+    S_TRY(fill_zero(rowpos, (size_t)h->n_pad * sizeof(uint32_t), h->compute));   // (every entry a valid position)
+    const uint32_t label_mask = h->kind == K_PRIMAL_LOGISTIC ? LABEL_BIT : 0u;
+    std::vector<uint32_t> slots((size_t)nwaves);
+    for (int64_t g = 0; g < G; ++g) {
+        const int64_t g0 = h->gbounds_host[g], g1 = h->gbounds_host[g + 1], sz = g1 - g0;
+        const int64_t k_lo = hptr[g0], k_hi = hptr[g1], cnt = k_hi - k_lo;
+        const int hot = h->ghot_host[g];
+        MAPT* narrow = (MAPT*)h->gring[0];        // (the ring is not in use yet)
+        if (sz == 0) continue;
+        hipLaunchKernelGGL(k_fill_u32, dim3(8192), dim3(256), 0, h->compute, wide, (size_t)h->n_pad, RANK_NONE);
+        if (cnt > 0) {
+            S_HIP(hipMemcpyAsync(stage, h->host_idx + k_lo, (size_t)cnt * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
+            if (label_mask) S_TRY(fold_labels(h, stage, cnt, h->compute));
+            hipLaunchKernelGGL(k_build_rowmap_group, dim3((unsigned)((cnt + 4095) / 4096)), dim3(256), 0, h->compute, h->ptr,
+                               stage, k_lo, k_hi, g0, g1, h->rank_of, wide, flags);
+        }
+        if (sizeof(MAPT) == 2)
+            hipLaunchKernelGGL(k_narrow_map, dim3(8192), dim3(256), 0, h->compute, wide, (uint16_t*)narrow, (size_t)h->n_pad);
+        const MAPT* dev_map = sizeof(MAPT) == 2 ? narrow : (const MAPT*)wide;
+        S_HIP(hipGetLastError());
+        if (h->gmap8_host[g]) {
+            hipLaunchKernelGGL(k_map16_to_8, dim3(8192), dim3(256), 0, h->compute, (const uint16_t*)dev_map, h->gring8[0], (size_t)h->n_pad);
+            S_HIP(hipGetLastError());
+            S_HIP(hipMemcpyAsync((char*)h->gmaps_host + h->gmap_off_host[g], h->gring8[0], (size_t)h->n_pad, hipMemcpyDeviceToHost, h->compute));
+        } else {
+            S_HIP(hipMemcpyAsync((char*)h->gmaps_host + h->gmap_off_host[g], dev_map, map_bytes, hipMemcpyDeviceToHost, h->compute));
+        }
+        if (h->gcompact_host[g] && n > 0) {
+            uint32_t* wb = h->gwbase + (size_t)g * nwaves;
+            hipLaunchKernelGGL((k_cold_rows<MAPT, false>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), 0, h->compute, dev_map,
+                               hot, n, wb, (uint32_t*)nullptr);
+            S_HIP(hipGetLastError());
+            S_HIP(hipMemcpyAsync(slots.data(), wb, slots.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+            S_HIP(hipStreamSynchronize(h->compute));
+            uint64_t sum = 0;
+            for (int w = 0; w < nwaves; ++w) {
+                const uint32_t count = slots[(size_t)w];
+                slots[(size_t)w] = (uint32_t)sum;
+                sum += count;
+            }
+            if ((int64_t)sum != cold_rows[(size_t)g]) {      // the row map and the column lengths disagree
+                set_error("internal error: the rows of the short coordinates do not add up");
+                return fail(SNAP_ESTATE);
+            }
+            S_HIP(hipMemcpyAsync(wb, slots.data(), slots.size() * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
+            hipLaunchKernelGGL((k_cold_rows<MAPT, true>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), 0, h->compute, dev_map,
+                               hot, n, wb, rowpos);
+            const int blocks = (int)std::min<int64_t>((sz - hot + 3) / 4, 16384);
+            hipLaunchKernelGGL(k_cold_index, dim3((unsigned)blocks), dim3(256), 0, h->compute, h->ptr, stage, k_lo, h->coord_of,
+                               h->gcptr, g0, hot, sz, label_mask, rowpos, h->gcidx);
+            S_HIP(hipGetLastError());
+        }
+        S_HIP(hipStreamSynchronize(h->compute));    // staging buffers and `slots` are reused by the next group
+    }
+    uint32_t fl = 0;
+    S_HIP(hipMemcpy(&fl, flags, sizeof(uint32_t), hipMemcpyDeviceToHost));
+#undef S_HIP
+#undef S_TRY
+    (void)fail(SNAP_OK);
+    if (fl & 1u) {
+        set_error("two coordinates of one group share a row: the groups are not disjoint");
+        return SNAP_EINVAL;
+    }
+    if (h->opt.profile) {
+        h->gev_prof = new (std::nothrow) hipEvent_t[(size_t)(4 * (G + 1))]();
+        if (!h->gev_prof) return SNAP_ENOMEM;
+        for (int64_t i = 0; i < 4 * (G + 1); ++i) SNAP_HIP(hipEventCreate(&h->gev_prof[i]));
+    }
+    return SNAP_OK;
+}
+
+static int streamed_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>&) {
+    h->unit_values = true;                 // (checked by the caller: streamed group sweeps take pattern-only data)
+    h->gscale_exp = 1;                     // largest |value| = 1 <= 2^1, as frexp gives it for resident data
+    h->gstream = true;
+    return h->map16 ? streamed_setup_maps<uint16_t>(h, hptr) : streamed_setup_maps<uint32_t>(h, hptr);
 }
 
 // Scales of the sums (powers of two, exact in fp32).  Logistic: a loss' <= 2^e in magnitude gets 19 - e
@@ -1036,6 +1288,41 @@ std::vector<int64_t> group_order(uint64_t seed, int64_t n_groups) {
     return order;
 }
 
+// Streamed row maps: enqueue the copy of group g's map into ring slot `slot` on the copy stream, once
+// the last pass that read the slot's earlier content is done.  A map that still sits in the slot is not
+// copied again.  prof >= 0: the copy's start and end are recorded in that visit's pair of events.
+static int enqueue_map_copy(snap_handle* h, int64_t g, int slot, int64_t prof) {
+    if (prof >= 0) h->gcopy_timed[(size_t)prof] = 0;
+    if (h->gring_group[slot] == g) return SNAP_OK;
+    const size_t map_bytes = (size_t)(h->gmap_off_host[g + 1] - h->gmap_off_host[g]);
+    const bool bytes8 = h->gmap8_host[g] != 0;
+    SNAP_HIP(hipStreamWaitEvent(h->copy, h->gev_free[slot], 0));
+    if (prof >= 0) {
+        SNAP_HIP(hipEventRecord(h->gev_prof[4 * prof + 0], h->copy));
+        h->gcopy_timed[(size_t)prof] = 1;
+    }
+    SNAP_HIP(hipMemcpyAsync(bytes8 ? (void*)h->gring8[slot] : h->gring[slot], (const char*)h->gmaps_host + h->gmap_off_host[g],
+                            map_bytes, hipMemcpyHostToDevice, h->copy));
+    h->gring_widened[slot] = !bytes8;
+    if (prof >= 0) SNAP_HIP(hipEventRecord(h->gev_prof[4 * prof + 1], h->copy));
+    SNAP_HIP(hipEventRecord(h->gev_copied[slot], h->copy));
+    h->gring_group[slot] = g;
+    h->bytes_copied += (int64_t)map_bytes;
+    return SNAP_OK;
+}
+
+// The compute stream takes over ring slot `slot`: wait for its copy and, for a byte map, widen it.
+static int acquire_map(snap_handle* h, int slot) {
+    SNAP_HIP(hipStreamWaitEvent(h->compute, h->gev_copied[slot], 0));
+    if (!h->gring_widened[slot]) {
+        hipLaunchKernelGGL(k_map8_to_16, dim3(4096), dim3(256), 0, h->compute, h->gring8[slot], (uint16_t*)h->gring[slot],
+                           (size_t)h->n_pad);
+        SNAP_HIP(hipGetLastError());
+        h->gring_widened[slot] = true;
+    }
+    return SNAP_OK;
+}
+
 template <int KIND, bool UNIT, typename MAPT>
 static int grouped_epoch_kind(snap_handle* h) {
     const StepParams sp = make_step_params(h);
@@ -1051,18 +1338,32 @@ static int grouped_epoch_kind(snap_handle* h) {
     // ... or, for a pass over part of the groups, the caller's list
     const std::vector<int64_t> gorder =
         h->pass_list ? std::vector<int64_t>(h->pass_list, h->pass_list + h->pass_count) : group_order(h->last_seed, G);
-    const int64_t n_visit = (int64_t)gorder.size();
+    std::vector<int64_t> visits;                    // the non-empty groups, in visiting order
+    for (int64_t g : gorder)
+        if (h->gbounds_host[g + 1] > h->gbounds_host[g]) visits.push_back(g);
+    const int64_t n_visit = (int64_t)visits.size();
+    // Streamed row maps (data in host memory, Section 3.2): visit i's map goes through ring slot i % 3.
+    // Pass i reads the maps of visits i - 1 and i while the copy engine brings in the map of visit i + 1;
+    // that copy is enqueued once pass i - 1, the last reader of the slot's earlier content, has been
+    // launched, so copies run one pass ahead of the kernels and follow each other without a gap as long
+    // as a pass is shorter than a copy.
+    const bool streamed = h->gstream;
+    const bool sprof = streamed && h->opt.profile != 0 && h->gev_prof != nullptr && !h->pass_list;
+    if (streamed) {
+        h->gcopy_timed.assign((size_t)(G + 1), 0);
+        for (int64_t i = 0; i < std::min<int64_t>(2, n_visit); ++i)
+            SNAP_TRY(enqueue_map_copy(h, visits[(size_t)i], (int)(i % 3), sprof ? i : -1));
+    }
     for (int64_t gi = 0; gi <= n_visit; ++gi) {
         const bool last = gi == n_visit;
-        const int64_t g = last ? G : gorder[(size_t)gi];
+        const int64_t g = last ? G : visits[(size_t)gi];
         const int64_t g0 = last ? 0 : h->gbounds_host[g], sz = last ? 0 : h->gbounds_host[g + 1] - g0;
-        if (!last && sz == 0) continue;
         const int hot = last ? 0 : h->ghot_host[g], k64 = last ? 0 : h->gk64_host[g];
         const MAPT* maps = (const MAPT*)h->rowmap;
-        const MAPT* map_prev = prev >= 0 ? maps + (size_t)prev * h->n_pad : nullptr;
+        const MAPT* map_prev = prev < 0 ? nullptr : streamed ? (const MAPT*)h->gring[(gi - 1) % 3] : maps + (size_t)prev * h->n_pad;
         const float* val_prev = (prev >= 0 && !UNIT) ? h->rowval + (size_t)prev * h->n_pad : nullptr;
         const float* delta_prev = prev >= 0 ? h->gdelta + h->gbounds_host[prev] : nullptr;
-        const MAPT* map_cur = last ? nullptr : maps + (size_t)g * h->n_pad;
+        const MAPT* map_cur = last ? nullptr : streamed ? (const MAPT*)h->gring[gi % 3] : maps + (size_t)g * h->n_pad;
         const float* val_cur = (last || UNIT) ? nullptr : h->rowval + (size_t)g * h->n_pad;
         const int kd = prev >= 0 ? (int)std::min<int64_t>(h->g_kd_max, h->gbounds_host[prev + 1] - h->gbounds_host[prev]) : 0;
         // short coordinates through the dense buffer (only with a row pass that computes sums)
@@ -1070,9 +1371,11 @@ static int grouped_epoch_kind(snap_handle* h) {
         const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + (size_t)(kd + 1) * sizeof(float) +
                            (compact ? (size_t)(ROW_TPB / WAVE) * COLD_RING * sizeof(float) : 0);
         const dim3 row_grid((unsigned)h->g_row_wgs);
-        const bool scatter = prev >= 0, histo = !last && hot > 0;
+        const bool scatter = prev >= 0, histo = !last && (hot > 0 || compact);
         float* cbuf = compact ? h->gcbuf : nullptr;
         const uint32_t* wbase = compact ? h->gwbase + (size_t)g * (size_t)(h->g_row_wgs * (ROW_TPB / WAVE)) : nullptr;
+        if (streamed && !last) SNAP_TRY(acquire_map(h, (int)(gi % 3)));
+        if (sprof) SNAP_HIP(hipEventRecord(h->gev_prof[4 * gi + 2], h->compute));
         if (n > 0 && (scatter || histo)) {
             // (profile: the two events take the kernel's own start and end times; events recorded between
             // the launches instead cost the chain of dependent kernels 3 us each)
@@ -1096,17 +1399,31 @@ static int grouped_epoch_kind(snap_handle* h) {
                                       h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
             ++n_pass;
         }
+        if (streamed) {
+            // the previous visit's map has had its last reader; the slot it frees takes the map of the
+            // visit after next
+            if (gi >= 1) SNAP_HIP(hipEventRecord(h->gev_free[(gi - 1) % 3], h->compute));
+            if (gi + 2 < n_visit) SNAP_TRY(enqueue_map_copy(h, visits[(size_t)(gi + 2)], (int)((gi + 2) % 3), sprof ? gi + 2 : -1));
+        }
+        if (!last) {
+            const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
+            const int64_t cold = sz - hot;
+            const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
+            const int per_block = compact ? STEP_RANKS * STEP_PARTS / 16 : waves_per_block;   // coordinates per pass of a workgroup
+            const int n_cold_blocks = (int)std::min<int64_t>((cold + per_block - 1) / per_block, 8192);
+            hipLaunchKernelGGL((k_group_finish<KIND, false>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
+                               dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
+                               n_hot_blocks, 1.0 / (double)scale.g, 1.0 / (double)scale.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
+                               h->gdelta, sp, nullptr, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
+        }
+        if (sprof) SNAP_HIP(hipEventRecord(h->gev_prof[4 * gi + 3], h->compute));
         if (last) break;
-        const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
-        const int64_t cold = sz - hot;
-        const int waves_per_block = STEP_RANKS * STEP_PARTS / WAVE;
-        const int per_block = compact ? STEP_RANKS * STEP_PARTS / 16 : waves_per_block;   // coordinates per pass of a workgroup
-        const int n_cold_blocks = (int)std::min<int64_t>((cold + per_block - 1) / per_block, 8192);
-        hipLaunchKernelGGL((k_group_finish<KIND, false>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
-                           dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
-                           n_hot_blocks, 1.0 / (double)scale.g, 1.0 / (double)scale.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
-                           h->gdelta, sp, nullptr, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
         prev = g;
+    }
+    if (streamed) {
+        h->g_visits = n_visit;
+        // the host does not run ahead of the copy stream by more than a pass (see for_each_chunk)
+        SNAP_HIP(hipStreamSynchronize(h->copy));
     }
     h->n_row_passes = n_pass;
     SNAP_HIP(hipGetLastError());
@@ -1122,21 +1439,35 @@ static int grouped_dots_kind(snap_handle* h) {
     long long* gpart = (long long*)h->gpartial;
     const SumScales scale = sum_scales(h);
     const MAPT* maps = (const MAPT*)h->rowmap;
-    for (int64_t g = 0; g < G; ++g) {
+    // streamed row maps: one map per pass through the ring of three, copies two passes ahead
+    const bool streamed = h->gstream;
+    std::vector<int64_t> visits;
+    for (int64_t g = 0; g < G; ++g)
+        if (h->gbounds_host[g + 1] > h->gbounds_host[g]) visits.push_back(g);
+    const int64_t n_visit = (int64_t)visits.size();
+    if (streamed)
+        for (int64_t i = 0; i < std::min<int64_t>(3, n_visit); ++i) SNAP_TRY(enqueue_map_copy(h, visits[(size_t)i], (int)(i % 3), -1));
+    for (int64_t gi = 0; gi < n_visit; ++gi) {
+        const int64_t g = visits[(size_t)gi];
         const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
-        if (sz == 0) continue;
         const int hot = h->ghot_host[g], k64 = h->gk64_host[g];
         const bool compact = h->gcompact_host[g] && n > 0;
         float* cbuf = compact ? h->gcbuf : nullptr;
         const uint32_t* wbase = compact ? h->gwbase + (size_t)g * (size_t)(h->g_row_wgs * (ROW_TPB / WAVE)) : nullptr;
-        if (n > 0 && hot > 0) {
+        const MAPT* map_cur = streamed ? (const MAPT*)h->gring[gi % 3] : maps + (size_t)g * h->n_pad;
+        if (streamed) SNAP_TRY(acquire_map(h, (int)(gi % 3)));
+        if (n > 0 && (hot > 0 || compact)) {
             const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + sizeof(float) +
                                (compact ? (size_t)(ROW_TPB / WAVE) * COLD_RING * sizeof(float) : 0);
             hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), lds,
                                h->compute, (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr,
-                               maps + (size_t)g * h->n_pad, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
+                               map_cur, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
                                k64, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale, 0, h->status, cbuf,
                                wbase);
+        }
+        if (streamed) {
+            SNAP_HIP(hipEventRecord(h->gev_free[gi % 3], h->compute));
+            if (gi + 3 < n_visit) SNAP_TRY(enqueue_map_copy(h, visits[(size_t)(gi + 3)], (int)((gi + 3) % 3), -1));
         }
         const int n_hot_blocks = (hot + STEP_RANKS - 1) / STEP_RANKS;
         const int64_t cold = sz - hot;
@@ -1149,6 +1480,7 @@ static int grouped_dots_kind(snap_handle* h) {
                                n_hot_blocks, 1.0 / (double)scale.g, 1.0 / (double)scale.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
                                h->gdelta, sp, h->gdot, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
     }
+    if (streamed) SNAP_HIP(hipStreamSynchronize(h->copy));
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
 }

@@ -741,6 +741,174 @@ def test_group_sweeps_other_launch_shapes(monkeypatch, knobs, loss, unit):
     g.close()
 
 
+# ---------------------------------------------------------------------------------------------
+# group sweeps on streamed data (Section 3.2): the matrix stays in pinned host memory; what is streamed
+# per epoch are the row maps, which the library builds at creation into pinned memory of its own
+@pytest.mark.parametrize("knobs", [{}, {"SNAP_ROW_WGS": "16", "SNAP_HOT_MAX": "8"}, {"SNAP_HOT_ROWS": "1000000000"},
+                                   {"SNAP_ROW_WGS": "3", "SNAP_HOT_MAX": "40", "SNAP_DELTA_LDS": "16"}, {"SNAP_MAP8": "0"}],
+                         ids=lambda k: ",".join("%s=%s" % (n[5:].lower(), v) for n, v in k.items()) or "default")
+@pytest.mark.parametrize("loss", ["logistic", "ridge"])
+def test_streamed_group_sweeps_equal_resident_ones_bit_for_bit_and_the_oracle(monkeypatch, knobs, loss):
+    for name, value in knobs.items():
+        monkeypatch.setenv(name, value)
+    p = _onehot_variant(loss, True)
+    groups = p.meta["field_starts"] + [p.d]
+    G = len(groups) - 1
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    r = gpu_solver(p, group_bounds=groups)                                  # resident twin
+    g = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, chunk_bytes=4 << 20, group_bounds=groups,
+                                 profile=True)
+    assert g.chunk_bounds() == groups
+    n_pad = (p.n + 7) // 8 * 8
+    # one row map per field: a byte per row for fields of at most 255 columns (all of them here), else two
+    small = [b - a <= 255 and knobs.get("SNAP_MAP8") != "0" for a, b in zip(groups, groups[1:])]
+    assert all(small) or not any(small)
+    assert g.stream_bytes() == sum(n_pad * (1 if s8 else 2) for s8 in small) and r.stream_bytes() == 0
+    mb = 1 if small[0] else 2
+    assert g.objective() == r.objective()
+    assert rel(g.duality_gap(), r.duality_gap()) <= (0 if "SNAP_HOT_ROWS" not in knobs else 1e-6)
+    o = oracle.Solver(A, y, p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    # (without any hot rank the resident sweeps sum the short coordinates straight from v, a wavefront each,
+    # the streamed ones from the dense buffer, 16 lanes each: same terms, another order of the fp32 additions)
+    same = (lambda a, b: np.array_equal(a, b)) if "SNAP_HOT_ROWS" not in knobs else (lambda a, b: relnorm(a, b.astype(np.float64)) <= 1e-6)
+    base = g.bytes_copied()
+    for e in range(5):
+        g.epoch(e)
+        r.epoch(e)
+        o.epoch(e)
+        xg, xr = g.model()[1], r.model()[1]
+        assert same(xg, xr), "streamed and resident sweeps differ after epoch %d" % e
+        assert same(g.shared(), r.shared())
+        np.testing.assert_allclose(xg, o.x, rtol=2e-4, atol=2e-5 * np.abs(o.x).max())
+        assert relnorm(xg, o.x) <= 2e-5
+        assert rel(g.objective(), o.primal()) <= 1e-5
+    assert 5 * (G - 2) * n_pad * mb <= g.bytes_copied() - base <= 5 * g.stream_bytes()   # (a map still in the ring is not copied)
+    st = g.epoch_stats()
+    assert st["n_chunks"] == G and st["copy_ms"] > 0 and st["scd_ms"] > 0 and st["row_map_bytes"] == 2 and st["unit_values"] == 1
+    assert np.array_equal(g.perm(), r.perm())
+    assert rel(g.duality_gap(), r.duality_gap()) <= (0 if "SNAP_HOT_ROWS" not in knobs else 1e-2)   # the gradient pass streams the maps too
+    if "SNAP_HOT_ROWS" not in knobs:
+        assert np.array_equal(g.chunk_gaps(), r.chunk_gaps())
+    else:   # (squared gradients near the optimum amplify the different order of the fp32 sums)
+        np.testing.assert_allclose(g.chunk_gaps(), r.chunk_gaps(), rtol=2e-2, atol=1e-3 * r.chunk_gaps().max())
+    for e, chunks in enumerate([[5, 0, 17], [38], [20, 21], list(range(G))]):   # passes over part of the fields
+        g.epoch_chunks(10 + e, chunks)
+        r.epoch_chunks(10 + e, chunks)
+        o.epoch(10 + e, chunks=chunks)
+        assert same(g.model()[1], r.model()[1]) and same(g.shared(), r.shared())
+    assert relnorm(g.model()[1], o.x) <= 2e-5
+    base = g.bytes_copied()
+    g.epoch_chunks(50, [3, 9])
+    g.epoch_chunks(51, [3, 9])                                            # the two maps are still in the ring
+    assert g.bytes_copied() - base <= 2 * n_pad * mb
+    # a new model goes through the caller's (borrowed) column arrays
+    w = (0.1 * np.random.default_rng(3).standard_normal(p.d)).astype(np.float32)
+    g.set_model(w)
+    r.set_model(w)
+    assert np.array_equal(g.shared(), r.shared()) or relnorm(g.shared(), r.shared().astype(np.float64)) <= 1e-6
+    g.close()
+    r.close()
+
+
+def test_streamed_group_sweeps_wide_group_and_error_paths(monkeypatch):
+    # a field with more than 65535 categories: 4-byte row maps through the ring
+    monkeypatch.setenv("SNAP_ROW_WGS", "16")
+    n, d1, d2 = 200_000, 70_000, 50
+    rng = np.random.default_rng(8)
+    c1 = np.where(rng.random(n) < 0.5, rng.integers(0, 100, size=n), rng.integers(0, d1, size=n))
+    c2 = rng.integers(0, d2, size=n)
+    cols = np.concatenate([c1, d1 + c2])
+    rows = np.concatenate([np.arange(n), np.arange(n)])
+    order = np.lexsort((rows, cols))
+    d = d1 + d2
+    ptr = np.zeros(d + 1, dtype=np.int64)
+    ptr[1:] = np.cumsum(np.bincount(cols, minlength=d))
+    idx = rows[order].astype(np.int32)
+    val = np.ones(idx.size, dtype=np.float32)
+    y = np.where(rng.random(n) < 0.3, 1.0, -1.0).astype(np.float32)
+    groups = [0, d1, d]
+    pin = lambda a: torch.from_numpy(a).pin_memory()
+    g = snap.Solver("csc", n, d, pin(ptr), pin(idx), pin(val), pin(y), "logistic", 1e-4, group_bounds=groups,
+                    device_budget_bytes=1 << 20, chunk_bytes=1 << 20)
+    assert g.stream_bytes() == 2 * n * 4
+    o = oracle.Solver(oracle.Matrix("csc", n, d, ptr, idx, val), y, "logistic", 1e-4, chunk_bounds=groups,
+                      shuffle_chunks=True)
+    for e in range(4):
+        g.epoch(e)
+        o.epoch(e)
+        assert relnorm(g.model()[1], o.x) <= 2e-5
+    assert rel(g.objective(), o.primal()) <= 1e-5
+    assert rel(g.duality_gap(), o.gap()) <= 1e-3
+    g.close()
+    # values other than 1 are not streamed as maps: refused, the asynchronous streamed epoch remains
+    val2 = (0.5 + rng.random(idx.size)).astype(np.float32)
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", n, d, pin(ptr), pin(idx), pin(val2), pin(y), "logistic", 1e-4, group_bounds=groups,
+                    device_budget_bytes=1 << 20, chunk_bytes=1 << 20)
+    assert e.value.code == -2
+    # overlapping groups are found while the maps are built
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver("csc", n, d, pin(ptr), pin(idx), pin(val), pin(y), "logistic", 1e-4, group_bounds=[0, d],
+                    device_budget_bytes=1 << 20, chunk_bytes=1 << 20)
+    assert e.value.code == -1
+
+
+def test_pattern_only_matrix_without_a_value_array():
+    """val = NULL at creation stands for "every stored value is 1": same results as an array of ones in the
+    three engines that take compressed columns (asynchronous, group sweeps, group sweeps on streamed maps)
+    and in the streamed asynchronous epoch."""
+    p = _onehot_variant("logistic", True)
+    groups = p.meta["field_starts"] + [p.d]
+    q = p.to("cpu")
+    q.val = None
+    assert q.nnz == p.nnz
+    o = oracle.Solver(oracle.Matrix.from_problem(q), p.y.numpy(), p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    for e in range(3):
+        o.epoch(e)
+    for kw, pin in [({"group_bounds": groups}, False), ({"group_bounds": groups, "device_budget_bytes": 1 << 20}, True)]:
+        a = snap.Solver.from_problem(_pinned(p) if pin else p.to(DEV), auto_groups=False, **kw)
+        b = snap.Solver.from_problem(_pinned_some(q) if pin else q.to(DEV), auto_groups=False, **kw)
+        for e in range(3):
+            a.epoch(e)
+            b.epoch(e)
+        assert np.array_equal(a.model()[1], b.model()[1]) and np.array_equal(a.shared(), b.shared())
+        assert relnorm(b.model()[1], o.x) <= 2e-5
+        assert a.duality_gap() == b.duality_gap()
+        a.close()
+        b.close()
+    # asynchronous engines: resident with one wavefront in flight (sequential, hence comparable), and streamed
+    a = gpu_solver(p, max_inflight_nnz=1, adaptive=False)
+    b = gpu_solver(q, max_inflight_nnz=1, adaptive=False)
+    a.epoch(0)
+    b.epoch(0)
+    assert relnorm(b.model()[1], a.model()[1].astype(np.float64)) <= 1e-6
+    a.close()
+    b.close()
+    s = snap.Solver.from_problem(_pinned_some(q), device_budget_bytes=1 << 20, chunk_bytes=4 << 20)
+    t = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, chunk_bytes=4 << 20)
+    assert s.stream_bytes() == t.stream_bytes() == 4 * p.nnz and s.epoch_stats()["unit_values"] == 1
+    assert s.objective() == t.objective() and s.duality_gap() == t.duality_gap()
+    for e in range(20):
+        s.epoch(e)
+        t.epoch(e)
+    # (two asynchronous runs: the same trajectory up to the order of their atomics)
+    assert rel(s.objective(), t.objective()) <= 1e-3 and s.objective() < 0.8 * np.log(2.0)
+    chk = oracle.Solver(oracle.Matrix.from_problem(q), p.y.numpy(), p.loss, p.lam)
+    chk.x[:] = s.model()[1]
+    assert relnorm(s.shared(), chk.shared_from_model()) <= 1e-4
+    s.close()
+    t.close()
+
+
+def _pinned_some(p):
+    q = p.to("cpu")
+    for name in ("ptr", "idx", "val", "y"):
+        if getattr(q, name) is not None:
+            setattr(q, name, getattr(q, name).pin_memory())
+    return q
+
+
 @pytest.mark.parametrize("loss", ["logistic", "ridge"])
 def test_group_sweeps_are_bit_reproducible(loss):
     """No floating-point atomics and no order left to chance (integer sums in LDS, fixed orders
