@@ -108,7 +108,18 @@ typedef struct {
                                     visited in a random order drawn from perm_seed (keys of the groups
                                     under chunk id 0xFFFFFFFF, sorted), all coordinates of a group at
                                     once -- identical to visiting them one by one, since they do not
-                                    interact -- with plain coalesced updates of v instead of atomics. */
+                                    interact -- with plain coalesced updates of v instead of atomics.
+                                    Streamed data (device_budget_bytes exceeded; pattern-only data, i.e. all
+                                    values 1): the row maps of the sweeps are built at creation into pinned
+                                    host memory of the library's own (1, 2 or 4 bytes per row and group) and
+                                    an epoch streams those through a ring of three device buffers instead of
+                                    the column indices.
+                                    The sums of the sweeps are fixed point.  Logistic loss: the sweeps are not
+                                    used when lambda * n_rows < max|value|^2 / 16 (their resolution could show
+                                    in a step); ridge loss: a term a (v - y) of 2^14 or more does not fit, the
+                                    epoch that meets one is done again by the asynchronous engine and the
+                                    handle stays with it.  In both cases snap_get_chunks then reports one
+                                    chunk, and with auto_groups = 1 creation fails instead. */
     int64_t n_groups;            /* 0: no groups */
     double lambda1;              /* >= 0: weight of an l1 term in the primal forms (eq. (1): lasso / elastic-net
                                     regularisers), P(w) = (1/n) sum loss + (lambda/2)||w||^2 + lambda1 ||w||_1.

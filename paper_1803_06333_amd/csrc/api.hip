@@ -52,6 +52,47 @@ __global__ void k_publish_status(const uint32_t* __restrict__ status, double* __
     if (threadIdx.x == 0) reinterpret_cast<uint32_t*>(host_mapped)[0] = *status;
 }
 
+__global__ void k_clear_status_bits(uint32_t* status, uint32_t mask) {
+    if (threadIdx.x == 0) *status &= ~mask;
+}
+
+// The handle's status word as it stands once the work enqueued so far is done (synchronises).
+int read_status(snap_handle* h, uint32_t* st) {
+    hipLaunchKernelGGL(k_publish_status, dim3(1), dim3(WAVE), 0, h->compute, h->status, h->red.host_mapped + 7);
+    SNAP_HIP(hipGetLastError());
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    *st = reinterpret_cast<const uint32_t*>(h->red.host + 7)[0];
+    return SNAP_OK;
+}
+
+static int alloc_snapshots(snap_handle* h) {
+    if (!h->x_snap) SNAP_HIP(hipMalloc(&h->x_snap, (size_t)(h->m ? h->m : 1) * sizeof(float)));
+    if (!h->v_snap) SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
+    return SNAP_OK;
+}
+
+// Group sweeps of the ridge loss keep their sums in 64-bit fixed point with 2^39 of range; a term
+// beyond 2^14 raises STATUS_RANGE.  The handle then leaves the group sweeps for good and goes on with
+// the asynchronous engine, which has no such limit: the caller sees a slower epoch, not an error.
+int leave_group_sweeps(snap_handle* h) {
+    hipLaunchKernelGGL(k_clear_status_bits, dim3(1), dim3(WAVE), 0, h->compute, h->status, STATUS_RANGE);
+    SNAP_HIP(hipGetLastError());
+    h->grouped = false;
+    h->group_fallback = true;
+    h->perm_stale = false;
+    (void)hipFree(h->share_bounds);                      // (the gap shares are per chunk from now on, not per group)
+    (void)hipFree(h->share_out);
+    h->share_bounds = nullptr;
+    h->share_out = nullptr;
+    h->adaptive = h->opt.adaptive != 2;                  // the asynchronous engine's default: accept check on
+    if (h->adaptive) {
+        SNAP_TRY(alloc_snapshots(h));
+        if (h->opt.max_inflight_nnz <= 0) h->inflight_nnz = std::max<int64_t>(WAVE, (int64_t)(0.25 * (double)h->vlen));
+    }
+    h->monitor_valid = false;
+    return SNAP_OK;
+}
+
 static int check_status(snap_handle* h) {
     hipLaunchKernelGGL(k_publish_status, dim3(1), dim3(WAVE), 0, h->compute, h->status, h->red.host_mapped + 7);
     SNAP_HIP(hipGetLastError());
@@ -370,7 +411,23 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
         SNAP_HIP(hipMalloc(&h->x_snap, (size_t)(m ? m : 1) * sizeof(float)));
         SNAP_HIP(hipMalloc(&h->v_snap, (size_t)(h->vlen ? h->vlen : 1) * sizeof(float)));
     }
-    if (!gbounds.empty()) SNAP_TRY(grouped_setup(h, hptr.data(), gbounds.data(), (int64_t)gbounds.size() - 1));
+    if (!gbounds.empty()) {
+        SNAP_TRY(grouped_setup(h, hptr.data(), gbounds.data(), (int64_t)gbounds.size() - 1));
+        if (!h->grouped) {
+            // declined (the fixed-point sums would be too coarse for this lambda): the asynchronous engine runs
+            if (h->opt.auto_groups == 1) {
+                set_error("group sweeps were required (auto_groups = 1) but lambda * n_rows is too small for their "
+                          "fixed-point sums");
+                return SNAP_EUNSUPPORTED;
+            }
+            h->adaptive = h->opt.adaptive != 2;
+            if (h->adaptive) {
+                SNAP_TRY(alloc_snapshots(h));
+                if (h->opt.max_inflight_nnz <= 0) h->inflight_nnz = std::max<int64_t>(WAVE, (int64_t)(0.25 * (double)h->vlen));
+            }
+        }
+    }
+    if (h->grouped && h->kind == K_PRIMAL_RIDGE) SNAP_TRY(alloc_snapshots(h));     // (see snap_epoch: the range guard)
     if (use_tiles) SNAP_TRY(dense_tiles_setup(h));
     if (h->form == SNAP_DUAL && h->loss == SNAP_LOGISTIC && m > 0) {
         // the entropy term of the logistic dual needs alpha inside (0,1): start at 1/2, v = A alpha
@@ -505,6 +562,10 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         }
         SNAP_TRY(copy_pair(h->x_snap, h->x, h->m, h->v_snap, h->v, h->vlen, h->compute));
     }
+    // group sweeps of the ridge loss can run out of the range of their fixed-point sums: the state before
+    // the epoch is kept so that the epoch can be done again by the asynchronous engine
+    const bool guard_range = h->grouped && h->kind == K_PRIMAL_RIDGE;
+    if (guard_range && !h->adaptive) SNAP_TRY(copy_pair(h->x_snap, h->x, h->m, h->v_snap, h->v, h->vlen, h->compute));
     if (prof) SNAP_HIP(hipEventRecord(h->ev[0], h->compute));
     if (h->grouped) {
         // exact group sweeps; the visiting order inside a group does not change the result and is
@@ -514,6 +575,17 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
         SNAP_TRY(grouped_epoch(h));
         if (prof) SNAP_HIP(hipEventRecord(h->ev[3], h->compute));
         h->perm_stale = true;
+        if (guard_range) {
+            uint32_t st = 0;
+            SNAP_TRY(read_status(h, &st));
+            if (st & STATUS_RANGE) {
+                SNAP_TRY(copy_pair(h->x, h->x_snap, h->m, h->v, h->v_snap, h->vlen, h->compute));
+                SNAP_TRY(leave_group_sweeps(h));
+                h->pass_list = nullptr;                  // (a pass over part of the groups becomes a whole epoch)
+                h->pass_count = 0;
+                return snap_epoch(h, perm_seed);         // the same epoch, by the engine without the limit
+            }
+        }
     } else if (h->tiled) {
         if (h->pass_list) {
             set_error("a pass over part of the tiles is not supported by the dense tile sweeps");
@@ -586,10 +658,11 @@ int snap_chunk_gaps(snap_handle* h, double* shares_out, double* gap_out) {
         set_error("null argument");
         return SNAP_EINVAL;
     }
+    const int64_t C = chunk_count(h);
     SNAP_TRY(chunk_gap_shares(h, shares_out));
     if (gap_out) {
         double g = 0.0;
-        for (int64_t c = 0; c < chunk_count(h); ++c) g += shares_out[c];
+        for (int64_t c = 0; c < C; ++c) g += shares_out[c];
         *gap_out = g;
     }
     return SNAP_OK;

@@ -181,6 +181,7 @@ struct snap_handle {
     int n_row_passes = 0;
     std::vector<char> pass_timed;        // profile: which row passes of the last epoch carry their two events
     int64_t g_hot_coords = 0, g_hot_nnz = 0;
+    bool group_fallback = false;      // the group sweeps were left for the asynchronous engine (fixed-point range)
     bool perm_stale = false;          // grouped mode makes the visiting order only on request
     uint64_t last_seed = 0;
     // group sweeps over streamed data: the row maps live in pinned host memory of the library's own and
@@ -248,6 +249,10 @@ int scd_run_chunk(snap_handle* h, const ChunkView& cv, const snap_handle::Chunk&
 // double-buffered copies on the copy stream overlap fn's work on the compute stream.
 using ChunkFn = int (*)(snap_handle* h, int64_t chunk, const ChunkView& cv, void* arg);
 int for_each_chunk(snap_handle* h, ChunkFn fn, void* arg, bool fold, bool profile);
+// api.hip: a ridge term beyond the range of the group sweeps' fixed-point sums was seen: clear the flag,
+// switch the handle to the asynchronous engine for good
+int leave_group_sweeps(snap_handle* h);
+int read_status(snap_handle* h, uint32_t* st);      // the status word once the enqueued work is done (synchronises)
 // grouped.hip
 int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* bounds, int64_t n_groups);
 int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bounds);   // empty: nothing found

@@ -357,6 +357,17 @@ int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bou
 static int cold_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>& coord_of);
 static int streamed_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>& coord_of);
 
+// The terms of the logistic loss enter the sums with a resolution of 2^-20 (loss') and 2^-23 (loss'') of
+// the largest |value| a (squared for loss'').  That is far below fp32 rounding of the sums themselves unless
+// the curvature sum of a coordinate is tiny and lambda n is tiny too (rows that the model separates
+// perfectly: the step is g / (h + lambda n)): up to 4095 rounded terms are off by about 64 * 2^-24 a^2 in
+// total, which stays below 1e-4 of the denominator when lambda n >= a^2 / 16.  Below that the group
+// sweeps are declined and the handle runs the asynchronous engine.
+static bool resolution_too_coarse(const snap_handle* h, int scale_exp) {
+    // (the largest |value| lies in (2^(scale_exp - 1), 2^scale_exp])
+    return h->kind == K_PRIMAL_LOGISTIC && h->lambda * (double)h->n < ldexp(1.0, 2 * scale_exp - 6);
+}
+
 int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_t G) {
     const int64_t m = h->m, n = h->n;
     if (h->form != SNAP_PRIMAL || h->dense) {
@@ -456,6 +467,11 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         }
     }
     if (h->streaming) {
+        if (resolution_too_coarse(h, 1)) {               // (pattern-only data: the largest value is 1 <= 2^1)
+            grouped_free(h);
+            h->n_groups = 0;
+            return SNAP_OK;
+        }
         SNAP_TRY(streamed_setup(h, hptr, coord_of));
         h->grouped = true;
         return SNAP_OK;
@@ -493,6 +509,12 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         int e = 0;
         if (amax > 0.0f) (void)frexpf(amax, &e);     // amax <= 2^e
         h->gscale_exp = e;
+    }
+    if (resolution_too_coarse(h, h->gscale_exp)) {
+        (void)fail(SNAP_OK);
+        grouped_free(h);
+        h->n_groups = 0;
+        return SNAP_OK;
     }
     if (!h->unit_values) {
         G_HIP(hipMalloc(&h->rowval, map_count * sizeof(float)));

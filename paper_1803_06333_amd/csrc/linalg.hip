@@ -524,6 +524,20 @@ __global__ void k_scale(const float* __restrict__ in, float s, float* __restrict
 
 // P, D and the gap.  Any of the outputs may be null; the gap (and D in primal form) needs one pass
 // over the matrix, P in primal form only the vectors.
+// Inner products of every coordinate with loss'(v): by the row passes of the group sweeps when the
+// handle has them.  Ridge terms beyond the range of those passes' fixed-point sums make the handle leave
+// the group sweeps, and the inner products are taken column by column instead.
+static int gradient_dots(snap_handle* h) {
+    if (!h->grouped) return coord_dots(h);
+    SNAP_TRY(grouped_dots(h));
+    if (h->kind != K_PRIMAL_RIDGE) return SNAP_OK;
+    uint32_t st = 0;
+    SNAP_TRY(read_status(h, &st));
+    if (!(st & STATUS_RANGE)) return SNAP_OK;
+    SNAP_TRY(leave_group_sweeps(h));
+    return coord_dots(h);
+}
+
 int objective(snap_handle* h, double* primal, double* dual, double* gap) {
     const double n = (double)h->n, lam = h->lambda, lam1 = h->lambda1;
     double* res = h->red.host;
@@ -535,7 +549,7 @@ int objective(snap_handle* h, double* primal, double* dual, double* gap) {
         SNAP_TRY(reduce_to(h, R_SQNORM, rx, 1));
         if (lam1 > 0.0) SNAP_TRY(reduce_to(h, R_ABSSUM, rx, 3));
         if (need_gap) {
-            SNAP_TRY(h->grouped ? grouped_dots(h) : coord_dots(h));
+            SNAP_TRY(gradient_dots(h));
             if (lam1 > 0.0) {
                 // Fenchel form: P + f*(u) + sum_j g*(a_j.u), u = grad f(v); a_j.u = gdot_j / n
                 ReduceArgs rg{nullptr, nullptr, h->gdot, 1.0 / n, lam1, h->m};
@@ -627,7 +641,7 @@ int chunk_gap_shares(snap_handle* h, double* shares_out) {
         SNAP_HIP(hipMalloc(&h->share_out, (size_t)C * sizeof(double)));
         SNAP_HIP(hipMemcpy(h->share_bounds, b.data(), ((size_t)C + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     }
-    SNAP_TRY(h->grouped ? grouped_dots(h) : coord_dots(h));
+    SNAP_TRY(gradient_dots(h));
     const dim3 grid((unsigned)C), block(LTPB);
     const double n = (double)h->n;
     if (h->form == SNAP_PRIMAL)

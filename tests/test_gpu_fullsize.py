@@ -62,6 +62,33 @@ def test_config4_click_log_logistic_full_size():
     g.close()
 
 
+def test_config4_shaped_asynchronous_epoch_reaches_the_converged_objective():
+    """The click-log generator at a size the oracle can converge on (0.4 % of the rows, all 10^6 columns, lambda
+    raised so that a minute of sequential epochs is enough): the asynchronous engine in its default launch
+    configuration (split and one-wavefront coordinates, automatic cap, accept check) against the oracle's
+    converged objective, at the stated 1e-4."""
+    p = datagen.config(4, device=DEV, scale=0.004)
+    p.lam = 1e-4
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.cpu().numpy()
+    ref = oracle.Solver(A, y, p.loss, p.lam)
+    for e in range(200):
+        ref.epoch(e)
+        if e % 5 == 4 and ref.gap() <= 1e-5 * ref.primal():
+            break
+    target, slack = ref.primal(), ref.gap()          # the minimum lies in [target - slack, target]
+    assert slack <= 1e-5 * target
+    g = snap.Solver.from_problem(p, auto_groups=False)
+    assert g.epoch_stats()["n_large"] > 0 and g.epoch_stats()["n_small"] > 0
+    epochs, gap = g.solve(0, 400, 1e-5 * target, check_every=5)
+    assert gap <= 1e-5 * target and epochs < 400
+    assert rel(g.objective(), target) <= 1e-4
+    _, x = g.model()
+    vo = A.matvec(x)
+    assert np.linalg.norm(g.shared() - vo) <= 1e-4 * np.linalg.norm(vo)
+    g.close()
+
+
 def test_config4_group_sweeps_full_size():
     """The launch configuration bench.py times for config 4 (exact sweeps over the 39 one-hot fields).  The
     sweeps are deterministic, so the oracle can replay the first two fields of the first epoch in closed
@@ -76,29 +103,22 @@ def test_config4_group_sweeps_full_size():
     P1 = g.objective()
     _, x = g.model()
     x = x.astype(np.float64)
-    y = p.y.cpu().numpy().astype(np.float64)
+    yf = p.y.cpu().numpy()
+    A = oracle.Matrix.from_problem(p)
+    # the oracle sweeps the first two fields of the epoch's order itself (92 M nonzeros, a few seconds);
+    # the model of their columns is final for that epoch, and is compared coordinate by coordinate
+    o = oracle.Solver(A, yf, p.loss, lam, chunk_bounds=bounds, shuffle_chunks=True)
     order = oracle.permutation(0, 39, chunk=oracle.Solver.GROUP_ORDER_CHUNK)   # fields in visiting order
     f0, f1 = int(order[0]), int(order[1])
-    # first field: every column from the zero model, loss' = -y/2, loss'' = 1/4
-    c0 = datagen.onehot_categories(n, p.d, seed, f0, "cpu").numpy()
-    size0 = bounds[f0 + 1] - bounds[f0]
-    gsum = np.bincount(c0, weights=-0.5 * y, minlength=size0)
-    hsum = 0.25 * np.bincount(c0, minlength=size0)
-    w0 = -(gsum / n) / (hsum / n + lam)
-    got0 = x[bounds[f0]:bounds[f0 + 1]]
-    assert np.linalg.norm(got0 - w0) <= 1e-5 * np.linalg.norm(w0)
-    # second field: one Newton step per column at v = (first field's model of the row's column)
-    v = w0[c0]
-    c1 = datagen.onehot_categories(n, p.d, seed, f1, "cpu").numpy()
-    size1 = bounds[f1 + 1] - bounds[f1]
-    prob = 1.0 / (1.0 + np.exp(y * v))                                      # sigmoid(-y v)
-    gsum = np.bincount(c1, weights=-y * prob, minlength=size1)
-    hsum = np.bincount(c1, weights=prob * (1.0 - prob), minlength=size1)
-    w1 = -(gsum / n) / (hsum / n + lam)
-    got1 = x[bounds[f1]:bounds[f1 + 1]]
-    assert np.linalg.norm(got1 - w1) <= 2e-5 * np.linalg.norm(w1)
-    assert np.max(np.abs(got1 - w1)) <= 1e-4 * np.max(np.abs(w1))
-    del c0, c1, prob, v
+    o.epoch(0, chunks=[f0, f1])
+    for f in (f0, f1):
+        got, want = x[bounds[f]:bounds[f + 1]], o.x[bounds[f]:bounds[f + 1]]
+        assert np.linalg.norm(got - want) <= 2e-5 * np.linalg.norm(want)
+        np.testing.assert_allclose(got, want, rtol=2e-4, atol=5e-6 * np.abs(want).max())
+    untouched = np.ones(p.d, dtype=bool)
+    untouched[bounds[f0]:bounds[f0 + 1]] = untouched[bounds[f1]:bounds[f1 + 1]] = False
+    assert not o.x[untouched].any()
+    del o
     # later epochs: monotone objective, sampled rows of v, objective and gap by the oracle at the GPU's state
     P = [P1]
     for e in range(1, 4):
@@ -114,9 +134,7 @@ def test_config4_group_sweeps_full_size():
         want += x.astype(np.float64)[starts[f] + cat]
     got = v[rows.numpy()].astype(np.float64)
     assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want)
-    yf = p.y.cpu().numpy()
     assert rel(P[3], oracle.primal_objective(oracle.LOGISTIC, v, yf, x, lam)) <= 1e-5
-    A = oracle.Matrix.from_problem(p)
     assert rel(g.duality_gap(), oracle.primal_gap(A, oracle.LOGISTIC, v, yf, x, lam)) <= 1e-5
     g.close()
 
@@ -196,6 +214,22 @@ def test_config5_streamed_full_size():
         del src
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
+    starts = p.meta["field_starts"]
+    rows = torch.from_numpy(np.unique(np.random.default_rng(7).integers(0, p.n, size=20000)))
+
+    def check_state(g, P_last):
+        """Sampled rows of v against the generator's definition, the objective by the oracle at the GPU's state."""
+        _, x = g.model()
+        v = g.shared()
+        want = np.zeros(rows.numel())
+        for f in range(39):
+            cat = datagen.onehot_categories(p.n, p.d, seed, f, "cpu", rows=rows).numpy()
+            want += x.astype(np.float64)[starts[f] + cat]
+        got = v[rows.numpy()].astype(np.float64)
+        assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want)
+        assert rel(P_last, oracle.primal_objective(oracle.LOGISTIC, v, p.y.numpy(), x, p.lam)) <= 1e-5
+
+    # (1) the asynchronous epoch on streamed column chunks
     g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30, profile=True)
     bounds = g.chunk_bounds()
     ptr = p.ptr.numpy()
@@ -209,19 +243,41 @@ def test_config5_streamed_full_size():
     assert P[2] < P[1] < P[0]
     st = g.epoch_stats()
     assert st["n_chunks"] == len(bounds) - 1
-    assert g.stream_bytes() == 4 * p.nnz                  # the all-ones values stay on the device
+    assert g.stream_bytes() == 4 * p.nnz                  # no value array: only the indices are streamed
     assert st["copy_ms"] > 0 and st["scd_ms"] > 0 and st["epoch_ms"] < st["copy_ms"] + st["scd_ms"]   # overlapped
+    check_state(g, P[2])
+    g.close()
+    # (2) group sweeps on streamed row maps (the configuration bench.py times): the first field of the
+    # first epoch in closed form from the generator's definition, the rest by invariants
+    fields = starts + [p.d]
+    g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30, group_bounds=fields, profile=True)
+    assert g.chunk_bounds() == fields
+    n_pad = (p.n + 7) // 8 * 8
+    assert g.stream_bytes() == 13 * n_pad + 26 * 2 * n_pad   # a byte per row for the 64-bin fields, two for the others
+    g.epoch(0)
+    P = [np.log(2.0), g.objective()]
     _, x = g.model()
-    v = g.shared()
-    rows = torch.from_numpy(np.unique(np.random.default_rng(7).integers(0, p.n, size=20000)))
-    starts = p.meta["field_starts"]
-    want = np.zeros(rows.numel())
-    for f in range(39):
-        cat = datagen.onehot_categories(p.n, p.d, seed, f, "cpu", rows=rows).numpy()
-        want += x.astype(np.float64)[starts[f] + cat]
-    got = v[rows.numpy()].astype(np.float64)
-    assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want)
-    assert rel(P[2], oracle.primal_objective(oracle.LOGISTIC, v, p.y.numpy(), x, p.lam)) <= 1e-5
+    # the first field of the epoch's order, swept by the oracle itself on the sub-matrix of that field's
+    # columns (200 M nonzeros; same n and lambda, so the same steps): final for this epoch, coordinate by coordinate
+    f0 = int(oracle.permutation(0, 39, chunk=oracle.Solver.GROUP_ORDER_CHUNK)[0])
+    c_lo, c_hi = fields[f0], fields[f0 + 1]
+    k_lo, k_hi = int(ptr[c_lo]), int(ptr[c_hi])
+    sub = oracle.Matrix("csc", p.n, c_hi - c_lo, ptr[c_lo:c_hi + 1] - k_lo, p.idx.numpy()[k_lo:k_hi],
+                        np.ones(k_hi - k_lo, dtype=np.float32))
+    o = oracle.Solver(sub, p.y.numpy(), p.loss, p.lam)
+    o.epoch(0)
+    got0 = x[c_lo:c_hi].astype(np.float64)
+    assert np.linalg.norm(got0 - o.x) <= 2e-5 * np.linalg.norm(o.x)
+    np.testing.assert_allclose(got0, o.x, rtol=2e-4, atol=5e-6 * np.abs(o.x).max())
+    del o, sub
+    for e in range(1, 3):
+        g.epoch(e)
+        P.append(g.objective())
+    assert P[3] < P[2] < P[1] < P[0]
+    st = g.epoch_stats()
+    assert st["n_chunks"] == 39 and st["copy_ms"] > 0 and st["scd_ms"] > 0
+    assert st["epoch_ms"] < st["copy_ms"] + 0.5 * st["scd_ms"]          # the kernels hide behind the copies
+    check_state(g, P[3])
     g.close()
     # give the 62 GB of pinned host memory back: PyTorch's host allocator would keep them cached, and
     # later pinned allocations of this process (the runtime's own included) would fail
