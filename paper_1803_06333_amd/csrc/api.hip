@@ -554,18 +554,34 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
     }
     if (h->m == 0) return SNAP_OK;
     const bool prof = h->opt.profile != 0;
+    // group sweeps of the ridge loss can run out of the range of their fixed-point sums: the state before
+    // the epoch is kept so that the epoch can be done again by the asynchronous engine
+    const bool guard_range = h->grouped && h->kind == K_PRIMAL_RIDGE;
+    // Group sweeps keep the state before the epoch for free (their first writing pass writes the shared
+    // vector into the second array, and the two change roles at the end; only the model is copied) and sum
+    // the loss in their last pass: the accept check then costs one small reduction (Section 3.1: the cost
+    // of evaluating the objective is absorbed by the epoch's kernels).
+    const bool keep_by_swap = h->grouped && (h->adaptive || guard_range);
     if (h->adaptive) {
         // value and state before the epoch, for the accept / discard decision
         if (!h->monitor_valid) {
             SNAP_TRY(monitor_value(h, &h->monitor_prev));
             h->monitor_valid = true;
         }
-        SNAP_TRY(copy_pair(h->x_snap, h->x, h->m, h->v_snap, h->v, h->vlen, h->compute));
     }
-    // group sweeps of the ridge loss can run out of the range of their fixed-point sums: the state before
-    // the epoch is kept so that the epoch can be done again by the asynchronous engine
-    const bool guard_range = h->grouped && h->kind == K_PRIMAL_RIDGE;
-    if (guard_range && !h->adaptive) SNAP_TRY(copy_pair(h->x_snap, h->x, h->m, h->v_snap, h->v, h->vlen, h->compute));
+    if (keep_by_swap) SNAP_TRY(copy_pair(h->x_snap, h->x, h->m, nullptr, nullptr, 0, h->compute));
+    else if (h->adaptive) SNAP_TRY(copy_pair(h->x_snap, h->x, h->m, h->v_snap, h->v, h->vlen, h->compute));
+    h->g_keep_old = keep_by_swap;
+    h->g_want_loss = keep_by_swap && h->adaptive;
+    h->g_swapped = false;
+    auto restore = [&]() -> int {                    // back to the state before the epoch
+        if (keep_by_swap) {
+            if (h->g_swapped) std::swap(h->v, h->v_snap);
+            h->g_swapped = false;
+            return copy_pair(h->x, h->x_snap, h->m, nullptr, nullptr, 0, h->compute);
+        }
+        return copy_pair(h->x, h->x_snap, h->m, h->v, h->v_snap, h->vlen, h->compute);
+    };
     if (prof) SNAP_HIP(hipEventRecord(h->ev[0], h->compute));
     if (h->grouped) {
         // exact group sweeps; the visiting order inside a group does not change the result and is
@@ -579,7 +595,7 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
             uint32_t st = 0;
             SNAP_TRY(read_status(h, &st));
             if (st & STATUS_RANGE) {
-                SNAP_TRY(copy_pair(h->x, h->x_snap, h->m, h->v, h->v_snap, h->vlen, h->compute));
+                SNAP_TRY(restore());
                 SNAP_TRY(leave_group_sweeps(h));
                 h->pass_list = nullptr;                  // (a pass over part of the groups becomes a whole epoch)
                 h->pass_count = 0;
@@ -610,14 +626,19 @@ int snap_epoch(snap_handle* h, uint64_t perm_seed) {
     if (h->opt.refresh_v_every > 0 && h->epochs_done % h->opt.refresh_v_every == 0) SNAP_TRY(recompute_shared(h));
     if (h->adaptive) {
         double now = 0.0;
-        SNAP_TRY(monitor_value(h, &now));
+        const bool refreshed = h->opt.refresh_v_every > 0 && h->epochs_done % h->opt.refresh_v_every == 0;
+        if (keep_by_swap && h->g_want_loss && !refreshed)  // (g_want_loss: now "the last pass has left its loss sums")
+            SNAP_TRY(grouped_loss_value(h, &now));
+        else
+            SNAP_TRY(monitor_value(h, &now));
         const double slack = 1e-6 * std::max(std::fabs(h->monitor_prev), 1e-30);
         if (!(now <= h->monitor_prev + slack)) {          // worse (or not a number): discard the epoch
-            SNAP_TRY(copy_pair(h->x, h->x_snap, h->m, h->v, h->v_snap, h->vlen, h->compute));
+            SNAP_TRY(restore());
             h->stats.rejected = 1;
-            // first fewer nonzeros in flight (down to one wavefront's worth), then smaller steps
+            // first fewer nonzeros in flight (down to one wavefront's worth), then smaller steps; group
+            // sweeps have nothing in flight: smaller steps at once
             const int64_t cur = h->inflight_nnz > 0 ? h->inflight_nnz : (int64_t)256 * 8 * h->seg;
-            if (cur > h->inflight_floor)
+            if (cur > h->inflight_floor && !keep_by_swap)
                 h->inflight_nnz = std::max<int64_t>(h->inflight_floor, cur / 2);
             else
                 h->damping *= 0.5f;

@@ -181,6 +181,13 @@ struct snap_handle {
     int n_row_passes = 0;
     std::vector<char> pass_timed;        // profile: which row passes of the last epoch carry their two events
     int64_t g_hot_coords = 0, g_hot_nnz = 0;
+    // an epoch of group sweeps that may have to be undone (accept check; ridge range guard): its first
+    // writing pass reads v and writes v_snap, the later ones work in v_snap, and the two pointers are swapped
+    // at the end -- the state before the epoch is then what v_snap holds, at no cost
+    bool g_keep_old = false;          // set by snap_epoch for the epoch it is about to run
+    bool g_want_loss = false;         // ... and: the last pass sums the loss into gloss_partial
+    bool g_swapped = false;           // set by the epoch: v and v_snap have changed roles
+    double* gloss_partial = nullptr;  // [row-pass workgroups]
     bool group_fallback = false;      // the group sweeps were left for the asynchronous engine (fixed-point range)
     bool perm_stale = false;          // grouped mode makes the visiting order only on request
     uint64_t last_seed = 0;
@@ -281,6 +288,7 @@ int clamp_range(float* p, float lo, float hi, int64_t count, hipStream_t s);
 int objective(snap_handle* h, double* primal, double* dual, double* gap);
 // the quantity the solver decreases (P in primal form, -D in dual form), vectors only
 int monitor_value(snap_handle* h, double* value);
+int grouped_loss_value(snap_handle* h, double* value);   // grouped.hip: the same value from the sums the epoch's last row pass left
 int chunk_gap_shares(snap_handle* h, double* shares_out);   // host array, one entry per chunk (or group)
 
 int predict(snap_handle* h, const snap_matrix* X, float* out);

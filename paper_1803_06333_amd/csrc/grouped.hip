@@ -238,6 +238,8 @@ void grouped_free(snap_handle* h) {
     (void)hipFree(h->coord_of);
     (void)hipFree(h->gdelta);
     (void)hipFree(h->gpartial);
+    (void)hipFree(h->gloss_partial);
+    h->gloss_partial = nullptr;
     h->rowmap = nullptr;
     h->rowval = nullptr;
     h->rank_of = h->coord_of = nullptr;
@@ -444,6 +446,7 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
     SNAP_HIP(hipMalloc(&h->coord_of, (size_t)(m ? m : 1) * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->gdelta, (size_t)(m ? m : 1) * sizeof(float)));
     SNAP_HIP(hipMalloc(&h->gpartial, (size_t)h->g_row_wgs * (size_t)h->gpartial_stride * sizeof(long long)));
+    SNAP_HIP(hipMalloc(&h->gloss_partial, (size_t)h->g_row_wgs * 3 * sizeof(double)));
     SNAP_HIP(hipMalloc(&h->ybits, (size_t)(h->n_pad / 8 + 16)));
     SNAP_HIP(hipMemcpyAsync(h->rank_of, rank_of.data(), (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
     SNAP_HIP(hipMemcpyAsync(h->coord_of, coord_of.data(), (size_t)m * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
@@ -951,16 +954,24 @@ static SumScales sum_scales(const snap_handle* h) {
 constexpr float FIX_MAGIC = 12582912.0f;         // 1.5 * 2^23
 constexpr unsigned long long FIX_BIAS = 0x4B400000ull;   // its bit pattern
 
-template <int KIND, bool UNIT, bool SCATTER, bool HIST, typename MAPT>
+// The shared vector is read from vin and (SCATTER) written to vout: the same array, except in the first
+// writing pass of an epoch whose earlier state must survive (the accept check of Section 3.1 may discard
+// the epoch: the state before it then simply stays where it was, and the two arrays change roles).
+// LOSS (the last pass of such an epoch): the loss of every row at its final value is summed on the way,
+// per workgroup in a fixed order, so that the objective after the epoch costs one small reduction more.
+template <int KIND, bool UNIT, bool SCATTER, bool HIST, typename MAPT, bool LOSS = false>
 __global__ void __launch_bounds__(ROW_TPB)
 k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_prev,
              const float* __restrict__ delta_prev, const MAPT* __restrict__ map_cur,
-             const float* __restrict__ val_cur, int hot, int k64, float* __restrict__ v, const float* __restrict__ y,
+             const float* __restrict__ val_cur, int hot, int k64, const float* vin, float* vout, const float* __restrict__ y,
              const uint8_t* __restrict__ ybits, int64_t n, long long* __restrict__ partial, int64_t partial_stride,
              SumScales scale, int kd, uint32_t* __restrict__ status,
-             float* __restrict__ cbuf, const uint32_t* __restrict__ wbase) {
+             float* __restrict__ cbuf, const uint32_t* __restrict__ wbase, double* __restrict__ loss_partial = nullptr,
+             const float* __restrict__ model = nullptr, int64_t m = 0) {
     constexpr int R = MapTraits<MAPT>::R;
     constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
+    __shared__ double s_loss[LOSS ? 3 * (ROW_TPB / WAVE) : 1];
+    double loss_acc = 0.0;
     // LDS: fixed-point sums.  Logistic: ranks below k64: [rank] sum of a loss' * scale.g, [k64 + rank]
     // sum of a^2 loss'' * scale.h; ranks k64 .. hot-1: one packed word at [k64 + rank] (k64 = hot: none).
     // Ridge: [rank] sum of a loss' * scale.g, k64 = 0.
@@ -980,10 +991,10 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         const int64_t r = R * q;
         const bool full = r + R - 1 < n;           // maps, values and label bits are padded; v and y are not
         if (full) {
-            load_floats<R>(v + r, vv);
+            load_floats<R>(vin + r, vv);
         } else {
 #pragma unroll
-            for (int j = 0; j < R; ++j) vv[j] = r + j < n ? v[r + j] : 0.0f;
+            for (int j = 0; j < R; ++j) vv[j] = r + j < n ? vin[r + j] : 0.0f;
         }
         if (SCATTER) {
             raw_prev = load_map(map_prev + r);
@@ -992,6 +1003,8 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         if (HIST) {
             raw_cur = load_map(map_cur + r);
             if (!UNIT) load_floats<R>(val_cur + r, ac);
+        }
+        if (HIST || LOSS) {
             if (KIND == K_PRIMAL_LOGISTIC) {
                 lab_byte = ybits[r >> 3];
             } else if (full) {
@@ -1045,13 +1058,30 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             if (full) {
 #pragma unroll
                 for (int qq = 0; qq < R / 4; ++qq)
-                    *reinterpret_cast<float4*>(v + r + 4 * qq) =
+                    *reinterpret_cast<float4*>(vout + r + 4 * qq) =
                         make_float4(vv[4 * qq], vv[4 * qq + 1], vv[4 * qq + 2], vv[4 * qq + 3]);
             } else {
 #pragma unroll
                 for (int j = 0; j < R; ++j)
-                    if (r + j < n) v[r + j] = vv[j];
+                    if (r + j < n) vout[r + j] = vv[j];
             }
+        }
+        if (LOSS) {
+            // loss of the rows at their value after the epoch (rows past the end count nothing)
+            float s = 0.0f;
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                float l;
+                if (KIND == K_PRIMAL_LOGISTIC) {
+                    const uint32_t sgn = (lab << (31 - j)) & 0x80000000u;
+                    l = logistic_loss_f32(-__uint_as_float(__float_as_uint(vv[j]) ^ sgn));       // log(1 + exp(-y v))
+                } else {
+                    const float t = vv[j] - yy[j];
+                    l = 0.5f * t * t;
+                }
+                s += (full || r + j < n) ? l : 0.0f;
+            }
+            loss_acc += (double)s;
         }
         if (HIST) {
             unpack_ranks(map_cur, raw_cur, mc);
@@ -1144,6 +1174,62 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
         long long* out = partial + (size_t)blockIdx.x * (size_t)partial_stride;
         for (int i = threadIdx.x; i < hot + k64; i += ROW_TPB) out[i] = (long long)hist[i];
     }
+    if (LOSS) {
+        // the regulariser's sums over this workgroup's slice of the model (final by now: the last step kernel
+        // of the epoch ran before this pass), so that the objective needs no pass of its own at all
+        double sq = 0.0, ab = 0.0;
+        const int64_t mper = (m + gridDim.x - 1) / gridDim.x;
+        const int64_t m0 = min(m, (int64_t)blockIdx.x * mper), m1 = min(m, m0 + mper);
+        for (int64_t i = m0 + threadIdx.x; i < m1; i += ROW_TPB) {
+            const double xi = (double)model[i];
+            sq += xi * xi;
+            ab += fabs(xi);
+        }
+#pragma unroll
+        for (int off = WAVE / 2; off > 0; off >>= 1) {
+            loss_acc += __shfl_xor(loss_acc, off, WAVE);
+            sq += __shfl_xor(sq, off, WAVE);
+            ab += __shfl_xor(ab, off, WAVE);
+        }
+        if ((threadIdx.x & (WAVE - 1)) == 0) {
+            s_loss[3 * (threadIdx.x / WAVE)] = loss_acc;
+            s_loss[3 * (threadIdx.x / WAVE) + 1] = sq;
+            s_loss[3 * (threadIdx.x / WAVE) + 2] = ab;
+        }
+        __syncthreads();
+        if (threadIdx.x < 3) {
+            double t = 0.0;
+            for (int w = 0; w < ROW_TPB / WAVE; ++w) t += s_loss[3 * w + threadIdx.x];
+            loss_partial[3 * blockIdx.x + threadIdx.x] = t;
+        }
+    }
+}
+
+// The three sums that the last row pass of an epoch leaves per workgroup (loss, ||x||^2, ||x||_1), added up
+// in a fixed order and written straight into host memory mapped into the device's address space.
+__global__ void __launch_bounds__(256)
+k_group_loss_final(const double* __restrict__ partial, int n_wgs, double* __restrict__ host_mapped) {
+    __shared__ double s[3][256];
+    double t[3] = {0.0, 0.0, 0.0};
+    for (int w = threadIdx.x; w < n_wgs; w += 256)
+        for (int k = 0; k < 3; ++k) t[k] += partial[3 * w + k];
+    for (int k = 0; k < 3; ++k) s[k][threadIdx.x] = t[k];
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double acc = 0.0;
+        for (int i = 0; i < 256; ++i) acc += s[threadIdx.x][i];
+        host_mapped[threadIdx.x] = acc;
+    }
+}
+
+// The objective after an epoch whose last pass has summed the loss (see g_want_loss); synchronises.
+int grouped_loss_value(snap_handle* h, double* value) {
+    hipLaunchKernelGGL(k_group_loss_final, dim3(1), dim3(256), 0, h->compute, h->gloss_partial, h->g_row_wgs, h->red.host_mapped);
+    SNAP_HIP(hipGetLastError());
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    const double* res = h->red.host;
+    *value = res[0] / (double)h->n + 0.5 * h->lambda * res[1] + h->lambda1 * res[2];
+    return SNAP_OK;
 }
 
 // ---- sums of the short coordinates and the steps of one group ------------------------------------------
@@ -1371,6 +1457,10 @@ static int grouped_epoch_kind(snap_handle* h) {
     // as a pass is shorter than a copy.
     const bool streamed = h->gstream;
     const bool sprof = streamed && h->opt.profile != 0 && h->gev_prof != nullptr && !h->pass_list;
+    // an epoch that may have to be undone leaves the state before it untouched: see g_keep_old
+    const bool keep_old = h->g_keep_old && h->v_snap != nullptr;
+    float* v_cur = h->v;
+    bool swapped = false, loss_done = false;
     if (streamed) {
         h->gcopy_timed.assign((size_t)(G + 1), 0);
         for (int64_t i = 0; i < std::min<int64_t>(2, n_visit); ++i)
@@ -1406,19 +1496,32 @@ static int grouped_epoch_kind(snap_handle* h) {
             const bool timed = prof && (h->opt.profile != 2 || ((n_pass + h->epochs_done) & 3) == 0);
             if (prof) h->pass_timed[(size_t)n_pass] = timed ? 1 : 0;   // (sized with the events, at set-up)
             hipEvent_t ev_a = timed ? h->ev_group[2 * n_pass] : nullptr, ev_b = timed ? h->ev_group[2 * n_pass + 1] : nullptr;
+            // the first writing pass of an epoch that may be undone writes into the other array
+            const float* vin = v_cur;
+            float* vout = (scatter && keep_old && !swapped) ? h->v_snap : v_cur;
             if (scatter && histo)
                 hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y,
-                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
-            else if (scatter)
-                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, h->v, h->y,
+                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, vin, vout, h->y,
+                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase, (double*)nullptr, (const float*)nullptr, (int64_t)0);
+            else if (scatter && last && h->g_want_loss) {
+                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT, true>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, vin, vout, h->y,
                                       h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
-                                      (const uint32_t*)nullptr);
+                                      (const uint32_t*)nullptr, h->gloss_partial, (const float*)h->x, h->m);
+                loss_done = true;
+            } else if (scatter)
+                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, vin, vout, h->y,
+                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
+                                      (const uint32_t*)nullptr, (double*)nullptr, (const float*)nullptr, (int64_t)0);
             else
                 hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, h->v, h->y,
-                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase);
+                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, vin, vout, h->y,
+                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase, (double*)nullptr, (const float*)nullptr, (int64_t)0);
+            if (vout != v_cur) {
+                v_cur = vout;
+                swapped = true;
+            }
             ++n_pass;
         }
         if (streamed) {
@@ -1435,7 +1538,7 @@ static int grouped_epoch_kind(snap_handle* h) {
             const int n_cold_blocks = (int)std::min<int64_t>((cold + per_block - 1) / per_block, 8192);
             hipLaunchKernelGGL((k_group_finish<KIND, false>), dim3((unsigned)(n_hot_blocks + n_cold_blocks)),
                                dim3(STEP_RANKS * STEP_PARTS), 0, h->compute, gpart, h->gpartial_stride, h->g_row_wgs, hot, k64,
-                               n_hot_blocks, 1.0 / (double)scale.g, 1.0 / (double)scale.h, h->ptr, h->idx, h->val, h->v, h->y, h->coord_of, g0, sz, h->x, h->norms,
+                               n_hot_blocks, 1.0 / (double)scale.g, 1.0 / (double)scale.h, h->ptr, h->idx, h->val, v_cur, h->y, h->coord_of, g0, sz, h->x, h->norms,
                                h->gdelta, sp, nullptr, cbuf, h->gcidx, h->gcptr, UNIT ? 1 : 0);
         }
         if (sprof) SNAP_HIP(hipEventRecord(h->gev_prof[4 * gi + 3], h->compute));
@@ -1447,6 +1550,9 @@ static int grouped_epoch_kind(snap_handle* h) {
         // the host does not run ahead of the copy stream by more than a pass (see for_each_chunk)
         SNAP_HIP(hipStreamSynchronize(h->copy));
     }
+    if (swapped) std::swap(h->v, h->v_snap);       // v: the state after the epoch; v_snap: the one before it
+    h->g_swapped = swapped;
+    h->g_want_loss = loss_done;                    // (tells the caller whether the loss sums are there)
     h->n_row_passes = n_pass;
     SNAP_HIP(hipGetLastError());
     return SNAP_OK;
@@ -1484,8 +1590,8 @@ static int grouped_dots_kind(snap_handle* h) {
             hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), lds,
                                h->compute, (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr,
                                map_cur, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
-                               k64, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale, 0, h->status, cbuf,
-                               wbase);
+                               k64, h->v, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale, 0, h->status, cbuf,
+                               wbase, (double*)nullptr, (const float*)nullptr, (int64_t)0);
         }
         if (streamed) {
             SNAP_HIP(hipEventRecord(h->gev_free[gi % 3], h->compute));

@@ -3,7 +3,7 @@
 // the 1/n scaling), the duality gap and decision values.  fp32 data, every sum in fp64 and in a
 // fixed order (no atomics on the reduction paths, so repeated calls give identical bits; the
 // only exception is the scatter product for compressed-column data, which uses atomics on v).
-#include "common.h"
+#include "scd_device.h"
 #include <algorithm>
 #include <mutex>
 
@@ -399,10 +399,7 @@ __device__ __forceinline__ double reduce_term(const ReduceArgs& r, int64_t i) {
         const double t = -(double)r.b[i] * (double)r.a[i];
         return t > 0 ? t + log1p(exp(-t)) : log1p(exp(t));
     }
-    if (MODE == R_LOSS_LOGISTIC_F32) {
-        const float t = -r.b[i] * r.a[i];
-        return (double)(t > 0.0f ? t + log1pf(__expf(-t)) : log1pf(__expf(t)));
-    }
+    if (MODE == R_LOSS_LOGISTIC_F32) return (double)logistic_loss_f32(-r.b[i] * r.a[i]);
     if (MODE == R_SQNORM) return (double)r.a[i] * (double)r.a[i];
     if (MODE == R_SUM) return (double)r.a[i];
     if (MODE == R_ABSSUM) return fabs((double)r.a[i]);

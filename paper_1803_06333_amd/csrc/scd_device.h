@@ -47,6 +47,15 @@ __device__ __forceinline__ float load_shared(const float* v, uint32_t r) {
     return __hip_atomic_load(v + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// log(1 + exp(t)) in fp32 with the fast exponential, overflow safe: the logistic loss of a margin -t as
+// the accept check of the epoch sums it (Section 3.1).  One definition for every place that takes this
+// sum, so that values from different kernels can be compared.
+__device__ __forceinline__ float logistic_loss_f32(float t) {
+    // max(t, 0) + log(1 + exp(-|t|)) with the hardware exponential and logarithm (a few instructions;
+    // absolute error of a term about 1e-7, the same in every place that uses it)
+    return fmaxf(t, 0.0f) + __logf(1.0f + __expf(-fabsf(t)));
+}
+
 // Contribution of one nonzero (value a, shared entry vv, label yy) to the two sums of the step.
 template <int KIND>
 __device__ __forceinline__ void accumulate(float a, float vv, float yy, float& g, float& h) {

@@ -1033,6 +1033,56 @@ def test_group_sweeps_wide_group_uses_32_bit_maps(monkeypatch, skewed):
     g.close()
 
 
+@pytest.mark.parametrize("loss,stream", [("logistic", False), ("ridge", False), ("logistic", True)])
+def test_group_sweeps_with_the_accept_check(loss, stream):
+    """With the accept check on, the group sweeps keep the state before an epoch by writing into a second
+    array (no copy) and sum the objective in their last pass.  Accepted epochs are the same epochs bit for
+    bit; a discarded one (forced here by steps scaled far beyond a Newton step) leaves model and shared
+    vector exactly as they were, halves the step scale, and the solver still reaches the oracle's objective."""
+    p = _onehot_variant(loss, True)
+    groups = p.meta["field_starts"] + [p.d]
+    A = oracle.Matrix.from_problem(p)
+    y = p.y.numpy()
+    mk = (lambda **kw: snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, group_bounds=groups, **kw)) if stream \
+        else (lambda **kw: gpu_solver(p, group_bounds=groups, **kw))
+    a, b = mk(adaptive=True, profile=True), mk(adaptive=False)
+    for e in range(5):
+        a.epoch(e)
+        b.epoch(e)
+        assert a.epoch_stats()["rejected"] == 0
+        assert np.array_equal(a.model()[1], b.model()[1]) and np.array_equal(a.shared(), b.shared())
+        assert rel(a.objective(), b.objective()) == 0.0
+    a.epoch_chunks(7, [3, 1])                                # a pass over part of the fields, checked as well
+    b.epoch_chunks(7, [3, 1])
+    assert np.array_equal(a.model()[1], b.model()[1]) and np.array_equal(a.shared(), b.shared())
+    a.close()
+    b.close()
+    # steps 24 times too long make the first epochs worse: discarded, state untouched, scale halved (24, 12, 6,
+    # 3, then 1.5, which converges; a power of two would pass through 2, where exact steps on a quadratic
+    # leave the objective where it is)
+    target = oracle.solve(A, y, p.loss, p.lam, epochs=500, tol=1e-7).primal()
+    g = mk(adaptive=True, damping=24.0, profile=True)
+    rejected, prev_x, prev_v, prev_P = 0, g.model()[1].copy(), np.array(g.shared(), copy=True), g.objective()
+    scales = []
+    for e in range(80):
+        g.epoch(e)
+        st = g.epoch_stats()
+        scales.append(st["damping"])
+        if st["rejected"]:
+            rejected += 1
+            assert np.array_equal(g.model()[1], prev_x) and np.array_equal(g.shared(), prev_v)
+            assert g.objective() == prev_P
+        else:
+            assert g.objective() <= prev_P * (1 + 2e-6)
+        prev_x, prev_v, prev_P = g.model()[1].copy(), np.array(g.shared(), copy=True), g.objective()
+    assert rejected >= 2 and scales[-1] < scales[0]
+    assert rel(prev_P, target) <= 1e-4
+    chk = oracle.Solver(A, y, p.loss, p.lam)
+    chk.x[:] = prev_x
+    assert relnorm(prev_v, chk.shared_from_model()) <= 1e-4
+    g.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # the accept check (Section 3.1, "Adaptive Damping"): too much work in flight makes an epoch worse;
 # the epoch is discarded, the cap on work in flight halved, and the solver still converges
