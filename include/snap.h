@@ -212,8 +212,10 @@ int snap_duality_gap(snap_handle *h, double *gap);
  * column-major; X->n_cols must equal the training n_cols).  out has X->n_rows floats in the memory
  * space X->mem.  Compressed X is checked first (ptr from 0 to nnz without decreasing, every index in
  * range; SNAP_EINVAL otherwise, nothing written): one more pass over ptr and idx.  Every value is an
- * fp64 sum rounded once to fp32 (CSC: summed with fp64 atomics in a buffer of 8 bytes per row held for the
- * call), so the layouts agree to the last bit or two.  Synchronises. */
+ * fp64 sum rounded once to fp32.  The row layouts add in a fixed order (same bits on every call); CSC
+ * adds with fp64 atomics in a buffer of 8 bytes per row held for the call, in no fixed order, so its
+ * fp64 sum can move in its last places and the fp32 result, rarely, by one unit in the last place
+ * (contract: within one fp32 ulp of the row layouts' result).  Synchronises. */
 int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
 
 /* snap_predict for callers that cannot allocate device memory: code under HIP graph capture, tight
@@ -239,9 +241,10 @@ int snap_set_model(snap_handle *h, const float *coord_in);
  * n_cols dual). */
 int snap_get_shared(snap_handle *h, float *v_out);
 
-/* v <- A x recomputed from the model (removes fp32 drift of the atomically updated v).  The sums are
- * taken in fp64 and rounded once, in a device buffer of 8 bytes per entry of v that is allocated for the
- * call (fp32 sums if that allocation fails); synchronises.  snap_set_model does the same. */
+/* Algorithm 1 (v = A alpha): v recomputed from the model (removes fp32 drift of the atomically updated
+ * v).  The sums are taken in fp64 (atomics, no fixed order) and rounded once, in a device buffer of
+ * 8 bytes per entry of v that is allocated for the call (fp32 sums if that allocation fails): the same
+ * one-ulp contract as snap_predict's CSC layout; synchronises.  snap_set_model does the same. */
 int snap_recompute_shared(snap_handle *h);
 
 /* Section 3.2 (a random permutation of the coordinates of the active buffer from 32-bit xorshift

@@ -389,6 +389,40 @@ def test_predict_csr_rows_of_every_length(mean_len):
     g.close()
 
 
+def test_predict_column_layout_agrees_with_the_row_layout_to_the_last_bit_of_its_fp64_sums():
+    """The contract of the compressed-column layouts (predict, and v = A x in set_model / recompute_shared):
+    every entry is an fp64 sum of its terms rounded once to fp32.  The terms are added with fp64 atomics, so
+    the order is not fixed, but the fp64 sum moves by at most a few units in its last place (2^-52 relative
+    to the largest partial sum), which changes the fp32 result only when the sum sits within that distance
+    of a rounding boundary: against the row layout (fixed order) at most one fp32 ulp, and almost always none."""
+    r = np.random.default_rng(77)
+    rows, d = 30_000, 2_000
+    lengths = np.clip(r.poisson(25, size=rows), 0, d)
+    ptr, idx, val = _ragged_matrix(lengths, d, 78)
+    rr = np.repeat(np.arange(rows), np.diff(ptr))
+    order = np.lexsort((rr, idx))
+    cptr = np.concatenate([[0], np.cumsum(np.bincount(idx, minlength=d))]).astype(np.int64)
+    cidx, cval = rr[order].astype(np.int32), val[order]
+    y = np.sign(r.standard_normal(rows)).astype(np.float32)
+    g = snap.Solver("csc", rows, d, cptr, cidx, cval, y, "logistic", 1e-3, auto_groups=False)
+    w = r.standard_normal(d).astype(np.float32)
+    g.set_model(w)
+    by_rows = g.predict("csr", rows, ptr, idx, val)
+    want = oracle.Matrix("csr", rows, d, ptr, idx, val).matvec(w.astype(np.float64))
+    ulp = np.spacing(np.abs(by_rows).astype(np.float32)).astype(np.float64)
+    differing = 0
+    for _ in range(3):
+        by_cols = g.predict("csc", rows, cptr, cidx, cval)
+        assert np.all(np.abs(by_cols.astype(np.float64) - by_rows) <= ulp)
+        differing = max(differing, int(np.sum(by_cols != by_rows)))
+        assert np.all(np.abs(by_cols - want) <= 0.5 * ulp + 1e-12 * np.abs(want).max() + 1e-6 * ulp)
+    assert differing <= rows // 1000
+    # the maintained v after set_model is the same product through the same kernel
+    v = g.shared()
+    assert np.all(np.abs(v.astype(np.float64) - by_rows) <= ulp) and int(np.sum(v != by_rows)) <= rows // 1000
+    g.close()
+
+
 def test_predict_checks_compressed_input():
     """ptr and idx of the matrix handed to predict are checked before any kernel follows them."""
     ptr = np.array([0, 2, 3], dtype=np.int64)
