@@ -111,9 +111,10 @@ typedef struct {
                                     interact -- with plain coalesced updates of v instead of atomics.
                                     Streamed data (device_budget_bytes exceeded; pattern-only data, i.e. all
                                     values 1): the row maps of the sweeps are built at creation into pinned
-                                    host memory of the library's own (1, 2 or 4 bytes per row and group) and
-                                    an epoch streams those through a ring of three device buffers instead of
-                                    the column indices.
+                                    host memory of the library's own (1, 2 or 4 bytes per row and group; groups
+                                    of up to 65535 coordinates whose rows concentrate on few of them: a byte per
+                                    row plus two bytes for each row that does not fit) and an epoch streams
+                                    those through a ring of three device buffers instead of the column indices.
                                     The sums of the sweeps are fixed point.  Logistic loss: the sweeps are not
                                     used when lambda * n_rows < max|value|^2 / 16 (their resolution could show
                                     in a step); ridge loss: a term a (v - y) of 2^14 or more does not fit, the

@@ -175,6 +175,89 @@ __global__ void k_map8_to_16(const uint8_t* __restrict__ in, uint16_t* __restric
     }
 }
 
+// Escape-coded byte maps: the ranks of a one-hot field with a Zipf-like popularity are concentrated
+// (four of five rows of the click-log fields have a rank below 254), so a field of up to 65535 columns
+// crosses the host link as one byte per row -- the rank, ESC8 for "rank >= 254", 0xFF for "none" -- plus
+// the two-byte ranks of the escaped rows in row order.  Layout of a blob:
+//   [ n_pad bytes ][ one uint32 per block of ESC_BLOCK rows: escaped rows before the block ][ uint16 ranks ]
+// A workgroup of ESC_TPB threads handles one block, four consecutive rows per thread; the place of a
+// thread's first escaped row is the block's offset plus an exclusive scan of the per-thread counts.
+constexpr int ESC_TPB = 1024, ESC_BLOCK = 4 * ESC_TPB;
+constexpr uint32_t ESC8 = 254u;
+
+// exclusive prefix, over the workgroup, of a count 0 .. 4 per thread (three ballots per wavefront, one
+// round through LDS for the wavefronts' totals); s_tot: ESC_TPB / WAVE + 1 words
+__device__ __forceinline__ uint32_t esc_scan(uint32_t c, uint32_t* s_tot) {
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        const unsigned long long m = __builtin_amdgcn_ballot_w64((c >> b) & 1u);
+        before += (uint32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u)) << b;
+        total += (uint32_t)__popcll(m) << b;
+    }
+    __syncthreads();                                   // (s_tot may still be read from an earlier use)
+    if (lane == 0) s_tot[wave] = total;
+    __syncthreads();
+    uint32_t base = 0;
+    for (int w = 0; w < wave; ++w) base += s_tot[w];
+    return base + before;
+}
+
+__device__ __forceinline__ bool esc_row(uint32_t rank) { return rank >= ESC8 && rank != 0xFFFFu; }
+
+// counts[block] <- escaped rows of the block
+__global__ void __launch_bounds__(ESC_TPB)
+k_esc_count(const uint16_t* __restrict__ map, uint32_t* __restrict__ counts) {
+    __shared__ uint32_t s_tot[ESC_TPB / WAVE + 1];
+    const uint2 u = reinterpret_cast<const uint2*>(map)[(size_t)blockIdx.x * ESC_TPB + threadIdx.x];
+    const uint32_t c = esc_row(u.x & 0xFFFFu) + esc_row(u.x >> 16) + esc_row(u.y & 0xFFFFu) + esc_row(u.y >> 16);
+    const uint32_t at = esc_scan(c, s_tot);
+    if (threadIdx.x == ESC_TPB - 1) counts[blockIdx.x] = at + c;
+}
+
+// map (n_pad 16-bit entries, n_pad a multiple of ESC_BLOCK here: the staging map is padded with "none")
+// -> bytes, and the escaped ranks at their places; offs[block] = escaped rows before the block
+__global__ void __launch_bounds__(ESC_TPB)
+k_esc_encode(const uint16_t* __restrict__ map, const uint32_t* __restrict__ offs, uint8_t* __restrict__ bytes,
+             uint16_t* __restrict__ esc) {
+    __shared__ uint32_t s_tot[ESC_TPB / WAVE + 1];
+    const size_t t = (size_t)blockIdx.x * ESC_TPB + threadIdx.x;
+    const uint2 u = reinterpret_cast<const uint2*>(map)[t];
+    const uint32_t r[4] = {u.x & 0xFFFFu, u.x >> 16, u.y & 0xFFFFu, u.y >> 16};
+    const uint32_t c = esc_row(r[0]) + esc_row(r[1]) + esc_row(r[2]) + esc_row(r[3]);
+    uint32_t at = offs[blockIdx.x] + esc_scan(c, s_tot);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t b = r[j] == 0xFFFFu ? 0xFFu : r[j];
+        if (esc_row(r[j])) {
+            esc[at++] = (uint16_t)r[j];
+            b = ESC8;
+        }
+        packed |= b << (8 * j);
+    }
+    reinterpret_cast<uint32_t*>(bytes)[t] = packed;
+}
+
+__global__ void __launch_bounds__(ESC_TPB)
+k_esc_decode(const uint8_t* __restrict__ bytes, const uint32_t* __restrict__ offs, const uint16_t* __restrict__ esc,
+             uint16_t* __restrict__ map) {
+    __shared__ uint32_t s_tot[ESC_TPB / WAVE + 1];
+    const size_t t = (size_t)blockIdx.x * ESC_TPB + threadIdx.x;
+    const uint32_t u = reinterpret_cast<const uint32_t*>(bytes)[t];
+    const uint32_t b[4] = {u & 0xFFu, u >> 8 & 0xFFu, u >> 16 & 0xFFu, u >> 24};
+    const uint32_t c = (b[0] == ESC8) + (b[1] == ESC8) + (b[2] == ESC8) + (b[3] == ESC8);
+    uint32_t at = offs[blockIdx.x] + esc_scan(c, s_tot);
+    uint32_t r[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = b[j] == ESC8 ? (uint32_t)esc[at++] : (b[j] == 0xFFu ? 0xFFFFu : b[j]);
+    uint2 o;
+    o.x = r[0] | (r[1] << 16);
+    o.y = r[2] | (r[3] << 16);
+    reinterpret_cast<uint2*>(map)[t] = o;
+}
+
 // bit (r & 7) of byte (r >> 3) = 1 when y[r] < 0
 __global__ void k_label_bits(const float* __restrict__ y, int64_t n, uint8_t* __restrict__ bits, int64_t n_bytes) {
     for (int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; b < n_bytes; b += (int64_t)gridDim.x * blockDim.x) {
@@ -813,22 +896,38 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
         set_error("group sweeps on streamed data need the dense buffer of the short coordinates (SNAP_COMPACT=0 is set)");
         return SNAP_EUNSUPPORTED;
     }
+    // How every group's map crosses the host link: 0 = as it is read (2 or 4 bytes per row), 1 = one byte per
+    // row (at most 255 coordinates), 2 = escape-coded bytes (see k_esc_encode) when that is at least a
+    // tenth shorter than two bytes per row.  The device buffers are padded to whole blocks of ESC_BLOCK rows.
+    const int64_t n_esc = (h->n_pad + ESC_BLOCK - 1) / ESC_BLOCK * ESC_BLOCK, n_blk = n_esc / ESC_BLOCK;
     const size_t map_bytes = (size_t)h->n_pad * sizeof(MAPT);
     h->gmap8_host = new (std::nothrow) uint8_t[(size_t)G]();
     h->gmap_off_host = new (std::nothrow) int64_t[(size_t)G + 1]();
     if (!h->gmap8_host || !h->gmap_off_host) return SNAP_ENOMEM;
-    bool any8 = false;
+    std::vector<int64_t> escaped((size_t)G, 0);     // rows of the group whose rank does not fit a byte
+    int64_t land_bytes = 0;                          // largest byte-coded map: size of the landing buffers
     for (int64_t g = 0; g < G; ++g) {
-        const int64_t sz = h->gbounds_host[g + 1] - h->gbounds_host[g];
-        h->gmap8_host[g] = sizeof(MAPT) == 2 && sz <= 255 && map8_knob();      // ranks 0 .. 254, 255 = none
-        any8 = any8 || h->gmap8_host[g];
-        h->gmap_off_host[g + 1] = h->gmap_off_host[g] + (sz == 0 ? 0 : h->gmap8_host[g] ? (int64_t)h->n_pad : (int64_t)map_bytes);
+        const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
+        for (int64_t r = ESC8; r < sz; ++r) {
+            const int64_t c = coord_of[(size_t)(g0 + r)];
+            escaped[(size_t)g] += hptr[c + 1] - hptr[c];
+        }
+        const int64_t blob = (n_esc + 4 * n_blk + 2 * escaped[(size_t)g] + 7) / 8 * 8;
+        int mode = 0;
+        int64_t bytes = (int64_t)map_bytes;
+        if (sizeof(MAPT) == 2 && map8_knob()) {
+            if (sz <= 255) mode = 1, bytes = h->n_pad;                              // ranks 0 .. 254, 255 = none
+            else if (10 * blob <= 9 * (int64_t)map_bytes) mode = 2, bytes = blob;
+        }
+        h->gmap8_host[g] = (uint8_t)mode;
+        if (mode != 0) land_bytes = std::max(land_bytes, bytes);
+        h->gmap_off_host[g + 1] = h->gmap_off_host[g] + (sz == 0 ? 0 : bytes);
     }
     h->gmap_bytes_per_pass = h->gmap_off_host[G];
     SNAP_HIP(hipHostMalloc(&h->gmaps_host, (size_t)std::max<int64_t>(h->gmap_off_host[G], 8), hipHostMallocDefault));
     for (int b = 0; b < 3; ++b) {
-        SNAP_HIP(hipMalloc(&h->gring[b], map_bytes));
-        if (any8) SNAP_HIP(hipMalloc(&h->gring8[b], (size_t)h->n_pad));
+        SNAP_HIP(hipMalloc(&h->gring[b], (size_t)n_esc * sizeof(MAPT)));
+        if (land_bytes > 0) SNAP_HIP(hipMalloc(&h->gring8[b], (size_t)land_bytes));
         SNAP_HIP(hipEventCreateWithFlags(&h->gev_copied[b], hipEventDisableTiming));
         SNAP_HIP(hipEventCreateWithFlags(&h->gev_free[b], hipEventDisableTiming));
         h->gring_group[b] = -1;
@@ -859,8 +958,9 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
         if (rc_ != SNAP_OK) return fail(rc_); \
     } while (0)
     S_HIP(hipMalloc(&stage, (size_t)(max_group_nnz ? max_group_nnz : 1) * sizeof(uint32_t)));
-    S_HIP(hipMalloc(&wide, (size_t)h->n_pad * sizeof(uint32_t)));
+    S_HIP(hipMalloc(&wide, (size_t)n_esc * sizeof(uint32_t)));
     S_HIP(hipMalloc(&rowpos, (size_t)h->n_pad * sizeof(uint32_t)));
+    std::vector<uint32_t> blk((size_t)n_blk);
     S_HIP(hipMalloc(&flags, sizeof(uint32_t)));
     S_TRY(fill_zero(flags, sizeof(uint32_t), h->compute));
     S_TRY(fill_zero(rowpos, (size_t)h->n_pad * sizeof(uint32_t), h->compute));   // (every entry a valid position)
@@ -872,7 +972,7 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
         const int hot = h->ghot_host[g];
         MAPT* narrow = (MAPT*)h->gring[0];        // (the ring is not in use yet)
         if (sz == 0) continue;
-        hipLaunchKernelGGL(k_fill_u32, dim3(8192), dim3(256), 0, h->compute, wide, (size_t)h->n_pad, RANK_NONE);
+        hipLaunchKernelGGL(k_fill_u32, dim3(8192), dim3(256), 0, h->compute, wide, (size_t)n_esc, RANK_NONE);
         if (cnt > 0) {
             S_HIP(hipMemcpyAsync(stage, h->host_idx + k_lo, (size_t)cnt * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
             if (label_mask) S_TRY(fold_labels(h, stage, cnt, h->compute));
@@ -880,13 +980,37 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
                                stage, k_lo, k_hi, g0, g1, h->rank_of, wide, flags);
         }
         if (sizeof(MAPT) == 2)
-            hipLaunchKernelGGL(k_narrow_map, dim3(8192), dim3(256), 0, h->compute, wide, (uint16_t*)narrow, (size_t)h->n_pad);
+            hipLaunchKernelGGL(k_narrow_map, dim3(8192), dim3(256), 0, h->compute, wide, (uint16_t*)narrow, (size_t)n_esc);
         const MAPT* dev_map = sizeof(MAPT) == 2 ? narrow : (const MAPT*)wide;
         S_HIP(hipGetLastError());
-        if (h->gmap8_host[g]) {
+        if (h->gmap8_host[g] == 1) {
             hipLaunchKernelGGL(k_map16_to_8, dim3(8192), dim3(256), 0, h->compute, (const uint16_t*)dev_map, h->gring8[0], (size_t)h->n_pad);
             S_HIP(hipGetLastError());
             S_HIP(hipMemcpyAsync((char*)h->gmaps_host + h->gmap_off_host[g], h->gring8[0], (size_t)h->n_pad, hipMemcpyDeviceToHost, h->compute));
+        } else if (h->gmap8_host[g] == 2) {
+            // escape-coded: count per block, offsets by a prefix sum on the host, then bytes and escaped ranks
+            uint8_t* blob = h->gring8[0];
+            uint32_t* offs = reinterpret_cast<uint32_t*>(blob + n_esc);
+            uint16_t* esc = reinterpret_cast<uint16_t*>(blob + n_esc + 4 * n_blk);
+            hipLaunchKernelGGL(k_esc_count, dim3((unsigned)n_blk), dim3(ESC_TPB), 0, h->compute, (const uint16_t*)dev_map, offs);
+            S_HIP(hipGetLastError());
+            S_HIP(hipMemcpyAsync(blk.data(), offs, (size_t)n_blk * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+            S_HIP(hipStreamSynchronize(h->compute));
+            uint64_t run = 0;
+            for (int64_t b = 0; b < n_blk; ++b) {
+                const uint32_t cnt = blk[(size_t)b];
+                blk[(size_t)b] = (uint32_t)run;
+                run += cnt;
+            }
+            if ((int64_t)run != escaped[(size_t)g]) {      // the row map and the column lengths disagree
+                set_error("internal error: the escaped rows of a row map do not add up");
+                return fail(SNAP_ESTATE);
+            }
+            S_HIP(hipMemcpyAsync(offs, blk.data(), (size_t)n_blk * sizeof(uint32_t), hipMemcpyHostToDevice, h->compute));
+            hipLaunchKernelGGL(k_esc_encode, dim3((unsigned)n_blk), dim3(ESC_TPB), 0, h->compute, (const uint16_t*)dev_map, offs, blob, esc);
+            S_HIP(hipGetLastError());
+            S_HIP(hipMemcpyAsync((char*)h->gmaps_host + h->gmap_off_host[g], blob,
+                                 (size_t)(h->gmap_off_host[g + 1] - h->gmap_off_host[g]), hipMemcpyDeviceToHost, h->compute));
         } else {
             S_HIP(hipMemcpyAsync((char*)h->gmaps_host + h->gmap_off_host[g], dev_map, map_bytes, hipMemcpyDeviceToHost, h->compute));
         }
@@ -1403,7 +1527,7 @@ static int enqueue_map_copy(snap_handle* h, int64_t g, int slot, int64_t prof) {
     if (prof >= 0) h->gcopy_timed[(size_t)prof] = 0;
     if (h->gring_group[slot] == g) return SNAP_OK;
     const size_t map_bytes = (size_t)(h->gmap_off_host[g + 1] - h->gmap_off_host[g]);
-    const bool bytes8 = h->gmap8_host[g] != 0;
+    const bool bytes8 = h->gmap8_host[g] != 0;          // byte-coded (plain or with escapes): lands in the byte buffer
     SNAP_HIP(hipStreamWaitEvent(h->copy, h->gev_free[slot], 0));
     if (prof >= 0) {
         SNAP_HIP(hipEventRecord(h->gev_prof[4 * prof + 0], h->copy));
@@ -1423,8 +1547,16 @@ static int enqueue_map_copy(snap_handle* h, int64_t g, int slot, int64_t prof) {
 static int acquire_map(snap_handle* h, int slot) {
     SNAP_HIP(hipStreamWaitEvent(h->compute, h->gev_copied[slot], 0));
     if (!h->gring_widened[slot]) {
-        hipLaunchKernelGGL(k_map8_to_16, dim3(4096), dim3(256), 0, h->compute, h->gring8[slot], (uint16_t*)h->gring[slot],
-                           (size_t)h->n_pad);
+        if (h->gmap8_host[h->gring_group[slot]] == 2) {
+            const int64_t n_esc = (h->n_pad + ESC_BLOCK - 1) / ESC_BLOCK * ESC_BLOCK, n_blk = n_esc / ESC_BLOCK;
+            const uint8_t* blob = h->gring8[slot];
+            hipLaunchKernelGGL(k_esc_decode, dim3((unsigned)n_blk), dim3(ESC_TPB), 0, h->compute, blob,
+                               reinterpret_cast<const uint32_t*>(blob + n_esc),
+                               reinterpret_cast<const uint16_t*>(blob + n_esc + 4 * n_blk), (uint16_t*)h->gring[slot]);
+        } else {
+            hipLaunchKernelGGL(k_map8_to_16, dim3(4096), dim3(256), 0, h->compute, h->gring8[slot], (uint16_t*)h->gring[slot],
+                               (size_t)h->n_pad);
+        }
         SNAP_HIP(hipGetLastError());
         h->gring_widened[slot] = true;
     }

@@ -891,6 +891,65 @@ def test_streamed_group_sweeps_equal_resident_ones_bit_for_bit_and_the_oracle(mo
     r.close()
 
 
+@pytest.mark.parametrize("row_wgs", [None, "5"])
+def test_streamed_group_sweeps_escape_coded_row_maps(monkeypatch, row_wgs):
+    """Fields of 256 ... 65535 columns whose rows concentrate on the low ranks cross the host link as one
+    byte per row plus the two-byte ranks of the rows that do not fit (rank >= 254), and are decoded on the
+    device: same sweeps bit for bit as with resident maps, and the bytes per pass are the coded sizes."""
+    if row_wgs:
+        monkeypatch.setenv("SNAP_ROW_WGS", row_wgs)
+    p = datagen.onehot_fields(n=100_003, d=13 * 64 + 26 * 1000, lam=1e-4, seed=23)    # 26 Zipf fields of 1000 columns
+    groups = p.meta["field_starts"] + [p.d]
+    G = len(groups) - 1
+    lengths = np.diff(p.ptr.numpy())
+    n_pad = (p.n + 7) // 8 * 8
+    n_esc = (n_pad + 4095) // 4096 * 4096
+    want_bytes, coded = 0, 0
+    for a, b in zip(groups, groups[1:]):
+        by_rank = np.sort(lengths[a:b], kind="stable")[::-1]
+        if b - a <= 255:
+            want_bytes += n_pad
+        else:
+            blob = (n_esc + 4 * (n_esc // 4096) + 2 * int(by_rank[254:].sum()) + 7) // 8 * 8
+            assert 10 * blob <= 9 * 2 * n_pad          # the generator's Zipf fields are concentrated enough
+            want_bytes += blob
+            coded += 1
+    assert coded == 26
+    r = gpu_solver(p, group_bounds=groups)
+    g = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, group_bounds=groups)
+    assert g.stream_bytes() == want_bytes < 0.75 * G * n_pad * 2
+    o = oracle.Solver(oracle.Matrix.from_problem(p), p.y.numpy(), p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    for e in range(4):
+        g.epoch(e)
+        r.epoch(e)
+        o.epoch(e)
+        assert np.array_equal(g.model()[1], r.model()[1]) and np.array_equal(g.shared(), r.shared())
+    close(g.model()[1], o.x, rtol=GROUP_RTOL, atol_rel=GROUP_ATOL)
+    assert g.duality_gap() == r.duality_gap()
+    g.close()
+    # a field whose rows spread evenly over 3000 columns gains nothing from the coding: two bytes per row
+    n, d1, d2 = 60_000, 3_000, 40
+    rng = np.random.default_rng(5)
+    cols = np.concatenate([rng.integers(0, d1, size=n), d1 + rng.integers(0, d2, size=n)])
+    rows = np.concatenate([np.arange(n), np.arange(n)])
+    order = np.lexsort((rows, cols))
+    ptr = np.concatenate([[0], np.cumsum(np.bincount(cols, minlength=d1 + d2))]).astype(np.int64)
+    idx = rows[order].astype(np.int32)
+    y = np.where(rng.random(n) < 0.4, 1.0, -1.0).astype(np.float32)
+    pin = lambda a: torch.from_numpy(a).pin_memory()
+    u = snap.Solver("csc", n, d1 + d2, pin(ptr), pin(idx), None, pin(y), "logistic", 1e-4, group_bounds=[0, d1, d1 + d2],
+                    device_budget_bytes=1 << 16)
+    assert u.stream_bytes() == 2 * n + n
+    ou = oracle.Solver(oracle.Matrix("csc", n, d1 + d2, ptr, idx, np.ones(idx.size, dtype=np.float32)), y, "logistic", 1e-4,
+                       chunk_bounds=[0, d1, d1 + d2], shuffle_chunks=True)
+    for e in range(3):
+        u.epoch(e)
+        ou.epoch(e)
+    close(u.model()[1], ou.x, rtol=GROUP_RTOL, atol_rel=GROUP_ATOL)
+    u.close()
+    r.close()
+
+
 def test_streamed_group_sweeps_wide_group_and_error_paths(monkeypatch):
     # a field with more than 65535 categories: 4-byte row maps through the ring
     monkeypatch.setenv("SNAP_ROW_WGS", "16")
