@@ -902,7 +902,7 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         SNAP_HIP(hipStreamSynchronize(h->copy));
         float total = 0, copy = 0, scd = 0;
         SNAP_HIP(hipEventElapsedTime(&total, h->ev[0], h->ev[2]));
-        if (h->gev_prof && !h->gcopy_timed.empty())
+        if (h->gev_prof && h->gprof_valid && !h->gcopy_timed.empty())
             for (int64_t i = 0; i <= h->g_visits; ++i) {
                 float a = 0, b = 0;
                 if (i < h->g_visits && h->gcopy_timed[(size_t)i])

@@ -206,6 +206,7 @@ struct snap_handle {
     hipEvent_t gev_copied[3] = {nullptr, nullptr, nullptr}, gev_free[3] = {nullptr, nullptr, nullptr};
     hipEvent_t* gev_prof = nullptr;   // profile: per visit copy begin / end (copy stream), kernels begin / end (compute stream)
     int64_t g_visits = 0;             // visits of the last pass (for the statistics)
+    bool gprof_valid = false;         // the last pass recorded its per-visit events
     std::vector<char> gcopy_timed;    // profile: the visit's map was copied (not found in the ring) in the last pass
     int64_t gmap_bytes_per_pass = 0;  // bytes of row maps that a pass over all groups copies
 

@@ -1543,9 +1543,11 @@ static int enqueue_map_copy(snap_handle* h, int64_t g, int slot, int64_t prof) {
     return SNAP_OK;
 }
 
-// The compute stream takes over ring slot `slot`: wait for its copy and, for a byte map, widen it.
-static int acquire_map(snap_handle* h, int slot) {
+// The compute stream takes over ring slot `slot`: wait for its copy and, for a byte-coded map, decode it.
+// begin (may be null): an event to record once the copy is there, ahead of the decoding (profiling).
+static int acquire_map(snap_handle* h, int slot, hipEvent_t begin) {
     SNAP_HIP(hipStreamWaitEvent(h->compute, h->gev_copied[slot], 0));
+    if (begin) SNAP_HIP(hipEventRecord(begin, h->compute));
     if (!h->gring_widened[slot]) {
         if (h->gmap8_host[h->gring_group[slot]] == 2) {
             const int64_t n_esc = (h->n_pad + ESC_BLOCK - 1) / ESC_BLOCK * ESC_BLOCK, n_blk = n_esc / ESC_BLOCK;
@@ -1618,8 +1620,8 @@ static int grouped_epoch_kind(snap_handle* h) {
         const bool scatter = prev >= 0, histo = !last && (hot > 0 || compact);
         float* cbuf = compact ? h->gcbuf : nullptr;
         const uint32_t* wbase = compact ? h->gwbase + (size_t)g * (size_t)(h->g_row_wgs * (ROW_TPB / WAVE)) : nullptr;
-        if (streamed && !last) SNAP_TRY(acquire_map(h, (int)(gi % 3)));
-        if (sprof) SNAP_HIP(hipEventRecord(h->gev_prof[4 * gi + 2], h->compute));
+        if (streamed && !last) SNAP_TRY(acquire_map(h, (int)(gi % 3), sprof ? h->gev_prof[4 * gi + 2] : nullptr));
+        else if (sprof) SNAP_HIP(hipEventRecord(h->gev_prof[4 * gi + 2], h->compute));
         if (n > 0 && (scatter || histo)) {
             // (profile: the two events take the kernel's own start and end times; events recorded between
             // the launches instead cost the chain of dependent kernels 3 us each)
@@ -1679,6 +1681,7 @@ static int grouped_epoch_kind(snap_handle* h) {
     }
     if (streamed) {
         h->g_visits = n_visit;
+        h->gprof_valid = sprof;                      // (a pass over listed groups is not timed)
         // the host does not run ahead of the copy stream by more than a pass (see for_each_chunk)
         SNAP_HIP(hipStreamSynchronize(h->copy));
     }
@@ -1715,7 +1718,7 @@ static int grouped_dots_kind(snap_handle* h) {
         float* cbuf = compact ? h->gcbuf : nullptr;
         const uint32_t* wbase = compact ? h->gwbase + (size_t)g * (size_t)(h->g_row_wgs * (ROW_TPB / WAVE)) : nullptr;
         const MAPT* map_cur = streamed ? (const MAPT*)h->gring[gi % 3] : maps + (size_t)g * h->n_pad;
-        if (streamed) SNAP_TRY(acquire_map(h, (int)(gi % 3)));
+        if (streamed) SNAP_TRY(acquire_map(h, (int)(gi % 3), nullptr));
         if (n > 0 && (hot > 0 || compact)) {
             const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + sizeof(float) +
                                (compact ? (size_t)(ROW_TPB / WAVE) * COLD_RING * sizeof(float) : 0);

@@ -83,6 +83,21 @@ def test_onehot_fields_structure():
     assert torch.equal(q.idx, p.idx) and torch.equal(q.y, p.y)
 
 
+def test_pattern_only_problem_has_no_value_array_and_the_same_pattern():
+    """pattern_only: no value array at all (val = None stands for "every stored value is 1"); the oracle's
+    matrix gets an array of ones for it, everything else is the same problem."""
+    import oracle
+    a = datagen.onehot_fields(n=3000, d=2000, seed=9)
+    b = datagen.onehot_fields(n=3000, d=2000, seed=9, pattern_only=True)
+    assert b.val is None and b.nnz == a.nnz == 39 * 3000
+    assert torch.equal(a.ptr, b.ptr) and torch.equal(a.idx, b.idx) and torch.equal(a.y, b.y)
+    assert b.to("cpu").val is None
+    A, B = oracle.Matrix.from_problem(a), oracle.Matrix.from_problem(b)
+    assert B.val.dtype == np.float32 and np.array_equal(A.val, B.val) and np.array_equal(A.idx, B.idx)
+    w = np.random.default_rng(0).standard_normal(2000)
+    assert np.array_equal(A.matvec(w), B.matvec(w))
+
+
 def test_row_ranges_of_categories_are_consistent():
     a = datagen.onehot_categories(1000, 5000, 7, 15, "cpu")
     b = datagen.onehot_categories(1000, 5000, 7, 15, "cpu", row0=400, nrows=100)

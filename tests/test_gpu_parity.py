@@ -878,6 +878,7 @@ def test_streamed_group_sweeps_equal_resident_ones_bit_for_bit_and_the_oracle(mo
         o.epoch(10 + e, chunks=chunks)
         assert same(g.model()[1], r.model()[1]) and same(g.shared(), r.shared())
     assert relnorm(g.model()[1], o.x) <= 2e-5
+    assert g.epoch_stats()["n_chunks"] == G                  # (a pass over listed fields is not timed: no stale figures)
     base = g.bytes_copied()
     g.epoch_chunks(50, [3, 9])
     g.epoch_chunks(51, [3, 9])                                            # the two maps are still in the ring
