@@ -114,7 +114,8 @@ typedef struct {
                                     host memory of the library's own (1, 2 or 4 bytes per row and group; groups
                                     of up to 65535 coordinates whose rows concentrate on few of them: a byte per
                                     row plus two bytes for each row that does not fit) and an epoch streams
-                                    those through a ring of three device buffers instead of the column indices.
+                                    those through a ring of three device buffers instead of the column indices
+                                    (when that pinned memory cannot be had, the sweeps are declined as below).
                                     The sums of the sweeps are fixed point.  Logistic loss: the sweeps are not
                                     used when lambda * n_rows < max|value|^2 / 16 (their resolution could show
                                     in a step); ridge loss: a term a (v - y) of 2^14 or more does not fit, the
@@ -138,12 +139,15 @@ typedef struct {
                                     0: automatic (used whenever it applies), 1: required (error when it does
                                     not apply), 2: off (asynchronous epoch with atomic updates of v).
                                     snap_get_chunks reports the tiles. */
-    int auto_groups;             /* without group_bounds (primal form, sparse, resident): look for a partition of
+    int auto_groups;             /* without group_bounds (primal form, sparse): look for a partition of
                                     the coordinates into few ranges of consecutive coordinates with pairwise
                                     disjoint supports (the fields of one-hot encoded data) and, when one is
                                     found, use the group sweeps described at group_bounds.  The search costs
                                     about two passes over the nonzeros and gives up as soon as the ranges
-                                    turn out short (more than 8 + 10 nnz_covered / n_rows of them).
+                                    turn out short (more than 8 + 10 nnz_covered / n_rows of them).  Streamed
+                                    data: the search works on each chunk while the pass that creation makes
+                                    over the data anyway has it on the device (nothing more crosses the host
+                                    link for it); what it finds is used when every stored value is 1.
                                     0: automatic, 1: required (error when nothing is found), 2: off.
                                     snap_get_chunks reports what was found. */
     int host_keys;               /* 1: the 32-bit keys of the epoch order are generated by host threads into

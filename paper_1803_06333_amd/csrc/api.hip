@@ -156,6 +156,8 @@ static void destroy(snap_handle* h) {
 struct CreatePass {
     uint32_t* freq;
     int64_t minor;
+    GroupSearch* search;       // streamed data: the search for groups rides on this pass (else null)
+    const int64_t* hptr;
 };
 
 static int create_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void* arg) {
@@ -169,7 +171,9 @@ static int create_chunk(snap_handle* h, int64_t chunk, const ChunkView& cv, void
         hipLaunchKernelGGL(k_check_unit_values, dim3(4096), dim3(256), 0, h->compute, cv.val, count, h->status);
     SNAP_HIP(hipGetLastError());
     if (!h->dense && cp->freq) SNAP_TRY(count_accesses_chunk(h, cv, count, cp->freq));
-    return norms_and_classes_chunk(h, cv);
+    SNAP_TRY(norms_and_classes_chunk(h, cv));
+    if (cp->search) SNAP_TRY(group_search_advance(h, cp->search, cp->hptr, cv.idx, cv.nnz_base, cv.c1));
+    return SNAP_OK;
 }
 
 // The library's own streams: one compute and one copy stream per device, created on first use and
@@ -346,7 +350,10 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     h->damping = h->opt.damping > 0.0f ? h->opt.damping : 1.0f;
     h->inflight_floor = WAVE;
     const bool auto_cap = h->opt.max_inflight_nnz <= 0 && !h->dense && !h->adaptive;
-    CreatePass cp{nullptr, h->form == SNAP_PRIMAL ? h->n : h->d};
+    CreatePass cp{nullptr, h->form == SNAP_PRIMAL ? h->n : h->d, nullptr, hptr.data()};
+    // streamed data: the search for groups is carried along by this pass, so that the data cross the host link once
+    const bool search_streamed = h->streaming && h->opt.n_groups == 0 && h->opt.auto_groups != 2 && h->form == SNAP_PRIMAL &&
+                                 m >= 2 && h->n >= 1 && h->nnz >= 1;
     if (auto_cap && h->vlen > 0) {
         SNAP_HIP(hipMalloc(&cp.freq, (size_t)h->vlen * sizeof(uint32_t)));
         const int rc = fill_zero(cp.freq, (size_t)h->vlen * sizeof(uint32_t), h->compute);
@@ -357,7 +364,10 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     }
     if (h->loss != SNAP_RIDGE && h->n > 0)
         hipLaunchKernelGGL(k_check_labels, dim3(1024), dim3(256), 0, h->compute, h->y, h->n, h->status);
-    int rc = for_each_chunk(h, create_chunk, &cp, /*fold=*/false, /*profile=*/false);
+    int rc = search_streamed ? group_search_begin(h, &cp.search) : SNAP_OK;
+    if (rc == SNAP_OK) rc = for_each_chunk(h, create_chunk, &cp, /*fold=*/false, /*profile=*/false);
+    std::vector<int64_t> gbounds;
+    if (rc == SNAP_OK && cp.search) rc = group_search_end(h, cp.search, hptr.data(), gbounds);
     uint32_t st = 0;
     if (rc == SNAP_OK) {
         hipError_t e = hipMemcpyAsync(&st, h->status, 4, hipMemcpyDeviceToHost, h->compute);
@@ -368,6 +378,7 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     if (rc == SNAP_OK && cp.freq && !(st & 1u)) rc = access_moments(h, cp.freq, &eff);
     (void)hipStreamSynchronize(h->compute);
     (void)hipFree(cp.freq);
+    group_search_free(cp.search);
     SNAP_TRY(rc);
     SNAP_TRY(fill_zero(h->status, 4, h->compute));
     if (st & 1u) {
@@ -389,9 +400,10 @@ static int build(snap_handle* h, const snap_matrix* A, const float* y) {
     SNAP_HIP(hipStreamSynchronize(h->compute));   // host vectors above go out of scope
 
     // ---- groups of coordinates with disjoint supports: given by the caller, or looked for ------------
-    std::vector<int64_t> gbounds;
     if (h->opt.n_groups > 0) gbounds.assign(h->opt.group_bounds, h->opt.group_bounds + h->opt.n_groups + 1);
-    else if (h->opt.auto_groups != 2) SNAP_TRY(detect_groups(h, hptr.data(), gbounds));
+    else if (h->streaming) {
+        if (!h->stream_unit) gbounds.clear();          // (streamed group sweeps take pattern-only data)
+    } else if (h->opt.auto_groups != 2) SNAP_TRY(detect_groups(h, hptr.data(), gbounds));
     if (h->opt.auto_groups == 1 && gbounds.empty()) {
         set_error("no partition of the coordinates into few ranges with disjoint supports was found");
         return SNAP_EUNSUPPORTED;

@@ -264,6 +264,12 @@ int read_status(snap_handle* h, uint32_t* st);      // the status word once the 
 // grouped.hip
 int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* bounds, int64_t n_groups);
 int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bounds);   // empty: nothing found
+// the same search piece by piece, for streamed data (advanced as the chunks pass through the device at creation)
+struct GroupSearch;
+int group_search_begin(snap_handle* h, GroupSearch** out);
+int group_search_advance(snap_handle* h, GroupSearch* s, const int64_t* hptr, const uint32_t* idx, int64_t nnz_base, int64_t c_limit);
+int group_search_end(snap_handle* h, GroupSearch* s, const int64_t* hptr, std::vector<int64_t>& bounds);
+void group_search_free(GroupSearch* s);
 int grouped_epoch(snap_handle* h);
 int grouped_dots(snap_handle* h);    // gdot[c] = inner product of coordinate c with loss'(v), by row passes
 std::vector<int64_t> group_order(uint64_t seed, int64_t n_groups);   // visiting order of the groups for a seed

@@ -338,13 +338,15 @@ void grouped_free(snap_handle* h) {
 // until the exact end of the range is known.  Tags of refused blocks stay behind and are ignored
 // (ok[] says which tags of the current range were accepted), so nothing is ever cleared and every
 // nonzero is visited about twice.
-__global__ void k_mark_rows(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, int64_t c0, int64_t c1,
-                            uint32_t tag, uint32_t tag_lo, const uint8_t* __restrict__ ok, uint32_t* __restrict__ tags,
-                            uint32_t* __restrict__ conflict) {
+__global__ void k_mark_rows(const int64_t* __restrict__ ptr, const uint32_t* __restrict__ idx, int64_t nnz_base, int64_t c0,
+                            int64_t c1, int64_t n, uint32_t tag, uint32_t tag_lo, const uint8_t* __restrict__ ok,
+                            uint32_t* __restrict__ tags, uint32_t* __restrict__ conflict) {
+    // (idx holds the nonzeros from nnz_base on; an index outside [0, n) is skipped here: creation reports it)
     const int64_t k0 = ptr[c0], k1 = ptr[c1];
     bool bad = false;
     for (int64_t k = k0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < k1; k += (int64_t)gridDim.x * blockDim.x) {
-        const uint32_t r = idx[k] & ~LABEL_BIT;
+        const uint32_t r = idx[k - nnz_base] & ~LABEL_BIT;
+        if ((int64_t)r >= n) continue;
         const uint32_t seen = tags[r];
         if (seen >= tag_lo && seen < tag && ok[seen - tag_lo]) {
             bad = true;                                   // the row belongs to the range already
@@ -355,88 +357,146 @@ __global__ void k_mark_rows(const int64_t* __restrict__ ptr, const uint32_t* __r
     if (bad) atomicOr(conflict, 1u);
 }
 
-// bounds: empty when the data have no such structure worth using (see the give-up rule below).
-int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bounds) {
-    bounds.clear();
-    const int64_t m = h->m, n = h->n;
-    if (h->form != SNAP_PRIMAL || h->dense || h->streaming || m < 2 || n < 1 || h->nnz < 1) return SNAP_OK;
-    constexpr int MAX_TESTS = 128;                        // per range: 2 log2(range length) is needed
+// The search as a state that can be advanced piece by piece: resident data in one go, streamed data chunk by
+// chunk as the chunks pass through the device during creation (a block of candidates never reaches beyond
+// the chunk at hand; the end of a range, the first coordinate that shares a row with an earlier one of the
+// range, does not depend on how the blocks were cut).
+struct GroupSearch {
+    static constexpr int MAX_TESTS = 128;                 // per range: 2 log2(range length) is needed
     uint32_t* tags = nullptr;
     uint32_t* conflict = nullptr;
     uint8_t* ok = nullptr;
     uint32_t* host_flag = nullptr;
-    SNAP_HIP(hipMalloc(&tags, (size_t)n * sizeof(uint32_t)));
-    auto done = [&](int rc) {
-        (void)hipFree(tags);
-        (void)hipFree(conflict);
-        (void)hipFree(ok);
-        (void)hipHostFree(host_flag);
-        return rc;
-    };
-#define D_HIP(call)                                                                \
-    do {                                                                           \
-        hipError_t e_ = (call);                                                    \
-        if (e_ != hipSuccess) return done(hip_fail(e_, #call, __FILE__, __LINE__)); \
-    } while (0)
-    D_HIP(hipMalloc(&conflict, sizeof(uint32_t)));
-    D_HIP(hipMalloc(&ok, MAX_TESTS));
-    D_HIP(hipHostMalloc(&host_flag, sizeof(uint32_t)));
-    int rc = fill_zero(tags, (size_t)n * sizeof(uint32_t), h->compute);
-    if (rc != SNAP_OK) return done(rc);
     uint8_t ok_host[MAX_TESTS];
-    uint32_t tag = 1;                                     // 0: never marked
+    uint32_t tag = 1, tag_lo = 1;                         // 0: never marked
+    int tests = 0;
+    int64_t start = 0, end = 0, step = 1;
+    bool refused = false, gave_up = false;
     std::vector<int64_t> gb{0};
-    int64_t start = 0;
-    while (start < m) {
-        // one range [start, end)
-        const uint32_t tag_lo = tag;
-        int tests = 0;
-        memset(ok_host, 0, sizeof(ok_host));
-        D_HIP(hipMemsetAsync(ok, 0, MAX_TESTS, h->compute));
-        int64_t end = start, step = 1;
-        bool refused = false;
-        while (end < m && step > 0 && tests < MAX_TESTS) {
-            const int64_t to = std::min(m, end + step);
-            bool good = true;
-            if (hptr[to] > hptr[end]) {
-                const int64_t cnt = hptr[to] - hptr[end];
-                const int grid = (int)std::min<int64_t>((cnt + 255) / 256, 16384);
-                D_HIP(hipMemsetAsync(conflict, 0, sizeof(uint32_t), h->compute));
-                hipLaunchKernelGGL(k_mark_rows, dim3(grid), dim3(256), 0, h->compute, h->ptr, h->idx, end, to, tag, tag_lo,
-                                   ok, tags, conflict);
-                D_HIP(hipMemcpyAsync(host_flag, conflict, sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
-                D_HIP(hipStreamSynchronize(h->compute));
-                good = *host_flag == 0;
-                if (good) {
-                    ok_host[tag - tag_lo] = 1;
-                    D_HIP(hipMemcpyAsync(ok + (tag - tag_lo), ok_host + (tag - tag_lo), 1, hipMemcpyHostToDevice, h->compute));
-                }
-                ++tag;
-                ++tests;
-            }
-            if (good) {
-                end = to;
-                step = refused ? step / 2 : step * 2;
-            } else {
-                refused = true;
-                step /= 2;
-            }
-        }
-        if (end == start) return done(SNAP_OK);           // a coordinate with a repeated row: no structure to use
-        gb.push_back(end);
-        start = end;
-        // give up early on data without such structure: a range pays one pass over all rows, which is
-        // only worth it when the range holds a good fraction of a nonzero per row
-        const double covered = (double)hptr[end] / (double)n;
-        if ((double)(gb.size() - 1) > 8.0 + 10.0 * covered) return done(SNAP_OK);
+};
+
+void group_search_free(GroupSearch* s) {
+    if (!s) return;
+    (void)hipFree(s->tags);
+    (void)hipFree(s->conflict);
+    (void)hipFree(s->ok);
+    (void)hipHostFree(s->host_flag);
+    delete s;
+}
+
+static int search_open_range(snap_handle* h, GroupSearch& s) {
+    s.tag_lo = s.tag;
+    s.tests = 0;
+    memset(s.ok_host, 0, sizeof(s.ok_host));
+    SNAP_HIP(hipMemsetAsync(s.ok, 0, GroupSearch::MAX_TESTS, h->compute));
+    s.end = s.start;
+    s.step = 1;
+    s.refused = false;
+    return SNAP_OK;
+}
+
+int group_search_begin(snap_handle* h, GroupSearch** out) {
+    *out = nullptr;
+    GroupSearch* s = new (std::nothrow) GroupSearch();
+    if (!s) return SNAP_ENOMEM;
+    *out = s;                                             // (freed by the caller, also after a failure below)
+    SNAP_HIP(hipMalloc(&s->tags, (size_t)(h->n ? h->n : 1) * sizeof(uint32_t)));
+    SNAP_HIP(hipMalloc(&s->conflict, sizeof(uint32_t)));
+    SNAP_HIP(hipMalloc(&s->ok, GroupSearch::MAX_TESTS));
+    SNAP_HIP(hipHostMalloc(&s->host_flag, sizeof(uint32_t)));
+    SNAP_TRY(fill_zero(s->tags, (size_t)h->n * sizeof(uint32_t), h->compute));
+    return search_open_range(h, *s);
+}
+
+// The range under way is complete: note its end, apply the give-up rule, open the next one.
+static int search_close_range(snap_handle* h, GroupSearch& s, const int64_t* hptr) {
+    if (s.end == s.start) {                               // a coordinate with a repeated row: no structure to use
+        s.gave_up = true;
+        return SNAP_OK;
     }
+    s.gb.push_back(s.end);
+    s.start = s.end;
+    // give up early on data without such structure: a range pays one pass over all rows, which is
+    // only worth it when the range holds a good fraction of a nonzero per row
+    const double covered = (double)hptr[s.end] / (double)h->n;
+    if ((double)(s.gb.size() - 1) > 8.0 + 10.0 * covered) {
+        s.gave_up = true;
+        return SNAP_OK;
+    }
+    return search_open_range(h, s);
+}
+
+// Advance over the coordinates up to c_limit, whose nonzeros sit in idx (from nnz_base on).
+int group_search_advance(snap_handle* h, GroupSearch* sp, const int64_t* hptr, const uint32_t* idx, int64_t nnz_base,
+                         int64_t c_limit) {
+    GroupSearch& s = *sp;
+    while (!s.gave_up && s.end < c_limit) {
+        if (s.step == 0 || s.tests >= GroupSearch::MAX_TESTS) {
+            SNAP_TRY(search_close_range(h, s, hptr));
+            continue;
+        }
+        const int64_t to = std::min(c_limit, s.end + s.step);
+        bool good = true;
+        if (hptr[to] > hptr[s.end]) {
+            const int64_t cnt = hptr[to] - hptr[s.end];
+            const int grid = (int)std::min<int64_t>((cnt + 255) / 256, 16384);
+            SNAP_HIP(hipMemsetAsync(s.conflict, 0, sizeof(uint32_t), h->compute));
+            hipLaunchKernelGGL(k_mark_rows, dim3(grid), dim3(256), 0, h->compute, h->ptr, idx, nnz_base, s.end, to, h->n, s.tag,
+                               s.tag_lo, s.ok, s.tags, s.conflict);
+            SNAP_HIP(hipMemcpyAsync(s.host_flag, s.conflict, sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+            SNAP_HIP(hipStreamSynchronize(h->compute));
+            good = *s.host_flag == 0;
+            if (good) {
+                s.ok_host[s.tag - s.tag_lo] = 1;
+                SNAP_HIP(hipMemcpyAsync(s.ok + (s.tag - s.tag_lo), s.ok_host + (s.tag - s.tag_lo), 1, hipMemcpyHostToDevice,
+                                        h->compute));
+            }
+            ++s.tag;
+            ++s.tests;
+        }
+        if (good) {
+            s.end = to;
+            s.step = s.refused ? s.step / 2 : s.step * 2;
+        } else {
+            s.refused = true;
+            s.step /= 2;
+        }
+    }
+    return SNAP_OK;
+}
+
+// After the last coordinate: the ranges found, or nothing when the search gave up.
+int group_search_end(snap_handle* h, GroupSearch* sp, const int64_t* hptr, std::vector<int64_t>& bounds) {
+    GroupSearch& s = *sp;
+    bounds.clear();
+    SNAP_HIP(hipStreamSynchronize(h->compute));
+    if (!s.gave_up && s.gb.back() != h->m) {
+        s.end = h->m;
+        SNAP_TRY(search_close_range(h, s, hptr));
+        SNAP_HIP(hipStreamSynchronize(h->compute));
+    }
+    if (!s.gave_up) bounds = s.gb;
+    return SNAP_OK;
+}
+
+// bounds: empty when the data have no such structure worth using (see the give-up rule above).
+int detect_groups(snap_handle* h, const int64_t* hptr, std::vector<int64_t>& bounds) {
+    bounds.clear();
+    const int64_t m = h->m, n = h->n;
+    if (h->form != SNAP_PRIMAL || h->dense || h->streaming || m < 2 || n < 1 || h->nnz < 1) return SNAP_OK;
+    GroupSearch* s = nullptr;
+    int rc = group_search_begin(h, &s);
+    if (rc == SNAP_OK) rc = group_search_advance(h, s, hptr, h->idx, 0, m);
+    if (rc == SNAP_OK) rc = group_search_end(h, s, hptr, bounds);
+    (void)hipStreamSynchronize(h->compute);
+    group_search_free(s);
+    SNAP_TRY(rc);
+    if (bounds.empty()) return SNAP_OK;
     size_t free_b = 0, total_b = 0;
-    D_HIP(hipMemGetInfo(&free_b, &total_b));
+    SNAP_HIP(hipMemGetInfo(&free_b, &total_b));
     const size_t n_pad = (size_t)((n + 7) / 8 * 8);
-    if ((gb.size() - 1) * n_pad * 6 > free_b / 2) return done(SNAP_OK);      // the row maps would not fit comfortably
-#undef D_HIP
-    bounds = gb;
-    return done(SNAP_OK);
+    if ((bounds.size() - 1) * n_pad * 6 > free_b / 2) bounds.clear();      // the row maps would not fit comfortably
+    return SNAP_OK;
 }
 
 static int cold_setup(snap_handle* h, const int64_t* hptr, const std::vector<uint32_t>& coord_of);
@@ -558,7 +618,14 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
             h->n_groups = 0;
             return SNAP_OK;
         }
-        SNAP_TRY(streamed_setup(h, hptr, coord_of));
+        const int rc = streamed_setup(h, hptr, coord_of);
+        if (rc == SNAP_ENOMEM && h->gmaps_host == nullptr && h->gring[0] == nullptr) {   // no pinned memory for the maps
+            grouped_free(h);
+            h->n_groups = 0;
+            h->gstream = false;
+            return SNAP_OK;                              // declined: asynchronous engine on streamed column chunks
+        }
+        SNAP_TRY(rc);
         h->grouped = true;
         return SNAP_OK;
     }
@@ -924,7 +991,14 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
         h->gmap_off_host[g + 1] = h->gmap_off_host[g] + (sz == 0 ? 0 : bytes);
     }
     h->gmap_bytes_per_pass = h->gmap_off_host[G];
-    SNAP_HIP(hipHostMalloc(&h->gmaps_host, (size_t)std::max<int64_t>(h->gmap_off_host[G], 8), hipHostMallocDefault));
+    const bool refuse = getenv("SNAP_NO_PINNED_MAPS") != nullptr;      // (test hook: behave as if the allocation had failed)
+    if (refuse || hipHostMalloc(&h->gmaps_host, (size_t)std::max<int64_t>(h->gmap_off_host[G], 8), hipHostMallocDefault) != hipSuccess) {
+        // pinned host memory is a limited resource (the caller's matrix sits in it too): without room for
+        // the maps the group sweeps are declined and the handle streams column chunks instead
+        (void)hipGetLastError();
+        h->gmaps_host = nullptr;
+        return SNAP_ENOMEM;
+    }
     for (int b = 0; b < 3; ++b) {
         SNAP_HIP(hipMalloc(&h->gring[b], (size_t)n_esc * sizeof(MAPT)));
         if (land_bytes > 0) SNAP_HIP(hipMalloc(&h->gring8[b], (size_t)land_bytes));

@@ -230,7 +230,7 @@ def test_config5_streamed_full_size():
         assert rel(P_last, oracle.primal_objective(oracle.LOGISTIC, v, p.y.numpy(), x, p.lam)) <= 1e-5
 
     # (1) the asynchronous epoch on streamed column chunks
-    g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30, profile=True)
+    g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30, auto_groups=False, profile=True)
     bounds = g.chunk_bounds()
     ptr = p.ptr.numpy()
     assert len(bounds) - 1 >= 15 and bounds[0] == 0 and bounds[-1] == p.d
@@ -252,8 +252,20 @@ def test_config5_streamed_full_size():
     fields = starts + [p.d]
     g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30, group_bounds=fields, profile=True)
     assert g.chunk_bounds() == fields
+    # what crosses the host link per epoch: a byte per row for the 64-bin fields; for the categorical fields a byte per
+    # row, a count per 4096 rows and two bytes for every row whose column is not among the field's 254 longest
     n_pad = (p.n + 7) // 8 * 8
-    assert g.stream_bytes() == 13 * n_pad + 26 * 2 * n_pad   # a byte per row for the 64-bin fields, two for the others
+    n_esc = (n_pad + 4095) // 4096 * 4096
+    lengths, want = np.diff(ptr), 0
+    for a, b in zip(fields, fields[1:]):
+        if b - a <= 255:
+            want += n_pad
+        else:
+            escaped = int(np.sort(lengths[a:b])[::-1][254:].sum())
+            blob = (n_esc + 4 * (n_esc // 4096) + 2 * escaped + 7) // 8 * 8
+            assert 10 * blob <= 9 * 2 * n_pad
+            want += blob
+    assert g.stream_bytes() == want < 10.1e9
     g.epoch(0)
     P = [np.log(2.0), g.objective()]
     _, x = g.model()

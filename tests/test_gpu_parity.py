@@ -474,7 +474,7 @@ def test_streamed_epochs_match_oracle_and_resident(name, chunk_bytes, budget, un
     q = _pinned(p)
     A = oracle.Matrix.from_problem(p)
     y = p.y.numpy()
-    g = snap.Solver.from_problem(q, device_budget_bytes=budget, chunk_bytes=chunk_bytes, profile=True)
+    g = snap.Solver.from_problem(q, device_budget_bytes=budget, chunk_bytes=chunk_bytes, auto_groups=False, profile=True)
     ptr = p.ptr.numpy()
     bounds = expected_chunks(ptr, chunk_bytes)           # the chunking rule, applied here to the same offsets
     assert g.chunk_bounds() == bounds
@@ -537,7 +537,7 @@ def test_profiling_a_streamed_epoch_copies_nothing_extra():
     q = _pinned(p)
     copied = []
     for profile in (False, True):
-        g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, profile=profile)
+        g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, auto_groups=False, profile=profile)
         C = len(g.chunk_bounds()) - 1
         assert C > 2
         g.epoch(0)
@@ -563,7 +563,7 @@ def test_chunk_gap_shares_match_the_oracle_streamed_and_grouped():
     p = problem("stream_uniform_logistic")
     q = _pinned(p)
     A = oracle.Matrix.from_problem(p)
-    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20)
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, auto_groups=False)
     bounds = g.chunk_bounds()
     o = oracle.Solver(A, p.y.numpy(), p.loss, p.lam, chunk_bounds=bounds)
     for e in range(3):
@@ -655,7 +655,7 @@ def test_streamed_pass_over_selected_chunks_and_the_selected_solve():
     q = _pinned(p)
     A = oracle.Matrix.from_problem(p)
     y = p.y.numpy()
-    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20)
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, auto_groups=False)
     bounds = g.chunk_bounds()
     C = len(bounds) - 1
     chunk_nnz = np.diff(p.ptr.numpy()[bounds])
@@ -684,7 +684,7 @@ def test_streamed_pass_over_selected_chunks_and_the_selected_solve():
     assert 0 < g.bytes_copied() - base <= 4 * (chunk_nnz[1] + chunk_nnz[3] + chunk_nnz[0] + chunk_nnz[1])
     g.close()
     # the selected solve ends at the same optimum as plain epochs, with fewer chunk visits per pass
-    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20)
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, auto_groups=False)
     target = oracle.solve(A, y, p.loss, p.lam, epochs=500, tol=1e-6, chunk_bounds=bounds).primal()
     passes, visits, gap = g.solve_selected(0, 400, 1e-5, 4, max(2, C // 2))
     assert gap <= 1e-5 and passes < 400
@@ -716,7 +716,7 @@ def test_keys_made_on_the_host_give_the_same_epoch_order():
     p = problem("stream_uniform_logistic")
     q = _pinned(p)
     A = oracle.Matrix.from_problem(p)
-    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, host_keys=True)
+    g = snap.Solver.from_problem(q, device_budget_bytes=2 << 20, chunk_bytes=1 << 20, auto_groups=False, host_keys=True)
     bounds = g.chunk_bounds()
     o = oracle.Solver(A, p.y.numpy(), p.loss, p.lam, chunk_bounds=bounds)
     for e in range(30):
@@ -951,6 +951,30 @@ def test_streamed_group_sweeps_escape_coded_row_maps(monkeypatch, row_wgs):
     r.close()
 
 
+def test_streamed_group_sweeps_are_declined_without_pinned_memory_for_the_maps(monkeypatch):
+    """The row maps need pinned host memory of the library's own; when that cannot be had (forced here), the
+    handle streams column chunks with the asynchronous engine instead of failing."""
+    monkeypatch.setenv("SNAP_NO_PINNED_MAPS", "1")
+    p = problem("stream_onehot_logistic")
+    groups = p.meta["field_starts"] + [p.d]
+    g = snap.Solver.from_problem(_pinned(p), device_budget_bytes=4 << 20, chunk_bytes=5 << 20, group_bounds=groups)
+    bounds = g.chunk_bounds()
+    assert bounds == expected_chunks(p.ptr.numpy(), 5 << 20) and g.stream_bytes() == 4 * p.nnz
+    P0 = g.objective()
+    for e in range(10):
+        g.epoch(e)
+    assert g.objective() < 0.8 * P0
+    assert np.array_equal(g.perm().astype(np.int64),
+                          executed_order(_chunked_perm(9, bounds), np.diff(p.ptr.numpy()), bounds=bounds))
+    g.close()
+
+
+def _chunked_perm(seed, bounds):
+    """The oracle's permutation chunk by chunk (absolute coordinate numbers)."""
+    return np.concatenate([oracle.permutation(seed, b - a, chunk=k).astype(np.int64) + a
+                           for k, (a, b) in enumerate(zip(bounds, bounds[1:]))])
+
+
 def test_streamed_group_sweeps_wide_group_and_error_paths(monkeypatch):
     # a field with more than 65535 categories: 4-byte row maps through the ring
     monkeypatch.setenv("SNAP_ROW_WGS", "16")
@@ -1025,8 +1049,8 @@ def test_pattern_only_matrix_without_a_value_array():
     assert relnorm(b.model()[1], a.model()[1].astype(np.float64)) <= 1e-6
     a.close()
     b.close()
-    s = snap.Solver.from_problem(_pinned_some(q), device_budget_bytes=1 << 20, chunk_bytes=4 << 20)
-    t = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, chunk_bytes=4 << 20)
+    s = snap.Solver.from_problem(_pinned_some(q), device_budget_bytes=1 << 20, chunk_bytes=4 << 20, auto_groups=False)
+    t = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, chunk_bytes=4 << 20, auto_groups=False)
     assert s.stream_bytes() == t.stream_bytes() == 4 * p.nnz and s.epoch_stats()["unit_values"] == 1
     assert s.objective() == t.objective() and s.duality_gap() == t.duality_gap()
     for e in range(20):
@@ -1553,6 +1577,43 @@ def test_auto_groups_merges_what_can_be_merged_and_handles_empty_columns():
         o.epoch(e)
     assert relnorm(g.model()[1], o.x) <= 2e-5
     g.close()
+
+
+def test_auto_groups_on_streamed_data_rides_on_the_creation_pass():
+    """Streamed pattern-only data: the search is advanced chunk by chunk while the creation pass has each chunk
+    on the device (several chunks per field and several fields per chunk here), finds the same fields and
+    the sweeps equal those with the fields given; the search copies nothing of its own over the host link."""
+    p = _onehot_variant("logistic", True)
+    fields = p.meta["field_starts"] + [p.d]
+    ref = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, chunk_bytes=1 << 19, group_bounds=fields)
+    g = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, chunk_bytes=1 << 19)        # default: search
+    assert g.chunk_bounds() == fields and g.stream_bytes() == ref.stream_bytes()
+    assert g.bytes_copied() == ref.bytes_copied()
+    for e in range(3):
+        g.epoch(e)
+        ref.epoch(e)
+        assert np.array_equal(g.model()[1], ref.model()[1]) and np.array_equal(g.shared(), ref.shared())
+    assert g.epoch_stats()["rejected"] == 0 and g.epoch_stats()["unit_values"] == 1
+    g.close()
+    ref.close()
+    # values other than 1: streamed maps do not apply; by default the asynchronous streamed epoch runs, on request an error
+    q = _onehot_variant("logistic", False)
+    g = snap.Solver.from_problem(_pinned(q), device_budget_bytes=1 << 20, chunk_bytes=1 << 19)
+    b = g.chunk_bounds()
+    g.epoch(0)
+    st = g.epoch_stats()
+    assert b != fields and st["n_chunks"] == len(b) - 1 > 2 and st["unit_values"] == 0 and g.stream_bytes() == 8 * q.nnz
+    g.close()
+    with pytest.raises(snap.SnapError) as e:
+        snap.Solver.from_problem(_pinned(q), device_budget_bytes=1 << 20, chunk_bytes=1 << 19, auto_groups=True)
+    assert e.value.code == -2
+    # data without such structure: the search gives up during the pass, nothing else changes
+    u = problem("stream_uniform_logistic")
+    g = snap.Solver.from_problem(_pinned(u), device_budget_bytes=2 << 20, chunk_bytes=1 << 20)
+    a = snap.Solver.from_problem(_pinned(u), device_budget_bytes=2 << 20, chunk_bytes=1 << 20, auto_groups=False)
+    assert g.chunk_bounds() == a.chunk_bounds() and g.stream_bytes() == a.stream_bytes()
+    g.close()
+    a.close()
 
 
 def test_auto_groups_gives_up_on_unstructured_data():
