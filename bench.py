@@ -421,6 +421,18 @@ def main():
     }
     out.update(res)
 
+    # ---- what bare streaming kernels reach on this device, beside the dominant kernel's figure ---------
+    if mode == "groups" and out["roofline"].get("achieved"):
+        n_rows = p.n
+        bare = {}
+        for kind, name, per_row in ((0, "read_only", 4), (1, "copy", 8), (2, "row_pass_mix", 12)):
+            us = snap.stream_probe(kind, n_rows, 40)
+            bare[name + "_GBps"] = round(per_row * n_rows / (us * 1e-6) / 1e9, 1)
+        bare["achieved_over_row_pass_mix"] = round(out["roofline"]["achieved"] / bare["row_pass_mix_GBps"], 3)
+        bare["note"] = "bare kernels over as many rows (snap_stream_probe): a read of 4 B per row, a copy (4 in, 4 out), and " \
+                       "the row pass's mix with two-byte maps (4 + 2 + 2 in, 4 out) that does nothing else; best launch shape each"
+        out["roofline"]["bare_kernels"] = bare
+
     # ---- the accept check on top of the group sweeps: what it costs (config 4, auto) ------------------
     if args.mode == "auto" and cfg == 4:
         gc_ = snap.Solver.from_problem(p, adaptive=True, **kw)

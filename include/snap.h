@@ -234,6 +234,17 @@ int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
  * serialised by the caller.  Synchronises. */
 int snap_predict_static(snap_handle *h, const snap_matrix *X, float *out);
 
+/* A measurement aid beside the method (no handle, no paper passage): the time of one pass of a bare
+ * streaming kernel over `rows` rows of zeros in device memory that the call allocates and frees, to
+ * set the row pass of the group sweeps beside what the memory system of this device delivers.
+ * kind 0: read 4 bytes per row; 1: copy (read 4, write 4); 2: the row pass's mix with two-byte row
+ * maps (read 4 + 2 + 2, write 4 bytes per row, arrays alternated from pass to pass as the sweeps
+ * alternate them).  Each of two or three launch shapes is run three times over `passes` passes on
+ * `stream` (NULL: the default stream), the first time as a warm-up; *us_per_pass receives the best
+ * average in microseconds.  SNAP_EINVAL for kind outside 0..2, rows outside 1..2^32, passes outside
+ * 1..1000.  Synchronises. */
+int snap_stream_probe(int kind, int64_t rows, int passes, void *stream, double *us_per_pass);
+
 /* The model of eq. (1) / Algorithm 1: w (n_cols floats, may be NULL; in the dual form w = v / (lambda n))
  * and the coordinate vector alpha of eq. (1) (w in primal form, alpha in dual form; m floats, may be
  * NULL), to host memory. */

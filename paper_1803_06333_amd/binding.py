@@ -27,7 +27,7 @@ EXPORTS = ["snap_create", "snap_epoch", "snap_objective", "snap_duality_gap", "s
            "snap_set_model", "snap_get_shared", "snap_recompute_shared", "snap_get_perm", "snap_get_epoch_stats",
            "snap_get_dims", "snap_get_chunks", "snap_get_stream_bytes", "snap_solve", "snap_perm_key", "snap_block_order",
            "snap_epoch_chunks", "snap_chunk_gaps", "snap_solve_selected", "snap_get_bytes_copied", "snap_last_error",
-           "snap_destroy", "snap_predict_static"]
+           "snap_destroy", "snap_predict_static", "snap_stream_probe"]
 
 
 class SnapMatrix(C.Structure):
@@ -97,6 +97,7 @@ def load_library():
         L.snap_perm_key.restype = C.c_uint32
         L.snap_perm_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
         L.snap_block_order.argtypes = [C.c_uint64, C.c_int64, C.c_void_p]
+        L.snap_stream_probe.argtypes = [C.c_int, C.c_int64, C.c_int, C.c_void_p, C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -145,6 +146,13 @@ def block_order(seed: int, n_blocks: int) -> list:
     out = np.empty(max(n_blocks, 1), dtype=np.int64)
     _check(load_library().snap_block_order(seed, n_blocks, out.ctypes.data))
     return out[:n_blocks].tolist()
+
+
+def stream_probe(kind: int, rows: int, passes: int = 40) -> float:
+    """snap_stream_probe: microseconds per pass of a bare streaming kernel (0 read, 1 copy, 2 the row pass's mix)."""
+    us = C.c_double()
+    _check(load_library().snap_stream_probe(kind, rows, passes, None, C.byref(us)))
+    return us.value
 
 
 class Solver:

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC_DIR = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libsnap.so")
-SOURCES = ["api.hip", "perm.hip", "scd.hip", "linalg.hip", "stream.hip", "grouped.hip", "dense_tiles.hip"]
+SOURCES = ["api.hip", "perm.hip", "scd.hip", "linalg.hip", "stream.hip", "grouped.hip", "dense_tiles.hip", "probe.hip"]
 
 
 def build(verbose: bool = False, out: str = LIB_PATH, defines=()) -> str:

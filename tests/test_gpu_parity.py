@@ -1760,3 +1760,18 @@ def test_group_sweeps_are_declined_when_lambda_n_is_below_their_resolution():
         o.epoch(e)
     assert relnorm(g.model()[1], o.x) <= 2e-5
     g.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# the measurement aid: bare streaming kernels
+def test_stream_probe_reports_plausible_times_and_rejects_bad_arguments():
+    rows = 8_000_000
+    for kind, per_row in ((0, 4), (1, 8), (2, 12)):
+        us = snap.stream_probe(kind, rows, 10)
+        tbps = per_row * rows / (us * 1e-6) / 1e12
+        assert 0.3 < tbps < 20.0, (kind, us)             # (small arrays may be served by the caches: above the HBM peak)
+    assert snap.stream_probe(2, 1001, 2) > 0             # ragged size
+    for bad in ((3, 100, 1), (-1, 100, 1), (0, 0, 1), (0, 100, 0), (0, 100, 1001), (0, (1 << 32) + 1, 1)):
+        with pytest.raises(snap.SnapError) as e:
+            snap.stream_probe(*bad)
+        assert e.value.code == -1
