@@ -107,11 +107,14 @@ def roofline_of(cfg, mode, p, nnz, m, dense, st, kms, ms_per_step, scale):
     if mode == "groups":
         # a row pass between two fields: map entry of the previous and of the current field, v in, v out,
         # one label bit (logistic), the two value arrays only when the values are not all 1
-        mb, unit = st["row_map_bytes"], bool(st["unit_values"])
+        unit = bool(st["unit_values"])
         lab = 0.125 if p.loss == "logistic" else 4.0
-        per_row = 2 * mb + 8 + lab + (0 if unit else 8)
         passes = max(1, st["n_items"])
         G = st["n_chunks"]
+        # bytes per map entry, averaged over the groups (groups of at most 255 columns are read as bytes); a pass
+        # reads the maps of two groups that the epoch's random order puts next to each other
+        mb = (st["row_map_bytes"] * (G - st["byte_map_groups"]) + st["byte_map_groups"]) / max(1, G)
+        per_row = 2 * mb + 8 + lab + (0 if unit else 8)
         dom, dom_ms, dom_bytes = "k_group_rows", kms["large_ms"] / passes, per_row * n
         if cfg == 5:
             # streamed row maps: the kernels of a visit (row pass, step kernel, widening of a byte map) are
@@ -122,7 +125,7 @@ def roofline_of(cfg, mode, p, nnz, m, dense, st, kms, ms_per_step, scale):
         # by G + 1 passes and written by G, labels by the G passes that take sums
         fmt_epoch = n * (2 * G * mb + 4 * (2 * G + 1) + G * lab + (0 if unit else 8 * G)) + 24 * m
         compulsory = n * (G * mb + lab + (0 if unit else 4 * G))
-        extra["bytes_per_row_of_a_pass"] = {"row_map_prev": mb, "row_map_cur": mb, "v_read": 4, "v_write": 4,
+        extra["bytes_per_row_of_a_pass"] = {"row_map_prev": round(mb, 4), "row_map_cur": round(mb, 4), "v_read": 4, "v_write": 4,
                                             "label": lab, "values": 0 if unit else 8}
     elif mode == "tiles":
         # one pass reads the columns of two tiles (write-back of one, inner products of the next) and
@@ -271,7 +274,8 @@ def run_config(cfg, mode, steps, warmup, args, mods, want_gap=True, keep_problem
         out["groups"] = {"n_groups": st["n_chunks"], "row_passes_per_epoch": st["n_items"],
                          "hot_coordinates": st["n_large"], "hot_nnz": st["nnz_large"],
                          "cold_coordinates": st["n_small"], "cold_nnz": st["nnz_small"],
-                         "row_map_bytes": st["row_map_bytes"], "unit_values": bool(st["unit_values"])}
+                         "row_map_bytes": st["row_map_bytes"], "byte_map_groups": st["byte_map_groups"],
+                         "unit_values": bool(st["unit_values"])}
         out["epoch_contents"] = "row passes and step kernels of all fields; no permutation (the order inside a field " \
                                 "does not change the result) and no accept check (nothing is asynchronous)"
     else:

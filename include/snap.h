@@ -179,6 +179,8 @@ typedef struct {
     int64_t nnz_small;     /* nonzeros of the wavefront-per-coordinate class */
     int row_map_bytes;     /* group sweeps: bytes per entry of a row map (1, 2 or 4); 0 without groups */
     int unit_values;       /* group sweeps / streaming: 1 when every stored value is 1.0 (no value arrays are read) */
+    int byte_map_groups;   /* group sweeps on resident data: how many groups (those of at most 255 coordinates) have their
+                              row map read as one byte per row instead of row_map_bytes */
 } snap_epoch_stats;
 
 /* Section 1 eq. (1) / Section 3.1.  Builds the solver state for X (A), y, loss and lambda:
@@ -235,11 +237,11 @@ int snap_predict(snap_handle *h, const snap_matrix *X, float *out);
 int snap_predict_static(snap_handle *h, const snap_matrix *X, float *out);
 
 /* A measurement aid beside the method (no handle, no paper passage): the time of one pass of a bare
- * streaming kernel over `rows` rows of zeros in device memory that the call allocates and frees, to
+ * streaming kernel over `rows` rows of pattern data in device memory that the call allocates and frees, to
  * set the row pass of the group sweeps beside what the memory system of this device delivers.
  * kind 0: read 4 bytes per row; 1: copy (read 4, write 4); 2: the row pass's mix with two-byte row
- * maps (read 4 + 2 + 2, write 4 bytes per row, arrays alternated from pass to pass as the sweeps
- * alternate them).  Each of two or three launch shapes is run three times over `passes` passes on
+ * maps (read 4 + 2 + 2, write 4 bytes per row; rows walked, vector updated in place and maps
+ * alternated from pass to pass as the sweeps do).  Each of two or three variants is run three times over `passes` passes on
  * `stream` (NULL: the default stream), the first time as a warm-up; *us_per_pass receives the best
  * average in microseconds.  SNAP_EINVAL for kind outside 0..2, rows outside 1..2^32, passes outside
  * 1..1000.  Synchronises. */

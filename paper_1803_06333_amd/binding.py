@@ -48,7 +48,7 @@ class SnapEpochStats(C.Structure):
                 ("n_chunks", C.c_int64), ("n_small", C.c_int64), ("n_large", C.c_int64), ("n_items", C.c_int64),
                 ("inflight_nnz", C.c_int64), ("damping", C.c_float), ("rejected", C.c_int),
                 ("large_ms", C.c_float), ("small_ms", C.c_float), ("nnz_large", C.c_int64), ("nnz_small", C.c_int64),
-                ("row_map_bytes", C.c_int), ("unit_values", C.c_int)]
+                ("row_map_bytes", C.c_int), ("unit_values", C.c_int), ("byte_map_groups", C.c_int)]
 
 
 class SnapError(RuntimeError):

@@ -1005,6 +1005,7 @@ int snap_get_epoch_stats(snap_handle* h, snap_epoch_stats* out) {
         h->stats.n_items = h->n_row_passes;
     }
     h->stats.row_map_bytes = h->grouped ? (h->map16 ? 2 : 4) : 0;
+    h->stats.byte_map_groups = h->grouped ? h->n_byte_maps : 0;
     h->stats.unit_values = (h->grouped ? h->unit_values : h->stream_unit) ? 1 : 0;
     *out = h->stats;
     return SNAP_OK;

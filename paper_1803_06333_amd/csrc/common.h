@@ -162,6 +162,9 @@ struct snap_handle {
     int g_row_wgs = 0, g_kd_max = 0;  // workgroups of a row pass; steps of the previous group kept in LDS
     void* rowmap = nullptr;           // [n_groups][n_pad]: rank of the row's coordinate in the group (uint16 or uint32)
     bool map16 = true;
+    uint8_t* rowmap8 = nullptr;       // resident 16-bit maps: byte copies of the maps of groups with at most 255 coordinates
+    int* g8slot_host = nullptr;       // [n_groups] which of them (-1: the group has none)
+    int n_byte_maps = 0;
     uint8_t* ybits = nullptr;         // bit r = 1 when y[r] < 0
     float* rowval = nullptr;          // [n_groups][n_pad] values (null when unit_values)
     uint32_t* rank_of = nullptr;      // [m] rank of a coordinate inside its group (by decreasing length)

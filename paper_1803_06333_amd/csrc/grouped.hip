@@ -29,6 +29,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <numeric>
+#include <type_traits>
 #include <vector>
 
 namespace snap {
@@ -79,7 +80,7 @@ static bool pack_knob() {
     return !(e && e[0] == '0');
 }
 static bool map8_knob() {
-    const char* e = getenv("SNAP_MAP8");             // 0: streamed row maps never travel as bytes
+    const char* e = getenv("SNAP_MAP8");             // 0: no byte maps (resident: read by the row passes; streamed: on the host link)
     return !(e && e[0] == '0');
 }
 static bool compact_knob() {
@@ -314,6 +315,11 @@ void grouped_free(snap_handle* h) {
     h->ghot_host = nullptr;
     h->gk64_host = nullptr;
     (void)hipFree(h->rowmap);
+    (void)hipFree(h->rowmap8);
+    h->rowmap8 = nullptr;
+    delete[] h->g8slot_host;
+    h->g8slot_host = nullptr;
+    h->n_byte_maps = 0;
     (void)hipFree(h->rowval);
     (void)hipFree(h->ybits);
     h->ybits = nullptr;
@@ -696,6 +702,21 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
         set_error("two coordinates of one group share a row: the groups are not disjoint");
         return SNAP_EINVAL;
     }
+    // groups of at most 255 coordinates: the row passes read their maps as bytes (a byte less per row and map)
+    h->g8slot_host = new (std::nothrow) int[(size_t)G];
+    if (!h->g8slot_host) return SNAP_ENOMEM;
+    for (int64_t g = 0; g < G; ++g) {
+        const int64_t sz = gb[g + 1] - gb[g];
+        h->g8slot_host[g] = (h->map16 && map8_knob() && sz > 0 && sz <= 255 && n > 0) ? h->n_byte_maps++ : -1;
+    }
+    if (h->n_byte_maps > 0) {
+        SNAP_HIP(hipMalloc(&h->rowmap8, (size_t)h->n_byte_maps * (size_t)h->n_pad));
+        for (int64_t g = 0; g < G; ++g)
+            if (h->g8slot_host[g] >= 0)
+                hipLaunchKernelGGL(k_map16_to_8, dim3(8192), dim3(256), 0, h->compute, (const uint16_t*)h->rowmap + (size_t)g * h->n_pad,
+                                   h->rowmap8 + (size_t)h->g8slot_host[g] * h->n_pad, (size_t)h->n_pad);
+        SNAP_HIP(hipGetLastError());
+    }
     rc = cold_setup(h, hptr, coord_of);
     if (rc != SNAP_OK) return rc;
     h->grouped = true;
@@ -706,9 +727,12 @@ int grouped_setup(snap_handle* h, const int64_t* hptr, const int64_t* gb, int64_
 // SCATTER: v[r] += delta_prev[rank] * a for the previous group.  HIST: sums of the current group's
 // hot ranks.  Every thread takes one 128-bit load of each map per iteration: 8 consecutive rows with
 // 16-bit maps, 4 with 32-bit maps.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <typename MAPT> struct MapTraits;
-template <> struct MapTraits<uint16_t> { static constexpr int R = 8; static constexpr uint32_t NONE = 0xFFFFu; };
-template <> struct MapTraits<uint32_t> { static constexpr int R = 4; static constexpr uint32_t NONE = 0xFFFFFFFFu; };
+template <> struct MapTraits<uint8_t> { static constexpr int R = 8; static constexpr uint32_t NONE = 0xFFu; typedef u32x2 Raw; };
+template <> struct MapTraits<uint16_t> { static constexpr int R = 8; static constexpr uint32_t NONE = 0xFFFFu; typedef u32x4 Raw; };
+template <> struct MapTraits<uint32_t> { static constexpr int R = 4; static constexpr uint32_t NONE = 0xFFFFFFFFu; typedef u32x4 Raw; };
 
 // Ridge terms a (v - y) have no a-priori bound and take the 64-bit conversion to fixed point.  With 24
 // fractional bits the 64-bit sum of a ridge coordinate has 2^39 of range: every term must stay below 2^14
@@ -716,9 +740,15 @@ template <> struct MapTraits<uint32_t> { static constexpr int R = 4; static cons
 constexpr float RIDGE_TERM_LIMIT = 16384.0f;
 
 // One 128-bit load of map entries (non-temporal: the maps are read once per pass and should not push the
-// shared vector out of the last-level cache), and its unpacking into ranks.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ u32x4 load_map(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+// shared vector out of the last-level cache; the shared vector itself is read with plain loads: with the
+// hint on those too the pass was measured 12 % slower), and its unpacking into ranks.
+__device__ __forceinline__ u32x4 load_map(const uint16_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+__device__ __forceinline__ u32x4 load_map(const uint32_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+__device__ __forceinline__ u32x2 load_map(const uint8_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p)); }
+__device__ __forceinline__ void unpack_ranks(const uint8_t*, u32x2 u, uint32_t (&out)[8]) {
+    out[0] = u.x & 0xFFu; out[1] = u.x >> 8 & 0xFFu; out[2] = u.x >> 16 & 0xFFu; out[3] = u.x >> 24;
+    out[4] = u.y & 0xFFu; out[5] = u.y >> 8 & 0xFFu; out[6] = u.y >> 16 & 0xFFu; out[7] = u.y >> 24;
+}
 __device__ __forceinline__ void unpack_ranks(const uint16_t*, u32x4 u, uint32_t (&out)[8]) {
     out[0] = u.x & 0xFFFFu; out[1] = u.x >> 16; out[2] = u.y & 0xFFFFu; out[3] = u.y >> 16;
     out[4] = u.z & 0xFFFFu; out[5] = u.z >> 16; out[6] = u.w & 0xFFFFu; out[7] = u.w >> 16;
@@ -762,10 +792,8 @@ k_cold_rows(const MAPT* __restrict__ map, int hot, int64_t n, uint32_t* __restri
     constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
     const int wave = (int)blockIdx.x * (ROW_TPB / WAVE) + (int)threadIdx.x / WAVE;
     uint32_t run = WRITE ? slots[wave] : 0u;
-    const int64_t packs = (n + R - 1) / R;                     // (the same split of the rows as in the row pass)
-    const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
-    const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
-    for (int64_t q = q0 + threadIdx.x; q < q1; q += ROW_TPB) {
+    const int64_t packs = (n + R - 1) / R;                     // (the same walk over the rows as in the row pass)
+    for (int64_t q = (int64_t)blockIdx.x * ROW_TPB + threadIdx.x; q < packs; q += (int64_t)gridDim.x * ROW_TPB) {
         uint32_t mc[R];
         unpack_ranks(map, load_map(map + R * q), mc);
 #pragma unroll
@@ -1157,17 +1185,20 @@ constexpr unsigned long long FIX_BIAS = 0x4B400000ull;   // its bit pattern
 // the epoch: the state before it then simply stays where it was, and the two arrays change roles).
 // LOSS (the last pass of such an epoch): the loss of every row at its final value is summed on the way,
 // per workgroup in a fixed order, so that the objective after the epoch costs one small reduction more.
-template <int KIND, bool UNIT, bool SCATTER, bool HIST, typename MAPT, bool LOSS = false>
+// MAPP, MAPC: entry types of the previous and of the current group's map (one byte for groups of at most
+// 255 coordinates; both take the same number of rows per thread and iteration).
+template <int KIND, bool UNIT, bool SCATTER, bool HIST, typename MAPP, typename MAPC, bool LOSS = false>
 __global__ void __launch_bounds__(ROW_TPB)
-k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_prev,
-             const float* __restrict__ delta_prev, const MAPT* __restrict__ map_cur,
+k_group_rows(const MAPP* __restrict__ map_prev, const float* __restrict__ val_prev,
+             const float* __restrict__ delta_prev, const MAPC* __restrict__ map_cur,
              const float* __restrict__ val_cur, int hot, int k64, const float* vin, float* vout, const float* __restrict__ y,
              const uint8_t* __restrict__ ybits, int64_t n, long long* __restrict__ partial, int64_t partial_stride,
              SumScales scale, int kd, uint32_t* __restrict__ status,
              float* __restrict__ cbuf, const uint32_t* __restrict__ wbase, double* __restrict__ loss_partial = nullptr,
              const float* __restrict__ model = nullptr, int64_t m = 0) {
-    constexpr int R = MapTraits<MAPT>::R;
-    constexpr uint32_t NONE = MapTraits<MAPT>::NONE;
+    constexpr int R = MapTraits<MAPC>::R;
+    static_assert(MapTraits<MAPP>::R == R, "both maps must give a thread the same rows");
+    constexpr uint32_t NONE_P = MapTraits<MAPP>::NONE, NONE_C = MapTraits<MAPC>::NONE;
     __shared__ double s_loss[LOSS ? 3 * (ROW_TPB / WAVE) : 1];
     double loss_acc = 0.0;
     // LDS: fixed-point sums.  Logistic: ranks below k64: [rank] sum of a loss' * scale.g, [k64 + rank]
@@ -1177,13 +1208,18 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
     // costs a third of the pass; nearly every row hits one of these).
     extern __shared__ unsigned long long hist[];
     float* dl = reinterpret_cast<float*>(hist + hot + k64);
+    // The workgroups walk the rows side by side: in iteration i workgroup b takes the ROW_TPB packs from
+    // (i * gridDim.x + b) * ROW_TPB on, so that at any time the whole grid works on one contiguous window of
+    // every array (measured with a bare kernel of the same byte mix: 5.65 TB/s, against 5.0 TB/s when every
+    // workgroup streams a slab of its own).
     const int64_t packs = (n + R - 1) / R;
-    const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
-    const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
+    const int64_t q_first = (int64_t)blockIdx.x * ROW_TPB + threadIdx.x, q_stride = (int64_t)gridDim.x * ROW_TPB;
     // All loads of an iteration are issued together, ahead of its first wait, and those of the first
-    // iteration ahead of the set-up of the LDS tables (the loop below asks for the next pack's at its end).
+    // iteration ahead of the set-up of the LDS tables (the loop below asks for the next pack's at its end;
+    // asking a whole iteration ahead, with two packs per thread in turn, was measured 3 % slower).
     float vv[R], ap[R], ac[R], yy[R];
-    u32x4 raw_prev = {0u, 0u, 0u, 0u}, raw_cur = {0u, 0u, 0u, 0u};
+    typename MapTraits<MAPP>::Raw raw_prev = {};
+    typename MapTraits<MAPC>::Raw raw_cur = {};
     uint32_t lab_byte = 0;
     auto request = [&](int64_t q) {
         const int64_t r = R * q;
@@ -1213,7 +1249,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             }
         }
     };
-    if (q0 + threadIdx.x < q1) request(q0 + threadIdx.x);
+    if (q_first < packs) request(q_first);
     if (HIST)
         for (int i = threadIdx.x; i < hot + k64; i += ROW_TPB) hist[i] = 0ull;
     if (SCATTER)
@@ -1229,7 +1265,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
     uint32_t cflushed = crun;
     float* stage = dl + kd + 1 + (threadIdx.x / WAVE) * COLD_RING;
     bool too_large = false;                    // ridge: a term outside the range the 64-bit sums are laid out for
-    for (int64_t q = q0 + threadIdx.x; q < q1;) {
+    for (int64_t q = q_first; q < packs;) {
         const int64_t r = R * q;
         uint32_t mp[R], mc[R];
         const bool full = r + R - 1 < n;
@@ -1250,7 +1286,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
             for (int j = 0; j < R; ++j) asm("" : "+v"(dv[j]));   // (keeps these LDS reads: merged with the global ones they turn into flat loads)
 #pragma unroll
             for (int j = 0; j < R; ++j)
-                if (mp[j] >= (uint32_t)kd && mp[j] != NONE) dv[j] = delta_prev[mp[j]];
+                if (mp[j] >= (uint32_t)kd && mp[j] != NONE_P) dv[j] = delta_prev[mp[j]];
 #pragma unroll
             for (int j = 0; j < R; ++j) vv[j] += dv[j] * (UNIT ? 1.0f : ap[j]);
             if (full) {
@@ -1307,7 +1343,7 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                 if (cbuf) {
                     // a row of a short coordinate: its entry goes to the buffer (ridge: minus the label,
                     // which the finishing kernel then need not gather either)
-                    const bool cold = !in && rk != NONE;
+                    const bool cold = !in && rk != NONE_C;
                     const uint32_t pos = cold_slot(cold, crun);
                     if (cold) stage[pos & (COLD_RING - 1)] = KIND == K_PRIMAL_LOGISTIC ? vv[j] : vv[j] - yy[j];
                     if (crun - cflushed >= (uint32_t)WAVE) {      // (uniform; at most 64 entries arrive per row step)
@@ -1344,8 +1380,8 @@ k_group_rows(const MAPT* __restrict__ map_prev, const float* __restrict__ val_pr
                 }
             }
         }
-        q += ROW_TPB;
-        if (q < q1) request(q);
+        q += q_stride;
+        if (q < packs) request(q);
     }
     if (HIST) {
         if (cbuf) {
@@ -1707,25 +1743,48 @@ static int grouped_epoch_kind(snap_handle* h) {
             // the first writing pass of an epoch that may be undone writes into the other array
             const float* vin = v_cur;
             float* vout = (scatter && keep_old && !swapped) ? h->v_snap : v_cur;
-            if (scatter && histo)
-                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, vin, vout, h->y,
-                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase, (double*)nullptr, (const float*)nullptr, (int64_t)0);
-            else if (scatter && last && h->g_want_loss) {
-                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT, true>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, vin, vout, h->y,
-                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
-                                      (const uint32_t*)nullptr, h->gloss_partial, (const float*)h->x, h->m);
-                loss_done = true;
-            } else if (scatter)
-                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, 0, 0, vin, vout, h->y,
-                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
-                                      (const uint32_t*)nullptr, (double*)nullptr, (const float*)nullptr, (int64_t)0);
-            else
-                hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), row_grid, dim3(ROW_TPB), lds, h->compute,
-                                      ev_a, ev_b, 0, map_prev, val_prev, delta_prev, map_cur, val_cur, hot, k64, vin, vout, h->y,
-                                      h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase, (double*)nullptr, (const float*)nullptr, (int64_t)0);
+            // byte maps where the group has one (resident 16-bit maps only); a pass that uses one map names its type twice
+            const int slot_p = (prev >= 0 && !streamed && h->g8slot_host) ? h->g8slot_host[prev] : -1;
+            const int slot_c = (!last && !streamed && h->g8slot_host) ? h->g8slot_host[g] : -1;
+            auto launch = [&](auto tag_p, auto tag_c) {
+                using MP = decltype(tag_p);
+                using MC = decltype(tag_c);
+                const MP* mp = std::is_same<MP, uint8_t>::value ? (const MP*)(h->rowmap8 + (size_t)std::max(slot_p, 0) * h->n_pad)
+                                                                : (const MP*)map_prev;
+                const MC* mc = std::is_same<MC, uint8_t>::value ? (const MC*)(h->rowmap8 + (size_t)std::max(slot_c, 0) * h->n_pad)
+                                                                : (const MC*)map_cur;
+                if (scatter && histo)
+                    hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, true, MP, MC>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                          ev_a, ev_b, 0, mp, val_prev, delta_prev, mc, val_cur, hot, k64, vin, vout, h->y,
+                                          h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase, (double*)nullptr,
+                                          (const float*)nullptr, (int64_t)0);
+                else if (scatter && last && h->g_want_loss) {
+                    hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MP, MP, true>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                          ev_a, ev_b, 0, mp, val_prev, delta_prev, (const MP*)nullptr, val_cur, 0, 0, vin, vout, h->y,
+                                          h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
+                                          (const uint32_t*)nullptr, h->gloss_partial, (const float*)h->x, h->m);
+                    loss_done = true;
+                } else if (scatter)
+                    hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, true, false, MP, MP>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                          ev_a, ev_b, 0, mp, val_prev, delta_prev, (const MP*)nullptr, val_cur, 0, 0, vin, vout, h->y,
+                                          h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, (float*)nullptr,
+                                          (const uint32_t*)nullptr, (double*)nullptr, (const float*)nullptr, (int64_t)0);
+                else
+                    hipExtLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MC, MC>), row_grid, dim3(ROW_TPB), lds, h->compute,
+                                          ev_a, ev_b, 0, (const MC*)nullptr, val_prev, delta_prev, mc, val_cur, hot, k64, vin, vout, h->y,
+                                          h->ybits, n, gpart, h->gpartial_stride, scale, kd, h->status, cbuf, wbase, (double*)nullptr,
+                                          (const float*)nullptr, (int64_t)0);
+            };
+            if constexpr (std::is_same<MAPT, uint16_t>::value) {
+                // (a pass with one map takes that map's type for both)
+                const bool p8 = scatter ? slot_p >= 0 : slot_c >= 0, c8 = histo ? slot_c >= 0 : slot_p >= 0;
+                if (p8 && c8) launch(uint8_t{}, uint8_t{});
+                else if (p8) launch(uint8_t{}, uint16_t{});
+                else if (c8) launch(uint16_t{}, uint8_t{});
+                else launch(uint16_t{}, uint16_t{});
+            } else {
+                launch(MAPT{}, MAPT{});
+            }
             if (vout != v_cur) {
                 v_cur = vout;
                 swapped = true;
@@ -1796,11 +1855,17 @@ static int grouped_dots_kind(snap_handle* h) {
         if (n > 0 && (hot > 0 || compact)) {
             const size_t lds = (size_t)(hot + k64) * sizeof(unsigned long long) + sizeof(float) +
                                (compact ? (size_t)(ROW_TPB / WAVE) * COLD_RING * sizeof(float) : 0);
-            hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MAPT>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), lds,
-                               h->compute, (const MAPT*)nullptr, (const float*)nullptr, (const float*)nullptr,
-                               map_cur, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
-                               k64, h->v, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale, 0, h->status, cbuf,
-                               wbase, (double*)nullptr, (const float*)nullptr, (int64_t)0);
+            const int slot_c = (!streamed && h->g8slot_host) ? h->g8slot_host[g] : -1;
+            auto launch = [&](auto tag_c, const void* map) {
+                using MC = decltype(tag_c);
+                hipLaunchKernelGGL((k_group_rows<KIND, UNIT, false, true, MC, MC>), dim3((unsigned)h->g_row_wgs), dim3(ROW_TPB), lds,
+                                   h->compute, (const MC*)nullptr, (const float*)nullptr, (const float*)nullptr,
+                                   (const MC*)map, UNIT ? (const float*)nullptr : h->rowval + (size_t)g * h->n_pad, hot,
+                                   k64, h->v, h->v, h->y, h->ybits, n, gpart, h->gpartial_stride, scale, 0, h->status, cbuf,
+                                   wbase, (double*)nullptr, (const float*)nullptr, (int64_t)0);
+            };
+            if (slot_c >= 0) launch(uint8_t{}, h->rowmap8 + (size_t)slot_c * h->n_pad);
+            else launch(MAPT{}, map_cur);
         }
         if (streamed) {
             SNAP_HIP(hipEventRecord(h->gev_free[gi % 3], h->compute));

@@ -4,8 +4,9 @@
 //   kind 0: read only (4 bytes per row)
 //   kind 1: copy (read 4, write 4)
 //   kind 2: the row pass's mix with two-byte row maps: read 4 + 2 + 2, write 4 bytes per row,
-//           from four arrays laid out and alternated the way the row pass alternates them
-// The kernels do nothing else (an add per element so that the loads cannot be dropped).
+//           walking the rows the way the row pass walks them, the maps alternated as the sweeps alternate them
+// The kernels do nothing else (an add per element so that the loads cannot be dropped).  The arrays hold
+// a pattern, not zeros (all-zero data was measured 15 % faster than any other).
 #include "common.h"
 #include <algorithm>
 
@@ -14,6 +15,11 @@ namespace snap {
 typedef float probe_f4 __attribute__((ext_vector_type(4)));
 typedef unsigned probe_u2 __attribute__((ext_vector_type(2)));
 
+__global__ void k_probe_fill(uint32_t* p, int64_t count, uint32_t base, uint32_t mask) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = base | ((uint32_t)i * 2654435761u & mask);
+}
+
 template <int TPB>
 __global__ void __launch_bounds__(TPB) k_probe_read(const probe_f4* __restrict__ in, float* __restrict__ sink, int64_t packs) {
     float s = 0.0f;
@@ -21,7 +27,7 @@ __global__ void __launch_bounds__(TPB) k_probe_read(const probe_f4* __restrict__
         const probe_f4 a = in[q];
         s += a.x + a.y + a.z + a.w;
     }
-    if (s == 12345.678f) sink[0] = s;            // (never true for the zeros the probe reads; keeps the loads)
+    if (s == 12345.678f) sink[0] = s;            // (practically never true; keeps the loads)
 }
 
 template <int TPB>
@@ -29,36 +35,34 @@ __global__ void __launch_bounds__(TPB) k_probe_copy(const probe_f4* __restrict__
     for (int64_t q = (int64_t)blockIdx.x * TPB + threadIdx.x; q < packs; q += (int64_t)gridDim.x * TPB) out[q] = in[q];
 }
 
-// every workgroup takes one contiguous slab of the rows, as the row pass does; U packs of four rows per
-// thread and iteration, all loads ahead of the first use
-template <int U, bool NT, int TPB>
-__global__ void __launch_bounds__(TPB) k_probe_mix(const probe_f4* __restrict__ vin, probe_f4* __restrict__ vout,
-                                                   const probe_u2* __restrict__ ma, const probe_u2* __restrict__ mb, int64_t packs) {
-    const int64_t per = (packs + gridDim.x - 1) / gridDim.x;
-    const int64_t q0 = min(packs, (int64_t)blockIdx.x * per), q1 = min(packs, q0 + per);
-    for (int64_t q = q0 + threadIdx.x; q < q1; q += (int64_t)U * TPB) {
-        probe_f4 a[U];
-        probe_u2 x[U], y[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t qq = q + (int64_t)u * TPB;
-            if (qq < q1) {
-                a[u] = NT ? __builtin_nontemporal_load(vin + qq) : vin[qq];
-                x[u] = NT ? __builtin_nontemporal_load(ma + qq) : ma[qq];
-                y[u] = NT ? __builtin_nontemporal_load(mb + qq) : mb[qq];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t qq = q + (int64_t)u * TPB;
-            if (qq < q1) {
-                a[u].x += (float)(x[u].x & 1u) + (float)(y[u].x & 2u);
-                a[u].y += (float)(x[u].y & 1u);
-                a[u].z += (float)(y[u].y & 1u);
-                if (NT) __builtin_nontemporal_store(a[u], vout + qq);
-                else vout[qq] = a[u];
-            }
-        }
+// the workgroups walk the rows side by side, as the row pass does (in iteration i workgroup b takes the TPB
+// packs from (i * gridDim.x + b) * TPB on), one pack of four rows per thread and iteration, the next
+// pack's loads asked for before the work on the current one; vin may equal vout (the row pass updates the
+// shared vector in place unless an epoch's earlier state must survive).  NTV / NTM: non-temporal loads of
+// the vector / of the two maps.
+template <bool NTV, bool NTM, int TPB>
+__global__ void __launch_bounds__(TPB) k_probe_mix(const probe_f4* vin, probe_f4* vout, const probe_u2* __restrict__ ma,
+                                                   const probe_u2* __restrict__ mb, int64_t packs) {
+    const int64_t stride = (int64_t)gridDim.x * TPB;
+    int64_t q = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    probe_f4 a = {};
+    probe_u2 x = {}, y = {};
+    auto request = [&](int64_t qq) {
+        a = NTV ? __builtin_nontemporal_load(vin + qq) : vin[qq];
+        x = NTM ? __builtin_nontemporal_load(ma + qq) : ma[qq];
+        y = NTM ? __builtin_nontemporal_load(mb + qq) : mb[qq];
+    };
+    if (q < packs) request(q);
+    while (q < packs) {
+        probe_f4 t = a;
+        const probe_u2 xx = x, yy = y;
+        const int64_t qn = q + stride;
+        if (qn < packs) request(qn);
+        t.x += (float)(xx.x & 1u) + (float)(yy.x & 2u);
+        t.y += (float)(xx.y & 1u);
+        t.z += (float)(yy.y & 1u);
+        vout[q] = t;
+        q = qn;
     }
 }
 
@@ -80,13 +84,15 @@ static int probe_run(int kind, int64_t rows, int passes, hipStream_t s, double* 
     ProbeBuffers pb;
     SNAP_HIP(hipMalloc(&pb.a, (size_t)n * sizeof(float)));
     SNAP_HIP(hipMalloc(&pb.b, (size_t)n * sizeof(float)));
-    SNAP_TRY(fill_zero(pb.a, (size_t)n * sizeof(float), s));
-    SNAP_TRY(fill_zero(pb.b, (size_t)n * sizeof(float), s));
+    // floats in [1, 2) and arbitrary map words
+    hipLaunchKernelGGL(k_probe_fill, dim3(4096), dim3(256), 0, s, (uint32_t*)pb.a, n, 0x3F800000u, 0x007FFFFFu);
+    hipLaunchKernelGGL(k_probe_fill, dim3(4096), dim3(256), 0, s, (uint32_t*)pb.b, n, 0x3F800000u, 0x007FFFFFu);
     if (kind == 2)
         for (auto& m : pb.maps) {
             SNAP_HIP(hipMalloc(&m, (size_t)n * sizeof(uint16_t)));
-            SNAP_TRY(fill_zero(m, (size_t)n * sizeof(uint16_t), s));
+            hipLaunchKernelGGL(k_probe_fill, dim3(4096), dim3(256), 0, s, (uint32_t*)m, n / 2, 0u, 0xFFFFFFFFu);
         }
+    SNAP_HIP(hipGetLastError());
     SNAP_HIP(hipEventCreate(&pb.e0));
     SNAP_HIP(hipEventCreate(&pb.e1));
     const int n_shapes = kind == 2 ? 3 : 2;
@@ -106,12 +112,14 @@ static int probe_run(int kind, int64_t rows, int passes, hipStream_t s, double* 
                 } else {
                     const probe_u2* ma = (const probe_u2*)pb.maps[p & 3];
                     const probe_u2* mb = (const probe_u2*)pb.maps[(p + 1) & 3];
+                    // in place with the hint on the maps (what the row pass does), the same between two arrays,
+                    // and between two arrays with the hint on every load
                     if (shape == 0)
-                        hipLaunchKernelGGL((k_probe_mix<4, true, 256>), dim3(4096), dim3(256), 0, s, (const probe_f4*)in, (probe_f4*)out, ma, mb, packs);
+                        hipLaunchKernelGGL((k_probe_mix<false, true, 1024>), dim3(256), dim3(1024), 0, s, (const probe_f4*)pb.a, (probe_f4*)pb.a, ma, mb, packs);
                     else if (shape == 1)
-                        hipLaunchKernelGGL((k_probe_mix<1, false, 1024>), dim3(256), dim3(1024), 0, s, (const probe_f4*)in, (probe_f4*)out, ma, mb, packs);
+                        hipLaunchKernelGGL((k_probe_mix<false, true, 1024>), dim3(256), dim3(1024), 0, s, (const probe_f4*)in, (probe_f4*)out, ma, mb, packs);
                     else
-                        hipLaunchKernelGGL((k_probe_mix<2, false, 512>), dim3(1024), dim3(512), 0, s, (const probe_f4*)in, (probe_f4*)out, ma, mb, packs);
+                        hipLaunchKernelGGL((k_probe_mix<true, true, 1024>), dim3(256), dim3(1024), 0, s, (const probe_f4*)in, (probe_f4*)out, ma, mb, packs);
                 }
             }
             SNAP_HIP(hipEventRecord(pb.e1, s));

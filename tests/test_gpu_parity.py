@@ -821,6 +821,51 @@ def test_group_sweeps_other_launch_shapes(monkeypatch, knobs, loss, unit):
     g.close()
 
 
+@pytest.mark.parametrize("loss,unit", [("logistic", True), ("logistic", False), ("ridge", True)])
+def test_group_sweeps_read_the_maps_of_small_groups_as_bytes(monkeypatch, loss, unit):
+    """Resident maps: a group of at most 255 columns has its map read as one byte per row, the others as two;
+    every pairing of the two widths in a row pass occurs (13 fields of 64 columns among 26 of 500), and the
+    results are those of two-byte maps throughout, bit for bit, with the accept check's fused loss sums too."""
+    p = datagen.onehot_fields(n=90_011, d=13 * 64 + 26 * 500, lam=1e-4, seed=29)
+    rng = np.random.default_rng(6)
+    if not unit:
+        p.val = torch.from_numpy((0.5 + rng.random(p.nnz)).astype(np.float32))
+    if loss == "ridge":
+        p.loss = "ridge"
+        p.y = torch.from_numpy(rng.standard_normal(p.n).astype(np.float32))
+    groups = p.meta["field_starts"] + [p.d]
+    G = len(groups) - 1
+    small = sum(1 for a, b in zip(groups, groups[1:]) if b - a <= 255)
+    assert 0 < small < G
+    a = gpu_solver(p, group_bounds=groups, adaptive=True)
+    monkeypatch.setenv("SNAP_MAP8", "0")
+    b = gpu_solver(p, group_bounds=groups, adaptive=True)
+    monkeypatch.delenv("SNAP_MAP8")
+    o = oracle.Solver(oracle.Matrix.from_problem(p), p.y.numpy(), p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    assert a.duality_gap() == b.duality_gap()
+    pairs = set()
+    for e in range(5):
+        a.epoch(e)
+        b.epoch(e)
+        o.epoch(e)
+        assert np.array_equal(a.model()[1], b.model()[1]) and np.array_equal(a.shared(), b.shared())
+        assert a.objective() == b.objective()
+        order = [c for c in snap.block_order(e, G)]
+        pairs |= {(groups[u + 1] - groups[u] <= 255, groups[w + 1] - groups[w] <= 255) for u, w in zip(order, order[1:])}
+    assert len(pairs) == 4
+    sa, sb = a.epoch_stats(), b.epoch_stats()
+    assert sa["byte_map_groups"] == small and sb["byte_map_groups"] == 0 and sa["row_map_bytes"] == sb["row_map_bytes"] == 2
+    assert sa["rejected"] == 0
+    close(a.model()[1], o.x, rtol=GROUP_RTOL, atol_rel=GROUP_ATOL)
+    assert a.duality_gap() == b.duality_gap()
+    assert np.array_equal(a.chunk_gaps(), b.chunk_gaps())
+    a.epoch_chunks(9, [0, 20, 1])
+    b.epoch_chunks(9, [0, 20, 1])
+    assert np.array_equal(a.model()[1], b.model()[1])
+    a.close()
+    b.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # group sweeps on streamed data (Section 3.2): the matrix stays in pinned host memory; what is streamed
 # per epoch are the row maps, which the library builds at creation into pinned memory of its own

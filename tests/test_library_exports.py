@@ -24,7 +24,7 @@ def test_struct_sizes_match_header_layout():
     import ctypes as C
     assert C.sizeof(snap.binding.SnapMatrix) == 4 + 4 + 3 * 8 + 3 * 8
     assert C.sizeof(snap.binding.SnapOptions) == 8 + 8 + 8 + 8 + 8 + 4 + 4 + 4 + 4 + 8 + 8 + 8 + 8 + 8 + 8
-    assert C.sizeof(snap.binding.SnapEpochStats) == 16 + 32 + 8 + 4 + 4 + 4 + 4 + 8 + 8 + 4 + 4
+    assert C.sizeof(snap.binding.SnapEpochStats) == 16 + 32 + 8 + 4 + 4 + 4 + 4 + 8 + 8 + 4 + 4 + 4 + 4   # (the last 4: padding)
 
 
 def test_create_without_a_gpu_reports_an_error_instead_of_crashing():
