@@ -109,6 +109,9 @@ typedef struct {
                                     under chunk id 0xFFFFFFFF, sorted), all coordinates of a group at
                                     once -- identical to visiting them one by one, since they do not
                                     interact -- with plain coalesced updates of v instead of atomics.
+                                    Resident data: the library holds a row map per group (2 bytes per row, 4
+                                    when a group has more than 65535 coordinates; a copy of 1 byte per row for
+                                    every group of at most 255, which the sweeps then read instead).
                                     Streamed data (device_budget_bytes exceeded; pattern-only data, i.e. all
                                     values 1): the row maps of the sweeps are built at creation into pinned
                                     host memory of the library's own (1, 2 or 4 bytes per row and group; groups
