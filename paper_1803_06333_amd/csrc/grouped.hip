@@ -1265,6 +1265,7 @@ k_group_rows(const MAPP* __restrict__ map_prev, const float* __restrict__ val_pr
     uint32_t cflushed = crun;
     float* stage = dl + kd + 1 + (threadIdx.x / WAVE) * COLD_RING;
     bool too_large = false;                    // ridge: a term outside the range the 64-bit sums are laid out for
+    const uint32_t hot_lds = (uint32_t)max(hot, 2) - 2u;      // ranks 2 .. hot-1 take their sums in LDS: rank - 2 < hot_lds
     for (int64_t q = q_first; q < packs;) {
         const int64_t r = R * q;
         uint32_t mp[R], mc[R];
@@ -1286,7 +1287,7 @@ k_group_rows(const MAPP* __restrict__ map_prev, const float* __restrict__ val_pr
             for (int j = 0; j < R; ++j) asm("" : "+v"(dv[j]));   // (keeps these LDS reads: merged with the global ones they turn into flat loads)
 #pragma unroll
             for (int j = 0; j < R; ++j)
-                if (mp[j] >= (uint32_t)kd && mp[j] != NONE_P) dv[j] = delta_prev[mp[j]];
+                if (mp[j] - (uint32_t)kd < NONE_P - (uint32_t)kd) dv[j] = delta_prev[mp[j]];   // kd <= rank < "none", in one comparison
 #pragma unroll
             for (int j = 0; j < R; ++j) vv[j] += dv[j] * (UNIT ? 1.0f : ap[j]);
             if (full) {
@@ -1343,7 +1344,7 @@ k_group_rows(const MAPP* __restrict__ map_prev, const float* __restrict__ val_pr
                 if (cbuf) {
                     // a row of a short coordinate: its entry goes to the buffer (ridge: minus the label,
                     // which the finishing kernel then need not gather either)
-                    const bool cold = !in && rk != NONE_C;
+                    const bool cold = rk - (uint32_t)hot < NONE_C - (uint32_t)hot;      // hot <= rank < "none", in one comparison
                     const uint32_t pos = cold_slot(cold, crun);
                     if (cold) stage[pos & (COLD_RING - 1)] = KIND == K_PRIMAL_LOGISTIC ? vv[j] : vv[j] - yy[j];
                     if (crun - cflushed >= (uint32_t)WAVE) {      // (uniform; at most 64 entries arrive per row step)
@@ -1363,7 +1364,7 @@ k_group_rows(const MAPP* __restrict__ map_prev, const float* __restrict__ val_pr
                 if (KIND == K_PRIMAL_LOGISTIC) {
                     rh0 = fmaf(m0, hh, rh0);
                     rh1 = fmaf(m1, hh, rh1);
-                    if (in && rk >= 2u) {
+                    if (rk - 2u < hot_lds) {                       // 2 <= rank < hot
                         // fixed point by the rounding of an addition: the low mantissa bits of
                         // x + 1.5 * 2^23 hold round(x) for |x| < 2^22; the constant's bit pattern stays
                         // in every term and is taken out per coordinate, times its row count, by the
@@ -1375,7 +1376,7 @@ k_group_rows(const MAPP* __restrict__ map_prev, const float* __restrict__ val_pr
                         atomicAdd(&hist[k64 + rk], (unsigned long long)hb | ((unsigned long long)(two ? 0u : gb) << PACK_H_BITS));
                         if (two) atomicAdd(&hist[rk], (unsigned long long)gb);
                     }
-                } else if (in && rk >= 2u) {
+                } else if (rk - 2u < hot_lds) {
                     atomicAdd(&hist[rk], (unsigned long long)__float2ll_rn(g * scale.g));
                 }
             }
