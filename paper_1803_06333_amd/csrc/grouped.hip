@@ -1215,8 +1215,11 @@ k_group_rows(const MAPP* __restrict__ map_prev, const float* __restrict__ val_pr
     const int64_t packs = (n + R - 1) / R;
     const int64_t q_first = (int64_t)blockIdx.x * ROW_TPB + threadIdx.x, q_stride = (int64_t)gridDim.x * ROW_TPB;
     // All loads of an iteration are issued together, ahead of its first wait, and those of the first
-    // iteration ahead of the set-up of the LDS tables (the loop below asks for the next pack's at its end;
-    // asking a whole iteration ahead, with two packs per thread in turn, was measured 3 % slower).
+    // iteration ahead of the set-up of the LDS tables (the loop below asks for the next pack's at its end.
+    // Asking earlier was measured slower, with two packs per thread in turn by 3 % and with three, the
+    // steps from beyond the LDS table gathered an iteration ahead too so that no wait is left inside the
+    // arithmetic, by 4 %: the memory side delivers less when more of a wavefront's loads are under way,
+    // as it does for a bare kernel that only moves the bytes).
     float vv[R], ap[R], ac[R], yy[R];
     typename MapTraits<MAPP>::Raw raw_prev = {};
     typename MapTraits<MAPC>::Raw raw_cur = {};
