@@ -114,9 +114,10 @@ typedef struct {
                                     every group of at most 255, which the sweeps then read instead).
                                     Streamed data (device_budget_bytes exceeded; pattern-only data, i.e. all
                                     values 1): the row maps of the sweeps are built at creation into pinned
-                                    host memory of the library's own (1, 2 or 4 bytes per row and group; groups
-                                    of up to 65535 coordinates whose rows concentrate on few of them: a byte per
-                                    row plus two bytes for each row that does not fit) and an epoch streams
+                                    host memory of the library's own (groups of up to 65535 coordinates:
+                                    prefix-coded, a Huffman code of rank classes that comes within a few percent
+                                    of the entropy of the ranks, decoded on the device; wider groups: 4 bytes
+                                    per row) and an epoch streams
                                     those through a ring of three device buffers instead of the column indices
                                     (when that pinned memory cannot be had, the sweeps are declined as below).
                                     The sums of the sweeps are fixed point.  Logistic loss: the sweeps are not

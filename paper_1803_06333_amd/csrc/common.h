@@ -202,7 +202,9 @@ struct snap_handle {
     int64_t gring_group[3] = {-1, -1, -1};                       // group whose map a slot holds or is being loaded with
     // a group of at most 255 coordinates crosses the host link as one byte per row and is widened to
     // the two-byte entries of the row pass on the device
-    uint8_t* gmap8_host = nullptr;    // [n_groups] 1: stored as bytes
+    uint8_t* gmap8_host = nullptr;    // [n_groups] how the group's map crosses the host link: 0 as read, 1 bytes, 2 escape-coded bytes, 3 prefix-coded
+    uint8_t* gpfx_tab = nullptr;      // device: per group the tables of its prefix code (groups coded that way)
+    int64_t* gpfx_words_host = nullptr;   // [n_groups] 32-bit words of the group's prefix-coded stream, padding included
     int64_t* gmap_off_host = nullptr; // [n_groups + 1] byte offset of every group's map in gmaps_host
     uint8_t* gring8[3] = {nullptr, nullptr, nullptr};            // device, [n_pad] bytes each: landing place of a byte map
     bool gring_widened[3] = {false, false, false};               // the slot's byte map has been widened into gring

@@ -83,6 +83,10 @@ static bool map8_knob() {
     const char* e = getenv("SNAP_MAP8");             // 0: no byte maps (resident: read by the row passes; streamed: on the host link)
     return !(e && e[0] == '0');
 }
+static bool pfx_knob() {
+    const char* e = getenv("SNAP_PFX");              // 0: streamed row maps are never prefix-coded
+    return !(e && e[0] == '0');
+}
 static bool compact_knob() {
     const char* e = getenv("SNAP_COMPACT");          // 0 switches the dense buffer of the short coordinates off
     return !(e && e[0] == '0');
@@ -259,6 +263,237 @@ k_esc_decode(const uint8_t* __restrict__ bytes, const uint32_t* __restrict__ off
     reinterpret_cast<uint2*>(map)[t] = o;
 }
 
+// Prefix-coded maps.  The ranks of a one-hot field carry far fewer bits than the one or two bytes of the
+// codings above (the click-log fields: 7.7 bits of entropy per row for 38 430 columns with a Zipf(1.2)
+// popularity, about 4 for the 64-bin fields), and what crosses the host link is what bounds a streamed
+// epoch.  A rank is sent as the prefix code of its class followed by the class's extra bits:
+//   groups of at most 62 coordinates: class = rank, no extra bits, "none" = class `size`;
+//   larger groups: x = rank + 1 = 1 .. 65535 by quarter octaves -- x <= 7: class x - 1; else, with
+//   b = floor(log2 x) >= 3, class 7 + 4 (b - 3) + (the two bits below the leading one), b - 2 extra
+//   bits -- "none" = class 59.  (Within a quarter octave a Zipf-like popularity varies by a third, which
+//   costs a tenth of a bit; whole octaves would cost 0.8.)
+// The code of the classes is a Huffman code of the group's own class counts (known from the column lengths),
+// limited to PFX_MAXLEN bits so that one table lookup decodes it; bits are written from the low end of
+// 32-bit words.  A thread codes or decodes PFX_SUB consecutive rows; layout of a blob:
+//   [ uint64 per block of PFX_BLOCK rows: bit offset of the block ][ the 32-bit words (+ 2 of padding) ]
+//   [ uint16 per PFX_SUB rows: bit offset inside the block (at most 2048 x 25 bits) ]
+// Per group the device holds a table: PFX_LUT entries (class << 4 | length) indexed by the next PFX_MAXLEN
+// bits, then per class (rank of the class's first member | extra bits << 16), then per class (code | length << 16).
+constexpr int PFX_SUB = 64, PFX_BLOCK = 2048, PFX_MAXLEN = 12, PFX_LUT = 1 << PFX_MAXLEN, PFX_CLASSES = 64;
+constexpr int PFX_DIRECT_MAX = 62, PFX_NONE_CLASS = 59;
+constexpr size_t PFX_TAB_BYTES = PFX_LUT * sizeof(uint16_t) + 2 * PFX_CLASSES * sizeof(uint32_t);
+
+// class, extra bits and their count of a rank; direct_none: the class of "none" for a small group, -1 for a large one
+__host__ __device__ __forceinline__ uint32_t pfx_class_of(uint32_t rank, int direct_none, uint32_t& extra, uint32_t& eb) {
+    extra = 0;
+    eb = 0;
+    if (rank == 0xFFFFu) return direct_none >= 0 ? (uint32_t)direct_none : (uint32_t)PFX_NONE_CLASS;
+    if (direct_none >= 0) return rank;
+    const uint32_t x = rank + 1u;
+    uint32_t b = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+    b = 31u - (uint32_t)__clz((int)x);
+#else
+    while ((x >> (b + 1)) != 0u) ++b;
+#endif
+    if (b <= 2u) return x - 1u;
+    eb = b - 2u;
+    extra = x & ((1u << eb) - 1u);
+    return 7u + 4u * (b - 3u) + ((x >> eb) & 3u);
+}
+
+// sub_rel[t] <- bits of the rows before sub-block t in its block; block_bits[block] <- bits of the block
+__global__ void __launch_bounds__(256)
+k_pfx_count(const uint16_t* __restrict__ map, int64_t n_sub, const uint32_t* __restrict__ enc, int direct_none,
+            uint16_t* __restrict__ sub_rel, uint32_t* __restrict__ block_bits) {
+    __shared__ uint32_t s_enc[PFX_CLASSES];
+    if (threadIdx.x < PFX_CLASSES) s_enc[threadIdx.x] = enc[threadIdx.x];
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t bits = 0;
+    if (t < n_sub) {
+        const uint4* src = reinterpret_cast<const uint4*>(map + (size_t)t * PFX_SUB);
+        for (int q = 0; q < PFX_SUB / 8; ++q) {
+            const uint4 u = src[q];
+            const uint32_t r[8] = {u.x & 0xFFFFu, u.x >> 16, u.y & 0xFFFFu, u.y >> 16, u.z & 0xFFFFu, u.z >> 16, u.w & 0xFFFFu, u.w >> 16};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t extra, eb;
+                const uint32_t c = pfx_class_of(r[j], direct_none, extra, eb);
+                bits += (s_enc[c] >> 16) + eb;
+            }
+        }
+    }
+    // exclusive prefix over the 32 sub-blocks of a block: 32 consecutive lanes (n_sub is a multiple of 32)
+    uint32_t incl = bits;
+#pragma unroll
+    for (int d = 1; d < PFX_BLOCK / PFX_SUB; d <<= 1) {
+        const uint32_t up = __shfl_up(incl, d, PFX_BLOCK / PFX_SUB);
+        if ((int)(threadIdx.x & (PFX_BLOCK / PFX_SUB - 1)) >= d) incl += up;
+    }
+    if (t < n_sub) {
+        sub_rel[t] = (uint16_t)(incl - bits);
+        if ((t & (PFX_BLOCK / PFX_SUB - 1)) == PFX_BLOCK / PFX_SUB - 1) block_bits[t / (PFX_BLOCK / PFX_SUB)] = incl;
+    }
+}
+
+// words must be zero before: neighbouring sub-blocks share their boundary words
+__global__ void __launch_bounds__(256)
+k_pfx_encode(const uint16_t* __restrict__ map, int64_t n_sub, const uint32_t* __restrict__ enc, int direct_none,
+             const unsigned long long* __restrict__ block_off, const uint16_t* __restrict__ sub_rel, uint32_t* __restrict__ words) {
+    __shared__ uint32_t s_enc[PFX_CLASSES];
+    if (threadIdx.x < PFX_CLASSES) s_enc[threadIdx.x] = enc[threadIdx.x];
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n_sub) return;
+    const unsigned long long bitpos = block_off[t / (PFX_BLOCK / PFX_SUB)] + sub_rel[t];
+    size_t wi = (size_t)(bitpos >> 5);
+    uint32_t fill = (uint32_t)(bitpos & 31u);
+    unsigned long long acc = 0;
+    const uint4* src = reinterpret_cast<const uint4*>(map + (size_t)t * PFX_SUB);
+    for (int q = 0; q < PFX_SUB / 8; ++q) {
+        const uint4 u = src[q];
+        const uint32_t r[8] = {u.x & 0xFFFFu, u.x >> 16, u.y & 0xFFFFu, u.y >> 16, u.z & 0xFFFFu, u.z >> 16, u.w & 0xFFFFu, u.w >> 16};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t extra, eb;
+            const uint32_t c = pfx_class_of(r[j], direct_none, extra, eb);
+            const uint32_t e = s_enc[c], len = e >> 16;
+            acc |= (unsigned long long)((e & 0xFFFFu) | (extra << len)) << fill;       // at most 25 bits on top of at most 31
+            fill += len + eb;
+            if (fill >= 32u) {
+                atomicOr(words + wi, (uint32_t)acc);
+                ++wi;
+                acc >>= 32;
+                fill -= 32u;
+            }
+        }
+    }
+    if (fill > 0u) atomicOr(words + wi, (uint32_t)acc);
+}
+
+__global__ void __launch_bounds__(256)
+k_pfx_decode(const unsigned long long* __restrict__ block_off, const uint32_t* __restrict__ words,
+             const uint16_t* __restrict__ sub_rel, const uint8_t* __restrict__ tab, int64_t n_sub, uint16_t* __restrict__ map) {
+    __shared__ uint16_t s_lut[PFX_LUT];
+    __shared__ uint32_t s_cls[PFX_CLASSES];
+    for (int i = threadIdx.x; i < PFX_LUT; i += 256) s_lut[i] = reinterpret_cast<const uint16_t*>(tab)[i];
+    if (threadIdx.x < PFX_CLASSES) s_cls[threadIdx.x] = reinterpret_cast<const uint32_t*>(tab + PFX_LUT * sizeof(uint16_t))[threadIdx.x];
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n_sub) return;
+    const unsigned long long bitpos = block_off[t / (PFX_BLOCK / PFX_SUB)] + sub_rel[t];
+    const uint32_t* wp = words + (size_t)(bitpos >> 5);
+    const uint32_t shift = (uint32_t)(bitpos & 31u);
+    // the low `have` bits of buf are the next bits of the stream (the words are padded: reading two past the end is fine)
+    unsigned long long buf = ((unsigned long long)wp[0] | ((unsigned long long)wp[1] << 32)) >> shift;
+    uint32_t have = 64u - shift;
+    wp += 2;
+    uint4* dst = reinterpret_cast<uint4*>(map + (size_t)t * PFX_SUB);
+    for (int q = 0; q < PFX_SUB / 8; ++q) {
+        uint32_t r[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (have < 32u) {
+                buf |= (unsigned long long)(*wp++) << have;
+                have += 32u;
+            }
+            const uint32_t e = s_lut[(uint32_t)buf & (PFX_LUT - 1)];
+            const uint32_t len = e & 15u, ce = s_cls[e >> 4], eb = ce >> 16;
+            buf >>= len;
+            r[j] = (ce & 0xFFFFu) + ((uint32_t)buf & ((1u << eb) - 1u));
+            buf >>= eb;
+            have -= len + eb;
+        }
+        dst[q] = make_uint4(r[0] | (r[1] << 16), r[2] | (r[3] << 16), r[4] | (r[5] << 16), r[6] | (r[7] << 16));
+    }
+}
+
+// Code lengths of a Huffman code of the counts, limited to max_len bits (counts are flattened until the
+// code fits: each round halves them, rounding up, which only shortens the longest codes).  Classes
+// that do not occur get length 0.
+static void pfx_code_lengths(const uint64_t (&count)[PFX_CLASSES], int max_len, int (&len)[PFX_CLASSES]) {
+    uint64_t f[PFX_CLASSES];
+    for (int i = 0; i < PFX_CLASSES; ++i) f[i] = count[i];
+    for (;;) {
+        struct Node {
+            uint64_t w;
+            int left, right;
+        };
+        std::vector<Node> nodes;
+        std::vector<int> alive;
+        for (int i = 0; i < PFX_CLASSES; ++i) {
+            len[i] = 0;
+            if (f[i] > 0) {
+                nodes.push_back({f[i], -1 - i, 0});
+                alive.push_back((int)nodes.size() - 1);
+            }
+        }
+        if (alive.size() <= 1) {
+            for (int i = 0; i < PFX_CLASSES; ++i) len[i] = f[i] > 0 ? 1 : 0;
+            return;
+        }
+        while (alive.size() > 1) {          // (at most 64 leaves: a plain search for the two lightest will do)
+            std::sort(alive.begin(), alive.end(), [&](int a, int b) { return nodes[a].w != nodes[b].w ? nodes[a].w > nodes[b].w : a > b; });
+            const int a = alive.back();
+            alive.pop_back();
+            const int b = alive.back();
+            alive.pop_back();
+            nodes.push_back({nodes[a].w + nodes[b].w, a, b});
+            alive.push_back((int)nodes.size() - 1);
+        }
+        int deepest = 0;
+        std::vector<std::pair<int, int>> stack{{alive[0], 0}};
+        while (!stack.empty()) {
+            const auto [id, depth] = stack.back();
+            stack.pop_back();
+            if (nodes[id].left < 0) {
+                len[-1 - nodes[id].left] = depth;
+                deepest = std::max(deepest, depth);
+            } else {
+                stack.push_back({nodes[id].left, depth + 1});
+                stack.push_back({nodes[id].right, depth + 1});
+            }
+        }
+        if (deepest <= max_len) return;
+        for (int i = 0; i < PFX_CLASSES; ++i)
+            if (f[i] > 0) f[i] = (f[i] + 1) / 2;
+    }
+}
+
+// The device table of a group (see above) from its code lengths: canonical codes, shorter first, reversed
+// so that a code's first bit is the lowest.
+static void pfx_make_table(const int (&len)[PFX_CLASSES], int direct_none, uint8_t* tab) {
+    uint16_t* lut = reinterpret_cast<uint16_t*>(tab);
+    uint32_t* cls = reinterpret_cast<uint32_t*>(tab + PFX_LUT * sizeof(uint16_t));
+    uint32_t* enc = cls + PFX_CLASSES;
+    memset(tab, 0, PFX_TAB_BYTES);
+    uint32_t code = 0;
+    for (int l = 1; l <= PFX_MAXLEN; ++l) {
+        for (int c = 0; c < PFX_CLASSES; ++c) {
+            if (len[c] != l) continue;
+            uint32_t rev = 0;
+            for (int b = 0; b < l; ++b) rev |= ((code >> b) & 1u) << (l - 1 - b);
+            enc[c] = rev | ((uint32_t)l << 16);
+            for (uint32_t hi = 0; hi < (1u << (PFX_MAXLEN - l)); ++hi) lut[rev | (hi << l)] = (uint16_t)((c << 4) | l);
+            ++code;
+        }
+        code <<= 1;
+    }
+    for (int c = 0; c < PFX_CLASSES; ++c) {
+        uint32_t base, eb = 0;
+        if (direct_none >= 0) base = c == direct_none ? 0xFFFFu : (uint32_t)c;
+        else if (c == PFX_NONE_CLASS) base = 0xFFFFu;
+        else if (c < 7) base = (uint32_t)c;
+        else {
+            const uint32_t b = 3u + (uint32_t)(c - 7) / 4u, f = (uint32_t)(c - 7) % 4u;
+            eb = b - 2u;
+            base = ((4u + f) << eb) - 1u;
+        }
+        cls[c] = (base & 0xFFFFu) | (eb << 16);
+    }
+}
+
 // bit (r & 7) of byte (r >> 3) = 1 when y[r] < 0
 __global__ void k_label_bits(const float* __restrict__ y, int64_t n, uint8_t* __restrict__ bits, int64_t n_bytes) {
     for (int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; b < n_bytes; b += (int64_t)gridDim.x * blockDim.x) {
@@ -297,8 +532,12 @@ void grouped_free(snap_handle* h) {
     h->gmaps_host = nullptr;
     delete[] h->gmap8_host;
     delete[] h->gmap_off_host;
+    delete[] h->gpfx_words_host;
     h->gmap8_host = nullptr;
     h->gmap_off_host = nullptr;
+    h->gpfx_words_host = nullptr;
+    (void)hipFree(h->gpfx_tab);
+    h->gpfx_tab = nullptr;
     delete[] h->gbounds_host;
     delete[] h->ghot_host;
     delete[] h->gk64_host;
@@ -996,10 +1235,15 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
     // tenth shorter than two bytes per row.  The device buffers are padded to whole blocks of ESC_BLOCK rows.
     const int64_t n_esc = (h->n_pad + ESC_BLOCK - 1) / ESC_BLOCK * ESC_BLOCK, n_blk = n_esc / ESC_BLOCK;
     const size_t map_bytes = (size_t)h->n_pad * sizeof(MAPT);
+    // 3 = prefix-coded (see k_pfx_decode) when that is another tenth shorter.
     h->gmap8_host = new (std::nothrow) uint8_t[(size_t)G]();
     h->gmap_off_host = new (std::nothrow) int64_t[(size_t)G + 1]();
-    if (!h->gmap8_host || !h->gmap_off_host) return SNAP_ENOMEM;
+    h->gpfx_words_host = new (std::nothrow) int64_t[(size_t)G]();
+    if (!h->gmap8_host || !h->gmap_off_host || !h->gpfx_words_host) return SNAP_ENOMEM;
     std::vector<int64_t> escaped((size_t)G, 0);     // rows of the group whose rank does not fit a byte
+    std::vector<uint8_t> pfx_tabs;                   // tables of the prefix-coded groups (all groups' slots, to keep the indexing plain)
+    std::vector<int64_t> pfx_bits((size_t)G, 0);
+    const int64_t n_sub = n_esc / PFX_SUB, n_blk2 = n_esc / PFX_BLOCK;
     int64_t land_bytes = 0;                          // largest byte-coded map: size of the landing buffers
     for (int64_t g = 0; g < G; ++g) {
         const int64_t g0 = h->gbounds_host[g], sz = h->gbounds_host[g + 1] - g0;
@@ -1013,6 +1257,34 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
         if (sizeof(MAPT) == 2 && map8_knob()) {
             if (sz <= 255) mode = 1, bytes = h->n_pad;                              // ranks 0 .. 254, 255 = none
             else if (10 * blob <= 9 * (int64_t)map_bytes) mode = 2, bytes = blob;
+        }
+        if (sizeof(MAPT) == 2 && map8_knob() && pfx_knob() && sz > 0) {
+            // class counts from the column lengths (the maps are built from the same columns), code, size
+            const int direct_none = sz <= PFX_DIRECT_MAX ? (int)sz : -1;
+            uint64_t count[PFX_CLASSES] = {};
+            int64_t covered = 0, extra_bits = 0;
+            for (int64_t r = 0; r < sz; ++r) {
+                const int64_t c = coord_of[(size_t)(g0 + r)], rows = hptr[c + 1] - hptr[c];
+                uint32_t extra, eb;
+                count[pfx_class_of((uint32_t)r, direct_none, extra, eb)] += (uint64_t)rows;
+                extra_bits += rows * (int64_t)eb;
+                covered += rows;
+            }
+            uint32_t extra, eb;
+            count[pfx_class_of(0xFFFFu, direct_none, extra, eb)] += (uint64_t)(n_esc - covered);     // rows outside the group, padding
+            int len[PFX_CLASSES];
+            pfx_code_lengths(count, PFX_MAXLEN, len);
+            int64_t bits = extra_bits;
+            for (int c = 0; c < PFX_CLASSES; ++c) bits += (int64_t)count[c] * len[c];
+            const int64_t words = (bits + 31) / 32 + 2;
+            const int64_t pfx_blob = (8 * n_blk2 + 4 * words + 2 * n_sub + 7) / 8 * 8;
+            if (covered <= n_esc && 10 * pfx_blob <= 9 * bytes) {
+                mode = 3, bytes = pfx_blob;
+                pfx_bits[(size_t)g] = bits;
+                h->gpfx_words_host[g] = words;
+                if (pfx_tabs.empty()) pfx_tabs.assign((size_t)G * PFX_TAB_BYTES, 0);
+                pfx_make_table(len, direct_none, pfx_tabs.data() + (size_t)g * PFX_TAB_BYTES);
+            }
         }
         h->gmap8_host[g] = (uint8_t)mode;
         if (mode != 0) land_bytes = std::max(land_bytes, bytes);
@@ -1033,6 +1305,10 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
         SNAP_HIP(hipEventCreateWithFlags(&h->gev_copied[b], hipEventDisableTiming));
         SNAP_HIP(hipEventCreateWithFlags(&h->gev_free[b], hipEventDisableTiming));
         h->gring_group[b] = -1;
+    }
+    if (!pfx_tabs.empty()) {
+        SNAP_HIP(hipMalloc(&h->gpfx_tab, pfx_tabs.size()));
+        SNAP_HIP(hipMemcpy(h->gpfx_tab, pfx_tabs.data(), pfx_tabs.size(), hipMemcpyHostToDevice));
     }
     SNAP_HIP(hipMalloc(&h->gwbase, (size_t)G * (size_t)nwaves * sizeof(uint32_t)));
     SNAP_HIP(hipMalloc(&h->gcptr, (size_t)(m + 1) * sizeof(int64_t)));
@@ -1089,6 +1365,42 @@ static int streamed_setup_maps(snap_handle* h, const int64_t* hptr) {
             hipLaunchKernelGGL(k_map16_to_8, dim3(8192), dim3(256), 0, h->compute, (const uint16_t*)dev_map, h->gring8[0], (size_t)h->n_pad);
             S_HIP(hipGetLastError());
             S_HIP(hipMemcpyAsync((char*)h->gmaps_host + h->gmap_off_host[g], h->gring8[0], (size_t)h->n_pad, hipMemcpyDeviceToHost, h->compute));
+        } else if (h->gmap8_host[g] == 3) {
+            // prefix-coded: bits per sub-block and block, block offsets by a prefix sum on the host, then the bits
+            uint8_t* blob = h->gring8[0];
+            const int64_t words = h->gpfx_words_host[g];
+            unsigned long long* block_off = reinterpret_cast<unsigned long long*>(blob);
+            uint32_t* stream = reinterpret_cast<uint32_t*>(blob + 8 * n_blk2);
+            uint16_t* sub_rel = reinterpret_cast<uint16_t*>(blob + 8 * n_blk2 + 4 * words);
+            const uint8_t* tab = h->gpfx_tab + (size_t)g * PFX_TAB_BYTES;
+            const uint32_t* enc = reinterpret_cast<const uint32_t*>(tab + PFX_LUT * sizeof(uint16_t)) + PFX_CLASSES;
+            const int direct_none = sz <= PFX_DIRECT_MAX ? (int)sz : -1;
+            uint32_t* block_bits = wide;              // (the 32-bit staging map has been narrowed: free)
+            const unsigned sub_grid = (unsigned)((n_sub + 255) / 256);
+            hipLaunchKernelGGL(k_pfx_count, dim3(sub_grid), dim3(256), 0, h->compute, (const uint16_t*)dev_map, n_sub, enc, direct_none,
+                               sub_rel, block_bits);
+            S_HIP(hipGetLastError());
+            std::vector<uint32_t> bb((size_t)n_blk2);
+            S_HIP(hipMemcpyAsync(bb.data(), block_bits, (size_t)n_blk2 * sizeof(uint32_t), hipMemcpyDeviceToHost, h->compute));
+            S_HIP(hipStreamSynchronize(h->compute));
+            std::vector<unsigned long long> boff((size_t)n_blk2);
+            unsigned long long run = 0;
+            for (int64_t b = 0; b < n_blk2; ++b) {
+                boff[(size_t)b] = run;
+                run += bb[(size_t)b];
+            }
+            if ((int64_t)run != pfx_bits[(size_t)g]) {       // the row map and the column lengths disagree
+                set_error("internal error: the bits of a prefix-coded row map do not add up");
+                return fail(SNAP_ESTATE);
+            }
+            S_HIP(hipMemcpyAsync(block_off, boff.data(), (size_t)n_blk2 * sizeof(unsigned long long), hipMemcpyHostToDevice, h->compute));
+            S_TRY(fill_zero(stream, (size_t)words * sizeof(uint32_t), h->compute));
+            hipLaunchKernelGGL(k_pfx_encode, dim3(sub_grid), dim3(256), 0, h->compute, (const uint16_t*)dev_map, n_sub, enc, direct_none,
+                               (const unsigned long long*)block_off, (const uint16_t*)sub_rel, stream);
+            S_HIP(hipGetLastError());
+            S_HIP(hipMemcpyAsync((char*)h->gmaps_host + h->gmap_off_host[g], blob,
+                                 (size_t)(h->gmap_off_host[g + 1] - h->gmap_off_host[g]), hipMemcpyDeviceToHost, h->compute));
+            S_HIP(hipStreamSynchronize(h->compute));     // (boff goes out of scope)
         } else if (h->gmap8_host[g] == 2) {
             // escape-coded: count per block, offsets by a prefix sum on the host, then bytes and escaped ranks
             uint8_t* blob = h->gring8[0];
@@ -1663,7 +1975,15 @@ static int acquire_map(snap_handle* h, int slot, hipEvent_t begin) {
     SNAP_HIP(hipStreamWaitEvent(h->compute, h->gev_copied[slot], 0));
     if (begin) SNAP_HIP(hipEventRecord(begin, h->compute));
     if (!h->gring_widened[slot]) {
-        if (h->gmap8_host[h->gring_group[slot]] == 2) {
+        const int64_t gg = h->gring_group[slot];
+        if (h->gmap8_host[gg] == 3) {
+            const int64_t n_esc = (h->n_pad + ESC_BLOCK - 1) / ESC_BLOCK * ESC_BLOCK, n_sub = n_esc / PFX_SUB, n_blk2 = n_esc / PFX_BLOCK;
+            const uint8_t* blob = h->gring8[slot];
+            hipLaunchKernelGGL(k_pfx_decode, dim3((unsigned)((n_sub + 255) / 256)), dim3(256), 0, h->compute,
+                               reinterpret_cast<const unsigned long long*>(blob), reinterpret_cast<const uint32_t*>(blob + 8 * n_blk2),
+                               reinterpret_cast<const uint16_t*>(blob + 8 * n_blk2 + 4 * h->gpfx_words_host[gg]),
+                               (const uint8_t*)(h->gpfx_tab + (size_t)gg * PFX_TAB_BYTES), n_sub, (uint16_t*)h->gring[slot]);
+        } else if (h->gmap8_host[gg] == 2) {
             const int64_t n_esc = (h->n_pad + ESC_BLOCK - 1) / ESC_BLOCK * ESC_BLOCK, n_blk = n_esc / ESC_BLOCK;
             const uint8_t* blob = h->gring8[slot];
             hipLaunchKernelGGL(k_esc_decode, dim3((unsigned)n_blk), dim3(ESC_TPB), 0, h->compute, blob,

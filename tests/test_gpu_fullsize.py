@@ -252,20 +252,18 @@ def test_config5_streamed_full_size():
     fields = starts + [p.d]
     g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30, group_bounds=fields, profile=True)
     assert g.chunk_bounds() == fields
-    # what crosses the host link per epoch: a byte per row for the 64-bin fields; for the categorical fields a byte per
-    # row, a count per 4096 rows and two bytes for every row whose column is not among the field's 254 longest
+    # what crosses the host link per epoch: every field's row map prefix-coded, i.e. between the entropy of its ranks
+    # (from the column lengths) and a twentieth above it, plus the offsets of the blocks (8 bytes per 2048 rows, 2 per 64)
     n_pad = (p.n + 7) // 8 * 8
     n_esc = (n_pad + 4095) // 4096 * 4096
-    lengths, want = np.diff(ptr), 0
+    lengths, floor_bits = np.diff(ptr), 0.0
     for a, b in zip(fields, fields[1:]):
-        if b - a <= 255:
-            want += n_pad
-        else:
-            escaped = int(np.sort(lengths[a:b])[::-1][254:].sum())
-            blob = (n_esc + 4 * (n_esc // 4096) + 2 * escaped + 7) // 8 * 8
-            assert 10 * blob <= 9 * 2 * n_pad
-            want += blob
-    assert g.stream_bytes() == want < 10.1e9
+        c = np.concatenate([lengths[a:b], [n_esc - int(lengths[a:b].sum())]]).astype(np.float64)
+        c = c[c > 0]
+        floor_bits += float(-(c * np.log2(c / c.sum())).sum())
+    overhead = 39 * (8 * (n_esc // 2048) + 2 * (n_esc // 64) + 16)
+    assert floor_bits / 8 <= g.stream_bytes() - overhead <= 1.05 * floor_bits / 8
+    assert g.stream_bytes() < 7.7e9
     g.epoch(0)
     P = [np.log(2.0), g.objective()]
     _, x = g.model()

@@ -870,7 +870,8 @@ def test_group_sweeps_read_the_maps_of_small_groups_as_bytes(monkeypatch, loss, 
 # group sweeps on streamed data (Section 3.2): the matrix stays in pinned host memory; what is streamed
 # per epoch are the row maps, which the library builds at creation into pinned memory of its own
 @pytest.mark.parametrize("knobs", [{}, {"SNAP_ROW_WGS": "16", "SNAP_HOT_MAX": "8"}, {"SNAP_HOT_ROWS": "1000000000"},
-                                   {"SNAP_ROW_WGS": "3", "SNAP_HOT_MAX": "40", "SNAP_DELTA_LDS": "16"}, {"SNAP_MAP8": "0"}],
+                                   {"SNAP_ROW_WGS": "3", "SNAP_HOT_MAX": "40", "SNAP_DELTA_LDS": "16"}, {"SNAP_MAP8": "0"},
+                                   {"SNAP_PFX": "0"}],
                          ids=lambda k: ",".join("%s=%s" % (n[5:].lower(), v) for n, v in k.items()) or "default")
 @pytest.mark.parametrize("loss", ["logistic", "ridge"])
 def test_streamed_group_sweeps_equal_resident_ones_bit_for_bit_and_the_oracle(monkeypatch, knobs, loss):
@@ -889,7 +890,9 @@ def test_streamed_group_sweeps_equal_resident_ones_bit_for_bit_and_the_oracle(mo
     # one row map per field: a byte per row for fields of at most 255 columns (all of them here), else two
     small = [b - a <= 255 and knobs.get("SNAP_MAP8") != "0" for a, b in zip(groups, groups[1:])]
     assert all(small) or not any(small)
-    assert g.stream_bytes() == sum(n_pad * (1 if s8 else 2) for s8 in small) and r.stream_bytes() == 0
+    plain = sum(n_pad * (1 if s8 else 2) for s8 in small)
+    prefix_coded = knobs.get("SNAP_PFX") != "0" and knobs.get("SNAP_MAP8") != "0"      # (the default: fewer bytes still)
+    assert (0.3 * plain < g.stream_bytes() <= 0.9 * plain if prefix_coded else g.stream_bytes() == plain) and r.stream_bytes() == 0
     mb = 1 if small[0] else 2
     assert g.objective() == r.objective()
     assert rel(g.duality_gap(), r.duality_gap()) <= (0 if "SNAP_HOT_ROWS" not in knobs else 1e-6)
@@ -908,7 +911,8 @@ def test_streamed_group_sweeps_equal_resident_ones_bit_for_bit_and_the_oracle(mo
         np.testing.assert_allclose(xg, o.x, rtol=2e-4, atol=2e-5 * np.abs(o.x).max())
         assert relnorm(xg, o.x) <= 2e-5
         assert rel(g.objective(), o.primal()) <= 1e-5
-    assert 5 * (G - 2) * n_pad * mb <= g.bytes_copied() - base <= 5 * g.stream_bytes()   # (a map still in the ring is not copied)
+    # (a map still in the ring is not copied)
+    assert 5 * (g.stream_bytes() - 2 * n_pad * mb) <= g.bytes_copied() - base <= 5 * g.stream_bytes()
     st = g.epoch_stats()
     assert st["n_chunks"] == G and st["copy_ms"] > 0 and st["scd_ms"] > 0 and st["row_map_bytes"] == 2 and st["unit_values"] == 1
     assert np.array_equal(g.perm(), r.perm())
@@ -944,6 +948,7 @@ def test_streamed_group_sweeps_escape_coded_row_maps(monkeypatch, row_wgs):
     device: same sweeps bit for bit as with resident maps, and the bytes per pass are the coded sizes."""
     if row_wgs:
         monkeypatch.setenv("SNAP_ROW_WGS", row_wgs)
+    monkeypatch.setenv("SNAP_PFX", "0")              # (the prefix code, which is shorter still, has a test of its own)
     p = datagen.onehot_fields(n=100_003, d=13 * 64 + 26 * 1000, lam=1e-4, seed=23)    # 26 Zipf fields of 1000 columns
     groups = p.meta["field_starts"] + [p.d]
     G = len(groups) - 1
@@ -994,6 +999,76 @@ def test_streamed_group_sweeps_escape_coded_row_maps(monkeypatch, row_wgs):
     close(u.model()[1], ou.x, rtol=GROUP_RTOL, atol_rel=GROUP_ATOL)
     u.close()
     r.close()
+
+
+def _entropy_bits(counts):
+    c = np.asarray([x for x in counts if x > 0], dtype=np.float64)
+    return float(-(c * np.log2(c / c.sum())).sum())
+
+
+@pytest.mark.parametrize("row_wgs", [None, "7"])
+def test_streamed_group_sweeps_prefix_coded_row_maps(monkeypatch, row_wgs):
+    """By default a streamed row map crosses the host link prefix-coded (a Huffman code of rank classes, whole
+    ranks for small groups, quarter octaves with extra bits for large ones) and is decoded on the device: the
+    sweeps are those of resident maps bit for bit, and the bytes per pass lie between the entropy of the ranks
+    and a little above it.  Groups of every kind: 64-bin fields, Zipf fields of 1000 columns, a field that
+    covers only part of the rows, evenly spread columns, a group of one column."""
+    if row_wgs:
+        monkeypatch.setenv("SNAP_ROW_WGS", row_wgs)
+    p = datagen.onehot_fields(n=100_003, d=13 * 64 + 26 * 1000, lam=1e-4, seed=23)
+    groups = p.meta["field_starts"] + [p.d]
+    G = len(groups) - 1
+    lengths = np.diff(p.ptr.numpy())
+    n_pad = (p.n + 7) // 8 * 8
+    n_esc = (n_pad + 4095) // 4096 * 4096
+    floor_bits = sum(_entropy_bits(list(lengths[a:b]) + [n_esc - int(lengths[a:b].sum())]) for a, b in zip(groups, groups[1:]))
+    overhead = G * (8 * (n_esc // 2048) + 2 * (n_esc // 64) + 16)
+    r = gpu_solver(p, group_bounds=groups)
+    g = snap.Solver.from_problem(_pinned(p), device_budget_bytes=1 << 20, group_bounds=groups)
+    assert floor_bits / 8 <= g.stream_bytes() - overhead <= 1.05 * floor_bits / 8
+    assert g.stream_bytes() < 0.62 * (13 * n_pad + 26 * 2 * n_pad)
+    o = oracle.Solver(oracle.Matrix.from_problem(p), p.y.numpy(), p.loss, p.lam, chunk_bounds=groups, shuffle_chunks=True)
+    for e in range(4):
+        g.epoch(e)
+        r.epoch(e)
+        o.epoch(e)
+        assert np.array_equal(g.model()[1], r.model()[1]) and np.array_equal(g.shared(), r.shared())
+    close(g.model()[1], o.x, rtol=GROUP_RTOL, atol_rel=GROUP_ATOL)
+    assert g.duality_gap() == r.duality_gap()
+    g.close()
+    r.close()
+    # hand-made groups: 3000 evenly spread columns over all rows; 100 columns over the first half of the rows
+    # only; one column that holds every third row; 40 columns over two thirds of the rows
+    n = 70_001
+    rng = np.random.default_rng(12)
+    parts, d0 = [], 0
+    for width, rows in ((3000, np.arange(n)), (100, np.arange(n // 2)), (1, np.arange(0, n, 3)), (40, np.arange(n)[np.arange(n) % 3 != 1])):
+        cols = d0 + (rng.integers(0, width, size=rows.size) if width > 100 else np.minimum(rng.geometric(0.08, size=rows.size) - 1, width - 1))
+        parts.append((cols, rows))
+        d0 += width
+    cols = np.concatenate([c for c, _ in parts])
+    rows = np.concatenate([r_ for _, r_ in parts])
+    order = np.lexsort((rows, cols))
+    ptr = np.concatenate([[0], np.cumsum(np.bincount(cols, minlength=d0))]).astype(np.int64)
+    idx = rows[order].astype(np.int32)
+    y = np.where(rng.random(n) < 0.4, 1.0, -1.0).astype(np.float32)
+    bounds = [0, 3000, 3100, 3101, 3141]
+    pin = lambda a: torch.from_numpy(a).pin_memory()
+    u = snap.Solver("csc", n, d0, pin(ptr), pin(idx), None, pin(y), "logistic", 1e-4, group_bounds=bounds, device_budget_bytes=1 << 16)
+    ur = snap.Solver("csc", n, d0, ptr, idx, None, y, "logistic", 1e-4, group_bounds=bounds, auto_groups=False)
+    n_pad = (n + 7) // 8 * 8
+    assert u.stream_bytes() < 0.8 * (2 * n_pad + 3 * n_pad)           # (two bytes for the wide group, one for the others, uncoded)
+    ou = oracle.Solver(oracle.Matrix("csc", n, d0, ptr, idx, np.ones(idx.size, dtype=np.float32)), y, "logistic", 1e-4,
+                       chunk_bounds=bounds, shuffle_chunks=True)
+    for e in range(4):
+        u.epoch(e)
+        ur.epoch(e)
+        ou.epoch(e)
+        assert np.array_equal(u.model()[1], ur.model()[1]) and np.array_equal(u.shared(), ur.shared())
+    close(u.model()[1], ou.x, rtol=GROUP_RTOL, atol_rel=GROUP_ATOL)
+    assert u.duality_gap() == ur.duality_gap()
+    u.close()
+    ur.close()
 
 
 def test_streamed_group_sweeps_are_declined_without_pinned_memory_for_the_maps(monkeypatch):
