@@ -117,7 +117,7 @@ def roofline_of(cfg, mode, p, nnz, m, dense, st, kms, ms_per_step, scale):
         per_row = 2 * mb + 8 + lab + (0 if unit else 8)
         dom, dom_ms, dom_bytes = "k_group_rows", kms["large_ms"] / passes, per_row * n
         if cfg == 5:
-            # streamed row maps: the kernels of a visit (row pass, step kernel, widening of a byte map) are
+            # streamed row maps: the kernels of a visit (decoding of the map, row pass, step kernel) are
             # timed together, from the moment the visit's map has arrived; the epoch is bound by the host link
             dom, dom_ms = "row passes + step kernels of all %d visits" % G, kms["scd_ms"]
             dom_bytes = n * (2 * G * mb + 4 * (2 * G + 1) + G * lab) + 24 * m
@@ -162,7 +162,8 @@ def roofline_of(cfg, mode, p, nnz, m, dense, st, kms, ms_per_step, scale):
     r.update(extra)
     if mode == "groups" and cfg == 5:
         r["note"] = "the epoch is bound by the host link (see streaming.host_to_device_GBps), not by HBM: the kernels " \
-                    "take a tenth of the epoch and run behind the copies; achieved / frac are those of the kernels alone"
+                    "(the decoding of the prefix-coded maps included) take two fifths of the epoch and run behind the " \
+                    "copies; achieved / frac are those of the kernels alone"
     if mode not in ("groups", "tiles") and cfg != 5:
         r["note"] = "bound in practice by the memory side's atomic unit (about 21 G scattered fp32 atomics/s on " \
                     "this part), not by bandwidth; the fraction of the HBM peak is what the metric asks for"
