@@ -1038,26 +1038,28 @@ def test_streamed_group_sweeps_prefix_coded_row_maps(monkeypatch, row_wgs):
     g.close()
     r.close()
     # hand-made groups: 3000 evenly spread columns over all rows; 100 columns over the first half of the rows
-    # only; one column that holds every third row; 40 columns over two thirds of the rows
+    # only; one column that holds every third row; 40 columns over two thirds of the rows; 62 and 63 columns (the
+    # largest group coded rank by rank, the smallest coded by classes); 65535 columns (the highest classes)
     n = 70_001
     rng = np.random.default_rng(12)
-    parts, d0 = [], 0
-    for width, rows in ((3000, np.arange(n)), (100, np.arange(n // 2)), (1, np.arange(0, n, 3)), (40, np.arange(n)[np.arange(n) % 3 != 1])):
+    parts, d0, bounds = [], 0, [0]
+    for width, rows in ((3000, np.arange(n)), (100, np.arange(n // 2)), (1, np.arange(0, n, 3)), (40, np.arange(n)[np.arange(n) % 3 != 1]),
+                        (62, np.arange(n)), (63, np.arange(n)), (65535, np.arange(n))):
         cols = d0 + (rng.integers(0, width, size=rows.size) if width > 100 else np.minimum(rng.geometric(0.08, size=rows.size) - 1, width - 1))
         parts.append((cols, rows))
         d0 += width
+        bounds.append(d0)
     cols = np.concatenate([c for c, _ in parts])
     rows = np.concatenate([r_ for _, r_ in parts])
     order = np.lexsort((rows, cols))
     ptr = np.concatenate([[0], np.cumsum(np.bincount(cols, minlength=d0))]).astype(np.int64)
     idx = rows[order].astype(np.int32)
     y = np.where(rng.random(n) < 0.4, 1.0, -1.0).astype(np.float32)
-    bounds = [0, 3000, 3100, 3101, 3141]
     pin = lambda a: torch.from_numpy(a).pin_memory()
     u = snap.Solver("csc", n, d0, pin(ptr), pin(idx), None, pin(y), "logistic", 1e-4, group_bounds=bounds, device_budget_bytes=1 << 16)
     ur = snap.Solver("csc", n, d0, ptr, idx, None, y, "logistic", 1e-4, group_bounds=bounds, auto_groups=False)
     n_pad = (n + 7) // 8 * 8
-    assert u.stream_bytes() < 0.8 * (2 * n_pad + 3 * n_pad)           # (two bytes for the wide group, one for the others, uncoded)
+    assert u.stream_bytes() < 0.85 * (2 * 2 * n_pad + 5 * n_pad)      # (uncoded: two bytes for the wide groups, one for the others)
     ou = oracle.Solver(oracle.Matrix("csc", n, d0, ptr, idx, np.ones(idx.size, dtype=np.float32)), y, "logistic", 1e-4,
                        chunk_bounds=bounds, shuffle_chunks=True)
     for e in range(4):
