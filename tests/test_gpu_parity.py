@@ -1049,6 +1049,10 @@ def test_streamed_group_sweeps_prefix_coded_row_maps(monkeypatch, row_wgs):
         parts.append((cols, rows))
         d0 += width
         bounds.append(d0)
+    # ... and 16 columns whose lengths halve from 32768 down to 1: an unlimited Huffman code would need 16 bits
+    parts.append((d0 + np.repeat(np.arange(16), 2 ** np.arange(15, -1, -1)), np.arange(65535)))
+    d0 += 16
+    bounds.append(d0)
     cols = np.concatenate([c for c, _ in parts])
     rows = np.concatenate([r_ for _, r_ in parts])
     order = np.lexsort((rows, cols))
@@ -1059,7 +1063,7 @@ def test_streamed_group_sweeps_prefix_coded_row_maps(monkeypatch, row_wgs):
     u = snap.Solver("csc", n, d0, pin(ptr), pin(idx), None, pin(y), "logistic", 1e-4, group_bounds=bounds, device_budget_bytes=1 << 16)
     ur = snap.Solver("csc", n, d0, ptr, idx, None, y, "logistic", 1e-4, group_bounds=bounds, auto_groups=False)
     n_pad = (n + 7) // 8 * 8
-    assert u.stream_bytes() < 0.85 * (2 * 2 * n_pad + 5 * n_pad)      # (uncoded: two bytes for the wide groups, one for the others)
+    assert u.stream_bytes() < 0.85 * (2 * 2 * n_pad + 6 * n_pad)      # (uncoded: two bytes for the wide groups, one for the others)
     ou = oracle.Solver(oracle.Matrix("csc", n, d0, ptr, idx, np.ones(idx.size, dtype=np.float32)), y, "logistic", 1e-4,
                        chunk_bounds=bounds, shuffle_chunks=True)
     for e in range(4):
