@@ -196,7 +196,7 @@ k_tile_solve(const float* __restrict__ partial, int n_wg, int64_t c0, int nb, ui
         const float4* p4 = reinterpret_cast<const float4*>(partial);
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
         int wg = part;
-        for (; wg + 3 * SOLVE_PARTS < n_wg; wg += 4 * SOLVE_PARTS) {      // four loads in flight
+        for (; wg + 3 * SOLVE_PARTS < n_wg; wg += 4 * SOLVE_PARTS) {      // four loads in flight (sixteen, predicated: slower)
             const float4 q0 = p4[(size_t)wg * CG + cg];
             const float4 q1 = p4[(size_t)(wg + SOLVE_PARTS) * CG + cg];
             const float4 q2 = p4[(size_t)(wg + 2 * SOLVE_PARTS) * CG + cg];
@@ -243,17 +243,21 @@ k_tile_solve(const float* __restrict__ partial, int n_wg, int64_t c0, int nb, ui
     __syncthreads();
     const int lane = threadIdx.x & (WAVE - 1);
     const bool stepper = threadIdx.x < WAVE;             // wavefront 0 takes the steps
-    // lane l holds the coordinates c0 + l, c0 + 64 + l, ...; u = (inner product) / n is kept in fp64
+    // Lane l holds, in slot s, the coordinate that is visited (s * 64 + l)-th: then the step of the p-th visit
+    // is taken from lane p % 64's own registers, slot p / 64, with no selection by coordinate, and only the
+    // Gram row of the visited coordinate has to be read in that order (a gather from LDS).  u = (inner
+    // product) / n is kept in fp64.
     double u[CPL];
     float Hf[CPL], rinv[CPL], xb[CPL], my_mult[CPL];
-    int seq[CPL];                                         // seq[s] of lane l: the coordinate visited (s * 64 + l)-th
+    int seq[CPL];                                         // the coordinate (0 .. nb-1 within the tile) of slot s
     if (stepper) {
 #pragma unroll
         for (int s = 0; s < CPL; ++s) {
-            const int b = s * WAVE + lane;
-            const bool live = b < nb;
-            u[s] = gfin[b] * sp.inv_n;
-            seq[s] = live ? seq_lds[b] : 0;
+            const int pos = s * WAVE + lane;
+            const bool live = pos < nb;
+            const int b = live ? seq_lds[pos] : 0;
+            seq[s] = b;
+            u[s] = live ? gfin[b] * sp.inv_n : 0.0;
             xb[s] = live ? x[c0 + b] : 0.0f;
             const double hf = (double)(live ? norms[c0 + b] : 0.0f) * sp.inv_n;     // constant per coordinate
             Hf[s] = (float)hf;
@@ -275,69 +279,57 @@ k_tile_solve(const float* __restrict__ partial, int n_wg, int64_t c0, int nb, ui
     if (!stepper) return;
     // Straight-line loop.  A single wavefront issues its instructions one after the other and fp64
     // instructions take several issue slots each, so only the running sums u stay in fp64; the step
-    // itself is fp32 arithmetic on the coordinate whose turn it is (the result is an fp32 number
-    // anyway; the cancellation in u + lambda x costs at most an ulp of x).  The Gram rows of the next
-    // two coordinates are already on their way while a step is computed.
+    // itself is fp32 arithmetic (the result is an fp32 number anyway; the cancellation in u + lambda x
+    // costs at most an ulp of x).  Every lane computes "its" step from its current sums at every visit; the one
+    // whose turn it is publishes it.  The Gram rows of the next two visits are already on their way while a
+    // step is computed; sums of coordinates that have had their turn are no longer kept up to date.
     const float lam = (float)sp.lambda, lam1 = (float)sp.lambda1, damp = (float)sp.damping;
-    auto visited = [&](int p) -> int {                    // coordinate visited p-th (uniform)
-        int r = 0;
+    auto gram_row = [&](int pos, float (&m)[CPL]) {       // row of the coordinate visited pos-th, in visiting order
+        int a = 0;
 #pragma unroll
         for (int s = 0; s < CPL; ++s)
-            if (p / WAVE == s) r = __builtin_amdgcn_readlane(seq[s], p & (WAVE - 1));
-        return r;
+            if (pos / WAVE == s) a = __builtin_amdgcn_readlane(seq[s], pos & (WAVE - 1));
+#pragma unroll
+        for (int s = 0; s < CPL; ++s) m[s] = lds[a * TILE_B + seq[s]];
     };
-    int a0 = visited(0), a1 = nb > 1 ? visited(1) : 0;
     float m0[CPL], m1[CPL];
+    gram_row(0, m0);
+    gram_row(nb > 1 ? 1 : 0, m1);
+    int p = 0;
 #pragma unroll
-    for (int s = 0; s < CPL; ++s) {
-        m0[s] = lds[a0 * TILE_B + s * WAVE + lane];
-        m1[s] = lds[a1 * TILE_B + s * WAVE + lane];
-    }
-    for (int p = 0; p < nb; ++p) {
-        const int a2 = p + 2 < nb ? visited(p + 2) : 0;
-        float m2[CPL];
-#pragma unroll
-        for (int s = 0; s < CPL; ++s) m2[s] = lds[a2 * TILE_B + s * WAVE + lane];
-        const int la = a0 & (WAVE - 1), sa = a0 / WAVE;
-        double usel = u[0];
-        float xsel = xb[0], hsel = Hf[0], rsel = rinv[0];
-#pragma unroll
-        for (int s = 1; s < CPL; ++s)
-            if (s == sa) {
-                usel = u[s];
-                xsel = xb[s];
-                hsel = Hf[s];
-                rsel = rinv[s];
+    for (int sa = 0; sa < CPL; ++sa) {
+        const int p_end = min(nb, (sa + 1) * WAVE);
+        for (; p < p_end; ++p) {
+            float m2[CPL];
+            gram_row(p + 2 < nb ? p + 2 : 0, m2);
+            const int la = p & (WAVE - 1);
+            const float uf = (float)u[sa], xsel = xb[sa];
+            float step;
+            if (lam1 == 0.0f) {
+                step = -(uf + lam * xsel) * rinv[sa];
+            } else {
+                const float t = Hf[sa] * xsel - uf;           // soft threshold, as in primal_step
+                step = (t - fmaxf(-lam1, fminf(t, lam1))) * rinv[sa] - xsel;
             }
-        const float uf = (float)usel;
-        float step;
-        if (lam1 == 0.0f) {
-            step = -(uf + lam * xsel) * rsel;
-        } else {
-            const float t = hsel * xsel - uf;             // soft threshold, as in primal_step
-            step = (t - fmaxf(-lam1, fminf(t, lam1))) * rsel - xsel;
-        }
-        const float xn = xsel + damp * step;
-        const float m = xn - xsel;
-        const float mult = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), la));
+            const float xn = xsel + damp * step;
+            const float m = xn - xsel;
+            const float mult = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), la));
+            const bool commit = lane == la;
+            xb[sa] = commit ? xn : xb[sa];
+            my_mult[sa] = commit ? m : my_mult[sa];
 #pragma unroll
-        for (int s = 0; s < CPL; ++s) {
-            const bool commit = lane == la && s == sa;
-            xb[s] = commit ? xn : xb[s];
-            my_mult[s] = commit ? m : my_mult[s];
-            u[s] += (double)(m0[s] * mult);
-            m0[s] = m1[s];
-            m1[s] = m2[s];
+            for (int s = 0; s < CPL; ++s) {
+                if (s >= sa) u[s] += (double)(m0[s] * mult);      // (earlier slots have had their turns)
+                m0[s] = m1[s];
+                m1[s] = m2[s];
+            }
         }
-        a0 = a1;
-        a1 = a2;
     }
 #pragma unroll
     for (int s = 0; s < CPL; ++s) {
-        const int b = s * WAVE + lane;
-        if (b < nb) {
-            x[c0 + b] = xb[s];
-            mult_out[b] = my_mult[s];
+        if (s * WAVE + lane < nb) {
+            x[c0 + seq[s]] = xb[s];
+            mult_out[seq[s]] = my_mult[s];
         }
     }
 }
