@@ -14,6 +14,7 @@
 #include "common.h"
 #include "perm_key.h"
 #include "scd_device.h"
+#include <type_traits>
 
 #include <algorithm>
 #include <cstdlib>
@@ -292,39 +293,48 @@ k_tile_solve(const float* __restrict__ partial, int n_wg, int64_t c0, int nb, ui
 #pragma unroll
         for (int s = 0; s < CPL; ++s) m[s] = lds[a * TILE_B + seq[s]];
     };
-    float m0[CPL], m1[CPL];
-    gram_row(0, m0);
-    gram_row(nb > 1 ? 1 : 0, m1);
-    int p = 0;
-#pragma unroll
-    for (int sa = 0; sa < CPL; ++sa) {
-        const int p_end = min(nb, (sa + 1) * WAVE);
-        for (; p < p_end; ++p) {
-            float m2[CPL];
-            gram_row(p + 2 < nb ? p + 2 : 0, m2);
-            const int la = p & (WAVE - 1);
-            const float uf = (float)u[sa], xsel = xb[sa];
-            float step;
-            if (lam1 == 0.0f) {
-                step = -(uf + lam * xsel) * rinv[sa];
-            } else {
-                const float t = Hf[sa] * xsel - uf;           // soft threshold, as in primal_step
-                step = (t - fmaxf(-lam1, fminf(t, lam1))) * rinv[sa] - xsel;
-            }
-            const float xn = xsel + damp * step;
-            const float m = xn - xsel;
-            const float mult = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), la));
-            const bool commit = lane == la;
-            xb[sa] = commit ? xn : xb[sa];
-            my_mult[sa] = commit ? m : my_mult[sa];
-#pragma unroll
-            for (int s = 0; s < CPL; ++s) {
-                if (s >= sa) u[s] += (double)(m0[s] * mult);      // (earlier slots have had their turns)
-                m0[s] = m1[s];
-                m1[s] = m2[s];
-            }
+    // A ring of four rows in registers, handed on by name (the loop is unrolled by four), not by moves: a move
+    // at the end of a pass of the loop made every visit wait for the row it had just asked for.  Visit p works
+    // with the row asked for three visits earlier and asks for the row of visit p + 3.
+    float r0[CPL], r1[CPL], r2[CPL], r3[CPL];
+    gram_row(0, r0);
+    gram_row(nb > 1 ? 1 : 0, r1);
+    gram_row(nb > 2 ? 2 : 0, r2);
+    auto visit = [&](auto slot, int p, int p_end, const float (&row)[CPL], float (&ahead)[CPL]) {
+        constexpr int sa = decltype(slot)::value;
+        if (p >= p_end) return;                           // (uniform)
+        gram_row(p + 3 < nb ? p + 3 : 0, ahead);
+        const int la = p & (WAVE - 1);
+        const float uf = (float)u[sa], xsel = xb[sa];
+        float step;
+        if (lam1 == 0.0f) {
+            step = -(uf + lam * xsel) * rinv[sa];
+        } else {
+            const float t = Hf[sa] * xsel - uf;           // soft threshold, as in primal_step
+            step = (t - fmaxf(-lam1, fminf(t, lam1))) * rinv[sa] - xsel;
         }
-    }
+        const float xn = xsel + damp * step;
+        const float m = xn - xsel;
+        const float mult = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), la));
+        const bool commit = lane == la;
+        xb[sa] = commit ? xn : xb[sa];
+        my_mult[sa] = commit ? m : my_mult[sa];
+#pragma unroll
+        for (int s = sa; s < CPL; ++s) u[s] += (double)(row[s] * mult);      // (earlier slots have had their turns)
+    };
+    auto half = [&](auto slot) {
+        constexpr int sa = decltype(slot)::value;
+        const int p_end = min(nb, (sa + 1) * WAVE);
+        for (int p = sa * WAVE; p < p_end; p += 4) {      // (a slot starts at a multiple of four: the ring carries on)
+            visit(slot, p, p_end, r0, r3);
+            visit(slot, p + 1, p_end, r1, r0);
+            visit(slot, p + 2, p_end, r2, r1);
+            visit(slot, p + 3, p_end, r3, r2);
+        }
+    };
+    static_assert(CPL == 2 && WAVE % 4 == 0, "two slots per lane");
+    half(std::integral_constant<int, 0>{});
+    half(std::integral_constant<int, 1>{});
 #pragma unroll
     for (int s = 0; s < CPL; ++s) {
         if (s * WAVE + lane < nb) {
