@@ -288,6 +288,15 @@ def test_config5_streamed_full_size():
     assert st["n_chunks"] == 39 and st["copy_ms"] > 0 and st["scd_ms"] > 0
     assert st["epoch_ms"] < st["copy_ms"] + 0.5 * st["scd_ms"]          # the kernels hide behind the copies
     check_state(g, P[3])
+    x3 = g.model()[1].copy()
+    g.close()
+    # (3) the same without the field boundaries: the search rides on the creation pass, chunk by chunk, finds the 39
+    # fields, and the epochs are the same to the bit
+    g = snap.Solver.from_problem(p, device_budget_bytes=16 << 30, chunk_bytes=4 << 30)
+    assert g.chunk_bounds() == fields
+    for e in range(3):
+        g.epoch(e)
+    assert g.objective() == P[3] and np.array_equal(g.model()[1], x3)
     g.close()
     # give the 62 GB of pinned host memory back: PyTorch's host allocator would keep them cached, and
     # later pinned allocations of this process (the runtime's own included) would fail
